@@ -1,0 +1,157 @@
+/*
+ * hdc.h - C ABI of the MI355X (gfx950) library for the data-parallel hot path of
+ * binary hyperdimensional computing as defined in arXiv 2206.04746 (HDTorch):
+ * ID-Level encoding (Sec. III, Eq. 1), classical and online class-vector training
+ * (Sec. III, Eqs. 2-3) and Hamming-distance inference (Sec. III), on bit-packed
+ * hypervectors (Sec. IV-B1).
+ *
+ * Conventions for every entry point
+ *   - All functions return 0 (HDC_OK) or a negative hdc_status; nothing throws.
+ *     hdc_strerror() gives a short text; after HDC_EHIP, hdc_last_hip_error() gives the
+ *     HIP runtime's own message for the calling thread.
+ *   - Names ending in _host are HOST pointers, read during the call only.
+ *     Names ending in _dev are DEVICE pointers owned by the caller (for example the
+ *     data_ptr() of a PyTorch tensor).  The library never frees or keeps them; they
+ *     must stay valid until the work enqueued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; the caller synchronises.
+ *   - A hypervector of D bits is W = ceil(D/32) uint32 words, dimension d at bit
+ *     (d & 31) of word (d >> 5) (LSB first); bits D..32W-1 of the last word are zero in
+ *     every table the caller passes and in every vector the library writes.  Matrices
+ *     are row-major and contiguous: hv[N][W], acc[C][D], dist[N][C].
+ *   - N == 0 is a successful no-op.  A context may be used from one host thread at a
+ *     time; work enqueued on different streams with the same context must not overlap
+ *     (the context owns small device scratch buffers).
+ */
+#ifndef HDC_H
+#define HDC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hdc_ctx hdc_ctx; /* opaque; owns DEVICE copies of the tables */
+
+typedef enum {
+    HDC_OK = 0,
+    HDC_EINVAL = -1, /* null pointer, size out of range, misaligned pointer */
+    HDC_ENOMEM = -2, /* host or device allocation failed */
+    HDC_EHIP = -3,   /* a HIP runtime call or kernel launch failed */
+    HDC_ELIMIT = -4  /* argument is valid but beyond what this build supports */
+} hdc_status;
+
+typedef enum { HDC_F32 = 0, HDC_U8 = 1 } hdc_dtype;
+
+/* Limits of this build (checked by hdc_create): */
+#define HDC_MAX_D 1048576 /* bits per hypervector */
+#define HDC_MAX_F 65535   /* features per sample */
+#define HDC_MAX_L 256     /* quantisation levels (bin index is kept in one byte) */
+#define HDC_MAX_C 1024    /* classes */
+
+typedef struct {
+    int32_t D;            /* hypervector dimension in bits, 1..HDC_MAX_D */
+    int32_t F;            /* features per sample, 1..HDC_MAX_F */
+    int32_t L;            /* quantisation levels (bins), 1..HDC_MAX_L */
+    int32_t C;            /* classes, 1..HDC_MAX_C */
+    hdc_dtype feat_dtype; /* element type of the feature matrix */
+} hdc_params;
+
+/*
+ * Create a context on the CURRENT HIP device and copy the encoding tables to it
+ * (synchronous, one time, not part of the timed path).
+ *   item_host  [F][W]  ID vector of every feature            (Sec. III: "ID vectors")
+ *   level_host [L][W]  value vector of every bin             (Sec. III: "Value vectors")
+ *   tie_host   [W]     bit taken when a majority vote ties exactly (F or a class count
+ *                      even); the paper names only "majority voting", the tie rule is
+ *                      this library's: strict majority, exact tie -> tie bit
+ *   lo_host, scale_host [F]  bin rule for HDC_F32 features: t = (x - lo[f]) * scale[f]
+ *                      in fp32 (two roundings, no fused multiply-add), bin = floor(t)
+ *                      clamped to [0, L-1]; t < 0 or NaN -> bin 0.  scale is normally
+ *                      float(L / (hi - lo)).  Both must be NULL for HDC_U8, whose rule is
+ *                      bin = (x * L) >> 8.  (Sec. III says only that values are
+ *                      "discretized into a fixed number of bins".)
+ * Errors: HDC_EINVAL (null/invalid arguments, nonzero pad bits in a table),
+ * HDC_ENOMEM, HDC_EHIP.  On error *out is NULL.
+ */
+int hdc_create(hdc_ctx **out, const hdc_params *p, const uint32_t *item_host,
+               const uint32_t *level_host, const uint32_t *tie_host, const float *lo_host,
+               const float *scale_host);
+
+/* Free the context and its device tables.  Synchronises the device.  NULL is a no-op. */
+int hdc_destroy(hdc_ctx *ctx);
+
+/*
+ * ID-Level encoding, Sec. III Eq. (1):
+ *   hv[n][d] = majority over f of ( item[f][d] XOR level[bin(feats[n][f])][d] ),
+ * strict majority (2*count > F), an exact tie takes tie[d]; pad bits are written 0.
+ *   feats_dev [N][F]  fp32 or uint8 as given by feat_dtype, row-major, 4-byte aligned
+ *   hv_dev    [N][W]  out
+ */
+int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);
+
+/*
+ * Classical training, Sec. III ("single-pass accumulation of the encoded vectors
+ * belonging to the same class into a class vector"):
+ *   acc[c][d] += hv[n][d]  and  class_n[c] += 1   for c = labels[n].
+ * Both outputs are ADDED TO, so chunks of a stream compose in any order (integer sums:
+ * the result does not depend on chunking or sample order); the caller zeroes them
+ * before the first chunk.  Samples whose label is outside [0, C) are skipped.
+ *   hv_dev [N][W], labels_dev [N] int32, acc_dev [C][D] int32 in/out,
+ *   class_n_dev [C] int64 in/out.
+ */
+int hdc_train_classical(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev,
+                        int64_t N, int32_t *acc_dev, int64_t *class_n_dev, void *stream);
+
+/*
+ * Class vectors from classical accumulators by the same majority rule as encoding:
+ *   class_hv[c][d] = 1 if 2*acc > class_n[c], 0 if <, tie[d] if equal
+ * (so an empty class becomes the tie vector).  class_hv_dev [C][W] out, pad bits 0.
+ */
+int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *class_n_dev,
+                           uint32_t *class_hv_dev, void *stream);
+
+/*
+ * Online training, Sec. III Eqs. (2),(3) and the caption of Fig. 1: for each epoch, for
+ * each sample n = 0..N-1 IN THIS ORDER, with s = 2*hv[n] - 1 (the +-1 view of the bits):
+ *   cos_c = <acc[c], s> / (|acc[c]| * sqrt(D))   for every class, from the accumulators
+ *           as they are before this sample (0 for an all-zero row; fp64 sums);
+ *   pred  = lowest c with the largest cos_c;
+ *   acc[y]    += float(1 - cos_y) * s                       (y = labels[n], always);
+ *   acc[pred] -= float(lr * (1 - cos_pred)) * s             (only if pred != y).
+ * acc_dev [C][D] fp32 is in/out (zero it for a fresh model); repeated calls continue
+ * training.  Samples whose label is outside [0, C) are skipped.  The sequential
+ * dependency between samples is the method's; one call is one dependency chain.
+ * epochs >= 0; lr is the paper's learning rate gamma.
+ */
+int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
+                     int32_t epochs, float lr, float *acc_dev, void *stream);
+
+/* class_hv[c][d] = 1 if acc > 0, 0 if acc < 0, tie[d] if acc == 0; [C][W] out, pad 0. */
+int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_dev, void *stream);
+
+/*
+ * Hamming-distance inference, Sec. III ("compared to the class vectors to find the most
+ * similar vector"):
+ *   dist[n][c] = number of dimensions in which hv[n] and class_hv[c] differ,
+ *   pred[n]    = lowest c with the smallest dist[n][c].
+ *   hv_dev [N][W], class_hv_dev [C][W] (pad bits zero), dist_dev [N][C] uint32 out or
+ *   NULL when only predictions are wanted, pred_dev [N] int32 out (required).
+ */
+int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
+               uint32_t *dist_dev, int32_t *pred_dev, void *stream);
+
+/* Text for a status code (static storage, never NULL). */
+const char *hdc_strerror(int code);
+
+/* hipGetErrorString of the last HIP failure seen by the calling thread ("" if none). */
+const char *hdc_last_hip_error(void);
+
+/* Library version, "major.minor.patch". */
+const char *hdc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HDC_H */

@@ -1,0 +1,435 @@
+"""Pins for the CPU oracle: hand-worked fixtures, closed forms, brute force on tiny
+inputs, library special cases and invariants.  None of these tests touches the GPU
+library.  Citations are to arXiv 2206.04746: Sec. III (Eqs. 1-3) and Sec. IV-B."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_workload, pack_bits_lsb
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_bits(rng, *shape):
+    return rng.integers(0, 2, size=shape, dtype=np.uint8)
+
+
+def bits_of(s):
+    return np.array([int(ch) for ch in s], dtype=np.uint8)
+
+
+# --------------------------------------------------------------------- pack / unpack
+def test_pack_is_lsb_first_with_zero_pad():
+    # Sec. IV-B1: bits go into 32-bit integers; dimension d is bit d%32 of word d//32.
+    D = 70
+    for d, (word, value) in {0: (0, 1), 5: (0, 32), 31: (0, 0x80000000), 32: (1, 1),
+                             69: (2, 1 << 5)}.items():
+        b = np.zeros((1, D), dtype=np.uint8)
+        b[0, d] = 1
+        w = oracle.pack(b)
+        assert w.shape == (1, 3) and w.dtype == np.uint32
+        expect = np.zeros(3, dtype=np.uint32)
+        expect[word] = value
+        assert np.array_equal(w[0], expect)
+    ones = oracle.pack(np.ones((1, D), dtype=np.uint8))
+    assert ones[0].tolist() == [0xFFFFFFFF, 0xFFFFFFFF, 0x3F]  # pad bits 70..95 stay zero
+
+
+@pytest.mark.parametrize("D", [1, 31, 32, 33, 64, 1000])
+def test_pack_matches_numpy_packbits_and_roundtrips(D):
+    rng = np.random.default_rng(D)
+    b = rand_bits(rng, 7, D)
+    w = oracle.pack(b)
+    assert np.array_equal(w, pack_bits_lsb(b))          # numpy.packbits(bitorder="little")
+    assert np.array_equal(oracle.unpack(w, D), b)
+
+
+# ------------------------------------------------------------------------- quantiser
+def test_quantiser_edges_f32():
+    L = 16
+    lo = np.array([0.0, -1.0], dtype=np.float32)
+    hi = np.array([1.0, 1.0])
+    scale = (L / (hi - lo)).astype(np.float32)
+    x = np.array([[0.0, -1.0],        # x == lo  -> bin 0
+                  [1.0, 1.0],         # x == hi  -> last bin
+                  [-3.0, -1.5],       # below    -> 0
+                  [7.0, 1.0001],      # above    -> L-1
+                  [np.nan, np.nan],   # NaN      -> 0
+                  [np.inf, -np.inf],
+                  [0.5, 0.0],         # exact bin edge k/L -> bin k
+                  [0.49999997, -1e-7]], dtype=np.float32)
+    q = oracle.quantize(x, L, lo, scale)
+    assert q.tolist() == [[0, 0], [15, 15], [0, 0], [15, 15], [0, 0], [15, 0], [8, 8], [7, 7]]
+
+
+def test_quantiser_bin_edges_exact_and_monotone():
+    # [0,1) in L=16 equal bins: every k/16 is exact in fp32 and opens bin k.
+    L = 16
+    lo, scale = np.zeros(1, np.float32), np.full(1, 16.0, np.float32)
+    edges = (np.arange(L) / L).astype(np.float32)[:, None]
+    assert oracle.quantize(edges, L, lo, scale)[:, 0].tolist() == list(range(L))
+    just_below = np.nextafter(edges[1:], np.float32(-1))
+    assert oracle.quantize(just_below, L, lo, scale)[:, 0].tolist() == list(range(L - 1))
+    xs = np.sort(np.random.default_rng(0).uniform(-0.2, 1.2, 5000)).astype(np.float32)[:, None]
+    q = oracle.quantize(xs, L, lo, scale)[:, 0]
+    assert np.all(np.diff(q) >= 0) and q.min() == 0 and q.max() == L - 1
+    # equal-width: inside the range the bin is floor((x-lo)/(hi-lo)*L) (floor, not round)
+    inside = (xs[:, 0] >= 0) & (xs[:, 0] < 1)
+    assert np.array_equal(q[inside], np.floor(xs[inside, 0].astype(np.float64) * L).astype(int))
+
+
+def test_quantiser_u8():
+    x = np.arange(256, dtype=np.uint8)[:, None]
+    assert np.array_equal(oracle.quantize(x, 256)[:, 0], np.arange(256))        # identity
+    assert np.array_equal(oracle.quantize(x, 64)[:, 0], np.arange(256) // 4)    # 4 values per bin
+    assert np.array_equal(oracle.quantize(x, 2)[:, 0], (np.arange(256) >= 128).astype(int))
+    q100 = oracle.quantize(x, 100)[:, 0]
+    assert q100[0] == 0 and q100[255] == 99 and np.all(np.diff(q100) >= 0)
+
+
+# -------------------------------------------------------------------------- encoding
+def test_encode_hand_case_from_golden_file():
+    ids, levels, tie, cases = [], [], None, []
+    for line in open(os.path.join(GOLDEN, "encode_hand_case.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "id":
+            ids.append(bits_of(t[1]))
+        elif t[0] == "level":
+            levels.append(bits_of(t[1]))
+        elif t[0] == "tie":
+            tie = bits_of(t[1])
+        elif t[0] == "q":
+            cases.append(([int(v) for v in t[1:5]], bits_of(t[6])))
+    q = np.array([c[0] for c in cases], dtype=np.int32)
+    hv = oracle.encode_bits(q, np.array(ids), np.array(levels), tie)
+    assert np.array_equal(hv, np.array([c[1] for c in cases]))
+
+
+def test_encode_single_feature_is_the_bound_vector():
+    # F = 1: the "majority" of one vector is the vector: H = ID_0 xor V_q (Eq. 1).
+    rng = np.random.default_rng(1)
+    D, L = 77, 5
+    item, level, tie = rand_bits(rng, 1, D), rand_bits(rng, L, D), rand_bits(rng, D)
+    q = np.arange(L, dtype=np.int32)[:, None]
+    hv = oracle.encode_bits(q, item, level, tie)
+    assert np.array_equal(hv, item[0][None, :] ^ level)
+    # XOR is self-inverse: binding the result with the level again gives the ID back.
+    assert np.array_equal(hv ^ level, np.repeat(item, L, axis=0))
+
+
+def test_encode_two_and_three_features_closed_forms():
+    rng = np.random.default_rng(2)
+    D, L = 130, 4
+    level, tie = rand_bits(rng, L, D), rand_bits(rng, D)
+    for F in (2, 3):
+        item = rand_bits(rng, F, D)
+        q = rng.integers(0, L, size=(9, F)).astype(np.int32)
+        hv = oracle.encode_bits(q, item, level, tie)
+        for n in range(q.shape[0]):
+            b = [item[f] ^ level[q[n, f]] for f in range(F)]
+            if F == 3:   # majority of three = (a&b)|(a&c)|(b&c)
+                want = (b[0] & b[1]) | (b[0] & b[2]) | (b[1] & b[2])
+            else:        # two votes: agree -> that bit, disagree (tie) -> tie vector
+                want = (b[0] & b[1]) | ((b[0] ^ b[1]) & tie)
+            assert np.array_equal(hv[n], want)
+
+
+@pytest.mark.parametrize("D,F,L", [(1, 1, 2), (31, 2, 2), (33, 4, 3), (64, 5, 16), (40, 100, 16)])
+def test_encode_brute_force_per_bit(D, F, L):
+    rng = np.random.default_rng(D * 1000 + F)
+    item, level, tie = rand_bits(rng, F, D), rand_bits(rng, L, D), rand_bits(rng, D)
+    q = rng.integers(0, L, size=(6, F)).astype(np.int32)
+    hv = oracle.encode_bits(q, item, level, tie)
+    for n in range(6):
+        for d in range(D):
+            votes = sum(int(item[f, d]) != int(level[q[n, f], d]) for f in range(F))
+            want = 1 if 2 * votes > F else 0 if 2 * votes < F else int(tie[d])
+            assert hv[n, d] == want, (n, d)
+
+
+def test_encode_tie_vector_equals_extra_vote_when_F_even():
+    # With F even, breaking ties by T is the same as letting T cast an (F+1)-th vote.
+    rng = np.random.default_rng(3)
+    D, F, L = 96, 6, 4
+    item, level, tie = rand_bits(rng, F, D), rand_bits(rng, L, D), rand_bits(rng, D)
+    q = rng.integers(0, L, size=(20, F)).astype(np.int32)
+    hv = oracle.encode_bits(q, item, level, tie)
+    level_x = np.vstack([level, np.zeros((1, D), np.uint8)])      # extra level: all zero
+    item_x = np.vstack([item, tie[None, :]])                      # extra feature: ID = T
+    q_x = np.hstack([q, np.full((20, 1), L, np.int32)])
+    hv_x = oracle.encode_bits(q_x, item_x, level_x, rand_bits(rng, D))  # odd F: tie unused
+    assert np.array_equal(hv, hv_x)
+
+
+def test_encode_complementing_levels_complements_output_for_odd_F():
+    rng = np.random.default_rng(4)
+    D, F, L = 50, 7, 3
+    item, level, tie = rand_bits(rng, F, D), rand_bits(rng, L, D), rand_bits(rng, D)
+    q = rng.integers(0, L, size=(10, F)).astype(np.int32)
+    a = oracle.encode_bits(q, item, level, tie)
+    b = oracle.encode_bits(q, item, level ^ 1, tie)
+    assert np.array_equal(a ^ 1, b)
+
+
+def test_encode_packed_path_pad_bits_and_structure_with_linear_levels():
+    # End to end through packed tables (config 1 shapes, D cut to a non-multiple of 32).
+    wl = make_workload(1, D=1000, n_train=64)
+    x, _ = wl.train(64)
+    hv = oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+    assert hv.shape == (64, 32) and hv.dtype == np.uint32
+    assert np.all(hv[:, -1] >> (1000 - 31 * 32) == 0)                 # pad bits zero
+    # Linear-scaling level table: Hamming(V_i, V_j) = |i-j| * b exactly (closed form).
+    lv = oracle.unpack(wl.level, wl.D).astype(int)
+    b = wl.D // (2 * (wl.L - 1))
+    for i, j in itertools.combinations(range(wl.L), 2):
+        assert np.sum(lv[i] != lv[j]) == (j - i) * b
+    # Dimensions no level ever flips carry the same bound bits for every sample, so the
+    # encoded bit there cannot depend on the sample.
+    never = np.all(lv == lv[0], axis=0)
+    assert never.sum() == wl.D - (wl.L - 1) * b
+    bits = oracle.unpack(hv, wl.D)
+    assert np.all(bits[:, never] == bits[0, never])
+    assert not np.all(bits[:, ~never] == bits[0, ~never])
+
+
+def test_encode_vs_numpy_column_sums():
+    wl = make_workload(2, D=257, F=33, L=8, n_train=40)
+    x, _ = wl.train(40)
+    hv = oracle.unpack(oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale), wl.D)
+    q = oracle.quantize(x, wl.L, wl.lo, wl.scale)
+    it, lv, tie = (oracle.unpack(a, wl.D) for a in (wl.item, wl.level, wl.tie))
+    for n in range(40):
+        cnt = (it ^ lv[q[n]]).sum(axis=0)                              # library reduction
+        want = np.where(2 * cnt > wl.F, 1, np.where(2 * cnt < wl.F, 0, tie))
+        assert np.array_equal(hv[n], want)
+
+
+# ----------------------------------------------------------------- classical training
+def _rand_hv(rng, N, D):
+    return pack_bits_lsb(rand_bits(rng, N, D))
+
+
+def test_classical_column_and_row_sum_identities():
+    rng = np.random.default_rng(5)
+    N, D, C = 300, 203, 4
+    hv, y = _rand_hv(rng, N, D), rng.integers(0, C, N).astype(np.int32)
+    acc, cn = oracle.train_classical(hv, y, D, C)
+    bits = np.unpackbits(hv.view(np.uint8), axis=1, bitorder="little")[:, :D].astype(np.int64)
+    assert np.array_equal(cn, np.bincount(y, minlength=C))
+    assert np.array_equal(acc.sum(axis=0), bits.sum(axis=0))          # over classes = all rows
+    for c in range(C):
+        assert acc[c].sum() == bits[y == c].sum()                     # total popcount of class
+        assert np.array_equal(acc[c], bits[y == c].sum(axis=0))
+
+
+def test_classical_chunking_order_and_repeat():
+    rng = np.random.default_rng(6)
+    N, D, C = 120, 64, 3
+    hv, y = _rand_hv(rng, N, D), rng.integers(0, C, N).astype(np.int32)
+    tie = _rand_hv(rng, 1, D)[0]
+    acc, cn = oracle.train_classical(hv, y, D, C)
+    a1, n1 = oracle.train_classical(hv[:50], y[:50], D, C)
+    a2, n2 = oracle.train_classical(hv[50:], y[50:], D, C, a1, n1)
+    assert np.array_equal(a2, acc) and np.array_equal(n2, cn)         # chunks compose
+    p = rng.permutation(N)
+    ap, _ = oracle.train_classical(hv[p], y[p], D, C)
+    assert np.array_equal(ap, acc)                                     # order-free
+    ad, nd = oracle.train_classical(hv, y, D, C, acc, cn)
+    assert np.array_equal(ad, 2 * acc) and np.array_equal(nd, 2 * cn)  # twice the data
+    assert np.array_equal(oracle.binarize_classical(ad, nd, tie),
+                          oracle.binarize_classical(acc, cn, tie))     # same class vectors
+
+
+def test_classical_majority_special_cases():
+    rng = np.random.default_rng(7)
+    D = 90
+    tie = _rand_hv(rng, 1, D)[0]
+    hv = _rand_hv(rng, 6, D)
+    # one sample per class -> class vector is that sample
+    acc, cn = oracle.train_classical(hv[:3], np.arange(3, dtype=np.int32), D, 3)
+    assert np.array_equal(oracle.binarize_classical(acc, cn, tie), hv[:3])
+    # three samples -> bitwise majority; two samples -> agree or tie vector; empty -> tie
+    y = np.array([0, 0, 0, 1, 1, 7], dtype=np.int32)                  # label 7 is out of range
+    acc, cn = oracle.train_classical(hv, y, D, 3)
+    assert cn.tolist() == [3, 2, 0]
+    m = oracle.binarize_classical(acc, cn, tie)
+    a, b, c = hv[0], hv[1], hv[2]
+    assert np.array_equal(m[0], (a & b) | (a & c) | (b & c))
+    assert np.array_equal(m[1], (hv[3] & hv[4]) | ((hv[3] ^ hv[4]) & tie))
+    assert np.array_equal(m[2], tie)
+
+
+# ---------------------------------------------------------------------------- search
+def test_search_basic_identities():
+    rng = np.random.default_rng(8)
+    D, N = 333, 40
+    x = _rand_hv(rng, N, D)
+    mask = pack_bits_lsb(np.ones(D, dtype=np.uint8))
+    dist, pred = oracle.search(x, x, D)
+    assert np.all(np.diag(dist) == 0) and np.array_equal(dist, dist.T)      # d(x,x)=0, symmetric
+    assert np.array_equal(pred, np.arange(N))
+    dc, _ = oracle.search(x, (~x) & mask, D)
+    assert np.all(np.diag(dc) == D)                                          # complement: D
+    pc = np.array([bin(int(v)).count("1") for v in x.ravel()]).reshape(N, -1).sum(axis=1)
+    assert np.all((dist - (pc[:, None] + pc[None, :])) % 2 == 0)             # parity rule
+    assert dist.max() <= D
+    for i, j, k in itertools.product(range(6), repeat=3):
+        assert dist[i, k] <= dist[i, j] + dist[j, k]                         # triangle
+    # library special case: count of unequal unpacked bits
+    ub = np.unpackbits(x.view(np.uint8), axis=1, bitorder="little")[:, :D]
+    assert np.array_equal(dist, (ub[:, None, :] != ub[None, :, :]).sum(axis=2))
+
+
+def test_search_argmin_tie_goes_to_lowest_class():
+    D = 40
+    q = pack_bits_lsb(np.zeros((1, D), np.uint8))
+    cls = np.zeros((4, D), np.uint8)
+    cls[0, :5] = 1
+    cls[1, 5:8] = 1     # distance 3
+    cls[2, 30:33] = 1   # distance 3 as well
+    cls[3, :] = 1
+    dist, pred = oracle.search(q, pack_bits_lsb(cls), D)
+    assert dist.tolist() == [[5, 3, 3, 40]] and pred.tolist() == [1]
+
+
+def test_search_distance_to_noisy_copy_is_number_of_flips():
+    rng = np.random.default_rng(9)
+    D = 500
+    base = rand_bits(rng, 3, D)
+    qs, want = [], []
+    for c, k in [(0, 0), (1, 17), (2, 249), (1, 1)]:
+        v = base[c].copy()
+        v[rng.choice(D, k, replace=False)] ^= 1
+        qs.append(v)
+        want.append((c, k))
+    dist, pred = oracle.search(pack_bits_lsb(np.array(qs)), pack_bits_lsb(base), D)
+    for i, (c, k) in enumerate(want):
+        assert dist[i, c] == k and pred[i] == c
+
+
+# -------------------------------------------------------------------- online training
+def _load_online_case():
+    hs, ys, after = [], [], []
+    for line in open(os.path.join(GOLDEN, "online_hand_case.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "h":
+            hs.append(bits_of(t[1]))
+            ys.append(int(t[2]))
+        elif t[0] == "after":
+            after.append((int(t[1]), int(t[3]), [float(v) for v in t[5:9]], [float(v) for v in t[10:14]]))
+    return pack_bits_lsb(np.array(hs)), np.array(ys, dtype=np.int32), after
+
+
+def test_online_hand_case_from_golden_file():
+    hv, y, after = _load_online_case()
+    for k, pred_k, m0, m1 in after:
+        acc, pred, _ = oracle.train_online(hv[:k], y[:k], 4, 2, epochs=1, lr=1.0, log=True)
+        assert pred[k - 1] == pred_k
+        np.testing.assert_allclose(acc, np.array([m0, m1]), rtol=0, atol=2e-7)
+
+
+def test_online_learning_rate_scales_only_the_subtraction():
+    hv, y, _ = _load_online_case()
+    # lr = 0: step 2 mispredicts but class 0 must stay untouched; class 1 still gets the sample
+    acc = oracle.train_online(hv[:2], y[:2], 4, 2, lr=0.0)
+    assert acc.tolist() == [[1, 1, -1, -1], [1, -1, 1, -1]]
+    acc = oracle.train_online(hv[:2], y[:2], 4, 2, lr=0.25)
+    assert acc.tolist() == [[0.75, 1.25, -1.25, -0.75], [1, -1, 1, -1]]
+
+
+def test_online_first_step_repeat_and_complement():
+    rng = np.random.default_rng(10)
+    D, C = 10000, 3                                   # sqrt(D) = 100 exactly
+    h = rand_bits(rng, 1, D)
+    s = 2.0 * h[0] - 1.0
+    hv = pack_bits_lsb(h)
+    mask = pack_bits_lsb(np.ones(D, np.uint8))
+    for y in range(C):
+        lab = np.array([y], dtype=np.int32)
+        acc = oracle.train_online(hv, lab, D, C)
+        want = np.zeros((C, D), np.float32)
+        want[y] = s
+        # first sample of an all-zero model: cosine 0, weight 1 -> acc[y] = s exactly; the
+        # all-zero model predicts class 0, which is "wrong" for y > 0 but subtracts from a
+        # zero row with weight lr*(1-0): acc[0] = -s.
+        if y != 0:
+            want[0] = -s
+        assert np.array_equal(acc, want)
+    lab = np.array([0], dtype=np.int32)
+    acc1 = oracle.train_online(hv, lab, D, C)
+    acc2, pred, margin = oracle.train_online(hv, lab, D, C, acc=acc1, log=True)
+    assert np.array_equal(acc2, acc1) and pred[0] == 0 and margin[0] == 1.0   # cos = 1, weight 0
+    acc3 = oracle.train_online((~hv) & mask, lab, D, C, acc=acc1)
+    # cos_0 = -1 -> weight 2: acc[0] = s - 2s = -s; the zero rows (cosine 0) now beat
+    # class 0, the lowest of them (class 1) is the wrong prediction and loses 1 * (-s).
+    assert np.array_equal(acc3[0], -s) and np.array_equal(acc3[1], s) and not acc3[2].any()
+    # epochs = 2 on one sample equals two calls
+    assert np.array_equal(oracle.train_online(hv, lab, D, C, epochs=2), acc2)
+
+
+def test_online_single_class_never_subtracts():
+    rng = np.random.default_rng(11)
+    D, N = 64, 30
+    hv = _rand_hv(rng, N, D)
+    y = np.zeros(N, dtype=np.int32)
+    a = oracle.train_online(hv, y, D, 1, epochs=2, lr=0.0)
+    b = oracle.train_online(hv, y, D, 1, epochs=2, lr=1000.0)
+    assert np.array_equal(a, b)
+
+
+def test_online_matches_independent_float64_rederivation_on_small_cases():
+    # Cross-check (not a pin): the same steps written with numpy on +-1 vectors.
+    rng = np.random.default_rng(12)
+    D, C, N = 48, 4, 60
+    h = rand_bits(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    acc, pred, _ = oracle.train_online(pack_bits_lsb(h), y, D, C, epochs=2, lr=0.7, log=True)
+    m = np.zeros((C, D), np.float32)
+    k = 0
+    for _ in range(2):
+        for n in range(N):
+            s = (2.0 * h[n] - 1.0)
+            md = m.astype(np.float64)
+            nrm = np.sqrt((md * md).sum(axis=1))
+            cos = np.where(nrm == 0, 0.0, (md @ s) / np.where(nrm == 0, 1, nrm * np.sqrt(D)))
+            p = int(np.argmax(cos))
+            assert p == pred[k]
+            k += 1
+            wy = np.float32(1.0 - cos[y[n]])
+            wp = np.float32(np.float32(0.7).astype(np.float64) * (1.0 - cos[p]))
+            m[y[n]] = m[y[n]] + wy * s.astype(np.float32)
+            if p != y[n]:
+                m[p] = m[p] - wp * s.astype(np.float32)
+    np.testing.assert_allclose(acc, m, rtol=1e-6, atol=1e-6)
+
+
+def test_online_binarise_sign_and_tie():
+    D = 6
+    tie = pack_bits_lsb(bits_of("010101"))
+    acc = np.array([[1.5, -2.0, 0.0, 0.0, -0.0, 1e-30],
+                    [0, 0, 0, 0, 0, 0]], dtype=np.float32)
+    m = oracle.unpack(oracle.binarize_online(acc, tie), D)
+    assert m.tolist() == [[1, 0, 0, 1, 0, 1], [0, 1, 0, 1, 0, 1]]
+
+
+# ------------------------------------------------------------------------ end to end
+def test_config1_end_to_end_is_accurate_on_separated_clusters():
+    wl = make_workload(1, n_train=600, n_test=200)
+    xt, yt = wl.train()
+    xs, ys = wl.test()
+    enc = lambda x: oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+    ht, hs = enc(xt), enc(xs)
+    acc, cn = oracle.train_classical(ht, yt, wl.D, wl.C)
+    m = oracle.binarize_classical(acc, cn, wl.tie)
+    _, pred = oracle.search(hs, m, wl.D)
+    assert (pred == ys).mean() > 0.9          # smoke level only; the paper's accuracies are in a lost figure
+    acc_o = oracle.train_online(ht, yt, wl.D, wl.C, epochs=2)
+    _, pred_o = oracle.search(hs, oracle.binarize_online(acc_o, wl.tie), wl.D)
+    assert (pred_o == ys).mean() > 0.9
