@@ -1,0 +1,168 @@
+"""ctypes binding of the C ABI in ``include/hdc.h`` - same names, argument marshalling only.
+
+Tensors must live on the GPU, be contiguous and have the dtype the ABI states; nothing is
+copied or converted here.  All calls enqueue on ``torch.cuda.current_stream()`` unless a
+stream is given; the caller synchronises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhdc.so")
+
+HDC_OK, HDC_EINVAL, HDC_ENOMEM, HDC_EHIP, HDC_ELIMIT = 0, -1, -2, -3, -4
+HDC_F32, HDC_U8 = 0, 1
+
+# every symbol include/hdc.h declares
+SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
+           "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search",
+           "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
+
+
+class HdcParams(ctypes.Structure):
+    _fields_ = [("D", ctypes.c_int32), ("F", ctypes.c_int32), ("L", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("feat_dtype", ctypes.c_int)]
+
+
+class HdcError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libhdc error {code}: {text}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2206_04746_amd.build` "
+            "(there is no CPU fallback for the HDC kernels)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.hdc_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(HdcParams), vp, vp, vp, vp, vp]
+    lib.hdc_destroy.argtypes = [vp]
+    lib.hdc_encode.argtypes = [vp, vp, i64, vp, vp]
+    lib.hdc_train_classical.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+    lib.hdc_binarize_classical.argtypes = [vp, vp, vp, vp, vp]
+    lib.hdc_train_online.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp]
+    lib.hdc_binarize_online.argtypes = [vp, vp, vp, vp]
+    lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
+                 "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.hdc_strerror.argtypes = [ctypes.c_int]
+    lib.hdc_strerror.restype = ctypes.c_char_p
+    lib.hdc_last_hip_error.restype = ctypes.c_char_p
+    lib.hdc_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def strerror(code: int) -> str:
+    return lib.hdc_strerror(code).decode()
+
+
+def _check(code: int) -> None:
+    if code != HDC_OK:
+        text = strerror(code)
+        if code == HDC_EHIP:
+            text += ": " + lib.hdc_last_hip_error().decode()
+        raise HdcError(code, text)
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, shape=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream if hasattr(s, "cuda_stream") else int(s)
+
+
+def _host(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+class Context:
+    """Owns an ``hdc_ctx`` (device copies of the item / level / tie tables)."""
+
+    def __init__(self, D: int, F: int, L: int, C: int, item, level, tie, lo=None, scale=None,
+                 feat_dtype: str = "f32"):
+        self.D, self.F, self.L, self.C = int(D), int(F), int(L), int(C)
+        self.W = (self.D + 31) // 32
+        self.feat_dtype = feat_dtype
+        self._torch_feat = torch.float32 if feat_dtype == "f32" else torch.uint8
+        p = HdcParams(self.D, self.F, self.L, self.C, HDC_F32 if feat_dtype == "f32" else HDC_U8)
+        item_h, level_h, tie_h = _host(item, np.uint32), _host(level, np.uint32), _host(tie, np.uint32)
+        if item_h.shape != (self.F, self.W) or level_h.shape != (self.L, self.W) or tie_h.shape != (self.W,):
+            raise ValueError("table shapes must be item[F][W], level[L][W], tie[W]")
+        lo_h = None if lo is None else _host(lo, np.float32)
+        sc_h = None if scale is None else _host(scale, np.float32)
+        torch.cuda.init()
+        self._h = ctypes.c_void_p()
+        _check(lib.hdc_create(ctypes.byref(self._h), ctypes.byref(p), item_h.ctypes.data,
+                              level_h.ctypes.data, tie_h.ctypes.data,
+                              None if lo_h is None else lo_h.ctypes.data,
+                              None if sc_h is None else sc_h.ctypes.data))
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            h, self._h = self._h, None
+            _check(lib.hdc_destroy(h))
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the entry points, same names as the C ABI ---------------------------------------
+    def hdc_encode(self, feats: torch.Tensor, hv: torch.Tensor, stream=None) -> None:
+        N = feats.shape[0]
+        _check(lib.hdc_encode(self._h, _dev(feats, self._torch_feat, (N, self.F)), N,
+                              _dev(hv, torch.int32, (N, self.W)), _stream(stream)))
+
+    def hdc_train_classical(self, hv, labels, acc, class_n, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_train_classical(self._h, _dev(hv, torch.int32, (N, self.W)),
+                                       _dev(labels, torch.int32, (N,)), N,
+                                       _dev(acc, torch.int32, (self.C, self.D)),
+                                       _dev(class_n, torch.int64, (self.C,)), _stream(stream)))
+
+    def hdc_binarize_classical(self, acc, class_n, class_hv, stream=None) -> None:
+        _check(lib.hdc_binarize_classical(self._h, _dev(acc, torch.int32, (self.C, self.D)),
+                                          _dev(class_n, torch.int64, (self.C,)),
+                                          _dev(class_hv, torch.int32, (self.C, self.W)), _stream(stream)))
+
+    def hdc_train_online(self, hv, labels, acc, epochs: int = 1, lr: float = 1.0, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_train_online(self._h, _dev(hv, torch.int32, (N, self.W)),
+                                    _dev(labels, torch.int32, (N,)), N, int(epochs), float(lr),
+                                    _dev(acc, torch.float32, (self.C, self.D)), _stream(stream)))
+
+    def hdc_binarize_online(self, acc, class_hv, stream=None) -> None:
+        _check(lib.hdc_binarize_online(self._h, _dev(acc, torch.float32, (self.C, self.D)),
+                                       _dev(class_hv, torch.int32, (self.C, self.W)), _stream(stream)))
+
+    def hdc_search(self, hv, class_hv, pred, dist=None, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_search(self._h, _dev(hv, torch.int32, (N, self.W)), N,
+                              _dev(class_hv, torch.int32, (self.C, self.W)),
+                              _dev(dist, torch.int32, (N, self.C)), _dev(pred, torch.int32, (N,)),
+                              _stream(stream)))
+
+
+def version() -> str:
+    return lib.hdc_version().decode()

@@ -1,0 +1,246 @@
+// C ABI of libhdc: argument checking, the context (device copies of the tables laid out for
+// the kernels, scratch buffers) and dispatch to the kernel launchers.  No compute here.
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "hdc_internal.h"
+
+namespace hdc {
+
+static thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char *what) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();   // clear the sticky error so later calls report their own
+    return HDC_EHIP;
+}
+
+constexpr int64_t kEncodeChunk = 65536;      // samples quantised per encode launch
+constexpr int64_t kPermRows = 1 << 22;       // rows grouped by class per training launch
+
+static void free_ctx(hdc_ctx_impl *c) {
+    if (!c) return;
+    void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
+                    c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->online_d};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete c;
+}
+
+template <typename T>
+static int dev_alloc(T **p, size_t count) {
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(p), count * sizeof(T) + 256);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return HDC_ENOMEM;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    return HDC_OK;
+}
+
+static bool pads_are_zero(const uint32_t *t, int64_t rows, int W, uint32_t last_mask) {
+    for (int64_t r = 0; r < rows; ++r)
+        if (t[r * W + (W - 1)] & ~last_mask) return false;
+    return true;
+}
+
+static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, const uint32_t *level,
+                  const uint32_t *tie, const float *lo, const float *scale) {
+    if (!out) return HDC_EINVAL;
+    *out = nullptr;
+    if (!p || !item || !level || !tie) return HDC_EINVAL;
+    if (p->D < 1 || p->D > HDC_MAX_D || p->F < 1 || p->F > HDC_MAX_F || p->L < 1 ||
+        p->L > HDC_MAX_L || p->C < 1 || p->C > HDC_MAX_C)
+        return HDC_EINVAL;
+    if (p->feat_dtype == HDC_F32) {
+        if (!lo || !scale) return HDC_EINVAL;
+    } else if (p->feat_dtype == HDC_U8) {
+        if (lo || scale) return HDC_EINVAL;
+    } else {
+        return HDC_EINVAL;
+    }
+    const int W = (p->D + 31) / 32;
+    const uint32_t last_mask = (p->D & 31) ? ((1u << (p->D & 31)) - 1u) : 0xffffffffu;
+    if (!pads_are_zero(item, p->F, W, last_mask) || !pads_are_zero(level, p->L, W, last_mask) ||
+        !pads_are_zero(tie, 1, W, last_mask))
+        return HDC_EINVAL;
+
+    hdc_ctx_impl *c = new (std::nothrow) hdc_ctx_impl();
+    if (!c) return HDC_ENOMEM;
+    memset(c, 0, sizeof(*c));
+    c->p = *p;
+    c->W = W;
+    c->Wp = (W + kSliceWords - 1) / kSliceWords * kSliceWords;
+    c->votes = (p->F & 1) ? p->F : p->F + 1;
+    c->Fp = (c->votes + kFeatBlock - 1) / kFeatBlock * kFeatBlock;
+    c->last_word_mask = last_mask;
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) {
+        delete c;
+        return hip_fail(e, "hipGetDevice");
+    }
+
+    // Host staging of the padded device tables (layout described in hdc_internal.h).
+    std::vector<uint32_t> item_h, level_h, tie_h;
+    try {
+        item_h.assign((size_t)c->Fp * c->Wp, 0u);
+        level_h.assign((size_t)p->L * c->Wp, 0u);
+        tie_h.assign((size_t)c->Wp, 0u);
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return HDC_ENOMEM;
+    }
+    for (int l = 0; l < p->L; ++l)
+        memcpy(&level_h[(size_t)l * c->Wp], level + (size_t)l * W, (size_t)W * 4);
+    memcpy(tie_h.data(), tie, (size_t)W * 4);
+    for (int f = 0; f < c->Fp; ++f) {
+        uint32_t *dst = &item_h[(size_t)f * c->Wp];
+        if (f < p->F) {
+            memcpy(dst, item + (size_t)f * W, (size_t)W * 4);
+        } else if (f == p->F && c->votes != p->F) {
+            for (int w = 0; w < W; ++w) dst[w] = tie[w] ^ level[w];   // binds with level 0 to tie
+        } else {
+            memcpy(dst, level, (size_t)W * 4);                        // binds with level 0 to zero
+        }
+    }
+
+    int rc = HDC_OK;
+#define TRY(x)                         \
+    do {                               \
+        if (rc == HDC_OK) rc = (x);    \
+    } while (0)
+#define TRY_HIP(x)                                              \
+    do {                                                        \
+        if (rc == HDC_OK) {                                     \
+            hipError_t e2 = (x);                                \
+            if (e2 != hipSuccess) rc = hip_fail(e2, #x);        \
+        }                                                       \
+    } while (0)
+    TRY(dev_alloc(&c->item_d, item_h.size()));
+    TRY(dev_alloc(&c->level_d, level_h.size()));
+    TRY(dev_alloc(&c->tie_d, tie_h.size()));
+    TRY_HIP(hipMemcpy(c->item_d, item_h.data(), item_h.size() * 4, hipMemcpyHostToDevice));
+    TRY_HIP(hipMemcpy(c->level_d, level_h.data(), level_h.size() * 4, hipMemcpyHostToDevice));
+    TRY_HIP(hipMemcpy(c->tie_d, tie_h.data(), tie_h.size() * 4, hipMemcpyHostToDevice));
+    if (p->feat_dtype == HDC_F32) {
+        TRY(dev_alloc(&c->lo_d, (size_t)p->F));
+        TRY(dev_alloc(&c->scale_d, (size_t)p->F));
+        TRY_HIP(hipMemcpy(c->lo_d, lo, (size_t)p->F * 4, hipMemcpyHostToDevice));
+        TRY_HIP(hipMemcpy(c->scale_d, scale, (size_t)p->F * 4, hipMemcpyHostToDevice));
+    }
+    c->q_rows = kEncodeChunk;
+    TRY(dev_alloc(&c->q_d, (size_t)c->q_rows * c->Fp));
+    TRY(dev_alloc(&c->cls_cnt_d, (size_t)p->C + 1));
+    TRY(dev_alloc(&c->cls_off_d, (size_t)p->C + 1));
+    TRY(dev_alloc(&c->cls_cur_d, (size_t)p->C + 1));
+    TRY(dev_alloc(&c->cls_blk_d, (size_t)p->C + 1));
+    c->perm_rows = kPermRows;
+    TRY(dev_alloc(&c->perm_d, (size_t)c->perm_rows));
+    TRY_HIP(hipDeviceSynchronize());
+#undef TRY
+#undef TRY_HIP
+    if (rc != HDC_OK) {
+        free_ctx(c);
+        return rc;
+    }
+    *out = reinterpret_cast<hdc_ctx *>(c);
+    return HDC_OK;
+}
+
+static inline hdc_ctx_impl *impl(hdc_ctx *c) { return reinterpret_cast<hdc_ctx_impl *>(c); }
+static inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+static inline bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
+
+}  // namespace hdc
+
+using namespace hdc;
+
+extern "C" {
+
+int hdc_create(hdc_ctx **out, const hdc_params *p, const uint32_t *item_host,
+               const uint32_t *level_host, const uint32_t *tie_host, const float *lo_host,
+               const float *scale_host) {
+    return create(out, p, item_host, level_host, tie_host, lo_host, scale_host);
+}
+
+int hdc_destroy(hdc_ctx *ctx) {
+    if (!ctx) return HDC_OK;
+    hipError_t e = hipDeviceSynchronize();
+    free_ctx(impl(ctx));
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+    return HDC_OK;
+}
+
+int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!feats_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
+    if (impl(ctx)->p.feat_dtype == HDC_F32 && !aligned4(feats_dev)) return HDC_EINVAL;
+    return launch_encode(impl(ctx), feats_dev, N, hv_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_train_classical(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
+                        int32_t *acc_dev, int64_t *class_n_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!hv_dev || !labels_dev || !acc_dev || !class_n_dev) return HDC_EINVAL;
+    if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev) || !aligned8(class_n_dev))
+        return HDC_EINVAL;
+    return launch_train_classical(impl(ctx), hv_dev, labels_dev, N, acc_dev, class_n_dev,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *class_n_dev,
+                           uint32_t *class_hv_dev, void *stream) {
+    if (!ctx || !acc_dev || !class_n_dev || !class_hv_dev) return HDC_EINVAL;
+    if (!aligned4(acc_dev) || !aligned8(class_n_dev) || !aligned4(class_hv_dev)) return HDC_EINVAL;
+    return launch_binarize_classical(impl(ctx), acc_dev, class_n_dev, class_hv_dev,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
+                     int32_t epochs, float lr, float *acc_dev, void *stream) {
+    if (!ctx || N < 0 || epochs < 0) return HDC_EINVAL;
+    if (N == 0 || epochs == 0) return HDC_OK;
+    if (!hv_dev || !labels_dev || !acc_dev) return HDC_EINVAL;
+    if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev)) return HDC_EINVAL;
+    return launch_train_online(impl(ctx), hv_dev, labels_dev, N, epochs, lr, acc_dev,
+                               static_cast<hipStream_t>(stream));
+}
+
+int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_dev, void *stream) {
+    if (!ctx || !acc_dev || !class_hv_dev) return HDC_EINVAL;
+    if (!aligned4(acc_dev) || !aligned4(class_hv_dev)) return HDC_EINVAL;
+    return launch_binarize_online(impl(ctx), acc_dev, class_hv_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
+               uint32_t *dist_dev, int32_t *pred_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!hv_dev || !class_hv_dev || !pred_dev) return HDC_EINVAL;
+    if (!aligned4(hv_dev) || !aligned4(class_hv_dev) || !aligned4(pred_dev) || !aligned4(dist_dev))
+        return HDC_EINVAL;
+    return launch_search(impl(ctx), hv_dev, N, class_hv_dev, dist_dev, pred_dev,
+                         static_cast<hipStream_t>(stream));
+}
+
+const char *hdc_strerror(int code) {
+    switch (code) {
+        case HDC_OK: return "ok";
+        case HDC_EINVAL: return "invalid argument";
+        case HDC_ENOMEM: return "out of memory";
+        case HDC_EHIP: return "HIP runtime error (see hdc_last_hip_error)";
+        case HDC_ELIMIT: return "size beyond what this build supports";
+        default: return "unknown status";
+    }
+}
+
+const char *hdc_last_hip_error(void) { return g_hip_err; }
+
+const char *hdc_version(void) { return "0.1.0"; }
+
+}  // extern "C"

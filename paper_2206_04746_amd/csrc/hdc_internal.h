@@ -1,0 +1,77 @@
+// Internal declarations shared by the HIP translation units of libhdc (gfx950 only).
+// Nothing here is part of the public C ABI; see include/hdc.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hdc.h"
+
+namespace hdc {
+
+constexpr int kWave = 64;         // CDNA4 wavefront width
+constexpr int kSliceWords = 64;   // one 32-bit word column per lane: a wave owns 64 words
+constexpr int kFeatBlock = 32;    // features consumed per carry-save tree in encode
+
+// Device-side copy of the model: everything the kernels need, laid out for them.
+struct hdc_ctx_impl {
+    hdc_params p;
+    int device;
+    int32_t W;        // ceil(D / 32)
+    int32_t Wp;       // W rounded up to a multiple of kSliceWords (pad words are zero)
+    int32_t Fp;       // rows of item_d: F, +1 tie-vote row when F is even, padded to kFeatBlock
+    int32_t votes;    // F or F + 1: number of real votes per dimension (always odd)
+    uint32_t last_word_mask;  // valid bits of word W-1
+
+    // Encoding tables in device memory.  item_d holds, after the F real rows, the rows that
+    // make the vote count odd and the feature count a multiple of kFeatBlock:
+    //   row F (only if F is even) = tie XOR level[0]   -> binds with level 0 to the tie vector
+    //   remaining pad rows        = level[0]           -> bind with level 0 to all-zero votes
+    uint32_t *item_d;   // [Fp][Wp]
+    uint32_t *level_d;  // [L][Wp]
+    uint32_t *tie_d;    // [Wp]
+    float *lo_d;        // [F]   (HDC_F32 only)
+    float *scale_d;     // [F]
+
+    // Scratch owned by the context (sized at create, never grown on the hot path).
+    uint8_t *q_d;         // [kEncodeChunk][Fp] bin indices of the samples being encoded
+    int64_t q_rows;       // rows q_d can hold
+    uint32_t *cls_cnt_d;  // [C + 1] per-class sample counts of the current training chunk
+    uint32_t *cls_off_d;  // [C + 1] exclusive prefix of cls_cnt_d
+    uint32_t *cls_cur_d;  // [C] scatter cursors
+    uint32_t *cls_blk_d;  // [C + 1] exclusive prefix of per-class row-block counts
+    uint32_t *perm_d;     // [perm_rows] sample indices grouped by class
+    int64_t perm_rows;
+    double *online_d;     // scratch of the online trainer (norms, partial sums)
+};
+
+// Records a HIP failure for hdc_last_hip_error() and maps it to HDC_EHIP.
+int hip_fail(hipError_t e, const char *what);
+
+#define HDC_HIP(call)                                        \
+    do {                                                     \
+        hipError_t e__ = (call);                             \
+        if (e__ != hipSuccess) return ::hdc::hip_fail(e__, #call); \
+    } while (0)
+
+// Kernel launchers (one per translation unit); all only enqueue on `s`.
+int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s);
+int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                           int32_t *acc, int64_t *class_n, hipStream_t s);
+int launch_binarize_classical(hdc_ctx_impl *c, const int32_t *acc, const int64_t *class_n,
+                              uint32_t *class_hv, hipStream_t s);
+int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                        int32_t epochs, float lr, float *acc, hipStream_t s);
+int launch_binarize_online(hdc_ctx_impl *c, const float *acc, uint32_t *class_hv, hipStream_t s);
+int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                  uint32_t *dist, int32_t *pred, hipStream_t s);
+
+// 3-input bitwise ops of gfx950 (v_bitop3_b32); truth table index = (a<<2)|(b<<1)|c.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+__device__ __forceinline__ uint32_t maj3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);
+}
+
+}  // namespace hdc

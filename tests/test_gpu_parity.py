@@ -1,0 +1,283 @@
+"""GPU parity: every entry point of libhdc, called through the C ABI binding, against the CPU
+oracle on the same seeded inputs.  Bit-exact for encode / classical accumulators / class
+vectors / Hamming distances / predictions; 1e-4 relative for the online fp32 accumulators
+(fixed sample order).  Sizes span several tiles of every kernel plus ragged tails."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from workloads import make_workload, pack_bits_lsb  # noqa: E402
+
+
+def _binding():
+    from paper_2206_04746_amd import binding
+    return binding
+
+
+def dev_u32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).cuda()
+
+
+def host_u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def make_ctx(wl):
+    b = _binding()
+    return b.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+
+
+def gpu_encode(ctx, x):
+    xd = torch.from_numpy(x).cuda()
+    hv = torch.empty((x.shape[0], ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(xd, hv)
+    torch.cuda.synchronize()
+    return hv
+
+
+def orc_encode(wl, x):
+    return oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+
+
+def rand_hv(rng, N, D):
+    return pack_bits_lsb(rng.integers(0, 2, size=(N, D), dtype=np.uint8))
+
+
+# ------------------------------------------------------------------------------ encode
+@pytest.mark.parametrize("cfg,n", [(1, 2000), (2, 1500), (3, 1200), (4, 1000), (5, 1100)])
+def test_encode_configs_bit_exact(cfg, n):
+    wl = make_workload(cfg)
+    x, _ = wl.train(n)
+    ctx = make_ctx(wl)
+    got = host_u32(gpu_encode(ctx, x))
+    want = orc_encode(wl, x)
+    assert np.array_equal(got, want)
+    ctx.close()
+
+
+@pytest.mark.parametrize("D,F,L,N", [
+    (1, 1, 1, 1), (31, 2, 2, 5), (32, 3, 2, 16), (33, 31, 16, 17), (64, 32, 16, 15),
+    (1000, 33, 7, 63), (2048, 64, 256, 65), (2049, 100, 16, 130), (4097, 63, 3, 33),
+    (10000, 127, 64, 19), (10000, 128, 100, 21), (12345, 1000, 5, 9), (10000, 2100, 9, 6),
+])
+def test_encode_ragged_shapes_bit_exact(D, F, L, N):
+    wl = make_workload(2, seed=D + F, D=D, F=F, L=L, n_train=N)
+    x, _ = wl.train(N)
+    # push some values onto and beyond the range edges, and a NaN
+    x = x.copy()
+    x.ravel()[::7] = -1.0
+    x.ravel()[3::11] = 1.0
+    x.ravel()[5::13] = 1.5
+    x.ravel()[::97] = np.nan
+    ctx = make_ctx(wl)
+    got = host_u32(gpu_encode(ctx, x))
+    assert np.array_equal(got, orc_encode(wl, x))
+    last_bits = D - 32 * (ctx.W - 1)
+    if last_bits < 32:
+        assert np.all(got[:, -1] >> last_bits == 0)        # pad bits are written as zero
+    ctx.close()
+
+
+def test_encode_u8_levels_and_random_tables():
+    rng = np.random.default_rng(5)
+    for L in (256, 100, 2):
+        wl = make_workload(3, F=36, L=L, D=777, n_train=50)
+        wl.level = rand_hv(rng, L, wl.D)                    # unrelated level vectors, not linear
+        x = rng.integers(0, 256, size=(50, wl.F), dtype=np.uint8)
+        ctx = make_ctx(wl)
+        assert np.array_equal(host_u32(gpu_encode(ctx, x)), orc_encode(wl, x))
+        ctx.close()
+
+
+def test_encode_forced_ties_follow_tie_vector():
+    # F = 2 with complementary level choice forces an exact tie in every dimension where the
+    # two bound vectors differ.
+    wl = make_workload(1, D=300, F=2, L=4, n_train=40)
+    x, _ = wl.train(40)
+    ctx = make_ctx(wl)
+    assert np.array_equal(host_u32(gpu_encode(ctx, x)), orc_encode(wl, x))
+    ctx.close()
+
+
+def test_encode_empty_and_chunk_boundary():
+    wl = make_workload(1, D=96, F=5, L=4, n_train=70000)
+    ctx = make_ctx(wl)
+    hv = torch.empty((0, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(torch.empty((0, wl.F), dtype=torch.float32, device="cuda"), hv)
+    x, _ = wl.train(70000)                                   # crosses the 65536-sample chunk
+    got = host_u32(gpu_encode(ctx, x))
+    assert np.array_equal(got, orc_encode(wl, x))
+    ctx.close()
+
+
+# ------------------------------------------------------------------ classical training
+def gpu_classical(ctx, hv_d, y, acc=None, cn=None):
+    yd = torch.from_numpy(y).cuda()
+    acc = torch.zeros((ctx.C, ctx.D), dtype=torch.int32, device="cuda") if acc is None else acc
+    cn = torch.zeros(ctx.C, dtype=torch.int64, device="cuda") if cn is None else cn
+    ctx.hdc_train_classical(hv_d, yd, acc, cn)
+    torch.cuda.synchronize()
+    return acc, cn
+
+
+@pytest.mark.parametrize("D,C,N", [(1024, 5, 2000), (10000, 26, 6238), (10000, 2, 9000),
+                                   (33, 1, 10), (2049, 7, 4100), (10000, 100, 700)])
+def test_classical_accumulate_and_binarize_bit_exact(D, C, N):
+    rng = np.random.default_rng(D + C)
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    hv = rand_hv(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    if C > 2:
+        y[y == 1] = 0                                        # class 1 stays empty
+    y[::50] = C + 3                                          # out-of-range labels are skipped
+    y[1::50] = -1
+    ctx = make_ctx(wl)
+    hv_d = dev_u32(hv)
+    acc, cn = gpu_classical(ctx, hv_d, y)
+    want_acc, want_cn = oracle.train_classical(hv, y, D, C)
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    assert np.array_equal(cn.cpu().numpy(), want_cn)
+    m = torch.empty((C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_binarize_classical(acc, cn, m)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(m), oracle.binarize_classical(want_acc, want_cn, wl.tie))
+    # chunks compose: second half added onto the first gives the same sums
+    h = N // 3
+    a2, n2 = gpu_classical(ctx, hv_d[:h].contiguous(), y[:h])
+    a2, n2 = gpu_classical(ctx, hv_d[h:].contiguous(), y[h:], a2, n2)
+    assert torch.equal(a2, acc) and torch.equal(n2, cn)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ search
+@pytest.mark.parametrize("D,C,N", [(1024, 5, 500), (10000, 26, 1559), (10000, 2, 3001),
+                                   (10000, 10, 1000), (10000, 6, 2947), (33, 1, 7), (31, 17, 66),
+                                   (2049, 16, 129), (20000, 33, 50), (32768, 3, 20), (10000, 100, 64)])
+def test_search_bit_exact(D, C, N):
+    rng = np.random.default_rng(D * 7 + C)
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    cls = rand_hv(rng, C, D)
+    # queries: noisy copies of class vectors, so minima are meaningful, plus exact ties
+    src = rng.integers(0, C, N)
+    q_bits = oracle.unpack(cls, D)[src]
+    flips = rng.random((N, D)) < 0.3
+    q_bits = q_bits ^ flips.astype(np.uint8)
+    q = pack_bits_lsb(q_bits)
+    if C > 2:
+        cls[2] = cls[0]                                      # duplicate class: argmin must pick 0
+    ctx = make_ctx(wl)
+    qd, cd = dev_u32(q), dev_u32(cls)
+    dist = torch.empty((N, C), dtype=torch.int32, device="cuda")
+    pred = torch.empty(N, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(qd, cd, pred, dist)
+    torch.cuda.synchronize()
+    want_d, want_p = oracle.search(q, cls, D)
+    assert np.array_equal(host_u32(dist), want_d)
+    assert np.array_equal(pred.cpu().numpy(), want_p)
+    pred2 = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(qd, cd, pred2, None)                      # predictions only
+    torch.cuda.synchronize()
+    assert torch.equal(pred2, pred)
+    ctx.close()
+
+
+# --------------------------------------------------------------------- online training
+def rel_err(got, want):
+    scale = np.maximum(np.abs(want), 1e-3 * np.abs(want).max() + 1e-30)
+    return float(np.max(np.abs(got - want) / scale))
+
+
+@pytest.mark.parametrize("D,C,N,epochs,lr", [(1024, 5, 600, 2, 1.0), (10000, 6, 1500, 3, 1.0),
+                                             (10000, 26, 300, 1, 0.5), (33, 1, 20, 2, 1.0),
+                                             (2049, 3, 100, 1, 0.0), (32768, 2, 40, 1, 1.0)])
+def test_online_training_matches_oracle(D, C, N, epochs, lr):
+    rng = np.random.default_rng(D + C + N)
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    protos = rng.integers(0, 2, size=(C, D), dtype=np.uint8)
+    y = rng.integers(0, C, N).astype(np.int32)
+    bits = protos[y] ^ (rng.random((N, D)) < 0.35).astype(np.uint8)
+    hv = pack_bits_lsb(bits)
+    y[N // 2] = C                                            # one out-of-range label: skipped
+    ctx = make_ctx(wl)
+    acc = torch.zeros((C, D), dtype=torch.float32, device="cuda")
+    ctx.hdc_train_online(dev_u32(hv), torch.from_numpy(y).cuda(), acc, epochs=epochs, lr=lr)
+    torch.cuda.synchronize()
+    want = oracle.train_online(hv, y, D, C, epochs=epochs, lr=lr)
+    got = acc.cpu().numpy()
+    assert rel_err(got, want) < 1e-4
+    m = torch.empty((C, ctx.W), dtype=torch.int32, device="cuda")
+    acc_same = torch.from_numpy(want).cuda()                 # binarise identical inputs
+    acc_same[0, :7] = 0.0                                    # exact zeros take the tie bit
+    ctx.hdc_binarize_online(acc_same, m)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(m), oracle.binarize_online(acc_same.cpu().numpy(), wl.tie))
+    # continuing from a non-zero model: a second call equals one more epoch
+    if epochs == 1:
+        ctx.hdc_train_online(dev_u32(hv), torch.from_numpy(y).cuda(), acc, epochs=1, lr=lr)
+        torch.cuda.synchronize()
+        want2 = oracle.train_online(hv, y, D, C, epochs=2, lr=lr)
+        assert rel_err(acc.cpu().numpy(), want2) < 1e-4
+    ctx.close()
+
+
+# -------------------------------------------------------------------------- end to end
+@pytest.mark.parametrize("cfg,ntr,nte", [(1, 2000, 500), (2, 6238, 1559), (3, 2500, 1000), (4, 2000, 800)])
+def test_end_to_end_pipeline_matches_oracle(cfg, ntr, nte):
+    wl = make_workload(cfg)
+    xt, yt = wl.train(ntr)
+    xs, ys = wl.test(nte)
+    ctx = make_ctx(wl)
+    ht, hs = gpu_encode(ctx, xt), gpu_encode(ctx, xs)
+    o_ht, o_hs = orc_encode(wl, xt), orc_encode(wl, xs)
+    assert np.array_equal(host_u32(ht), o_ht) and np.array_equal(host_u32(hs), o_hs)
+    m = torch.empty((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    if wl.mode == "classical":
+        acc, cn = gpu_classical(ctx, ht, yt)
+        ctx.hdc_binarize_classical(acc, cn, m)
+        o_acc, o_cn = oracle.train_classical(o_ht, yt, wl.D, wl.C)
+        assert np.array_equal(acc.cpu().numpy(), o_acc)
+        o_m = oracle.binarize_classical(o_acc, o_cn, wl.tie)
+    else:
+        acc = torch.zeros((wl.C, wl.D), dtype=torch.float32, device="cuda")
+        ctx.hdc_train_online(ht, torch.from_numpy(yt).cuda(), acc, epochs=wl.epochs, lr=wl.lr)
+        ctx.hdc_binarize_online(acc, m)
+        o_acc = oracle.train_online(o_ht, yt, wl.D, wl.C, epochs=wl.epochs, lr=wl.lr)
+        torch.cuda.synchronize()
+        assert rel_err(acc.cpu().numpy(), o_acc) < 1e-4
+        o_m = oracle.binarize_online(o_acc, wl.tie)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(m), o_m)
+    dist = torch.empty((nte, wl.C), dtype=torch.int32, device="cuda")
+    pred = torch.empty(nte, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hs, m, pred, dist)
+    torch.cuda.synchronize()
+    o_dist, o_pred = oracle.search(o_hs, o_m, wl.D)
+    assert np.array_equal(host_u32(dist), o_dist) and np.array_equal(pred.cpu().numpy(), o_pred)
+    assert (o_pred == ys).mean() > 0.5
+    ctx.close()
+
+
+# ----------------------------------------------------------------------- error handling
+def test_argument_errors_are_reported_not_faulted():
+    b = _binding()
+    wl = make_workload(1, D=64, F=4, L=4, C=2)
+    bad_tie = wl.tie.copy()
+    with pytest.raises(b.HdcError) as e:
+        b.Context(63, wl.F, wl.L, wl.C, wl.item, wl.level, bad_tie | np.uint32(0x80000000),
+                  wl.lo, wl.scale)                           # pad bit set
+    assert e.value.code == b.HDC_EINVAL
+    with pytest.raises(b.HdcError):
+        b.Context(wl.D, wl.F, 300, wl.C, wl.item, np.zeros((300, 2), np.uint32), wl.tie, wl.lo, wl.scale)
+    ctx = make_ctx(wl)
+    hv = torch.zeros((4, ctx.W), dtype=torch.int32, device="cuda")
+    assert b.lib.hdc_search(ctx._h, hv.data_ptr(), 4, None, None, None, None) == b.HDC_EINVAL
+    assert b.lib.hdc_encode(ctx._h, None, 4, hv.data_ptr(), None) == b.HDC_EINVAL
+    assert b.lib.hdc_encode(ctx._h, None, -1, None, None) == b.HDC_EINVAL
+    assert b.lib.hdc_train_online(ctx._h, hv.data_ptr(), hv.data_ptr(), 4, -1, 1.0, hv.data_ptr(), None) \
+        == b.HDC_EINVAL
+    assert b.lib.hdc_encode(ctx._h, None, 0, None, None) == b.HDC_OK      # N == 0 is a no-op
+    ctx.close()
