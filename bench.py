@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the HDC hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the classical pipeline over the ISOLET-shaped synthetic workload
+(D=10000, F=617, L=64, C=26, 6238 train / 1559 test samples, all resident in HBM):
+    encode(train) -> classical accumulate -> majority binarise -> encode(test) -> Hamming search.
+Prints ONE JSON line.  `value` = encoded+trained samples/s (N_train over the device time of
+encode(train) + train + binarise, from events inside the timed steps); Hamming queries/s,
+the online-training rate (UCIHAR-shaped config) and large-N figures for the HBM-bound
+kernels ride along as extra keys.  `roofline` describes the dominant kernel (encode_kernel,
+VALU-bound); `cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X figures used for the rooflines
+HBM_PEAK_GBS = 8000.0
+# Plain 32-bit VALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-ops/s
+# (one v_bitop3_b32 / v_xor_b32 / v_bcnt per lane per clock; half the fp32 FMA-flop figure of
+# 157.3 TFLOP/s, which counts 2 flops per FMA and the packed-fp32 dual issue).
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2206_04746_amd import binding  # fails loudly if libhdc.so is missing
+    from workloads import make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    K, Wm = max(1, args.steps), max(0, args.warmup)
+
+    wl = make_workload(2)
+    xt_h, yt_h = wl.train()
+    xs_h, ys_h = wl.test()
+    ntr, nte = xt_h.shape[0], xs_h.shape[0]
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    W = ctx.W
+    dev = "cuda"
+    xt, yt = torch.from_numpy(xt_h).to(dev), torch.from_numpy(yt_h).to(dev)
+    xs = torch.from_numpy(xs_h).to(dev)
+    hv_t = torch.empty((ntr, W), dtype=torch.int32, device=dev)
+    hv_s = torch.empty((nte, W), dtype=torch.int32, device=dev)
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device=dev)
+    cn = torch.zeros(wl.C, dtype=torch.int64, device=dev)
+    cls = torch.empty((wl.C, W), dtype=torch.int32, device=dev)
+    dist = torch.empty((nte, wl.C), dtype=torch.int32, device=dev)
+    pred = torch.empty(nte, dtype=torch.int32, device=dev)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+
+    def step(e=None):
+        if e:
+            e[0].record()
+        ctx.hdc_encode(xt, hv_t)
+        acc.zero_()
+        cn.zero_()
+        ctx.hdc_train_classical(hv_t, yt, acc, cn)
+        ctx.hdc_binarize_classical(acc, cn, cls)
+        if e:
+            e[1].record()
+        ctx.hdc_encode(xs, hv_s)
+        if e:
+            e[2].record()
+        ctx.hdc_search(hv_s, cls, pred, dist)
+        if e:
+            e[3].record()
+
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize()
+    ctx.hdc_profile_enable(True)
+    for k in ("encode", "quantize", "accumulate", "search"):
+        ctx.hdc_profile_read(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    prof = {k: ctx.hdc_profile_read(k) for k in ("encode", "quantize", "accumulate", "search")}
+    ctx.hdc_profile_enable(False)
+
+    t_train = np.array([e[0].elapsed_time(e[1]) for e in ev])    # ms: encode(train)+train+binarise
+    t_enc_s = np.array([e[1].elapsed_time(e[2]) for e in ev])    # ms: encode(test)
+    t_search = np.array([e[2].elapsed_time(e[3]) for e in ev])   # ms: search
+    value = ntr / (t_train.mean() * 1e-3)
+    queries = nte / (t_search.mean() * 1e-3)
+    accuracy = float((pred.cpu().numpy() == ys_h).mean())
+
+    # ---- roofline of the dominant kernel: encode_kernel (plain VALU bound) --------------
+    # algorithmic work: one bind XOR + one full adder (two 3-input bit ops) per
+    # (sample, feature, 32-bit word) = 3 * F * W lane-ops per sample.
+    enc_ms, enc_launches = prof["encode"]
+    ops_per_sample = 3.0 * wl.F * W
+    enc_ops_total = ops_per_sample * (ntr + nte) * K
+    achieved = enc_ops_total / (enc_ms * 1e-3) / 1e12 if enc_ms > 0 else 0.0
+    roofline = {
+        "kernel": "encode_kernel", "bound": "alu", "achieved": round(achieved, 3),
+        "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
+        "frac": round(achieved / VALU_PEAK_TOPS, 4), "traffic": None,
+        "avg_launch_us": round(enc_ms * 1e3 / max(1, enc_launches), 2), "launches": enc_launches,
+        "algorithmic_ops_per_sample": ops_per_sample,
+        "hbm_equiv_GBs": round((wl.F * 4 + W * 4) * (ntr + nte) * K / (enc_ms * 1e-3) / 1e9, 2)
+        if enc_ms > 0 else 0.0,
+    }
+    srch_ms, srch_launches = prof["search"]
+    accu_ms, accu_launches = prof["accumulate"]
+    kernels = {
+        "search_kernel": {"avg_launch_us": round(srch_ms * 1e3 / max(1, srch_launches), 2),
+                          "GBs": round((nte * W * 4 + nte * 4 * (wl.C + 1)) * srch_launches / (srch_ms * 1e-3) / 1e9, 2)
+                          if srch_ms > 0 else 0.0},
+        "accumulate_kernel": {"avg_launch_us": round(accu_ms * 1e3 / max(1, accu_launches), 2),
+                              "GBs": round((ntr * W * 4 + ntr * 4) * accu_launches / (accu_ms * 1e-3) / 1e9, 2)
+                              if accu_ms > 0 else 0.0},
+        "quantize_kernel": {"avg_launch_us": round(prof["quantize"][0] * 1e3 / max(1, prof["quantize"][1]), 2)},
+    }
+
+    out = {
+        "metric": "encoded+trained samples/sec and Hamming queries/sec at D=10000; % HBM roofline",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "configs[1]: classical HDC, D=10000, F=617 fp32, L=64, C=26, "
+                               "6238 train / 1559 test (ISOLET shape, seeded Gaussian clusters)",
+                   "step": "encode(train)+train_classical+binarize | encode(test) | search"},
+        "queries_per_s": round(queries, 1),
+        "encode_test_samples_per_s": round(nte / (t_enc_s.mean() * 1e-3), 1),
+        "stage_ms": {"encode_train_plus_train": round(float(t_train.mean()), 4),
+                     "encode_test": round(float(t_enc_s.mean()), 4),
+                     "search": round(float(t_search.mean()), 4)},
+        "test_accuracy": round(accuracy, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_extras:
+        out["extras"] = extras(torch, binding, make_workload)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, xt_h, yt_h)
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
+def _timed(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def extras(torch, binding, make_workload):
+    """Large-N figures for the HBM-bound kernels (CHB-MIT-shaped: C=2, one 1M-window chunk of
+    random packed hypervectors) and the online trainer on the UCIHAR-shaped config."""
+    res = {}
+    dev = "cuda"
+    # --- config 5 shape: search and classical accumulation over 1M packed rows
+    wl5 = make_workload(5)
+    ctx = binding.Context(wl5.D, wl5.F, wl5.L, wl5.C, wl5.item, wl5.level, wl5.tie, wl5.lo, wl5.scale, wl5.dtype)
+    N = 1 << 20
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    hv = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, ctx.W), dtype=torch.int32, device=dev, generator=g)
+    hv[:, -1] &= (1 << (wl5.D - 32 * (ctx.W - 1))) - 1
+    y = (torch.rand(N, device=dev, generator=g) < 0.01).to(torch.int32)
+    cls = hv[:2].clone()
+    pred = torch.empty(N, dtype=torch.int32, device=dev)
+    acc = torch.zeros((2, wl5.D), dtype=torch.int32, device=dev)
+    cn = torch.zeros(2, dtype=torch.int64, device=dev)
+    bytes_rows = N * ctx.W * 4
+    ms = _timed(torch, lambda: ctx.hdc_search(hv, cls, pred, None), 5)
+    res["search_1M_C2"] = {"ms": round(ms, 4), "queries_per_s": round(N / ms * 1e3, 0),
+                           "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),
+                           "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    ms = _timed(torch, lambda: ctx.hdc_train_classical(hv, y, acc, cn), 5)
+    res["train_classical_1M_C2"] = {"ms": round(ms, 4), "samples_per_s": round(N / ms * 1e3, 0),
+                                    "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),
+                                    "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    x5, _ = wl5.train(65536)
+    x5d = torch.from_numpy(x5).to(dev)
+    hv5 = torch.empty((65536, ctx.W), dtype=torch.int32, device=dev)
+    ms = _timed(torch, lambda: ctx.hdc_encode(x5d, hv5), 3)
+    res["encode_64k_cfg5"] = {"ms": round(ms, 4), "samples_per_s": round(65536 / ms * 1e3, 0),
+                              "frac_valu": round(3.0 * wl5.F * ctx.W * 65536 / (ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, 4)}
+    ctx.close()
+    del hv, y, pred, x5d, hv5
+    # --- config 4 shape: online training, one epoch over 7352 samples (a dependency chain)
+    wl4 = make_workload(4)
+    ctx = binding.Context(wl4.D, wl4.F, wl4.L, wl4.C, wl4.item, wl4.level, wl4.tie, wl4.lo, wl4.scale, wl4.dtype)
+    x4, y4 = wl4.train()
+    x4d, y4d = torch.from_numpy(x4).to(dev), torch.from_numpy(y4).to(dev)
+    hv4 = torch.empty((x4.shape[0], ctx.W), dtype=torch.int32, device=dev)
+    ctx.hdc_encode(x4d, hv4)
+    acc4 = torch.zeros((wl4.C, wl4.D), dtype=torch.float32, device=dev)
+
+    def online():
+        acc4.zero_()
+        ctx.hdc_train_online(hv4, y4d, acc4, epochs=1, lr=wl4.lr)
+    ms = _timed(torch, online, 2)
+    res["train_online_cfg4_1epoch"] = {"ms": round(ms, 3), "us_per_step": round(ms * 1e3 / x4.shape[0], 3),
+                                       "samples_per_s": round(x4.shape[0] / ms * 1e3, 0)}
+    ctx.close()
+    return res
+
+
+def cpu_baseline(wl, xt_h, yt_h):
+    """The CPU oracle, as it stands, on a bounded prefix of the same train set (about 15 s)."""
+    import oracle
+    oracle.build()
+    probe = 128
+    t = time.perf_counter()
+    oracle.encode(xt_h[:probe], wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+    per = (time.perf_counter() - t) / probe
+    n = int(min(xt_h.shape[0], max(probe, 15.0 / max(per, 1e-9))))
+    t = time.perf_counter()
+    hv = oracle.encode(xt_h[:n], wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+    acc, cn = oracle.train_classical(hv, yt_h[:n], wl.D, wl.C)
+    m = oracle.binarize_classical(acc, cn, wl.tie)
+    dt = time.perf_counter() - t
+    t = time.perf_counter()
+    oracle.search(hv, m, wl.D)
+    ds = time.perf_counter() - t
+    return {"value": round(n / dt, 1), "unit": "samples/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {n} of {xt_h.shape[0]} train samples of configs[1]: oracle encode + "
+                      f"train_classical + binarize ({dt:.1f} s); search of the same {n} rows: "
+                      f"{n / ds:.0f} queries/s",
+            "queries_per_s": round(n / ds, 1)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -142,6 +142,27 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream);
 
+/*
+ * Measurement aid (not an operation of the paper): per-kernel device time.  While enabled,
+ * every launch of a hot kernel is bracketed by a pair of HIP events recorded on the stream
+ * the kernel runs on.  hdc_profile_read waits for the recorded events of one kernel, returns
+ * the summed elapsed milliseconds and the number of timed launches, and forgets them.  At
+ * most HDC_PROFILE_SLOTS launches per kernel are kept between two reads; later ones run
+ * untimed.  Disabled by default (no events, no overhead).  total_ms / launches are HOST
+ * pointers.
+ */
+typedef enum {
+    HDC_K_ENCODE = 0,     /* bind + bundle + majority kernel of hdc_encode */
+    HDC_K_QUANTIZE = 1,   /* bin-index kernel of hdc_encode */
+    HDC_K_ACCUMULATE = 2, /* per-class vertical count kernel of hdc_train_classical */
+    HDC_K_ONLINE = 3,     /* sequential updater of hdc_train_online */
+    HDC_K_SEARCH = 4,     /* Hamming distance + argmin kernel of hdc_search */
+    HDC_K_COUNT = 5
+} hdc_kernel_id;
+#define HDC_PROFILE_SLOTS 512
+int hdc_profile_enable(hdc_ctx *ctx, int enable);
+int hdc_profile_read(hdc_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+
 /* Text for a status code (static storage, never NULL). */
 const char *hdc_strerror(int code);
 

@@ -52,6 +52,11 @@ def _c(a, dtype) -> np.ndarray:
 I64, I32 = ctypes.c_int64, ctypes.c_int32
 
 
+def threads() -> int:
+    """Host threads the sample-parallel oracle loops use."""
+    return int(_load().orc_threads())
+
+
 def unpack(words: np.ndarray, D: int) -> np.ndarray:
     """u32 words ``[..., W]`` -> {0,1} bytes ``[..., D]``."""
     words = _c(words, np.uint32)

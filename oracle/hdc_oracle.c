@@ -37,6 +37,20 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the "parallel for" loops over samples will use (1 without OpenMP). */
+int32_t orc_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /* ---- layout helpers (Sec. IV-B1: bits are packed into 32-bit integers) -------- */
 
 /* words[r][W] -> bits[r][D], dimension d = bit (d mod 32) of word (d div 32). */

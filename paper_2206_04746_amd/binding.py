@@ -22,7 +22,10 @@ HDC_F32, HDC_U8 = 0, 1
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search",
+           "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
+
+KERNEL_IDS = {"encode": 0, "quantize": 1, "accumulate": 2, "online": 3, "search": 4}
 
 
 class HdcParams(ctypes.Structure):
@@ -51,6 +54,11 @@ def _load() -> ctypes.CDLL:
     lib.hdc_train_online.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp]
     lib.hdc_binarize_online.argtypes = [vp, vp, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    lib.hdc_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.hdc_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                     ctypes.POINTER(ctypes.c_int64)]
+    lib.hdc_profile_enable.restype = ctypes.c_int
+    lib.hdc_profile_read.restype = ctypes.c_int
     for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
                  "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search"):
         getattr(lib, name).restype = ctypes.c_int
@@ -162,6 +170,16 @@ class Context:
                               _dev(class_hv, torch.int32, (self.C, self.W)),
                               _dev(dist, torch.int32, (N, self.C)), _dev(pred, torch.int32, (N,)),
                               _stream(stream)))
+
+
+    def hdc_profile_enable(self, enable: bool = True) -> None:
+        _check(lib.hdc_profile_enable(self._h, int(bool(enable))))
+
+    def hdc_profile_read(self, kernel: str):
+        """(total device milliseconds, timed launches) of one hot kernel since the last read."""
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(lib.hdc_profile_read(self._h, KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
 
 
 def version() -> str:

@@ -154,9 +154,12 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
                            c->cls_cur_d, c->perm_d);
         const unsigned items = (unsigned)((n + kRowBlock - 1) / kRowBlock) + (unsigned)C;
         const unsigned slice_groups = (unsigned)((c->Wp / kSliceWords + kAccWaves - 1) / kAccWaves);
-        hipLaunchKernelGGL(accumulate_kernel, dim3(items, slice_groups), dim3(kAccWaves * kWave), 0, s,
-                           hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, C, c->W, c->p.D,
-                           acc);
+        {
+            ProfScope prof(c, HDC_K_ACCUMULATE, s);
+            hipLaunchKernelGGL(accumulate_kernel, dim3(items, slice_groups), dim3(kAccWaves * kWave), 0,
+                               s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, C, c->W,
+                               c->p.D, acc);
+        }
         HDC_HIP(hipGetLastError());
     }
     return HDC_OK;

@@ -2,7 +2,7 @@
 //   hv[n][d] = majority_f( item[f][d] XOR level[bin(x[n][f])][d] ).
 //
 // Two kernels per chunk of samples:
-//   quantize_kernel  features -> one bin index byte per (sample, feature)   (HBM-bound, tiny)
+//   quantize_kernel  features -> one 16-bit level-row offset per (sample, feature)  (tiny)
 //   encode_kernel    bind + bundle + majority + pack                        (VALU-bound)
 //
 // encode_kernel keeps the per-dimension vote counts bit-sliced: a lane owns one 32-bit word
@@ -26,20 +26,22 @@ __device__ __forceinline__ uint32_t bin_f32(float x, float lo, float scale, int 
     return (uint32_t)(int)t;
 }
 
-// One thread produces the four bin bytes of features 4g..4g+3 of one sample; features at
-// or beyond F (the tie-vote row and the pad rows of the device item table) get bin 0.
+// One thread produces the entries of features 4g..4g+3 of one sample.  An entry is the byte
+// offset of the bin's row in the LDS level slice (bin * 256, fits 16 bits for L <= 256);
+// features at or beyond F (the tie-vote row and the pad rows of the device item table) get
+// bin 0.
 template <bool kU8>
 __global__ __launch_bounds__(256) void quantize_kernel(const void *__restrict__ feats, int64_t N,
                                                         int F, int Fp, int L,
                                                         const float *__restrict__ lo,
                                                         const float *__restrict__ scale,
-                                                        uint32_t *__restrict__ q4) {
+                                                        uint2 *__restrict__ q4) {
     const int groups = Fp >> 2;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= N * groups) return;
     const int64_t n = i / groups;
     const int f0 = (int)(i - n * groups) << 2;
-    uint32_t packed = 0;
+    uint32_t packed[2] = {0u, 0u};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int f = f0 + k;
@@ -51,20 +53,53 @@ __global__ __launch_bounds__(256) void quantize_kernel(const void *__restrict__ 
                 b = bin_f32(reinterpret_cast<const float *>(feats)[n * F + f], lo[f], scale[f], L);
             }
         }
-        packed |= b << (8 * k);
+        packed[k >> 1] |= (b * (kSliceWords * 4u)) << (16 * (k & 1));
     }
-    q4[i] = packed;
+    q4[i] = make_uint2(packed[0], packed[1]);
 }
 
 // ------------------------------------------------------------- bundling (Eq. 1's sum)
-// Adds the 2^LV bound words of features J0 .. J0+2^LV-1 into planes 0..LV-1 and returns the
-// carry of weight 2^LV.  Depth-first, so only one pending carry per level is alive.
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+
+// Level words of 16 features for this lane's column, fetched from the LDS level slice.
+// qpair[k] holds the LDS byte offsets (bin * 256) of features 2k and 2k+1 as two u16.  The
+// row offset is wave-uniform, so it goes through M0 and ds_read_addtid_b32 (address = M0 +
+// lane * 4): no vector ALU work is spent on addresses.  One wait state separates a write of
+// M0 from the LDS instruction that reads it; the trailing s_waitcnt makes the outputs valid.
+__device__ __forceinline__ void gather16(uint32_t (&x)[16], const uint32_t (&qpair)[8]) {
+    asm volatile(
+        "s_and_b32 m0, %16, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
+        "s_lshr_b32 m0, %16, 16\n\ts_nop 0\n\tds_read_addtid_b32 %1\n\t"
+        "s_and_b32 m0, %17, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %2\n\t"
+        "s_lshr_b32 m0, %17, 16\n\ts_nop 0\n\tds_read_addtid_b32 %3\n\t"
+        "s_and_b32 m0, %18, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %4\n\t"
+        "s_lshr_b32 m0, %18, 16\n\ts_nop 0\n\tds_read_addtid_b32 %5\n\t"
+        "s_and_b32 m0, %19, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %6\n\t"
+        "s_lshr_b32 m0, %19, 16\n\ts_nop 0\n\tds_read_addtid_b32 %7\n\t"
+        "s_and_b32 m0, %20, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %8\n\t"
+        "s_lshr_b32 m0, %20, 16\n\ts_nop 0\n\tds_read_addtid_b32 %9\n\t"
+        "s_and_b32 m0, %21, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %10\n\t"
+        "s_lshr_b32 m0, %21, 16\n\ts_nop 0\n\tds_read_addtid_b32 %11\n\t"
+        "s_and_b32 m0, %22, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %12\n\t"
+        "s_lshr_b32 m0, %22, 16\n\ts_nop 0\n\tds_read_addtid_b32 %13\n\t"
+        "s_and_b32 m0, %23, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %14\n\t"
+        "s_lshr_b32 m0, %23, 16\n\ts_nop 0\n\tds_read_addtid_b32 %15\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]),
+          "=&v"(x[7]), "=&v"(x[8]), "=&v"(x[9]), "=&v"(x[10]), "=&v"(x[11]), "=&v"(x[12]),
+          "=&v"(x[13]), "=&v"(x[14]), "=&v"(x[15])
+        : "s"(qpair[0]), "s"(qpair[1]), "s"(qpair[2]), "s"(qpair[3]), "s"(qpair[4]), "s"(qpair[5]),
+          "s"(qpair[6]), "s"(qpair[7])
+        : "m0", "scc", "memory");
+}
+
+// Adds the 2^LV bound words x[J0 .. J0+2^LV-1] into planes 0..LV-1 and returns the carry of
+// weight 2^LV.  Depth-first, so only one pending carry per level is alive.
 template <int LV, int J0>
 struct Tree {
-    static __device__ __forceinline__ uint32_t run(uint32_t *pl, const uint32_t *id,
-                                                   const uint32_t *lv_lane, const uint32_t *qw) {
-        const uint32_t a = Tree<LV - 1, J0>::run(pl, id, lv_lane, qw);
-        const uint32_t b = Tree<LV - 1, J0 + (1 << (LV - 1))>::run(pl, id, lv_lane, qw);
+    static __device__ __forceinline__ uint32_t run(uint32_t *pl, const uint32_t *x) {
+        const uint32_t a = Tree<LV - 1, J0>::run(pl, x);
+        const uint32_t b = Tree<LV - 1, J0 + (1 << (LV - 1))>::run(pl, x);
         const uint32_t p = pl[LV - 1];
         pl[LV - 1] = xor3(p, a, b);
         return maj3(p, a, b);
@@ -72,47 +107,52 @@ struct Tree {
 };
 template <int J0>
 struct Tree<1, J0> {
-    static __device__ __forceinline__ uint32_t bound(const uint32_t *id, const uint32_t *lv_lane,
-                                                     const uint32_t *qw, int j) {
-        const uint32_t bin = (qw[j >> 2] >> (8 * (j & 3))) & 0xffu;   // wave-uniform
-        return id[j] ^ lv_lane[bin * kSliceWords];                     // bind (XOR)
-    }
-    static __device__ __forceinline__ uint32_t run(uint32_t *pl, const uint32_t *id,
-                                                   const uint32_t *lv_lane, const uint32_t *qw) {
-        const uint32_t x0 = bound(id, lv_lane, qw, J0);
-        const uint32_t x1 = bound(id, lv_lane, qw, J0 + 1);
+    static __device__ __forceinline__ uint32_t run(uint32_t *pl, const uint32_t *x) {
         const uint32_t p = pl[0];
-        pl[0] = xor3(p, x0, x1);
-        return maj3(p, x0, x1);
+        pl[0] = xor3(p, x[J0], x[J0 + 1]);
+        return maj3(p, x[J0], x[J0 + 1]);
     }
 };
 
-typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
-constexpr int kEncodeWaves = 4;   // waves per block of encode_kernel
+// Carry `c` of weight 2^FROM rippled into planes FROM..P-1 (half adders).
+template <int FROM, int P>
+__device__ __forceinline__ void ripple(uint32_t *pl, uint32_t c) {
+#pragma unroll
+    for (int i = FROM; i < P; ++i) {
+        const uint32_t t = pl[i] & c;
+        pl[i] ^= c;
+        c = t;
+    }
+}
 
-// Block = kEncodeWaves waves, all on the same slice of 64 word columns (one column per lane);
-// each wave carries S samples through all Fp features.  Dynamic LDS: level[L][64].
-template <int S, int P>
-__global__ __launch_bounds__(kEncodeWaves * kWave) void encode_kernel(const uint8_t *__restrict__ q,
-                                                      const uint32_t *__restrict__ item,
-                                                      const uint32_t *__restrict__ level,
-                                                      uint32_t *__restrict__ hv, int N, int Fp, int L,
-                                                      int W, int Wp, uint32_t bias) {
+// Block = WAVES waves, all on the same slice of 64 word columns (one column per lane, level
+// slice [L][64] in dynamic LDS, which starts at LDS address 0 because the kernel has no static
+// LDS); each wave carries S samples through all Fp features, 16 at a time.
+template <int S, int P, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
+    const uint16_t *__restrict__ q, const uint32_t *__restrict__ item,
+    const uint32_t *__restrict__ level, uint32_t *__restrict__ hv, int N, int Fp, int L, int W, int Wp,
+    uint32_t bias) {
     extern __shared__ uint32_t lv[];
     const int slice = blockIdx.x;
     const int tile = blockIdx.y;
     const int lane = threadIdx.x & (kWave - 1);
     const int col = slice * kSliceWords + lane;
 
-    for (int i = threadIdx.x; i < L * kSliceWords; i += kEncodeWaves * kWave)
+    for (int i = threadIdx.x; i < L * kSliceWords; i += WAVES * kWave)
         lv[i] = level[(int64_t)(i >> 6) * Wp + slice * kSliceWords + (i & 63)];
     __syncthreads();
 
-    // kEncodeWaves is a compile-time constant on purpose: a block size read from the dispatch
-    // packet makes the compiler treat the sample index as divergent and the bin loads as vector.
+    // WAVES is a compile-time constant on purpose: a block size read from the dispatch packet
+    // makes the compiler treat the sample index as divergent and the bin loads as vector loads.
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n_base = (tile * kEncodeWaves + wave) * S;
+    const int n_base = (tile * WAVES + wave) * S;
     if (n_base >= N) return;
+
+    // LDS byte address of the level slice, replicated into both halves of a dword so that one
+    // scalar add rebases two packed offsets (it is 0 unless static LDS is ever added here).
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lv;
+    const uint32_t rebase = lds_base | (lds_base << 16);
 
     uint32_t pl[S][P];
 #pragma unroll
@@ -120,7 +160,7 @@ __global__ __launch_bounds__(kEncodeWaves * kWave) void encode_kernel(const uint
 #pragma unroll
         for (int i = 0; i < P; ++i) pl[s][i] = ((bias >> i) & 1u) ? 0xffffffffu : 0u;
 
-    // The bin bytes are wave-uniform and were written by an earlier kernel: read them through
+    // The bin offsets are wave-uniform and were written by an earlier kernel: read them through
     // the constant address space so they arrive by scalar loads, off the vector pipeline.
     const_u32_ptr qrow[S];
 #pragma unroll
@@ -128,28 +168,46 @@ __global__ __launch_bounds__(kEncodeWaves * kWave) void encode_kernel(const uint
         const int n = min(n_base + s, N - 1);   // a ragged last wave recomputes row N-1
         qrow[s] = (const_u32_ptr)(uintptr_t)(q + (int64_t)n * Fp);
     }
-    const uint32_t *lv_lane = lv + lane;
 
-    for (int f0 = 0; f0 < Fp; f0 += kFeatBlock) {
-        uint32_t id[kFeatBlock];
+    // One half-block: bind 16 features of every sample of this wave with their level rows and
+    // bundle them; c16[s] receives the carry of weight 16.
+    auto half_block = [&](int f0, uint32_t (&c16)[S]) {
+        uint32_t id[16];
 #pragma unroll
-        for (int j = 0; j < kFeatBlock; ++j) {
+        for (int j = 0; j < 16; ++j) {
             const uint32_t *row = item + (int64_t)(f0 + j) * Wp;   // uniform base, lane offset
             id[j] = row[col];
         }
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            uint32_t qw[kFeatBlock / 4];
+            uint32_t qpair[8];
 #pragma unroll
-            for (int k = 0; k < kFeatBlock / 4; ++k) qw[k] = qrow[s][(f0 >> 2) + k];
-            uint32_t c = Tree<5, 0>::run(pl[s], id, lv_lane, qw);   // carry of weight 32
+            for (int k = 0; k < 8; ++k) qpair[k] = qrow[s][(f0 >> 1) + k] + rebase;
+            uint32_t x[16];
+            gather16(x, qpair);
 #pragma unroll
-            for (int i = 5; i < P; ++i) {                            // ripple it upward
-                const uint32_t t = pl[s][i] & c;
-                pl[s][i] ^= c;
-                c = t;
-            }
+            for (int j = 0; j < 16; ++j) x[j] ^= id[j];     // bind (XOR)
+            c16[s] = Tree<4, 0>::run(pl[s], x);              // bundle 16 votes
         }
+    };
+
+    int f0 = 0;
+    for (; f0 + 32 <= Fp; f0 += 32) {
+        uint32_t ca[S], cb[S];
+        half_block(f0, ca);
+        half_block(f0 + 16, cb);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const uint32_t p = pl[s][4];
+            pl[s][4] = xor3(p, ca[s], cb[s]);
+            ripple<5, P>(pl[s], maj3(p, ca[s], cb[s]));
+        }
+    }
+    if (f0 < Fp) {   // Fp is a multiple of 16: one unpaired half-block may remain
+        uint32_t ca[S];
+        half_block(f0, ca);
+#pragma unroll
+        for (int s = 0; s < S; ++s) ripple<4, P>(pl[s], ca[s]);
     }
 
     if (col < W) {
@@ -159,15 +217,22 @@ __global__ __launch_bounds__(kEncodeWaves * kWave) void encode_kernel(const uint
     }
 }
 
-template <int S, int P>
-static int launch_encode_sp(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+template <int S, int P, int WAVES>
+static void launch_encode_spw(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
     const int nslices = c->Wp / kSliceWords;
-    const int waves = kEncodeWaves;
-    const int tiles = (N + waves * S - 1) / (waves * S);
+    const int tiles = (N + WAVES * S - 1) / (WAVES * S);
     const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
-    hipLaunchKernelGGL((encode_kernel<S, P>), dim3((unsigned)nslices, (unsigned)tiles), dim3(waves * kWave), lds, s,
-                       c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L, c->W, c->Wp, bias);
-    return HDC_OK;
+    ProfScope prof(c, HDC_K_ENCODE, s);
+    hipLaunchKernelGGL((encode_kernel<S, P, WAVES>), dim3((unsigned)nslices, (unsigned)tiles),
+                       dim3(WAVES * kWave), lds, s, c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L,
+                       c->W, c->Wp, bias);
+}
+
+template <int S, int P>
+static void launch_encode_sp(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+    // a large level table leaves room for few blocks per CU: use bigger blocks then
+    if (c->p.L > 128) launch_encode_spw<S, P, 8>(c, N, hv, bias, s);
+    else launch_encode_spw<S, P, 4>(c, N, hv, bias, s);
 }
 
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
@@ -187,12 +252,16 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
         const void *x = reinterpret_cast<const uint8_t *>(feats) + (size_t)n0 * c->p.F * esz;
         const int64_t items = n * (c->Fp >> 2);
         const unsigned qblocks = (unsigned)((items + 255) / 256);
-        if (c->p.feat_dtype == HDC_U8)
-            hipLaunchKernelGGL(quantize_kernel<true>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
-                               c->Fp, c->p.L, c->lo_d, c->scale_d, reinterpret_cast<uint32_t *>(c->q_d));
-        else
-            hipLaunchKernelGGL(quantize_kernel<false>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
-                               c->Fp, c->p.L, c->lo_d, c->scale_d, reinterpret_cast<uint32_t *>(c->q_d));
+        {
+            ProfScope prof(c, HDC_K_QUANTIZE, s);
+            uint2 *q4 = reinterpret_cast<uint2 *>(c->q_d);
+            if (c->p.feat_dtype == HDC_U8)
+                hipLaunchKernelGGL(quantize_kernel<true>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
+                                   c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
+            else
+                hipLaunchKernelGGL(quantize_kernel<false>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
+                                   c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
+        }
         uint32_t *out = hv + (size_t)n0 * c->W;
         switch (P) {
             case 6: launch_encode_sp<4, 6>(c, (int)n, out, bias, s); break;

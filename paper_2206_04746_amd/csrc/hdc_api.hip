@@ -27,6 +27,12 @@ static void free_ctx(hdc_ctx_impl *c) {
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->online_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    for (int k = 0; k < HDC_K_COUNT; ++k) {
+        if (!c->prof_ev[k]) continue;
+        for (int i = 0; i < 2 * HDC_PROFILE_SLOTS; ++i)
+            if (c->prof_ev[k][i]) (void)hipEventDestroy(c->prof_ev[k][i]);
+        free(c->prof_ev[k]);
+    }
     delete c;
 }
 
@@ -226,6 +232,38 @@ int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *
         return HDC_EINVAL;
     return launch_search(impl(ctx), hv_dev, N, class_hv_dev, dist_dev, pred_dev,
                          static_cast<hipStream_t>(stream));
+}
+
+int hdc_profile_enable(hdc_ctx *ctx, int enable) {
+    if (!ctx) return HDC_EINVAL;
+    hdc_ctx_impl *c = impl(ctx);
+    if (enable) {
+        for (int k = 0; k < HDC_K_COUNT; ++k) {
+            if (c->prof_ev[k]) continue;
+            c->prof_ev[k] = static_cast<hipEvent_t *>(calloc(2 * HDC_PROFILE_SLOTS, sizeof(hipEvent_t)));
+            if (!c->prof_ev[k]) return HDC_ENOMEM;
+            for (int i = 0; i < 2 * HDC_PROFILE_SLOTS; ++i) HDC_HIP(hipEventCreate(&c->prof_ev[k][i]));
+        }
+    }
+    c->prof_on = enable != 0;
+    return HDC_OK;
+}
+
+int hdc_profile_read(hdc_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches) {
+    if (!ctx || kernel_id < 0 || kernel_id >= HDC_K_COUNT || !total_ms || !launches) return HDC_EINVAL;
+    hdc_ctx_impl *c = impl(ctx);
+    double sum = 0.0;
+    const int n = c->prof_ev[kernel_id] ? c->prof_used[kernel_id] : 0;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.0f;
+        HDC_HIP(hipEventSynchronize(c->prof_ev[kernel_id][2 * i + 1]));
+        HDC_HIP(hipEventElapsedTime(&ms, c->prof_ev[kernel_id][2 * i], c->prof_ev[kernel_id][2 * i + 1]));
+        sum += (double)ms;
+    }
+    c->prof_used[kernel_id] = 0;
+    *total_ms = sum;
+    *launches = n;
+    return HDC_OK;
 }
 
 const char *hdc_strerror(int code) {

@@ -11,7 +11,7 @@ namespace hdc {
 
 constexpr int kWave = 64;         // CDNA4 wavefront width
 constexpr int kSliceWords = 64;   // one 32-bit word column per lane: a wave owns 64 words
-constexpr int kFeatBlock = 32;    // features consumed per carry-save tree in encode
+constexpr int kFeatBlock = 16;    // features consumed per carry-save tree in encode
 
 // Device-side copy of the model: everything the kernels need, laid out for them.
 struct hdc_ctx_impl {
@@ -34,7 +34,7 @@ struct hdc_ctx_impl {
     float *scale_d;     // [F]
 
     // Scratch owned by the context (sized at create, never grown on the hot path).
-    uint8_t *q_d;         // [kEncodeChunk][Fp] bin indices of the samples being encoded
+    uint16_t *q_d;        // [q_rows][Fp] level-row offsets (bin * 256) of the samples being encoded
     int64_t q_rows;       // rows q_d can hold
     uint32_t *cls_cnt_d;  // [C + 1] per-class sample counts of the current training chunk
     uint32_t *cls_off_d;  // [C + 1] exclusive prefix of cls_cnt_d
@@ -43,6 +43,29 @@ struct hdc_ctx_impl {
     uint32_t *perm_d;     // [perm_rows] sample indices grouped by class
     int64_t perm_rows;
     double *online_d;     // scratch of the online trainer (norms, partial sums)
+
+    // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.
+    bool prof_on;
+    hipEvent_t *prof_ev[HDC_K_COUNT];   // [2 * HDC_PROFILE_SLOTS] start/stop interleaved
+    int prof_used[HDC_K_COUNT];
+};
+
+// Brackets one kernel launch with events when profiling is enabled; otherwise does nothing.
+struct ProfScope {
+    hdc_ctx_impl *c;
+    int id;
+    hipStream_t s;
+    bool live;
+    ProfScope(hdc_ctx_impl *ctx, int kernel_id, hipStream_t stream)
+        : c(ctx), id(kernel_id), s(stream), live(false) {
+        if (c->prof_on && c->prof_ev[id] && c->prof_used[id] < HDC_PROFILE_SLOTS) {
+            live = hipEventRecord(c->prof_ev[id][2 * c->prof_used[id]], s) == hipSuccess;
+        }
+    }
+    ~ProfScope() {
+        if (live && hipEventRecord(c->prof_ev[id][2 * c->prof_used[id] + 1], s) == hipSuccess)
+            c->prof_used[id] += 1;
+    }
 };
 
 // Records a HIP failure for hdc_last_hip_error() and maps it to HDC_EHIP.

@@ -136,8 +136,11 @@ int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labe
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(kern, dim3(1), dim3(kOnlineThreads), lds, s, hv, labels, N, (int)epochs, lr, acc,
-                       c->p.D, c->W, C, sqrt((double)c->p.D));
+    {
+        ProfScope prof(c, HDC_K_ONLINE, s);
+        hipLaunchKernelGGL(kern, dim3(1), dim3(kOnlineThreads), lds, s, hv, labels, N, (int)epochs, lr,
+                           acc, c->p.D, c->W, C, sqrt((double)c->p.D));
+    }
     HDC_HIP(hipGetLastError());
     return HDC_OK;
 }

@@ -131,8 +131,11 @@ static int launch_search_wpl(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, con
     const int64_t tiles = (N + kRows - 1) / kRows;
     int64_t blocks = (tiles + kSearchWaves - 1) / kSearchWaves;
     if (blocks > 256 * 16) blocks = 256 * 16;   // persistent-style grid, a few blocks per CU
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kSearchWaves * kWave), lds, s, hv, N, class_hv,
-                       c->p.C, c->W, dist, pred);
+    {
+        ProfScope prof(c, HDC_K_SEARCH, s);
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kSearchWaves * kWave), lds, s, hv, N,
+                           class_hv, c->p.C, c->W, dist, pred);
+    }
     HDC_HIP(hipGetLastError());
     return HDC_OK;
 }
