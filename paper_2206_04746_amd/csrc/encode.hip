@@ -65,7 +65,9 @@ typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 // qpair[k] holds the LDS byte offsets (bin * 256) of features 2k and 2k+1 as two u16.  The
 // row offset is wave-uniform, so it goes through M0 and ds_read_addtid_b32 (address = M0 +
 // lane * 4): no vector ALU work is spent on addresses.  One wait state separates a write of
-// M0 from the LDS instruction that reads it; the trailing s_waitcnt makes the outputs valid.
+// M0 from the LDS instruction that reads it.
+//
+// The trailing s_waitcnt makes the outputs valid before the asm statement ends.
 __device__ __forceinline__ void gather16(uint32_t (&x)[16], const uint32_t (&qpair)[8]) {
     asm volatile(
         "s_and_b32 m0, %16, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
@@ -90,9 +92,8 @@ __device__ __forceinline__ void gather16(uint32_t (&x)[16], const uint32_t (&qpa
           "=&v"(x[13]), "=&v"(x[14]), "=&v"(x[15])
         : "s"(qpair[0]), "s"(qpair[1]), "s"(qpair[2]), "s"(qpair[3]), "s"(qpair[4]), "s"(qpair[5]),
           "s"(qpair[6]), "s"(qpair[7])
-        : "m0", "scc", "memory");
+        : "scc", "memory");
 }
-
 // Adds the 2^LV bound words x[J0 .. J0+2^LV-1] into planes 0..LV-1 and returns the carry of
 // weight 2^LV.  Depth-first, so only one pending carry per level is alive.
 template <int LV, int J0>
@@ -126,113 +127,190 @@ __device__ __forceinline__ void ripple(uint32_t *pl, uint32_t c) {
 }
 
 // Block = WAVES waves, all on the same slice of 64 word columns (one column per lane, level
-// slice [L][64] in dynamic LDS, which starts at LDS address 0 because the kernel has no static
-// LDS); each wave carries S samples through all Fp features, 16 at a time.
-template <int S, int P, int WAVES>
+// slice [L][64] in dynamic LDS; the level-row offsets the quantiser wrote are absolute LDS
+// byte addresses, which holds because this kernel has no static LDS, so its dynamic LDS starts
+// at address 0 - the launcher checks that).  The waves form WAVES/FS groups; a group carries S samples through all Fp features,
+// 16 at a time, its FS waves each taking a contiguous share of the features and adding their
+// bit-sliced partial counts together through LDS at the end.  FS > 1 makes the work units
+// smaller, which is what a small batch needs to fill 1024 SIMDs; FS = 1 has no merge at all.
+template <int S, int P, int WAVES, int FS>
 __global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
     const uint16_t *__restrict__ q, const uint32_t *__restrict__ item,
     const uint32_t *__restrict__ level, uint32_t *__restrict__ hv, int N, int Fp, int L, int W, int Wp,
     uint32_t bias) {
     extern __shared__ uint32_t lv[];
+    constexpr int GROUPS = WAVES / FS;
     const int slice = blockIdx.x;
     const int tile = blockIdx.y;
     const int lane = threadIdx.x & (kWave - 1);
     const int col = slice * kSliceWords + lane;
 
-    for (int i = threadIdx.x; i < L * kSliceWords; i += WAVES * kWave)
-        lv[i] = level[(int64_t)(i >> 6) * Wp + slice * kSliceWords + (i & 63)];
+    {   // this slice of the level table is one contiguous run of L * 64 words
+        const uint32_t *src = level + (size_t)slice * L * kSliceWords;
+        for (int i = threadIdx.x; i < L * kSliceWords; i += WAVES * kWave) lv[i] = src[i];
+    }
     __syncthreads();
 
     // WAVES is a compile-time constant on purpose: a block size read from the dispatch packet
     // makes the compiler treat the sample index as divergent and the bin loads as vector loads.
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n_base = (tile * WAVES + wave) * S;
-    if (n_base >= N) return;
+    const int group = wave / FS;
+    const int part = wave % FS;
+    const int n_base = (tile * GROUPS + group) * S;
+    const bool live = n_base < N;
+    if (FS == 1 && !live) return;   // with FS > 1 every wave must reach the merge barriers
 
-    // LDS byte address of the level slice, replicated into both halves of a dword so that one
-    // scalar add rebases two packed offsets (it is 0 unless static LDS is ever added here).
-    const uint32_t lds_base = (uint32_t)(uintptr_t)lv;
-    const uint32_t rebase = lds_base | (lds_base << 16);
-
+    // Only the first wave of a group starts from the bias; the others add plain partial counts.
+    const uint32_t my_bias = part == 0 ? bias : 0u;
     uint32_t pl[S][P];
 #pragma unroll
     for (int s = 0; s < S; ++s)
 #pragma unroll
-        for (int i = 0; i < P; ++i) pl[s][i] = ((bias >> i) & 1u) ? 0xffffffffu : 0u;
+        for (int i = 0; i < P; ++i) pl[s][i] = ((my_bias >> i) & 1u) ? 0xffffffffu : 0u;
 
     // The bin offsets are wave-uniform and were written by an earlier kernel: read them through
     // the constant address space so they arrive by scalar loads, off the vector pipeline.
     const_u32_ptr qrow[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) {
-        const int n = min(n_base + s, N - 1);   // a ragged last wave recomputes row N-1
+        const int n = min(n_base + s, N - 1);   // a ragged last group recomputes row N-1
         qrow[s] = (const_u32_ptr)(uintptr_t)(q + (int64_t)n * Fp);
     }
 
-    // One half-block: bind 16 features of every sample of this wave with their level rows and
-    // bundle them; c16[s] receives the carry of weight 16.
-    auto half_block = [&](int f0, uint32_t (&c16)[S]) {
-        uint32_t id[16];
+    // This wave's share of the features: a contiguous run of 32-feature pairs (the last share
+    // also takes the unpaired half-block, if Fp is an odd multiple of 16).
+    const int pairs = Fp >> 5;
+    const int per = (pairs + FS - 1) / FS;
+    int f0 = min(part * per, pairs) << 5;
+    const int f_end = (part == FS - 1) ? Fp : (min((part + 1) * per, pairs) << 5);
+
+    // ID rows are loaded one half-block ahead of their use (ida / idb alternate), so their
+    // latency hides behind the arithmetic of the half-block before.
+    // (address = wave-uniform base of the half-block in SGPRs + this lane's byte offset +
+    // j * 256 as an immediate: no vector address arithmetic, no address registers)
+    const uint32_t lane_bytes = (uint32_t)lane * 4u;
+    const char *item_slice = reinterpret_cast<const char *>(item + (size_t)slice * Fp * kSliceWords);
+    auto load_ids = [&](int f, uint32_t (&id)[16]) {
+        const char *base = item_slice + (size_t)f * (kSliceWords * 4);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const uint32_t *row = item + (int64_t)(f0 + j) * Wp;   // uniform base, lane offset
-            id[j] = row[col];
-        }
+        for (int j = 0; j < 16; ++j)
+            id[j] = *reinterpret_cast<const uint32_t *>(base + j * (kSliceWords * 4) + lane_bytes);
+    };
+    // the S samples of one half-block: bind 16 features with their level rows and bundle
+    // them; c16[s] receives the carry of weight 16
+    auto half_block = [&](int f, const uint32_t (&id)[16], uint32_t (&c16)[S]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             uint32_t qpair[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) qpair[k] = qrow[s][(f0 >> 1) + k] + rebase;
+            for (int k = 0; k < 8; ++k) qpair[k] = qrow[s][(f >> 1) + k];
             uint32_t x[16];
             gather16(x, qpair);
 #pragma unroll
             for (int j = 0; j < 16; ++j) x[j] ^= id[j];     // bind (XOR)
             c16[s] = Tree<4, 0>::run(pl[s], x);              // bundle 16 votes
+            // Keep the samples in program order: the gathers are volatile and cannot move, so
+            // pinning the results here (empty volatile asm, no instruction) stops the compiler
+            // from sinking this sample's arithmetic below the next gathers, which would hold
+            // S * 16 landing registers alive at once.
+            asm volatile("" : "+v"(c16[s]), "+v"(pl[s][0]), "+v"(pl[s][1]), "+v"(pl[s][2]), "+v"(pl[s][3]));
         }
     };
 
-    int f0 = 0;
-    for (; f0 + 32 <= Fp; f0 += 32) {
-        uint32_t ca[S], cb[S];
-        half_block(f0, ca);
-        half_block(f0 + 16, cb);
+    if (live && f0 < f_end) {
+        uint32_t ida[16], idb[16];
+        load_ids(f0, ida);
+        for (; f0 + 32 <= f_end; f0 += 32) {
+            uint32_t ca[S], cb[S];
+            load_ids(f0 + 16, idb);
+            half_block(f0, ida, ca);
+            if (f0 + 32 < f_end) load_ids(f0 + 32, ida);
+            half_block(f0 + 16, idb, cb);
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            const uint32_t p = pl[s][4];
-            pl[s][4] = xor3(p, ca[s], cb[s]);
-            ripple<5, P>(pl[s], maj3(p, ca[s], cb[s]));
+            for (int s = 0; s < S; ++s) {
+                const uint32_t p = pl[s][4];
+                pl[s][4] = xor3(p, ca[s], cb[s]);
+                ripple<5, P>(pl[s], maj3(p, ca[s], cb[s]));
+            }
+        }
+        if (f0 < f_end) {   // the unpaired last half-block; its IDs are already in flight
+            uint32_t ca[S];
+            half_block(f0, ida, ca);
+#pragma unroll
+            for (int s = 0; s < S; ++s) ripple<4, P>(pl[s], ca[s]);
         }
     }
-    if (f0 < Fp) {   // Fp is a multiple of 16: one unpaired half-block may remain
-        uint32_t ca[S];
-        half_block(f0, ca);
+
+    if (FS > 1) {
+        // Sum the FS partial counts of every sample: waves 1..FS-1 of a group park their planes
+        // in LDS (behind the level slice), wave 0 adds them with P full adders each.
+        uint32_t *mbuf = lv + L * kSliceWords + group * ((FS - 1) * P * kWave);
 #pragma unroll
-        for (int s = 0; s < S; ++s) ripple<4, P>(pl[s], ca[s]);
+        for (int s = 0; s < S; ++s) {
+            if (part > 0) {
+#pragma unroll
+                for (int i = 0; i < P; ++i) mbuf[((part - 1) * P + i) * kWave + lane] = pl[s][i];
+            }
+            __syncthreads();
+            if (part == 0) {
+#pragma unroll
+                for (int r = 0; r < FS - 1; ++r) {
+                    uint32_t carry = 0;
+#pragma unroll
+                    for (int i = 0; i < P; ++i) {
+                        const uint32_t a = pl[s][i], b2 = mbuf[(r * P + i) * kWave + lane];
+                        pl[s][i] = xor3(a, b2, carry);
+                        carry = maj3(a, b2, carry);
+                    }
+                }
+            }
+            __syncthreads();
+        }
     }
 
-    if (col < W) {
+    if (part == 0 && live && col < W) {
 #pragma unroll
         for (int s = 0; s < S; ++s)
             if (n_base + s < N) hv[(int64_t)(n_base + s) * W + col] = pl[s][P - 1];
     }
 }
 
-template <int S, int P, int WAVES>
-static void launch_encode_spw(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+template <int S, int P, int WAVES, int FS>
+static int launch_encode_spwf(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+    constexpr int GROUPS = WAVES / FS;
     const int nslices = c->Wp / kSliceWords;
-    const int tiles = (N + WAVES * S - 1) / (WAVES * S);
-    const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
+    const int tiles = (N + GROUPS * S - 1) / (GROUPS * S);
+    const size_t lds = ((size_t)c->p.L * kSliceWords + (FS > 1 ? (size_t)GROUPS * (FS - 1) * P * kWave : 0)) *
+                       sizeof(uint32_t);
+    static int static_lds = -1;   // level-row offsets are absolute: no static LDS allowed
+    if (static_lds < 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(encode_kernel<S, P, WAVES, FS>)) !=
+            hipSuccess)
+            return HDC_EHIP;
+        static_lds = (int)attr.sharedSizeBytes;
+    }
+    if (static_lds != 0) return HDC_ELIMIT;
     ProfScope prof(c, HDC_K_ENCODE, s);
-    hipLaunchKernelGGL((encode_kernel<S, P, WAVES>), dim3((unsigned)nslices, (unsigned)tiles),
+    hipLaunchKernelGGL((encode_kernel<S, P, WAVES, FS>), dim3((unsigned)nslices, (unsigned)tiles),
                        dim3(WAVES * kWave), lds, s, c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L,
                        c->W, c->Wp, bias);
+    return HDC_OK;
 }
 
 template <int S, int P>
-static void launch_encode_sp(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+static int launch_encode_sp(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+    // Work units needed to give every SIMD of the chip a few waves; below that, split the
+    // features of a sample group over the waves of a block (smaller units, one LDS merge).
+    const int64_t units = (int64_t)((N + S - 1) / S) * (c->Wp / kSliceWords);
+    const bool split = units < 4 * 1024 * 4 && (c->Fp >> 5) >= 8;
     // a large level table leaves room for few blocks per CU: use bigger blocks then
-    if (c->p.L > 128) launch_encode_spw<S, P, 8>(c, N, hv, bias, s);
-    else launch_encode_spw<S, P, 4>(c, N, hv, bias, s);
+    if (c->p.L > 128) {
+        if (split) return launch_encode_spwf<S, P, 8, 4>(c, N, hv, bias, s);
+        return launch_encode_spwf<S, P, 8, 1>(c, N, hv, bias, s);
+    }
+    if (split) return launch_encode_spwf<S, P, 4, 4>(c, N, hv, bias, s);
+    return launch_encode_spwf<S, P, 4, 1>(c, N, hv, bias, s);
 }
 
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
@@ -263,13 +341,15 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
                                    c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
         }
         uint32_t *out = hv + (size_t)n0 * c->W;
+        int rc;
         switch (P) {
-            case 6: launch_encode_sp<4, 6>(c, (int)n, out, bias, s); break;
-            case 8: launch_encode_sp<4, 8>(c, (int)n, out, bias, s); break;
-            case 10: launch_encode_sp<4, 10>(c, (int)n, out, bias, s); break;
-            case 12: launch_encode_sp<4, 12>(c, (int)n, out, bias, s); break;
-            default: launch_encode_sp<4, 16>(c, (int)n, out, bias, s); break;
+            case 6: rc = launch_encode_sp<4, 6>(c, (int)n, out, bias, s); break;
+            case 8: rc = launch_encode_sp<4, 8>(c, (int)n, out, bias, s); break;
+            case 10: rc = launch_encode_sp<4, 10>(c, (int)n, out, bias, s); break;
+            case 12: rc = launch_encode_sp<4, 12>(c, (int)n, out, bias, s); break;
+            default: rc = launch_encode_sp<4, 16>(c, (int)n, out, bias, s); break;
         }
+        if (rc != HDC_OK) return rc;
         HDC_HIP(hipGetLastError());
     }
     return HDC_OK;

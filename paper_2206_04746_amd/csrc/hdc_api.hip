@@ -99,17 +99,24 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
         delete c;
         return HDC_ENOMEM;
     }
-    for (int l = 0; l < p->L; ++l)
-        memcpy(&level_h[(size_t)l * c->Wp], level + (size_t)l * W, (size_t)W * 4);
+    // slice-major layout: word w of row r lives at [(w / 64) * rows + r][w % 64]
+    const int nsl = c->Wp / kSliceWords;
+    auto put = [&](std::vector<uint32_t> &dst, int rows, int r, const uint32_t *src_row) {
+        for (int w = 0; w < W; ++w)
+            dst[((size_t)(w / kSliceWords) * rows + r) * kSliceWords + (w % kSliceWords)] = src_row[w];
+    };
+    (void)nsl;
+    std::vector<uint32_t> tmp((size_t)W);
+    for (int l = 0; l < p->L; ++l) put(level_h, p->L, l, level + (size_t)l * W);
     memcpy(tie_h.data(), tie, (size_t)W * 4);
     for (int f = 0; f < c->Fp; ++f) {
-        uint32_t *dst = &item_h[(size_t)f * c->Wp];
         if (f < p->F) {
-            memcpy(dst, item + (size_t)f * W, (size_t)W * 4);
+            put(item_h, c->Fp, f, item + (size_t)f * W);
         } else if (f == p->F && c->votes != p->F) {
-            for (int w = 0; w < W; ++w) dst[w] = tie[w] ^ level[w];   // binds with level 0 to tie
+            for (int w = 0; w < W; ++w) tmp[w] = tie[w] ^ level[w];   // binds with level 0 to tie
+            put(item_h, c->Fp, f, tmp.data());
         } else {
-            memcpy(dst, level, (size_t)W * 4);                        // binds with level 0 to zero
+            put(item_h, c->Fp, f, level);                             // binds with level 0 to zero
         }
     }
 

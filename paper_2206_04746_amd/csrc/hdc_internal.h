@@ -27,8 +27,10 @@ struct hdc_ctx_impl {
     // make the vote count odd and the feature count a multiple of kFeatBlock:
     //   row F (only if F is even) = tie XOR level[0]   -> binds with level 0 to the tie vector
     //   remaining pad rows        = level[0]           -> bind with level 0 to all-zero votes
-    uint32_t *item_d;   // [Fp][Wp]
-    uint32_t *level_d;  // [L][Wp]
+    // Both tables are stored slice-major so that a wave's 64 word columns of consecutive rows
+    // are 256 bytes apart: [Wp / 64][rows][64].
+    uint32_t *item_d;   // [Wp/64][Fp][64]
+    uint32_t *level_d;  // [Wp/64][L][64]
     uint32_t *tie_d;    // [Wp]
     float *lo_d;        // [F]   (HDC_F32 only)
     float *scale_d;     // [F]

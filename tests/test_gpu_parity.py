@@ -48,7 +48,8 @@ def rand_hv(rng, N, D):
 
 
 # ------------------------------------------------------------------------------ encode
-@pytest.mark.parametrize("cfg,n", [(1, 2000), (2, 1500), (3, 1200), (4, 1000), (5, 1100)])
+# small batches take the feature-split launch, the 14000-sample cases the unsplit one
+@pytest.mark.parametrize("cfg,n", [(1, 2000), (2, 1500), (3, 1200), (4, 1000), (5, 1100), (5, 14000), (3, 14001)])
 def test_encode_configs_bit_exact(cfg, n):
     wl = make_workload(cfg)
     x, _ = wl.train(n)
