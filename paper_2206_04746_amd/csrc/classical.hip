@@ -4,81 +4,155 @@
 // The per-dimension sum down a column of packed rows is the paper's "vertical summation"
 // (Sec. IV-B2).  Here it needs no transposition: a lane owns one 32-bit word column and
 // keeps the 32 counts bit-sliced (plane i = bit i of each count); adding rows is carry-save
-// arithmetic with v_bitop3_b32 full adders, about 3 VALU ops per streamed word, so the kernel
+// arithmetic with v_bitop3_b32 full adders, a few VALU ops per streamed word, so the kernel
 // stays HBM-bound.  Rows are first grouped by class (a counting sort of the labels, only the
-// row indices move), then every wave streams up to kRowBlock rows of ONE class and flushes
-// its counters to acc with integer atomics - sums of integers, so any order gives the same
-// bits.
+// row indices move).  A block then takes up to kAccWaves * rb rows of ONE class and one
+// slice of 64 word columns: every wave streams its rb rows, the waves' bit-sliced counts are
+// added through LDS, and one wave flushes the block's counts to acc with integer atomics -
+// sums of integers, so any order gives the same bits.
 #include "hdc_internal.h"
 
 namespace hdc {
 
-constexpr int kRowBlock = 2040;   // rows per wave before a flush (count fits kPlanes bits)
-constexpr int kPlanes = 11;
+constexpr int kAccWaves = 8;       // waves per accumulate block
+constexpr int kWavePlanes = 11;    // a wave counts at most 2040 rows
+constexpr int kBlockPlanes = 12;   // a block counts at most 4088 rows
+constexpr int kMaxWaveRows = 504;  // 8 * 504 = 4032 < 2^12
+constexpr int kGroupThreads = 1024;
+constexpr int64_t kSmallN = 32768;   // up to here one block groups the rows in one launch
+
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 
 // ---- grouping rows by class ----------------------------------------------------------
-// cnt[c] = rows with label c; cnt[C] = rows with a label outside [0, C) (skipped later).
+// cnt[c] = rows with label c (c < C); off = exclusive prefix of cnt (row offsets into perm);
+// blk = exclusive prefix of ceil(cnt / block_rows) (work list of the accumulate kernel).
+// Run by the first wave of a block: lane l owns a contiguous chunk of classes and the chunk
+// totals are prefix-summed across the wave.  cnt_s may alias cnt.
+__device__ __forceinline__ void scan_counts(const uint32_t *cnt_s, int C, uint32_t block_rows,
+                                            uint32_t *cnt, uint32_t *off, uint32_t *blk, uint32_t *off_s,
+                                            int64_t *class_n) {
+    const int lane = threadIdx.x;
+    if (lane >= kWave) return;
+    const int per = (C + kWave - 1) / kWave;
+    const int c0 = min(lane * per, C), c1 = min(c0 + per, C);
+    uint32_t so = 0, sb = 0;
+    for (int c = c0; c < c1; ++c) {
+        so += cnt_s[c];
+        sb += (cnt_s[c] + block_rows - 1) / block_rows;
+    }
+    uint32_t po = so, pb = sb;   // inclusive wave scan
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t to = __shfl_up(po, d, kWave), tb = __shfl_up(pb, d, kWave);
+        if (lane >= d) {
+            po += to;
+            pb += tb;
+        }
+    }
+    uint32_t o = po - so, b = pb - sb;
+    for (int c = c0; c < c1; ++c) {
+        const uint32_t k = cnt_s[c];
+        off[c] = o;
+        blk[c] = b;
+        if (off_s) off_s[c] = o;
+        cnt[c] = k;
+        class_n[c] += (int64_t)k;
+        o += k;
+        b += (k + block_rows - 1) / block_rows;
+    }
+    if (lane == kWave - 1) {
+        off[C] = po;
+        blk[C] = pb;
+    }
+}
+
+// Small batches: one block counts, scans and scatters in a single launch.
+__global__ __launch_bounds__(kGroupThreads) void group_small_kernel(
+    const int32_t *__restrict__ labels, int N, int C, uint32_t block_rows, uint32_t *cnt, uint32_t *off,
+    uint32_t *blk, uint32_t *perm, int64_t *class_n) {
+    extern __shared__ uint32_t sm[];   // cnt_s[C + 1] | off_s[C + 1] (then the scatter cursors)
+    uint32_t *cnt_s = sm, *off_s = sm + (C + 1);
+    for (int i = threadIdx.x; i <= C; i += kGroupThreads) cnt_s[i] = 0;
+    __syncthreads();
+    for (int n = threadIdx.x; n < N; n += kGroupThreads) {
+        const int32_t y = labels[n];
+        if (y >= 0 && y < C) atomicAdd(&cnt_s[y], 1u);
+    }
+    __syncthreads();
+    scan_counts(cnt_s, C, block_rows, cnt, off, blk, off_s, class_n);
+    __syncthreads();
+    for (int n = threadIdx.x; n < N; n += kGroupThreads) {
+        const int32_t y = labels[n];
+        if (y >= 0 && y < C) perm[atomicAdd(&off_s[y], 1u)] = (uint32_t)n;
+    }
+}
+
+// Large batches: clear -> count -> scan -> scatter, count and scatter over many blocks.
 __global__ void clear_counts_kernel(uint32_t *cnt, uint32_t *cur, int C) {
     for (int i = threadIdx.x; i <= C; i += blockDim.x) {
         cnt[i] = 0;
-        if (i < C) cur[i] = 0;
+        cur[i] = 0;
     }
 }
 
 __global__ __launch_bounds__(256) void count_labels_kernel(const int32_t *__restrict__ labels,
                                                             int64_t N, int C, uint32_t *cnt) {
     extern __shared__ uint32_t h[];
-    for (int i = threadIdx.x; i <= C; i += blockDim.x) h[i] = 0;
+    for (int i = threadIdx.x; i < C; i += 256) h[i] = 0;
     __syncthreads();
-    for (int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; n < N;
-         n += (int64_t)gridDim.x * blockDim.x) {
+    for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)gridDim.x * 256) {
         const int32_t y = labels[n];
-        atomicAdd(&h[(y >= 0 && y < C) ? y : C], 1u);
+        if (y >= 0 && y < C) atomicAdd(&h[y], 1u);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i <= C; i += blockDim.x)
+    for (int i = threadIdx.x; i < C; i += 256)
         if (h[i]) atomicAdd(&cnt[i], h[i]);
 }
 
-// One block: exclusive prefix of the class counts (row offsets into perm) and of the
-// per-class row-block counts (work list of the accumulate kernel); class_n += counts.
-__global__ void scan_counts_kernel(const uint32_t *cnt, uint32_t *off, uint32_t *blk, int C,
-                                   int64_t *class_n) {
-    if (threadIdx.x == 0) {
-        uint32_t o = 0, b = 0;
-        for (int c = 0; c < C; ++c) {
-            off[c] = o;
-            blk[c] = b;
-            o += cnt[c];
-            b += (cnt[c] + kRowBlock - 1) / kRowBlock;
-        }
-        off[C] = o;
-        blk[C] = b;
-    }
-    for (int c = threadIdx.x; c < C; c += blockDim.x) class_n[c] += (int64_t)cnt[c];
+__global__ __launch_bounds__(kWave) void scan_counts_kernel(uint32_t *cnt, uint32_t *off, uint32_t *blk,
+                                                            int C, uint32_t block_rows, int64_t *class_n) {
+    scan_counts(cnt, C, block_rows, cnt, off, blk, nullptr, class_n);
 }
 
+// Each block handles contiguous runs of labels: local histogram, ONE global atomic per class to
+// reserve the run's range in perm, then local ranks from LDS cursors.
+constexpr int kScatterRun = 4096;
 __global__ __launch_bounds__(256) void scatter_rows_kernel(const int32_t *__restrict__ labels,
                                                             int64_t N, int C,
                                                             const uint32_t *__restrict__ off,
                                                             uint32_t *cur, uint32_t *perm) {
-    for (int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; n < N;
-         n += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t y = labels[n];
-        if (y >= 0 && y < C) perm[off[y] + atomicAdd(&cur[y], 1u)] = (uint32_t)n;
+    extern __shared__ uint32_t h[];   // h[C]: count, then the run's next free slot per class
+    for (int64_t run0 = (int64_t)blockIdx.x * kScatterRun; run0 < N;
+         run0 += (int64_t)gridDim.x * kScatterRun) {
+        const int64_t run1 = min(run0 + (int64_t)kScatterRun, N);
+        for (int i = threadIdx.x; i < C; i += 256) h[i] = 0;
+        __syncthreads();
+        for (int64_t n = run0 + threadIdx.x; n < run1; n += 256) {
+            const int32_t y = labels[n];
+            if (y >= 0 && y < C) atomicAdd(&h[y], 1u);
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < C; i += 256) {
+            const uint32_t k = h[i];
+            h[i] = k ? off[i] + atomicAdd(&cur[i], k) : 0u;
+        }
+        __syncthreads();
+        for (int64_t n = run0 + threadIdx.x; n < run1; n += 256) {
+            const int32_t y = labels[n];
+            if (y >= 0 && y < C) perm[atomicAdd(&h[y], 1u)] = (uint32_t)n;
+        }
+        __syncthreads();
     }
 }
 
 // ---- vertical count ------------------------------------------------------------------
-typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
-constexpr int kAccWaves = 4;
-
-// grid.x = row-block index in the work list (an upper bound; surplus blocks exit),
-// grid.y = group of kAccWaves word slices.  A wave = one slice of 64 word columns.
+// grid.x = work item (block of rows of one class; an upper bound, surplus blocks exit),
+// grid.y = slice of 64 word columns.  Wave w streams rows [w * rb, (w + 1) * rb) of the item.
 __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
     const uint32_t *__restrict__ hv, const uint32_t *__restrict__ perm,
     const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ off,
-    const uint32_t *__restrict__ blk, int C, int W, int D, int32_t *acc) {
+    const uint32_t *__restrict__ blk, int C, int W, int D, int rb, int32_t *acc) {
+    __shared__ uint32_t merge[(kAccWaves - 1) * kWavePlanes * kWave];
     const uint32_t item = blockIdx.x;
     if (item >= blk[C]) return;
     // class of this work item: last c with blk[c] <= item (blk is non-decreasing)
@@ -88,24 +162,25 @@ __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
         if (blk[mid] <= item) lo = mid; else hi = mid - 1;
     }
     const int c = lo;
-    const uint32_t first = (item - blk[c]) * kRowBlock;
-    const uint32_t rows = min((uint32_t)kRowBlock, cnt[c] - first);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
-    const int col = (blockIdx.y * kAccWaves + wave) * kSliceWords + lane;
-    if (col >= W) return;
+    const int col = blockIdx.y * kSliceWords + lane;
+    const uint32_t first = (item - blk[c]) * (uint32_t)(kAccWaves * rb) + (uint32_t)(wave * rb);
+    const uint32_t total = cnt[c];
+    const uint32_t rows = first < total ? min((uint32_t)rb, total - first) : 0u;
+    const bool in_range = col < W;
 
     const_u32_ptr idx = (const_u32_ptr)(uintptr_t)(perm + off[c] + first);   // wave-uniform
-    uint32_t pl[kPlanes];
+    uint32_t pl[kBlockPlanes];
 #pragma unroll
-    for (int i = 0; i < kPlanes; ++i) pl[i] = 0;
+    for (int i = 0; i < kBlockPlanes; ++i) pl[i] = 0;
 
     for (uint32_t r0 = 0; r0 < rows; r0 += 8) {
         uint32_t x[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             x[j] = 0;
-            if (r0 + j < rows) {   // uniform
+            if (r0 + j < rows && in_range) {   // the row test is wave-uniform
                 const uint32_t *row = hv + (int64_t)idx[r0 + j] * W;
                 x[j] = row[col];
             }
@@ -119,19 +194,37 @@ __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
         p = pl[1]; c2b = maj3(p, a, b); pl[1] = xor3(p, a, b);
         p = pl[2]; c3 = maj3(p, c2a, c2b); pl[2] = xor3(p, c2a, c2b);
 #pragma unroll
-        for (int i = 3; i < kPlanes; ++i) {
+        for (int i = 3; i < kWavePlanes; ++i) {
             const uint32_t t = pl[i] & c3;
             pl[i] ^= c3;
             c3 = t;
         }
     }
 
+    // add the waves' counts: waves 1.. park their planes in LDS, wave 0 sums and flushes
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < kWavePlanes; ++i) merge[((wave - 1) * kWavePlanes + i) * kWave + lane] = pl[i];
+    }
+    __syncthreads();
+    if (wave != 0 || !in_range) return;
+#pragma unroll
+    for (int w = 0; w < kAccWaves - 1; ++w) {
+        uint32_t carry = 0;
+#pragma unroll
+        for (int i = 0; i < kWavePlanes; ++i) {
+            const uint32_t a = pl[i], b = merge[(w * kWavePlanes + i) * kWave + lane];
+            pl[i] = xor3(a, b, carry);
+            carry = maj3(a, b, carry);
+        }
+        pl[kWavePlanes] ^= carry;   // top plane: the block total stays below 2^12
+    }
     int32_t *dst = acc + (int64_t)c * D + (int64_t)col * 32;
     const int valid = min(32, D - col * 32);
     for (int b = 0; b < valid; ++b) {
         uint32_t v = 0;
 #pragma unroll
-        for (int i = 0; i < kPlanes; ++i) v |= ((pl[i] >> b) & 1u) << i;
+        for (int i = 0; i < kBlockPlanes; ++i) v |= ((pl[i] >> b) & 1u) << i;
         if (v) atomicAdd(&dst[b], (int32_t)v);
     }
 }
@@ -139,26 +232,37 @@ __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
 int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                            int32_t *acc, int64_t *class_n, hipStream_t s) {
     const int C = c->p.C;
+    const int nslices = c->Wp / kSliceWords;
     for (int64_t n0 = 0; n0 < N; n0 += c->perm_rows) {
         const int64_t n = (N - n0 < c->perm_rows) ? N - n0 : c->perm_rows;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
         const int32_t *lab0 = labels + n0;
-        const unsigned gb = (unsigned)((n + 256 * 8 - 1) / (256 * 8));
-        const unsigned nb = gb < 1 ? 1 : (gb > 2048 ? 2048 : gb);
-        hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(256), 0, s, c->cls_cnt_d, c->cls_cur_d, C);
-        hipLaunchKernelGGL(count_labels_kernel, dim3(nb), dim3(256), (size_t)(C + 1) * 4, s, lab0, n, C,
-                           c->cls_cnt_d);
-        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(256), 0, s, c->cls_cnt_d, c->cls_off_d,
-                           c->cls_blk_d, C, class_n);
-        hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), 0, s, lab0, n, C, c->cls_off_d,
-                           c->cls_cur_d, c->perm_d);
-        const unsigned items = (unsigned)((n + kRowBlock - 1) / kRowBlock) + (unsigned)C;
-        const unsigned slice_groups = (unsigned)((c->Wp / kSliceWords + kAccWaves - 1) / kAccWaves);
+        // rows per wave: enough waves to fill the chip (about 8 per SIMD), capped so that a
+        // block's count fits its planes; always a multiple of the 8-row inner step
+        int64_t rb = (n * nslices / 8192 + 7) / 8 * 8;
+        rb = rb < 16 ? 16 : (rb > kMaxWaveRows ? kMaxWaveRows : rb);
+        const uint32_t block_rows = (uint32_t)(kAccWaves * rb);
+        if (n <= kSmallN) {
+            hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(kGroupThreads), (size_t)(2 * C + 2) * 4, s,
+                               lab0, (int)n, C, block_rows, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d,
+                               c->perm_d, class_n);
+        } else {
+            const int64_t runs = (n + kScatterRun - 1) / kScatterRun;
+            const unsigned nb = (unsigned)(runs > 4096 ? 4096 : runs);
+            hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(256), 0, s, c->cls_cnt_d, c->cls_cur_d, C);
+            hipLaunchKernelGGL(count_labels_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
+                               c->cls_cnt_d);
+            hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kWave), 0, s, c->cls_cnt_d, c->cls_off_d,
+                               c->cls_blk_d, C, block_rows, class_n);
+            hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
+                               c->cls_off_d, c->cls_cur_d, c->perm_d);
+        }
+        const unsigned items = (unsigned)((n + block_rows - 1) / block_rows) + (unsigned)C;
         {
             ProfScope prof(c, HDC_K_ACCUMULATE, s);
-            hipLaunchKernelGGL(accumulate_kernel, dim3(items, slice_groups), dim3(kAccWaves * kWave), 0,
+            hipLaunchKernelGGL(accumulate_kernel, dim3(items, (unsigned)nslices), dim3(kAccWaves * kWave), 0,
                                s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, C, c->W,
-                               c->p.D, acc);
+                               c->p.D, (int)rb, acc);
         }
         HDC_HIP(hipGetLastError());
     }

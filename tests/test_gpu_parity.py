@@ -125,8 +125,10 @@ def gpu_classical(ctx, hv_d, y, acc=None, cn=None):
     return acc, cn
 
 
+# N > 32768 takes the multi-block grouping path, smaller batches the single-launch one
 @pytest.mark.parametrize("D,C,N", [(1024, 5, 2000), (10000, 26, 6238), (10000, 2, 9000),
-                                   (33, 1, 10), (2049, 7, 4100), (10000, 100, 700)])
+                                   (33, 1, 10), (2049, 7, 4100), (10000, 100, 700),
+                                   (10000, 2, 70001), (4000, 26, 40000), (64, 1000, 50000)])
 def test_classical_accumulate_and_binarize_bit_exact(D, C, N):
     rng = np.random.default_rng(D + C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
