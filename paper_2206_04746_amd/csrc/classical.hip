@@ -6,18 +6,20 @@
 // keeps the 32 counts bit-sliced (plane i = bit i of each count); adding rows is carry-save
 // arithmetic with v_bitop3_b32 full adders, a few VALU ops per streamed word, so the kernel
 // stays HBM-bound.  Rows are first grouped by class (a counting sort of the labels, only the
-// row indices move).  A block then takes up to kAccWaves * rb rows of ONE class and one
-// slice of 64 word columns: every wave streams its rb rows, the waves' bit-sliced counts are
-// added through LDS, and one wave flushes the block's counts to acc with integer atomics -
-// sums of integers, so any order gives the same bits.
+// row indices move).  A block then takes a run of rows of ONE class: its waves cover the
+// slices of 64 word columns side by side (so rows are read as whole contiguous lines) times a
+// few row groups; the row groups' bit-sliced counts are added through LDS and written out as
+// 16-bit partial sums, one row of partials per block.  A second, tiny kernel adds the partial
+// rows of each class into acc.  (Flushing blocks straight into acc with atomics was measured at
+// 10-25 G atomics/s, several times slower than streaming the rows themselves.)  Everything is
+// integer addition, so any order gives the same bits.
 #include "hdc_internal.h"
 
 namespace hdc {
 
-constexpr int kAccWaves = 8;       // waves per accumulate block
+constexpr int kAccWaves = 16;      // most waves per accumulate block (slices x row groups)
 constexpr int kWavePlanes = 11;    // a wave counts at most 2040 rows
 constexpr int kBlockPlanes = 12;   // a block counts at most 4088 rows
-constexpr int kMaxWaveRows = 504;  // 8 * 504 = 4032 < 2^12
 constexpr int kGroupThreads = 1024;
 constexpr int64_t kSmallN = 32768;   // up to here one block groups the rows in one launch
 
@@ -147,12 +149,17 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const int32_t *__rest
 
 // ---- vertical count ------------------------------------------------------------------
 // grid.x = work item (block of rows of one class; an upper bound, surplus blocks exit),
-// grid.y = slice of 64 word columns.  Wave w streams rows [w * rb, (w + 1) * rb) of the item.
-__global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
+// grid.y = chunk of `spb` slices of 64 word columns.  The block's waves form rg row groups x
+// spb slices: waves of one row group read the SAME rows side by side, so every row is fetched
+// as one contiguous run by one CU (whole cache lines, no refetch by other CUs); row group g
+// streams rows [g * rb, (g + 1) * rb) of the item.  Dynamic LDS: the merge area
+// [(rg - 1) * spb][kWavePlanes][64].
+__global__ __launch_bounds__(1024) void accumulate_kernel(
     const uint32_t *__restrict__ hv, const uint32_t *__restrict__ perm,
     const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ off,
-    const uint32_t *__restrict__ blk, int C, int W, int D, int rb, int32_t *acc) {
-    __shared__ uint32_t merge[(kAccWaves - 1) * kWavePlanes * kWave];
+    const uint32_t *__restrict__ blk, int C, int W, int Wp, int rb, int spb, int rg,
+    uint32_t *__restrict__ partial) {
+    extern __shared__ uint32_t merge[];
     const uint32_t item = blockIdx.x;
     if (item >= blk[C]) return;
     // class of this work item: last c with blk[c] <= item (blk is non-decreasing)
@@ -164,8 +171,10 @@ __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
     const int c = lo;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
-    const int col = blockIdx.y * kSliceWords + lane;
-    const uint32_t first = (item - blk[c]) * (uint32_t)(kAccWaves * rb) + (uint32_t)(wave * rb);
+    const int group = wave / spb;          // row group
+    const int sl = wave - group * spb;     // slice within the block
+    const int col = (blockIdx.y * spb + sl) * kSliceWords + lane;
+    const uint32_t first = (item - blk[c]) * (uint32_t)(rg * rb) + (uint32_t)(group * rb);
     const uint32_t total = cnt[c];
     const uint32_t rows = first < total ? min((uint32_t)rb, total - first) : 0u;
     const bool in_range = col < W;
@@ -201,47 +210,117 @@ __global__ __launch_bounds__(kAccWaves * kWave) void accumulate_kernel(
         }
     }
 
-    // add the waves' counts: waves 1.. park their planes in LDS, wave 0 sums and flushes
-    if (wave > 0) {
+    // add the row groups' counts: groups 1.. park their planes in LDS, group 0 sums and flushes
+    if (group > 0) {
+        uint32_t *dst = merge + (size_t)((group - 1) * spb + sl) * (kWavePlanes * kWave) + lane;
 #pragma unroll
-        for (int i = 0; i < kWavePlanes; ++i) merge[((wave - 1) * kWavePlanes + i) * kWave + lane] = pl[i];
+        for (int i = 0; i < kWavePlanes; ++i) dst[i * kWave] = pl[i];
     }
     __syncthreads();
-    if (wave != 0 || !in_range) return;
-#pragma unroll
-    for (int w = 0; w < kAccWaves - 1; ++w) {
+    if (group != 0) return;
+    for (int g = 0; g < rg - 1; ++g) {
+        const uint32_t *src = merge + (size_t)(g * spb + sl) * (kWavePlanes * kWave) + lane;
         uint32_t carry = 0;
 #pragma unroll
         for (int i = 0; i < kWavePlanes; ++i) {
-            const uint32_t a = pl[i], b = merge[(w * kWavePlanes + i) * kWave + lane];
+            const uint32_t a = pl[i], b = src[i * kWave];
             pl[i] = xor3(a, b, carry);
             carry = maj3(a, b, carry);
         }
         pl[kWavePlanes] ^= carry;   // top plane: the block total stays below 2^12
     }
-    int32_t *dst = acc + (int64_t)c * D + (int64_t)col * 32;
-    const int valid = min(32, D - col * 32);
-    for (int b = 0; b < valid; ++b) {
-        uint32_t v = 0;
+    // this lane's 32 counts as 16 dwords of two 16-bit sums each (pad columns store zeros)
+    uint4 *dst = reinterpret_cast<uint4 *>(partial + ((size_t)item * Wp + col) * 16);
 #pragma unroll
-        for (int i = 0; i < kBlockPlanes; ++i) v |= ((pl[i] >> b) & 1u) << i;
-        if (v) atomicAdd(&dst[b], (int32_t)v);
+    for (int q4 = 0; q4 < 4; ++q4) {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int b0 = (q4 * 4 + k) * 2;
+            uint32_t v = 0;
+#pragma unroll
+            for (int i = 0; i < kBlockPlanes; ++i)
+                v |= (((pl[i] >> b0) & 1u) << i) | (((pl[i] >> (b0 + 1)) & 1u) << (16 + i));
+            w[k] = v;
+        }
+        dst[q4] = make_uint4(w[0], w[1], w[2], w[3]);
     }
+}
+
+// acc[c][d] += sum over the class's partial rows.  grid = (dimension pairs / 256, C, K): the
+// K parts of a class's item range are combined with atomics only when K > 1.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__restrict__ partial,
+                                                               const uint32_t *__restrict__ blk, int Wp,
+                                                               int D, int K, int32_t *acc) {
+    const int c = blockIdx.y;
+    const int pair = blockIdx.x * 256 + threadIdx.x;   // dims 2*pair, 2*pair + 1
+    if (pair >= Wp * 16) return;
+    const uint32_t i0 = blk[c], i1 = blk[c + 1];
+    const uint32_t per = (i1 - i0 + K - 1) / K;
+    const uint32_t a = min(i0 + blockIdx.z * per, i1), b = min(a + per, i1);
+    uint32_t s0 = 0, s1 = 0;
+    for (uint32_t it = a; it < b; ++it) {
+        const uint32_t v = partial[(size_t)it * Wp * 16 + pair];
+        s0 += v & 0xffffu;
+        s1 += v >> 16;
+    }
+    const int d = pair * 2;
+    int32_t *dst = acc + (int64_t)c * D + d;
+    if (K == 1) {
+        if (d < D && s0) dst[0] += (int32_t)s0;
+        if (d + 1 < D && s1) dst[1] += (int32_t)s1;
+    } else {
+        if (d < D && s0) atomicAdd(&dst[0], (int32_t)s0);
+        if (d + 1 < D && s1) atomicAdd(&dst[1], (int32_t)s1);
+    }
+}
+
+// Shape of the accumulate launch for a chunk of n rows: slices per block, row groups per block
+// and rows per wave - enough waves to fill the chip (about 8 per SIMD), capped so that a
+// block's count fits its planes; rows per wave are a multiple of the 8-row inner step.
+struct AccPlan {
+    int spb, rg, ychunks;
+    int64_t rb;
+};
+static AccPlan acc_plan(const hdc_ctx_impl *c, int64_t n) {
+    AccPlan p;
+    const int nslices = c->Wp / kSliceWords;
+    p.spb = nslices < kAccWaves ? nslices : kAccWaves;
+    p.rg = kAccWaves / p.spb;
+    p.ychunks = (nslices + p.spb - 1) / p.spb;
+    int64_t rb = (n * nslices / 8192 + 7) / 8 * 8;
+    int64_t rb_max = (4088 / p.rg) / 8 * 8;
+    if (rb_max > 2040) rb_max = 2040;
+    p.rb = rb < 16 ? 16 : (rb > rb_max ? rb_max : rb);
+    return p;
+}
+
+int64_t classical_max_items(const hdc_ctx_impl *c) {
+    // items(n) = ceil(n / (rg * rb(n))) + C; rb grows with n until its cap, so the maximum is at
+    // the largest chunk or just below a step of rb: scan the steps.
+    int64_t worst = 0;
+    for (int64_t n = 1; n <= c->perm_rows; n = n < 4096 ? n + 1 : n + n / 64) {
+        const AccPlan p = acc_plan(c, n);
+        const int64_t items = (n + p.rg * p.rb - 1) / (p.rg * p.rb);
+        if (items > worst) worst = items;
+    }
+    const AccPlan p = acc_plan(c, c->perm_rows);
+    const int64_t last = (c->perm_rows + p.rg * p.rb - 1) / (p.rg * p.rb);
+    if (last > worst) worst = last;
+    return worst + worst / 8 + 16 + c->p.C;   // margin for the sizes the scan stepped over
 }
 
 int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                            int32_t *acc, int64_t *class_n, hipStream_t s) {
     const int C = c->p.C;
-    const int nslices = c->Wp / kSliceWords;
     for (int64_t n0 = 0; n0 < N; n0 += c->perm_rows) {
         const int64_t n = (N - n0 < c->perm_rows) ? N - n0 : c->perm_rows;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
         const int32_t *lab0 = labels + n0;
-        // rows per wave: enough waves to fill the chip (about 8 per SIMD), capped so that a
-        // block's count fits its planes; always a multiple of the 8-row inner step
-        int64_t rb = (n * nslices / 8192 + 7) / 8 * 8;
-        rb = rb < 16 ? 16 : (rb > kMaxWaveRows ? kMaxWaveRows : rb);
-        const uint32_t block_rows = (uint32_t)(kAccWaves * rb);
+        const AccPlan plan = acc_plan(c, n);
+        const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
+        const int64_t rb = plan.rb;
+        const uint32_t block_rows = (uint32_t)(rg * rb);
         if (n <= kSmallN) {
             hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(kGroupThreads), (size_t)(2 * C + 2) * 4, s,
                                lab0, (int)n, C, block_rows, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d,
@@ -257,13 +336,21 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
             hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
                                c->cls_off_d, c->cls_cur_d, c->perm_d);
         }
-        const unsigned items = (unsigned)((n + block_rows - 1) / block_rows) + (unsigned)C;
+        const int64_t items = (n + block_rows - 1) / block_rows + C;
+        if (items > c->partial_items) return HDC_ELIMIT;   // cannot happen: sized for the worst case
+        const size_t lds = (size_t)(rg - 1) * spb * kWavePlanes * kWave * sizeof(uint32_t);
         {
             ProfScope prof(c, HDC_K_ACCUMULATE, s);
-            hipLaunchKernelGGL(accumulate_kernel, dim3(items, (unsigned)nslices), dim3(kAccWaves * kWave), 0,
-                               s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, C, c->W,
-                               c->p.D, (int)rb, acc);
+            hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks),
+                               dim3(spb * rg * kWave), lds, s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d,
+                               c->cls_blk_d, C, c->W, c->Wp, (int)rb, spb, rg, c->partial_d);
         }
+        // enough threads for the reduction: split a class's partial rows K ways when C is small
+        const int pairs = c->Wp * 16;
+        int K = (int)((32768 + (int64_t)C * pairs - 1) / ((int64_t)C * pairs));
+        K = K < 1 ? 1 : (K > 16 ? 16 : K);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)C, (unsigned)K),
+                           dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
         HDC_HIP(hipGetLastError());
     }
     return HDC_OK;

@@ -24,7 +24,7 @@ constexpr int64_t kPermRows = 1 << 22;       // rows grouped by class per traini
 static void free_ctx(hdc_ctx_impl *c) {
     if (!c) return;
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
-                    c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->online_d};
+                    c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->online_d, c->partial_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -152,6 +152,8 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     TRY(dev_alloc(&c->cls_blk_d, (size_t)p->C + 1));
     c->perm_rows = kPermRows;
     TRY(dev_alloc(&c->perm_d, (size_t)c->perm_rows));
+    c->partial_items = classical_max_items(c);
+    TRY(dev_alloc(&c->partial_d, (size_t)c->partial_items * c->Wp * 16));
     TRY_HIP(hipDeviceSynchronize());
 #undef TRY
 #undef TRY_HIP

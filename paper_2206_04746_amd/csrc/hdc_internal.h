@@ -44,6 +44,8 @@ struct hdc_ctx_impl {
     uint32_t *cls_blk_d;  // [C + 1] exclusive prefix of per-class row-block counts
     uint32_t *perm_d;     // [perm_rows] sample indices grouped by class
     int64_t perm_rows;
+    uint32_t *partial_d;  // [partial_items][Wp * 16] per-block partial counts, two u16 per dword
+    int64_t partial_items;
     double *online_d;     // scratch of the online trainer (norms, partial sums)
 
     // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.
@@ -88,6 +90,8 @@ int launch_binarize_classical(hdc_ctx_impl *c, const int32_t *acc, const int64_t
 int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                         int32_t epochs, float lr, float *acc, hipStream_t s);
 int launch_binarize_online(hdc_ctx_impl *c, const float *acc, uint32_t *class_hv, hipStream_t s);
+// Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
+int64_t classical_max_items(const hdc_ctx_impl *c);
 int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                   uint32_t *dist, int32_t *pred, hipStream_t s);
 
