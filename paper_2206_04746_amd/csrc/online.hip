@@ -127,10 +127,219 @@ __global__ __launch_bounds__(kOnlineThreads) void online_kernel(
     }
 }
 
+// ---- register-resident variant ---------------------------------------------------------
+// Same algorithm, but the accumulators never leave the registers during the call: thread t
+// holds acc[c][t + 1024 k] for c < CMAX, k < KPT.  Per step: prefetch the next sample's bits,
+// C dot products (fp64 partial sums per thread, DPP butterfly per wave, 16 wave sums through
+// LDS), thread c finishes cos_c, then the one or two row updates, whose new squared norms ride
+// along to the next step's barrier.  Two block barriers per step.
+__device__ __forceinline__ double dpp_shuffle_f64(double v, const int ctrl_sel) {
+    // helper for wave_sum_dpp: moves both halves of a double with the same DPP control
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    int mlo, mhi;
+    switch (ctrl_sel) {
+        case 0: mlo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, true);    // quad_perm 1,0,3,2
+                mhi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, true); break;
+        case 1: mlo = __builtin_amdgcn_update_dpp(0, lo, 0x4E, 0xF, 0xF, true);    // quad_perm 2,3,0,1
+                mhi = __builtin_amdgcn_update_dpp(0, hi, 0x4E, 0xF, 0xF, true); break;
+        case 2: mlo = __builtin_amdgcn_update_dpp(0, lo, 0x141, 0xF, 0xF, true);   // row_half_mirror
+                mhi = __builtin_amdgcn_update_dpp(0, hi, 0x141, 0xF, 0xF, true); break;
+        default: mlo = __builtin_amdgcn_update_dpp(0, lo, 0x140, 0xF, 0xF, true);  // row_mirror
+                 mhi = __builtin_amdgcn_update_dpp(0, hi, 0x140, 0xF, 0xF, true); break;
+    }
+    return __hiloint2double(mhi, mlo);
+}
+
+// Sum over the 64 lanes, result in every lane.  Rows of 16 lanes fold with DPP (no LDS), the
+// four row sums are exchanged with two lane permutes.
+__device__ __forceinline__ double wave_sum_dpp(double v) {
+    v += dpp_shuffle_f64(v, 0);
+    v += dpp_shuffle_f64(v, 1);
+    v += dpp_shuffle_f64(v, 2);
+    v += dpp_shuffle_f64(v, 3);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+template <int CMAX, int KPT>
+__global__ __launch_bounds__(kOnlineThreads) void online_reg_kernel(
+    const uint32_t *__restrict__ hv, const int32_t *__restrict__ labels, int64_t N, int epochs,
+    float lr, float *acc, int D, int W, int C, double root_d) {
+    __shared__ double nrm[CMAX];
+    __shared__ double cosv[CMAX];
+    __shared__ double red[kOnlineWaves][CMAX];
+    __shared__ double red2[kOnlineWaves][2];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+
+    // which dimensions this thread owns, and the hv word / bit of each
+    float m[CMAX][KPT];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int d = tid + k * kOnlineThreads;
+            m[c][k] = (c < C && d < D) ? acc[(int64_t)c * D + d] : 0.0f;
+        }
+    // squared norms of the rows as handed in
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) {
+        double p = 0.0;
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) p += (double)m[c][k] * (double)m[c][k];
+        p = wave_sum_dpp(p);
+        if (lane == 0) red[wave][c] = p;
+    }
+    __syncthreads();
+    if (tid < CMAX) {
+        double s = 0.0;
+        for (int w = 0; w < kOnlineWaves; ++w) s += red[w][tid];
+        nrm[tid] = s;
+    }
+    __syncthreads();   // red[] is rewritten by the first step
+    // no row has pending norm partials yet
+    int upd_y = -1, upd_p = -1;
+
+    auto load_bits = [&](int64_t n) {
+        uint32_t bits = 0;
+        const uint32_t *h = hv + n * W;
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int d = tid + k * kOnlineThreads;
+            if (d < D) bits |= ((h[d >> 5] >> (d & 31)) & 1u) << k;
+        }
+        return bits;
+    };
+
+    const int64_t steps = (int64_t)epochs * N;
+    uint32_t bits_next = steps > 0 ? load_bits(0) : 0u;
+    int y_next = steps > 0 ? labels[0] : 0;
+    int64_t n = 0;
+    for (int64_t step = 0; step < steps; ++step) {
+        const uint32_t bits = bits_next;
+        const int y = y_next;
+        const int64_t n1 = (n + 1 == N) ? 0 : n + 1;
+        if (step + 1 < steps) {   // next sample's bits and label travel while this step computes
+            bits_next = load_bits(n1);
+            y_next = labels[n1];
+        }
+        n = n1;
+        if (y < 0 || y >= C) continue;   // uniform
+
+        // ---- similarity of the sample to every class, from the rows as they are now
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+            if (c < C) {
+                double p = 0.0;
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    const double v = (double)m[c][k];
+                    p += ((bits >> k) & 1u) ? v : -v;
+                }
+                p = wave_sum_dpp(p);
+                if (lane == 0) red[wave][c] = p;
+            }
+        }
+        __syncthreads();
+        if (tid < C) {
+            // rows changed by the previous step first get their new squared norm
+            if (tid == upd_y || tid == upd_p) {
+                double s = 0.0;
+                const int which = tid == upd_y ? 0 : 1;
+                for (int w = 0; w < kOnlineWaves; ++w) s += red2[w][which];
+                nrm[tid] = s;
+            }
+            double dot = 0.0;
+            for (int w = 0; w < kOnlineWaves; ++w) dot += red[w][tid];
+            const double nn = nrm[tid];
+            cosv[tid] = nn == 0.0 ? 0.0 : dot / (sqrt(nn) * root_d);
+        }
+        __syncthreads();
+        int pred = 0;
+        double best = cosv[0];
+        for (int c = 1; c < C; ++c) {
+            const double v = cosv[c];
+            if (v > best) { best = v; pred = c; }
+        }
+        const float w_y = (float)(1.0 - cosv[y]);
+        const float w_p = (float)((double)lr * (1.0 - best));
+        const bool wrong = pred != y;
+
+        // ---- updates (Eq. 2 always, Eq. 3 only after a wrong prediction) and new norms
+        double py = 0.0, pp = 0.0;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+            if (c == y) {
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    if (tid + k * kOnlineThreads < D) {
+                        const float v = __fadd_rn(m[c][k], ((bits >> k) & 1u) ? w_y : -w_y);
+                        m[c][k] = v;
+                        py += (double)v * (double)v;
+                    }
+                }
+            } else if (wrong && c == pred) {
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    if (tid + k * kOnlineThreads < D) {
+                        const float v = __fadd_rn(m[c][k], ((bits >> k) & 1u) ? -w_p : w_p);
+                        m[c][k] = v;
+                        pp += (double)v * (double)v;
+                    }
+                }
+            }
+        }
+        py = wave_sum_dpp(py);
+        pp = wave_sum_dpp(pp);
+        if (lane == 0) {
+            red2[wave][0] = py;
+            red2[wave][1] = pp;
+        }
+        upd_y = y;
+        upd_p = wrong ? pred : -1;
+        // red2 is read after the next step's first barrier and rewritten after its second
+    }
+
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int d = tid + k * kOnlineThreads;
+            if (c < C && d < D) acc[(int64_t)c * D + d] = m[c][k];
+        }
+}
+
+template <int CMAX, int KPT>
+static int launch_online_reg(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                             int32_t epochs, float lr, float *acc, hipStream_t s) {
+    ProfScope prof(c, HDC_K_ONLINE, s);
+    hipLaunchKernelGGL((online_reg_kernel<CMAX, KPT>), dim3(1), dim3(kOnlineThreads), 0, s, hv, labels, N,
+                       (int)epochs, lr, acc, c->p.D, c->W, c->p.C, sqrt((double)c->p.D));
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                         int32_t epochs, float lr, float *acc, hipStream_t s) {
     const int C = c->p.C;
     if (c->p.D > 32 * kOnlineThreads) return HDC_ELIMIT;   // a thread keeps its sample bits in one word
+    // Register-resident kernel when C x (dimensions per thread) fits the register file.
+    const int kpt = (c->p.D + kOnlineThreads - 1) / kOnlineThreads;
+#define HDC_ONLINE_CASE(CM, KP) \
+    if (C <= CM && kpt <= KP) return launch_online_reg<CM, KP>(c, hv, labels, N, epochs, lr, acc, s)
+    HDC_ONLINE_CASE(8, 1);
+    HDC_ONLINE_CASE(32, 1);
+    HDC_ONLINE_CASE(80, 1);
+    HDC_ONLINE_CASE(8, 2);
+    HDC_ONLINE_CASE(40, 2);
+    HDC_ONLINE_CASE(4, 4);
+    HDC_ONLINE_CASE(20, 4);
+    HDC_ONLINE_CASE(2, 10);
+    HDC_ONLINE_CASE(6, 10);
+    HDC_ONLINE_CASE(2, 16);
+#undef HDC_ONLINE_CASE
     const size_t lds = (size_t)(2 + kOnlineWaves) * (C < 2 ? 2 : C) * sizeof(double);
     auto kern = online_kernel;
     if (lds > 64 * 1024)
