@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="only run a 1 GiB device copy 10 times (known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -57,6 +60,15 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     K, Wm = max(1, args.steps), max(0, args.warmup)
+    if args.copy_reference:
+        a = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference_bytes_read": a.numel() * 4, "copy_reference_bytes_written": a.numel() * 4,
+                          "launches": 10}))
+        return 0
 
     wl = make_workload(2)
     xt_h, yt_h = wl.train()
@@ -127,7 +139,7 @@ def main() -> int:
     roofline = {
         "kernel": "encode_kernel", "bound": "alu", "achieved": round(achieved, 3),
         "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
-        "frac": round(achieved / VALU_PEAK_TOPS, 4), "traffic": None,
+        "frac": round(achieved / VALU_PEAK_TOPS, 4), "traffic": _profiled_traffic("hdc::encode_kernel"),
         "avg_launch_us": round(enc_ms * 1e3 / max(1, enc_launches), 2), "launches": enc_launches,
         "algorithmic_ops_per_sample": ops_per_sample,
         "hbm_equiv_GBs": round((wl.F * 4 + W * 4) * (ntr + nte) * K / (enc_ms * 1e-3) / 1e9, 2)
@@ -170,6 +182,29 @@ def main() -> int:
     ctx.close()
     print(json.dumps(out))
     return 0
+
+
+def _profiled_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel factors stated in that file); None
+    if the summary is absent.  Counters cannot be collected from inside this process."""
+    path = os.path.join(ROOT, "profiles", "encode_kernel_cfg2_pmc.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    import re
+    scale = {"FETCH_SIZE": 2.0, "WRITE_SIZE": 1.0}
+    m = re.search(r"FETCH_SIZE x ([0-9.]+), WRITE_SIZE x ([0-9.]+)", text)
+    if m:
+        scale = {"FETCH_SIZE": float(m.group(1)), "WRITE_SIZE": float(m.group(2))}
+    total = 0.0
+    for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
+        mm = re.search(re.escape(kernel) + r"[^\n]*," + ctr + r",launches=\d+,mean=([0-9.]+)", text)
+        if not mm:
+            return None
+        total += float(mm.group(1)) * 1024.0 * scale[ctr]
+    return total
 
 
 def _timed(torch, fn, reps):
