@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhdc.so")
+# HDC_LIBRARY may point at another build of the same ABI (e.g. a tuning variant)
+LIB_PATH = os.environ.get("HDC_LIBRARY") or os.path.join(_HERE, "libhdc.so")
 
 HDC_OK, HDC_EINVAL, HDC_ENOMEM, HDC_EHIP, HDC_ELIMIT = 0, -1, -2, -3, -4
 HDC_F32, HDC_U8 = 0, 1

@@ -61,39 +61,29 @@ __global__ __launch_bounds__(256) void quantize_kernel(const void *__restrict__ 
 // ------------------------------------------------------------- bundling (Eq. 1's sum)
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 
-// Level words of 16 features for this lane's column, fetched from the LDS level slice.
-// qpair[k] holds the LDS byte offsets (bin * 256) of features 2k and 2k+1 as two u16.  The
-// row offset is wave-uniform, so it goes through M0 and ds_read_addtid_b32 (address = M0 +
-// lane * 4): no vector ALU work is spent on addresses.  One wait state separates a write of
-// M0 from the LDS instruction that reads it.
-//
-// The trailing s_waitcnt makes the outputs valid before the asm statement ends.
-__device__ __forceinline__ void gather16(uint32_t (&x)[16], const uint32_t (&qpair)[8]) {
-    asm volatile(
-        "s_and_b32 m0, %16, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %0\n\t"
-        "s_lshr_b32 m0, %16, 16\n\ts_nop 0\n\tds_read_addtid_b32 %1\n\t"
-        "s_and_b32 m0, %17, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %2\n\t"
-        "s_lshr_b32 m0, %17, 16\n\ts_nop 0\n\tds_read_addtid_b32 %3\n\t"
-        "s_and_b32 m0, %18, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %4\n\t"
-        "s_lshr_b32 m0, %18, 16\n\ts_nop 0\n\tds_read_addtid_b32 %5\n\t"
-        "s_and_b32 m0, %19, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %6\n\t"
-        "s_lshr_b32 m0, %19, 16\n\ts_nop 0\n\tds_read_addtid_b32 %7\n\t"
-        "s_and_b32 m0, %20, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %8\n\t"
-        "s_lshr_b32 m0, %20, 16\n\ts_nop 0\n\tds_read_addtid_b32 %9\n\t"
-        "s_and_b32 m0, %21, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %10\n\t"
-        "s_lshr_b32 m0, %21, 16\n\ts_nop 0\n\tds_read_addtid_b32 %11\n\t"
-        "s_and_b32 m0, %22, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %12\n\t"
-        "s_lshr_b32 m0, %22, 16\n\ts_nop 0\n\tds_read_addtid_b32 %13\n\t"
-        "s_and_b32 m0, %23, 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 %14\n\t"
-        "s_lshr_b32 m0, %23, 16\n\ts_nop 0\n\tds_read_addtid_b32 %15\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]),
-          "=&v"(x[7]), "=&v"(x[8]), "=&v"(x[9]), "=&v"(x[10]), "=&v"(x[11]), "=&v"(x[12]),
-          "=&v"(x[13]), "=&v"(x[14]), "=&v"(x[15])
-        : "s"(qpair[0]), "s"(qpair[1]), "s"(qpair[2]), "s"(qpair[3]), "s"(qpair[4]), "s"(qpair[5]),
-          "s"(qpair[6]), "s"(qpair[7])
-        : "scc", "memory");
+// Level words of 16 features for this lane's column come from the LDS level slice.  The row
+// offset is wave-uniform, so it goes through M0 and ds_read_addtid_b32 (address = M0 + lane*4):
+// no vector ALU work is spent on addresses.  One wait state separates a write of M0 from the
+// LDS instruction that reads it.  q[k] holds the LDS byte offsets (bin * 256) of features 2k
+// and 2k+1 as two u16.  The 16 level words arrive in compiler-allocated registers and the asm
+// statement ends with the wait, so nothing is in flight outside it.  No "memory" clobber: the
+// level slice is read-only after the barrier that publishes it (a volatile asm cannot cross
+// that barrier), and without the clobber the compiler may fetch the next bin offsets early.
+__device__ __forceinline__ void gather16(uint32_t (&x)[16], const uint32_t (&q)[8]) {
+#define HDC_G2(qs, a, b)                                                      \
+    "s_and_b32 m0, " qs ", 0xffff\n\ts_nop 0\n\tds_read_addtid_b32 " a "\n\t" \
+    "s_lshr_b32 m0, " qs ", 16\n\ts_nop 0\n\tds_read_addtid_b32 " b "\n\t"
+    asm volatile(HDC_G2("%16", "%0", "%1") HDC_G2("%17", "%2", "%3") HDC_G2("%18", "%4", "%5")
+                 HDC_G2("%19", "%6", "%7") HDC_G2("%20", "%8", "%9") HDC_G2("%21", "%10", "%11")
+                 HDC_G2("%22", "%12", "%13") HDC_G2("%23", "%14", "%15") "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]),
+                   "=&v"(x[7]), "=&v"(x[8]), "=&v"(x[9]), "=&v"(x[10]), "=&v"(x[11]), "=&v"(x[12]),
+                   "=&v"(x[13]), "=&v"(x[14]), "=&v"(x[15])
+                 : "s"(q[0]), "s"(q[1]), "s"(q[2]), "s"(q[3]), "s"(q[4]), "s"(q[5]), "s"(q[6]), "s"(q[7])
+                 : "scc");
+#undef HDC_G2
 }
+
 // Adds the 2^LV bound words x[J0 .. J0+2^LV-1] into planes 0..LV-1 and returns the carry of
 // weight 2^LV.  Depth-first, so only one pending carry per level is alive.
 template <int LV, int J0>
@@ -127,21 +117,23 @@ __device__ __forceinline__ void ripple(uint32_t *pl, uint32_t c) {
 }
 
 // Block = WAVES waves, all on the same slice of 64 word columns (one column per lane, level
-// slice [L][64] in dynamic LDS; the level-row offsets the quantiser wrote are absolute LDS
-// byte addresses, which holds because this kernel has no static LDS, so its dynamic LDS starts
-// at address 0 - the launcher checks that).  The waves form WAVES/FS groups; a group carries S samples through all Fp features,
-// 16 at a time, its FS waves each taking a contiguous share of the features and adding their
-// bit-sliced partial counts together through LDS at the end.  FS > 1 makes the work units
-// smaller, which is what a small batch needs to fill 1024 SIMDs; FS = 1 has no merge at all.
-template <int S, int P, int WAVES, int FS>
+// slice [L][64] in dynamic LDS; the level-row offsets the quantiser wrote are absolute LDS byte
+// addresses, which holds because this kernel has no static LDS, so its dynamic LDS starts at
+// address 0 - the launcher checks that).  Blocks are persistent: the grid is what the chip
+// holds at once and every wave walks over several units of S samples of its slice, so the
+// level slice is loaded once per block whatever the batch size.  A unit runs the features 16
+// at a time: 16 ID words are loaded once and serve all S samples.
+//
+// Carries: a 16-vote tree leaves a carry of weight 16; two of them meet in plane 4, two of
+// those in plane 5, and only every 64 features does a carry ripple through the upper planes.
+template <int S, int P, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
     const uint16_t *__restrict__ q, const uint32_t *__restrict__ item,
-    const uint32_t *__restrict__ level, uint32_t *__restrict__ hv, int N, int Fp, int L, int W, int Wp,
+    const uint32_t *__restrict__ level, uint32_t *__restrict__ hv, int N, int Fp, int L, int W,
     uint32_t bias) {
+    static_assert(P >= 8, "planes 4 and 5 take the deferred carries");
     extern __shared__ uint32_t lv[];
-    constexpr int GROUPS = WAVES / FS;
     const int slice = blockIdx.x;
-    const int tile = blockIdx.y;
     const int lane = threadIdx.x & (kWave - 1);
     const int col = slice * kSliceWords + lane;
 
@@ -151,43 +143,8 @@ __global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
     }
     __syncthreads();
 
-    // WAVES is a compile-time constant on purpose: a block size read from the dispatch packet
-    // makes the compiler treat the sample index as divergent and the bin loads as vector loads.
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int group = wave / FS;
-    const int part = wave % FS;
-    const int n_base = (tile * GROUPS + group) * S;
-    const bool live = n_base < N;
-    if (FS == 1 && !live) return;   // with FS > 1 every wave must reach the merge barriers
-
-    // Only the first wave of a group starts from the bias; the others add plain partial counts.
-    const uint32_t my_bias = part == 0 ? bias : 0u;
-    uint32_t pl[S][P];
-#pragma unroll
-    for (int s = 0; s < S; ++s)
-#pragma unroll
-        for (int i = 0; i < P; ++i) pl[s][i] = ((my_bias >> i) & 1u) ? 0xffffffffu : 0u;
-
-    // The bin offsets are wave-uniform and were written by an earlier kernel: read them through
-    // the constant address space so they arrive by scalar loads, off the vector pipeline.
-    const_u32_ptr qrow[S];
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
-        const int n = min(n_base + s, N - 1);   // a ragged last group recomputes row N-1
-        qrow[s] = (const_u32_ptr)(uintptr_t)(q + (int64_t)n * Fp);
-    }
-
-    // This wave's share of the features: a contiguous run of 32-feature pairs (the last share
-    // also takes the unpaired half-block, if Fp is an odd multiple of 16).
-    const int pairs = Fp >> 5;
-    const int per = (pairs + FS - 1) / FS;
-    int f0 = min(part * per, pairs) << 5;
-    const int f_end = (part == FS - 1) ? Fp : (min((part + 1) * per, pairs) << 5);
-
-    // ID rows are loaded one half-block ahead of their use (ida / idb alternate), so their
-    // latency hides behind the arithmetic of the half-block before.
-    // (address = wave-uniform base of the half-block in SGPRs + this lane's byte offset +
-    // j * 256 as an immediate: no vector address arithmetic, no address registers)
+    // (address = wave-uniform base of the half-block + this lane's byte offset + j * 256 as an
+    // immediate: no per-row address arithmetic)
     const uint32_t lane_bytes = (uint32_t)lane * 4u;
     const char *item_slice = reinterpret_cast<const char *>(item + (size_t)slice * Fp * kSliceWords);
     auto load_ids = [&](int f, uint32_t (&id)[16]) {
@@ -196,121 +153,151 @@ __global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
         for (int j = 0; j < 16; ++j)
             id[j] = *reinterpret_cast<const uint32_t *>(base + j * (kSliceWords * 4) + lane_bytes);
     };
-    // the S samples of one half-block: bind 16 features with their level rows and bundle
-    // them; c16[s] receives the carry of weight 16
-    auto half_block = [&](int f, const uint32_t (&id)[16], uint32_t (&c16)[S]) {
+
+    // units of S samples are dealt round-robin to the waves of this slice (all units cost the
+    // same, so a static deal balances as well as a work queue and needs no atomics).  WAVES is
+    // a template constant on purpose: derived from blockDim, the compiler would treat the
+    // sample index as divergent and fetch the bin offsets with vector loads.
+    const int units = (N + S - 1) / S;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int stride = (int)gridDim.y * WAVES;
+    for (int u = (int)blockIdx.y * WAVES + wave; u < units; u += stride) {
+        const int n_base = u * S;
+
+        uint32_t pl[S][P];
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int i = 0; i < P; ++i) pl[s][i] = ((bias >> i) & 1u) ? 0xffffffffu : 0u;
+
+        // The bin offsets are wave-uniform and were written by an earlier kernel: read them
+        // through the constant address space so they arrive by scalar loads.
+        const_u32_ptr qrow[S];
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            uint32_t qpair[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) qpair[k] = qrow[s][(f >> 1) + k];
-            uint32_t x[16];
-            gather16(x, qpair);
-#pragma unroll
-            for (int j = 0; j < 16; ++j) x[j] ^= id[j];     // bind (XOR)
-            c16[s] = Tree<4, 0>::run(pl[s], x);              // bundle 16 votes
-            // Keep the samples in program order: the gathers are volatile and cannot move, so
-            // pinning the results here (empty volatile asm, no instruction) stops the compiler
-            // from sinking this sample's arithmetic below the next gathers, which would hold
-            // S * 16 landing registers alive at once.
-            asm volatile("" : "+v"(c16[s]), "+v"(pl[s][0]), "+v"(pl[s][1]), "+v"(pl[s][2]), "+v"(pl[s][3]));
+            const int n = min(n_base + s, N - 1);   // a ragged last unit recomputes row N-1
+            qrow[s] = (const_u32_ptr)(uintptr_t)(q + (int64_t)n * Fp);
         }
-    };
-
-    if (live && f0 < f_end) {
-        uint32_t ida[16], idb[16];
-        load_ids(f0, ida);
-        for (; f0 + 32 <= f_end; f0 += 32) {
-            uint32_t ca[S], cb[S];
-            load_ids(f0 + 16, idb);
-            half_block(f0, ida, ca);
-            if (f0 + 32 < f_end) load_ids(f0 + 32, ida);
-            half_block(f0 + 16, idb, cb);
+        // one half-block: bind 16 features of every sample with their level rows and bundle
+        // them; c16[s] receives the carry of weight 16
+        auto half_block = [&](int f, uint32_t (&c16)[S]) {
+            uint32_t id[16];
+            load_ids(f, id);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                const uint32_t p = pl[s][4];
-                pl[s][4] = xor3(p, ca[s], cb[s]);
-                ripple<5, P>(pl[s], maj3(p, ca[s], cb[s]));
+                uint32_t qpair[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) qpair[k] = qrow[s][(f >> 1) + k];
+                uint32_t x[16];
+                gather16(x, qpair);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) x[j] ^= id[j];  // bind (XOR)
+                c16[s] = Tree<4, 0>::run(pl[s], x);          // bundle 16 votes
+                // Pin the step's results here (empty volatile asm, no instruction): the asm
+                // statements keep their order, so the tree above cannot be sunk below the next
+                // gather, which would keep several samples' 16 bound words alive at once.
+                asm volatile("" : "+v"(c16[s]), "+v"(pl[s][0]), "+v"(pl[s][1]), "+v"(pl[s][2]), "+v"(pl[s][3]));
+            }
+        };
+
+        // two pairs (64 features) per trip: their weight-32 carries meet in plane 5 and only the
+        // weight-64 carry ripples up
+        auto pair_carry = [&](int f, uint32_t (&c32)[S]) {
+            uint32_t ca[S], cb[S];
+            half_block(f, ca);
+            half_block(f + 16, cb);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const uint32_t p4 = pl[s][4];
+                pl[s][4] = xor3(p4, ca[s], cb[s]);
+                c32[s] = maj3(p4, ca[s], cb[s]);
+            }
+        };
+        int f0 = 0;
+        for (; f0 + 64 <= Fp; f0 += 64) {
+            uint32_t ea[S], eb[S];
+            pair_carry(f0, ea);
+            pair_carry(f0 + 32, eb);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const uint32_t p5 = pl[s][5];
+                pl[s][5] = xor3(p5, ea[s], eb[s]);
+                ripple<6, P>(pl[s], maj3(p5, ea[s], eb[s]));
             }
         }
-        if (f0 < f_end) {   // the unpaired last half-block; its IDs are already in flight
+        if (f0 + 32 <= Fp) {   // one pair left over
+            uint32_t ea[S];
+            pair_carry(f0, ea);
+            f0 += 32;
+#pragma unroll
+            for (int s = 0; s < S; ++s) ripple<5, P>(pl[s], ea[s]);
+        }
+        if (f0 < Fp) {   // Fp is an odd multiple of 16: the last half-block has no partner
             uint32_t ca[S];
-            half_block(f0, ida, ca);
+            half_block(f0, ca);
 #pragma unroll
             for (int s = 0; s < S; ++s) ripple<4, P>(pl[s], ca[s]);
         }
-    }
 
-    if (FS > 1) {
-        // Sum the FS partial counts of every sample: waves 1..FS-1 of a group park their planes
-        // in LDS (behind the level slice), wave 0 adds them with P full adders each.
-        uint32_t *mbuf = lv + L * kSliceWords + group * ((FS - 1) * P * kWave);
+        if (col < W) {
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            if (part > 0) {
-#pragma unroll
-                for (int i = 0; i < P; ++i) mbuf[((part - 1) * P + i) * kWave + lane] = pl[s][i];
-            }
-            __syncthreads();
-            if (part == 0) {
-#pragma unroll
-                for (int r = 0; r < FS - 1; ++r) {
-                    uint32_t carry = 0;
-#pragma unroll
-                    for (int i = 0; i < P; ++i) {
-                        const uint32_t a = pl[s][i], b2 = mbuf[(r * P + i) * kWave + lane];
-                        pl[s][i] = xor3(a, b2, carry);
-                        carry = maj3(a, b2, carry);
-                    }
-                }
-            }
-            __syncthreads();
+            for (int s = 0; s < S; ++s)
+                if (n_base + s < N) hv[(int64_t)(n_base + s) * W + col] = pl[s][P - 1];
         }
     }
-
-    if (part == 0 && live && col < W) {
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-            if (n_base + s < N) hv[(int64_t)(n_base + s) * W + col] = pl[s][P - 1];
-    }
 }
 
-template <int S, int P, int WAVES, int FS>
-static int launch_encode_spwf(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
-    constexpr int GROUPS = WAVES / FS;
+typedef void (*encode_fn)(const uint16_t *, const uint32_t *, const uint32_t *, uint32_t *, int, int, int,
+                          int, uint32_t);
+struct EncodeVariant {
+    encode_fn fn;
+    int S, P, waves;
+};
+#define HDC_VARIANTS(P) \
+    {encode_kernel<2, P, 4>, 2, P, 4}, {encode_kernel<4, P, 4>, 4, P, 4}, \
+    {encode_kernel<2, P, 8>, 2, P, 8}, {encode_kernel<4, P, 8>, 4, P, 8}
+static const EncodeVariant kVariants[] = {HDC_VARIANTS(8), HDC_VARIANTS(10), HDC_VARIANTS(12), HDC_VARIANTS(16)};
+#undef HDC_VARIANTS
+
+static int launch_encode_kernel(hdc_ctx_impl *c, int P, int N, uint32_t *hv, uint32_t bias,
+                                hipStream_t s) {
     const int nslices = c->Wp / kSliceWords;
-    const int tiles = (N + GROUPS * S - 1) / (GROUPS * S);
-    const size_t lds = ((size_t)c->p.L * kSliceWords + (FS > 1 ? (size_t)GROUPS * (FS - 1) * P * kWave : 0)) *
-                       sizeof(uint32_t);
-    static int static_lds = -1;   // level-row offsets are absolute: no static LDS allowed
-    if (static_lds < 0) {
+    const int waves = c->p.L > 128 ? 8 : 4;   // a big level slice: fewer, larger blocks per CU
+    // small batches take 2-sample units so that there are enough of them for 1024 SIMDs
+    // (measured crossover: about 3 four-sample units per SIMD)
+    const int S = ((int64_t)((N + 3) / 4) * nslices >= 3072) ? 4 : 2;
+    const EncodeVariant *v = nullptr;
+    for (const EncodeVariant &k : kVariants)
+        if (k.S == S && k.P == P && k.waves == waves) v = &k;
+    if (!v) return HDC_ELIMIT;
+    const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
+    // Per variant, once: no static LDS allowed (the level-row offsets are absolute LDS
+    // addresses), and how many blocks of it a CU holds (registers and LDS).
+    static int blocks_per_cu[sizeof(kVariants) / sizeof(kVariants[0])][2];   // [variant][L > 128]
+    int &bpc = blocks_per_cu[v - kVariants][0];
+    if (bpc == 0 || blocks_per_cu[v - kVariants][1] != c->p.L) {
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(encode_kernel<S, P, WAVES, FS>)) !=
-            hipSuccess)
-            return HDC_EHIP;
-        static_lds = (int)attr.sharedSizeBytes;
+        HDC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(v->fn)));
+        if (attr.sharedSizeBytes != 0) return HDC_ELIMIT;
+        int n = 0;
+        HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(v->fn),
+                                                             waves * kWave, lds));
+        bpc = n < 1 ? 1 : n;
+        blocks_per_cu[v - kVariants][1] = c->p.L;
     }
-    if (static_lds != 0) return HDC_ELIMIT;
+    // persistent grid: at most what the chip holds at once, sized so that the deal comes out
+    // even - every wave gets k units (the last few k-1), never some waves one unit more than
+    // the rest of a nearly idle chip
+    const int units = (N + S - 1) / S;
+    int max_waves = (c->num_cus * bpc) / nslices * waves;
+    if (max_waves < waves) max_waves = waves;
+    const int k = (units + max_waves - 1) / max_waves;          // units per wave
+    const int need_waves = (units + k - 1) / k;
+    const int per_slice = (need_waves + waves - 1) / waves;
     ProfScope prof(c, HDC_K_ENCODE, s);
-    hipLaunchKernelGGL((encode_kernel<S, P, WAVES, FS>), dim3((unsigned)nslices, (unsigned)tiles),
-                       dim3(WAVES * kWave), lds, s, c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L,
-                       c->W, c->Wp, bias);
+    hipLaunchKernelGGL(v->fn, dim3((unsigned)nslices, (unsigned)per_slice), dim3(waves * kWave), lds, s,
+                       c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L, c->W, bias);
     return HDC_OK;
-}
-
-template <int S, int P>
-static int launch_encode_sp(hdc_ctx_impl *c, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
-    // Work units needed to give every SIMD of the chip a few waves; below that, split the
-    // features of a sample group over the waves of a block (smaller units, one LDS merge).
-    const int64_t units = (int64_t)((N + S - 1) / S) * (c->Wp / kSliceWords);
-    const bool split = units < 4 * 1024 * 4 && (c->Fp >> 5) >= 8;
-    // a large level table leaves room for few blocks per CU: use bigger blocks then
-    if (c->p.L > 128) {
-        if (split) return launch_encode_spwf<S, P, 8, 4>(c, N, hv, bias, s);
-        return launch_encode_spwf<S, P, 8, 1>(c, N, hv, bias, s);
-    }
-    if (split) return launch_encode_spwf<S, P, 4, 4>(c, N, hv, bias, s);
-    return launch_encode_spwf<S, P, 4, 1>(c, N, hv, bias, s);
 }
 
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
@@ -321,7 +308,7 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
     int top = 0;
     while ((1u << top) < thr) ++top;
     int P = top + 1;
-    P = P <= 6 ? 6 : P <= 8 ? 8 : P <= 10 ? 10 : P <= 12 ? 12 : 16;
+    P = P <= 8 ? 8 : P <= 10 ? 10 : P <= 12 ? 12 : 16;
     const uint32_t bias = (1u << (P - 1)) - thr;
 
     for (int64_t n0 = 0; n0 < N; n0 += c->q_rows) {
@@ -340,15 +327,7 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
                 hipLaunchKernelGGL(quantize_kernel<false>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
                                    c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
         }
-        uint32_t *out = hv + (size_t)n0 * c->W;
-        int rc;
-        switch (P) {
-            case 6: rc = launch_encode_sp<4, 6>(c, (int)n, out, bias, s); break;
-            case 8: rc = launch_encode_sp<4, 8>(c, (int)n, out, bias, s); break;
-            case 10: rc = launch_encode_sp<4, 10>(c, (int)n, out, bias, s); break;
-            case 12: rc = launch_encode_sp<4, 12>(c, (int)n, out, bias, s); break;
-            default: rc = launch_encode_sp<4, 16>(c, (int)n, out, bias, s); break;
-        }
+        const int rc = launch_encode_kernel(c, P, (int)n, hv + (size_t)n0 * c->W, bias, s);
         if (rc != HDC_OK) return rc;
         HDC_HIP(hipGetLastError());
     }

@@ -88,6 +88,11 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
         delete c;
         return hip_fail(e, "hipGetDevice");
     }
+    e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
+    if (e != hipSuccess || c->num_cus < 1) {
+        delete c;
+        return hip_fail(e, "hipDeviceGetAttribute");
+    }
 
     // Host staging of the padded device tables (layout described in hdc_internal.h).
     std::vector<uint32_t> item_h, level_h, tie_h;

@@ -17,6 +17,7 @@ constexpr int kFeatBlock = 16;    // features consumed per carry-save tree in en
 struct hdc_ctx_impl {
     hdc_params p;
     int device;
+    int num_cus;      // compute units of the device (sizes the persistent encode grid)
     int32_t W;        // ceil(D / 32)
     int32_t Wp;       // W rounded up to a multiple of kSliceWords (pad words are zero)
     int32_t Fp;       // rows of item_d: F, +1 tie-vote row when F is even, padded to kFeatBlock
