@@ -26,36 +26,52 @@ __device__ __forceinline__ uint32_t bin_f32(float x, float lo, float scale, int 
     return (uint32_t)(int)t;
 }
 
-// One thread produces the entries of features 4g..4g+3 of one sample.  An entry is the byte
+// One thread produces the entries of features 4g..4g+3 for kQuantRows consecutive samples
+// (the per-feature range is loaded once and reused down the rows).  An entry is the byte
 // offset of the bin's row in the LDS level slice (bin * 256, fits 16 bits for L <= 256);
 // features at or beyond F (the tie-vote row and the pad rows of the device item table) get
-// bin 0.
+// bin 0.  grid = (feature groups / 64, row tiles).
+constexpr int kQuantRows = 8;
 template <bool kU8>
-__global__ __launch_bounds__(256) void quantize_kernel(const void *__restrict__ feats, int64_t N,
-                                                        int F, int Fp, int L,
-                                                        const float *__restrict__ lo,
-                                                        const float *__restrict__ scale,
-                                                        uint2 *__restrict__ q4) {
+__global__ __launch_bounds__(64) void quantize_kernel(const void *__restrict__ feats, int64_t N,
+                                                       int F, int Fp, int L,
+                                                       const float *__restrict__ lo,
+                                                       const float *__restrict__ scale,
+                                                       uint2 *__restrict__ q4) {
     const int groups = Fp >> 2;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= N * groups) return;
-    const int64_t n = i / groups;
-    const int f0 = (int)(i - n * groups) << 2;
-    uint32_t packed[2] = {0u, 0u};
+    const int g = blockIdx.x * 64 + threadIdx.x;
+    if (g >= groups) return;
+    const int f0 = g << 2;
+    float lo4[4] = {0.f, 0.f, 0.f, 0.f}, sc4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!kU8) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int f = f0 + k;
-        uint32_t b = 0;
-        if (f < F) {
-            if (kU8) {
-                b = ((uint32_t) reinterpret_cast<const uint8_t *>(feats)[n * F + f] * (uint32_t)L) >> 8;
-            } else {
-                b = bin_f32(reinterpret_cast<const float *>(feats)[n * F + f], lo[f], scale[f], L);
+        for (int k = 0; k < 4; ++k)
+            if (f0 + k < F) {
+                lo4[k] = lo[f0 + k];
+                sc4[k] = scale[f0 + k];
             }
-        }
-        packed[k >> 1] |= (b * (kSliceWords * 4u)) << (16 * (k & 1));
     }
-    q4[i] = make_uint2(packed[0], packed[1]);
+    const int64_t r0 = (int64_t)blockIdx.y * kQuantRows;
+#pragma unroll
+    for (int r = 0; r < kQuantRows; ++r) {
+        const int64_t n = r0 + r;
+        if (n >= N) break;
+        uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int f = f0 + k;
+            uint32_t b = 0;
+            if (f < F) {
+                if (kU8) {
+                    b = ((uint32_t) reinterpret_cast<const uint8_t *>(feats)[n * F + f] * (uint32_t)L) >> 8;
+                } else {
+                    b = bin_f32(reinterpret_cast<const float *>(feats)[n * F + f], lo4[k], sc4[k], L);
+                }
+            }
+            packed[k >> 1] |= (b * (kSliceWords * 4u)) << (16 * (k & 1));
+        }
+        q4[n * groups + g] = make_uint2(packed[0], packed[1]);
+    }
 }
 
 // ------------------------------------------------------------- bundling (Eq. 1's sum)
@@ -315,17 +331,16 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
         const int64_t n = (N - n0 < c->q_rows) ? N - n0 : c->q_rows;
         const size_t esz = c->p.feat_dtype == HDC_U8 ? 1 : 4;
         const void *x = reinterpret_cast<const uint8_t *>(feats) + (size_t)n0 * c->p.F * esz;
-        const int64_t items = n * (c->Fp >> 2);
-        const unsigned qblocks = (unsigned)((items + 255) / 256);
         {
             ProfScope prof(c, HDC_K_QUANTIZE, s);
+            const dim3 qgrid((unsigned)(((c->Fp >> 2) + 63) / 64), (unsigned)((n + kQuantRows - 1) / kQuantRows));
             uint2 *q4 = reinterpret_cast<uint2 *>(c->q_d);
             if (c->p.feat_dtype == HDC_U8)
-                hipLaunchKernelGGL(quantize_kernel<true>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
-                                   c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
+                hipLaunchKernelGGL(quantize_kernel<true>, qgrid, dim3(64), 0, s, x, n, c->p.F, c->Fp, c->p.L,
+                                   c->lo_d, c->scale_d, q4);
             else
-                hipLaunchKernelGGL(quantize_kernel<false>, dim3(qblocks), dim3(256), 0, s, x, n, c->p.F,
-                                   c->Fp, c->p.L, c->lo_d, c->scale_d, q4);
+                hipLaunchKernelGGL(quantize_kernel<false>, qgrid, dim3(64), 0, s, x, n, c->p.F, c->Fp, c->p.L,
+                                   c->lo_d, c->scale_d, q4);
         }
         const int rc = launch_encode_kernel(c, P, (int)n, hv + (size_t)n0 * c->W, bias, s);
         if (rc != HDC_OK) return rc;
