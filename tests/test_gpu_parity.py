@@ -284,3 +284,129 @@ def test_argument_errors_are_reported_not_faulted():
         == b.HDC_EINVAL
     assert b.lib.hdc_encode(ctx._h, None, 0, None, None) == b.HDC_OK      # N == 0 is a no-op
     ctx.close()
+
+
+# ------------------------------------------------- full sizes of the BASELINE configurations
+def test_config3_full_size_classical_pipeline():
+    """MNIST-shaped config at its full size (60000 train / 10000 test, u8 features, L=256)."""
+    wl = make_workload(3)
+    xt, yt = wl.train()
+    xs, ys = wl.test()
+    ctx = make_ctx(wl)
+    ht, hs = gpu_encode(ctx, xt), gpu_encode(ctx, xs)
+    acc, cn = gpu_classical(ctx, ht, yt)
+    m = torch.empty((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_binarize_classical(acc, cn, m)
+    pred = torch.empty(xs.shape[0], dtype=torch.int32, device="cuda")
+    dist = torch.empty((xs.shape[0], wl.C), dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hs, m, pred, dist)
+    torch.cuda.synchronize()
+    o_ht, o_hs = orc_encode(wl, xt), orc_encode(wl, xs)
+    assert np.array_equal(host_u32(ht), o_ht) and np.array_equal(host_u32(hs), o_hs)
+    o_acc, o_cn = oracle.train_classical(o_ht, yt, wl.D, wl.C)
+    assert np.array_equal(acc.cpu().numpy(), o_acc) and np.array_equal(cn.cpu().numpy(), o_cn)
+    o_m = oracle.binarize_classical(o_acc, o_cn, wl.tie)
+    assert np.array_equal(host_u32(m), o_m)
+    o_dist, o_pred = oracle.search(o_hs, o_m, wl.D)
+    assert np.array_equal(host_u32(dist), o_dist) and np.array_equal(pred.cpu().numpy(), o_pred)
+    ctx.close()
+
+
+def test_config4_full_size_online_pipeline():
+    """UCIHAR-shaped config at its full size: 7352 samples, 3 epochs, fixed order."""
+    wl = make_workload(4)
+    xt, yt = wl.train()
+    xs, _ = wl.test()
+    ctx = make_ctx(wl)
+    ht, hs = gpu_encode(ctx, xt), gpu_encode(ctx, xs)
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.float32, device="cuda")
+    ctx.hdc_train_online(ht, torch.from_numpy(yt).cuda(), acc, epochs=wl.epochs, lr=wl.lr)
+    m = torch.empty((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_binarize_online(acc, m)
+    pred = torch.empty(xs.shape[0], dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hs, m, pred, None)
+    torch.cuda.synchronize()
+    o_ht, o_hs = orc_encode(wl, xt), orc_encode(wl, xs)
+    assert np.array_equal(host_u32(ht), o_ht)
+    o_acc, o_pred_log, margin = oracle.train_online(o_ht, yt, wl.D, wl.C, epochs=wl.epochs, lr=wl.lr, log=True)
+    assert rel_err(acc.cpu().numpy(), o_acc) < 1e-4
+    # where the sign of an accumulator is not within rounding of zero the class bits must agree
+    o_m = oracle.binarize_online(o_acc, wl.tie)
+    safe = np.abs(o_acc) > 1e-3 * np.abs(o_acc).max()
+    got_bits, want_bits = oracle.unpack(host_u32(m), wl.D), oracle.unpack(o_m, wl.D)
+    assert np.array_equal(got_bits[safe], want_bits[safe])
+    if np.array_equal(host_u32(m), o_m):
+        _, o_pred = oracle.search(o_hs, o_m, wl.D)
+        assert np.array_equal(pred.cpu().numpy(), o_pred)
+    ctx.close()
+
+
+def test_config5_full_stream_invariants_and_sampled_parity():
+    """CHB-MIT-shaped stream at its full size: 5,000,000 windows in five 1M-window chunks are
+    encoded, accumulated and searched.  The oracle is far too slow for 5M encodes, so it checks
+    sampled windows one by one (from its own inputs only); integer invariants cover the rest."""
+    wl = make_workload(5)
+    ctx = make_ctx(wl)
+    chunk, nchunks, nsub = 1_000_000, 5, 5000
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device="cuda")
+    cn = torch.zeros(wl.C, dtype=torch.int64, device="cuda")
+    hv_all, y_all, samples = [], [], []
+    o_m_sub = None
+    for ci in range(nchunks):
+        x, y = wl.train(chunk, start=ci * chunk)
+        hv = gpu_encode(ctx, x)
+        # sampled parity of the encoder: a prefix and a random scatter of every chunk
+        rows = np.unique(np.concatenate([np.arange(300), np.random.default_rng(ci).choice(chunk, 300)]))
+        o_rows = orc_encode(wl, x[rows])
+        assert np.array_equal(host_u32(hv[torch.from_numpy(rows).cuda()]), o_rows)
+        samples.append((ci * chunk + rows, o_rows))
+        if ci == 0:   # a subset small enough for the oracle to train on
+            o_hv = orc_encode(wl, x[:nsub])
+            assert np.array_equal(host_u32(hv[:nsub]), o_hv)
+            a_s, n_s = gpu_classical(ctx, hv[:nsub].contiguous(), y[:nsub])
+            o_a, o_n = oracle.train_classical(o_hv, y[:nsub], wl.D, wl.C)
+            assert np.array_equal(a_s.cpu().numpy(), o_a) and np.array_equal(n_s.cpu().numpy(), o_n)
+            o_m_sub = oracle.binarize_classical(o_a, o_n, wl.tie)
+        acc, cn = gpu_classical(ctx, hv, y, acc, cn)
+        hv_all.append(hv)
+        y_all.append(y)
+        del x
+    hv_cat = torch.cat(hv_all)
+    del hv_all
+    y_cat = np.concatenate(y_all)
+    N = hv_cat.shape[0]
+    assert N == 5_000_000
+    # chunked == unchunked (integer sums compose in any order); counts match the labels
+    acc1, cn1 = gpu_classical(ctx, hv_cat, y_cat)
+    assert torch.equal(acc1, acc) and torch.equal(cn1, cn)
+    assert np.array_equal(cn.cpu().numpy(), np.bincount(y_cat, minlength=wl.C))
+    # sum over dimensions of acc[c] == total popcount of the class's vectors; the popcounts come
+    # from a different kernel: Hamming distance to the all-zero vector
+    zero = torch.zeros((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    pc = torch.empty((N, wl.C), dtype=torch.int32, device="cuda")
+    pr = torch.empty(N, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hv_cat, zero, pr, pc)
+    torch.cuda.synchronize()
+    yd = torch.from_numpy(y_cat).cuda()
+    for c in range(wl.C):
+        assert int(acc[c].sum(dtype=torch.int64)) == int(pc[yd == c, 0].sum(dtype=torch.int64))
+    assert int((pr != 0).sum()) == 0                       # equal distances: lowest class wins
+    # class vectors of the full stream obey the majority rule (checked with plain tensor ops)
+    m = torch.empty((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_binarize_classical(acc, cn, m)
+    torch.cuda.synchronize()
+    tie_bits = np.unpackbits(wl.tie.view(np.uint8), bitorder="little")[:wl.D]
+    a_h, n_h = acc.cpu().numpy().astype(np.int64), cn.cpu().numpy()
+    want = np.where(2 * a_h > n_h[:, None], 1, np.where(2 * a_h < n_h[:, None], 0, tie_bits[None, :]))
+    got = np.unpackbits(host_u32(m).view(np.uint8), axis=1, bitorder="little")[:, :wl.D]
+    assert np.array_equal(got, want)
+    # search of all 5M windows against the oracle-trained subset model: sampled rows one by one
+    dist = torch.empty((N, wl.C), dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hv_cat, dev_u32(o_m_sub), pr, dist)
+    torch.cuda.synchronize()
+    assert int(dist.min()) >= 0 and int(dist.max()) <= wl.D
+    for rows, o_rows in samples:
+        o_d, o_p = oracle.search(o_rows, o_m_sub, wl.D)
+        idx = torch.from_numpy(rows).cuda()
+        assert np.array_equal(host_u32(dist[idx]), o_d) and np.array_equal(pr[idx].cpu().numpy(), o_p)
+    ctx.close()
