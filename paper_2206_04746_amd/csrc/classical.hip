@@ -184,8 +184,8 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
 #pragma unroll
     for (int i = 0; i < kBlockPlanes; ++i) pl[i] = 0;
 
-    for (uint32_t r0 = 0; r0 < rows; r0 += 8) {
-        uint32_t x[8];
+    // eight rows at a time, the next eight already in flight while these are counted
+    auto load8 = [&](uint32_t r0, uint32_t (&x)[8]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             x[j] = 0;
@@ -194,6 +194,8 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
                 x[j] = row[col];
             }
         }
+    };
+    auto add8 = [&](const uint32_t (&x)[8]) {
         uint32_t a, b, p, c2a, c2b, c3;
         p = pl[0]; a = maj3(p, x[0], x[1]); p = xor3(p, x[0], x[1]);
         b = maj3(p, x[2], x[3]); p = xor3(p, x[2], x[3]); pl[0] = p;
@@ -208,6 +210,14 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
             pl[i] ^= c3;
             c3 = t;
         }
+    };
+    uint32_t xa[8], xb[8];
+    load8(0, xa);
+    for (uint32_t r0 = 0; r0 < rows; r0 += 16) {
+        load8(r0 + 8, xb);
+        add8(xa);
+        load8(r0 + 16, xa);
+        add8(xb);
     }
 
     // add the row groups' counts: groups 1.. park their planes in LDS, group 0 sums and flushes
@@ -275,51 +285,58 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__
     }
 }
 
-// Shape of the accumulate launch for a chunk of n rows: slices per block, row groups per block
-// and rows per wave - enough waves to fill the chip (about 8 per SIMD), capped so that a
-// block's count fits its planes; rows per wave are a multiple of the 8-row inner step.
+// Shape of the accumulate launch: slices per block, row groups per block, how many blocks the
+// chip holds at once, and for a chunk of n rows the rows per wave.  Rows per wave are chosen so
+// that the whole chunk is ONE round of blocks (a second, nearly empty round would double the
+// time), capped so that a block's count fits its planes, and a multiple of the 8-row step.
 struct AccPlan {
     int spb, rg, ychunks;
-    int64_t rb;
+    int64_t cap;      // blocks per launch that run at once, minus the C possible partial blocks
+    int64_t rb_max;   // most rows per wave
+    int64_t rows_max; // most rows one launch takes in a single round
 };
-static AccPlan acc_plan(const hdc_ctx_impl *c, int64_t n) {
-    AccPlan p;
+static int plan_static(const hdc_ctx_impl *c, AccPlan *p) {
     const int nslices = c->Wp / kSliceWords;
-    p.spb = nslices < kAccWaves ? nslices : kAccWaves;
-    p.rg = kAccWaves / p.spb;
-    p.ychunks = (nslices + p.spb - 1) / p.spb;
-    int64_t rb = (n * nslices / 8192 + 7) / 8 * 8;
-    int64_t rb_max = (4088 / p.rg) / 8 * 8;
-    if (rb_max > 2040) rb_max = 2040;
-    p.rb = rb < 16 ? 16 : (rb > rb_max ? rb_max : rb);
-    return p;
+    p->spb = nslices < kAccWaves ? nslices : kAccWaves;
+    p->rg = kAccWaves / p->spb;
+    p->ychunks = (nslices + p->spb - 1) / p->spb;
+    int bpc = 0;
+    const size_t lds = (size_t)(p->rg - 1) * p->spb * kWavePlanes * kWave * sizeof(uint32_t);
+    HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, reinterpret_cast<const void *>(accumulate_kernel),
+                                                         p->spb * p->rg * kWave, lds));
+    if (bpc < 1) bpc = 1;
+    p->cap = (int64_t)c->num_cus * bpc / p->ychunks - c->p.C;
+    if (p->cap < 1) p->cap = 1;
+    p->rb_max = (4088 / p->rg) / 8 * 8;
+    if (p->rb_max > 2040) p->rb_max = 2040;
+    p->rows_max = p->cap * p->rg * p->rb_max;
+    if (p->rows_max > c->perm_rows) p->rows_max = c->perm_rows;
+    return HDC_OK;
+}
+static int64_t plan_rb(const AccPlan &p, int64_t n) {
+    int64_t rb = ((n + p.rg * p.cap - 1) / (p.rg * p.cap) + 7) / 8 * 8;
+    return rb < 16 ? 16 : (rb > p.rb_max ? p.rb_max : rb);
 }
 
 int64_t classical_max_items(const hdc_ctx_impl *c) {
-    // items(n) = ceil(n / (rg * rb(n))) + C; rb grows with n until its cap, so the maximum is at
-    // the largest chunk or just below a step of rb: scan the steps.
-    int64_t worst = 0;
-    for (int64_t n = 1; n <= c->perm_rows; n = n < 4096 ? n + 1 : n + n / 64) {
-        const AccPlan p = acc_plan(c, n);
-        const int64_t items = (n + p.rg * p.rb - 1) / (p.rg * p.rb);
-        if (items > worst) worst = items;
-    }
-    const AccPlan p = acc_plan(c, c->perm_rows);
-    const int64_t last = (c->perm_rows + p.rg * p.rb - 1) / (p.rg * p.rb);
-    if (last > worst) worst = last;
-    return worst + worst / 8 + 16 + c->p.C;   // margin for the sizes the scan stepped over
+    AccPlan p;
+    if (plan_static(c, &p) != HDC_OK) return -1;
+    // full blocks of one round plus at most one partial block per class, with some slack
+    return p.cap + 2 * (int64_t)c->p.C + 16 + c->perm_rows / (p.rg * p.rb_max);
 }
 
 int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                            int32_t *acc, int64_t *class_n, hipStream_t s) {
     const int C = c->p.C;
-    for (int64_t n0 = 0; n0 < N; n0 += c->perm_rows) {
-        const int64_t n = (N - n0 < c->perm_rows) ? N - n0 : c->perm_rows;
+    AccPlan plan;
+    const int prc = plan_static(c, &plan);
+    if (prc != HDC_OK) return prc;
+    const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
+    for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
+        const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
         const int32_t *lab0 = labels + n0;
-        const AccPlan plan = acc_plan(c, n);
-        const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
-        const int64_t rb = plan.rb;
+        const int64_t rb = plan_rb(plan, n);
         const uint32_t block_rows = (uint32_t)(rg * rb);
         if (n <= kSmallN) {
             hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(kGroupThreads), (size_t)(2 * C + 2) * 4, s,

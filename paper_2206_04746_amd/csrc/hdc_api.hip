@@ -158,6 +158,7 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     c->perm_rows = kPermRows;
     TRY(dev_alloc(&c->perm_d, (size_t)c->perm_rows));
     c->partial_items = classical_max_items(c);
+    if (c->partial_items < 0 && rc == HDC_OK) rc = HDC_EHIP;
     TRY(dev_alloc(&c->partial_d, (size_t)c->partial_items * c->Wp * 16));
     TRY_HIP(hipDeviceSynchronize());
 #undef TRY
