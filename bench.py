@@ -200,11 +200,13 @@ def _profiled_traffic(kernel: str):
         scale = {"FETCH_SIZE": float(m.group(1)), "WRITE_SIZE": float(m.group(2))}
     total = 0.0
     for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
-        mm = re.search(re.escape(kernel) + r"[^\n]*," + ctr + r",launches=\d+,mean=([0-9.]+)", text)
-        if not mm:
+        # one line per kernel instantiation: average over all launches of all of them
+        rows = re.findall(re.escape(kernel) + r"[^\n]*," + ctr + r",launches=(\d+),mean=([0-9.]+)", text)
+        if not rows:
             return None
-        total += float(mm.group(1)) * 1024.0 * scale[ctr]
-    return total
+        launches = sum(int(n) for n, _ in rows)
+        total += sum(int(n) * float(m) for n, m in rows) / launches * 1024.0 * scale[ctr]
+    return round(total, 1)
 
 
 def _timed(torch, fn, reps):
