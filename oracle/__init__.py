@@ -157,6 +157,20 @@ def train_online(hv: np.ndarray, labels: np.ndarray, D: int, C: int, epochs: int
     return (acc, pred, margin) if log else acc
 
 
+def train_online_batched(hv: np.ndarray, labels: np.ndarray, D: int, C: int, batch: int,
+                         epochs: int = 1, lr: float = 1.0, acc: Optional[np.ndarray] = None) -> np.ndarray:
+    """Online training with the class rows frozen over each batch of ``batch`` samples
+    (Sec. VI-D2).  Returns ``acc f32[C][D]``."""
+    bits = unpack(hv, D)
+    labels = _c(labels, np.int32)
+    N = bits.shape[0]
+    assert labels.shape == (N,) and batch >= 1
+    acc = np.zeros((C, D), dtype=np.float32) if acc is None else _c(acc, np.float32).copy()
+    _load().orc_train_online_batched(_p(bits), _p(labels), I64(N), I32(D), I32(C), I32(epochs),
+                                     ctypes.c_float(lr), I64(batch), _p(acc))
+    return acc
+
+
 def binarize_online(acc: np.ndarray, tie: np.ndarray) -> np.ndarray:
     acc = _c(acc, np.float32)
     C, D = acc.shape

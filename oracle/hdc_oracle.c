@@ -226,6 +226,73 @@ void orc_train_online(const uint8_t *hv, const int32_t *labels, int64_t N, int32
     free(cosv);
 }
 
+/* ---- batched online training (Sec. VI-D2) -------------------------------------- */
+
+/* "Only updating class vectors after a batch size of n new datapoints are received":
+ * the class accumulators stay frozen while a batch of `batch` consecutive samples is
+ * scored exactly as in orc_train_online (cosines, prediction, weights from the frozen
+ * rows); the batch's weighted +-s vectors are summed per class in fp64, in sample
+ * order, and added to the rows in one step, acc = float(double(acc) + delta).
+ * Reading where the paper is silent: the sum of a batch is formed in fp64 and rounded
+ * to fp32 once.  The paper prints no worked example: parity unpinned beyond the
+ * hand-worked and closed-form cases in the tests. */
+void orc_train_online_batched(const uint8_t *hv, const int32_t *labels, int64_t N, int32_t D,
+                              int32_t C, int32_t epochs, float lr, int64_t batch, float *acc)
+{
+    double *cosv = (double *)malloc((size_t)C * sizeof(double));
+    double *nrm = (double *)malloc((size_t)C * sizeof(double));
+    double *delta = (double *)malloc((size_t)C * D * sizeof(double));
+    const double root_d = sqrt((double)D);
+    for (int32_t e = 0; e < epochs; ++e)
+        for (int64_t b0 = 0; b0 < N; b0 += batch) {
+            const int64_t b1 = b0 + batch < N ? b0 + batch : N;
+            for (int64_t i = 0; i < (int64_t)C * D; ++i)
+                delta[i] = 0.0;
+            for (int32_t c = 0; c < C; ++c) {
+                double s2 = 0.0;
+                for (int32_t d = 0; d < D; ++d) {
+                    double v = (double)acc[(int64_t)c * D + d];
+                    s2 += v * v;
+                }
+                nrm[c] = s2;
+            }
+            for (int64_t n = b0; n < b1; ++n) {
+                const uint8_t *h = hv + n * D;
+                const int32_t y = labels[n];
+                if (y < 0 || y >= C)
+                    continue;
+                for (int32_t c = 0; c < C; ++c) {
+                    const float *m = acc + (int64_t)c * D;
+                    double dot = 0.0;
+                    for (int32_t d = 0; d < D; ++d) {
+                        double v = (double)m[d];
+                        dot += h[d] ? v : -v;
+                    }
+                    cosv[c] = nrm[c] == 0.0 ? 0.0 : dot / (sqrt(nrm[c]) * root_d);
+                }
+                int32_t pred = 0;
+                for (int32_t c = 1; c < C; ++c)
+                    if (cosv[c] > cosv[pred])
+                        pred = c;
+                const double w_y = (double)(float)(1.0 - cosv[y]);
+                const double w_p = (double)(float)((double)lr * (1.0 - cosv[pred]));
+                double *dy = delta + (int64_t)y * D;
+                for (int32_t d = 0; d < D; ++d)
+                    dy[d] += h[d] ? w_y : -w_y;
+                if (pred != y) {
+                    double *dp = delta + (int64_t)pred * D;
+                    for (int32_t d = 0; d < D; ++d)
+                        dp[d] += h[d] ? -w_p : w_p;
+                }
+            }
+            for (int64_t i = 0; i < (int64_t)C * D; ++i)
+                acc[i] = (float)((double)acc[i] + delta[i]);
+        }
+    free(cosv);
+    free(nrm);
+    free(delta);
+}
+
 /* class bit = sign of the accumulator; exactly zero takes tie[d]. */
 void orc_binarize_online(const float *acc, int32_t C, int32_t D, const uint8_t *tie,
                          uint8_t *class_bits)

@@ -433,3 +433,65 @@ def test_config1_end_to_end_is_accurate_on_separated_clusters():
     acc_o = oracle.train_online(ht, yt, wl.D, wl.C, epochs=2)
     _, pred_o = oracle.search(hs, oracle.binarize_online(acc_o, wl.tie), wl.D)
     assert (pred_o == ys).mean() > 0.9
+
+
+# ------------------------------------------------------- batched online training (Sec. VI-D2)
+def test_online_batched_hand_case_from_golden_file():
+    hs, ys, after, batch = [], [], [], None
+    for line in open(os.path.join(GOLDEN, "online_batched_hand_case.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "h":
+            hs.append(bits_of(t[1]))
+            ys.append(int(t[2]))
+        elif t[0] == "batch":
+            batch = int(t[1])
+        elif t[0] == "after":
+            after.append((int(t[1]), [float(v) for v in t[3:7]], [float(v) for v in t[8:12]]))
+    hv, y = pack_bits_lsb(np.array(hs)), np.array(ys, dtype=np.int32)
+    for k, m0, m1 in after:
+        acc = oracle.train_online_batched(hv[:k], y[:k], 4, 2, batch)
+        np.testing.assert_allclose(acc, np.array([m0, m1]), rtol=0, atol=2e-7)
+
+
+def test_online_batched_whole_set_from_zero_model_closed_form():
+    # One batch over everything, zero start: every cosine is 0, every prediction is class 0, all
+    # weights are 1 (lr for the subtraction): acc[c] = sum of s over class c, and class 0
+    # additionally loses lr * (sum of s over all other classes).  Small integers: exact.
+    rng = np.random.default_rng(20)
+    D, C, N, lr = 96, 4, 50, 0.5
+    h = rand_bits(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    s = 2.0 * h - 1.0
+    acc = oracle.train_online_batched(pack_bits_lsb(h), y, D, C, batch=N, lr=lr)
+    want = np.zeros((C, D))
+    for c in range(C):
+        want[c] = s[y == c].sum(axis=0)
+    want[0] -= lr * s[y != 0].sum(axis=0)
+    assert np.array_equal(acc, want.astype(np.float32))
+    # a batch larger than the set is the same thing; two epochs = two such batches
+    assert np.array_equal(oracle.train_online_batched(pack_bits_lsb(h), y, D, C, batch=10 * N, lr=lr), acc)
+
+
+def test_online_batched_with_batch_one_is_plain_online_training():
+    rng = np.random.default_rng(21)
+    D, C, N = 64, 3, 40
+    hv = _rand_hv(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    a = oracle.train_online(hv, y, D, C, epochs=2, lr=0.8)
+    b = oracle.train_online_batched(hv, y, D, C, batch=1, epochs=2, lr=0.8)
+    np.testing.assert_allclose(b, a, rtol=1e-6, atol=1e-6)
+
+
+def test_online_batched_order_inside_a_batch_does_not_matter_but_batches_do():
+    rng = np.random.default_rng(22)
+    D, C, N, B = 80, 3, 24, 8
+    hv = _rand_hv(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    a = oracle.train_online_batched(hv, y, D, C, batch=B)
+    p = np.concatenate([b0 + rng.permutation(B) for b0 in range(0, N, B)])     # shuffle inside batches
+    b = oracle.train_online_batched(hv[p], y[p], D, C, batch=B)
+    np.testing.assert_allclose(b, a, rtol=1e-6, atol=1e-6)
+    c = oracle.train_online_batched(hv, y, D, C, batch=N)                      # different batching
+    assert not np.allclose(c, a)
