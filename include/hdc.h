@@ -128,6 +128,25 @@ int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *
 int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
                      int32_t epochs, float lr, float *acc_dev, void *stream);
 
+/*
+ * Batched online training, Sec. VI-D2 (class vectors updated only after every `batch`
+ * datapoints).  For each epoch the samples are taken in consecutive batches of `batch`
+ * (the last one may be shorter).  Within a batch the accumulators are frozen: every sample
+ * of the batch is scored as in hdc_train_online (cos_c, pred, the two fp32 weights) against
+ * the rows as they were before the batch; then
+ *   delta[c] = sum over the batch of  +float(1 - cos_y) * s         for c == y
+ *                                     -float(lr*(1 - cos_pred)) * s for c == pred != y
+ * (fp64 sums) and acc[c] = float(double(acc[c]) + delta[c]), one rounding per element and
+ * batch.  batch >= 1; a batch larger than N is one batch per epoch.  Other arguments, layout
+ * and the treatment of out-of-range labels are those of hdc_train_online.  The first call,
+ * and a call that needs more scratch than any before it (larger batch), allocates device
+ * memory owned by the context (HDC_ENOMEM if that fails) and therefore synchronises the
+ * device; later calls only enqueue on `stream`.
+ */
+int hdc_train_online_batched(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev,
+                             int64_t N, int32_t epochs, float lr, int64_t batch, float *acc_dev,
+                             void *stream);
+
 /* class_hv[c][d] = 1 if acc > 0, 0 if acc < 0, tie[d] if acc == 0; [C][W] out, pad 0. */
 int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_dev, void *stream);
 
@@ -157,7 +176,9 @@ typedef enum {
     HDC_K_ACCUMULATE = 2, /* per-class vertical count kernel of hdc_train_classical */
     HDC_K_ONLINE = 3,     /* sequential updater of hdc_train_online */
     HDC_K_SEARCH = 4,     /* Hamming distance + argmin kernel of hdc_search */
-    HDC_K_COUNT = 5
+    HDC_K_ONLINE_FWD = 5, /* partial dot products of hdc_train_online_batched */
+    HDC_K_ONLINE_BWD = 6, /* batch sum + accumulator update of hdc_train_online_batched */
+    HDC_K_COUNT = 7
 } hdc_kernel_id;
 #define HDC_PROFILE_SLOTS 512
 int hdc_profile_enable(hdc_ctx *ctx, int enable);

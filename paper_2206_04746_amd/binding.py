@@ -22,11 +22,12 @@ HDC_F32, HDC_U8 = 0, 1
 
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
-           "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search",
+           "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
            "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
-KERNEL_IDS = {"encode": 0, "quantize": 1, "accumulate": 2, "online": 3, "search": 4}
+KERNEL_IDS = {"encode": 0, "quantize": 1, "accumulate": 2, "online": 3, "search": 4,
+              "online_fwd": 5, "online_bwd": 6}
 
 
 class HdcParams(ctypes.Structure):
@@ -53,6 +54,7 @@ def _load() -> ctypes.CDLL:
     lib.hdc_train_classical.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.hdc_binarize_classical.argtypes = [vp, vp, vp, vp, vp]
     lib.hdc_train_online.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp]
+    lib.hdc_train_online_batched.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, i64, vp, vp]
     lib.hdc_binarize_online.argtypes = [vp, vp, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     lib.hdc_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -61,7 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.hdc_profile_enable.restype = ctypes.c_int
     lib.hdc_profile_read.restype = ctypes.c_int
     for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
-                 "hdc_binarize_classical", "hdc_train_online", "hdc_binarize_online", "hdc_search"):
+                 "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched",
+                 "hdc_binarize_online", "hdc_search"):
         getattr(lib, name).restype = ctypes.c_int
     lib.hdc_strerror.argtypes = [ctypes.c_int]
     lib.hdc_strerror.restype = ctypes.c_char_p
@@ -160,6 +163,14 @@ class Context:
         _check(lib.hdc_train_online(self._h, _dev(hv, torch.int32, (N, self.W)),
                                     _dev(labels, torch.int32, (N,)), N, int(epochs), float(lr),
                                     _dev(acc, torch.float32, (self.C, self.D)), _stream(stream)))
+
+    def hdc_train_online_batched(self, hv, labels, acc, batch: int, epochs: int = 1, lr: float = 1.0,
+                                 stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_train_online_batched(self._h, _dev(hv, torch.int32, (N, self.W)),
+                                            _dev(labels, torch.int32, (N,)), N, int(epochs), float(lr),
+                                            int(batch), _dev(acc, torch.float32, (self.C, self.D)),
+                                            _stream(stream)))
 
     def hdc_binarize_online(self, acc, class_hv, stream=None) -> None:
         _check(lib.hdc_binarize_online(self._h, _dev(acc, torch.float32, (self.C, self.D)),

@@ -24,7 +24,7 @@ constexpr int64_t kPermRows = 1 << 22;       // rows grouped by class per traini
 static void free_ctx(hdc_ctx_impl *c) {
     if (!c) return;
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
-                    c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->online_d, c->partial_d};
+                    c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -230,6 +230,16 @@ int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels
     if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev)) return HDC_EINVAL;
     return launch_train_online(impl(ctx), hv_dev, labels_dev, N, epochs, lr, acc_dev,
                                static_cast<hipStream_t>(stream));
+}
+
+int hdc_train_online_batched(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
+                             int32_t epochs, float lr, int64_t batch, float *acc_dev, void *stream) {
+    if (!ctx || N < 0 || epochs < 0 || batch < 1) return HDC_EINVAL;
+    if (N == 0 || epochs == 0) return HDC_OK;
+    if (!hv_dev || !labels_dev || !acc_dev) return HDC_EINVAL;
+    if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev)) return HDC_EINVAL;
+    return launch_train_online_batched(impl(ctx), hv_dev, labels_dev, N, epochs, lr, batch, acc_dev,
+                                       static_cast<hipStream_t>(stream));
 }
 
 int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_dev, void *stream) {

@@ -47,7 +47,15 @@ struct hdc_ctx_impl {
     int64_t perm_rows;
     uint32_t *partial_d;  // [partial_items][Wp * 16] per-block partial counts, two u16 per dword
     int64_t partial_items;
-    double *online_d;     // scratch of the online trainer (norms, partial sums)
+    // Scratch of hdc_train_online_batched, allocated on its first call and grown when a call
+    // needs more (batch size is a call argument, not a property of the model).
+    double *ob_part_d;    // [slices][sub-batch][C] partial dot products
+    size_t ob_part_bytes;
+    void *ob_wts_d;       // [batch] per-sample weight records
+    size_t ob_wts_bytes;
+    double *ob_norm_d;    // [C][ceil(D/64)] squared-norm partials of the class rows
+    size_t ob_norm_bytes;
+    bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised
 
     // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.
     bool prof_on;
@@ -90,6 +98,8 @@ int launch_binarize_classical(hdc_ctx_impl *c, const int32_t *acc, const int64_t
                               uint32_t *class_hv, hipStream_t s);
 int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                         int32_t epochs, float lr, float *acc, hipStream_t s);
+int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                                int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s);
 int launch_binarize_online(hdc_ctx_impl *c, const float *acc, uint32_t *class_hv, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(const hdc_ctx_impl *c);
