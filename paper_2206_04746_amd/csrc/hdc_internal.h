@@ -51,8 +51,14 @@ struct hdc_ctx_impl {
     // needs more (batch size is a call argument, not a property of the model).
     double *ob_part_d;    // [slices][sub-batch][C] partial dot products
     size_t ob_part_bytes;
-    void *ob_wts_d;       // [batch] per-sample weight records
+    void *ob_wts_d;       // [sub-batch] per-sample weight records
     size_t ob_wts_bytes;
+    double *ob_coef_d;    // [sub-batch][2|4|8|16] dense signed weights (C <= 16 only)
+    size_t ob_coef_bytes;
+    uint64_t *ob_col_d;   // [ceil(D/64)][sub-batch] 64-bit lane masks, dimension group major
+    size_t ob_col_bytes;
+    double *ob_carry_d;   // [C][D] batch sum carried between the launches of a long batch
+    size_t ob_carry_bytes;
     double *ob_norm_d;    // [C][ceil(D/64)] squared-norm partials of the class rows
     size_t ob_norm_bytes;
     bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised

@@ -28,9 +28,8 @@ struct OnlineWeight {
 typedef const OnlineWeight __attribute__((address_space(4))) *kptr_w;
 
 constexpr int kFwdWaves = 4;     // waves per forward block
-constexpr int kFwdGroups = 16;   // 64-dimension groups per forward slice
-constexpr int kFwdClasses = 2;   // classes per forward wave
 constexpr int kBwdMaxWaves = 16;
+constexpr int kBwdUnroll = 8;    // samples per trip of the backward loop
 constexpr int kBwdSlots = 256;   // (waves x classes) rows of 64 doubles in the backward LDS: 128 KB
 
 __device__ __forceinline__ double dpp_f64(double v, const int sel) {
@@ -69,85 +68,197 @@ __device__ __forceinline__ double lane_sign(uint64_t mask) {
     return __hiloint2double(hi, 0);
 }
 
-// 64-bit lane mask of dimension group `g` (dimensions 64 g .. 64 g + 63) of one sample row.
-// `row` and `g` are wave-uniform: scalar loads.  With FULL the caller guarantees that both
-// words lie inside the row; otherwise words past the row read as zero (the load itself is
-// clamped to the row, so that it stays unconditional).
-template <bool FULL>
-__device__ __forceinline__ uint64_t group_mask(kptr_u32 row, int g, int W) {
-    if (FULL) return (uint64_t)row[2 * g] | ((uint64_t)row[2 * g + 1] << 32);
-    const int i0 = 2 * g, i1 = 2 * g + 1;
-    const uint32_t lo = row[i0 < W ? i0 : W - 1], hi = row[i1 < W ? i1 : W - 1];
-    return (uint64_t)(i0 < W ? lo : 0u) | ((uint64_t)(i1 < W ? hi : 0u) << 32);
+// mem += v on an LDS double that only this lane touches; nothing is returned, so the wave does
+// not wait for it (ds_add_f64).
+__device__ __forceinline__ void lds_add(double *mem, double v) {
+    (void)__hip_atomic_fetch_add(mem, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
+
+// 64-bit lane mask of dimension group `g` (dimensions 64 g .. 64 g + 63) of one sample row.
+// `row` and `g` are wave-uniform: scalar loads.  SAFE = 2: both words lie inside the row;
+// SAFE = 1: the low word does, the high word may be the first word past the row (odd W) and
+// then reads as zero; SAFE = 0: either may lie past the row.  A load that might leave the row
+// is clamped to it, so that it stays unconditional.
+template <int SAFE>
+__device__ __forceinline__ uint64_t group_mask(kptr_u32 row, int g, int W) {
+    const int i0 = 2 * g, i1 = 2 * g + 1;
+    const uint32_t lo = SAFE >= 1 ? row[i0] : row[i0 < W ? i0 : W - 1];
+    const uint32_t hi = SAFE >= 2 ? row[i1] : row[i1 < W ? i1 : W - 1];
+    return (uint64_t)((SAFE >= 1 || i0 < W) ? lo : 0u) | ((uint64_t)((SAFE >= 2 || i1 < W) ? hi : 0u) << 32);
+}
+
+// Scalar loads return in any order, so the only wait there is for them is "all of them".  A
+// loop that wants the next trip's scalar operands in flight while it computes therefore waits
+// at the top of a trip (for the loads issued a trip ago), issues the next loads, and pins them
+// above the arithmetic.
+__device__ __forceinline__ void wait_scalar_loads() {
+    __builtin_amdgcn_sched_barrier(0);    // keeps the wait below the arithmetic of the trip before
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+}
+__device__ __forceinline__ void pin_schedule() { __builtin_amdgcn_sched_barrier(0); }
 
 // ---- forward: partial dot products ---------------------------------------------------------
 // grid (slices, class chunks, sample tiles).  A wave keeps acc[c0 .. c0+CC)[its 64 KPT
-// dimensions] in registers as fp64 and walks `spw` samples; per sample and class it leaves one
-// partial dot product part[slice][n][c].
+// dimensions] in registers as fp64 and walks `spw` samples, NS at a time; per sample and class
+// it leaves one partial dot product part[slice][n][c].  Per sample and group of 64 dimensions:
+// one v_cndmask for the signs, CC FMAs.  The NS * CC = 16 per-lane sums of a trip are reduced
+// over the lanes together: each lane parks its 16 values in the wave's LDS tile, then lane
+// (j, r) adds up value j of source lanes 16 r .. 16 r + 15 and two lane exchanges fold the four
+// r.  That is ~4 issue slots per value instead of ~20 for a butterfly per value.  The masks of
+// the next sample are loaded (scalar) while the current one computes.
+constexpr int kFwdVals = 16;                 // values reduced per trip = NS * CC
+constexpr int kFwdStride = kWave + 1;        // doubles per value row in the LDS tile (+1: banks)
+
 template <int CC, int KPT>
 __global__ __launch_bounds__(kFwdWaves *kWave) void online_fwd_kernel(
     const uint32_t *__restrict__ hv, int64_t nb, const float *__restrict__ acc, int D, int W, int C,
     int spw, double *__restrict__ part) {
+    constexpr int NS = kFwdVals / CC;
+    __shared__ double xch[kFwdWaves][kFwdVals * kFwdStride];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int slice = blockIdx.x;
     const int c0 = blockIdx.y * CC;
     const int64_t n0 = ((int64_t)blockIdx.z * kFwdWaves + wave) * spw;
-    if (n0 >= nb) return;   // the kernel has no barrier
+    if (n0 >= nb) return;   // the kernel has no block barrier
     const int64_t n1 = n0 + spw < nb ? n0 + spw : nb;
+    double *buf = xch[wave];
+
+    // The last slice is shifted back to end with the last group, so that its 2 KPT words are
+    // (but for the word after an odd W) inside the row like everyone else's; the groups it
+    // shares with the slice before it count there, not here.
+    const int G = (D + kWave - 1) / kWave;
+    const int g_own = slice * KPT;
+    const int g_base = (g_own + KPT <= G || G < KPT) ? g_own : G - KPT;
 
     double v[CC][KPT];
 #pragma unroll
     for (int j = 0; j < CC; ++j)
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
-            const int d = (slice * KPT + k) * kWave + lane;
-            v[j][k] = (c0 + j < C && d < D) ? (double)acc[(int64_t)(c0 + j) * D + d] : 0.0;
+            // clamped address, value dropped afterwards: the loads stay unconditional and all
+            // of them are in flight together
+            const int d = (g_base + k) * kWave + lane;
+            const int cc = c0 + j < C ? c0 + j : C - 1, dd = d < D ? d : D - 1;
+            const float x = acc[(int64_t)cc * D + dd];
+            v[j][k] = (c0 + j < C && d < D && g_base + k >= g_own) ? (double)x : 0.0;
         }
 
-    auto walk = [&](auto full) {
-        constexpr bool FULL = decltype(full)::value;
-        for (int64_t n = n0; n < n1; ++n) {
+    auto walk = [&](auto safe) {
+        constexpr int SAFE = decltype(safe)::value;
+        auto masks = [&](int64_t n, uint64_t(&m)[KPT]) {
             kptr_u32 row = (kptr_u32)(hv + n * W);
-            double p[CC];
 #pragma unroll
-            for (int j = 0; j < CC; ++j) p[j] = 0.0;
+            for (int k = 0; k < KPT; ++k)
+                m[k] = k + 1 < KPT || SAFE == 2 ? group_mask<(SAFE > 0 ? 2 : 0)>(row, g_base + k, W)
+                                                : group_mask<SAFE>(row, g_base + k, W);
+        };
+        uint64_t nxt[KPT];
+        masks(n0, nxt);
+        for (int64_t n = n0; n < n1; n += NS) {
+            double p[NS][CC];
 #pragma unroll
-            for (int k = 0; k < KPT; ++k) {
-                const double sgn = lane_sign(group_mask<FULL>(row, slice * KPT + k, W));
+            for (int u = 0; u < NS; ++u) {
+                uint64_t cur[KPT];
+                wait_scalar_loads();
 #pragma unroll
-                for (int j = 0; j < CC; ++j) p[j] = fma(v[j][k], sgn, p[j]);
+                for (int k = 0; k < KPT; ++k) cur[k] = nxt[k];
+                // rows past the wave's last sample repeat it; their sums are not stored
+                masks(n + u + 1 < n1 ? n + u + 1 : n1 - 1, nxt);
+                pin_schedule();
+#pragma unroll
+                for (int j = 0; j < CC; ++j) p[u][j] = 0.0;
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    const double sgn = lane_sign(cur[k]);
+#pragma unroll
+                    for (int j = 0; j < CC; ++j) p[u][j] = fma(v[j][k], sgn, p[u][j]);
+                }
             }
+            // all lanes -> lane (value, quarter): through the wave's LDS tile
 #pragma unroll
-            for (int j = 0; j < CC; ++j) {
-                const double t = wave_sum_f64(p[j]);
-                if (lane == 0 && c0 + j < C) part[((int64_t)slice * nb + n) * C + c0 + j] = t;
-            }
+            for (int u = 0; u < NS; ++u)
+#pragma unroll
+                for (int j = 0; j < CC; ++j) buf[(u * CC + j) * kFwdStride + lane] = p[u][j];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int val = lane & (kFwdVals - 1), quarter = lane >> 4;
+            const double *src = buf + val * kFwdStride + quarter * 16;
+            double t = 0.0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t += src[i];
+            t += __shfl_xor(t, 16, kWave);
+            t += __shfl_xor(t, 32, kWave);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();   // the tile is rewritten by the next trip
+            const int u = val / CC, j = val % CC;
+            if (lane < kFwdVals && n + u < n1 && c0 + j < C)
+                part[((int64_t)slice * nb + n + u) * C + c0 + j] = t;
         }
     };
-    if ((slice + 1) * KPT * 2 <= W)
-        walk(std::true_type{});
+    if ((g_base + KPT) * 2 <= W)
+        walk(std::integral_constant<int, 2>{});
+    else if ((g_base + KPT) * 2 - 1 <= W)
+        walk(std::integral_constant<int, 1>{});
     else
-        walk(std::false_type{});
+        walk(std::integral_constant<int, 0>{});
 }
 
-// ---- weights ---------------------------------------------------------------------------------
-// One thread per sample: finishes the dot products (slices in ascending order), cosines against
-// the frozen rows, prediction (lowest class among equals) and the two weights.
+// ---- weights (and the transposed sample bits for the backward step) -----------------------------
+// Blocks [0, wblocks): one thread per sample finishes the dot products (slices in ascending
+// order), cosines against the frozen rows, prediction (lowest class among equals) and the two
+// weights, as a record per sample and, for few classes, also as a dense row of signed fp64
+// coefficients (+w_y at y, -w_p at a wrong prediction, 0 elsewhere).  Blocks from wblocks on do an unrelated job that needs no launch of its own: each
+// turns a tile of 64 samples x 32 words of hv into colmask[g][n], the 64-bit lane mask of
+// dimension group g of sample n, so that the backward step, which works on one group of all
+// samples, reads its masks contiguously (8 samples per 64-byte scalar load) instead of 8 bytes
+// out of every 4 W-byte row.
+constexpr int kTileSamples = 64;
+constexpr int kTileGroups = 16;
+
 __global__ __launch_bounds__(256) void online_weights_kernel(
     const double *__restrict__ part, int slices, int64_t nb, const int32_t *__restrict__ labels,
     const double *__restrict__ normpart, int G, int C, double root_d, float lr,
-    OnlineWeight *__restrict__ out) {
+    OnlineWeight *__restrict__ out, double *__restrict__ coef, int CB, int wblocks,
+    const uint32_t *__restrict__ hv, int W, uint64_t *__restrict__ colmask, int64_t ld) {
     extern __shared__ double nrm[];   // [C] squared norms of the frozen rows
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    __shared__ uint32_t tile[kTileSamples][2 * kTileGroups + 1];
+    const int t = threadIdx.x;
+    if ((int)blockIdx.x >= wblocks) {
+        const int idx = blockIdx.x - wblocks;
+        const int stiles = (int)(ld / kTileSamples);
+        const int64_t ns = (int64_t)(idx % stiles) * kTileSamples;
+        const int g0 = (idx / stiles) * kTileGroups;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int sm = r * 8 + (t >> 5), w = 2 * g0 + (t & 31);
+            tile[sm][t & 31] = (ns + sm < nb && w < W) ? hv[(ns + sm) * W + w] : 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int gg = (t >> 6) + 4 * i, sm = t & 63;
+            if (g0 + gg < G)
+                colmask[(int64_t)(g0 + gg) * ld + ns + sm] =
+                    (uint64_t)tile[sm][2 * gg] | ((uint64_t)tile[sm][2 * gg + 1] << 32);
+        }
+        return;
+    }
+    // squared norm of row c: a wave per class, lanes stride over the groups (fixed order)
+    for (int c = t >> 6; c < C; c += 4) {
         double s = 0.0;
-        for (int g = 0; g < G; ++g) s += normpart[(int64_t)c * G + g];
-        nrm[c] = s;
+        for (int g = t & 63; g < G; g += kWave) s += normpart[(int64_t)c * G + g];
+        s = wave_sum_f64(s);
+        if ((t & 63) == 0) nrm[c] = s;
     }
     __syncthreads();
-    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= nb) return;
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + t;
+    if (n >= nb) {   // rows up to the padded length: zero coefficients, so that they add nothing
+        if (coef && n < ld)
+            for (int j = 0; j < CB; ++j) coef[n * CB + j] = 0.0;
+        return;
+    }
     const int y = labels[n];
     OnlineWeight r;
     r.y = -1;
@@ -174,52 +285,147 @@ __global__ __launch_bounds__(256) void online_weights_kernel(
         r.w_p = (float)((double)lr * (1.0 - best));
     }
     out[n] = r;
+    // the same two weights as a dense row of CB signed fp64 coefficients (small C only)
+    if (coef)
+        for (int j = 0; j < CB; ++j)
+            coef[n * CB + j] = j == r.y ? (double)r.w_y : j == r.pred ? -(double)r.w_p : 0.0;
 }
 
 // ---- backward: batch sum, update, new norms ----------------------------------------------------
-// One block per group of 64 dimensions; its waves split the batch into contiguous runs.  A wave
-// adds the weighted +-1 of each of its samples into its own LDS rows (one row of 64 doubles
-// per class of the window [c_lo, c_lo + c_n)), in sample order; after the barrier the rows of
-// the waves are added in wave order, the accumulators take the sum in one rounding, and the
-// squared norm of this block's 64 elements of each row goes to normpart[c][g].
+// One block per group of 64 dimensions; its waves split the nb samples into contiguous runs.  A
+// wave adds the weighted +-1 of each of its samples into its own LDS rows (one row of 64
+// doubles per class of the window [c_lo, c_lo + c_n)), in sample order; after the barrier the
+// rows of the waves are added in wave order.  A batch longer than one launch covers is summed
+// over several launches through `carry` (fp64 [C][D]: read unless `first`, written unless
+// `last`).  On the last one the accumulators take the sum in one rounding and the squared norm
+// of this block's 64 elements of each row goes to normpart[c][g].
+//
+// Where the sum of a wave lives depends on C.  CB > 0 (C <= CB <= 16): in registers, one fp64
+// per class; every sample is one FMA per class with the dense coefficient row from the weights
+// step, which arrives by scalar loads (an FMA with a zero coefficient leaves the sum as it is).
+// CB == 0: in the LDS rows themselves, one ds_add_f64 per weight of a sample - about 30
+// cycles of the LDS pipe each, which the 16 waves of a block share, so it only wins when a
+// dense row would be long.
+typedef const uint64_t __attribute__((address_space(4))) *kptr_u64;
+typedef const double __attribute__((address_space(4))) *kptr_f64;
+
+template <int CB>
 __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
-    const uint32_t *__restrict__ hv, const OnlineWeight *__restrict__ wts, int64_t B, float *acc,
-    int D, int W, int c_lo, int c_n, int G, double *__restrict__ normpart) {
+    const uint64_t *__restrict__ colmask, int64_t ld, const OnlineWeight *__restrict__ wts,
+    const double *__restrict__ coef, int64_t nb, float *acc, int D, int c_lo, int c_n, int G,
+    double *carry, int first, int last, double *__restrict__ normpart) {
     extern __shared__ double rows[];   // [waves][c_n][64]
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;
     const int g = blockIdx.x;
     double *mine = rows + (int64_t)wave * c_n * kWave;
-    for (int c = 0; c < c_n; ++c) mine[c * kWave + lane] = 0.0;
 
-    const int64_t per = (B + nw - 1) / nw;
+    // runs are whole trips, so that a trip's 8 masks are one aligned 64-byte load
+    const int64_t per = ((nb + nw - 1) / nw + kBwdUnroll - 1) / kBwdUnroll * kBwdUnroll;
     const int64_t n0 = wave * per;
-    const int64_t n1 = n0 + per < B ? n0 + per : B;
-    kptr_w rec = (kptr_w)wts;
-    for (int64_t n = n0; n < n1; ++n) {
-        const int y = rec[n].y;
-        if (y < 0) continue;
-        const int pred = rec[n].pred;
-        const int yy = y - c_lo, pp = pred - c_lo;
-        const bool hit_y = yy >= 0 && yy < c_n;
-        const bool hit_p = pred >= 0 && pp >= 0 && pp < c_n;
-        if (!hit_y && !hit_p) continue;
-        const double sgn = lane_sign(group_mask<false>((kptr_u32)(hv + n * W), g, W));
-        if (hit_y) mine[yy * kWave + lane] += (double)rec[n].w_y * sgn;
-        if (hit_p) mine[pp * kWave + lane] -= (double)rec[n].w_p * sgn;
+    const int64_t n1 = n0 + per < nb ? n0 + per : nb;
+    kptr_u64 col = (kptr_u64)(colmask + (int64_t)g * ld);
+    // All buffers are readable up to the next multiple of 64 samples; entries past nb are
+    // ignored.
+    if constexpr (CB > 0) {
+        // samples per trip: two trips' operands (T masks + T * CB coefficients) fit the SGPRs
+        constexpr int T = CB <= 4 ? 4 : 16 / CB;
+        double delta[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) delta[j] = 0.0;
+        kptr_f64 cf = (kptr_f64)coef;
+        auto fetch = [&](int64_t n, uint64_t(&m)[T], double(&k)[T][CB]) {
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                m[u] = col[n + u];
+#pragma unroll
+                for (int j = 0; j < CB; ++j) k[u][j] = cf[(n + u) * CB + j];
+            }
+        };
+        // no test for n + u < n1 inside a trip: coefficient rows from nb up to the next
+        // multiple of 64 are zero, and a run ends at a multiple of 8 or at nb
+        auto add = [&](const uint64_t(&m)[T], const double(&k)[T][CB]) {
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                const double sgn = lane_sign(m[u]);
+#pragma unroll
+                for (int j = 0; j < CB; ++j) delta[j] = fma(k[u][j], sgn, delta[j]);
+            }
+        };
+        // A run is a whole number of kBwdUnroll-sample rounds and every trip of a round is
+        // executed: samples from nb up to the end of the round have zero coefficients.  The
+        // fetch after a run's last trip is redirected to the run's start (in bounds, unused).
+        constexpr int U = kBwdUnroll / T;
+        const int64_t n_end = (n1 + kBwdUnroll - 1) / kBwdUnroll * kBwdUnroll;   // end of the last round
+        uint64_t mn[T];
+        double kn[T][CB];
+        if (n0 < n1) fetch(n0, mn, kn);
+        for (int64_t n = n0; n < n1; n += kBwdUnroll) {
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                uint64_t mc[T];
+                double kc[T][CB];
+                wait_scalar_loads();
+#pragma unroll
+                for (int u = 0; u < T; ++u) {
+                    mc[u] = mn[u];
+#pragma unroll
+                    for (int j = 0; j < CB; ++j) kc[u][j] = kn[u][j];
+                }
+                const int64_t nn = n + (q + 1) * T;
+                fetch(nn < n_end ? nn : n0, mn, kn);
+                pin_schedule();
+                add(mc, kc);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+            if (j < c_n) mine[j * kWave + lane] = delta[j];
+    } else {
+        for (int c = 0; c < c_n; ++c) mine[c * kWave + lane] = 0.0;
+        kptr_w rec = (kptr_w)wts;
+        // kBwdUnroll samples per trip: their scalar loads are in flight together, and the LDS
+        // adds return nothing, so a trip never waits on the LDS.  LDS operations of one wave
+        // complete in issue order: two samples of the same class add in sample order.
+        for (int64_t n = n0; n < n1; n += kBwdUnroll) {
+            OnlineWeight r[kBwdUnroll];
+            uint64_t m[kBwdUnroll];
+#pragma unroll
+            for (int u = 0; u < kBwdUnroll; ++u) {
+                r[u].y = rec[n + u].y;
+                r[u].pred = rec[n + u].pred;
+                r[u].w_y = rec[n + u].w_y;
+                r[u].w_p = rec[n + u].w_p;
+                m[u] = col[n + u];
+            }
+#pragma unroll
+            for (int u = 0; u < kBwdUnroll; ++u) {
+                const bool live = n + u < n1 && r[u].y >= 0;
+                const int yy = r[u].y - c_lo, pp = r[u].pred - c_lo;
+                const bool hit_y = live && yy >= 0 && yy < c_n;
+                const bool hit_p = live && r[u].pred >= 0 && pp >= 0 && pp < c_n;
+                const double sgn = lane_sign(m[u]);
+                if (hit_y) lds_add(&mine[yy * kWave + lane], (double)r[u].w_y * sgn);
+                if (hit_p) lds_add(&mine[pp * kWave + lane], -((double)r[u].w_p * sgn));
+            }
+        }
     }
     __syncthreads();
 
     const int d = g * kWave + lane;
     for (int c = wave; c < c_n; c += nw) {
-        double s = 0.0;
+        const int64_t at = (int64_t)(c_lo + c) * D + d;
+        double s = (!first && d < D) ? carry[at] : 0.0;
         for (int w = 0; w < nw; ++w) s += rows[((int64_t)w * c_n + c) * kWave + lane];
+        if (!last) {
+            if (d < D) carry[at] = s;
+            continue;
+        }
         double q = 0.0;
         if (d < D) {
-            float *a = acc + (int64_t)(c_lo + c) * D + d;
-            const float nv = (float)((double)*a + s);
-            *a = nv;
+            const float nv = (float)((double)acc[at] + s);
+            acc[at] = nv;
             q = (double)nv * (double)nv;
         }
         q = wave_sum_f64(q);
@@ -228,12 +434,13 @@ __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
 }
 
 // ---- host side ---------------------------------------------------------------------------------
-static int grow(void **p, size_t *have, size_t want) {
+template <typename T>
+static int grow(T **p, size_t *have, size_t want) {
     if (*have >= want) return HDC_OK;
     if (*p) HDC_HIP(hipFree(*p));   // waits for the device: nothing still reads the old buffer
     *p = nullptr;
     *have = 0;
-    const hipError_t e = hipMalloc(p, want + 256);
+    const hipError_t e = hipMalloc(reinterpret_cast<void **>(p), want + 256);
     if (e == hipErrorOutOfMemory) {
         (void)hipGetLastError();
         return HDC_ENOMEM;
@@ -243,18 +450,32 @@ static int grow(void **p, size_t *have, size_t want) {
     return HDC_OK;
 }
 
-static int launch_bwd(hdc_ctx_impl *c, const uint32_t *hv, const OnlineWeight *wts, int64_t B, float *acc,
-                      int G, double *normpart, hipStream_t s) {
+// Width of the dense coefficient rows of the backward step, 0 = none (LDS sums).
+static int bwd_dense_width(int C) { return C <= 2 ? 2 : C <= 4 ? 4 : C <= 8 ? 8 : C <= 16 ? 16 : 0; }
+
+static int launch_bwd(hdc_ctx_impl *c, int64_t ld, int64_t nb, float *acc, int G, bool first, bool last,
+                      hipStream_t s) {
     const int C = c->p.C;
     for (int c_lo = 0; c_lo < C; c_lo += kBwdSlots) {
         const int c_n = C - c_lo < kBwdSlots ? C - c_lo : kBwdSlots;
         int nw = kBwdSlots / c_n;
         if (nw > kBwdMaxWaves) nw = kBwdMaxWaves;
-        while (nw > 1 && (int64_t)(nw / 2) * 4 >= B) nw /= 2;   // at least a few samples per wave
+        while (nw > 1 && (int64_t)(nw / 2) * kBwdUnroll >= nb) nw /= 2;   // no wave without a trip
         const size_t lds = (size_t)nw * c_n * kWave * sizeof(double);
+        const dim3 grid((unsigned)G), block((unsigned)nw * kWave);
+        const OnlineWeight *wts = static_cast<const OnlineWeight *>(c->ob_wts_d);
         ProfScope prof(c, HDC_K_ONLINE_BWD, s);
-        hipLaunchKernelGGL(online_bwd_kernel, dim3((unsigned)G), dim3((unsigned)nw * kWave), lds, s, hv, wts,
-                           B, acc, c->p.D, c->W, c_lo, c_n, G, normpart);
+#define HDC_BWD(CB)                                                                                       \
+    hipLaunchKernelGGL(online_bwd_kernel<CB>, grid, block, lds, s, c->ob_col_d, ld, wts, c->ob_coef_d, nb, \
+                       acc, c->p.D, c_lo, c_n, G, c->ob_carry_d, first ? 1 : 0, last ? 1 : 0, c->ob_norm_d)
+        switch (bwd_dense_width(C)) {
+            case 2: HDC_BWD(2); break;
+            case 4: HDC_BWD(4); break;
+            case 8: HDC_BWD(8); break;
+            case 16: HDC_BWD(16); break;
+            default: HDC_BWD(0); break;
+        }
+#undef HDC_BWD
         HDC_HIP(hipGetLastError());
     }
     return HDC_OK;
@@ -264,68 +485,82 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
                                 int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s) {
     const int C = c->p.C, D = c->p.D, W = c->W;
     const int G = (D + kWave - 1) / kWave;
-    const int slices = (G + kFwdGroups - 1) / kFwdGroups;
-    const int chunks = (C + kFwdClasses - 1) / kFwdClasses;
+    // forward shape: 2 classes x 16 groups or 4 classes x 8 groups per wave, whichever wastes
+    // fewer class slots (relative cost per class slot and 16 groups: 71 : 62 issue slots / 2 : 4)
+    const bool wide = ((C + 3) / 4) * 125 < ((C + 1) / 2) * 71;
+    const int fwd_cc = wide ? 4 : 2, fwd_groups = wide ? 8 : 16;
+    const int slices = (G + fwd_groups - 1) / fwd_groups;
+    const int chunks = (C + fwd_cc - 1) / fwd_cc;
+    const int fwd_ns = kFwdVals / fwd_cc;
     if (batch > N) batch = N;
 
-    // forward + weights run over sub-batches of at most `sb` samples (bounds the partial buffer)
+    // A batch is worked off in pieces of at most `sb` samples (forward, weights, backward each);
+    // sb bounds the scratch: partial dot products (<= 256 MB) and transposed masks.
     int64_t sb = (int64_t)(256u << 20) / ((int64_t)slices * C * (int64_t)sizeof(double));
-    if (sb > 4096) sb = 4096;
+    if (sb > 8192) sb = 8192;
     if (sb < 64) sb = 64;
     if (sb > batch) sb = batch;
-    {
-        void *p = c->ob_part_d;
-        HDC_HIP(hipSetDevice(c->device));
-        int rc = grow(&p, &c->ob_part_bytes, (size_t)slices * sb * C * sizeof(double));
-        c->ob_part_d = static_cast<double *>(p);
-        if (rc != HDC_OK) return rc;
-        p = c->ob_wts_d;
-        rc = grow(&p, &c->ob_wts_bytes, (size_t)batch * sizeof(OnlineWeight));
-        c->ob_wts_d = p;
-        if (rc != HDC_OK) return rc;
-        p = c->ob_norm_d;
-        rc = grow(&p, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
-        c->ob_norm_d = static_cast<double *>(p);
-        if (rc != HDC_OK) return rc;
-    }
-    double *part = c->ob_part_d;
-    OnlineWeight *wts = static_cast<OnlineWeight *>(c->ob_wts_d);
-    double *normpart = c->ob_norm_d;
+    const int64_t ld = (sb + kTileSamples - 1) / kTileSamples * kTileSamples;
+    HDC_HIP(hipSetDevice(c->device));
+    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)slices * sb * C * sizeof(double));
+    if (rc == HDC_OK) rc = grow(&c->ob_wts_d, &c->ob_wts_bytes, (size_t)ld * sizeof(OnlineWeight));
+    if (rc == HDC_OK) rc = grow(&c->ob_col_d, &c->ob_col_bytes, (size_t)G * ld * sizeof(uint64_t));
+    const int cb = bwd_dense_width(C);
+    if (rc == HDC_OK && cb) rc = grow(&c->ob_coef_d, &c->ob_coef_bytes, (size_t)ld * cb * sizeof(double));
+    if (rc == HDC_OK) rc = grow(&c->ob_norm_d, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
+    if (rc == HDC_OK && batch > sb)
+        rc = grow(&c->ob_carry_d, &c->ob_carry_bytes, (size_t)C * D * sizeof(double));
+    if (rc != HDC_OK) return rc;
     if (!c->ob_attr_set) {
-        HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(online_bwd_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(kBwdSlots * kWave * sizeof(double))));
+        const void *kernels[] = {reinterpret_cast<const void *>(online_bwd_kernel<0>),
+                                 reinterpret_cast<const void *>(online_bwd_kernel<2>),
+                                 reinterpret_cast<const void *>(online_bwd_kernel<4>),
+                                 reinterpret_cast<const void *>(online_bwd_kernel<8>),
+                                 reinterpret_cast<const void *>(online_bwd_kernel<16>)};
+        for (const void *k : kernels)
+            HDC_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)(kBwdSlots * kWave * sizeof(double))));
         c->ob_attr_set = true;
     }
 
-    // squared norms of the rows as handed in: a backward step over an empty batch
-    int rc = launch_bwd(c, hv, wts, 0, acc, G, normpart, s);
+    // squared norms of the rows as handed in: a backward step over no samples
+    rc = launch_bwd(c, ld, 0, acc, G, true, true, s);
     if (rc != HDC_OK) return rc;
     const double root_d = sqrt((double)D);
+    const int ttiles = (G + kTileGroups - 1) / kTileGroups;
     for (int32_t e = 0; e < epochs; ++e)
         for (int64_t b0 = 0; b0 < N; b0 += batch) {
             const int64_t B = b0 + batch < N ? batch : N - b0;
             for (int64_t s0 = 0; s0 < B; s0 += sb) {
                 const int64_t nb = s0 + sb < B ? sb : B - s0;
-                int64_t spw = (nb * slices * chunks + 2047) / 2048;
-                if (spw < 1) spw = 1;
+                const uint32_t *rows = hv + (b0 + s0) * W;
+                // about four waves per SIMD when there is that much work; whole trips per wave
+                int64_t spw = (nb * slices * chunks + 4095) / 4096;
+                spw = (spw + fwd_ns - 1) / fwd_ns * fwd_ns;
                 if (spw > 64) spw = 64;
                 const int64_t tiles = (nb + kFwdWaves * spw - 1) / (kFwdWaves * spw);
+                const dim3 grid((unsigned)slices, (unsigned)chunks, (unsigned)tiles);
                 {
                     ProfScope prof(c, HDC_K_ONLINE_FWD, s);
-                    hipLaunchKernelGGL((online_fwd_kernel<kFwdClasses, kFwdGroups>),
-                                       dim3((unsigned)slices, (unsigned)chunks, (unsigned)tiles),
-                                       dim3(kFwdWaves * kWave), 0, s, hv + (b0 + s0) * W, nb, acc, D, W, C,
-                                       (int)spw, part);
+                    if (wide)
+                        hipLaunchKernelGGL((online_fwd_kernel<4, 8>), grid, dim3(kFwdWaves * kWave), 0, s, rows,
+                                           nb, acc, D, W, C, (int)spw, c->ob_part_d);
+                    else
+                        hipLaunchKernelGGL((online_fwd_kernel<2, 16>), grid, dim3(kFwdWaves * kWave), 0, s, rows,
+                                           nb, acc, D, W, C, (int)spw, c->ob_part_d);
                 }
                 HDC_HIP(hipGetLastError());
-                hipLaunchKernelGGL(online_weights_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256),
-                                   (size_t)C * sizeof(double), s, part, slices, nb, labels + b0 + s0, normpart,
-                                   G, C, root_d, lr, wts + s0);
+                const int64_t ld_used = (nb + kTileSamples - 1) / kTileSamples * kTileSamples;
+                const int wblocks = (int)((ld_used + 255) / 256);
+                const int tblocks = (int)(ld_used / kTileSamples) * ttiles;
+                hipLaunchKernelGGL(online_weights_kernel, dim3((unsigned)(wblocks + tblocks)), dim3(256),
+                                   (size_t)C * sizeof(double), s, c->ob_part_d, slices, nb, labels + b0 + s0,
+                                   c->ob_norm_d, G, C, root_d, lr, static_cast<OnlineWeight *>(c->ob_wts_d),
+                                   cb ? c->ob_coef_d : nullptr, cb, wblocks, rows, W, c->ob_col_d, ld_used);
                 HDC_HIP(hipGetLastError());
+                rc = launch_bwd(c, ld_used, nb, acc, G, s0 == 0, s0 + nb == B, s);
+                if (rc != HDC_OK) return rc;
             }
-            rc = launch_bwd(c, hv + b0 * W, wts, B, acc, G, normpart, s);
-            if (rc != HDC_OK) return rc;
         }
     return HDC_OK;
 }
