@@ -33,6 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # (one v_bitop3_b32 / v_xor_b32 / v_bcnt per lane per clock; half the fp32 FMA-flop figure of
 # 157.3 TFLOP/s, which counts 2 flops per FMA and the packed-fp32 dual issue).
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+FP64_PEAK_TFLOPS = 78.6           # MI355X published fp64 vector peak (FMA = 2 flop)
 
 
 def main() -> int:
@@ -271,7 +272,67 @@ def extras(torch, binding, make_workload):
     ms = _timed(torch, online, 2)
     res["train_online_cfg4_1epoch"] = {"ms": round(ms, 3), "us_per_step": round(ms * 1e3 / x4.shape[0], 3),
                                        "samples_per_s": round(x4.shape[0] / ms * 1e3, 0)}
+    # --- batched online training over the same set: the paper's batch-size axis (Sec. VI-D2).
+    # The two big kernels are fp64 FMA work on the vector unit: C*D per sample in the forward
+    # step, cb*D in the backward step (cb = C rounded up to 2/4/8/16 coefficient slots).
+    cb = next(w for w in (2, 4, 8, 16, wl4.C) if w >= wl4.C)
+    sweep = {}
+    for batch in (8, 64, 512, 2048, 8192):
+        def batched(b=batch):
+            acc4.zero_()
+            ctx.hdc_train_online_batched(hv4, y4d, acc4, b, epochs=1, lr=wl4.lr)
+        ms = _timed(torch, batched, 3)
+        entry = {"ms": round(ms, 4), "samples_per_s": round(x4.shape[0] / ms * 1e3, 0),
+                 "speedup_vs_batch1_chain": round(res["train_online_cfg4_1epoch"]["ms"] / ms, 1)}
+        if batch >= 2048:
+            ctx.hdc_profile_enable(True)
+            batched()
+            torch.cuda.synchronize()
+            f_ms, f_n = ctx.hdc_profile_read("online_fwd")
+            b_ms, b_n = ctx.hdc_profile_read("online_bwd")
+            ctx.hdc_profile_enable(False)
+            n = x4.shape[0]
+            entry["fwd_us"] = round(f_ms * 1e3, 2)
+            entry["bwd_us"] = round(b_ms * 1e3, 2)
+            entry["fwd_frac_fp64_valu"] = round(2.0 * n * wl4.C * wl4.D / (f_ms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS, 4)
+            entry["bwd_frac_fp64_valu"] = round(2.0 * n * cb * wl4.D / (b_ms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS, 4)
+        sweep[str(batch)] = entry
+    res["train_online_batched_cfg4_1epoch"] = sweep
     ctx.close()
+    del hv4, x4d
+
+    # --- the whole classical step (as timed for `value`) along the paper's dimension axis
+    # (Sec. VI-D1, ISOLET shape) and at the small-feature PAMAP shape of Table II
+    def pipeline(wl, ntr, nte):
+        c = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+        xt, yt = wl.train(ntr)
+        xs, _ = wl.test(nte)
+        xt, yt, xs = torch.from_numpy(xt).to(dev), torch.from_numpy(yt).to(dev), torch.from_numpy(xs).to(dev)
+        ht = torch.empty((ntr, c.W), dtype=torch.int32, device=dev)
+        hs = torch.empty((nte, c.W), dtype=torch.int32, device=dev)
+        a = torch.zeros((wl.C, wl.D), dtype=torch.int32, device=dev)
+        n = torch.zeros(wl.C, dtype=torch.int64, device=dev)
+        m = torch.empty((wl.C, c.W), dtype=torch.int32, device=dev)
+        p = torch.empty(nte, dtype=torch.int32, device=dev)
+
+        def train():
+            c.hdc_encode(xt, ht)
+            a.zero_()
+            n.zero_()
+            c.hdc_train_classical(ht, yt, a, n)
+            c.hdc_binarize_classical(a, n, m)
+
+        def infer():
+            c.hdc_encode(xs, hs)
+            c.hdc_search(hs, m, p, None)
+        t_ms, i_ms = _timed(torch, train, 20), _timed(torch, infer, 20)
+        c.close()
+        return {"train_ms": round(t_ms, 4), "train_samples_per_s": round(ntr / t_ms * 1e3, 0),
+                "infer_ms": round(i_ms, 4), "queries_per_s": round(nte / i_ms * 1e3, 0)}
+    res["dimension_sweep_isolet_shape"] = {
+        str(D): pipeline(make_workload(2, D=D), 6238, 1559) for D in (1024, 2048, 4096, 8192, 16384, 32768)}
+    wl6 = make_workload(6)
+    res["pamap_shape"] = pipeline(wl6, wl6.n_train, wl6.n_test)
     return res
 
 

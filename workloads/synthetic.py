@@ -1,4 +1,4 @@
-"""Seeded synthetic stand-ins for the paper's five datasets (Table II shapes).
+"""Seeded synthetic stand-ins for the paper's datasets (Table II shapes).
 
 Nothing here is real ISOLET / MNIST / UCIHAR / CHB-MIT data: every matrix is drawn
 from ``numpy.random.default_rng`` with a key derived from ``(seed, config, stream,
@@ -32,6 +32,10 @@ CONFIGS = {
             n_train=7352, n_test=2947, mode="online", epochs=3, lr=1.0),
     5: dict(name="chbmit-shape-classical", D=10000, F=342, L=64, C=2, dtype="f32",
             n_train=5_000_000, n_test=5_000_000, mode="classical", epochs=1, lr=1.0),
+    # not one of the five benchmark configurations: the fourth small dataset of Table II
+    # (31 features, 5 classes, about 80k samples), the small-F end of the evaluation
+    6: dict(name="pamap-shape-classical", D=10000, F=31, L=64, C=5, dtype="f32",
+            n_train=64000, n_test=16000, mode="classical", epochs=1, lr=1.0),
 }
 
 
@@ -164,7 +168,7 @@ class Workload:
 
 
 def make_workload(cfg: int, seed: int = 0, **override) -> Workload:
-    """Tables and class parameters of config ``cfg`` (1..5); rows are drawn lazily.
+    """Tables and class parameters of config ``cfg`` (1..6); rows are drawn lazily.
 
     Draw order: item table, level-0 vector, flip permutation, tie vector (stream 0);
     then the class parameters (stream 1); labels and features come per block.
@@ -183,7 +187,7 @@ def make_workload(cfg: int, seed: int = 0, **override) -> Workload:
     if cfg == 1:
         params = dict(means=rp.uniform(0.2, 0.8, size=(C, F)), sigma=0.1, clip=(0.0, 1.0))
         lo, hi = np.zeros(F), np.ones(F)
-    elif cfg in (2, 4):
+    elif cfg in (2, 4, 6):
         params = dict(means=rp.uniform(-0.5, 0.5, size=(C, F)), sigma=0.25, clip=(-1.0, 1.0))
         lo, hi = -np.ones(F), np.ones(F)
     elif cfg == 3:
@@ -200,7 +204,7 @@ def make_workload(cfg: int, seed: int = 0, **override) -> Workload:
         # fixed upper edge: the 99.9th percentile of the negative-class lognormal
         hi = np.repeat(np.exp(mu_ch + 3.0902 * 0.5), 19)
     else:
-        raise ValueError("config must be 1..5")
+        raise ValueError("config must be 1..6")
     lo32 = scale32 = None
     if c["dtype"] == "f32":
         lo32 = lo.astype(np.float32)
