@@ -157,6 +157,35 @@ def train_online(hv: np.ndarray, labels: np.ndarray, D: int, C: int, epochs: int
     return (acc, pred, margin) if log else acc
 
 
+def hsum(hv: np.ndarray, D: int) -> np.ndarray:
+    """Horizontal summation (Sec. IV-B2): set dimensions per row, ``int32 [N]``."""
+    bits = unpack(hv, D)
+    out = np.empty(bits.shape[0], dtype=np.int32)
+    _load().orc_hsum(_p(bits), I64(bits.shape[0]), I32(D), _p(out))
+    return out
+
+
+def vsum(hv: np.ndarray, D: int) -> np.ndarray:
+    """Vertical summation (Sec. IV-B2): rows with the dimension set, ``int32 [D]``."""
+    bits = unpack(hv, D)
+    out = np.empty(D, dtype=np.int32)
+    _load().orc_vsum(_p(bits), I64(bits.shape[0]), I32(D), _p(out))
+    return out
+
+
+def search_cosine(hv: np.ndarray, m: np.ndarray, D: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Cosine inference against real-valued class rows ``m f32[C][D]`` (Sec. III):
+    ``(cos f64[N][C], pred int32[N])``."""
+    bits = unpack(hv, D)
+    m = _c(m, np.float32)
+    N, C = bits.shape[0], m.shape[0]
+    assert m.shape == (C, D)
+    cosv = np.empty((N, C), dtype=np.float64)
+    pred = np.empty(N, dtype=np.int32)
+    _load().orc_search_cosine(_p(bits), I64(N), I32(D), _p(m), I32(C), _p(cosv), _p(pred))
+    return cosv, pred
+
+
 def train_online_batched(hv: np.ndarray, labels: np.ndarray, D: int, C: int, batch: int,
                          epochs: int = 1, lr: float = 1.0, acc: Optional[np.ndarray] = None) -> np.ndarray:
     """Online training with the class rows frozen over each batch of ``batch`` samples

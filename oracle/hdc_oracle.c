@@ -226,6 +226,65 @@ void orc_train_online(const uint8_t *hv, const int32_t *labels, int64_t N, int32
     free(cosv);
 }
 
+/* ---- stand-alone summations (Sec. IV-B2) and cosine inference (Sec. III) ------------ */
+
+/* Horizontal summation: out[n] = number of set dimensions of row n. */
+void orc_hsum(const uint8_t *bits, int64_t N, int32_t D, int32_t *out)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        int32_t s = 0;
+        for (int32_t d = 0; d < D; ++d)
+            s += bits[n * D + d];
+        out[n] = s;
+    }
+}
+
+/* Vertical summation: out[d] = number of rows whose dimension d is set. */
+void orc_vsum(const uint8_t *bits, int64_t N, int32_t D, int32_t *out)
+{
+    for (int32_t d = 0; d < D; ++d)
+        out[d] = 0;
+    for (int64_t n = 0; n < N; ++n)
+        for (int32_t d = 0; d < D; ++d)
+            out[d] += bits[n * D + d];
+}
+
+/* Cosine-similarity inference against real-valued class rows m[C][D]: with s = 2 h - 1,
+ * cos[n][c] = <m_c, s> / (|m_c| sqrt(D)), 0 for an all-zero row (the same expression as inside
+ * online training); pred[n] = lowest c with the largest cosine.  fp64. */
+void orc_search_cosine(const uint8_t *hv, int64_t N, int32_t D, const float *m, int32_t C,
+                       double *cosv, int32_t *pred)
+{
+    const double root_d = sqrt((double)D);
+    double *nrm = (double *)malloc((size_t)C * sizeof(double));
+    for (int32_t c = 0; c < C; ++c) {
+        double s2 = 0.0;
+        for (int32_t d = 0; d < D; ++d) {
+            double v = (double)m[(int64_t)c * D + d];
+            s2 += v * v;
+        }
+        nrm[c] = s2;
+    }
+    for (int64_t n = 0; n < N; ++n) {
+        const uint8_t *h = hv + n * D;
+        int32_t best = 0;
+        for (int32_t c = 0; c < C; ++c) {
+            const float *row = m + (int64_t)c * D;
+            double dot = 0.0;
+            for (int32_t d = 0; d < D; ++d) {
+                double v = (double)row[d];
+                dot += h[d] ? v : -v;
+            }
+            const double cs = nrm[c] == 0.0 ? 0.0 : dot / (sqrt(nrm[c]) * root_d);
+            cosv[n * C + c] = cs;
+            if (cs > cosv[n * C + best])
+                best = c;
+        }
+        pred[n] = best;
+    }
+    free(nrm);
+}
+
 /* ---- batched online training (Sec. VI-D2) -------------------------------------- */
 
 /* "Only updating class vectors after a batch size of n new datapoints are received":

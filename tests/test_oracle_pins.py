@@ -495,3 +495,74 @@ def test_online_batched_order_inside_a_batch_does_not_matter_but_batches_do():
     np.testing.assert_allclose(b, a, rtol=1e-6, atol=1e-6)
     c = oracle.train_online_batched(hv, y, D, C, batch=N)                      # different batching
     assert not np.allclose(c, a)
+
+
+# ------------------------------------- stand-alone summations (Sec. IV-B2), cosine inference
+def test_hsum_and_vsum_are_row_and_column_sums():
+    rng = np.random.default_rng(30)
+    N, D = 37, 203
+    bits = rand_bits(rng, N, D)
+    hv = pack_bits_lsb(bits)
+    assert np.array_equal(oracle.hsum(hv, D), bits.sum(axis=1))
+    assert np.array_equal(oracle.vsum(hv, D), bits.sum(axis=0))
+    # the two agree on the grand total, and an all-ones / all-zero row counts D / 0
+    assert oracle.hsum(hv, D).sum() == oracle.vsum(hv, D).sum()
+    ends = pack_bits_lsb(np.stack([np.ones(D, np.uint8), np.zeros(D, np.uint8)]))
+    assert oracle.hsum(ends, D).tolist() == [D, 0]
+    assert oracle.vsum(ends, D).tolist() == [1] * D
+
+
+def test_hsum_of_xor_is_the_hamming_distance_and_vsum_is_the_class_accumulator():
+    rng = np.random.default_rng(31)
+    N, D, C = 25, 130, 3
+    q, cls = _rand_hv(rng, N, D), _rand_hv(rng, C, D)
+    dist, _ = oracle.search(q, cls, D)
+    for c in range(C):
+        assert np.array_equal(oracle.hsum(q ^ cls[c], D), dist[:, c])
+    y = rng.integers(0, C, N).astype(np.int32)
+    acc, _ = oracle.train_classical(q, y, D, C)
+    for c in range(C):
+        assert np.array_equal(oracle.vsum(q[y == c], D), acc[c])
+
+
+def test_cosine_inference_closed_forms():
+    rng = np.random.default_rng(32)
+    N, D, C = 20, 96, 4
+    bits = rand_bits(rng, N, D)
+    hv = pack_bits_lsb(bits)
+    s = 2.0 * bits - 1.0
+    # rows that are themselves +-1 vectors: cosine = 1 - 2 hamming / D (both sides exact in fp64)
+    cbits = rand_bits(rng, C, D)
+    m = (2.0 * cbits - 1.0).astype(np.float32)
+    cosv, pred = oracle.search_cosine(hv, m, D)
+    dist, hpred = oracle.search(hv, pack_bits_lsb(cbits), D)
+    np.testing.assert_allclose(cosv, 1.0 - 2.0 * dist / D, rtol=0, atol=1e-15)
+    assert np.array_equal(pred, hpred)
+    # a sample against itself / its complement / a zero row; scaling a row changes nothing
+    m2 = np.stack([s[0], -s[0], np.zeros(D), 7.5 * s[0]]).astype(np.float32)
+    c2, p2 = oracle.search_cosine(hv[:1], m2, D)
+    np.testing.assert_allclose(c2[0], [1.0, -1.0, 0.0, 1.0], rtol=0, atol=1e-15)
+    assert p2[0] == 0                                        # the lowest of the equal best
+    # general rows: the definition, written with numpy
+    m3 = rng.standard_normal((C, D)).astype(np.float32)
+    c3, p3 = oracle.search_cosine(hv, m3, D)
+    want = (s @ m3.astype(np.float64).T) / (np.linalg.norm(m3.astype(np.float64), axis=1) * np.sqrt(D))
+    np.testing.assert_allclose(c3, want, rtol=1e-12, atol=1e-15)
+    assert np.array_equal(p3, want.argmax(axis=1))
+
+
+def test_cosine_scores_are_the_ones_online_training_uses():
+    # one online step from a trained model: the weights it applies follow from search_cosine
+    rng = np.random.default_rng(33)
+    D, C, N = 64, 3, 30
+    hv = _rand_hv(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    acc = oracle.train_online(hv, y, D, C)
+    cosv, pred = oracle.search_cosine(hv[:1], acc, D)
+    nxt = oracle.train_online(hv[:1], y[:1], D, C, acc=acc)
+    s = 2.0 * oracle.unpack(hv[:1], D)[0] - 1.0
+    want = acc.astype(np.float64).copy()
+    want[y[0]] += np.float32(1.0 - cosv[0, y[0]]) * s
+    if pred[0] != y[0]:
+        want[pred[0]] -= np.float32(1.0 - cosv[0, pred[0]]) * s
+    np.testing.assert_allclose(nxt, want.astype(np.float32), rtol=1e-6, atol=1e-6)
