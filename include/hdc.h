@@ -162,6 +162,36 @@ int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *
                uint32_t *dist_dev, int32_t *pred_dev, void *stream);
 
 /*
+ * Cosine-similarity inference, Sec. III (the second similarity of Table I), against
+ * real-valued class rows such as the online accumulators: with s = 2*hv[n] - 1,
+ *   cos[n][c] = <acc[c], s> / (|acc[c]| * sqrt(D))   (0 for an all-zero row; fp64 sums),
+ *   pred[n]   = lowest c with the largest cos[n][c]  (compared in fp64).
+ *   hv_dev [N][W], acc_dev [C][D] fp32 (read only), cos_dev [N][C] fp32 out (the fp64 value
+ *   rounded once) or NULL, pred_dev [N] int32 out (required).  Allocates context-owned
+ *   scratch like hdc_train_online_batched.
+ */
+int hdc_search_cosine(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const float *acc_dev,
+                      float *cos_dev, int32_t *pred_dev, void *stream);
+
+/*
+ * The stand-alone hypervector primitives of Sec. IV-B.  D and W are the context's.
+ *   hdc_pack   (IV-B1)  bits_dev [N][D] bytes (any non-zero byte is a 1) -> hv_dev [N][W],
+ *                       LSB first, pad bits 0.
+ *   hdc_unpack (IV-B1)  hv_dev [N][W] -> bits_dev [N][D] bytes of 0 / 1.
+ *   hdc_hsum   (IV-B2, horizontal summation)  sum_dev[n] = set dimensions of row n, int32 [N]
+ *                       (pad bits must be zero, as everywhere in this library).
+ *   hdc_vsum   (IV-B2, vertical summation)    sum_dev[d] = rows with dimension d set,
+ *                       int32 [D], overwritten (zeros for N == 0); N <= INT32_MAX.  Uses the
+ *                       context's training scratch: do not overlap with hdc_train_classical
+ *                       on another stream.
+ * All matrices are device pointers, row-major, rows back to back.
+ */
+int hdc_pack(hdc_ctx *ctx, const uint8_t *bits_dev, int64_t N, uint32_t *hv_dev, void *stream);
+int hdc_unpack(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, uint8_t *bits_dev, void *stream);
+int hdc_hsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
+int hdc_vsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
+
+/*
  * Measurement aid (not an operation of the paper): per-kernel device time.  While enabled,
  * every launch of a hot kernel is bracketed by a pair of HIP events recorded on the stream
  * the kernel runs on.  hdc_profile_read waits for the recorded events of one kernel, returns

@@ -23,6 +23,7 @@ HDC_F32, HDC_U8 = 0, 1
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
+           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum",
            "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
@@ -56,6 +57,9 @@ def _load() -> ctypes.CDLL:
     lib.hdc_train_online.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp]
     lib.hdc_train_online_batched.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, i64, vp, vp]
     lib.hdc_binarize_online.argtypes = [vp, vp, vp, vp]
+    lib.hdc_search_cosine.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    for name in ("hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum"):
+        getattr(lib, name).argtypes = [vp, vp, i64, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     lib.hdc_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.hdc_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -64,7 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.hdc_profile_read.restype = ctypes.c_int
     for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
                  "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched",
-                 "hdc_binarize_online", "hdc_search"):
+                 "hdc_binarize_online", "hdc_search", "hdc_search_cosine", "hdc_pack", "hdc_unpack",
+                 "hdc_hsum", "hdc_vsum"):
         getattr(lib, name).restype = ctypes.c_int
     lib.hdc_strerror.argtypes = [ctypes.c_int]
     lib.hdc_strerror.restype = ctypes.c_char_p
@@ -175,6 +180,33 @@ class Context:
     def hdc_binarize_online(self, acc, class_hv, stream=None) -> None:
         _check(lib.hdc_binarize_online(self._h, _dev(acc, torch.float32, (self.C, self.D)),
                                        _dev(class_hv, torch.int32, (self.C, self.W)), _stream(stream)))
+
+    def hdc_search_cosine(self, hv, acc, pred, cos=None, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_search_cosine(self._h, _dev(hv, torch.int32, (N, self.W)), N,
+                                     _dev(acc, torch.float32, (self.C, self.D)),
+                                     None if cos is None else _dev(cos, torch.float32, (N, self.C)),
+                                     _dev(pred, torch.int32, (N,)), _stream(stream)))
+
+    def hdc_pack(self, bits, hv, stream=None) -> None:
+        N = bits.shape[0]
+        _check(lib.hdc_pack(self._h, _dev(bits, torch.uint8, (N, self.D)), N,
+                            _dev(hv, torch.int32, (N, self.W)), _stream(stream)))
+
+    def hdc_unpack(self, hv, bits, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_unpack(self._h, _dev(hv, torch.int32, (N, self.W)), N,
+                              _dev(bits, torch.uint8, (N, self.D)), _stream(stream)))
+
+    def hdc_hsum(self, hv, out, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_hsum(self._h, _dev(hv, torch.int32, (N, self.W)), N,
+                            _dev(out, torch.int32, (N,)), _stream(stream)))
+
+    def hdc_vsum(self, hv, out, stream=None) -> None:
+        N = hv.shape[0]
+        _check(lib.hdc_vsum(self._h, _dev(hv, torch.int32, (N, self.W)), N,
+                            _dev(out, torch.int32, (self.D,)), _stream(stream)))
 
     def hdc_search(self, hv, class_hv, pred, dist=None, stream=None) -> None:
         N = hv.shape[0]

@@ -325,19 +325,43 @@ int64_t classical_max_items(const hdc_ctx_impl *c) {
     return p.cap + 2 * (int64_t)c->p.C + 16 + c->perm_rows / (p.rg * p.rb_max);
 }
 
+// The accumulate + reduce launches for n rows already grouped into `classes` classes (perm,
+// cnt, off, blk in the context's scratch); acc [classes][D] is added to.
+static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32_t *hv0, int64_t n,
+                              int classes, int64_t rb, int32_t *acc, hipStream_t s) {
+    const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
+    const uint32_t block_rows = (uint32_t)(rg * rb);
+    const int64_t items = (n + block_rows - 1) / block_rows + classes;
+    if (items > c->partial_items) return HDC_ELIMIT;   // cannot happen: sized for the worst case
+    const size_t lds = (size_t)(rg - 1) * spb * kWavePlanes * kWave * sizeof(uint32_t);
+    {
+        ProfScope prof(c, HDC_K_ACCUMULATE, s);
+        hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks), dim3(spb * rg * kWave),
+                           lds, s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, classes, c->W,
+                           c->Wp, (int)rb, spb, rg, c->partial_d);
+    }
+    // enough threads for the reduction: split a class's partial rows K ways when C is small
+    const int pairs = c->Wp * 16;
+    int K = (int)((32768 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
+    K = K < 1 ? 1 : (K > 16 ? 16 : K);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)classes, (unsigned)K),
+                       dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                            int32_t *acc, int64_t *class_n, hipStream_t s) {
     const int C = c->p.C;
     AccPlan plan;
     const int prc = plan_static(c, &plan);
     if (prc != HDC_OK) return prc;
-    const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
         const int32_t *lab0 = labels + n0;
         const int64_t rb = plan_rb(plan, n);
-        const uint32_t block_rows = (uint32_t)(rg * rb);
+        const uint32_t block_rows = (uint32_t)(plan.rg * rb);
         if (n <= kSmallN) {
             hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(kGroupThreads), (size_t)(2 * C + 2) * 4, s,
                                lab0, (int)n, C, block_rows, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d,
@@ -353,23 +377,48 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
             hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
                                c->cls_off_d, c->cls_cur_d, c->perm_d);
         }
-        const int64_t items = (n + block_rows - 1) / block_rows + C;
-        if (items > c->partial_items) return HDC_ELIMIT;   // cannot happen: sized for the worst case
-        const size_t lds = (size_t)(rg - 1) * spb * kWavePlanes * kWave * sizeof(uint32_t);
-        {
-            ProfScope prof(c, HDC_K_ACCUMULATE, s);
-            hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks),
-                               dim3(spb * rg * kWave), lds, s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d,
-                               c->cls_blk_d, C, c->W, c->Wp, (int)rb, spb, rg, c->partial_d);
-        }
-        // enough threads for the reduction: split a class's partial rows K ways when C is small
-        const int pairs = c->Wp * 16;
-        int K = (int)((32768 + (int64_t)C * pairs - 1) / ((int64_t)C * pairs));
-        K = K < 1 ? 1 : (K > 16 ? 16 : K);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)C, (unsigned)K),
-                           dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
-        HDC_HIP(hipGetLastError());
+        const int rc = accumulate_grouped(c, plan, hv0, n, C, rb, acc, s);
+        if (rc != HDC_OK) return rc;
     }
+    return HDC_OK;
+}
+
+// ---- vertical summation on its own (Sec. IV-B2) --------------------------------------------
+// out[d] = number of rows with dimension d set: the class count with every row in one class.
+// The grouping step degenerates to the identity permutation.
+__global__ __launch_bounds__(256) void group_all_kernel(uint32_t n, uint32_t block_rows, uint32_t *cnt,
+                                                         uint32_t *off, uint32_t *blk, uint32_t *perm) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) perm[i] = i;
+    if (i == 0) {
+        cnt[0] = n;
+        off[0] = 0;
+        off[1] = n;
+        blk[0] = 0;
+        blk[1] = (n + block_rows - 1) / block_rows;
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s) {
+    AccPlan plan;
+    const int prc = plan_static(c, &plan);
+    if (prc != HDC_OK) return prc;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((c->p.D + 255) / 256)), dim3(256), 0, s, out,
+                       (int64_t)c->p.D);
+    for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
+        const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
+        const int64_t rb = plan_rb(plan, n);
+        hipLaunchKernelGGL(group_all_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t)n,
+                           (uint32_t)(plan.rg * rb), c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, c->perm_d);
+        const int rc = accumulate_grouped(c, plan, hv + (size_t)n0 * c->W, n, 1, rb, out, s);
+        if (rc != HDC_OK) return rc;
+    }
+    HDC_HIP(hipGetLastError());
     return HDC_OK;
 }
 

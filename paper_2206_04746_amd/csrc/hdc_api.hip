@@ -249,6 +249,42 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
     return launch_binarize_online(impl(ctx), acc_dev, class_hv_dev, static_cast<hipStream_t>(stream));
 }
 
+int hdc_search_cosine(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const float *acc_dev, float *cos_dev,
+                      int32_t *pred_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!hv_dev || !acc_dev || !pred_dev) return HDC_EINVAL;
+    if (!aligned4(hv_dev) || !aligned4(acc_dev) || !aligned4(cos_dev) || !aligned4(pred_dev)) return HDC_EINVAL;
+    return launch_search_cosine(impl(ctx), hv_dev, N, acc_dev, cos_dev, pred_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_pack(hdc_ctx *ctx, const uint8_t *bits_dev, int64_t N, uint32_t *hv_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!bits_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
+    return launch_pack(impl(ctx), bits_dev, N, hv_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_unpack(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, uint8_t *bits_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!bits_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
+    return launch_unpack(impl(ctx), hv_dev, N, bits_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_hsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!hv_dev || !sum_dev || !aligned4(hv_dev) || !aligned4(sum_dev)) return HDC_EINVAL;
+    return launch_hsum(impl(ctx), hv_dev, N, sum_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_vsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream) {
+    if (!ctx || N < 0 || N > INT32_MAX) return HDC_EINVAL;
+    if (!sum_dev || !aligned4(sum_dev) || (N > 0 && (!hv_dev || !aligned4(hv_dev)))) return HDC_EINVAL;
+    return launch_vsum(impl(ctx), hv_dev, N, sum_dev, static_cast<hipStream_t>(stream));
+}
+
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream) {
     if (!ctx || N < 0) return HDC_EINVAL;

@@ -107,6 +107,12 @@ int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labe
 int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                                 int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s);
 int launch_binarize_online(hdc_ctx_impl *c, const float *acc, uint32_t *class_hv, hipStream_t s);
+int launch_search_cosine(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const float *acc, float *cos_out,
+                         int32_t *pred, hipStream_t s);
+int launch_pack(hdc_ctx_impl *c, const uint8_t *bits, int64_t N, uint32_t *hv, hipStream_t s);
+int launch_unpack(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, uint8_t *bits, hipStream_t s);
+int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
+int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(const hdc_ctx_impl *c);
 int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,

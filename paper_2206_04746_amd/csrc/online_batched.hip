@@ -433,6 +433,57 @@ __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
     }
 }
 
+// ---- squared norms of given rows, and cosine inference ---------------------------------------
+// normpart[c][g] = sum of acc[c][d]^2 over the 64 dimensions of group g, with the arithmetic of
+// the backward step's epilogue.  grid (G, ceil(C / 4)), one wave per (class, group).
+__global__ __launch_bounds__(256) void online_norm_kernel(const float *__restrict__ acc, int D, int C, int G,
+                                                          double *__restrict__ normpart) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int c = blockIdx.y * 4 + (threadIdx.x >> 6), g = blockIdx.x;
+    if (c >= C) return;
+    const int d = g * kWave + lane;
+    double q = 0.0;
+    if (d < D) {
+        const double v = (double)acc[(int64_t)c * D + d];
+        q = v * v;
+    }
+    q = wave_sum_f64(q);
+    if (lane == 0) normpart[(int64_t)c * G + g] = q;
+}
+
+// Cosine-similarity inference (Sec. III): one thread per sample finishes the dot products of
+// the forward step into cosines; cos_out [nb][C] fp32 (optional), pred = lowest class with the
+// largest cosine (compared in fp64).
+__global__ __launch_bounds__(256) void cosine_finish_kernel(
+    const double *__restrict__ part, int slices, int64_t nb, const double *__restrict__ normpart, int G, int C,
+    double root_d, float *__restrict__ cos_out, int32_t *__restrict__ pred_out) {
+    extern __shared__ double nrm[];   // [C]
+    const int t = threadIdx.x;
+    for (int c = t >> 6; c < C; c += 4) {
+        double s = 0.0;
+        for (int g = t & 63; g < G; g += kWave) s += normpart[(int64_t)c * G + g];
+        s = wave_sum_f64(s);
+        if ((t & 63) == 0) nrm[c] = s;
+    }
+    __syncthreads();
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + t;
+    if (n >= nb) return;
+    double best = 0.0;
+    int pred = 0;
+    for (int c = 0; c < C; ++c) {
+        double dot = 0.0;
+        for (int s = 0; s < slices; ++s) dot += part[((int64_t)s * nb + n) * C + c];
+        const double nn = nrm[c];
+        const double cs = nn == 0.0 ? 0.0 : dot / (sqrt(nn) * root_d);
+        if (c == 0 || cs > best) {
+            best = cs;
+            pred = c;
+        }
+        if (cos_out) cos_out[n * C + c] = (float)cs;
+    }
+    pred_out[n] = pred;
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 template <typename T>
 static int grow(T **p, size_t *have, size_t want) {
@@ -481,28 +532,70 @@ static int launch_bwd(hdc_ctx_impl *c, int64_t ld, int64_t nb, float *acc, int G
     return HDC_OK;
 }
 
+// Shape of the forward launch for C classes and D dimensions.
+struct FwdShape {
+    bool wide;     // 4 classes x 8 groups per wave instead of 2 x 16
+    int slices, chunks, ns;
+};
+static FwdShape fwd_shape(int C, int G) {
+    FwdShape f;
+    // whichever wastes fewer class slots (relative cost per class slot and 16 groups: 71 : 62
+    // issue slots at 2 : 4 classes)
+    f.wide = ((C + 3) / 4) * 125 < ((C + 1) / 2) * 71;
+    const int cc = f.wide ? 4 : 2, groups = f.wide ? 8 : 16;
+    f.slices = (G + groups - 1) / groups;
+    f.chunks = (C + cc - 1) / cc;
+    f.ns = kFwdVals / cc;
+    return f;
+}
+
+// Most samples one forward launch takes: bounds the partial-dot-product scratch to 256 MB.
+static int64_t fwd_sub_batch(const FwdShape &f, int C, int64_t limit) {
+    int64_t sb = (int64_t)(256u << 20) / ((int64_t)f.slices * C * (int64_t)sizeof(double));
+    if (sb > 8192) sb = 8192;
+    if (sb < 64) sb = 64;
+    return sb > limit ? limit : sb;
+}
+
+static int launch_fwd(hdc_ctx_impl *c, const FwdShape &f, const uint32_t *rows, int64_t nb, const float *acc,
+                      hipStream_t s) {
+    // about four waves per SIMD when there is that much work; whole trips per wave
+    int64_t spw = (nb * f.slices * f.chunks + 4095) / 4096;
+    spw = (spw + f.ns - 1) / f.ns * f.ns;
+    if (spw > 64) spw = 64;
+    const int64_t tiles = (nb + kFwdWaves * spw - 1) / (kFwdWaves * spw);
+    const dim3 grid((unsigned)f.slices, (unsigned)f.chunks, (unsigned)tiles);
+    ProfScope prof(c, HDC_K_ONLINE_FWD, s);
+    if (f.wide)
+        hipLaunchKernelGGL((online_fwd_kernel<4, 8>), grid, dim3(kFwdWaves * kWave), 0, s, rows, nb, acc, c->p.D,
+                           c->W, c->p.C, (int)spw, c->ob_part_d);
+    else
+        hipLaunchKernelGGL((online_fwd_kernel<2, 16>), grid, dim3(kFwdWaves * kWave), 0, s, rows, nb, acc, c->p.D,
+                           c->W, c->p.C, (int)spw, c->ob_part_d);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
+static int launch_norm(hdc_ctx_impl *c, const float *acc, int G, hipStream_t s) {
+    hipLaunchKernelGGL(online_norm_kernel, dim3((unsigned)G, (unsigned)((c->p.C + 3) / 4)), dim3(256), 0, s, acc,
+                       c->p.D, c->p.C, G, c->ob_norm_d);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                                 int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s) {
     const int C = c->p.C, D = c->p.D, W = c->W;
     const int G = (D + kWave - 1) / kWave;
-    // forward shape: 2 classes x 16 groups or 4 classes x 8 groups per wave, whichever wastes
-    // fewer class slots (relative cost per class slot and 16 groups: 71 : 62 issue slots / 2 : 4)
-    const bool wide = ((C + 3) / 4) * 125 < ((C + 1) / 2) * 71;
-    const int fwd_cc = wide ? 4 : 2, fwd_groups = wide ? 8 : 16;
-    const int slices = (G + fwd_groups - 1) / fwd_groups;
-    const int chunks = (C + fwd_cc - 1) / fwd_cc;
-    const int fwd_ns = kFwdVals / fwd_cc;
+    const FwdShape f = fwd_shape(C, G);
     if (batch > N) batch = N;
 
     // A batch is worked off in pieces of at most `sb` samples (forward, weights, backward each);
-    // sb bounds the scratch: partial dot products (<= 256 MB) and transposed masks.
-    int64_t sb = (int64_t)(256u << 20) / ((int64_t)slices * C * (int64_t)sizeof(double));
-    if (sb > 8192) sb = 8192;
-    if (sb < 64) sb = 64;
-    if (sb > batch) sb = batch;
+    // sb bounds the scratch: partial dot products and transposed masks.
+    const int64_t sb = fwd_sub_batch(f, C, batch);
     const int64_t ld = (sb + kTileSamples - 1) / kTileSamples * kTileSamples;
     HDC_HIP(hipSetDevice(c->device));
-    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)slices * sb * C * sizeof(double));
+    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)f.slices * sb * C * sizeof(double));
     if (rc == HDC_OK) rc = grow(&c->ob_wts_d, &c->ob_wts_bytes, (size_t)ld * sizeof(OnlineWeight));
     if (rc == HDC_OK) rc = grow(&c->ob_col_d, &c->ob_col_bytes, (size_t)G * ld * sizeof(uint64_t));
     const int cb = bwd_dense_width(C);
@@ -523,8 +616,7 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
         c->ob_attr_set = true;
     }
 
-    // squared norms of the rows as handed in: a backward step over no samples
-    rc = launch_bwd(c, ld, 0, acc, G, true, true, s);
+    rc = launch_norm(c, acc, G, s);   // squared norms of the rows as handed in
     if (rc != HDC_OK) return rc;
     const double root_d = sqrt((double)D);
     const int ttiles = (G + kTileGroups - 1) / kTileGroups;
@@ -534,27 +626,13 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
             for (int64_t s0 = 0; s0 < B; s0 += sb) {
                 const int64_t nb = s0 + sb < B ? sb : B - s0;
                 const uint32_t *rows = hv + (b0 + s0) * W;
-                // about four waves per SIMD when there is that much work; whole trips per wave
-                int64_t spw = (nb * slices * chunks + 4095) / 4096;
-                spw = (spw + fwd_ns - 1) / fwd_ns * fwd_ns;
-                if (spw > 64) spw = 64;
-                const int64_t tiles = (nb + kFwdWaves * spw - 1) / (kFwdWaves * spw);
-                const dim3 grid((unsigned)slices, (unsigned)chunks, (unsigned)tiles);
-                {
-                    ProfScope prof(c, HDC_K_ONLINE_FWD, s);
-                    if (wide)
-                        hipLaunchKernelGGL((online_fwd_kernel<4, 8>), grid, dim3(kFwdWaves * kWave), 0, s, rows,
-                                           nb, acc, D, W, C, (int)spw, c->ob_part_d);
-                    else
-                        hipLaunchKernelGGL((online_fwd_kernel<2, 16>), grid, dim3(kFwdWaves * kWave), 0, s, rows,
-                                           nb, acc, D, W, C, (int)spw, c->ob_part_d);
-                }
-                HDC_HIP(hipGetLastError());
+                rc = launch_fwd(c, f, rows, nb, acc, s);
+                if (rc != HDC_OK) return rc;
                 const int64_t ld_used = (nb + kTileSamples - 1) / kTileSamples * kTileSamples;
                 const int wblocks = (int)((ld_used + 255) / 256);
                 const int tblocks = (int)(ld_used / kTileSamples) * ttiles;
                 hipLaunchKernelGGL(online_weights_kernel, dim3((unsigned)(wblocks + tblocks)), dim3(256),
-                                   (size_t)C * sizeof(double), s, c->ob_part_d, slices, nb, labels + b0 + s0,
+                                   (size_t)C * sizeof(double), s, c->ob_part_d, f.slices, nb, labels + b0 + s0,
                                    c->ob_norm_d, G, C, root_d, lr, static_cast<OnlineWeight *>(c->ob_wts_d),
                                    cb ? c->ob_coef_d : nullptr, cb, wblocks, rows, W, c->ob_col_d, ld_used);
                 HDC_HIP(hipGetLastError());
@@ -562,6 +640,31 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
                 if (rc != HDC_OK) return rc;
             }
         }
+    return HDC_OK;
+}
+
+int launch_search_cosine(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const float *acc, float *cos_out,
+                         int32_t *pred, hipStream_t s) {
+    const int C = c->p.C, D = c->p.D, W = c->W;
+    const int G = (D + kWave - 1) / kWave;
+    const FwdShape f = fwd_shape(C, G);
+    const int64_t sb = fwd_sub_batch(f, C, N);
+    HDC_HIP(hipSetDevice(c->device));
+    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)f.slices * sb * C * sizeof(double));
+    if (rc == HDC_OK) rc = grow(&c->ob_norm_d, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
+    if (rc != HDC_OK) return rc;
+    rc = launch_norm(c, acc, G, s);
+    if (rc != HDC_OK) return rc;
+    const double root_d = sqrt((double)D);
+    for (int64_t n0 = 0; n0 < N; n0 += sb) {
+        const int64_t nb = n0 + sb < N ? sb : N - n0;
+        rc = launch_fwd(c, f, hv + n0 * W, nb, acc, s);
+        if (rc != HDC_OK) return rc;
+        hipLaunchKernelGGL(cosine_finish_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256),
+                           (size_t)C * sizeof(double), s, c->ob_part_d, f.slices, nb, c->ob_norm_d, G, C, root_d,
+                           cos_out ? cos_out + n0 * C : nullptr, pred + n0);
+        HDC_HIP(hipGetLastError());
+    }
     return HDC_OK;
 }
 
