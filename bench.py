@@ -249,6 +249,24 @@ def extras(torch, binding, make_workload):
     res["train_classical_1M_C2"] = {"ms": round(ms, 4), "samples_per_s": round(N / ms * 1e3, 0),
                                     "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),
                                     "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    # the stand-alone primitives of Sec. IV-B on the same 1M rows (all HBM-bound streams)
+    nbits = 1 << 17                     # the byte matrix is 8x the packed one: 128k rows = 1.3 GB
+    bits = torch.empty((nbits, wl5.D), dtype=torch.uint8, device=dev)
+    hsum = torch.empty(N, dtype=torch.int32, device=dev)
+    vsum = torch.empty(wl5.D, dtype=torch.int32, device=dev)
+    ms = _timed(torch, lambda: ctx.hdc_unpack(hv[:nbits], bits), 5)
+    b = nbits * (ctx.W * 4 + wl5.D)
+    res["unpack_128k"] = {"ms": round(ms, 4), "GBs": round(b / ms / 1e6, 1), "frac_hbm": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    hv5p = torch.empty((nbits, ctx.W), dtype=torch.int32, device=dev)
+    ms = _timed(torch, lambda: ctx.hdc_pack(bits, hv5p), 5)
+    res["pack_128k"] = {"ms": round(ms, 4), "GBs": round(b / ms / 1e6, 1), "frac_hbm": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    ms = _timed(torch, lambda: ctx.hdc_hsum(hv, hsum), 5)
+    res["hsum_1M"] = {"ms": round(ms, 4), "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),
+                      "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    ms = _timed(torch, lambda: ctx.hdc_vsum(hv, vsum), 5)
+    res["vsum_1M"] = {"ms": round(ms, 4), "GBs": round(bytes_rows / ms / 1e6, 1),
+                      "frac_hbm": round(bytes_rows / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    del bits, hv5p, hsum, vsum
     x5, _ = wl5.train(65536)
     x5d = torch.from_numpy(x5).to(dev)
     hv5 = torch.empty((65536, ctx.W), dtype=torch.int32, device=dev)
@@ -298,6 +316,12 @@ def extras(torch, binding, make_workload):
             entry["bwd_frac_fp64_valu"] = round(2.0 * n * cb * wl4.D / (b_ms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS, 4)
         sweep[str(batch)] = entry
     res["train_online_batched_cfg4_1epoch"] = sweep
+    # cosine-similarity inference of the train set against the trained accumulators
+    pred4 = torch.empty(x4.shape[0], dtype=torch.int32, device=dev)
+    ms = _timed(torch, lambda: ctx.hdc_search_cosine(hv4, acc4, pred4, None), 5)
+    res["search_cosine_cfg4"] = {"ms": round(ms, 4), "queries_per_s": round(x4.shape[0] / ms * 1e3, 0),
+                                 "frac_fp64_valu": round(2.0 * x4.shape[0] * wl4.C * wl4.D / (ms * 1e-3) / 1e12
+                                                         / FP64_PEAK_TFLOPS, 4)}
     ctx.close()
     del hv4, x4d
 

@@ -75,19 +75,33 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict_
     }
 }
 
-// Horizontal sum: one wave per row, lanes stride over the words, v_bcnt accumulates.
+// Horizontal sum: a wave takes kHsumRows consecutive rows at a time, lanes stride over the words
+// of all of them together (kHsumRows independent loads per step, several steps unrolled, so a
+// lane has a dozen loads in flight), v_bcnt accumulates per row, one butterfly per row at the end.
 constexpr int kHsumWaves = 4;
+constexpr int kHsumRows = 4;
 __global__ __launch_bounds__(kHsumWaves *kWave) void hsum_kernel(const uint32_t *__restrict__ hv, int64_t N,
                                                                   int W, int32_t *__restrict__ out) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t n = (int64_t)blockIdx.x * kHsumWaves + (threadIdx.x >> 6);
-    if (n >= N) return;
-    const uint32_t *row = hv + n * W;
-    uint32_t s = 0;
-    for (int w = lane; w < W; w += kWave) s += __popc(row[w]);
+    const int64_t n0 = ((int64_t)blockIdx.x * kHsumWaves + (threadIdx.x >> 6)) * kHsumRows;
+    if (n0 >= N) return;
+    const uint32_t *row[kHsumRows];
+    uint32_t s[kHsumRows];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
-    if (lane == 0) out[n] = (int32_t)s;
+    for (int r = 0; r < kHsumRows; ++r) {
+        row[r] = hv + (n0 + r < N ? n0 + r : N - 1) * W;   // surplus rows repeat the last one, unused
+        s[r] = 0;
+    }
+#pragma unroll 4
+    for (int w = lane; w < W; w += kWave)
+#pragma unroll
+        for (int r = 0; r < kHsumRows; ++r) s[r] += __popc(row[r][w]);
+#pragma unroll
+    for (int r = 0; r < kHsumRows; ++r) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s[r] += __shfl_xor(s[r], off, kWave);
+        if (lane == 0 && n0 + r < N) out[n0 + r] = (int32_t)s[r];
+    }
 }
 
 static inline bool vec_ok(const void *p, int D) {
@@ -117,7 +131,8 @@ int launch_unpack(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, uint8_t *bits,
 }
 
 int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s) {
-    hipLaunchKernelGGL(hsum_kernel, dim3((unsigned)((N + kHsumWaves - 1) / kHsumWaves)), dim3(kHsumWaves * kWave), 0,
+    hipLaunchKernelGGL(hsum_kernel, dim3((unsigned)((N + kHsumWaves * kHsumRows - 1) / (kHsumWaves * kHsumRows))),
+                       dim3(kHsumWaves * kWave), 0,
                        s, hv, N, c->W, out);
     HDC_HIP(hipGetLastError());
     return HDC_OK;
