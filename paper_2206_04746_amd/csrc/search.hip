@@ -119,9 +119,105 @@ __global__ __launch_bounds__(kSearchWaves * kWave) void search_kernel(
     }
 }
 
+// Few queries: the kernel above would fill only a fraction of the chip (one tile of kRows rows per
+// wave, every block first staging all class vectors in LDS).  Here a block takes ONE tile and
+// its kSearchWaves waves split the classes between them, reading the class words straight from
+// global memory (the class vectors are a few tens of KB: cache hits after the first blocks).
+// The arithmetic and the reduction inside a wave are those of search_kernel; the waves' best keys
+// meet in LDS.
+template <int WPL>
+__global__ __launch_bounds__(kSearchWaves * kWave) void search_few_kernel(
+    const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W,
+    uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
+    __shared__ uint32_t xch_all[kSearchWaves * kXchWords];
+    __shared__ uint32_t keys[kSearchWaves][kRows];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t *xch = xch_all + wave * kXchWords;
+    const int r_of = lane / kGroup, g_of = lane % kGroup;
+    const int64_t n0 = (int64_t)blockIdx.x * kRows;
+    // this wave's classes: a contiguous share
+    const int per = (C + kSearchWaves - 1) / kSearchWaves;
+    const int c_lo = min(wave * per, C), c_hi = min(c_lo + per, C);
+
+    uint32_t x[kRows][WPL];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const int64_t n = (n0 + r < N) ? n0 + r : N - 1;
+        const uint32_t *row = hv + n * W;
+#pragma unroll
+        for (int j = 0; j < WPL; ++j) {
+            const int w = lane + j * kWave;
+            x[r][j] = w < W ? row[w] : 0u;
+        }
+    }
+    uint32_t best_key = 0xffffffffu;
+    for (int c0 = c_lo; c0 < c_hi; c0 += kGroup) {
+        const int gcount = min(kGroup, c_hi - c0);
+        for (int g = 0; g < gcount; ++g) {
+            const uint32_t *m = class_hv + (int64_t)(c0 + g) * W;
+            uint32_t part[kRows];
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) part[r] = 0;
+#pragma unroll
+            for (int j = 0; j < WPL; ++j) {
+                const int w = lane + j * kWave;
+                const uint32_t mw = w < W ? m[w] : 0u;
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) part[r] += __popc(x[r][j] ^ mw);
+            }
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                uint32_t v = part[r];
+                v += quad_xor1(v);
+                v += quad_xor2(v);
+                if ((lane & 3) == 0) xch[(r * kGroup + g) * kXchStride + (lane >> 2)] = v;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t total = 0;
+        if (g_of < gcount) {
+            const uint32_t *src = xch + lane * kXchStride;
+#pragma unroll
+            for (int l = 0; l < kWave / 4; ++l) total += src[l];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int cidx = c0 + g_of;
+        const int64_t n = n0 + r_of;
+        if (g_of < gcount && n < N) {
+            if (dist) dist[n * C + cidx] = total;
+            best_key = min(best_key, (total << 10) | (uint32_t)cidx);
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft < kGroup; sft <<= 1)
+        best_key = min(best_key, (uint32_t)__shfl_xor((int)best_key, sft, kWave));
+    if (g_of == 0) keys[wave][r_of] = best_key;   // 0xffffffff from a wave without classes
+    __syncthreads();
+    if (threadIdx.x < kRows && n0 + threadIdx.x < N) {
+        uint32_t k = keys[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kSearchWaves; ++w) k = min(k, keys[w][threadIdx.x]);
+        pred[n0 + threadIdx.x] = (int32_t)(k & 1023u);
+    }
+}
+
+constexpr int64_t kFewQueries = 8192;   // below this the one-tile-per-block kernel is used
+
 template <int WPL>
 static int launch_search_wpl(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                              uint32_t *dist, int32_t *pred, hipStream_t s) {
+    if (N < kFewQueries) {
+        ProfScope prof(c, HDC_K_SEARCH, s);
+        hipLaunchKernelGGL(search_few_kernel<WPL>, dim3((unsigned)((N + kRows - 1) / kRows)),
+                           dim3(kSearchWaves * kWave), 0, s, hv, N, class_hv, c->p.C, c->W, dist, pred);
+        HDC_HIP(hipGetLastError());
+        return HDC_OK;
+    }
     const size_t lds = ((size_t)c->p.C * WPL * kWave + (size_t)kSearchWaves * kXchWords) * 4;
     if (lds > 160 * 1024) return HDC_ELIMIT;
     auto kern = search_kernel<WPL>;
