@@ -52,25 +52,33 @@ __global__ __launch_bounds__(64) void quantize_kernel(const void *__restrict__ f
             }
     }
     const int64_t r0 = (int64_t)blockIdx.y * kQuantRows;
+    // All loads first, with clamped indices (a value loaded for a row or feature that does not
+    // exist is dropped below): nothing conditional stands between the 4 * kQuantRows loads, so
+    // they are all in flight together.
+    float xf[kQuantRows][4];
+    uint32_t xb[kQuantRows][4];
 #pragma unroll
     for (int r = 0; r < kQuantRows; ++r) {
-        const int64_t n = r0 + r;
-        if (n >= N) break;
+        const int64_t n = r0 + r < N ? r0 + r : N - 1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int f = f0 + k < F ? f0 + k : F - 1;
+            if (kU8)
+                xb[r][k] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
+            else
+                xf[r][k] = reinterpret_cast<const float *>(feats)[n * F + f];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kQuantRows; ++r) {
         uint32_t packed[2] = {0u, 0u};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int f = f0 + k;
-            uint32_t b = 0;
-            if (f < F) {
-                if (kU8) {
-                    b = ((uint32_t) reinterpret_cast<const uint8_t *>(feats)[n * F + f] * (uint32_t)L) >> 8;
-                } else {
-                    b = bin_f32(reinterpret_cast<const float *>(feats)[n * F + f], lo4[k], sc4[k], L);
-                }
-            }
+            uint32_t b = kU8 ? (xb[r][k] * (uint32_t)L) >> 8 : bin_f32(xf[r][k], lo4[k], sc4[k], L);
+            if (f0 + k >= F) b = 0;
             packed[k >> 1] |= (b * (kSliceWords * 4u)) << (16 * (k & 1));
         }
-        q4[n * groups + g] = make_uint2(packed[0], packed[1]);
+        if (r0 + r < N) q4[(r0 + r) * groups + g] = make_uint2(packed[0], packed[1]);
     }
 }
 

@@ -59,6 +59,8 @@ struct hdc_ctx_impl {
     size_t ob_col_bytes;
     double *ob_carry_d;   // [C][D] batch sum carried between the launches of a long batch
     size_t ob_carry_bytes;
+    double *ob_share_d;   // [shares][C][D] sums of the blocks that share one group's samples
+    size_t ob_share_bytes;
     double *ob_norm_d;    // [C][ceil(D/64)] squared-norm partials of the class rows
     size_t ob_norm_bytes;
     bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised

@@ -205,23 +205,70 @@ __global__ __launch_bounds__(kFwdWaves *kWave) void online_fwd_kernel(
         walk(std::integral_constant<int, 0>{});
 }
 
+// ---- finishing the dot products: cosines and their argmax --------------------------------------
+// Threads work in groups of `cp` lanes (a power of two <= 64, >= C when C <= 64) per sample;
+// lane lc of a group takes classes lc, lc + cp, ...  For each it adds the slice partials in
+// ascending slice order (independent loads), forms cos = dot / (|row| sqrt(D)) (0 for a zero
+// row), optionally stores it, and keeps its best; a butterfly over the group then leaves in every
+// lane the largest cosine and the lowest class that has it.  *cos_y receives cos of class y
+// (summed over the group: exactly one lane holds it).
+__device__ __forceinline__ void finish_cosines(const double *__restrict__ part, int slices, int64_t nb, int64_t n,
+                                               bool live, int C, const double *nrm, double root_d, int cp, int lc,
+                                               int y, float *cos_out, double *best_out, int *pred_out,
+                                               double *cos_y) {
+    double best = -2.0, cy = 0.0;   // cosines lie in [-1, 1]
+    int pred = 0x7fffffff;
+    if (live)
+        for (int c = lc; c < C; c += cp) {
+            double dot = 0.0;
+            for (int s = 0; s < slices; ++s) dot += part[((int64_t)s * nb + n) * C + c];
+            const double nn = nrm[c];
+            const double cs = nn == 0.0 ? 0.0 : dot / (sqrt(nn) * root_d);
+            if (cos_out) cos_out[n * C + c] = (float)cs;
+            if (cs > best) {   // classes ascend within a lane: the first of equals stays
+                best = cs;
+                pred = c;
+            }
+            if (c == y) cy = cs;
+        }
+    for (int off = cp >> 1; off > 0; off >>= 1) {
+        const double ob = __shfl_xor(best, off, kWave);
+        const int op = __shfl_xor(pred, off, kWave);
+        cy += __shfl_xor(cy, off, kWave);
+        if (ob > best || (ob == best && op < pred)) {
+            best = ob;
+            pred = op;
+        }
+    }
+    *best_out = best;
+    *pred_out = pred;
+    *cos_y = cy;
+}
+
+// lanes per sample for C classes
+static int cosine_group(int C) {
+    int cp = 1;
+    while (cp < C && cp < kWave) cp <<= 1;
+    return cp;
+}
+
 // ---- weights (and the transposed sample bits for the backward step) -----------------------------
-// Blocks [0, wblocks): one thread per sample finishes the dot products (slices in ascending
-// order), cosines against the frozen rows, prediction (lowest class among equals) and the two
+// Blocks [0, wblocks): cp lanes per sample finish the dot products (finish_cosines), cosines
+// against the frozen rows, prediction (lowest class among equals) and the two
 // weights, as a record per sample and, for few classes, also as a dense row of signed fp64
 // coefficients (+w_y at y, -w_p at a wrong prediction, 0 elsewhere).  Blocks from wblocks on do an unrelated job that needs no launch of its own: each
-// turns a tile of 64 samples x 32 words of hv into colmask[g][n], the 64-bit lane mask of
-// dimension group g of sample n, so that the backward step, which works on one group of all
-// samples, reads its masks contiguously (8 samples per 64-byte scalar load) instead of 8 bytes
-// out of every 4 W-byte row.
+// turns a tile of 64 samples x 32 words of hv into colmask, the 64-bit lane mask of dimension
+// group g of sample n stored group-major (or gw adjacent groups interleaved per sample), so
+// that the backward step, which works on one or a few groups of all samples, reads its masks
+// contiguously instead of 8 bytes out of every 4 W-byte row.
 constexpr int kTileSamples = 64;
 constexpr int kTileGroups = 16;
 
 __global__ __launch_bounds__(256) void online_weights_kernel(
     const double *__restrict__ part, int slices, int64_t nb, const int32_t *__restrict__ labels,
     const double *__restrict__ normpart, int G, int C, double root_d, float lr,
-    OnlineWeight *__restrict__ out, double *__restrict__ coef, int CB, int wblocks,
-    const uint32_t *__restrict__ hv, int W, uint64_t *__restrict__ colmask, int64_t ld) {
+    OnlineWeight *__restrict__ out, double *__restrict__ coef, int CB, int cp, int wblocks,
+    const uint32_t *__restrict__ hv, int W, uint64_t *__restrict__ colmask, int64_t ld, int gw) {
     extern __shared__ double nrm[];   // [C] squared norms of the frozen rows
     __shared__ uint32_t tile[kTileSamples][2 * kTileGroups + 1];
     const int t = threadIdx.x;
@@ -239,8 +286,9 @@ __global__ __launch_bounds__(256) void online_weights_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int gg = (t >> 6) + 4 * i, sm = t & 63;
-            if (g0 + gg < G)
-                colmask[(int64_t)(g0 + gg) * ld + ns + sm] =
+            const int g = g0 + gg;
+            if (g < G)   // layout [g / gw][n][g % gw]: gw = 1 is group-major, gw > 1 interleaves gw groups
+                colmask[((int64_t)(g / gw) * ld + ns + sm) * gw + g % gw] =
                     (uint64_t)tile[sm][2 * gg] | ((uint64_t)tile[sm][2 * gg + 1] << 32);
         }
         return;
@@ -253,41 +301,24 @@ __global__ __launch_bounds__(256) void online_weights_kernel(
         if ((t & 63) == 0) nrm[c] = s;
     }
     __syncthreads();
-    const int64_t n = (int64_t)blockIdx.x * blockDim.x + t;
-    if (n >= nb) {   // rows up to the padded length: zero coefficients, so that they add nothing
-        if (coef && n < ld)
-            for (int j = 0; j < CB; ++j) coef[n * CB + j] = 0.0;
-        return;
-    }
-    const int y = labels[n];
+    const int spb = 256 / cp, lc = t % cp;
+    const int64_t n = (int64_t)blockIdx.x * spb + t / cp;
+    const bool inside = n < nb;
+    const int y = inside ? labels[n] : -1;
+    const bool live = inside && y >= 0 && y < C;
+    double best, cos_y;
+    int pred;
+    finish_cosines(part, slices, nb, n, live, C, nrm, root_d, cp, lc, y, nullptr, &best, &pred, &cos_y);
     OnlineWeight r;
-    r.y = -1;
-    r.pred = -1;
-    r.w_y = 0.0f;
-    r.w_p = 0.0f;
-    if (y >= 0 && y < C) {
-        double best = 0.0, cos_y = 0.0;
-        int pred = 0;
-        for (int c = 0; c < C; ++c) {
-            double dot = 0.0;
-            for (int s = 0; s < slices; ++s) dot += part[((int64_t)s * nb + n) * C + c];
-            const double nn = nrm[c];
-            const double cs = nn == 0.0 ? 0.0 : dot / (sqrt(nn) * root_d);
-            if (c == 0 || cs > best) {
-                best = cs;
-                pred = c;
-            }
-            if (c == y) cos_y = cs;
-        }
-        r.y = y;
-        r.pred = pred != y ? pred : -1;
-        r.w_y = (float)(1.0 - cos_y);
-        r.w_p = (float)((double)lr * (1.0 - best));
-    }
-    out[n] = r;
-    // the same two weights as a dense row of CB signed fp64 coefficients (small C only)
-    if (coef)
-        for (int j = 0; j < CB; ++j)
+    r.y = live ? y : -1;
+    r.pred = (live && pred != y) ? pred : -1;
+    r.w_y = live ? (float)(1.0 - cos_y) : 0.0f;
+    r.w_p = live ? (float)((double)lr * (1.0 - best)) : 0.0f;
+    if (inside && lc == 0) out[n] = r;
+    // the same two weights as a dense row of CB signed fp64 coefficients (small C only; CB <= cp
+    // or the lanes loop); rows from nb up to the padded length are zero, so that they add nothing
+    if (coef && n < ld)
+        for (int j = lc; j < CB; j += cp)
             coef[n * CB + j] = j == r.y ? (double)r.w_y : j == r.pred ? -(double)r.w_p : 0.0;
 }
 
@@ -313,19 +344,28 @@ template <int CB>
 __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
     const uint64_t *__restrict__ colmask, int64_t ld, const OnlineWeight *__restrict__ wts,
     const double *__restrict__ coef, int64_t nb, float *acc, int D, int c_lo, int c_n, int G,
-    double *carry, int first, int last, double *__restrict__ normpart) {
+    double *carry, int first, int last, double *__restrict__ normpart, int gpb, int64_t bs,
+    double *__restrict__ partial, int c_all) {
     extern __shared__ double rows[];   // [waves][c_n][64]
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;
-    const int g = blockIdx.x;
+    // wave = (run, group): the block covers gpb adjacent groups and nw / gpb runs of samples.
+    // Waves of one run read the same coefficient rows (one fetch into the CU's scalar cache).
+    const int runs = nw / gpb;
+    const int gi = wave % gpb, run = wave / gpb;
+    const int g = blockIdx.x * gpb + gi;
     double *mine = rows + (int64_t)wave * c_n * kWave;
 
-    // runs are whole trips, so that a trip's 8 masks are one aligned 64-byte load
-    const int64_t per = ((nb + nw - 1) / nw + kBwdUnroll - 1) / kBwdUnroll * kBwdUnroll;
-    const int64_t n0 = wave * per;
-    const int64_t n1 = n0 + per < nb ? n0 + per : nb;
-    kptr_u64 col = (kptr_u64)(colmask + (int64_t)g * ld);
+    // the block's samples [b_lo, b_hi), split into runs of whole trips, so that a trip's 8
+    // masks are one aligned 64-byte load (bs is a multiple of 8)
+    const int64_t b_lo = (int64_t)blockIdx.y * bs;
+    const int64_t b_hi = b_lo + bs < nb ? b_lo + bs : nb;
+    const int64_t span = b_hi > b_lo ? b_hi - b_lo : 0;
+    const int64_t per = ((span + runs - 1) / runs + kBwdUnroll - 1) / kBwdUnroll * kBwdUnroll;
+    const int64_t n0 = b_lo + run * per;
+    const int64_t n1 = g >= G ? n0 : (n0 + per < b_hi ? n0 + per : b_hi);   // a group past the last: no samples
+    kptr_u64 col = (kptr_u64)(colmask + (int64_t)(g < G ? g : G - 1) * ld);
     // All buffers are readable up to the next multiple of 64 samples; entries past nb are
     // ignored.
     if constexpr (CB > 0) {
@@ -413,11 +453,18 @@ __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
     }
     __syncthreads();
 
-    const int d = g * kWave + lane;
-    for (int c = wave; c < c_n; c += nw) {
+    // (class, group) pairs of the block, dealt to the waves; runs are added in run order
+    for (int idx = wave; idx < c_n * gpb; idx += nw) {
+        const int c = idx / gpb, g2 = blockIdx.x * gpb + idx % gpb;
+        if (g2 >= G) continue;
+        const int d = g2 * kWave + lane;
         const int64_t at = (int64_t)(c_lo + c) * D + d;
-        double s = (!first && d < D) ? carry[at] : 0.0;
-        for (int w = 0; w < nw; ++w) s += rows[((int64_t)w * c_n + c) * kWave + lane];
+        double s = (!partial && !first && d < D) ? carry[at] : 0.0;
+        for (int r = 0; r < runs; ++r) s += rows[((int64_t)(r * gpb + idx % gpb) * c_n + c) * kWave + lane];
+        if (partial) {   // this block's share of the batch sum; online_apply_kernel does the rest
+            if (d < D) partial[((int64_t)blockIdx.y * c_all + c_lo + c) * D + d] = s;
+            continue;
+        }
         if (!last) {
             if (d < D) carry[at] = s;
             continue;
@@ -429,8 +476,115 @@ __global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_kernel(
             q = (double)nv * (double)nv;
         }
         q = wave_sum_f64(q);
-        if (lane == 0) normpart[(int64_t)(c_lo + c) * G + g] = q;
+        if (lane == 0) normpart[(int64_t)(c_lo + c) * G + g2] = q;
     }
+}
+
+// Backward sums for many samples (the split path): a wave owns GW adjacent groups (64 GW
+// dimensions) for its run of samples, so every coefficient that arrives through the scalar
+// cache - which delivers only about a dword per clock to a CU - feeds GW FMAs per lane instead
+// of one.  Block = 16 runs of one group column; grid (columns, shares).  Per sample: one scalar
+// load of CB coefficients, one of GW masks (colmask interleaved by GW), GW v_cndmask + CB * GW
+// FMAs; the next sample's operands are in flight meanwhile.  The 16 runs are then added in run
+// order through LDS, class by class, into this block's share of the batch sum.
+template <int CB, int GW>
+__global__ __launch_bounds__(kBwdMaxWaves *kWave) void online_bwd_wide_kernel(
+    const uint64_t *__restrict__ colmask, int64_t ld, const double *__restrict__ coef, int64_t nb, int D, int C,
+    int64_t bs, double *__restrict__ partial) {
+    __shared__ double buf[kBwdMaxWaves][GW * kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int run = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int colx = blockIdx.x;
+    const int64_t b_lo = (int64_t)blockIdx.y * bs;
+    const int64_t b_hi = b_lo + bs < nb ? b_lo + bs : nb;
+    const int64_t span = b_hi > b_lo ? b_hi - b_lo : 0;
+    const int64_t per = (span + kBwdMaxWaves - 1) / kBwdMaxWaves;
+    const int64_t n0 = b_lo + run * per;
+    const int64_t n1 = n0 + per < b_hi ? n0 + per : b_hi;
+    kptr_u64 col = (kptr_u64)(colmask + (int64_t)colx * ld * GW);
+    kptr_f64 cf = (kptr_f64)coef;
+
+    double delta[CB][GW];
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+        for (int i = 0; i < GW; ++i) delta[j][i] = 0.0;
+    auto fetch = [&](int64_t n, uint64_t(&m)[GW], double(&k)[CB]) {
+#pragma unroll
+        for (int i = 0; i < GW; ++i) m[i] = col[n * GW + i];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) k[j] = cf[n * CB + j];
+    };
+    uint64_t mn[GW];
+    double kn[CB];
+    if (n0 < n1) fetch(n0, mn, kn);
+    for (int64_t n = n0; n < n1; ++n) {
+        uint64_t mc[GW];
+        double kc[CB];
+        wait_scalar_loads();
+#pragma unroll
+        for (int i = 0; i < GW; ++i) mc[i] = mn[i];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) kc[j] = kn[j];
+        fetch(n + 1 < n1 ? n + 1 : n0, mn, kn);   // past the run: its start again (in bounds, unused)
+        pin_schedule();
+#pragma unroll
+        for (int i = 0; i < GW; ++i) {
+            const double sgn = lane_sign(mc[i]);
+#pragma unroll
+            for (int j = 0; j < CB; ++j) delta[j][i] = fma(kc[j], sgn, delta[j][i]);
+        }
+        pin_schedule();   // the register copies of the loop-carried operands stay below the arithmetic
+    }
+    // runs -> block sum, one class at a time through the LDS tile
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        if (j < C) {   // uniform over the block
+#pragma unroll
+            for (int i = 0; i < GW; ++i) buf[run][i * kWave + lane] = delta[j][i];
+            __syncthreads();
+            if (t < GW * kWave) {
+                double sum = 0.0;
+#pragma unroll
+                for (int r = 0; r < kBwdMaxWaves; ++r) sum += buf[r][t];
+                const int d = colx * GW * kWave + t;
+                if (d < D) partial[((int64_t)blockIdx.y * C + j) * D + d] = sum;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Second half of a backward step whose samples were split over several blocks per group:
+// delta = the blocks' shares in block order (plus the carry of earlier launches of the same
+// batch), then the update and the norm partials exactly as in online_bwd_kernel.
+// grid (G, ceil(C / 4)), one wave per (class, group).
+__global__ __launch_bounds__(256) void online_apply_kernel(const double *__restrict__ partial, int shares,
+                                                           float *acc, int D, int C, int G, double *carry,
+                                                           int first, int last, double *__restrict__ normpart) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int c = blockIdx.y * 4 + (threadIdx.x >> 6), g = blockIdx.x;
+    if (c >= C) return;
+    const int d = g * kWave + lane;
+    const int64_t at = (int64_t)c * D + d;
+    double s = 0.0;
+    if (d < D) {
+        if (!first) s = carry[at];
+        for (int y = 0; y < shares; ++y) s += partial[((int64_t)y * C + c) * D + d];
+    }
+    if (!last) {
+        if (d < D) carry[at] = s;
+        return;
+    }
+    double q = 0.0;
+    if (d < D) {
+        const float nv = (float)((double)acc[at] + s);
+        acc[at] = nv;
+        q = (double)nv * (double)nv;
+    }
+    q = wave_sum_f64(q);
+    if (lane == 0) normpart[(int64_t)c * G + g] = q;
 }
 
 // ---- squared norms of given rows, and cosine inference ---------------------------------------
@@ -451,12 +605,12 @@ __global__ __launch_bounds__(256) void online_norm_kernel(const float *__restric
     if (lane == 0) normpart[(int64_t)c * G + g] = q;
 }
 
-// Cosine-similarity inference (Sec. III): one thread per sample finishes the dot products of
-// the forward step into cosines; cos_out [nb][C] fp32 (optional), pred = lowest class with the
+// Cosine-similarity inference (Sec. III): cp lanes per sample finish the dot products of
+// the forward step into cosines (finish_cosines); cos_out [nb][C] fp32 (optional), pred = lowest class with the
 // largest cosine (compared in fp64).
 __global__ __launch_bounds__(256) void cosine_finish_kernel(
     const double *__restrict__ part, int slices, int64_t nb, const double *__restrict__ normpart, int G, int C,
-    double root_d, float *__restrict__ cos_out, int32_t *__restrict__ pred_out) {
+    double root_d, int cp, float *__restrict__ cos_out, int32_t *__restrict__ pred_out) {
     extern __shared__ double nrm[];   // [C]
     const int t = threadIdx.x;
     for (int c = t >> 6; c < C; c += 4) {
@@ -466,22 +620,12 @@ __global__ __launch_bounds__(256) void cosine_finish_kernel(
         if ((t & 63) == 0) nrm[c] = s;
     }
     __syncthreads();
-    const int64_t n = (int64_t)blockIdx.x * blockDim.x + t;
-    if (n >= nb) return;
-    double best = 0.0;
-    int pred = 0;
-    for (int c = 0; c < C; ++c) {
-        double dot = 0.0;
-        for (int s = 0; s < slices; ++s) dot += part[((int64_t)s * nb + n) * C + c];
-        const double nn = nrm[c];
-        const double cs = nn == 0.0 ? 0.0 : dot / (sqrt(nn) * root_d);
-        if (c == 0 || cs > best) {
-            best = cs;
-            pred = c;
-        }
-        if (cos_out) cos_out[n * C + c] = (float)cs;
-    }
-    pred_out[n] = pred;
+    const int spb = 256 / cp, lc = t % cp;
+    const int64_t n = (int64_t)blockIdx.x * spb + t / cp;
+    double best, cos_y;
+    int pred;
+    finish_cosines(part, slices, nb, n, n < nb, C, nrm, root_d, cp, lc, -1, cos_out, &best, &pred, &cos_y);
+    if (n < nb && lc == 0) pred_out[n] = pred;
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -504,9 +648,57 @@ static int grow(T **p, size_t *have, size_t want) {
 // Width of the dense coefficient rows of the backward step, 0 = none (LDS sums).
 static int bwd_dense_width(int C) { return C <= 2 ? 2 : C <= 4 ? 4 : C <= 8 ? 8 : C <= 16 ? 16 : 0; }
 
+constexpr int kBwdSplitMin = 2048;   // from this many samples on, the samples of a group are split over blocks
+
+// Groups per wave of the split path: 64 registers of sums (CB classes x GW groups x fp64).
+static int bwd_group_width(int C) { return bwd_dense_width(C) == 16 ? 2 : 4; }
+
+// How many blocks share the samples of one group column: one round of blocks, one per CU.
+static int bwd_shares(const hdc_ctx_impl *c, int G, int64_t nb) {
+    if (bwd_dense_width(c->p.C) == 0 || nb < kBwdSplitMin) return 1;
+    const int gw = bwd_group_width(c->p.C);
+    const int cols = (G + gw - 1) / gw;
+    int64_t shares = c->num_cus / cols;
+    const int64_t most = nb / 256;                                   // at least 256 samples per block
+    const int64_t fit = (int64_t)(64u << 20) / ((int64_t)c->p.C * c->p.D * (int64_t)sizeof(double));
+    if (shares > most) shares = most;
+    if (shares > fit) shares = fit;
+    if (shares > 64) shares = 64;
+    return shares < 1 ? 1 : (int)shares;
+}
+
 static int launch_bwd(hdc_ctx_impl *c, int64_t ld, int64_t nb, float *acc, int G, bool first, bool last,
                       hipStream_t s) {
     const int C = c->p.C;
+    const OnlineWeight *wts = static_cast<const OnlineWeight *>(c->ob_wts_d);
+    const int shares = bwd_shares(c, G, nb);
+    if (shares > 1) {
+        // dense sums, a column of bwd_group_width() groups per block, `shares` blocks per column; the
+        // blocks' sums meet in online_apply_kernel
+        const int gw = bwd_group_width(C);
+        const int64_t bs = (nb + shares - 1) / shares;
+        const int used = (int)((nb + bs - 1) / bs);
+        const dim3 grid((unsigned)((G + gw - 1) / gw), (unsigned)used), block(kBwdMaxWaves * kWave);
+        {
+            ProfScope prof(c, HDC_K_ONLINE_BWD, s);
+#define HDC_BWD(CB, GW)                                                                                     \
+    hipLaunchKernelGGL((online_bwd_wide_kernel<CB, GW>), grid, block, 0, s, c->ob_col_d, ld, c->ob_coef_d, nb, \
+                       c->p.D, C, bs, c->ob_share_d)
+            switch (bwd_dense_width(C)) {
+                case 2: HDC_BWD(2, 4); break;
+                case 4: HDC_BWD(4, 4); break;
+                case 8: HDC_BWD(8, 4); break;
+                default: HDC_BWD(16, 2); break;
+            }
+#undef HDC_BWD
+            HDC_HIP(hipGetLastError());
+            hipLaunchKernelGGL(online_apply_kernel, dim3((unsigned)G, (unsigned)((C + 3) / 4)), dim3(256), 0, s,
+                               c->ob_share_d, used, acc, c->p.D, C, G, c->ob_carry_d, first ? 1 : 0, last ? 1 : 0,
+                               c->ob_norm_d);
+        }
+        HDC_HIP(hipGetLastError());
+        return HDC_OK;
+    }
     for (int c_lo = 0; c_lo < C; c_lo += kBwdSlots) {
         const int c_n = C - c_lo < kBwdSlots ? C - c_lo : kBwdSlots;
         int nw = kBwdSlots / c_n;
@@ -514,11 +706,12 @@ static int launch_bwd(hdc_ctx_impl *c, int64_t ld, int64_t nb, float *acc, int G
         while (nw > 1 && (int64_t)(nw / 2) * kBwdUnroll >= nb) nw /= 2;   // no wave without a trip
         const size_t lds = (size_t)nw * c_n * kWave * sizeof(double);
         const dim3 grid((unsigned)G), block((unsigned)nw * kWave);
-        const OnlineWeight *wts = static_cast<const OnlineWeight *>(c->ob_wts_d);
+        const int64_t bs = (nb + kBwdUnroll - 1) / kBwdUnroll * kBwdUnroll;   // one block takes all samples
         ProfScope prof(c, HDC_K_ONLINE_BWD, s);
-#define HDC_BWD(CB)                                                                                       \
-    hipLaunchKernelGGL(online_bwd_kernel<CB>, grid, block, lds, s, c->ob_col_d, ld, wts, c->ob_coef_d, nb, \
-                       acc, c->p.D, c_lo, c_n, G, c->ob_carry_d, first ? 1 : 0, last ? 1 : 0, c->ob_norm_d)
+#define HDC_BWD(CB)                                                                                          \
+    hipLaunchKernelGGL(online_bwd_kernel<CB>, grid, block, lds, s, c->ob_col_d, ld, wts, c->ob_coef_d, nb, acc, \
+                       c->p.D, c_lo, c_n, G, c->ob_carry_d, first ? 1 : 0, last ? 1 : 0, c->ob_norm_d, 1, bs,  \
+                       static_cast<double *>(nullptr), C)
         switch (bwd_dense_width(C)) {
             case 2: HDC_BWD(2); break;
             case 4: HDC_BWD(4); break;
@@ -597,12 +790,15 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
     HDC_HIP(hipSetDevice(c->device));
     int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)f.slices * sb * C * sizeof(double));
     if (rc == HDC_OK) rc = grow(&c->ob_wts_d, &c->ob_wts_bytes, (size_t)ld * sizeof(OnlineWeight));
-    if (rc == HDC_OK) rc = grow(&c->ob_col_d, &c->ob_col_bytes, (size_t)G * ld * sizeof(uint64_t));
+    if (rc == HDC_OK) rc = grow(&c->ob_col_d, &c->ob_col_bytes, (size_t)(G + 3) * ld * sizeof(uint64_t));
     const int cb = bwd_dense_width(C);
     if (rc == HDC_OK && cb) rc = grow(&c->ob_coef_d, &c->ob_coef_bytes, (size_t)ld * cb * sizeof(double));
     if (rc == HDC_OK) rc = grow(&c->ob_norm_d, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
     if (rc == HDC_OK && batch > sb)
         rc = grow(&c->ob_carry_d, &c->ob_carry_bytes, (size_t)C * D * sizeof(double));
+    const int shares = bwd_shares(c, G, sb);
+    if (rc == HDC_OK && shares > 1)
+        rc = grow(&c->ob_share_d, &c->ob_share_bytes, (size_t)shares * C * D * sizeof(double));
     if (rc != HDC_OK) return rc;
     if (!c->ob_attr_set) {
         const void *kernels[] = {reinterpret_cast<const void *>(online_bwd_kernel<0>),
@@ -629,12 +825,14 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
                 rc = launch_fwd(c, f, rows, nb, acc, s);
                 if (rc != HDC_OK) return rc;
                 const int64_t ld_used = (nb + kTileSamples - 1) / kTileSamples * kTileSamples;
-                const int wblocks = (int)((ld_used + 255) / 256);
+                const int cp = cosine_group(C);
+                const int wblocks = (int)((ld_used + 256 / cp - 1) / (256 / cp));
                 const int tblocks = (int)(ld_used / kTileSamples) * ttiles;
                 hipLaunchKernelGGL(online_weights_kernel, dim3((unsigned)(wblocks + tblocks)), dim3(256),
                                    (size_t)C * sizeof(double), s, c->ob_part_d, f.slices, nb, labels + b0 + s0,
                                    c->ob_norm_d, G, C, root_d, lr, static_cast<OnlineWeight *>(c->ob_wts_d),
-                                   cb ? c->ob_coef_d : nullptr, cb, wblocks, rows, W, c->ob_col_d, ld_used);
+                                   cb ? c->ob_coef_d : nullptr, cb, cp, wblocks, rows, W, c->ob_col_d, ld_used,
+                                   bwd_shares(c, G, nb) > 1 ? bwd_group_width(C) : 1);
                 HDC_HIP(hipGetLastError());
                 rc = launch_bwd(c, ld_used, nb, acc, G, s0 == 0, s0 + nb == B, s);
                 if (rc != HDC_OK) return rc;
@@ -660,8 +858,9 @@ int launch_search_cosine(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const f
         const int64_t nb = n0 + sb < N ? sb : N - n0;
         rc = launch_fwd(c, f, hv + n0 * W, nb, acc, s);
         if (rc != HDC_OK) return rc;
-        hipLaunchKernelGGL(cosine_finish_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256),
-                           (size_t)C * sizeof(double), s, c->ob_part_d, f.slices, nb, c->ob_norm_d, G, C, root_d,
+        const int cp = cosine_group(C);
+        hipLaunchKernelGGL(cosine_finish_kernel, dim3((unsigned)((nb + 256 / cp - 1) / (256 / cp))), dim3(256),
+                           (size_t)C * sizeof(double), s, c->ob_part_d, f.slices, nb, c->ob_norm_d, G, C, root_d, cp,
                            cos_out ? cos_out + n0 * C : nullptr, pred + n0);
         HDC_HIP(hipGetLastError());
     }
