@@ -120,7 +120,6 @@ __global__ __launch_bounds__(kFwdWaves *kWave) void online_fwd_kernel(
     const int slice = blockIdx.x;
     const int c0 = blockIdx.y * CC;
     const int64_t n0 = ((int64_t)blockIdx.z * kFwdWaves + wave) * spw;
-    if (n0 >= nb) return;   // the kernel has no block barrier
     const int64_t n1 = n0 + spw < nb ? n0 + spw : nb;
     double *buf = xch[wave];
 
@@ -131,18 +130,35 @@ __global__ __launch_bounds__(kFwdWaves *kWave) void online_fwd_kernel(
     const int g_own = slice * KPT;
     const int g_base = (g_own + KPT <= G || G < KPT) ? g_own : G - KPT;
 
+    // The block's waves all work on the same slice of the class rows: it is fetched once per
+    // block (every thread a few elements; clamped addresses, values dropped afterwards, so that
+    // all loads are in flight together) and handed to the waves through LDS.  At launch every
+    // block on the chip asks for the same few hundred KB at once, so fewer requests count.
+    float *stage = reinterpret_cast<float *>(&xch[0][0]);   // CC * KPT * 64 floats; the tiles are not in use yet
+    static_assert(sizeof(float) * CC * KPT * kWave <= sizeof(xch), "staging area");
+    {
+        constexpr int kPerThread = CC * KPT * kWave / (kFwdWaves * kWave);
+        float x[kPerThread];
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int e = threadIdx.x + i * kFwdWaves * kWave;   // (j, k, lane) flattened
+            const int j = e / (KPT * kWave), k = (e / kWave) % KPT;
+            const int d = (g_base + k) * kWave + (e % kWave);
+            const int cc = c0 + j < C ? c0 + j : C - 1, dd = d < D ? d : D - 1;
+            x[i] = acc[(int64_t)cc * D + dd];
+            if (!(c0 + j < C && d < D && g_base + k >= g_own)) x[i] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) stage[threadIdx.x + i * kFwdWaves * kWave] = x[i];
+    }
+    __syncthreads();
     double v[CC][KPT];
 #pragma unroll
     for (int j = 0; j < CC; ++j)
 #pragma unroll
-        for (int k = 0; k < KPT; ++k) {
-            // clamped address, value dropped afterwards: the loads stay unconditional and all
-            // of them are in flight together
-            const int d = (g_base + k) * kWave + lane;
-            const int cc = c0 + j < C ? c0 + j : C - 1, dd = d < D ? d : D - 1;
-            const float x = acc[(int64_t)cc * D + dd];
-            v[j][k] = (c0 + j < C && d < D && g_base + k >= g_own) ? (double)x : 0.0;
-        }
+        for (int k = 0; k < KPT; ++k) v[j][k] = (double)stage[(j * KPT + k) * kWave + lane];
+    __syncthreads();        // the staging area becomes the waves' reduction tiles
+    if (n0 >= nb) return;   // no block barrier below this line
 
     auto walk = [&](auto safe) {
         constexpr int SAFE = decltype(safe)::value;
