@@ -123,7 +123,9 @@ int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *
  * acc_dev [C][D] fp32 is in/out (zero it for a fresh model); repeated calls continue
  * training.  Samples whose label is outside [0, C) are skipped.  The sequential
  * dependency between samples is the method's; one call is one dependency chain.
- * epochs >= 0; lr is the paper's learning rate gamma.
+ * epochs >= 0; lr is the paper's learning rate gamma.  D <= 32768 (HDC_ELIMIT beyond).
+ * For C <= 12 and D <= 10240 the first call allocates 64 MB of context-owned scratch
+ * (HDC_ENOMEM if that fails); later calls only enqueue on `stream`.
  */
 int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
                      int32_t epochs, float lr, float *acc_dev, void *stream);

@@ -25,7 +25,7 @@ static void free_ctx(hdc_ctx_impl *c) {
     if (!c) return;
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d,
-                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d};
+                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {

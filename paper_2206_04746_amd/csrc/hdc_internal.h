@@ -47,6 +47,8 @@ struct hdc_ctx_impl {
     int64_t perm_rows;
     uint32_t *partial_d;  // [partial_items][Wp * 16] per-block partial counts, two u16 per dword
     int64_t partial_items;
+    uint32_t *on_bits_d;  // [16384][1024] per-thread sample bits of hdc_train_online (first call allocates)
+
     // Scratch of hdc_train_online_batched, allocated on its first call and grown when a call
     // needs more (batch size is a call argument, not a property of the model).
     double *ob_part_d;    // [slices][sub-batch][C] partial dot products

@@ -162,6 +162,41 @@ __device__ __forceinline__ double wave_sum_dpp(double v) {
     return v;
 }
 
+// Sum over the 64 lanes, valid in lane 63 only: four DPP folds inside each row of 16 lanes, then
+// the row totals travel by row broadcast (lane 15 of a row into the next row, lane 31 into rows
+// 2 and 3) - no LDS round trips, which matters where one wave works alone.
+__device__ __forceinline__ double dpp_row_bcast_f64(double v, const int which) {
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    int mlo, mhi;
+    if (which == 15) {   // row_bcast:15 into rows 1 and 3
+        mlo = __builtin_amdgcn_update_dpp(0, lo, 0x142, 0xA, 0xF, false);
+        mhi = __builtin_amdgcn_update_dpp(0, hi, 0x142, 0xA, 0xF, false);
+    } else {             // row_bcast:31 into rows 2 and 3
+        mlo = __builtin_amdgcn_update_dpp(0, lo, 0x143, 0xC, 0xF, false);
+        mhi = __builtin_amdgcn_update_dpp(0, hi, 0x143, 0xC, 0xF, false);
+    }
+    return __hiloint2double(mhi, mlo);
+}
+__device__ __forceinline__ double wave_sum_to_lane63(double v) {
+    v += dpp_shuffle_f64(v, 0);
+    v += dpp_shuffle_f64(v, 1);
+    v += dpp_shuffle_f64(v, 2);
+    v += dpp_shuffle_f64(v, 3);
+    v += dpp_row_bcast_f64(v, 15);
+    v += dpp_row_bcast_f64(v, 31);
+    return v;
+}
+
+// x / (sqrt(nn) * root_d) for nn > 0 without the long IEEE square root and division: the
+// hardware reciprocal square root estimate refined by two Newton steps (error about one unit in
+// the last place), inv_root_d = 1 / sqrt(D) from the host.
+__device__ __forceinline__ double cosine_of(double dot, double nn, double inv_root_d) {
+    double r = __builtin_amdgcn_rsq(nn);
+    r = r * fma(-0.5 * nn * r, r, 1.5);
+    r = r * fma(-0.5 * nn * r, r, 1.5);
+    return dot * r * inv_root_d;
+}
+
 template <int CMAX, int KPT>
 __global__ __launch_bounds__(kOnlineThreads) void online_reg_kernel(
     const uint32_t *__restrict__ hv, const int32_t *__restrict__ labels, int64_t N, int epochs,
@@ -311,6 +346,237 @@ __global__ __launch_bounds__(kOnlineThreads) void online_reg_kernel(
         }
 }
 
+// ---- register-resident variant for few classes --------------------------------------------
+// As above, but the block-wide sums go through LDS in two stages instead of a butterfly per
+// value in every wave: each thread parks its per-class partial dot product (and, from the
+// update of the step before, its partial squared norms of the one or two rows that changed) in
+// LDS; after the barrier wave c alone adds up column c (16 loads per lane, one butterfly),
+// refreshes the norm of row c if that row changed, and its first lane finishes cos_c.  All
+// threads then read the C cosines, decide and update their own elements.  Two barriers per
+// step; the per-thread partial dot product is KPT FMAs per class on a +-1.0 built from the
+// sample's bit (two integer ops per element, shared by the classes).  Needs C + 2 <= 16 waves.
+template <int CMAX, int KPT>
+__global__ __launch_bounds__(kOnlineThreads) void online_lds_kernel(
+    const uint32_t *__restrict__ tbits, int64_t N, int epochs, float lr, float *acc, int D, int C,
+    double inv_root_d) {
+    static_assert(CMAX + 2 <= kOnlineWaves, "one wave per column");
+    extern __shared__ double part_dyn[];   // [CMAX + 2][1024] columns: C dot products, then norm(y), norm(pred)
+    auto part_at = [&](int col) { return part_dyn + col * kOnlineThreads; };
+    __shared__ double nrm[CMAX];
+    __shared__ double cosv[CMAX];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    float m[CMAX][KPT];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int d = tid + k * kOnlineThreads;
+            m[c][k] = (c < C && d < D) ? acc[(int64_t)c * D + d] : 0.0f;
+        }
+    // squared norms of the rows as handed in, through the same two stages
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) {
+        double p = 0.0;
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) p += (double)m[c][k] * (double)m[c][k];
+        part_at(c)[tid] = p;
+    }
+    __syncthreads();
+    if (wave < C) {
+        double s = 0.0;
+#pragma unroll
+        for (int i = 0; i < kOnlineWaves; ++i) s += part_at(wave)[lane + i * kWave];
+        s = wave_sum_dpp(s);
+        if (lane == 0) nrm[wave] = s;
+    }
+    __syncthreads();
+    int upd_y = -1, upd_p = -1;   // rows whose norm partials wait in columns CMAX, CMAX + 1
+
+    // low 16 bits of a thread's word: bit k = the sample's bit in the thread's k-th dimension;
+    // high 16 bits: label + 1, or 0 for a label outside [0, C).  Prepared by online_bits_kernel,
+    // so a step costs one coalesced load per thread.
+    static_assert(KPT <= 16, "sample bits share a word with the label");
+    auto load_word = [&](int64_t n) { return tbits[n * kOnlineThreads + tid]; };
+
+    // A sample's word (bits and label) is fetched two steps before its step: a first read comes
+    // from beyond the L2 and takes longer than one step.
+    const int64_t steps = (int64_t)epochs * N;
+    int64_t nf = 0;   // sample index of the next fetch
+    auto fetch = [&]() {
+        const uint32_t w = load_word(nf);   // harmless when it runs past the last step: in bounds, unused
+        nf = (nf + 1 == N) ? 0 : nf + 1;
+        return w;
+    };
+    // Two steps per trip, each with a register of its own for the prefetched word; a word is
+    // taken apart at the top of its step and its register reloaded at once, for the step two
+    // ahead - nothing is copied, so nothing waits for a load that has just been issued.
+    uint32_t word_a = fetch(), word_b = fetch();
+    auto one_step = [&](uint32_t &word) {
+        const uint32_t bits = word & 0xffffu;
+        const int y = __builtin_amdgcn_readfirstlane((int)(word >> 16)) - 1;   // -1: label out of range
+        word = fetch();
+        if (y < 0) return;   // uniform
+
+        // ---- stage 1: this thread's share of every dot product
+        {
+            // +1.0 where the bit is set, -1.0 where it is not: sign bit = inverted sample bit
+            const uint32_t inv = ~bits;
+            int sgn_hi[KPT];
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) sgn_hi[k] = (int)(((inv << (31 - k)) & 0x80000000u) | 0x3FF00000u);
+#pragma unroll
+            for (int c = 0; c < CMAX; ++c) {
+                if (c < C) {
+                    double p = 0.0;
+#pragma unroll
+                    for (int k = 0; k < KPT; ++k) p = fma((double)m[c][k], __hiloint2double(sgn_hi[k], 0), p);
+                    part_at(c)[tid] = p;
+                }
+            }
+        }
+        __syncthreads();
+        // ---- stage 2: wave c finishes column c
+        if (wave < C) {
+            // (8 loads in flight at a time: the registers of this stage are allocated in every
+            // wave, next to the accumulators; two running sums halve the chain of additions)
+            const double *colp = part_at(wave) + lane;
+            double d0 = 0.0, d1 = 0.0;
+#pragma unroll 4
+            for (int i = 0; i < kOnlineWaves; i += 2) {
+                d0 += colp[i * kWave];
+                d1 += colp[(i + 1) * kWave];
+            }
+            double dot = d0 + d1;
+            const int col = wave == upd_y ? CMAX : (wave == upd_p ? CMAX + 1 : -1);   // uniform
+            double nn = 0.0;
+            if (col >= 0) {
+                const double *np = part_at(col) + lane;
+                double n0 = 0.0, n1 = 0.0;
+#pragma unroll 4
+                for (int i = 0; i < kOnlineWaves; i += 2) {
+                    n0 += np[i * kWave];
+                    n1 += np[(i + 1) * kWave];
+                }
+                nn = wave_sum_to_lane63(n0 + n1);
+            }
+            dot = wave_sum_to_lane63(dot);
+            if (lane == kWave - 1) {
+                if (col >= 0) nrm[wave] = nn; else nn = nrm[wave];
+                cosv[wave] = nn == 0.0 ? 0.0 : cosine_of(dot, nn, inv_root_d);
+            }
+        }
+        __syncthreads();
+        // ---- stage 3: decision and updates (Eq. 2 always, Eq. 3 only after a wrong prediction)
+        int pred = 0;
+        double best = cosv[0];
+        for (int c = 1; c < C; ++c) {
+            const double v = cosv[c];
+            if (v > best) { best = v; pred = c; }
+        }
+        const float w_y = (float)(1.0 - cosv[y]);
+        const float w_p = (float)((double)lr * (1.0 - best));
+        const bool wrong = pred != y;
+        double py = 0.0, pp = 0.0;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+            if (c == y) {
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    if (tid + k * kOnlineThreads < D) {
+                        const float v = __fadd_rn(m[c][k], ((bits >> k) & 1u) ? w_y : -w_y);
+                        m[c][k] = v;
+                        py = fma((double)v, (double)v, py);
+                    }
+                }
+            } else if (wrong && c == pred) {
+#pragma unroll
+                for (int k = 0; k < KPT; ++k) {
+                    if (tid + k * kOnlineThreads < D) {
+                        const float v = __fadd_rn(m[c][k], ((bits >> k) & 1u) ? -w_p : w_p);
+                        m[c][k] = v;
+                        pp = fma((double)v, (double)v, pp);
+                    }
+                }
+            }
+        }
+        part_at(CMAX)[tid] = py;
+        part_at(CMAX + 1)[tid] = pp;
+        upd_y = y;
+        upd_p = wrong ? pred : -1;
+        // the norm columns are read after the next step's first barrier and rewritten after its
+        // second; cosv is rewritten after the next step's first barrier
+    };
+    for (int64_t step = 0; step < steps; step += 2) {
+        one_step(word_a);
+        if (step + 1 < steps) one_step(word_b);
+    }
+
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int d = tid + k * kOnlineThreads;
+            if (c < C && d < D) acc[(int64_t)c * D + d] = m[c][k];
+        }
+}
+
+// tbits[n][t]: low half = bits of sample n in the dimensions thread t owns (t, t + 1024, ...),
+// bit k for the k-th of them (D <= 16384); high half = label + 1, 0 if the label is outside
+// [0, C).  One block per sample.
+__global__ __launch_bounds__(kOnlineThreads) void online_bits_kernel(const uint32_t *__restrict__ hv,
+                                                                      const int32_t *__restrict__ labels, int C,
+                                                                      int D, int W, uint32_t *__restrict__ tbits) {
+    const int tid = threadIdx.x;
+    const uint32_t *h = hv + (int64_t)blockIdx.x * W;
+    const int y = labels[blockIdx.x];
+    uint32_t word = (y >= 0 && y < C) ? (uint32_t)(y + 1) << 16 : 0u;
+    for (int d = tid, k = 0; d < D; d += kOnlineThreads, ++k) word |= ((h[d >> 5] >> (d & 31)) & 1u) << k;
+    tbits[(int64_t)blockIdx.x * kOnlineThreads + tid] = word;
+}
+
+constexpr int64_t kOnlineChunk = 16384;   // samples whose per-thread bit words are prepared at a time (64 MB)
+
+template <int CMAX, int KPT>
+static int launch_online_lds(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                             int32_t epochs, float lr, float *acc, hipStream_t s) {
+    auto kern = online_lds_kernel<CMAX, KPT>;
+    const size_t lds = (size_t)(CMAX + 2) * kOnlineThreads * sizeof(double);
+    static bool raised = false;
+    if (!raised && lds > 64 * 1024) {
+        HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = true;
+    }
+    if (!c->on_bits_d) {
+        HDC_HIP(hipSetDevice(c->device));
+        const hipError_t e = hipMalloc(reinterpret_cast<void **>(&c->on_bits_d),
+                                       (size_t)kOnlineChunk * kOnlineThreads * sizeof(uint32_t));
+        if (e == hipErrorOutOfMemory) {
+            (void)hipGetLastError();
+            return HDC_ENOMEM;
+        }
+        HDC_HIP(e);
+    }
+    // A set that fits one chunk is prepared once and walked `epochs` times by one launch; a
+    // longer one is walked chunk by chunk, every epoch (the accumulators rest in memory between
+    // launches, which changes nothing: they are fp32 there and in the registers).
+    const bool one = N <= kOnlineChunk;
+    for (int32_t e = 0; e < (one ? 1 : epochs); ++e)
+        for (int64_t n0 = 0; n0 < N; n0 += kOnlineChunk) {
+            const int64_t n = N - n0 < kOnlineChunk ? N - n0 : kOnlineChunk;
+            hipLaunchKernelGGL(online_bits_kernel, dim3((unsigned)n), dim3(kOnlineThreads), 0, s, hv + n0 * c->W,
+                               labels + n0, c->p.C, c->p.D, c->W, c->on_bits_d);
+            ProfScope prof(c, HDC_K_ONLINE, s);
+            hipLaunchKernelGGL(kern, dim3(1), dim3(kOnlineThreads), lds, s, c->on_bits_d, n, one ? (int)epochs : 1,
+                               lr, acc, c->p.D, c->p.C, 1.0 / sqrt((double)c->p.D));
+        }
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 template <int CMAX, int KPT>
 static int launch_online_reg(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                              int32_t epochs, float lr, float *acc, hipStream_t s) {
@@ -327,6 +593,14 @@ int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labe
     if (c->p.D > 32 * kOnlineThreads) return HDC_ELIMIT;   // a thread keeps its sample bits in one word
     // Register-resident kernel when C x (dimensions per thread) fits the register file.
     const int kpt = (c->p.D + kOnlineThreads - 1) / kOnlineThreads;
+#define HDC_ONLINE_LDS_CASE(CM, KP) \
+    if (C <= CM && kpt <= KP) return launch_online_lds<CM, KP>(c, hv, labels, N, epochs, lr, acc, s)
+    HDC_ONLINE_LDS_CASE(8, 2);
+    HDC_ONLINE_LDS_CASE(4, 4);
+    HDC_ONLINE_LDS_CASE(12, 4);
+    HDC_ONLINE_LDS_CASE(2, 10);
+    HDC_ONLINE_LDS_CASE(6, 10);
+#undef HDC_ONLINE_LDS_CASE
 #define HDC_ONLINE_CASE(CM, KP) \
     if (C <= CM && kpt <= KP) return launch_online_reg<CM, KP>(c, hv, labels, N, epochs, lr, acc, s)
     HDC_ONLINE_CASE(8, 1);
