@@ -198,7 +198,11 @@ def rel_err(got, want):
 
 @pytest.mark.parametrize("D,C,N,epochs,lr", [(1024, 5, 600, 2, 1.0), (10000, 6, 1500, 3, 1.0),
                                              (10000, 26, 300, 1, 0.5), (33, 1, 20, 2, 1.0),
-                                             (2049, 3, 100, 1, 0.0), (32768, 2, 40, 1, 1.0)])
+                                             (2049, 3, 100, 1, 0.0), (32768, 2, 40, 1, 1.0),
+                                             # more samples than one prepared chunk (16384), two epochs
+                                             (1024, 3, 20000, 2, 1.0),
+                                             # 12 < C: the kernel with a butterfly per value; C > 80: accumulators in memory
+                                             (1024, 20, 300, 1, 1.0), (512, 100, 120, 1, 1.0)])
 def test_online_training_matches_oracle(D, C, N, epochs, lr):
     rng = np.random.default_rng(D + C + N)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
