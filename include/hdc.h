@@ -92,6 +92,16 @@ int hdc_destroy(hdc_ctx *ctx);
 int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);
 
 /*
+ * How many 32-bit words per sample hdc_encode actually bundles.  Where all L level vectors
+ * have the same bit, Eq. (1) gives the same bit for every sample; hdc_create finds those
+ * dimensions and, when at least a quarter of D is like that, hdc_encode bundles the other
+ * dimensions only and fills in the constants (the result is bit-identical).  Returns W when
+ * every dimension is bundled, fewer otherwise (0 if all level vectors are equal), -1 for a
+ * NULL context.  For reporting: the work of an encode call is this many words times F.
+ */
+int32_t hdc_encoded_words(const hdc_ctx *ctx);
+
+/*
  * Classical training, Sec. III ("single-pass accumulation of the encoded vectors
  * belonging to the same class into a class vector"):
  *   acc[c][d] += hv[n][d]  and  class_n[c] += 1   for c = labels[n].

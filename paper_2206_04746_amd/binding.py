@@ -23,7 +23,7 @@ HDC_F32, HDC_U8 = 0, 1
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
-           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum",
+           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_encoded_words",
            "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.hdc_train_online_batched.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, i64, vp, vp]
     lib.hdc_binarize_online.argtypes = [vp, vp, vp, vp]
     lib.hdc_search_cosine.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    lib.hdc_encoded_words.argtypes = [vp]
+    lib.hdc_encoded_words.restype = ctypes.c_int32
     for name in ("hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum"):
         getattr(lib, name).argtypes = [vp, vp, i64, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
@@ -180,6 +182,9 @@ class Context:
     def hdc_binarize_online(self, acc, class_hv, stream=None) -> None:
         _check(lib.hdc_binarize_online(self._h, _dev(acc, torch.float32, (self.C, self.D)),
                                        _dev(class_hv, torch.int32, (self.C, self.W)), _stream(stream)))
+
+    def hdc_encoded_words(self) -> int:
+        return int(lib.hdc_encoded_words(self._h))
 
     def hdc_search_cosine(self, hv, acc, pred, cos=None, stream=None) -> None:
         N = hv.shape[0]

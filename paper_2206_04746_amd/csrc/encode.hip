@@ -283,9 +283,10 @@ struct EncodeVariant {
 static const EncodeVariant kVariants[] = {HDC_VARIANTS(8), HDC_VARIANTS(10), HDC_VARIANTS(12), HDC_VARIANTS(16)};
 #undef HDC_VARIANTS
 
-static int launch_encode_kernel(hdc_ctx_impl *c, int P, int N, uint32_t *hv, uint32_t bias,
-                                hipStream_t s) {
-    const int nslices = c->Wp / kSliceWords;
+// `item`, `level`, W, Wp: the full tables of the context or its compact ones; hv has rows of W words.
+static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, int W, int Wp,
+                                int P, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
+    const int nslices = Wp / kSliceWords;
     const int waves = c->p.L > 128 ? 8 : 4;   // a big level slice: fewer, larger blocks per CU
     // small batches take 2-sample units so that there are enough of them for 1024 SIMDs
     // (measured crossover: about 3 four-sample units per SIMD)
@@ -320,8 +321,40 @@ static int launch_encode_kernel(hdc_ctx_impl *c, int P, int N, uint32_t *hv, uin
     const int per_slice = (need_waves + waves - 1) / waves;
     ProfScope prof(c, HDC_K_ENCODE, s);
     hipLaunchKernelGGL(v->fn, dim3((unsigned)nslices, (unsigned)per_slice), dim3(waves * kWave), lds, s,
-                       c->q_d, c->item_d, c->level_d, hv, N, c->Fp, c->p.L, c->W, bias);
+                       c->q_d, item, level, hv, N, c->Fp, c->p.L, W, bias);
     return HDC_OK;
+}
+
+// ---- spreading compact hypervectors back over all dimensions ---------------------------------
+// One lane per output word w.  The bits of w that vary are a run of the compact row starting at
+// bit tab[0][w]; they are spread to the set bits of tab[1][w] by five shift-and-merge stages
+// (a bit's distance to its place, in binary: stage i moves the bits whose distance has bit i
+// set by 2^i, highest first; tab[2 + i][w] marks where they land), and the model's constant
+// bits tab[7][w] fill the rest.  A thread keeps its word's eight table entries in registers and
+// walks down the rows.
+constexpr int kExpandRows = 4;
+__global__ __launch_bounds__(kExpandRows *kWave) void expand_kernel(const uint32_t *__restrict__ hvc, int64_t N, int Wc,
+                                                                    int W, const uint32_t *__restrict__ tab,
+                                                                    uint32_t *__restrict__ hv) {
+    const int w = blockIdx.x * kWave + (threadIdx.x & (kWave - 1));
+    if (w >= W) return;
+    const uint32_t off = tab[w], keep = tab[W + w], cst = tab[7 * W + w];
+    uint32_t stage[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) stage[i] = tab[(2 + i) * W + w];
+    const int i0 = (int)(off >> 5), sh = (int)(off & 31u);
+    for (int64_t n = (int64_t)blockIdx.y * kExpandRows + (threadIdx.x >> 6); n < N;
+         n += (int64_t)gridDim.y * kExpandRows) {
+        uint32_t x = 0;
+        if (keep) {
+            const uint32_t *row = hvc + n * Wc;
+            const uint32_t lo = i0 < Wc ? row[i0] : 0u, hi = i0 + 1 < Wc ? row[i0 + 1] : 0u;
+            x = sh ? (lo >> sh) | (hi << (32 - sh)) : lo;
+#pragma unroll
+            for (int i = 4; i >= 0; --i) x = (x & ~stage[i]) | ((x << (1 << i)) & stage[i]);
+        }
+        hv[n * W + w] = (x & keep) | cst;
+    }
 }
 
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
@@ -350,8 +383,21 @@ int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, h
                 hipLaunchKernelGGL(quantize_kernel<false>, qgrid, dim3(64), 0, s, x, n, c->p.F, c->Fp, c->p.L,
                                    c->lo_d, c->scale_d, q4);
         }
-        const int rc = launch_encode_kernel(c, P, (int)n, hv + (size_t)n0 * c->W, bias, s);
-        if (rc != HDC_OK) return rc;
+        uint32_t *out = hv + (size_t)n0 * c->W;
+        if (!c->compact) {
+            const int rc = launch_encode_kernel(c, c->item_d, c->level_d, c->W, c->Wp, P, (int)n, out, bias, s);
+            if (rc != HDC_OK) return rc;
+        } else {
+            if (c->Wc > 0) {
+                const int rc = launch_encode_kernel(c, c->citem_d, c->clevel_d, c->Wc, c->Wcp, P, (int)n, c->hvc_d,
+                                                    bias, s);
+                if (rc != HDC_OK) return rc;
+            }
+            int64_t gy = (n + kExpandRows - 1) / kExpandRows;
+            if (gy > 2048) gy = 2048;
+            hipLaunchKernelGGL(expand_kernel, dim3((unsigned)((c->W + kWave - 1) / kWave), (unsigned)gy),
+                               dim3(kExpandRows * kWave), 0, s, c->hvc_d, n, c->Wc, c->W, c->expand_d, out);
+        }
         HDC_HIP(hipGetLastError());
     }
     return HDC_OK;

@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -25,7 +26,8 @@ static void free_ctx(hdc_ctx_impl *c) {
     if (!c) return;
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d,
-                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d};
+                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d,
+                    c->citem_d, c->clevel_d, c->hvc_d, c->expand_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -52,6 +54,158 @@ static bool pads_are_zero(const uint32_t *t, int64_t rows, int W, uint32_t last_
     for (int64_t r = 0; r < rows; ++r)
         if (t[r * W + (W - 1)] & ~last_mask) return false;
     return true;
+}
+
+// ---- level-invariant dimensions: host-side preparation ---------------------------------------
+// The set bits of `keep`, lowest first, picked out of `word` and packed to the low end.
+static inline uint32_t gather_bits(uint32_t word, uint32_t keep) {
+    uint32_t out = 0;
+    for (int k = 0; keep; keep &= keep - 1, ++k) out |= ((word >> __builtin_ctz(keep)) & 1u) << k;
+    return out;
+}
+
+// Appends the kept bits of a W-word row to a densely packed row of Wc words (zeroed by the caller).
+static void compact_row(const uint32_t *row, const uint32_t *keep, int W, uint32_t *dst) {
+    uint64_t acc = 0;
+    int have = 0, at = 0;
+    for (int w = 0; w < W; ++w) {
+        const int cnt = __builtin_popcount(keep[w]);
+        if (!cnt) continue;
+        acc |= (uint64_t)gather_bits(row[w], keep[w]) << have;
+        have += cnt;
+        if (have >= 32) {
+            dst[at++] = (uint32_t)acc;
+            acc >>= 32;
+            have -= 32;
+        }
+    }
+    if (have) dst[at] = (uint32_t)acc;
+}
+
+// The inverse of gather_bits in five stages, as expand_kernel applies them: bit j of the packed
+// word belongs at the j-th set bit of `keep`, a distance z to the left; stage i (4 down to 0)
+// moves the bits whose z has bit i set by 2^i, and stage[i] marks where they land (the place a
+// bit has when only the lower i bits of its distance are still to go).
+static void spread_stages(uint32_t keep, uint32_t stage[5]) {
+    for (int i = 0; i < 5; ++i) stage[i] = 0;
+    int j = 0;
+    for (uint32_t m = keep; m; m &= m - 1, ++j) {
+        const int pos = __builtin_ctz(m), z = pos - j;
+        for (int i = 0; i < 5; ++i)
+            if ((z >> i) & 1) stage[i] |= 1u << (pos - (z & ((1 << i) - 1)));
+    }
+}
+
+static inline uint32_t spread_bits(uint32_t x, uint32_t keep, const uint32_t stage[5]) {
+    for (int i = 4; i >= 0; --i) x = (x & ~stage[i]) | ((x << (1 << i)) & stage[i]);
+    return x & keep;
+}
+
+// Word w of row r in the slice-major device layout [Wp / 64][rows][64].
+static inline size_t slice_major(int rows, int r, int w) {
+    return ((size_t)(w / kSliceWords) * rows + r) * kSliceWords + (w % kSliceWords);
+}
+
+constexpr int64_t kCompactMaxBits = 200000000;   // table bits the host is willing to repack at create
+
+// Decides whether encoding runs on the varying dimensions only and, if so, builds the compact
+// tables, the spreading table and the constant bits (the latter by encoding one sample with the
+// full tables: at an invariant dimension every sample gives the same bit).  Leaves c->compact
+// false on any doubt; only a failed allocation or copy is an error.
+static int prepare_compact(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie) {
+    const hdc_params &p = c->p;
+    const int W = c->W;
+    c->compact = false;
+    if (((int64_t)c->Fp + p.L) * p.D > kCompactMaxBits) return HDC_OK;
+    std::vector<uint32_t> keep((size_t)W, 0u);   // bit set = some level vector differs from level 0 there
+    int64_t varying = 0;
+    for (int w = 0; w < W; ++w) {
+        uint32_t diff = 0;
+        for (int l = 1; l < p.L; ++l) diff |= level[(size_t)l * W + w] ^ level[w];
+        keep[w] = diff;
+        varying += __builtin_popcount(diff);
+    }
+    if (varying * 4 > (int64_t)p.D * 3) return HDC_OK;   // less than a quarter to gain: not worth a second pass
+    const int Wc = (int)((varying + 31) / 32);
+    const int Wcp = (Wc + kSliceWords - 1) / kSliceWords * kSliceWords;
+
+    // spreading table, checked against the definition before it is trusted
+    std::vector<uint32_t> tab((size_t)8 * W, 0u);
+    uint32_t off = 0;
+    for (int w = 0; w < W; ++w) {
+        uint32_t stage[5];
+        spread_stages(keep[w], stage);
+        const uint32_t probes[3] = {0xffffffffu, 0x55555555u, 0x9e3779b9u};
+        for (uint32_t x : probes) {
+            uint32_t want = 0;
+            int j = 0;
+            for (uint32_t m = keep[w]; m; m &= m - 1, ++j) want |= ((x >> j) & 1u) << __builtin_ctz(m);
+            if (spread_bits(x, keep[w], stage) != want) return HDC_OK;   // never expected; keeps the full path
+        }
+        tab[w] = off;
+        tab[(size_t)W + w] = keep[w];
+        for (int i = 0; i < 5; ++i) tab[(size_t)(2 + i) * W + w] = stage[i];
+        off += (uint32_t)__builtin_popcount(keep[w]);
+    }
+
+    // constant bits: one sample (all features zero) through the full tables
+    {
+        const size_t esz = p.feat_dtype == HDC_U8 ? 1 : 4;
+        void *x_d = nullptr;
+        uint32_t *h_d = nullptr;
+        std::vector<uint32_t> h((size_t)W);
+        hipError_t e = hipMalloc(&x_d, (size_t)p.F * esz + 256);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&h_d), (size_t)W * 4 + 256);
+        if (e == hipSuccess) e = hipMemset(x_d, 0, (size_t)p.F * esz);
+        int rc = e == hipSuccess ? launch_encode(c, x_d, 1, h_d, nullptr) : HDC_EHIP;
+        if (rc == HDC_OK) e = hipMemcpy(h.data(), h_d, (size_t)W * 4, hipMemcpyDeviceToHost);
+        if (x_d) (void)hipFree(x_d);
+        if (h_d) (void)hipFree(h_d);
+        if (e == hipErrorOutOfMemory) {
+            (void)hipGetLastError();
+            return HDC_ENOMEM;
+        }
+        if (e != hipSuccess) return hip_fail(e, "constant bits of the level-invariant dimensions");
+        if (rc != HDC_OK) return rc;
+        for (int w = 0; w < W; ++w) tab[(size_t)7 * W + w] = h[w] & ~keep[w];
+    }
+
+    // compact tables in the same padded slice-major layout as the full ones
+    int rc = dev_alloc(&c->expand_d, tab.size());
+    if (rc != HDC_OK) return rc;
+    hipError_t e = hipMemcpy(c->expand_d, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    if (Wc > 0) {
+        std::vector<uint32_t> item_h((size_t)c->Fp * Wcp, 0u), level_h((size_t)p.L * Wcp, 0u);
+        std::vector<uint32_t> row((size_t)W), crow((size_t)Wc);
+        auto put = [&](std::vector<uint32_t> &dst, int rows, int r, const uint32_t *src_row) {
+            std::fill(crow.begin(), crow.end(), 0u);
+            compact_row(src_row, keep.data(), W, crow.data());
+            for (int w = 0; w < Wc; ++w) dst[slice_major(rows, r, w)] = crow[w];
+        };
+        for (int l = 0; l < p.L; ++l) put(level_h, p.L, l, level + (size_t)l * W);
+        for (int f = 0; f < c->Fp; ++f) {
+            if (f < p.F) {
+                put(item_h, c->Fp, f, item + (size_t)f * W);
+            } else if (f == p.F && c->votes != p.F) {
+                for (int w = 0; w < W; ++w) row[w] = tie[w] ^ level[w];
+                put(item_h, c->Fp, f, row.data());
+            } else {
+                put(item_h, c->Fp, f, level);
+            }
+        }
+        rc = dev_alloc(&c->citem_d, item_h.size());
+        if (rc == HDC_OK) rc = dev_alloc(&c->clevel_d, level_h.size());
+        if (rc == HDC_OK) rc = dev_alloc(&c->hvc_d, (size_t)c->q_rows * Wc);
+        if (rc != HDC_OK) return rc;
+        e = hipMemcpy(c->citem_d, item_h.data(), item_h.size() * 4, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->clevel_d, level_h.data(), level_h.size() * 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    }
+    c->Wc = Wc;
+    c->Wcp = Wcp;
+    c->compact = true;
+    return HDC_OK;
 }
 
 static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, const uint32_t *level,
@@ -162,6 +316,12 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     if (c->partial_items < 0 && rc == HDC_OK) rc = HDC_EHIP;
     TRY(dev_alloc(&c->partial_d, (size_t)c->partial_items * c->Wp * 16));
     TRY_HIP(hipDeviceSynchronize());
+    try {
+        TRY(prepare_compact(c, item, level, tie));
+    } catch (const std::bad_alloc &) {
+        rc = HDC_ENOMEM;
+    }
+    TRY_HIP(hipDeviceSynchronize());
 #undef TRY
 #undef TRY_HIP
     if (rc != HDC_OK) {
@@ -202,6 +362,12 @@ int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev,
     if (!feats_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
     if (impl(ctx)->p.feat_dtype == HDC_F32 && !aligned4(feats_dev)) return HDC_EINVAL;
     return launch_encode(impl(ctx), feats_dev, N, hv_dev, static_cast<hipStream_t>(stream));
+}
+
+int32_t hdc_encoded_words(const hdc_ctx *ctx) {
+    if (!ctx) return -1;
+    const hdc_ctx_impl *c = reinterpret_cast<const hdc_ctx_impl *>(ctx);
+    return c->compact ? c->Wc : c->W;
 }
 
 int hdc_train_classical(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,

@@ -36,6 +36,20 @@ struct hdc_ctx_impl {
     float *lo_d;        // [F]   (HDC_F32 only)
     float *scale_d;     // [F]
 
+    // Level-invariant dimensions (Sec. III: level vectors differ from one another in only part
+    // of the dimensions; with linear scaling about half never flip).  Where every level vector
+    // has the same bit, the vote of a feature is item XOR level[0] whatever the feature's value:
+    // the encoded bit is a constant of the model.  When enough dimensions are like that, encoding
+    // runs on the other dimensions only, packed densely ("compact" tables, same layouts), and
+    // expand_kernel spreads the result back and fills in the constants.
+    bool compact;
+    int32_t Wc, Wcp;        // words of a compact row, and padded to whole slices (Wc may be 0)
+    uint32_t *citem_d;      // [Wcp/64][Fp][64]
+    uint32_t *clevel_d;     // [Wcp/64][L][64]
+    uint32_t *hvc_d;        // [q_rows][Wc] compact hypervectors of the chunk being encoded
+    uint32_t *expand_d;     // [8][W]: bit offset into the compact row | mask of varying bits |
+                            // five bit-spreading stage masks | constant bits
+
     // Scratch owned by the context (sized at create, never grown on the hot path).
     uint16_t *q_d;        // [q_rows][Fp] level-row offsets (bin * 256) of the samples being encoded
     int64_t q_rows;       // rows q_d can hold

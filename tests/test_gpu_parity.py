@@ -190,6 +190,38 @@ def test_search_bit_exact(D, C, N):
     ctx.close()
 
 
+# Level tables decide which dimensions encode to a per-model constant (every level vector has the
+# same bit there).  The library then encodes only the other dimensions and spreads the result:
+# the output must not depend on how many dimensions vary, nor on where they sit.
+@pytest.mark.parametrize("D,F,L,N,vary", [
+    (10000, 617, 64, 300, 1.0),      # every dimension varies: nothing to leave out
+    (10000, 617, 64, 300, 0.80),     # too few invariant dimensions to bother
+    (10000, 617, 64, 300, 0.74),     # just enough
+    (10000, 128, 16, 200, 0.10),     # almost everything is a constant
+    (10000, 33, 5, 100, 0.0),        # identical level vectors: the whole hypervector is a constant
+    (10000, 61, 1, 50, 1.0),         # one level: same thing
+    (4097, 100, 8, 120, 0.5), (33, 7, 4, 40, 0.5), (64, 8, 4, 40, 0.03), (2048, 64, 256, 65, 0.6),
+    (20000, 40, 3, 30, 0.33)])
+def test_encode_any_pattern_of_level_invariant_dimensions(D, F, L, N, vary):
+    rng = np.random.default_rng(int(D + 7 * F + 13 * L + 1000 * vary))
+    wl = make_workload(1, D=D, F=F, L=L)
+    lv = np.repeat(rng.integers(0, 2, size=(1, D), dtype=np.uint8), L, axis=0)
+    cols = np.flatnonzero(rng.random(D) < vary)              # scattered, not a prefix
+    if L > 1 and cols.size:
+        lv[:, cols] = rng.integers(0, 2, size=(L, cols.size), dtype=np.uint8)
+        lv[1, cols] = lv[0, cols] ^ 1                        # each chosen dimension really varies
+    wl.level = pack_bits_lsb(lv)
+    x, _ = wl.train(N)
+    ctx = make_ctx(wl)
+    got = host_u32(gpu_encode(ctx, x))
+    assert np.array_equal(got, orc_encode(wl, x))
+    # what the library says it bundles: everything, or just the varying dimensions
+    varying = int(cols.size) if L > 1 else 0
+    want_words = ctx.W if 4 * varying > 3 * D else (varying + 31) // 32
+    assert ctx.hdc_encoded_words() == want_words
+    ctx.close()
+
+
 # --------------------------------------------------------------------- online training
 def rel_err(got, want):
     scale = np.maximum(np.abs(want), 1e-3 * np.abs(want).max() + 1e-30)
