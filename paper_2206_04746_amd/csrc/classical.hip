@@ -257,6 +257,158 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
     }
 }
 
+// ---- small batches: grouping, counting and the update of acc in one launch ----------------------
+// Up to kFusedMaxN rows.  grid = (C, slices of 64 word columns), 16 waves per block.  A block takes
+// class c and one slice: it lists the rows of the class in LDS by itself (every block reads the few
+// thousand labels; a wave appends its matches with one LDS atomic), its 16 waves count a sixteenth
+// of those rows each with the same bit-sliced adders as accumulate_kernel (a couple of 8-row
+// batches per wave), the 16 counts are added pairwise through LDS in four rounds, and all waves
+// together turn the planes into integers and add them to acc[c][the slice's 2048 dimensions],
+// which this block alone owns (coalesced 8-byte read-modify-writes, the old values fetched at the
+// start).  Three launches and two scratch round trips less than the general path; fourteen
+// planes hold any count up to the row limit, whatever the class sizes.
+constexpr int kFusedMaxN = 8192;
+constexpr int kFusedPlanes = 14;
+static_assert(kFusedMaxN < (1 << kFusedPlanes), "a class may hold every row");
+constexpr size_t kFusedSlotWords = (size_t)kAccWaves * kFusedPlanes * kWave;   // one plane set per wave
+
+__global__ __launch_bounds__(kAccWaves *kWave) void accumulate_small_kernel(
+    const uint32_t *__restrict__ hv, const int32_t *__restrict__ labels, int N, int W, int D, int32_t *acc,
+    int64_t *class_n) {
+    extern __shared__ uint32_t sm[];   // plane sets [16][kFusedPlanes][64], then the row list (u16)
+    __shared__ uint32_t count;
+    uint16_t *list = reinterpret_cast<uint16_t *>(sm + kFusedSlotWords);
+    const int c = blockIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    if (threadIdx.x == 0) count = 0;
+    __syncthreads();
+    {   // a thread's labels all at once (the loads are independent), then the appends
+        constexpr int kPer = kFusedMaxN / (kAccWaves * kWave);
+        int lab[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int i = threadIdx.x + k * kAccWaves * kWave;
+            lab[k] = i < N ? labels[i] : -1;
+        }
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const bool hit = lab[k] == c;
+            const uint64_t m = __ballot(hit);
+            if (m) {   // uniform: one atomic per wave reserves room for its matches (any order: integer sums)
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&count, (uint32_t)__popcll(m));
+                base = __builtin_amdgcn_readfirstlane(base);
+                const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                if (hit) list[base + rank] = (uint16_t)(threadIdx.x + k * kAccWaves * kWave);
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t total = count;
+    if (total == 0) return;   // uniform
+    if (blockIdx.y == 0 && threadIdx.x == 0) class_n[c] += (int64_t)total;
+
+    // the two accumulators this lane will add to at the end, on their way while the rows are counted:
+    // wave g finishes word columns 4g .. 4g+3 of the slice, lane l bits 2 (l % 16), +1 of column l / 16
+    const int fcol = blockIdx.y * kSliceWords + wave * 4 + (lane >> 4);
+    const int fbit = (lane & 15) * 2;
+    const int64_t fd = (int64_t)fcol * 32 + fbit;
+    int32_t *fdst = acc + (int64_t)c * D + fd;
+    const bool pair = (D & 1) == 0 && (reinterpret_cast<uintptr_t>(acc) & 7u) == 0 && fd + 1 < D;
+    int2 old2 = make_int2(0, 0);
+    if (pair) {
+        old2 = *reinterpret_cast<const int2 *>(fdst);
+    } else {
+        if (fd < D) old2.x = fdst[0];
+        if (fd + 1 < D) old2.y = fdst[1];
+    }
+
+    const int col = blockIdx.y * kSliceWords + lane;
+    const bool in_range = col < W;
+    const uint32_t rb = ((total + kAccWaves - 1) / kAccWaves + 7) / 8 * 8;
+    const uint32_t first = (uint32_t)wave * rb;
+    const uint32_t rows = first < total ? min(rb, total - first) : 0u;
+
+    uint32_t pl[kFusedPlanes];
+#pragma unroll
+    for (int i = 0; i < kFusedPlanes; ++i) pl[i] = 0;
+    auto load8 = [&](uint32_t r0, uint32_t(&x)[8]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x[j] = 0;
+            if (r0 + j < rows && in_range) x[j] = hv[(int64_t)list[first + r0 + j] * W + col];   // row test: uniform
+        }
+    };
+    auto add8 = [&](const uint32_t(&x)[8]) {
+        uint32_t a, b, p, c2a, c2b, c3;
+        p = pl[0]; a = maj3(p, x[0], x[1]); p = xor3(p, x[0], x[1]);
+        b = maj3(p, x[2], x[3]); p = xor3(p, x[2], x[3]); pl[0] = p;
+        p = pl[1]; c2a = maj3(p, a, b); pl[1] = xor3(p, a, b);
+        p = pl[0]; a = maj3(p, x[4], x[5]); p = xor3(p, x[4], x[5]);
+        b = maj3(p, x[6], x[7]); p = xor3(p, x[6], x[7]); pl[0] = p;
+        p = pl[1]; c2b = maj3(p, a, b); pl[1] = xor3(p, a, b);
+        p = pl[2]; c3 = maj3(p, c2a, c2b); pl[2] = xor3(p, c2a, c2b);
+#pragma unroll
+        for (int i = 3; i < kFusedPlanes; ++i) {
+            const uint32_t t = pl[i] & c3;
+            pl[i] ^= c3;
+            c3 = t;
+        }
+    };
+    uint32_t xa[8], xb[8];
+    load8(0, xa);
+    for (uint32_t r0 = 0; r0 < rows; r0 += 16) {
+        load8(r0 + 8, xb);
+        add8(xa);
+        load8(r0 + 16, xa);
+        add8(xb);
+    }
+
+    // 16 plane sets -> 1: the upper half of the waves still in play parks its planes, the lower
+    // half adds them (ripple-carry adders on the planes; the class total fits, so the last carry
+    // is zero).  Every wave has a set of its own in LDS, so one barrier per round is enough.
+    uint32_t *mine = sm + (size_t)wave * kFusedPlanes * kWave + lane;
+#pragma unroll
+    for (int stride = kAccWaves / 2; stride >= 1; stride >>= 1) {
+        if (wave >= stride && wave < 2 * stride) {
+#pragma unroll
+            for (int i = 0; i < kFusedPlanes; ++i) mine[i * kWave] = pl[i];
+        }
+        __syncthreads();
+        if (wave < stride) {
+            const uint32_t *src = mine + (size_t)stride * kFusedPlanes * kWave;
+            uint32_t carry = 0;
+#pragma unroll
+            for (int i = 0; i < kFusedPlanes; ++i) {
+                const uint32_t a = pl[i], b = src[i * kWave];
+                pl[i] = xor3(a, b, carry);
+                carry = maj3(a, b, carry);
+            }
+        }
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < kFusedPlanes; ++i) mine[i * kWave] = pl[i];
+    }
+    __syncthreads();
+    // all waves: planes of set 0 -> two integers per lane -> acc
+    uint32_t v0 = 0, v1 = 0;
+    const uint32_t *fin = sm + (wave * 4 + (lane >> 4));
+#pragma unroll
+    for (int i = 0; i < kFusedPlanes; ++i) {
+        const uint32_t p = fin[i * kWave] >> fbit;
+        v0 |= (p & 1u) << i;
+        v1 |= ((p >> 1) & 1u) << i;
+    }
+    if (pair) {
+        *reinterpret_cast<int2 *>(fdst) = make_int2(old2.x + (int)v0, old2.y + (int)v1);
+    } else {
+        if (fd < D) fdst[0] = old2.x + (int)v0;
+        if (fd + 1 < D) fdst[1] = old2.y + (int)v1;
+    }
+}
+
 // acc[c][d] += sum over the class's partial rows.  grid = (dimension pairs / 256, C, K): the
 // K parts of a class's item range are combined with atomics only when K > 1.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__restrict__ partial,
@@ -356,6 +508,20 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
     AccPlan plan;
     const int prc = plan_static(c, &plan);
     if (prc != HDC_OK) return prc;
+    if (N <= kFusedMaxN) {
+        const size_t lds = kFusedSlotWords * sizeof(uint32_t) + (size_t)(N + 1) / 2 * 2 * sizeof(uint16_t);
+        static size_t raised = 64 * 1024;   // dynamic LDS the kernel is cleared for so far
+        if (lds > raised) {
+            HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(accumulate_small_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            raised = lds;
+        }
+        ProfScope prof(c, HDC_K_ACCUMULATE, s);
+        hipLaunchKernelGGL(accumulate_small_kernel, dim3((unsigned)C, (unsigned)(c->Wp / kSliceWords)),
+                           dim3(kAccWaves * kWave), lds, s, hv, labels, (int)N, c->W, c->p.D, acc, class_n);
+        HDC_HIP(hipGetLastError());
+        return HDC_OK;
+    }
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;

@@ -125,10 +125,15 @@ def gpu_classical(ctx, hv_d, y, acc=None, cn=None):
     return acc, cn
 
 
-# N > 32768 takes the multi-block grouping path, smaller batches the single-launch one
+# up to 8192 rows one fused launch does everything; up to 32768 one block groups the rows; beyond,
+# grouping runs over many blocks
 @pytest.mark.parametrize("D,C,N", [(1024, 5, 2000), (10000, 26, 6238), (10000, 2, 9000),
                                    (33, 1, 10), (2049, 7, 4100), (10000, 100, 700),
-                                   (10000, 2, 70001), (4000, 26, 40000), (64, 1000, 50000)])
+                                   (10000, 2, 70001), (4000, 26, 40000), (64, 1000, 50000),
+                                   # the fused launch at its row limit: everything in one or two classes,
+                                   # many classes, a dimension count that is no multiple of 4, very wide rows
+                                   (10000, 1, 8192), (10000, 2, 8192), (1024, 1000, 8000), (10001, 3, 5000),
+                                   (70000, 2, 300), (31, 4, 8192), (10000, 26, 8193)])
 def test_classical_accumulate_and_binarize_bit_exact(D, C, N):
     rng = np.random.default_rng(D + C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
