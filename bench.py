@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="diagnosis: do not bracket the hot kernels with events in the timed region (no roofline)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a 1 GiB device copy 10 times (known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -110,19 +112,26 @@ def main() -> int:
     for _ in range(Wm):
         step()
     torch.cuda.synchronize()
-    ctx.hdc_profile_enable(True)
-    for k in ("encode", "quantize", "accumulate", "search"):
-        ctx.hdc_profile_read(k)
-    torch.cuda.synchronize()
+    # ---- the timed region: exactly K steps, stage boundaries marked by four events per step
     t0 = time.perf_counter()
     for k in range(K):
         step(ev[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
+    # ---- the same K steps once more with every hot kernel bracketed by its own pair of events on
+    # the launch stream (hdc_profile_*): per-kernel durations for the roofline.  Kept out of the
+    # region above because the extra events hold the stream up between kernels (about 20 % of a
+    # step of this size); a kernel's own duration is the same in both passes and in
+    # profiles/bench_cfg2_kernel_stats.txt.
+    ctx.hdc_profile_enable(not args.no_kernel_events)
+    for k in ("encode", "quantize", "accumulate", "search"):
+        ctx.hdc_profile_read(k)
+    for k in range(K):
+        step()
+    torch.cuda.synchronize()
     prof = {k: ctx.hdc_profile_read(k) for k in ("encode", "quantize", "accumulate", "search")}
     ctx.hdc_profile_enable(False)
-
     t_train = np.array([e[0].elapsed_time(e[1]) for e in ev])    # ms: encode(train)+train+binarise
     t_enc_s = np.array([e[1].elapsed_time(e[2]) for e in ev])    # ms: encode(test)
     t_search = np.array([e[2].elapsed_time(e[3]) for e in ev])   # ms: search
