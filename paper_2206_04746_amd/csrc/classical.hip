@@ -421,8 +421,16 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__
     const uint32_t per = (i1 - i0 + K - 1) / K;
     const uint32_t a = min(i0 + blockIdx.z * per, i1), b = min(a + per, i1);
     uint32_t s0 = 0, s1 = 0;
-    for (uint32_t it = a; it < b; ++it) {
-        const uint32_t v = partial[(size_t)it * Wp * 16 + pair];
+    const uint32_t *src = partial + (size_t)a * Wp * 16 + pair;
+    const size_t step = (size_t)Wp * 16;
+    uint32_t it = a;
+    for (; it + 4 <= b; it += 4, src += 4 * step) {   // four independent loads in flight
+        const uint32_t v0 = src[0], v1 = src[step], v2 = src[2 * step], v3 = src[3 * step];
+        s0 += (v0 & 0xffffu) + (v1 & 0xffffu) + (v2 & 0xffffu) + (v3 & 0xffffu);
+        s1 += (v0 >> 16) + (v1 >> 16) + (v2 >> 16) + (v3 >> 16);
+    }
+    for (; it < b; ++it, src += step) {
+        const uint32_t v = *src;
         s0 += v & 0xffffu;
         s1 += v >> 16;
     }
@@ -447,16 +455,19 @@ struct AccPlan {
     int64_t rb_max;   // most rows per wave
     int64_t rows_max; // most rows one launch takes in a single round
 };
-static int plan_static(const hdc_ctx_impl *c, AccPlan *p) {
+static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
     const int nslices = c->Wp / kSliceWords;
     p->spb = nslices < kAccWaves ? nslices : kAccWaves;
     p->rg = kAccWaves / p->spb;
     p->ychunks = (nslices + p->spb - 1) / p->spb;
-    int bpc = 0;
-    const size_t lds = (size_t)(p->rg - 1) * p->spb * kWavePlanes * kWave * sizeof(uint32_t);
-    HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, reinterpret_cast<const void *>(accumulate_kernel),
-                                                         p->spb * p->rg * kWave, lds));
-    if (bpc < 1) bpc = 1;
+    int bpc = c->acc_bpc;
+    if (bpc == 0) {   // asked once per context: the block shape depends on D alone
+        const size_t lds = (size_t)(p->rg - 1) * p->spb * kWavePlanes * kWave * sizeof(uint32_t);
+        HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &bpc, reinterpret_cast<const void *>(accumulate_kernel), p->spb * p->rg * kWave, lds));
+        if (bpc < 1) bpc = 1;
+        c->acc_bpc = bpc;
+    }
     p->cap = (int64_t)c->num_cus * bpc / p->ychunks - c->p.C;
     if (p->cap < 1) p->cap = 1;
     p->rb_max = (4088 / p->rg) / 8 * 8;
@@ -470,7 +481,7 @@ static int64_t plan_rb(const AccPlan &p, int64_t n) {
     return rb < 16 ? 16 : (rb > p.rb_max ? p.rb_max : rb);
 }
 
-int64_t classical_max_items(const hdc_ctx_impl *c) {
+int64_t classical_max_items(hdc_ctx_impl *c) {
     AccPlan p;
     if (plan_static(c, &p) != HDC_OK) return -1;
     // full blocks of one round plus at most one partial block per class, with some slack
@@ -494,7 +505,7 @@ static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32
     }
     // enough threads for the reduction: split a class's partial rows K ways when C is small
     const int pairs = c->Wp * 16;
-    int K = (int)((32768 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
+    int K = (int)((262144 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
     K = K < 1 ? 1 : (K > 16 ? 16 : K);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)classes, (unsigned)K),
                        dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
@@ -510,11 +521,10 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
     if (prc != HDC_OK) return prc;
     if (N <= kFusedMaxN) {
         const size_t lds = kFusedSlotWords * sizeof(uint32_t) + (size_t)(N + 1) / 2 * 2 * sizeof(uint16_t);
-        static size_t raised = 64 * 1024;   // dynamic LDS the kernel is cleared for so far
-        if (lds > raised) {
+        if (lds > 64 * 1024 && lds > c->acc_small_lds) {
             HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(accumulate_small_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            raised = lds;
+            c->acc_small_lds = lds;
         }
         ProfScope prof(c, HDC_K_ACCUMULATE, s);
         hipLaunchKernelGGL(accumulate_small_kernel, dim3((unsigned)C, (unsigned)(c->Wp / kSliceWords)),

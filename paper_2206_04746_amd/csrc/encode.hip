@@ -296,11 +296,12 @@ static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uin
         if (k.S == S && k.P == P && k.waves == waves) v = &k;
     if (!v) return HDC_ELIMIT;
     const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
-    // Per variant, once: no static LDS allowed (the level-row offsets are absolute LDS
+    // Per variant, once per context: no static LDS allowed (the level-row offsets are absolute LDS
     // addresses), and how many blocks of it a CU holds (registers and LDS).
-    static int blocks_per_cu[sizeof(kVariants) / sizeof(kVariants[0])][2];   // [variant][L > 128]
-    int &bpc = blocks_per_cu[v - kVariants][0];
-    if (bpc == 0 || blocks_per_cu[v - kVariants][1] != c->p.L) {
+    static_assert(sizeof(kVariants) / sizeof(kVariants[0]) <= sizeof(c->enc_bpc) / sizeof(c->enc_bpc[0]),
+                  "one slot per variant");
+    int &bpc = c->enc_bpc[v - kVariants];
+    if (bpc == 0 || c->enc_bpc_L[v - kVariants] != c->p.L) {
         hipFuncAttributes attr;
         HDC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(v->fn)));
         if (attr.sharedSizeBytes != 0) return HDC_ELIMIT;
@@ -308,7 +309,7 @@ static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uin
         HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(v->fn),
                                                              waves * kWave, lds));
         bpc = n < 1 ? 1 : n;
-        blocks_per_cu[v - kVariants][1] = c->p.L;
+        c->enc_bpc_L[v - kVariants] = c->p.L;
     }
     // persistent grid: at most what the chip holds at once, sized so that the deal comes out
     // even - every wave gets k units (the last few k-1), never some waves one unit more than

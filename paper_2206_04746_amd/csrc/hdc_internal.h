@@ -81,6 +81,14 @@ struct hdc_ctx_impl {
     size_t ob_norm_bytes;
     bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised
 
+    // Launch properties looked up once per context (kept here, not in function-local statics,
+    // so that two contexts used from two threads share no mutable state).
+    int enc_bpc[16];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
+    int enc_bpc_L[16];      //   ... and the level count that answer was for
+    int acc_bpc;            // blocks of accumulate_kernel a CU holds (0 = not asked yet)
+    size_t acc_small_lds;   // dynamic LDS accumulate_small_kernel is cleared for so far
+    bool on_attr_set[16];   // online_lds_kernel<CMAX, .>: dynamic-LDS limit raised, by CMAX
+
     // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.
     bool prof_on;
     hipEvent_t *prof_ev[HDC_K_COUNT];   // [2 * HDC_PROFILE_SLOTS] start/stop interleaved
@@ -132,7 +140,7 @@ int launch_unpack(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, uint8_t *bits,
 int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
-int64_t classical_max_items(const hdc_ctx_impl *c);
+int64_t classical_max_items(hdc_ctx_impl *c);
 int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                   uint32_t *dist, int32_t *pred, hipStream_t s);
 

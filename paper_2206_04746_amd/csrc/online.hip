@@ -544,11 +544,11 @@ static int launch_online_lds(hdc_ctx_impl *c, const uint32_t *hv, const int32_t 
                              int32_t epochs, float lr, float *acc, hipStream_t s) {
     auto kern = online_lds_kernel<CMAX, KPT>;
     const size_t lds = (size_t)(CMAX + 2) * kOnlineThreads * sizeof(double);
-    static bool raised = false;
-    if (!raised && lds > 64 * 1024) {
+    static_assert(CMAX < (int)(sizeof(c->on_attr_set) / sizeof(c->on_attr_set[0])), "flag per CMAX");
+    if (!c->on_attr_set[CMAX] && lds > 64 * 1024) {
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        raised = true;
+        c->on_attr_set[CMAX] = true;
     }
     if (!c->on_bits_d) {
         HDC_HIP(hipSetDevice(c->device));
