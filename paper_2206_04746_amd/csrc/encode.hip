@@ -278,8 +278,8 @@ struct EncodeVariant {
     int S, P, waves;
 };
 #define HDC_VARIANTS(P) \
-    {encode_kernel<2, P, 4>, 2, P, 4}, {encode_kernel<4, P, 4>, 4, P, 4}, \
-    {encode_kernel<2, P, 8>, 2, P, 8}, {encode_kernel<4, P, 8>, 4, P, 8}
+    {encode_kernel<1, P, 4>, 1, P, 4}, {encode_kernel<2, P, 4>, 2, P, 4}, {encode_kernel<4, P, 4>, 4, P, 4}, \
+    {encode_kernel<1, P, 8>, 1, P, 8}, {encode_kernel<2, P, 8>, 2, P, 8}, {encode_kernel<4, P, 8>, 4, P, 8}
 static const EncodeVariant kVariants[] = {HDC_VARIANTS(8), HDC_VARIANTS(10), HDC_VARIANTS(12), HDC_VARIANTS(16)};
 #undef HDC_VARIANTS
 
@@ -288,9 +288,9 @@ static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uin
                                 int P, int N, uint32_t *hv, uint32_t bias, hipStream_t s) {
     const int nslices = Wp / kSliceWords;
     const int waves = c->p.L > 128 ? 8 : 4;   // a big level slice: fewer, larger blocks per CU
-    // small batches take 2-sample units so that there are enough of them for 1024 SIMDs
-    // (measured crossover: about 3 four-sample units per SIMD)
-    const int S = ((int64_t)((N + 3) / 4) * nslices >= 3072) ? 4 : 2;
+    // small batches take 2-sample or 1-sample units so that there are enough of them for 1024
+    // SIMDs (measured crossovers: about 3 four-sample units, 2.5 two-sample units per SIMD)
+    const int S = ((int64_t)((N + 3) / 4) * nslices >= 3072) ? 4 : ((int64_t)((N + 1) / 2) * nslices >= 2560) ? 2 : 1;
     const EncodeVariant *v = nullptr;
     for (const EncodeVariant &k : kVariants)
         if (k.S == S && k.P == P && k.waves == waves) v = &k;

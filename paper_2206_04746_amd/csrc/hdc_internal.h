@@ -83,8 +83,8 @@ struct hdc_ctx_impl {
 
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).
-    int enc_bpc[16];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
-    int enc_bpc_L[16];      //   ... and the level count that answer was for
+    int enc_bpc[24];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
+    int enc_bpc_L[24];      //   ... and the level count that answer was for
     int acc_bpc;            // blocks of accumulate_kernel a CU holds (0 = not asked yet)
     size_t acc_small_lds;   // dynamic LDS accumulate_small_kernel is cleared for so far
     bool on_attr_set[16];   // online_lds_kernel<CMAX, .>: dynamic-LDS limit raised, by CMAX
