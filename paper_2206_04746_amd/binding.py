@@ -21,7 +21,7 @@ HDC_OK, HDC_EINVAL, HDC_ENOMEM, HDC_EHIP, HDC_ELIMIT = 0, -1, -2, -3, -4
 HDC_F32, HDC_U8 = 0, 1
 
 # every symbol include/hdc.h declares
-SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
+SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_encode_sparse", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
            "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_encoded_words",
            "hdc_profile_enable", "hdc_profile_read",
@@ -52,6 +52,7 @@ def _load() -> ctypes.CDLL:
     lib.hdc_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(HdcParams), vp, vp, vp, vp, vp]
     lib.hdc_destroy.argtypes = [vp]
     lib.hdc_encode.argtypes = [vp, vp, i64, vp, vp]
+    lib.hdc_encode_sparse.argtypes = [vp, vp, i64, vp, vp]
     lib.hdc_train_classical.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.hdc_binarize_classical.argtypes = [vp, vp, vp, vp, vp]
     lib.hdc_train_online.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp]
@@ -68,7 +69,7 @@ def _load() -> ctypes.CDLL:
                                      ctypes.POINTER(ctypes.c_int64)]
     lib.hdc_profile_enable.restype = ctypes.c_int
     lib.hdc_profile_read.restype = ctypes.c_int
-    for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_train_classical",
+    for name in ("hdc_create", "hdc_destroy", "hdc_encode", "hdc_encode_sparse", "hdc_train_classical",
                  "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched",
                  "hdc_binarize_online", "hdc_search", "hdc_search_cosine", "hdc_pack", "hdc_unpack",
                  "hdc_hsum", "hdc_vsum"):
@@ -152,6 +153,11 @@ class Context:
         N = feats.shape[0]
         _check(lib.hdc_encode(self._h, _dev(feats, self._torch_feat, (N, self.F)), N,
                               _dev(hv, torch.int32, (N, self.W)), _stream(stream)))
+
+    def hdc_encode_sparse(self, feats: torch.Tensor, hv: torch.Tensor, stream=None) -> None:
+        N = feats.shape[0]
+        _check(lib.hdc_encode_sparse(self._h, _dev(feats, self._torch_feat, (N, self.F)), N,
+                                     _dev(hv, torch.int32, (N, self.W)), _stream(stream)))
 
     def hdc_train_classical(self, hv, labels, acc, class_n, stream=None) -> None:
         N = hv.shape[0]

@@ -28,7 +28,8 @@ static void free_ctx(hdc_ctx_impl *c) {
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d,
                     c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d,
-                    c->citem_d, c->clevel_d, c->hvc_d, c->expand_d};
+                    c->citem_d, c->clevel_d, c->hvc_d, c->expand_d,
+                    c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -319,6 +320,14 @@ int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev,
     if (!feats_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
     if (impl(ctx)->p.feat_dtype == HDC_F32 && !aligned4(feats_dev)) return HDC_EINVAL;
     return launch_encode(impl(ctx), feats_dev, N, hv_dev, static_cast<hipStream_t>(stream));
+}
+
+int hdc_encode_sparse(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream) {
+    if (!ctx || N < 0) return HDC_EINVAL;
+    if (N == 0) return HDC_OK;
+    if (!feats_dev || !hv_dev || !aligned4(hv_dev)) return HDC_EINVAL;
+    if (impl(ctx)->p.feat_dtype == HDC_F32 && !aligned4(feats_dev)) return HDC_EINVAL;
+    return launch_encode_sparse(impl(ctx), feats_dev, N, hv_dev, static_cast<hipStream_t>(stream));
 }
 
 int32_t hdc_encoded_words(const hdc_ctx *ctx) {

@@ -81,6 +81,15 @@ struct hdc_ctx_impl {
     size_t ob_norm_bytes;
     bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised
 
+    // hdc_encode_sparse (allocated and derived on its first call)
+    bool sp_ready;
+    uint32_t *sp_b_d;       // [slices][Fp][64] item ^ level 0 (of the compact tables when `compact`)
+    uint32_t *sp_e_d;       // [slices][L][64]  level ^ level 0
+    uint32_t *sp_base_d;    // [slices][P][64]  bit-sliced counters of the all-bin-0 sample, bias included
+    uint32_t *sp_fb_d;      // [q_rows][Fp]     listed features' row offsets in a slice of sp_b_d
+    uint32_t *sp_blocks_d;  // [q_rows]         16-entry blocks per sample
+    int sp_bpc;             // blocks of encode_sparse_kernel a CU holds (0 = not asked yet)
+
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).
     int enc_bpc[24];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
@@ -124,6 +133,9 @@ int hip_fail(hipError_t e, const char *what);
 
 // Kernel launchers (one per translation unit); all only enqueue on `s`.
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s);
+int launch_encode_sparse(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s);
+void majority_planes(const hdc_ctx_impl *c, int *P_out, uint32_t *bias_out);   // planes and start value of a vote counter
+void launch_expand(hdc_ctx_impl *c, int64_t n, uint32_t *out, hipStream_t s);  // compact staging rows -> full rows
 int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                            int32_t *acc, int64_t *class_n, hipStream_t s);
 int launch_binarize_classical(hdc_ctx_impl *c, const int32_t *acc, const int64_t *class_n,
