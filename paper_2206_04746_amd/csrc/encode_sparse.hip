@@ -21,6 +21,15 @@
 
 namespace hdc {
 
+// Scalar loads are asked for a block ahead of their use: wait_scalar_loads() at the top of a trip
+// (for what was issued a trip ago) and pin_schedule() after new loads have been issued keep the
+// compiler from moving either next to the other.
+__device__ __forceinline__ void wait_scalar_loads() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+}
+__device__ __forceinline__ void pin_schedule() { __builtin_amdgcn_sched_barrier(0); }
+
 // ---- tables, derived on the device from the tables the dense kernel uses ------------------------
 // dst[slice][r][64] = src[slice][r][64] ^ ref[slice][0][64]
 __global__ __launch_bounds__(256) void xor_row0_kernel(const uint32_t *__restrict__ src,
@@ -72,22 +81,41 @@ __global__ __launch_bounds__(kListWaves *kWave) void sparse_lists_kernel(
     uint16_t *qrow = qa + n * Fp;
     uint32_t *frow = fb + n * Fp;
     int listed = 0;
-    for (int f0 = 0; f0 < F; f0 += kWave) {
-        const int f = f0 + lane;
-        uint32_t bin = 0;
-        if (f < F) {
+    constexpr int kAhead = 8;   // feature chunks of 64 whose values are fetched together
+    for (int f0 = 0; f0 < F; f0 += kAhead * kWave) {
+        // all loads first, at clamped indices (what is fetched for f >= F is dropped below)
+        float xf[kAhead];
+        uint32_t xb[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int f = min(f0 + u * kWave + lane, F - 1);
             if (kU8)
-                bin = ((uint32_t) reinterpret_cast<const uint8_t *>(feats)[n * F + f] * (uint32_t)L) >> 8;
+                xb[u] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
             else
-                bin = bin_f32(reinterpret_cast<const float *>(feats)[n * F + f], lo[f], scale[f], L);
+                xf[u] = reinterpret_cast<const float *>(feats)[n * F + f];
         }
-        const uint64_t hits = __ballot(bin != 0);
-        if (bin != 0) {
-            const int k = listed + __popcll(hits & ((1ull << lane) - 1ull));
-            qrow[k] = (uint16_t)(bin * (kSliceWords * 4u));
-            frow[k] = (uint32_t)f * (kSliceWords * 4u);
+        float lo_u[kAhead], sc_u[kAhead];
+        if (!kU8) {
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int f = min(f0 + u * kWave + lane, F - 1);
+                lo_u[u] = lo[f];
+                sc_u[u] = scale[f];
+            }
         }
-        listed += __popcll(hits);
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int f = f0 + u * kWave + lane;
+            uint32_t bin = kU8 ? (xb[u] * (uint32_t)L) >> 8 : bin_f32(xf[u], lo_u[u], sc_u[u], L);
+            if (f >= F) bin = 0;
+            const uint64_t hits = __ballot(bin != 0);
+            if (bin != 0) {
+                const int k = listed + __popcll(hits & ((1ull << lane) - 1ull));
+                qrow[k] = (uint16_t)(bin * (kSliceWords * 4u));
+                frow[k] = (uint32_t)f * (kSliceWords * 4u);
+            }
+            listed += __popcll(hits);
+        }
     }
     const int padded = (listed + 15) & ~15;   // <= Fp, which is a multiple of 16 and >= F
     if (listed + lane < padded) {
@@ -100,10 +128,12 @@ __global__ __launch_bounds__(kListWaves *kWave) void sparse_lists_kernel(
 // ---- bundling -------------------------------------------------------------------------------------
 // Same block shape as encode_kernel: WAVES waves on one slice of 64 word columns, the slice of e
 // in dynamic LDS (no static LDS: the listed bin offsets are absolute LDS addresses), persistent
-// blocks, samples dealt round-robin to the waves.  Rows of b come from global memory (L2): the
-// row offset of a listed feature is wave-uniform and goes into the scalar offset of a buffer load,
-// the lane's column into its vector offset, so no address arithmetic runs on the vector unit.  The
-// rows of the next block of 16 entries are requested before the current block is bundled.
+// blocks, samples dealt round-robin to the waves.  Rows of b come from global memory (L1 / L2, the
+// table is a few hundred KB): one 64-bit add per listed entry forms the lane's address from the
+// wave-uniform row offset.  (Buffer loads that take the row offset as their scalar offset need no
+// such add but measured 9 % slower: the kernel is bound by the issue of these loads, about one per
+// 5 clocks per CU, not by the vector ALU.)  The rows of the next block of 16 entries are requested
+// before the current block is bundled.
 template <int P, int WAVES>
 __global__ __launch_bounds__(WAVES *kWave) void encode_sparse_kernel(
     const uint16_t *__restrict__ qa, const uint32_t *__restrict__ fb, const uint32_t *__restrict__ blocks,
@@ -120,10 +150,8 @@ __global__ __launch_bounds__(WAVES *kWave) void encode_sparse_kernel(
     }
     __syncthreads();
 
-    // this slice of b as a raw buffer: offsets beyond its Fp rows read as zero instead of faulting
-    const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t *>(b + (size_t)slice * Fp * kSliceWords), 0, Fp * kSliceWords * 4, 0x00020000);
-    const int lane_bytes = lane * 4;
+    // this lane's column of this slice of b; a listed row offset f * 256 (f < F) stays inside it
+    const char *bcol = reinterpret_cast<const char *>(b + (size_t)slice * Fp * kSliceWords + lane);
     uint32_t start[P];
 #pragma unroll
     for (int i = 0; i < P; ++i) start[i] = base[((size_t)slice * P + i) * kSliceWords + lane];
@@ -148,24 +176,26 @@ __global__ __launch_bounds__(WAVES *kWave) void encode_sparse_kernel(
             }
         }
 
-        // request the 16 rows of b of entry block `blk` (clamped: a request past the last block
-        // repeats it and is dropped)
-        auto request = [&](int blk, uint32_t (&w)[16]) {
+        // Entry block `blk` of this sample (clamped: a block past the last repeats it, and what is
+        // fetched for it is dropped): its 16 row offsets / its 8 pairs of bin offsets, by scalar loads.
+        auto offsets_of = [&](int blk, uint32_t (&so)[16]) {
             const int at = (blk < nb ? blk : nb - 1) * 16;
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                w[j] = __builtin_amdgcn_raw_buffer_load_b32(rows, lane_bytes, (int)frow[at + j], 0);
-            // the requests stay here: left to itself the scheduler moves them down to their first
-            // use, behind the bundling they are meant to overlap with
-            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < 16; ++j) so[j] = frow[at + j];
         };
-        // bundle entry block `blk`, whose rows of b are in w
-        auto bundle = [&](int blk, const uint32_t (&w)[16]) {
-            uint32_t qpair[8];
+        auto bins_of = [&](int blk, uint32_t (&qp)[8]) {
+            const int at = (blk < nb ? blk : nb - 1) * 8;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) qpair[k] = qrow[blk * 8 + k];
-            uint32_t x[16];
-            gather16(x, qpair);   // the e rows of the 16 entries
+            for (int k = 0; k < 8; ++k) qp[k] = qrow[at + k];
+        };
+        // request the 16 rows of b at the byte offsets `so`
+        auto request = [&](const uint32_t (&so)[16], uint32_t (&w)[16]) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                w[j] = *reinterpret_cast<const uint32_t *>(bcol + so[j]);
+        };
+        // bundle an entry block: bin offsets qp, rows of b in w
+        auto bundle = [&](const uint32_t (&x)[16], const uint32_t (&w)[16]) {
             uint32_t c2[16];
             uint32_t p0 = pl[0];
 #pragma unroll
@@ -179,18 +209,39 @@ __global__ __launch_bounds__(WAVES *kWave) void encode_sparse_kernel(
         };
 
         if (nb > 0) {
-            // two blocks per trip, nothing conditional inside (a request whose only use sits in
-            // a branch would be moved into that branch, behind the bundling it should overlap)
-            uint32_t wa[16], wb[16];
-            request(0, wa);
+            // Two blocks per trip (A even, B odd), nothing conditional inside.  Everything a block
+            // needs is asked for a block or more ahead: its row offsets two blocks ahead (scalar
+            // loads), its rows of b one block ahead (buffer loads at those offsets), its bin
+            // offsets two blocks ahead.  Scalar loads are issued right after a gather has waited
+            // on the LDS counter, so the next such wait finds them long done.
+            uint32_t wa[16], wb[16], so_a[16], so_b[16], qa_[8], qb_[8], x[16];
+            offsets_of(0, so_a);
+            offsets_of(1, so_b);
+            bins_of(0, qa_);
+            bins_of(1, qb_);
+            request(so_a, wa);              // (waits for so_a)
+            offsets_of(2, so_a);
+            pin_schedule();
             int blk = 0;
             for (; blk + 1 < nb; blk += 2) {
-                request(blk + 1, wb);
-                bundle(blk, wa);
-                request(blk + 2, wa);
-                bundle(blk + 1, wb);
+                wait_scalar_loads();
+                request(so_b, wb);          // rows of block blk + 1
+                gather16(x, qa_);           // e rows of block blk
+                offsets_of(blk + 3, so_b);
+                bins_of(blk + 2, qa_);
+                pin_schedule();
+                bundle(x, wa);
+                request(so_a, wa);          // rows of block blk + 2
+                gather16(x, qb_);           // e rows of block blk + 1
+                offsets_of(blk + 4, so_a);
+                bins_of(blk + 3, qb_);
+                pin_schedule();
+                bundle(x, wb);
             }
-            if (blk < nb) bundle(blk, wa);
+            if (blk < nb) {
+                gather16(x, qa_);
+                bundle(x, wa);
+            }
         }
         if (col < W) hv[(int64_t)n * W + col] = pl[P - 1];
     }
