@@ -293,6 +293,23 @@ def extras(torch, binding, make_workload):
                               "note": "whole hdc_encode (quantise + bundle + expand) against the words the kernel bundles"}
     ctx.close()
     del hv, y, pred, x5d, hv5
+    # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): the dense
+    # encoder against the one that bundles only the features that leave bin 0 (same bits out)
+    wl3 = make_workload(3)
+    ctx = binding.Context(wl3.D, wl3.F, wl3.L, wl3.C, wl3.item, wl3.level, wl3.tie, wl3.lo, wl3.scale, wl3.dtype)
+    x3, _ = wl3.train()
+    x3d = torch.from_numpy(x3).to(dev)
+    n3 = x3.shape[0]
+    hv3 = torch.empty((n3, ctx.W), dtype=torch.int32, device=dev)
+    ms_d = _timed(torch, lambda: ctx.hdc_encode(x3d, hv3), 3)
+    ms_s = _timed(torch, lambda: ctx.hdc_encode_sparse(x3d, hv3), 3)
+    res["encode_cfg3_dense_vs_sparse"] = {
+        "samples": n3, "features_not_in_bin0": round(float((x3 != 0).mean()), 4),
+        "dense_ms": round(ms_d, 4), "dense_samples_per_s": round(n3 / ms_d * 1e3, 0),
+        "sparse_ms": round(ms_s, 4), "sparse_samples_per_s": round(n3 / ms_s * 1e3, 0),
+        "speedup": round(ms_d / ms_s, 2)}
+    ctx.close()
+    del x3d, hv3
     # --- config 4 shape: online training, one epoch over 7352 samples (a dependency chain)
     wl4 = make_workload(4)
     ctx = binding.Context(wl4.D, wl4.F, wl4.L, wl4.C, wl4.item, wl4.level, wl4.tie, wl4.lo, wl4.scale, wl4.dtype)
