@@ -287,15 +287,16 @@ constexpr int64_t kFewQueries = 8192;   // below this the one-tile-per-block ker
 template <int WPL, int G>
 static int launch_search_shape(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                                uint32_t *dist, int32_t *pred, hipStream_t s) {
-    if (N < kFewQueries) {
+    // class vectors too many for LDS: the few-query kernel reads them from global memory and is
+    // correct for any number of queries
+    const size_t lds = (size_t)c->p.C * WPL * kWave * 4;
+    if (N < kFewQueries || lds > 160 * 1024) {
         ProfScope prof(c, HDC_K_SEARCH, s);
         hipLaunchKernelGGL(search_few_kernel<WPL>, dim3((unsigned)((N + kRows - 1) / kRows)),
                            dim3(kSearchWaves * kWave), 0, s, hv, N, class_hv, c->p.C, c->W, dist, pred);
         HDC_HIP(hipGetLastError());
         return HDC_OK;
     }
-    const size_t lds = (size_t)c->p.C * WPL * kWave * 4;
-    if (lds > 160 * 1024) return HDC_ELIMIT;
     auto kern = search_kernel<WPL, G>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -166,7 +166,9 @@ def test_classical_accumulate_and_binarize_bit_exact(D, C, N):
                                    (10000, 10, 1000), (10000, 6, 2947), (33, 1, 7), (31, 17, 66),
                                    (2049, 16, 129), (20000, 33, 50), (32768, 3, 20), (10000, 100, 64),
                                    # from 8192 queries on: the kernel that stages the class vectors in LDS
-                                   (10000, 26, 9000), (2049, 16, 8193), (20000, 33, 8192), (31, 17, 20000)])
+                                   (10000, 26, 9000), (2049, 16, 8193), (20000, 33, 8192), (31, 17, 20000),
+                                   # class vectors larger than LDS: read from global memory at any N
+                                   (10000, 200, 8200), (4096, 1024, 8192)])
 def test_search_bit_exact(D, C, N):
     rng = np.random.default_rng(D * 7 + C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
