@@ -181,6 +181,7 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
  *   pred[n]    = lowest c with the smallest dist[n][c].
  *   hv_dev [N][W], class_hv_dev [C][W] (pad bits zero), dist_dev [N][C] uint32 out or
  *   NULL when only predictions are wanted, pred_dev [N] int32 out (required).
+ * D <= 32768 (a query row is held in the registers of one wave; HDC_ELIMIT beyond).
  */
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream);

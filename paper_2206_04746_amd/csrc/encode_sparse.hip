@@ -284,7 +284,14 @@ static int prepare_sparse(hdc_ctx_impl *c, int P, uint32_t bias, hipStream_t s) 
     if (rc == HDC_OK) rc = alloc(reinterpret_cast<void **>(&c->sp_base_d), (size_t)nslices * P * kSliceWords * 4);
     if (rc == HDC_OK) rc = alloc(reinterpret_cast<void **>(&c->sp_fb_d), (size_t)c->q_rows * c->Fp * 4);
     if (rc == HDC_OK) rc = alloc(reinterpret_cast<void **>(&c->sp_blocks_d), (size_t)c->q_rows * 4);
-    if (rc != HDC_OK) return rc;
+    if (rc != HDC_OK) {   // all or nothing: a later call starts over
+        uint32_t **owned[] = {&c->sp_b_d, &c->sp_e_d, &c->sp_base_d, &c->sp_fb_d, &c->sp_blocks_d};
+        for (uint32_t **p : owned) {
+            if (*p) (void)hipFree(*p);
+            *p = nullptr;
+        }
+        return rc;
+    }
     const int64_t nb = (int64_t)c->Fp * Wp, ne = (int64_t)c->p.L * Wp;
     hipLaunchKernelGGL(xor_row0_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, item, level, c->Fp,
                        c->p.L, nslices, c->sp_b_d);

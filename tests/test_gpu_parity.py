@@ -329,6 +329,16 @@ def test_argument_errors_are_reported_not_faulted():
         == b.HDC_EINVAL
     assert b.lib.hdc_encode(ctx._h, None, 0, None, None) == b.HDC_OK      # N == 0 is a no-op
     ctx.close()
+    # beyond the documented dimension limit of search and per-sample online training: an error code
+    big = make_workload(1, D=40000, F=4, L=4, C=2)
+    ctx = make_ctx(big)
+    hv = torch.zeros((4, ctx.W), dtype=torch.int32, device="cuda")
+    pred = torch.zeros(4, dtype=torch.int32, device="cuda")
+    acc = torch.zeros((2, 40000), dtype=torch.float32, device="cuda")
+    assert b.lib.hdc_search(ctx._h, hv.data_ptr(), 4, hv.data_ptr(), None, pred.data_ptr(), None) == b.HDC_ELIMIT
+    assert b.lib.hdc_train_online(ctx._h, hv.data_ptr(), pred.data_ptr(), 4, 1, 1.0, acc.data_ptr(), None) \
+        == b.HDC_ELIMIT
+    ctx.close()
 
 
 # ------------------------------------------------- full sizes of the BASELINE configurations
