@@ -203,6 +203,80 @@ __global__ __launch_bounds__(WAVES * kWave) void encode_kernel(
     }
 }
 
+// Few samples: with a sample (or a few) per wave there are not enough waves to keep the vector
+// units busy, and a lone wave runs at the pace of its dependent instructions.  Here the WAVES waves
+// of a block share ONE sample of the block's slice: wave w bundles its share of the half-blocks of
+// 16 features into planes of its own (wave 0's start at the bias), waves 1.. park theirs in LDS,
+// and wave 0 adds them up (ripple-carry over the planes) and stores the majority word.  One
+// barrier per sample: the merge area behind the level slice is double-buffered by sample parity.
+// Every wave of a block makes the same trips, so the barrier is reached by all.
+template <int P, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void encode_split_kernel(
+    const uint16_t *__restrict__ q, const uint32_t *__restrict__ item,
+    const uint32_t *__restrict__ level, uint32_t *__restrict__ hv, int N, int Fp, int L, int W,
+    uint32_t bias) {
+    extern __shared__ uint32_t lv[];   // level slice [L][64] at address 0, then merge [2][WAVES - 1][P][64]
+    const int slice = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int col = slice * kSliceWords + lane;
+    {
+        const uint32_t *src = level + (size_t)slice * L * kSliceWords;
+        for (int i = threadIdx.x; i < L * kSliceWords; i += WAVES * kWave) lv[i] = src[i];
+    }
+    __syncthreads();
+    uint32_t *merge = lv + (size_t)L * kSliceWords;
+
+    const uint32_t lane_bytes = (uint32_t)lane * 4u;
+    const char *item_slice = reinterpret_cast<const char *>(item + (size_t)slice * Fp * kSliceWords);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nhb = Fp / kFeatBlock;                      // half-blocks of 16 features
+    const int hb0 = wave * nhb / WAVES, hb1 = (wave + 1) * nhb / WAVES;
+
+    int parity = 0;
+    for (int n = blockIdx.y; n < N; n += (int)gridDim.y, parity ^= 1) {
+        uint32_t pl[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i) pl[i] = (wave == 0 && ((bias >> i) & 1u)) ? 0xffffffffu : 0u;
+        const_u32_ptr qrow = (const_u32_ptr)(uintptr_t)(q + (int64_t)n * Fp);
+        for (int hb = hb0; hb < hb1; ++hb) {
+            const int f = hb * kFeatBlock;
+            const char *base = item_slice + (size_t)f * (kSliceWords * 4);
+            uint32_t id[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                id[j] = *reinterpret_cast<const uint32_t *>(base + j * (kSliceWords * 4) + lane_bytes);
+            uint32_t qpair[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) qpair[k] = qrow[(f >> 1) + k];
+            uint32_t x[16];
+            gather16(x, qpair);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j] ^= id[j];
+            ripple<4, P>(pl, Tree<4, 0>::run(pl, x));
+        }
+        if (wave > 0) {
+            uint32_t *dst = merge + ((size_t)(parity * (WAVES - 1) + wave - 1) * P) * kSliceWords + lane;
+#pragma unroll
+            for (int i = 0; i < P; ++i) dst[i * kSliceWords] = pl[i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll 1
+            for (int w = 0; w < WAVES - 1; ++w) {
+                const uint32_t *src = merge + ((size_t)(parity * (WAVES - 1) + w) * P) * kSliceWords + lane;
+                uint32_t carry = 0;
+#pragma unroll
+                for (int i = 0; i < P; ++i) {
+                    const uint32_t a = pl[i], b = src[i * kSliceWords];
+                    pl[i] = xor3(a, b, carry);
+                    carry = maj3(a, b, carry);
+                }
+            }
+            if (col < W) hv[(int64_t)n * W + col] = pl[P - 1];
+        }
+    }
+}
+
 typedef void (*encode_fn)(const uint16_t *, const uint32_t *, const uint32_t *, uint32_t *, int, int, int,
                           int, uint32_t);
 struct EncodeVariant {
@@ -223,11 +297,45 @@ static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uin
     // small batches take 2-sample or 1-sample units so that there are enough of them for 1024
     // SIMDs (measured crossovers: about 3 four-sample units, 2.5 two-sample units per SIMD)
     const int S = ((int64_t)((N + 3) / 4) * nslices >= 3072) ? 4 : ((int64_t)((N + 1) / 2) * nslices >= 2560) ? 2 : 1;
+    const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
+    // Too few samples for a sample per wave: the waves of a block share one (measured against the
+    // one-sample units: faster up to about 2000 sample-slices; 16 waves per sample for a handful
+    // of samples - a single sample encodes in 8 us instead of 21 - and 8 beyond).
+    if (S == 1 && (int64_t)N * nslices <= 2048) {
+        const int which = (int64_t)N * nslices <= 256 ? 1 : 0;
+        const int kSplitWaves = which ? 16 : 8;
+#define HDC_SPLIT(W_) (P == 8 ? encode_split_kernel<8, W_> : P == 10 ? encode_split_kernel<10, W_> \
+                       : P == 12 ? encode_split_kernel<12, W_> : encode_split_kernel<16, W_>)
+        encode_fn fn = which ? HDC_SPLIT(16) : HDC_SPLIT(8);
+#undef HDC_SPLIT
+        const size_t lds_split = lds + (size_t)2 * (kSplitWaves - 1) * P * kSliceWords * sizeof(uint32_t);
+        if (c->enc_split_bpc[which] == 0 || c->enc_split_L[which] != c->p.L) {
+            hipFuncAttributes attr;
+            HDC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(fn)));
+            if (attr.sharedSizeBytes != 0) return HDC_ELIMIT;
+            if (lds_split > 64 * 1024)
+                HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_split));
+            int n = 0;
+            HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(fn),
+                                                                 kSplitWaves * kWave, lds_split));
+            c->enc_split_bpc[which] = n < 1 ? 1 : n;
+            c->enc_split_L[which] = c->p.L;
+        }
+        int per_slice = (c->num_cus * c->enc_split_bpc[which]) / nslices;
+        if (per_slice < 1) per_slice = 1;
+        if (per_slice > N) per_slice = N;
+        const int k = (N + per_slice - 1) / per_slice;   // samples per block, evened out
+        per_slice = (N + k - 1) / k;
+        ProfScope prof(c, HDC_K_ENCODE, s);
+        hipLaunchKernelGGL(fn, dim3((unsigned)nslices, (unsigned)per_slice), dim3(kSplitWaves * kWave), lds_split, s,
+                           c->q_d, item, level, hv, N, c->Fp, c->p.L, W, bias);
+        return HDC_OK;
+    }
     const EncodeVariant *v = nullptr;
     for (const EncodeVariant &k : kVariants)
         if (k.S == S && k.P == P && k.waves == waves) v = &k;
     if (!v) return HDC_ELIMIT;
-    const size_t lds = (size_t)c->p.L * kSliceWords * sizeof(uint32_t);
     // Per variant, once per context: no static LDS allowed (the level-row offsets are absolute LDS
     // addresses), and how many blocks of it a CU holds (registers and LDS).
     static_assert(sizeof(kVariants) / sizeof(kVariants[0]) <= sizeof(c->enc_bpc) / sizeof(c->enc_bpc[0]),

@@ -94,6 +94,8 @@ struct hdc_ctx_impl {
     // so that two contexts used from two threads share no mutable state).
     int enc_bpc[24];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
     int enc_bpc_L[24];      //   ... and the level count that answer was for
+    int enc_split_bpc[2];   // blocks of encode_split_kernel (8 / 16 waves) a CU holds (0 = not asked yet) ...
+    int enc_split_L[2];     //   ... and the level count that answer was for
     int acc_bpc;            // blocks of accumulate_kernel a CU holds (0 = not asked yet)
     size_t acc_small_lds;   // dynamic LDS accumulate_small_kernel is cleared for so far
     bool on_attr_set[16];   // online_lds_kernel<CMAX, .>: dynamic-LDS limit raised, by CMAX

@@ -83,6 +83,22 @@ def test_encode_ragged_shapes_bit_exact(D, F, L, N):
     ctx.close()
 
 
+# few samples: the waves of a block share one sample (16 waves each up to 256 sample-slices, 8 up
+# to 2048, one-sample units beyond); feature counts chosen to need 8, 10, 12 and 16 count planes
+# and half-block counts that do not divide by the waves
+@pytest.mark.parametrize("D,F,L,N", [
+    (10000, 617, 64, 1), (10000, 617, 64, 2), (10000, 617, 64, 85), (10000, 617, 64, 86),
+    (10000, 617, 64, 682), (10000, 617, 64, 683), (10000, 100, 16, 40), (10000, 1100, 7, 30),
+    (2048, 5000, 9, 5), (2048, 5000, 9, 70), (100, 15, 256, 300), (64, 1, 2, 3000), (4100, 784, 256, 25),
+])
+def test_encode_few_samples_bit_exact(D, F, L, N):
+    wl = make_workload(2, seed=D + F + N, D=D, F=F, L=L, n_train=N)
+    x, _ = wl.train(N)
+    ctx = make_ctx(wl)
+    assert np.array_equal(host_u32(gpu_encode(ctx, x)), orc_encode(wl, x))
+    ctx.close()
+
+
 def test_encode_u8_levels_and_random_tables():
     rng = np.random.default_rng(5)
     for L in (256, 100, 2):
