@@ -191,7 +191,7 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
             x[j] = 0;
             if (r0 + j < rows && in_range) {   // the row test is wave-uniform
                 const uint32_t *row = hv + (int64_t)idx[r0 + j] * W;
-                x[j] = row[col];
+                x[j] = __builtin_nontemporal_load(row + col);
             }
         }
     };

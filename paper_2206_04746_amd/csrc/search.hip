@@ -96,7 +96,7 @@ __device__ __forceinline__ uint32_t row_min(uint32_t k) {
 // This lane's words of kRows query rows starting at row n0 (rows past N repeat row N - 1, columns
 // past W read as zero).  Clamped addresses and a select instead of a branch around each load: all
 // loads are in flight together.
-template <int WPL>
+template <int WPL, bool kStream>
 __device__ __forceinline__ void load_rows(const uint32_t *__restrict__ hv, int64_t n0, int64_t N, int W, int lane,
                                           uint32_t (&x)[kRows][WPL]) {
 #pragma unroll
@@ -106,7 +106,7 @@ __device__ __forceinline__ void load_rows(const uint32_t *__restrict__ hv, int64
 #pragma unroll
         for (int j = 0; j < WPL; ++j) {
             const int w = lane + j * kWave;
-            const uint32_t v = row[w < W ? w : W - 1];
+            const uint32_t v = kStream ? __builtin_nontemporal_load(row + (w < W ? w : W - 1)) : row[w < W ? w : W - 1];
             x[r][j] = w < W ? v : 0u;
         }
     }
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kSearchWaves * kWave) void search_kernel(
          t += (int64_t)gridDim.x * kSearchWaves) {
         const int64_t n0 = t * kRows;
         uint32_t x[kRows][WPL];
-        load_rows<WPL>(hv, n0, N, W, lane, x);
+        load_rows<WPL, true>(hv, n0, N, W, lane, x);   // a million queries pass once: not worth caching
         uint32_t best_key = 0xffffffffu;
         for (int c0 = 0; c0 < C; c0 += G) {
             const uint32_t total = group_totals<WPL, G>(
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kSearchWaves * kWave) void search_few_kernel(
     const int c_lo = min(wave * per, C), c_hi = min(c_lo + per, C);
 
     uint32_t x[kRows][WPL];
-    load_rows<WPL>(hv, n0, N, W, lane, x);
+    load_rows<WPL, false>(hv, n0, N, W, lane, x);
     uint32_t best_key = 0xffffffffu;
     for (int c0 = c_lo; c0 < c_hi; c0 += kGroup) {
         const int gcount = min(kGroup, c_hi - c0);
