@@ -1,0 +1,88 @@
+"""GPU parity on randomly drawn shapes: every integer entry point against the CPU oracle for a
+few dozen seeded (D, F, L, C, N) combinations that mix the sizes at which the kernels change form
+(word and slice boundaries, one / few / many samples, compact and full tables, u8 and fp32)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from workloads import make_workload, pack_bits_lsb  # noqa: E402
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def _draw(rng):
+    D = int(rng.choice([1, 31, 32, 33, 64, 100, 1000, 2048, 2049, 4097, 10000, 10016, 20000]))
+    F = int(rng.choice([1, 2, 3, 15, 16, 17, 31, 33, 100, 127, 128, 617, 784, 1500]))
+    L = int(rng.choice([1, 2, 3, 16, 64, 100, 256]))
+    C = int(rng.choice([1, 2, 3, 5, 6, 10, 16, 17, 26, 40]))
+    N = int(rng.choice([1, 2, 7, 63, 64, 65, 300, 700, 1000, 2500, 9000]))
+    return D, F, L, C, N
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_match_oracle(seed):
+    from paper_2206_04746_amd import binding
+    rng = np.random.default_rng(1000 + seed)
+    done = 0
+    while done < 8:
+        D, F, L, C, N = _draw(rng)
+        if D * F * N > 4e8:          # keeps the oracle's share of the test to a second or so
+            continue
+        u8 = bool(rng.integers(0, 2)) and int(round(F ** 0.5)) ** 2 == F
+        wl = make_workload(3 if u8 else 2, seed=seed * 100 + done, D=D, F=F, L=L, C=C, n_train=N)
+        if rng.integers(0, 3) == 0:  # unrelated level vectors: every dimension varies
+            wl.level = pack_bits_lsb(rng.integers(0, 2, size=(L, D), dtype=np.uint8))
+        x, y = wl.train(N)
+        if not u8:                   # a share of the features at the low edge of the range: bin 0
+            x = x.copy()
+            x[rng.random(x.shape) < rng.choice([0.0, 0.5, 0.9])] = -1.0
+        what = f"D={D} F={F} L={L} C={C} N={N} u8={u8}"
+        ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+        xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+        hv = torch.empty((N, ctx.W), dtype=torch.int32, device="cuda")
+        hv_s = torch.full_like(hv, -1)
+        ctx.hdc_encode(xd, hv)
+        ctx.hdc_encode_sparse(xd, hv_s)
+        want = oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+        assert np.array_equal(_u32(hv), want), what
+        assert np.array_equal(_u32(hv_s), want), what
+
+        acc = torch.zeros((C, D), dtype=torch.int32, device="cuda")
+        cn = torch.zeros(C, dtype=torch.int64, device="cuda")
+        cls = torch.empty((C, ctx.W), dtype=torch.int32, device="cuda")
+        ctx.hdc_train_classical(hv, yd, acc, cn)
+        ctx.hdc_binarize_classical(acc, cn, cls)
+        o_acc, o_cn = oracle.train_classical(want, y, D, C)
+        o_cls = oracle.binarize_classical(o_acc, o_cn, wl.tie)
+        assert np.array_equal(acc.cpu().numpy(), o_acc), what
+        assert np.array_equal(cn.cpu().numpy(), o_cn), what
+        assert np.array_equal(_u32(cls), o_cls), what
+
+        dist = torch.empty((N, C), dtype=torch.int32, device="cuda")
+        pred = torch.empty(N, dtype=torch.int32, device="cuda")
+        ctx.hdc_search(hv, cls, pred, dist)
+        o_d, o_p = oracle.search(want, o_cls, D)
+        assert np.array_equal(_u32(dist), o_d), what
+        assert np.array_equal(pred.cpu().numpy(), o_p), what
+
+        bits = torch.empty((N, D), dtype=torch.uint8, device="cuda")
+        back = torch.empty_like(hv)
+        hs = torch.empty(N, dtype=torch.int32, device="cuda")
+        vs = torch.empty(D, dtype=torch.int32, device="cuda")
+        ctx.hdc_unpack(hv, bits)
+        ctx.hdc_pack(bits, back)
+        ctx.hdc_hsum(hv, hs)
+        ctx.hdc_vsum(hv, vs)
+        o_bits = oracle.unpack(want, D)
+        assert np.array_equal(bits.cpu().numpy(), o_bits), what
+        assert np.array_equal(_u32(back), want), what
+        assert np.array_equal(hs.cpu().numpy(), oracle.hsum(want, D)), what
+        assert np.array_equal(vs.cpu().numpy(), oracle.vsum(want, D)), what
+        ctx.close()
+        done += 1
