@@ -86,3 +86,54 @@ def test_random_shapes_match_oracle(seed):
         assert np.array_equal(vs.cpu().numpy(), oracle.vsum(want, D)), what
         ctx.close()
         done += 1
+
+
+def _rel(a, b):
+    return float(np.max(np.abs(a - b)) / max(1e-30, float(np.max(np.abs(b)))))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_shapes_online_paths_match_oracle(seed):
+    """Per-sample and batched online training and cosine inference on drawn (D, C, N, epochs,
+    learning rate, batch): accumulators within 1e-4 relative of the fp64 oracle, cosines within
+    1e-5, predictions equal except where the two best cosines tie to rounding."""
+    from paper_2206_04746_amd import binding
+    rng = np.random.default_rng(2000 + seed)
+    done = 0
+    while done < 6:
+        D = int(rng.choice([33, 64, 1000, 2049, 4097, 10000, 16384, 32768]))
+        C = int(rng.choice([1, 2, 3, 5, 6, 10, 12, 13, 16, 17, 26]))
+        N = int(rng.choice([1, 7, 64, 65, 300, 1000, 2500]))
+        epochs = int(rng.choice([1, 2, 3]))
+        lr = float(rng.choice([1.0, 0.5, 0.037]))
+        batch = int(rng.choice([1, 3, 8, 64, 300, 2048, 4096]))
+        if N * D * epochs > 2e7:
+            continue
+        what = f"D={D} C={C} N={N} epochs={epochs} lr={lr} batch={batch}"
+        wl = make_workload(1, D=D, C=C, F=3, L=2)
+        cls = pack_bits_lsb(rng.integers(0, 2, size=(C, D), dtype=np.uint8))
+        src = rng.integers(0, C, N)
+        bits = oracle.unpack(cls, D)[src] ^ (rng.random((N, D)) < 0.35).astype(np.uint8)
+        hv_h = pack_bits_lsb(bits)
+        y = src.astype(np.int32)
+        y[rng.random(N) < 0.05] = C          # labels outside [0, C) are skipped
+        ctx = binding.Context(wl.D, wl.F, wl.L, C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+        hv = torch.from_numpy(hv_h.view(np.int32)).cuda()
+        yd = torch.from_numpy(y).cuda()
+        acc = torch.zeros((C, D), dtype=torch.float32, device="cuda")
+        ctx.hdc_train_online(hv, yd, acc, epochs, lr)
+        assert _rel(acc.cpu().numpy(), oracle.train_online(hv_h, y, D, C, epochs, lr)) <= 1e-4, what
+        accb = torch.zeros((C, D), dtype=torch.float32, device="cuda")
+        ctx.hdc_train_online_batched(hv, yd, accb, batch, epochs, lr)
+        assert _rel(accb.cpu().numpy(), oracle.train_online_batched(hv_h, y, D, C, batch, epochs, lr)) <= 1e-4, what
+        cos = torch.empty((N, C), dtype=torch.float32, device="cuda")
+        pred = torch.empty(N, dtype=torch.int32, device="cuda")
+        ctx.hdc_search_cosine(hv, accb, pred, cos)
+        o_cos, o_pred = oracle.search_cosine(hv_h, accb.cpu().numpy(), D)
+        assert float(np.max(np.abs(cos.cpu().numpy() - o_cos))) <= 1e-5, what
+        differ = pred.cpu().numpy() != o_pred
+        if differ.any():
+            top2 = np.sort(o_cos[differ], axis=1)[:, -2:]
+            assert C > 1 and np.all(top2[:, 1] - top2[:, 0] < 1e-6), what
+        ctx.close()
+        done += 1
