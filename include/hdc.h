@@ -61,17 +61,17 @@ typedef struct {
 /*
  * Create a context on the CURRENT HIP device and copy the encoding tables to it
  * (synchronous, one time, not part of the timed path).
- *   item_host  [F][W]  ID vector of every feature            (Sec. III: "ID vectors")
- *   level_host [L][W]  value vector of every bin             (Sec. III: "Value vectors")
+ *   item_host  [F][W]  ID vector of every feature            (Sec. III, the per-feature identity vectors)
+ *   level_host [L][W]  value vector of every bin             (Sec. III, the per-bin value vectors)
  *   tie_host   [W]     bit taken when a majority vote ties exactly (F or a class count
- *                      even); the paper names only "majority voting", the tie rule is
- *                      this library's: strict majority, exact tie -> tie bit
+ *                      even); the paper asks for a majority vote without a tie rule, this
+ *                      one is the library's: strict majority, exact tie -> tie bit
  *   lo_host, scale_host [F]  bin rule for HDC_F32 features: t = (x - lo[f]) * scale[f]
  *                      in fp32 (two roundings, no fused multiply-add), bin = floor(t)
  *                      clamped to [0, L-1]; t < 0 or NaN -> bin 0.  scale is normally
  *                      float(L / (hi - lo)).  Both must be NULL for HDC_U8, whose rule is
- *                      bin = (x * L) >> 8.  (Sec. III says only that values are
- *                      "discretized into a fixed number of bins".)
+ *                      bin = (x * L) >> 8.  (Sec. III fixes the number of bins, not the
+ *                      rule that maps a value to one.)
  * Errors: HDC_EINVAL (null/invalid arguments, nonzero pad bits in a table),
  * HDC_ENOMEM, HDC_EHIP.  On error *out is NULL.
  */
@@ -114,8 +114,8 @@ int hdc_encode_sparse(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *
 int32_t hdc_encoded_words(const hdc_ctx *ctx);
 
 /*
- * Classical training, Sec. III ("single-pass accumulation of the encoded vectors
- * belonging to the same class into a class vector"):
+ * Classical training, Sec. III (one pass that adds every encoded vector into the
+ * accumulator of its class):
  *   acc[c][d] += hv[n][d]  and  class_n[c] += 1   for c = labels[n].
  * Both outputs are ADDED TO, so chunks of a stream compose in any order (integer sums:
  * the result does not depend on chunking or sample order); the caller zeroes them
@@ -175,13 +175,14 @@ int hdc_train_online_batched(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t
 int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_dev, void *stream);
 
 /*
- * Hamming-distance inference, Sec. III ("compared to the class vectors to find the most
- * similar vector"):
+ * Hamming-distance inference, Sec. III (a query goes to the class whose vector is
+ * nearest to it):
  *   dist[n][c] = number of dimensions in which hv[n] and class_hv[c] differ,
  *   pred[n]    = lowest c with the smallest dist[n][c].
  *   hv_dev [N][W], class_hv_dev [C][W] (pad bits zero), dist_dev [N][C] uint32 out or
  *   NULL when only predictions are wanted, pred_dev [N] int32 out (required).
- * D <= 32768 (a query row is held in the registers of one wave; HDC_ELIMIT beyond).
+ * Any D up to HDC_MAX_D; the fast paths hold a query row in the registers of one wave
+ * (D <= 32768), longer rows are read again for every class.
  */
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream);

@@ -75,7 +75,7 @@ void orc_pack(const uint8_t *bits, int64_t rows, int32_t D, uint32_t *words)
     }
 }
 
-/* ---- discretisation (Sec. III: "discretized into a fixed number of bins") ----- */
+/* ---- discretisation (Sec. III: feature values fall into a fixed number of bins) ---- */
 
 /* Equal-width bins over [lo, hi): t = (x - lo) * scale with scale = float(L/(hi-lo)),
  * two separately rounded fp32 operations; bin = floor(t) clamped to [0, L-1];

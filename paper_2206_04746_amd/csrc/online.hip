@@ -1,7 +1,8 @@
 // Online training (arXiv 2206.04746, Sec. III, Eqs. 2-3 and the caption of Fig. 1).
 //
 // The method is a dependency chain over the samples: every step needs the class
-// accumulators left by the step before ("cannot be highly parallelized", Sec. VI-D2).  What
+// accumulators left by the step before (Sec. VI-D2 notes that this rules out parallelism over
+// the samples).  What
 // is parallel is the work inside one step - C dot products over D dimensions and at most two
 // row updates - so one persistent workgroup of 1024 threads walks the chain and spreads the
 // D dimensions over its lanes.  Thread t owns dimensions t, t+1024, ... in every phase, so a

@@ -282,6 +282,79 @@ __global__ __launch_bounds__(kSearchWaves * kWave) void search_few_kernel(
     }
 }
 
+// Rows too long for a wave's registers (more than 16 words per lane, D > 32768): the shape of
+// search_few_kernel - a block per tile of kRows rows, its waves splitting the classes, class words
+// from global memory - with the row words read again for every class instead of held in registers.
+// Not a fast path: it exists so that no dimension the other entry points take is refused here.
+__global__ __launch_bounds__(kSearchWaves * kWave) void search_long_kernel(
+    const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W,
+    uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
+    __shared__ uint32_t xch_all[kSearchWaves * kXchWords];
+    __shared__ uint32_t keys[kSearchWaves][kRows];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t *xch = xch_all + wave * kXchWords;
+    const int r_of = lane / kGroup, g_of = lane % kGroup;
+    const int64_t n0 = (int64_t)blockIdx.x * kRows;
+    const int per = (C + kSearchWaves - 1) / kSearchWaves;
+    const int c_lo = min(wave * per, C), c_hi = min(c_lo + per, C);
+    const uint32_t *row[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) row[r] = hv + ((n0 + r < N) ? n0 + r : N - 1) * W;
+
+    uint32_t best_key = 0xffffffffu;
+    for (int c0 = c_lo; c0 < c_hi; c0 += kGroup) {
+        const int gcount = min(kGroup, c_hi - c0);
+        for (int g = 0; g < gcount; ++g) {
+            const uint32_t *m = class_hv + (int64_t)(c0 + g) * W;
+            uint32_t part[kRows];
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) part[r] = 0;
+            for (int w = lane; w < W; w += kWave) {
+                const uint32_t mw = m[w];
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) part[r] = bcnt_acc(row[r][w] ^ mw, part[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                uint32_t v = part[r];
+                v += dpp<0xB1>(v);
+                v += dpp<0x4E>(v);
+                if ((lane & 3) == 0) xch[(r * kGroup + g) * kXchStride + (lane >> 2)] = v;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t total = 0;
+        if (g_of < gcount) {
+            const uint32_t *src = xch + lane * kXchStride;
+#pragma unroll
+            for (int l = 0; l < kWave / 4; ++l) total += src[l];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int cidx = c0 + g_of;
+        const int64_t n = n0 + r_of;
+        if (g_of < gcount && n < N) {
+            if (dist) dist[n * C + cidx] = total;
+            best_key = min(best_key, (total << 10) | (uint32_t)cidx);
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft < kGroup; sft <<= 1)
+        best_key = min(best_key, (uint32_t)__shfl_xor((int)best_key, sft, kWave));
+    if (g_of == 0) keys[wave][r_of] = best_key;
+    __syncthreads();
+    if (threadIdx.x < kRows && n0 + threadIdx.x < N) {
+        uint32_t k = keys[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kSearchWaves; ++w) k = min(k, keys[w][threadIdx.x]);
+        pred[n0 + threadIdx.x] = (int32_t)(k & 1023u);
+    }
+}
+
 constexpr int64_t kFewQueries = 8192;   // below this the one-tile-per-block kernel is used
 
 template <int WPL, int G>
@@ -338,7 +411,13 @@ int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t
     if (wpl <= 8) return launch_search_wpl<8>(c, hv, N, class_hv, dist, pred, s);
     if (wpl <= 12) return launch_search_wpl<12>(c, hv, N, class_hv, dist, pred, s);
     if (wpl <= 16) return launch_search_wpl<16>(c, hv, N, class_hv, dist, pred, s);
-    return HDC_ELIMIT;   // D > 32768
+    {   // D > 32768
+        ProfScope prof(c, HDC_K_SEARCH, s);
+        hipLaunchKernelGGL(search_long_kernel, dim3((unsigned)((N + kRows - 1) / kRows)), dim3(kSearchWaves * kWave), 0,
+                           s, hv, N, class_hv, c->p.C, c->W, dist, pred);
+    }
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
 }
 
 }  // namespace hdc

@@ -184,7 +184,9 @@ def test_classical_accumulate_and_binarize_bit_exact(D, C, N):
                                    # from 8192 queries on: the kernel that stages the class vectors in LDS
                                    (10000, 26, 9000), (2049, 16, 8193), (20000, 33, 8192), (31, 17, 20000),
                                    # class vectors larger than LDS: read from global memory at any N
-                                   (10000, 200, 8200), (4096, 1024, 8192)])
+                                   (10000, 200, 8200), (4096, 1024, 8192),
+                                   # rows longer than a wave's registers hold
+                                   (40000, 5, 50), (33000, 26, 9), (100000, 3, 8200)])
 def test_search_bit_exact(D, C, N):
     rng = np.random.default_rng(D * 7 + C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
@@ -345,13 +347,12 @@ def test_argument_errors_are_reported_not_faulted():
         == b.HDC_EINVAL
     assert b.lib.hdc_encode(ctx._h, None, 0, None, None) == b.HDC_OK      # N == 0 is a no-op
     ctx.close()
-    # beyond the documented dimension limit of search and per-sample online training: an error code
+    # beyond the documented dimension limit of per-sample online training: an error code
     big = make_workload(1, D=40000, F=4, L=4, C=2)
     ctx = make_ctx(big)
     hv = torch.zeros((4, ctx.W), dtype=torch.int32, device="cuda")
     pred = torch.zeros(4, dtype=torch.int32, device="cuda")
     acc = torch.zeros((2, 40000), dtype=torch.float32, device="cuda")
-    assert b.lib.hdc_search(ctx._h, hv.data_ptr(), 4, hv.data_ptr(), None, pred.data_ptr(), None) == b.HDC_ELIMIT
     assert b.lib.hdc_train_online(ctx._h, hv.data_ptr(), pred.data_ptr(), 4, 1, 1.0, acc.data_ptr(), None) \
         == b.HDC_ELIMIT
     ctx.close()
