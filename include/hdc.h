@@ -145,7 +145,8 @@ int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *
  * acc_dev [C][D] fp32 is in/out (zero it for a fresh model); repeated calls continue
  * training.  Samples whose label is outside [0, C) are skipped.  The sequential
  * dependency between samples is the method's; one call is one dependency chain.
- * epochs >= 0; lr is the paper's learning rate gamma.  D <= 32768 (HDC_ELIMIT beyond).
+ * epochs >= 0; lr is the paper's learning rate gamma.  Beyond D = 32768 the call runs
+ * hdc_train_online_batched with batches of one sample (the same method, three launches per sample).
  * For C <= 12 and D <= 10240 the first call allocates 64 MB of context-owned scratch
  * (HDC_ENOMEM if that fails); later calls only enqueue on `stream`.
  */

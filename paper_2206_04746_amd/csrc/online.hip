@@ -591,7 +591,9 @@ static int launch_online_reg(hdc_ctx_impl *c, const uint32_t *hv, const int32_t 
 int launch_train_online(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                         int32_t epochs, float lr, float *acc, hipStream_t s) {
     const int C = c->p.C;
-    if (c->p.D > 32 * kOnlineThreads) return HDC_ELIMIT;   // a thread keeps its sample bits in one word
+    // a thread keeps its sample bits in one word: beyond 32768 dimensions the batched trainer runs
+    // with batches of one sample, which is the same method (slower: three launches per sample)
+    if (c->p.D > 32 * kOnlineThreads) return launch_train_online_batched(c, hv, labels, N, epochs, lr, 1, acc, s);
     // Register-resident kernel when C x (dimensions per thread) fits the register file.
     const int kpt = (c->p.D + kOnlineThreads - 1) / kOnlineThreads;
 #define HDC_ONLINE_LDS_CASE(CM, KP) \

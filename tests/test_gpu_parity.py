@@ -347,14 +347,22 @@ def test_argument_errors_are_reported_not_faulted():
         == b.HDC_EINVAL
     assert b.lib.hdc_encode(ctx._h, None, 0, None, None) == b.HDC_OK      # N == 0 is a no-op
     ctx.close()
-    # beyond the documented dimension limit of per-sample online training: an error code
-    big = make_workload(1, D=40000, F=4, L=4, C=2)
-    ctx = make_ctx(big)
-    hv = torch.zeros((4, ctx.W), dtype=torch.int32, device="cuda")
-    pred = torch.zeros(4, dtype=torch.int32, device="cuda")
-    acc = torch.zeros((2, 40000), dtype=torch.float32, device="cuda")
-    assert b.lib.hdc_train_online(ctx._h, hv.data_ptr(), pred.data_ptr(), 4, 1, 1.0, acc.data_ptr(), None) \
-        == b.HDC_ELIMIT
+
+
+def test_online_training_beyond_the_register_resident_dimensions():
+    # D > 32768: the per-sample trainer hands over to the batched one with batches of one sample
+    rng = np.random.default_rng(3)
+    D, C, N = 40000, 3, 24
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    hv_h = rand_hv(rng, N, D)
+    y = rng.integers(0, C, N).astype(np.int32)
+    ctx = make_ctx(wl)
+    acc = torch.zeros((C, D), dtype=torch.float32, device="cuda")
+    ctx.hdc_train_online(dev_u32(hv_h), torch.from_numpy(y).cuda(), acc, 2, 1.0)
+    torch.cuda.synchronize()
+    want = oracle.train_online(hv_h, y, D, C, 2, 1.0)
+    got = acc.cpu().numpy()
+    assert np.max(np.abs(got - want)) <= 1e-4 * np.max(np.abs(want))
     ctx.close()
 
 
