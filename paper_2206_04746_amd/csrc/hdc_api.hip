@@ -27,7 +27,7 @@ static void free_ctx(hdc_ctx_impl *c) {
     if (!c) return;
     void *ptrs[] = {c->item_d, c->level_d, c->tie_d, c->lo_d, c->scale_d, c->q_d, c->cls_cnt_d,
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d,
-                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d,
+                    c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d, c->ob_ln_d, c->ob_lw_d, c->ob_meta_d,
                     c->citem_d, c->clevel_d, c->hvc_d, c->expand_d,
                     c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d};
     for (void *p : ptrs)

@@ -79,6 +79,12 @@ struct hdc_ctx_impl {
     size_t ob_share_bytes;
     double *ob_norm_d;    // [C][ceil(D/64)] squared-norm partials of the class rows
     size_t ob_norm_bytes;
+    uint32_t *ob_ln_d;    // [C][sub-batch] per class: the samples that name it, in sample order
+    size_t ob_ln_bytes;
+    double *ob_lw_d;      // [C][sub-batch] ... and their signed weights
+    size_t ob_lw_bytes;
+    uint32_t *ob_meta_d;  // [3 C + 1 + rows] entries / first share row / share rows per class, row counter, work list
+    size_t ob_meta_bytes;
     bool ob_attr_set;     // dynamic-LDS limit of the backward kernel raised
 
     // hdc_encode_sparse (allocated and derived on its first call)

@@ -31,7 +31,10 @@ def clustered(rng, N, D, C, flip=0.35):
     (1024, 5, 600, 2, 1.0, 32), (10000, 6, 1500, 3, 1.0, 256), (10000, 26, 300, 1, 0.5, 300),
     (10000, 26, 300, 1, 0.5, 100000), (33, 1, 20, 2, 1.0, 3), (2049, 3, 100, 1, 0.0, 7),
     (32768, 2, 40, 1, 1.0, 16), (1024, 4, 100, 1, 1.0, 1), (1000, 3, 9000, 1, 1.0, 9000),
-    (4096, 300, 700, 1, 1.0, 128), (40000, 2, 30, 1, 1.0, 8)])
+    (4096, 300, 700, 1, 1.0, 128), (40000, 2, 30, 1, 1.0, 8),
+    # from 1024 samples per piece on the backward step goes by class lists
+    (10000, 26, 3000, 2, 1.0, 1024), (10000, 26, 2100, 1, 0.5, 4096), (2049, 17, 1500, 3, 1.0, 1500),
+    (100, 1, 1100, 2, 1.0, 1100), (4097, 40, 9000, 1, 1.0, 5000), (10000, 6, 20000, 1, 1.0, 20000)])
 def test_batched_online_training_matches_oracle(D, C, N, epochs, lr, batch):
     rng = np.random.default_rng(D + C + N + batch)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
