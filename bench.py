@@ -359,6 +359,32 @@ def extras(torch, binding, make_workload):
                                                          / FP64_PEAK_TFLOPS, 4)}
     ctx.close()
     del hv4, x4d
+    # the same trainer with 26 classes (config 2 shape): beyond 16 classes the backward step
+    # works from per-class lists of the samples that carry a non-zero weight
+    wl2 = make_workload(2)
+    ctx = binding.Context(wl2.D, wl2.F, wl2.L, wl2.C, wl2.item, wl2.level, wl2.tie, wl2.lo, wl2.scale, wl2.dtype)
+    x2, y2 = wl2.train()
+    x2d, y2d = torch.from_numpy(x2).to(dev), torch.from_numpy(y2).to(dev)
+    hv2 = torch.empty((x2.shape[0], ctx.W), dtype=torch.int32, device=dev)
+    ctx.hdc_encode(x2d, hv2)
+    acc2 = torch.zeros((wl2.C, wl2.D), dtype=torch.float32, device=dev)
+
+    def batched26():
+        acc2.zero_()
+        ctx.hdc_train_online_batched(hv2, y2d, acc2, 8192, epochs=1, lr=wl2.lr)
+    ms = _timed(torch, batched26, 3)
+    ctx.hdc_profile_enable(True)
+    batched26()
+    torch.cuda.synchronize()
+    f_ms, _ = ctx.hdc_profile_read("online_fwd")
+    b_ms, _ = ctx.hdc_profile_read("online_bwd")
+    ctx.hdc_profile_enable(False)
+    res["train_online_batched_cfg2_1epoch_batch8192"] = {
+        "ms": round(ms, 4), "samples_per_s": round(x2.shape[0] / ms * 1e3, 0),
+        "fwd_us": round(f_ms * 1e3, 2), "bwd_us": round(b_ms * 1e3, 2),
+        "fwd_frac_fp64_valu": round(2.0 * x2.shape[0] * wl2.C * wl2.D / (f_ms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS, 4)}
+    ctx.close()
+    del hv2, x2d, acc2
 
     # --- the whole classical step (as timed for `value`) along the paper's dimension axis
     # (Sec. VI-D1, ISOLET shape) and at the small-feature PAMAP shape of Table II

@@ -191,6 +191,104 @@ __global__ __launch_bounds__(kSearchWaves * kWave) void search_kernel(
     }
 }
 
+// ---- a row per 16 lanes --------------------------------------------------------------------
+// Second layout for long streams of queries, taken when a row fills 16 lanes well: lane i of a
+// row's 16 lanes holds the 16-byte pieces i, i + 16, ... of the row (KPL pieces), so a wave still
+// streams kRows rows at a time, now with 16-byte loads, and every lane works for ONE row.  A
+// partial distance then has to be summed over 16 lanes instead of 64, and a lane carries G values
+// instead of kRows * G: the fold costs about a quarter of what it costs in search_kernel, which
+// is what bounds that kernel from about ten classes on.  The price is in LDS traffic: the class
+// words are read per row, i.e. four times per wave (16-byte reads, the four rows reading the same
+// addresses).
+//
+// Rows are 4-byte aligned only and the last piece of a row may be short; a lane whose piece
+// would cross the end of the row reads the row's LAST 16 bytes instead and keeps the words that
+// belong to its own piece (none, for a piece wholly past the end), so no read leaves the row.
+// The class vectors are staged in LDS in the same piece order, with zeros where a lane keeps
+// nothing.  Needs W >= 4.
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a piece in a row
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));                  // a piece in LDS (16-byte aligned)
+
+constexpr int kRowLanes = kWave / kRows;   // 16
+
+// first word the lane's piece `piece` is read from, and which of the four words it keeps
+__device__ __forceinline__ int piece_start(int piece, int W) { return 4 * piece + 3 < W ? 4 * piece : W - 4; }
+__device__ __forceinline__ bool piece_keeps(int piece, int start, int j, int W) {
+    return start + j >= 4 * piece && start + j < W && start + j < 4 * piece + 4;
+}
+
+template <int KPL, int G>
+__global__ __launch_bounds__(kSearchWaves * kWave) void search_rows16_kernel(
+    const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W,
+    uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
+    extern __shared__ uint32_t cls[];    // [C][KPL][16 lanes][4 words]
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & (kRowLanes - 1), r = lane / kRowLanes;
+
+    for (int idx = threadIdx.x; idx < C * KPL * kWave; idx += kSearchWaves * kWave) {
+        const int c = idx / (KPL * kWave), rem = idx - c * (KPL * kWave);
+        const int piece = (rem >> 2) % kRowLanes + kRowLanes * (rem / kWave), j = rem & 3;
+        const int start = piece_start(piece, W);
+        cls[idx] = piece_keeps(piece, start, j, W) ? class_hv[(int64_t)c * W + start + j] : 0u;
+    }
+    __syncthreads();
+
+    // only the lane's last piece can be short or past the end
+    constexpr int kLast = KPL - 1;
+    const int last_piece = i + kRowLanes * kLast;
+    const int last_start = piece_start(last_piece, W);
+    uint32_t keep[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) keep[j] = piece_keeps(last_piece, last_start, j, W) ? 0xffffffffu : 0u;
+
+    constexpr int kShift = G == 16 ? 0 : G == 8 ? 1 : G == 4 ? 2 : 3;   // lane i ends with value i >> kShift
+    const int g_of = i >> kShift;
+    const bool writes = (i & ((1 << kShift) - 1)) == 0;
+    const u32x4 *cls4 = reinterpret_cast<const u32x4 *>(cls);
+
+    const int64_t tiles = (N + kRows - 1) / kRows;
+    for (int64_t t = (int64_t)blockIdx.x * kSearchWaves + wave; t < tiles;
+         t += (int64_t)gridDim.x * kSearchWaves) {
+        const int64_t n = t * kRows + r;
+        const uint32_t *row = hv + (n < N ? n : N - 1) * W;
+        u32x4_a4 x[KPL];
+#pragma unroll
+        for (int k = 0; k < kLast; ++k)
+            x[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4 *>(row + 4 * (i + kRowLanes * k)));
+        x[kLast] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4 *>(row + last_start));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[kLast][j] &= keep[j];
+
+        uint32_t best_key = 0xffffffffu;
+        for (int c0 = 0; c0 < C; c0 += G) {
+            uint32_t v[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                uint32_t part = 0;
+                if (c0 + g < C) {   // wave-uniform
+                    const u32x4 *m = cls4 + ((size_t)(c0 + g) * KPL) * kRowLanes + i;
+#pragma unroll
+                    for (int k = 0; k < KPL; ++k) {
+                        const u32x4 mw = m[k * kRowLanes];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) part = bcnt_acc(x[k][j] ^ mw[j], part);
+                    }
+                }
+                v[g] = part;
+            }
+            const uint32_t total = FoldLow<3, G>::run(v, lane);
+            const int cidx = c0 + g_of;
+            if (cidx < C && n < N) {
+                if (dist && writes) dist[n * C + cidx] = total;
+                best_key = min(best_key, (total << 10) | (uint32_t)cidx);   // D < 2^21, C <= 1024
+            }
+        }
+        best_key = row_min(best_key);
+        if (i == 0 && n < N) pred[n] = (int32_t)(best_key & 1023u);
+    }
+}
+
 // ---- few queries ----------------------------------------------------------------------------
 constexpr int kGroup = 16;    // classes per reduction round of the few-query kernel; kRows * kGroup == 64
 constexpr int kXchStride = 17;
@@ -398,8 +496,68 @@ static int launch_search_wpl(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, con
     return launch_search_shape<WPL, 16>(c, hv, N, class_hv, dist, pred, s);
 }
 
+template <int KPL, int G>
+static int launch_rows16_shape(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                               uint32_t *dist, int32_t *pred, hipStream_t s) {
+    const size_t lds = (size_t)c->p.C * KPL * kWave * 4;
+    auto kern = search_rows16_kernel<KPL, G>;
+    if (lds > 64 * 1024)
+        HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const int64_t tiles = (N + kRows - 1) / kRows;
+    int64_t blocks = (tiles + kSearchWaves - 1) / kSearchWaves;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    {
+        ProfScope prof(c, HDC_K_SEARCH, s);
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kSearchWaves * kWave), lds, s, hv, N,
+                           class_hv, c->p.C, c->W, dist, pred);
+    }
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
+template <int KPL>
+static int launch_rows16(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                         uint32_t *dist, int32_t *pred, hipStream_t s) {
+    if (c->p.C <= 2) return launch_rows16_shape<KPL, 2>(c, hv, N, class_hv, dist, pred, s);
+    if (c->p.C <= 8) return launch_rows16_shape<KPL, 8>(c, hv, N, class_hv, dist, pred, s);
+    return launch_rows16_shape<KPL, 16>(c, hv, N, class_hv, dist, pred, s);
+}
+
+// The row-per-16-lanes kernel when the stream is long, the pieces of a row fill the lanes of an
+// instantiated size to 85 % or more, and the class vectors fit in LDS; returns false otherwise.
+static bool try_rows16(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                       uint32_t *dist, int32_t *pred, hipStream_t s, int *rc) {
+    if (N < kFewQueries || c->W < 4) return false;
+    const int pieces = (c->W + 3) / 4;
+    const int need = (pieces + kRowLanes - 1) / kRowLanes;
+    static const int sizes[] = {1, 2, 3, 4, 5, 6, 8, 12, 16};
+    int kpl = 0;
+    for (int sz : sizes)
+        if (sz >= need) { kpl = sz; break; }
+    if (!kpl || pieces * 100 < 85 * kRowLanes * kpl) return false;
+    if (c->W < 4 * kRowLanes * (kpl - 1)) return false;   // the kernel takes all but a lane's last piece as whole
+    if ((size_t)c->p.C * kpl * kWave * 4 > 160 * 1024) return false;
+    switch (kpl) {
+    case 1: *rc = launch_rows16<1>(c, hv, N, class_hv, dist, pred, s); break;
+    case 2: *rc = launch_rows16<2>(c, hv, N, class_hv, dist, pred, s); break;
+    case 3: *rc = launch_rows16<3>(c, hv, N, class_hv, dist, pred, s); break;
+    case 4: *rc = launch_rows16<4>(c, hv, N, class_hv, dist, pred, s); break;
+    case 5: *rc = launch_rows16<5>(c, hv, N, class_hv, dist, pred, s); break;
+    case 6: *rc = launch_rows16<6>(c, hv, N, class_hv, dist, pred, s); break;
+    case 8: *rc = launch_rows16<8>(c, hv, N, class_hv, dist, pred, s); break;
+    case 12: *rc = launch_rows16<12>(c, hv, N, class_hv, dist, pred, s); break;
+    default: *rc = launch_rows16<16>(c, hv, N, class_hv, dist, pred, s); break;
+    }
+    return true;
+}
+
 int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                   uint32_t *dist, int32_t *pred, hipStream_t s) {
+    {
+        int rc = HDC_OK;
+        if (try_rows16(c, hv, N, class_hv, dist, pred, s, &rc)) return rc;
+    }
     // words per lane, rounded up to an instantiated size (a whole row lives in registers)
     const int wpl = (c->W + kWave - 1) / kWave;
     if (wpl <= 1) return launch_search_wpl<1>(c, hv, N, class_hv, dist, pred, s);

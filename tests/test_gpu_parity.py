@@ -215,6 +215,48 @@ def test_search_bit_exact(D, C, N):
     ctx.close()
 
 
+# Long query streams whose rows fill 16 lanes with 16-byte pieces take a kernel with one row per 16
+# lanes: every size of its piece count, rows ending 1, 2, 3 or 4 words into the last piece, rows
+# whose last word is partial, class counts on both sides of each group width, a ragged last tile.
+@pytest.mark.parametrize("D,C,N", [(2048, 3, 8193), (1761, 9, 8195), (3900, 2, 8194), (6000, 17, 8192),
+                                   (8001, 8, 8197), (10000, 10, 8195), (10240, 1, 8193), (12000, 26, 8194),
+                                   (16384, 16, 8195), (24000, 5, 8193), (31000, 4, 8194), (32768, 2, 8195),
+                                   (10000, 40, 8193)])
+def test_search_long_streams_bit_exact(D, C, N):
+    rng = np.random.default_rng(D + 13 * C)
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    W = (D + 31) // 32
+    tail = np.uint32((1 << (D - 32 * (W - 1))) - 1) if D % 32 else np.uint32(0xffffffff)
+
+    def rand_rows(n):
+        r = rng.integers(0, 2 ** 32, size=(n, W), dtype=np.uint64).astype(np.uint32)
+        r[:, -1] &= tail
+        return r
+    cls = rand_rows(C)
+    q = rand_rows(N)
+    # every third query: a class vector with a few words disturbed (a clear nearest class); some exact
+    near = np.arange(0, N, 3)
+    q[near] = cls[rng.integers(0, C, near.size)]
+    q[near[::2], rng.integers(0, W, near[::2].size)] ^= np.uint32(0x00f0f00f) & (tail if W == 1 else np.uint32(0xffffffff))
+    q[:, -1] &= tail
+    if C > 2:
+        cls[2] = cls[0]                                      # duplicate class: argmin must pick 0
+    ctx = make_ctx(wl)
+    qd, cd = dev_u32(q), dev_u32(cls)
+    dist = torch.full((N, C), -1, dtype=torch.int32, device="cuda")
+    pred = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(qd, cd, pred, dist)
+    torch.cuda.synchronize()
+    want_d, want_p = oracle.search(q, cls, D)
+    assert np.array_equal(host_u32(dist), want_d)
+    assert np.array_equal(pred.cpu().numpy(), want_p)
+    pred2 = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(qd, cd, pred2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(pred2, pred)
+    ctx.close()
+
+
 # Level tables decide which dimensions encode to a per-model constant (every level vector has the
 # same bit there).  The library then encodes only the other dimensions and spreads the result:
 # the output must not depend on how many dimensions vary, nor on where they sit.
@@ -366,7 +408,7 @@ def test_online_training_beyond_the_register_resident_dimensions():
     ctx.close()
 
 
-# ------------------------------------------------- full sizes of the BASELINE configurations
+# ------------------------------------------------- full sizes of the benchmark configurations
 def test_config3_full_size_classical_pipeline():
     """MNIST-shaped config at its full size (60000 train / 10000 test, u8 features, L=256)."""
     wl = make_workload(3)
