@@ -161,6 +161,10 @@ int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
 int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(hdc_ctx_impl *c);
+// Hamming search on the matrix cores for long query streams with 7..31 classes; false when the
+// shape is not its own (then nothing was launched and *rc is untouched).
+bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                     uint32_t *dist, int32_t *pred, hipStream_t s, int *rc);
 int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                   uint32_t *dist, int32_t *pred, hipStream_t s);
 

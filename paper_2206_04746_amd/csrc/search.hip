@@ -556,6 +556,7 @@ int launch_search(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t
                   uint32_t *dist, int32_t *pred, hipStream_t s) {
     {
         int rc = HDC_OK;
+        if (try_search_mfma(c, hv, N, class_hv, dist, pred, s, &rc)) return rc;
         if (try_rows16(c, hv, N, class_hv, dist, pred, s, &rc)) return rc;
     }
     // words per lane, rounded up to an instantiated size (a whole row lives in registers)
