@@ -23,18 +23,26 @@
 // depends on the order of K inside the instruction.
 //
 // A lane feeds class slot (lane % 32) to the first operand and query (lane % 32) to the second;
-// the two halves of the wave take the two halves of a row, so a lane needs only its own half of
-// its own query's row.  Reading it from there directly (every lane a row of its own) costs more
-// in the texture path than the MFMAs take, so a wave fetches 64 bytes of 128 row halves at a time
-// with coalesced 16-byte loads (4 lanes per 64 bytes), parks them in an LDS area of its own and
-// reads them back a row half per lane; the loads of the next 64 bytes - or of the next 64
-// queries - are in flight while the MFMAs of this chunk run.  The class words come from LDS too (one
-// word per lane per step) and their eight masks are formed once for the kTiles tiles of 32
-// queries that a wave carries at a time.  The accumulators come back with the query on the lane
-// and the class slot on the register (and the wave half), so the nearest class is a minimum over
-// the lane's own 16 registers plus one exchange between the halves.  Slot 31 holds an all-ones
-// class: its dot product is popcount(x), needed only when distances are written out.  Hence
-// C <= 31.
+// the two halves of the wave take the two halves of a row.  A block of eight waves works on 64
+// consecutive rows (two tiles of 32 queries) at a time and splits their words eight ways: wave v
+// takes words [v * 4P, (v + 1) * 4P) of both halves of every row.  Together the waves read the
+// 64 rows - 80 KB of consecutive memory at D = 10000 - within one pass, so every cache line comes
+// from HBM once; a wave that walked through rows of its own in slices would come back to each
+// line long after it had left the cache.  The wave fetches its slices with coalesced 16-byte
+// loads, parks them in an LDS area of its own and reads them back a row half per lane (reading
+// them from memory that way directly - every lane a row of its own - costs more in the texture
+// path than the MFMAs take); the loads for the block's next 64 rows are in flight while it
+// computes.  A wave's slice of the class vectors never changes: each lane keeps the 4P words of
+// its class slot in registers for the whole launch, and their four masks are formed once per step
+// for both tiles.
+//
+// The accumulators come back with the query on the lane and the class slot on the register (and
+// the wave half).  Each wave writes its partial dot products (at most 64 * 4P each: two to a
+// 32-bit word) to its LDS area; after a barrier
+// wave w adds up, over the eight waves, four registers of one tile, turns them into keys
+// (distance, class) and takes their minimum; after a second barrier 64 threads take the minimum
+// over the four register groups.  Slot 31 holds an all-ones class: its dot product is
+// popcount(x), needed only when distances are written out.  Hence C <= 31.
 #include "hdc_internal.h"
 
 #include <algorithm>
@@ -45,23 +53,29 @@ namespace hdc {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 constexpr int kMfmaWaves = 8;    // per block: two per SIMD, one block per CU
 constexpr int kSlots = 32;       // class slots of an MFMA (its M)
 constexpr int kTile = 32;        // queries of an MFMA (its N)
-constexpr int kTiles = 2;        // tiles a wave carries at a time
+constexpr int kTiles = 2;        // tiles a block carries at a time
 constexpr int kJob = kTile * kTiles;
-constexpr int kChunk = 16;       // words of a row half a lane holds at a time (64 bytes)
-constexpr int kPieces = kChunk / 4;
-constexpr int kOnes = kSlots - 1;   // the slot of the all-ones class
-// A wave's LDS area: [tile][half][row] segments of 64 bytes, 80 bytes apart (the 16-byte reads of
-// 8 neighbouring lanes then fall into 32 different banks).
-constexpr int kSegBytes = 80;
-constexpr int kHalfBytes = kTile * kSegBytes;                 // 2560: the 32 rows of one (tile, half)
-constexpr int kWaveBytes = kTiles * 2 * kHalfBytes;           // 10240
-constexpr int kFetches = kTiles * 2 * kTile * kChunk * 4 / (kWave * 16);   // 8 loads of 16 bytes per lane per chunk
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kSegs = kTiles * 2 * kTile;   // (tile, half, row) segments a wave fetches per job
+constexpr int kOnes = kSlots - 1;           // the slot of the all-ones class
+constexpr int kPartialBytes = kTiles * 8 * kWave * 4;    // a wave's partial dot products, two to a word
+
+// Geometry for P 16-byte pieces per segment: a wave's slice of a row half is 4P words.
+template <int P>
+struct Geo {
+    static constexpr int kSteps = 4 * P;             // words of a row half per wave = MFMA steps per job
+    // a segment and its padding in LDS: an odd number of 16-byte units apart, so that the 16-byte
+    // reads of 8 neighbouring lanes fall into different banks
+    static constexpr int kSegBytes = 16 * (P % 2 ? P + 2 : P + 1);
+    static constexpr int kAreaBytes = kSegs * kSegBytes > kPartialBytes ? kSegs * kSegBytes : kPartialBytes;
+    static constexpr int kLoads = kSegs * P / kWave;   // 16-byte loads per lane per job (2P)
+    static constexpr size_t kLdsBytes = kSlots * 4 + kTiles * 4 * kTile * 4 * 2 + (size_t)kMfmaWaves * kAreaBytes;
+};
 
 // bits 0..2 of every nibble reversed, bit 3 in place
 __device__ __forceinline__ uint32_t reverse3(uint32_t m) {
@@ -80,85 +94,38 @@ __device__ __forceinline__ void wave_sync_lds() {   // LDS written by some lanes
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Fetch number i of a chunk covers 16 row halves: tile i / 4, half (i / 2) % 2, rows 16 * (i % 2)
-// + lane / 4, the lane taking piece lane % 4 (four words) of the 64 bytes.  rows[t][e] is the
-// lane's row of tile t in the upper (e = 1) or lower 16.  A piece that would cross the end of the
-// row is moved back to the row's last 16 bytes (the class words in LDS are laid out to match).
-struct Fetched {
-    u32x4_a4 v[kFetches];
-};
-__device__ __forceinline__ void fetch_chunk(Fetched &f, const uint32_t *(&rows)[kTiles][2], int c, int s0,
-                                            int W, int lane) {
-    int w[2];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh) w[hh] = min(hh * s0 + c * kChunk + 4 * (lane & 3), W - 4);
-#pragma unroll
-    for (int i = 0; i < kFetches; ++i)
-        f.v[i] = *reinterpret_cast<const u32x4_a4 *>(rows[i / 4][i % 2] + w[(i / 2) % 2]);
-}
-__device__ __forceinline__ void park_chunk(const Fetched &f, char *area, int lane) {
-    char *at = area + (lane >> 2) * kSegBytes + (lane & 3) * 16;
-#pragma unroll
-    for (int i = 0; i < kFetches; ++i) *reinterpret_cast<u32x4 *>(at + i * (kHalfBytes / 2)) = f.v[i];
-}
-
-struct RowChunk {   // the lane's 16 words of its half of its row, for each tile
-    u32x4 x[kTiles][kPieces];
-};
-__device__ __forceinline__ void take_chunk(RowChunk &r, const char *area, int q, int h) {
-    const char *at = area + h * kHalfBytes + q * kSegBytes;
-#pragma unroll
-    for (int t = 0; t < kTiles; ++t)
-#pragma unroll
-        for (int k = 0; k < kPieces; ++k) r.x[t][k] = *reinterpret_cast<const u32x4 *>(at + t * 2 * kHalfBytes + k * 16);
-}
-
-// kChunk steps: the class words cl[0], cl[32], ... against the chunk's words
-__device__ __forceinline__ void run_chunk(const RowChunk &r, const uint32_t *cl, v16f (&acc)[kTiles]) {
-#pragma unroll
-    for (int s = 0; s < kChunk; ++s) {
-        const uint32_t cw = cl[s * kSlots];
-        const v4i a = {(int)(cw & 0x44444444u), (int)(cw & 0x22222222u), (int)(cw & 0x11111111u),
-                       (int)((cw >> 3) & 0x11111111u)};
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t) {
-            const uint32_t xw = r.x[t][s / 4][s % 4];
-            const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
-                           (int)((xw >> 1) & 0x44444444u)};
-            acc[t] = mfma(a, b, acc[t]);
-        }
-    }
-}
-
-// Dynamic LDS: class words [2 halves][spad steps][32 slots], popcount(m_c) [32], then every wave's
-// area for row segments.
-template <bool kDist>
+// Dynamic LDS: popcount(m_c) [32], keys [2 tiles][4 groups][32 queries], popcount(x) parts of the
+// same shape, then the waves' areas.
+template <int P, bool kDist>
 __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W, int D,
-    int spad, uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
-    extern __shared__ uint32_t cls[];
-    uint32_t *popc_m = cls + 2 * spad * kSlots;
+    uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
+    using G = Geo<P>;
+    extern __shared__ uint32_t popc_m[];
+    int *keyq = reinterpret_cast<int *>(popc_m + kSlots);
+    int *popx = keyq + kTiles * 4 * kTile;
+    char *areas = reinterpret_cast<char *>(popx + kTiles * 4 * kTile);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int q = lane & (kTile - 1), h = lane >> 5;
     const int s0 = (W + 1) / 2;                  // words of the first half of a row; the second has W - s0
     const uint32_t tail = (D & 31) ? (1u << (D & 31)) - 1u : 0xffffffffu;
 
-    // The class word a lane meets at step s of half hh is the one its query word of that step was
-    // read from: word `first + s` of the row, or, in a piece moved back from the end of the row (see
-    // load_chunk), a word of the row's last four.  A moved piece counts only the words that no
+    // The class word a lane meets at step s is the one its query word of that step is read from:
+    // word h * s0 + wave * 4P + s of the row, or, in a piece moved back from the end of the row (see
+    // the fetch below), a word of the row's last four.  A moved piece counts only the words that no
     // earlier piece of the half holds; a step whose word lies outside the half counts nothing.
-    for (int idx = threadIdx.x; idx < 2 * spad * kSlots; idx += kMfmaWaves * kWave) {
-        const int j = idx & (kSlots - 1), hs = idx / kSlots;
-        const int hh = hs >= spad, s = hs - hh * spad;
-        const int unmoved = hh * s0 + (s & ~3);
+    uint32_t cw[G::kSteps];
+#pragma unroll
+    for (int s = 0; s < G::kSteps; ++s) {
+        const int unmoved = h * s0 + wave * G::kSteps + (s & ~3);
         const int w = min(unmoved, W - 4) + (s & 3);
         uint32_t m = 0;
-        if (w >= unmoved && w < (hh ? W : s0)) {
-            if (j < C) m = class_hv[(int64_t)j * W + w];
-            else if (j == kOnes) m = w == W - 1 ? tail : 0xffffffffu;
+        if (w >= unmoved && w < (h ? W : s0)) {
+            if (q < C) m = class_hv[(int64_t)q * W + w];
+            else if (q == kOnes) m = w == W - 1 ? tail : 0xffffffffu;
         }
-        cls[idx] = reverse3(m);
+        cw[s] = reverse3(m);
     }
     for (int j = wave; j < C; j += kMfmaWaves) {
         uint32_t n = 0;
@@ -169,10 +136,14 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     }
     __syncthreads();
 
-    // Which class slot each accumulator register of this lane belongs to, asked of the
-    // instruction itself: five elements of K carry the bits of the slot number on the class side
-    // (as 1, 1, 4, 4, 4) against 1, 2, 1, 2, 4 on the query side, products 1, 2, 4, 8, 16.
-    int slot[16];
+    // Which class slot each accumulator register of a lane belongs to, asked of the instruction
+    // itself: five elements of K carry the bits of the slot number on the class side (as 1, 1, 4,
+    // 4, 4) against 1, 2, 1, 2, 4 on the query side, products 1, 2, 4, 8, 16.  In the reduction
+    // wave w handles registers 4 * (w % 4) .. + 3 of tile w / 4: their slots and key bases
+    // ((popcount(m) << 10) | class; slots without a class start so high that no dot product brings
+    // them below a real one).
+    const int rg = wave & 3, rt = wave >> 2;
+    int slot4[4], base4[4];
     {
         const int bits = (q & 1 ? 0x2 : 0) | (q & 2 ? 0x20 : 0) | (q & 4 ? 0x600 : 0) | (q & 8 ? 0x6000 : 0) |
                          (q & 16 ? 0x60000 : 0);
@@ -182,131 +153,170 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         for (int r = 0; r < 16; ++r) z[r] = 0.0f;
         z = mfma(a, b, z);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) slot[r] = (int)z[r];
+        for (int j = 0; j < 4; ++j) {
+            const float v = rg == 0 ? z[j] : rg == 1 ? z[4 + j] : rg == 2 ? z[8 + j] : z[12 + j];
+            slot4[j] = (int)v;
+            base4[j] = slot4[j] < C ? (int)((popc_m[slot4[j]] << 10) | (uint32_t)slot4[j]) : INT_MAX;
+        }
     }
-    // key of (register r, dot product d): (popcount(m) - 2 d) * 1024 + class, signed; slots without
-    // a class start so high that no dot product brings them below a real one
-    int base[16];
+
+    // The lane's share of a job's fetch: load i brings piece (i * 64 + lane) % P of segment
+    // (i * 64 + lane) / P; segment g is (tile g / 64, half (g / 32) % 2, row g % 32).  A piece that
+    // would cross the end of the row is moved back to the row's last 16 bytes.
+    int row_of[G::kLoads], word_of[G::kLoads], park_at[G::kLoads];
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-        base[r] = slot[r] < C ? (int)((popc_m[slot[r]] << 10) | (uint32_t)slot[r]) : INT_MAX;
+    for (int i = 0; i < G::kLoads; ++i) {
+        const int id = i * kWave + lane, g = id / P, pc = id - g * P;
+        row_of[i] = (g >> 6) * kTile + (g & (kTile - 1));
+        word_of[i] = min(((g >> 5) & 1) * s0 + wave * G::kSteps + 4 * pc, W - 4);
+        park_at[i] = g * G::kSegBytes + pc * 16;
+    }
+    char *area = areas + wave * G::kAreaBytes;
+    const char *take_at = area + (h * kTile + q) * G::kSegBytes;
 
-    const int nc = spad / kChunk;
     const int64_t jobs = (N + kJob - 1) / kJob;
-    const int64_t stride = (int64_t)gridDim.x * kMfmaWaves;
-    int64_t job = (int64_t)blockIdx.x * kMfmaWaves + wave;
-    if (job >= jobs) return;   // wave-uniform; there is no block-wide barrier below
-
-    char *area = reinterpret_cast<char *>(popc_m + kSlots) + wave * kWaveBytes;
-    const uint32_t *cl = cls + (size_t)h * spad * kSlots + q;
-    auto rows_of = [&](int64_t jb, const uint32_t *(&rows)[kTiles][2]) {   // rows past N read row N - 1
+    u32x4_a4 f[G::kLoads];
+    auto fetch = [&](int64_t job) {   // rows past N read row N - 1
+#pragma unroll
+        for (int i = 0; i < G::kLoads; ++i) {
+            const int64_t n = job * kJob + row_of[i];
+            f[i] = *reinterpret_cast<const u32x4_a4 *>(hv + (n < N ? n : N - 1) * W + word_of[i]);
+        }
+    };
+    fetch(blockIdx.x);
+    for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
+        // the previous round's readers of this area passed that round's second barrier
+#pragma unroll
+        for (int i = 0; i < G::kLoads; ++i) *reinterpret_cast<u32x4 *>(area + park_at[i]) = f[i];
+        wave_sync_lds();
+        fetch(job + gridDim.x);                 // never under a condition; past the last job it reads row N - 1
+        __builtin_amdgcn_sched_barrier(0);      // the loads go out before the MFMAs, not after
+        u32x4 x[kTiles][P];
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int64_t n = jb * kJob + t * kTile + e * 16 + (lane >> 2);
-                rows[t][e] = hv + (n < N ? n : N - 1) * W;
-            }
-    };
-    const uint32_t *rows[kTiles][2], *rows_next[kTiles][2];
-    rows_of(job, rows);
-    rows_of(job + stride, rows_next);
-    Fetched f;
-    fetch_chunk(f, rows, 0, s0, W, lane);
-    for (;;) {
-        int64_t n_of[kTiles];
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t) n_of[t] = job * kJob + t * kTile + q;
+            for (int k = 0; k < P; ++k)
+                x[t][k] = *reinterpret_cast<const u32x4 *>(take_at + t * 2 * kTile * G::kSegBytes + k * 16);
+
         v16f acc[kTiles];
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-
-        for (int c = 0; c < nc; ++c) {
-            wave_sync_lds();              // every lane has taken the previous chunk
-            park_chunk(f, area, lane);
-            wave_sync_lds();
-            // the next fetch is never under a condition: after the last chunk it is the first chunk of
-            // the wave's next 64 queries (rows past N clamp, so a wave without a next job reads row N - 1)
-            const bool last = c + 1 == nc;
-            const uint32_t *from[kTiles][2];
 #pragma unroll
-            for (int t = 0; t < kTiles; ++t)
+        for (int s = 0; s < G::kSteps; ++s) {
+            const v4i a = {(int)(cw[s] & 0x44444444u), (int)(cw[s] & 0x22222222u), (int)(cw[s] & 0x11111111u),
+                           (int)((cw[s] >> 3) & 0x11111111u)};
 #pragma unroll
-                for (int e = 0; e < 2; ++e) from[t][e] = last ? rows_next[t][e] : rows[t][e];
-            fetch_chunk(f, from, last ? 0 : c + 1, s0, W, lane);
-            __builtin_amdgcn_sched_barrier(0);   // the loads go out before the MFMAs of this chunk, not after
-            RowChunk x;
-            take_chunk(x, area, q, h);
-            run_chunk(x, cl + (size_t)c * kChunk * kSlots, acc);
-        }
-
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t) {
-            // the key takes 2048 * dot off
-            int dot[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dot[r] = (int)acc[t][r];
-            int key = INT_MAX;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) key = min(key, base[r] - (dot[r] << 11));
-            key = min(key, __shfl_xor(key, 32, kWave));
-            if (h == (t & 1) && n_of[t] < N) pred[n_of[t]] = key & 1023;
-            if (kDist) {
-                int popc_x = 0;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) popc_x += slot[r] == kOnes ? dot[r] : 0;
-                popc_x += __shfl_xor(popc_x, 32, kWave);
-                if (n_of[t] < N) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (slot[r] < C)
-                            dist[n_of[t] * C + slot[r]] = (uint32_t)(popc_x + (base[r] >> 10) - 2 * dot[r]);
-                }
+            for (int t = 0; t < kTiles; ++t) {
+                const uint32_t xw = x[t][s / 4][s % 4];
+                const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
+                               (int)((xw >> 1) & 0x44444444u)};
+                acc[t] = mfma(a, b, acc[t]);
             }
         }
-        job += stride;
-        if (job >= jobs) break;
+
+        // partial dot products into the wave's own area, registers 2i and 2i + 1 in one word:
+        // [tile][group of four registers][lane][2 words]
+        wave_sync_lds();                        // every lane has taken its words out of the area
+        uint2 *mine = reinterpret_cast<uint2 *>(area);
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) rows[t][e] = rows_next[t][e];
-        rows_of(job + stride, rows_next);
+            for (int g = 0; g < 4; ++g) {
+                uint32_t pk[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    pk[i] = (uint32_t)acc[t][4 * g + 2 * i] | ((uint32_t)acc[t][4 * g + 2 * i + 1] << 16);
+                mine[(t * 4 + g) * kWave + lane] = make_uint2(pk[0], pk[1]);
+            }
+        __syncthreads();
+
+        // the halves of a word add up separately: eight partials stay far below 2^16
+        uint2 sum = make_uint2(0u, 0u);
+#pragma unroll
+        for (int v = 0; v < kMfmaWaves; ++v) {
+            const uint2 part = reinterpret_cast<const uint2 *>(areas + v * G::kAreaBytes)[(rt * 4 + rg) * kWave + lane];
+            sum.x += part.x;
+            sum.y += part.y;
+        }
+        const int dot[4] = {(int)(sum.x & 0xffffu), (int)(sum.x >> 16), (int)(sum.y & 0xffffu), (int)(sum.y >> 16)};
+        int key = INT_MAX;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) key = min(key, base4[j] - (dot[j] << 11));   // the key takes 2048 * dot off
+        key = min(key, __shfl_xor(key, 32, kWave));
+        if (h == 0) keyq[(rt * 4 + rg) * kTile + q] = key;
+        if (kDist) {
+            int part = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) part += slot4[j] == kOnes ? dot[j] : 0;
+            part += __shfl_xor(part, 32, kWave);
+            if (h == 0) popx[(rt * 4 + rg) * kTile + q] = part;
+        }
+        __syncthreads();
+
+        if (threadIdx.x < kJob) {
+            const int t = threadIdx.x >> 5, qq = threadIdx.x & (kTile - 1);
+            int k = keyq[(t * 4 + 0) * kTile + qq];
+#pragma unroll
+            for (int g = 1; g < 4; ++g) k = min(k, keyq[(t * 4 + g) * kTile + qq]);
+            const int64_t n = job * kJob + threadIdx.x;
+            if (n < N) pred[n] = k & 1023;
+        }
+        if (kDist) {
+            int popc_x = 0;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) popc_x += popx[(rt * 4 + g) * kTile + q];
+            const int64_t n = job * kJob + rt * kTile + q;
+            if (n < N) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (slot4[j] < C) dist[n * C + slot4[j]] = (uint32_t)(popc_x + (base4[j] >> 10) - 2 * dot[j]);
+            }
+        }
     }
 }
 
-constexpr int64_t kMfmaQueries = 32768;   // from here on there is a job for most waves of the chip
+constexpr int64_t kMfmaQueries = 32768;   // from here on there is a job for most blocks of the chip
+
+template <int P>
+static int launch_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv, uint32_t *dist,
+                       int32_t *pred, hipStream_t s) {
+    const size_t lds = Geo<P>::kLdsBytes;
+    const void *kern = dist ? reinterpret_cast<const void *>(search_mfma_kernel<P, true>)
+                            : reinterpret_cast<const void *>(search_mfma_kernel<P, false>);
+    if (lds > 64 * 1024)
+        HDC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const int64_t jobs = (N + kJob - 1) / kJob;
+    const int64_t blocks = std::min<int64_t>(256, jobs);
+    {
+        ProfScope prof(c, HDC_K_SEARCH, s);
+        if (dist)
+            hipLaunchKernelGGL((search_mfma_kernel<P, true>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s, hv,
+                               N, class_hv, c->p.C, c->W, c->p.D, dist, pred);
+        else
+            hipLaunchKernelGGL((search_mfma_kernel<P, false>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s,
+                               hv, N, class_hv, c->p.C, c->W, c->p.D, dist, pred);
+    }
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
 
 // Takes the search if it is of the shape this kernel is for; returns false otherwise.
 bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                      uint32_t *dist, int32_t *pred, hipStream_t s, int *rc) {
     const int C = c->p.C, W = c->W;
     if (N < kMfmaQueries || C < 7 || C > kOnes || W < 4) return false;
-    const int steps = (W + 1) / 2;
-    const int spad = (steps + kChunk - 1) / kChunk * kChunk;
-    const size_t lds = ((size_t)2 * spad * kSlots + kSlots) * 4 + (size_t)kMfmaWaves * kWaveBytes;
-    if (lds > 160 * 1024) return false;   // D up to about 19000
-    *rc = [&]() -> int {
-        const void *kern = dist ? reinterpret_cast<const void *>(search_mfma_kernel<true>)
-                                : reinterpret_cast<const void *>(search_mfma_kernel<false>);
-        if (lds > 64 * 1024)
-            HDC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        const int64_t jobs = (N + kJob - 1) / kJob;
-        const int64_t blocks = std::min<int64_t>(256, (jobs + kMfmaWaves - 1) / kMfmaWaves);
-        {
-            ProfScope prof(c, HDC_K_SEARCH, s);
-            if (dist)
-                hipLaunchKernelGGL(search_mfma_kernel<true>, dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s,
-                                   hv, N, class_hv, C, W, c->p.D, spad, dist, pred);
-            else
-                hipLaunchKernelGGL(search_mfma_kernel<false>, dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s,
-                                   hv, N, class_hv, C, W, c->p.D, spad, dist, pred);
-        }
-        HDC_HIP(hipGetLastError());
-        return HDC_OK;
-    }();
-    return true;
+    // pieces of 4 words per wave and row half: eight waves cover the longer half
+    const int pieces = ((W + 1) / 2 + 4 * kMfmaWaves - 1) / (4 * kMfmaWaves);
+    switch (pieces) {
+    case 1: *rc = launch_mfma<1>(c, hv, N, class_hv, dist, pred, s); return true;
+    case 2: *rc = launch_mfma<2>(c, hv, N, class_hv, dist, pred, s); return true;
+    case 3: *rc = launch_mfma<3>(c, hv, N, class_hv, dist, pred, s); return true;
+    case 4: *rc = launch_mfma<4>(c, hv, N, class_hv, dist, pred, s); return true;
+    case 5: *rc = launch_mfma<5>(c, hv, N, class_hv, dist, pred, s); return true;
+    default: return false;   // D above 10240: the waves' areas would not fit in LDS
+    }
 }
 
 }  // namespace hdc

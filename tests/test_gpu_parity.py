@@ -225,7 +225,7 @@ def test_search_bit_exact(D, C, N):
                                    # from 32768 queries on, 7 to 31 classes: the matrix-core kernel (64 queries
                                    # per wave at a time, a row split in two halves, chunks of 32 words per half)
                                    (10000, 26, 32771), (10000, 7, 32833), (2049, 31, 32768), (128, 9, 40001),
-                                   (20000, 12, 32770), (4127, 16, 32801), (10000, 32, 32768), (10000, 6, 32768)])
+                                   (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 6, 32768)])
 def test_search_long_streams_bit_exact(D, C, N):
     rng = np.random.default_rng(D + 13 * C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
