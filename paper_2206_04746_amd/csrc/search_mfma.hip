@@ -38,10 +38,9 @@
 //
 // The accumulators come back with the query on the lane and the class slot on the register (and
 // the wave half).  Each wave writes its partial dot products (at most 64 * 4P each: two to a
-// 32-bit word) to its LDS area; after a barrier
-// wave w adds up, over the eight waves, four registers of one tile, turns them into keys
-// (distance, class) and takes their minimum; after a second barrier 64 threads take the minimum
-// over the four register groups.  Slot 31 holds an all-ones class: its dot product is
+// 32-bit word) to its LDS area; after a barrier wave w adds up, over the eight waves, four
+// registers of one tile, turns them into keys (distance, class) and takes their minimum; after
+// a second barrier 64 threads take the minimum over the four register groups.  Slot 31 holds an all-ones class: its dot product is
 // popcount(x), needed only when distances are written out.  Hence C <= 31.
 #include "hdc_internal.h"
 
@@ -64,6 +63,9 @@ constexpr int kJob = kTile * kTiles;
 constexpr int kSegs = kTiles * 2 * kTile;   // (tile, half, row) segments a wave fetches per job
 constexpr int kOnes = kSlots - 1;           // the slot of the all-ones class
 constexpr int kPartialBytes = kTiles * 8 * kWave * 4;    // a wave's partial dot products, two to a word
+constexpr int kRegs = kTiles * 16 / kMfmaWaves;          // accumulator registers a wave reduces (of one tile)
+constexpr int kGroups = 16 / kRegs;                     // such groups per tile
+static_assert(kRegs == 2 || kRegs == 4, "one or two packed words per lane and group");
 
 // Geometry for P 16-byte pieces per segment: a wave's slice of a row half is 4P words.
 template <int P>
@@ -74,7 +76,7 @@ struct Geo {
     static constexpr int kSegBytes = 16 * (P % 2 ? P + 2 : P + 1);
     static constexpr int kAreaBytes = kSegs * kSegBytes > kPartialBytes ? kSegs * kSegBytes : kPartialBytes;
     static constexpr int kLoads = kSegs * P / kWave;   // 16-byte loads per lane per job (2P)
-    static constexpr size_t kLdsBytes = kSlots * 4 + kTiles * 4 * kTile * 4 * 2 + (size_t)kMfmaWaves * kAreaBytes;
+    static constexpr size_t kLdsBytes = kSlots * 4 + kTiles * kGroups * kTile * 4 * 2 + (size_t)kMfmaWaves * kAreaBytes;
 };
 
 // bits 0..2 of every nibble reversed, bit 3 in place
@@ -103,8 +105,8 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     using G = Geo<P>;
     extern __shared__ uint32_t popc_m[];
     int *keyq = reinterpret_cast<int *>(popc_m + kSlots);
-    int *popx = keyq + kTiles * 4 * kTile;
-    char *areas = reinterpret_cast<char *>(popx + kTiles * 4 * kTile);
+    int *popx = keyq + kTiles * kGroups * kTile;
+    char *areas = reinterpret_cast<char *>(popx + kTiles * kGroups * kTile);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int q = lane & (kTile - 1), h = lane >> 5;
@@ -139,11 +141,11 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // Which class slot each accumulator register of a lane belongs to, asked of the instruction
     // itself: five elements of K carry the bits of the slot number on the class side (as 1, 1, 4,
     // 4, 4) against 1, 2, 1, 2, 4 on the query side, products 1, 2, 4, 8, 16.  In the reduction
-    // wave w handles registers 4 * (w % 4) .. + 3 of tile w / 4: their slots and key bases
+    // wave w handles kRegs registers of one tile (group w % kGroups of tile w / kGroups): their slots and key bases
     // ((popcount(m) << 10) | class; slots without a class start so high that no dot product brings
     // them below a real one).
-    const int rg = wave & 3, rt = wave >> 2;
-    int slot4[4], base4[4];
+    const int rg = wave % kGroups, rt = wave / kGroups;
+    int slot_of[kRegs], base_of[kRegs];
     {
         const int bits = (q & 1 ? 0x2 : 0) | (q & 2 ? 0x20 : 0) | (q & 4 ? 0x600 : 0) | (q & 8 ? 0x6000 : 0) |
                          (q & 16 ? 0x60000 : 0);
@@ -153,10 +155,12 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         for (int r = 0; r < 16; ++r) z[r] = 0.0f;
         z = mfma(a, b, z);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float v = rg == 0 ? z[j] : rg == 1 ? z[4 + j] : rg == 2 ? z[8 + j] : z[12 + j];
-            slot4[j] = (int)v;
-            base4[j] = slot4[j] < C ? (int)((popc_m[slot4[j]] << 10) | (uint32_t)slot4[j]) : INT_MAX;
+        for (int j = 0; j < kRegs; ++j) {
+            float v = 0.0f;
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) v = rg == g ? z[g * kRegs + j] : v;
+            slot_of[j] = (int)v;
+            base_of[j] = slot_of[j] < C ? (int)((popc_m[slot_of[j]] << 10) | (uint32_t)slot_of[j]) : INT_MAX;
         }
     }
 
@@ -217,61 +221,77 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         }
 
         // partial dot products into the wave's own area, registers 2i and 2i + 1 in one word:
-        // [tile][group of four registers][lane][2 words]
+        // [tile][group of kRegs registers][lane][kRegs / 2 words]
         wave_sync_lds();                        // every lane has taken its words out of the area
-        uint2 *mine = reinterpret_cast<uint2 *>(area);
+        uint32_t *mine = reinterpret_cast<uint32_t *>(area);
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint32_t pk[2];
+            for (int g = 0; g < kGroups; ++g) {
+                uint32_t pk[kRegs / 2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    pk[i] = (uint32_t)acc[t][4 * g + 2 * i] | ((uint32_t)acc[t][4 * g + 2 * i + 1] << 16);
-                mine[(t * 4 + g) * kWave + lane] = make_uint2(pk[0], pk[1]);
+                for (int i = 0; i < kRegs / 2; ++i)
+                    pk[i] = (uint32_t)acc[t][kRegs * g + 2 * i] | ((uint32_t)acc[t][kRegs * g + 2 * i + 1] << 16);
+                uint32_t *at = mine + ((t * kGroups + g) * kWave + lane) * (kRegs / 2);
+                if (kRegs == 4) *reinterpret_cast<uint2 *>(at) = make_uint2(pk[0], pk[kRegs / 2 - 1]);
+                else at[0] = pk[0];
             }
         __syncthreads();
 
         // the halves of a word add up separately: eight partials stay far below 2^16
-        uint2 sum = make_uint2(0u, 0u);
+        uint32_t sum[kRegs / 2];
+#pragma unroll
+        for (int i = 0; i < kRegs / 2; ++i) sum[i] = 0;
 #pragma unroll
         for (int v = 0; v < kMfmaWaves; ++v) {
-            const uint2 part = reinterpret_cast<const uint2 *>(areas + v * G::kAreaBytes)[(rt * 4 + rg) * kWave + lane];
-            sum.x += part.x;
-            sum.y += part.y;
+            const uint32_t *at = reinterpret_cast<const uint32_t *>(areas + v * G::kAreaBytes) +
+                                 ((rt * kGroups + rg) * kWave + lane) * (kRegs / 2);
+            if (kRegs == 4) {
+                const uint2 part = *reinterpret_cast<const uint2 *>(at);
+                sum[0] += part.x;
+                sum[kRegs / 2 - 1] += part.y;
+            } else {
+                sum[0] += at[0];
+            }
         }
-        const int dot[4] = {(int)(sum.x & 0xffffu), (int)(sum.x >> 16), (int)(sum.y & 0xffffu), (int)(sum.y >> 16)};
+        int dot[kRegs];
+#pragma unroll
+        for (int i = 0; i < kRegs / 2; ++i) {
+            dot[2 * i] = (int)(sum[i] & 0xffffu);
+            dot[2 * i + 1] = (int)(sum[i] >> 16);
+        }
         int key = INT_MAX;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) key = min(key, base4[j] - (dot[j] << 11));   // the key takes 2048 * dot off
+        for (int j = 0; j < kRegs; ++j) key = min(key, base_of[j] - (dot[j] << 11));   // the key takes 2048 * dot off
         key = min(key, __shfl_xor(key, 32, kWave));
-        if (h == 0) keyq[(rt * 4 + rg) * kTile + q] = key;
+        if (h == 0) keyq[(rt * kGroups + rg) * kTile + q] = key;
         if (kDist) {
             int part = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) part += slot4[j] == kOnes ? dot[j] : 0;
+            for (int j = 0; j < kRegs; ++j) part += slot_of[j] == kOnes ? dot[j] : 0;
             part += __shfl_xor(part, 32, kWave);
-            if (h == 0) popx[(rt * 4 + rg) * kTile + q] = part;
+            if (h == 0) popx[(rt * kGroups + rg) * kTile + q] = part;
         }
         __syncthreads();
 
         if (threadIdx.x < kJob) {
             const int t = threadIdx.x >> 5, qq = threadIdx.x & (kTile - 1);
-            int k = keyq[(t * 4 + 0) * kTile + qq];
+            int k = keyq[(t * kGroups + 0) * kTile + qq];
 #pragma unroll
-            for (int g = 1; g < 4; ++g) k = min(k, keyq[(t * 4 + g) * kTile + qq]);
+            for (int g = 1; g < kGroups; ++g) k = min(k, keyq[(t * kGroups + g) * kTile + qq]);
             const int64_t n = job * kJob + threadIdx.x;
             if (n < N) pred[n] = k & 1023;
         }
         if (kDist) {
             int popc_x = 0;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) popc_x += popx[(rt * 4 + g) * kTile + q];
+            for (int g = 0; g < kGroups; ++g) popc_x += popx[(rt * kGroups + g) * kTile + q];
             const int64_t n = job * kJob + rt * kTile + q;
             if (n < N) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (slot4[j] < C) dist[n * C + slot4[j]] = (uint32_t)(popc_x + (base4[j] >> 10) - 2 * dot[j]);
+                for (int j = 0; j < kRegs; ++j)
+                    if (slot_of[j] < C)
+                        dist[n * C + slot_of[j]] = (uint32_t)(popc_x + (base_of[j] >> 10) - 2 * dot[j]);
             }
         }
     }
@@ -306,7 +326,9 @@ static int launch_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uin
 bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                      uint32_t *dist, int32_t *pred, hipStream_t s, int *rc) {
     const int C = c->p.C, W = c->W;
-    if (N < kMfmaQueries || C < 7 || C > kOnes || W < 4) return false;
+    // fewer classes: the row-per-16-lanes kernel is as fast or faster (measured at D = 10000: it takes
+    // 0.30 ms for a million queries and 10 classes, 0.31 ms with distances; this kernel 0.29 and 0.34)
+    if (N < kMfmaQueries || C < (dist ? 12 : 10) || C > kOnes || W < 4) return false;
     // pieces of 4 words per wave and row half: eight waves cover the longer half
     const int pieces = ((W + 1) / 2 + 4 * kMfmaWaves - 1) / (4 * kMfmaWaves);
     switch (pieces) {
