@@ -60,24 +60,32 @@ constexpr int kSlots = 32;       // class slots of an MFMA (its M)
 constexpr int kTile = 32;        // queries of an MFMA (its N)
 constexpr int kTiles = 2;        // tiles a block carries at a time
 constexpr int kJob = kTile * kTiles;
-constexpr int kSegs = kTiles * 2 * kTile;   // (tile, half, row) segments a wave fetches per job
-constexpr int kOnes = kSlots - 1;           // the slot of the all-ones class
+constexpr int kWaveRows = kJob / kMfmaWaves;   // rows of a job a wave fetches
+constexpr int kOnes = kSlots - 1;              // the slot of the all-ones class
 constexpr int kPartialBytes = kTiles * 8 * kWave * 4;    // a wave's partial dot products, two to a word
 constexpr int kRegs = kTiles * 16 / kMfmaWaves;          // accumulator registers a wave reduces (of one tile)
 constexpr int kGroups = 16 / kRegs;                     // such groups per tile
-static_assert(kRegs == 2 || kRegs == 4, "one or two packed words per lane and group");
+static_assert(kRegs == 4, "two packed words per lane and group");
 
-// Geometry for P 16-byte pieces per segment: a wave's slice of a row half is 4P words.
-template <int P>
-struct Geo {
-    static constexpr int kSteps = 4 * P;             // words of a row half per wave = MFMA steps per job
-    // a segment and its padding in LDS: an odd number of 16-byte units apart, so that the 16-byte
-    // reads of 8 neighbouring lanes fall into different banks
-    static constexpr int kSegBytes = 16 * (P % 2 ? P + 2 : P + 1);
-    static constexpr int kAreaBytes = kSegs * kSegBytes > kPartialBytes ? kSegs * kSegBytes : kPartialBytes;
-    static constexpr int kLoads = kSegs * P / kWave;   // 16-byte loads per lane per job (2P)
-    static constexpr size_t kLdsBytes = kSlots * 4 + kTiles * kGroups * kTile * 4 * 2 + (size_t)kMfmaWaves * kAreaBytes;
+// Host and device agree on the geometry of a row: the first half is s0 words (a multiple of 4, so
+// that both halves start on a 16-byte boundary of the row), each wave takes 4P words of each half,
+// and a row's image in LDS is row_bytes long (an odd number of 16-byte units: the 16-byte reads of
+// 8 neighbouring lanes, a row each, then fall into different banks).
+struct RowGeo {
+    int s0, pieces, row_bytes;
+    size_t lds_bytes;
 };
+static inline RowGeo row_geo(int W) {
+    RowGeo g;
+    g.s0 = ((W + 1) / 2 + 3) / 4 * 4;
+    g.pieces = (g.s0 / 4 + kMfmaWaves - 1) / kMfmaWaves;
+    const int units = (W + 3) / 4;
+    g.row_bytes = 16 * (units | 1);
+    // the last wave's slice of the second half may reach past the last row's image: one more image of slack
+    g.lds_bytes = (size_t)(kSlots + 2 * kTiles * kGroups * kTile) * 4 + (size_t)(kJob + 1) * g.row_bytes +
+                  (size_t)kMfmaWaves * kPartialBytes;
+    return g;
+}
 
 // bits 0..2 of every nibble reversed, bit 3 in place
 __device__ __forceinline__ uint32_t reverse3(uint32_t m) {
@@ -90,40 +98,32 @@ __device__ __forceinline__ v16f mfma(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-__device__ __forceinline__ void wave_sync_lds() {   // LDS written by some lanes of the wave, read by others
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Dynamic LDS: popcount(m_c) [32], keys [2 tiles][4 groups][32 queries], popcount(x) parts of the
-// same shape, then the waves' areas.
+// same shape, the images of the job's 64 rows (and one of slack), then the waves' partial sums.
 template <int P, bool kDist>
 __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W, int D,
-    uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
-    using G = Geo<P>;
+    int s0, int row_bytes, uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
+    constexpr int kSteps = 4 * P;      // words of a row half per wave = MFMA steps per job
+    constexpr int kLoads = 2 * P;      // 16-byte loads per lane per job: 8 rows of at most 16P pieces over 64 lanes
     extern __shared__ uint32_t popc_m[];
     int *keyq = reinterpret_cast<int *>(popc_m + kSlots);
     int *popx = keyq + kTiles * kGroups * kTile;
-    char *areas = reinterpret_cast<char *>(popx + kTiles * kGroups * kTile);
+    char *rows = reinterpret_cast<char *>(popx + kTiles * kGroups * kTile);
+    char *partials = rows + (size_t)(kJob + 1) * row_bytes;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int q = lane & (kTile - 1), h = lane >> 5;
-    const int s0 = (W + 1) / 2;                  // words of the first half of a row; the second has W - s0
     const uint32_t tail = (D & 31) ? (1u << (D & 31)) - 1u : 0xffffffffu;
 
-    // The class word a lane meets at step s is the one its query word of that step is read from:
-    // word h * s0 + wave * 4P + s of the row, or, in a piece moved back from the end of the row (see
-    // the fetch below), a word of the row's last four.  A moved piece counts only the words that no
-    // earlier piece of the half holds; a step whose word lies outside the half counts nothing.
-    uint32_t cw[G::kSteps];
+    // The lane's class words: slot q's words h * s0 + wave * 4P + s of the class vector, zero where
+    // that is outside the half (the row words they meet there are other words or no words at all).
+    uint32_t cw[kSteps];
 #pragma unroll
-    for (int s = 0; s < G::kSteps; ++s) {
-        const int unmoved = h * s0 + wave * G::kSteps + (s & ~3);
-        const int w = min(unmoved, W - 4) + (s & 3);
+    for (int s = 0; s < kSteps; ++s) {
+        const int w = h * s0 + wave * kSteps + s;
         uint32_t m = 0;
-        if (w >= unmoved && w < (h ? W : s0)) {
+        if (w < (h ? W : s0)) {
             if (q < C) m = class_hv[(int64_t)q * W + w];
             else if (q == kOnes) m = w == W - 1 ? tail : 0xffffffffu;
         }
@@ -141,9 +141,9 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // Which class slot each accumulator register of a lane belongs to, asked of the instruction
     // itself: five elements of K carry the bits of the slot number on the class side (as 1, 1, 4,
     // 4, 4) against 1, 2, 1, 2, 4 on the query side, products 1, 2, 4, 8, 16.  In the reduction
-    // wave w handles kRegs registers of one tile (group w % kGroups of tile w / kGroups): their slots and key bases
-    // ((popcount(m) << 10) | class; slots without a class start so high that no dot product brings
-    // them below a real one).
+    // wave w handles kRegs registers of one tile (group w % kGroups of tile w / kGroups): their
+    // slots and key bases ((popcount(m) << 10) | class; slots without a class start so high that
+    // no dot product brings them below a real one).
     const int rg = wave % kGroups, rt = wave / kGroups;
     int slot_of[kRegs], base_of[kRegs];
     {
@@ -164,102 +164,107 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         }
     }
 
-    // The lane's share of a job's fetch: load i brings piece (i * 64 + lane) % P of segment
-    // (i * 64 + lane) / P; segment g is (tile g / 64, half (g / 32) % 2, row g % 32).  A piece that
-    // would cross the end of the row is moved back to the row's last 16 bytes.
-    int row_of[G::kLoads], word_of[G::kLoads], park_at[G::kLoads];
+    // The lane's share of a job's fetch.  Wave v brings rows 8v .. 8v + 7 of the job: their whole
+    // 16-byte pieces, piece after piece over the lanes (load i: piece number i * 64 + lane of the
+    // 8 * (W / 4); numbers past the end repeat the last piece), and, where W is no multiple of 4,
+    // the one to three words left over, a word per lane.  One register per load: the word's offset
+    // from the job's first word in bits 0..15, the 16-byte unit of the images from bit 16.
+    const int whole = W / 4;
+    uint32_t load_of[kLoads];
 #pragma unroll
-    for (int i = 0; i < G::kLoads; ++i) {
-        const int id = i * kWave + lane, g = id / P, pc = id - g * P;
-        row_of[i] = (g >> 6) * kTile + (g & (kTile - 1));
-        word_of[i] = min(((g >> 5) & 1) * s0 + wave * G::kSteps + 4 * pc, W - 4);
-        park_at[i] = g * G::kSegBytes + pc * 16;
+    for (int i = 0; i < kLoads; ++i) {
+        const int id = min(i * kWave + lane, kWaveRows * whole - 1);
+        const int r = wave * kWaveRows + id / whole, pc = id % whole;
+        load_of[i] = (uint32_t)(r * W + 4 * pc) | ((uint32_t)(r * (row_bytes / 16) + pc) << 16);
     }
-    char *area = areas + wave * G::kAreaBytes;
-    const char *take_at = area + (h * kTile + q) * G::kSegBytes;
+    const int left = W - 4 * whole;                  // 0..3 words
+    const int lr = wave * kWaveRows + (lane >> 2) % kWaveRows, lj = min(lane & 3, max(left - 1, 0));
+    const int left_word = lr * W + 4 * whole + lj;   // lanes past the words left over repeat the last one
+    char *left_at = rows + lr * row_bytes + (4 * whole + lj) * 4;
+
+    const char *take_at = rows + q * row_bytes + (h * s0 + wave * kSteps) * 4;
+    const int tile_bytes = kTile * row_bytes;
+    uint32_t *mine = reinterpret_cast<uint32_t *>(partials + wave * kPartialBytes);
 
     const int64_t jobs = (N + kJob - 1) / kJob;
-    u32x4_a4 f[G::kLoads];
-    auto fetch = [&](int64_t job) {   // rows past N read row N - 1
+    const int64_t last_word = N * W - 1;
+    u32x4_a4 f[kLoads];
+    uint32_t f_left = 0;
+    auto fetch = [&](int64_t job) {   // rows past N read the last row's last words
+        const int64_t first = job * kJob * W;
 #pragma unroll
-        for (int i = 0; i < G::kLoads; ++i) {
-            const int64_t n = job * kJob + row_of[i];
-            f[i] = *reinterpret_cast<const u32x4_a4 *>(hv + (n < N ? n : N - 1) * W + word_of[i]);
+        for (int i = 0; i < kLoads; ++i) {
+            const int64_t at = first + (load_of[i] & 0xffffu);
+            f[i] = *reinterpret_cast<const u32x4_a4 *>(hv + (at + 3 <= last_word ? at : last_word - 3));
+        }
+        if (left) {   // the same for every thread of the launch
+            const int64_t at = first + left_word;
+            f_left = hv[at <= last_word ? at : last_word];
         }
     };
     fetch(blockIdx.x);
     for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
-        // the previous round's readers of this area passed that round's second barrier
+        // (every wave has taken the previous job's words: it has passed that job's second barrier)
 #pragma unroll
-        for (int i = 0; i < G::kLoads; ++i) *reinterpret_cast<u32x4 *>(area + park_at[i]) = f[i];
-        wave_sync_lds();
-        fetch(job + gridDim.x);                 // never under a condition; past the last job it reads row N - 1
+        for (int i = 0; i < kLoads; ++i) *reinterpret_cast<u32x4 *>(rows + (load_of[i] >> 16) * 16) = f[i];
+        if (left) *reinterpret_cast<uint32_t *>(left_at) = f_left;
+        __syncthreads();
+        fetch(job + gridDim.x);                 // past the last job it reads the buffer's last words
         __builtin_amdgcn_sched_barrier(0);      // the loads go out before the MFMAs, not after
-        u32x4 x[kTiles][P];
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t)
-#pragma unroll
-            for (int k = 0; k < P; ++k)
-                x[t][k] = *reinterpret_cast<const u32x4 *>(take_at + t * 2 * kTile * G::kSegBytes + k * 16);
 
+        // the lane's words come out of the images a piece (four steps) ahead of their use
+        auto take = [&](u32x4(&x)[kTiles], int k) {
+#pragma unroll
+            for (int t = 0; t < kTiles; ++t) x[t] = *reinterpret_cast<const u32x4 *>(take_at + t * tile_bytes + k * 16);
+        };
         v16f acc[kTiles];
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        u32x4 x[2][kTiles];
+        take(x[0], 0);
 #pragma unroll
-        for (int s = 0; s < G::kSteps; ++s) {
-            const v4i a = {(int)(cw[s] & 0x44444444u), (int)(cw[s] & 0x22222222u), (int)(cw[s] & 0x11111111u),
-                           (int)((cw[s] >> 3) & 0x11111111u)};
+        for (int k = 0; k < P; ++k) {
+            if (k + 1 < P) take(x[(k + 1) & 1], k + 1);
 #pragma unroll
-            for (int t = 0; t < kTiles; ++t) {
-                const uint32_t xw = x[t][s / 4][s % 4];
-                const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
-                               (int)((xw >> 1) & 0x44444444u)};
-                acc[t] = mfma(a, b, acc[t]);
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t c = cw[4 * k + e];
+                const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
+                               (int)((c >> 3) & 0x11111111u)};
+#pragma unroll
+                for (int t = 0; t < kTiles; ++t) {
+                    const uint32_t xw = x[k & 1][t][e];
+                    const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
+                                   (int)((xw >> 1) & 0x44444444u)};
+                    acc[t] = mfma(a, b, acc[t]);
+                }
             }
         }
 
-        // partial dot products into the wave's own area, registers 2i and 2i + 1 in one word:
-        // [tile][group of kRegs registers][lane][kRegs / 2 words]
-        wave_sync_lds();                        // every lane has taken its words out of the area
-        uint32_t *mine = reinterpret_cast<uint32_t *>(area);
+        // partial dot products, registers 2i and 2i + 1 in one word: [tile][group of four registers][lane][2 words]
 #pragma unroll
         for (int t = 0; t < kTiles; ++t)
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) {
-                uint32_t pk[kRegs / 2];
+                uint32_t pk[2];
 #pragma unroll
-                for (int i = 0; i < kRegs / 2; ++i)
+                for (int i = 0; i < 2; ++i)
                     pk[i] = (uint32_t)acc[t][kRegs * g + 2 * i] | ((uint32_t)acc[t][kRegs * g + 2 * i + 1] << 16);
-                uint32_t *at = mine + ((t * kGroups + g) * kWave + lane) * (kRegs / 2);
-                if (kRegs == 4) *reinterpret_cast<uint2 *>(at) = make_uint2(pk[0], pk[kRegs / 2 - 1]);
-                else at[0] = pk[0];
+                *reinterpret_cast<uint2 *>(mine + ((t * kGroups + g) * kWave + lane) * 2) = make_uint2(pk[0], pk[1]);
             }
         __syncthreads();
 
         // the halves of a word add up separately: eight partials stay far below 2^16
-        uint32_t sum[kRegs / 2];
-#pragma unroll
-        for (int i = 0; i < kRegs / 2; ++i) sum[i] = 0;
+        uint2 sum = make_uint2(0u, 0u);
 #pragma unroll
         for (int v = 0; v < kMfmaWaves; ++v) {
-            const uint32_t *at = reinterpret_cast<const uint32_t *>(areas + v * G::kAreaBytes) +
-                                 ((rt * kGroups + rg) * kWave + lane) * (kRegs / 2);
-            if (kRegs == 4) {
-                const uint2 part = *reinterpret_cast<const uint2 *>(at);
-                sum[0] += part.x;
-                sum[kRegs / 2 - 1] += part.y;
-            } else {
-                sum[0] += at[0];
-            }
+            const uint2 part = *reinterpret_cast<const uint2 *>(
+                reinterpret_cast<const uint32_t *>(partials + v * kPartialBytes) + ((rt * kGroups + rg) * kWave + lane) * 2);
+            sum.x += part.x;
+            sum.y += part.y;
         }
-        int dot[kRegs];
-#pragma unroll
-        for (int i = 0; i < kRegs / 2; ++i) {
-            dot[2 * i] = (int)(sum[i] & 0xffffu);
-            dot[2 * i + 1] = (int)(sum[i] >> 16);
-        }
+        const int dot[kRegs] = {(int)(sum.x & 0xffffu), (int)(sum.x >> 16), (int)(sum.y & 0xffffu), (int)(sum.y >> 16)};
         int key = INT_MAX;
 #pragma unroll
         for (int j = 0; j < kRegs; ++j) key = min(key, base_of[j] - (dot[j] << 11));   // the key takes 2048 * dot off
@@ -300,23 +305,22 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 constexpr int64_t kMfmaQueries = 32768;   // from here on there is a job for most blocks of the chip
 
 template <int P>
-static int launch_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv, uint32_t *dist,
-                       int32_t *pred, hipStream_t s) {
-    const size_t lds = Geo<P>::kLdsBytes;
+static int launch_mfma(hdc_ctx_impl *c, const RowGeo &g, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
+                       uint32_t *dist, int32_t *pred, hipStream_t s) {
     const void *kern = dist ? reinterpret_cast<const void *>(search_mfma_kernel<P, true>)
                             : reinterpret_cast<const void *>(search_mfma_kernel<P, false>);
-    if (lds > 64 * 1024)
-        HDC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (g.lds_bytes > 64 * 1024)
+        HDC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes));
     const int64_t jobs = (N + kJob - 1) / kJob;
     const int64_t blocks = std::min<int64_t>(256, jobs);
     {
         ProfScope prof(c, HDC_K_SEARCH, s);
         if (dist)
-            hipLaunchKernelGGL((search_mfma_kernel<P, true>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s, hv,
-                               N, class_hv, c->p.C, c->W, c->p.D, dist, pred);
+            hipLaunchKernelGGL((search_mfma_kernel<P, true>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave),
+                               g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0, g.row_bytes, dist, pred);
         else
-            hipLaunchKernelGGL((search_mfma_kernel<P, false>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave), lds, s,
-                               hv, N, class_hv, c->p.C, c->W, c->p.D, dist, pred);
+            hipLaunchKernelGGL((search_mfma_kernel<P, false>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave),
+                               g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0, g.row_bytes, dist, pred);
     }
     HDC_HIP(hipGetLastError());
     return HDC_OK;
@@ -326,18 +330,17 @@ static int launch_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uin
 bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                      uint32_t *dist, int32_t *pred, hipStream_t s, int *rc) {
     const int C = c->p.C, W = c->W;
-    // fewer classes: the row-per-16-lanes kernel is as fast or faster (measured at D = 10000: it takes
-    // 0.30 ms for a million queries and 10 classes, 0.31 ms with distances; this kernel 0.29 and 0.34)
+    // fewer classes: the row-per-16-lanes kernel is as fast or faster
     if (N < kMfmaQueries || C < (dist ? 12 : 10) || C > kOnes || W < 4) return false;
-    // pieces of 4 words per wave and row half: eight waves cover the longer half
-    const int pieces = ((W + 1) / 2 + 4 * kMfmaWaves - 1) / (4 * kMfmaWaves);
-    switch (pieces) {
-    case 1: *rc = launch_mfma<1>(c, hv, N, class_hv, dist, pred, s); return true;
-    case 2: *rc = launch_mfma<2>(c, hv, N, class_hv, dist, pred, s); return true;
-    case 3: *rc = launch_mfma<3>(c, hv, N, class_hv, dist, pred, s); return true;
-    case 4: *rc = launch_mfma<4>(c, hv, N, class_hv, dist, pred, s); return true;
-    case 5: *rc = launch_mfma<5>(c, hv, N, class_hv, dist, pred, s); return true;
-    default: return false;   // D above 10240: the waves' areas would not fit in LDS
+    const RowGeo g = row_geo(W);
+    if (g.lds_bytes > 160 * 1024) return false;   // D above 10240 or so: the job's rows would not fit in LDS
+    switch (g.pieces) {
+    case 1: *rc = launch_mfma<1>(c, g, hv, N, class_hv, dist, pred, s); return true;
+    case 2: *rc = launch_mfma<2>(c, g, hv, N, class_hv, dist, pred, s); return true;
+    case 3: *rc = launch_mfma<3>(c, g, hv, N, class_hv, dist, pred, s); return true;
+    case 4: *rc = launch_mfma<4>(c, g, hv, N, class_hv, dist, pred, s); return true;
+    case 5: *rc = launch_mfma<5>(c, g, hv, N, class_hv, dist, pred, s); return true;
+    default: return false;
     }
 }
 
