@@ -222,11 +222,11 @@ def test_search_bit_exact(D, C, N):
                                    (8001, 8, 8197), (10000, 10, 8195), (10240, 1, 8193), (12000, 26, 8194),
                                    (16384, 16, 8195), (24000, 5, 8193), (31000, 4, 8194), (32768, 2, 8195),
                                    (10000, 40, 8193),
-                                   # from 32768 queries on, 12 to 31 classes (10 without distances), D up to 10240: the
+                                   # from 32768 queries on, 9 to 31 classes, D up to 10240: the
                                    # matrix-core kernel (64 rows per block at a time, a row split in two halves, every
                                    # half in eight slices); around it the shapes that just miss it
                                    (10000, 26, 32771), (10000, 12, 32833), (2049, 31, 32768), (128, 19, 40001),
-                                   (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 6, 32768)])
+                                   (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 8, 32768), (10000, 9, 32768), (6400, 31, 32770)])
 def test_search_long_streams_bit_exact(D, C, N):
     rng = np.random.default_rng(D + 13 * C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
