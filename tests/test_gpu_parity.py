@@ -226,7 +226,7 @@ def test_search_bit_exact(D, C, N):
                                    # matrix-core kernel (64 rows per block at a time, a row split in two halves, every
                                    # half in eight slices); around it the shapes that just miss it
                                    (10000, 26, 32771), (10000, 12, 32833), (2049, 31, 32768), (128, 19, 40001),
-                                   (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 8, 32768), (10000, 9, 32768), (6400, 31, 32770)])
+                                   (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 8, 32768), (10000, 9, 32768), (6400, 31, 32770), (10030, 13, 32785), (10240, 20, 32768), (10241, 20, 32768)])
 def test_search_long_streams_bit_exact(D, C, N):
     rng = np.random.default_rng(D + 13 * C)
     wl = make_workload(1, D=D, C=C, F=3, L=2)
