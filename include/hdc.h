@@ -239,7 +239,8 @@ typedef enum {
     HDC_K_SEARCH = 4,     /* Hamming distance + argmin kernel of hdc_search */
     HDC_K_ONLINE_FWD = 5, /* partial dot products of hdc_train_online_batched */
     HDC_K_ONLINE_BWD = 6, /* batch sum + accumulator update of hdc_train_online_batched */
-    HDC_K_COUNT = 7
+    HDC_K_ENCODE_CONTRACT = 7, /* the contraction form of hdc_encode (quantises, bundles and spreads in one kernel) */
+    HDC_K_COUNT = 8
 } hdc_kernel_id;
 #define HDC_PROFILE_SLOTS 512
 int hdc_profile_enable(hdc_ctx *ctx, int enable);

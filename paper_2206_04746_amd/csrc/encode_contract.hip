@@ -1,0 +1,360 @@
+// ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features, on the
+// matrix cores.  Same bits as encode_kernel; taken for level tables in which every dimension that
+// varies along the levels flips exactly once (the construction of Sec. III: neighbouring level
+// vectors differ in a few more dimensions each), with at most 64 levels and 640 features.
+//
+// For such a dimension d let t_d be the first level whose bit differs from level 0's, and
+// B[f][d] = item[f][d] ^ level[0][d].  The vote of feature f is B[f][d] ^ [q_f >= t_d], so the
+// number of votes is
+//     count[d] = sum_f B[f][d] + |U| - 2 * <U, B[.][d]>,     U_f = [q_f >= t_d],
+// a constant of the model, the number of features at or above the threshold, and a dot product of
+// two bit vectors over the features.  All dimensions with the same threshold share U: for a tile
+// of 32 samples and 32 such dimensions the dot products are one v_mfma_f32_32x32x64_f8f6f4 per 64
+// features, on 4-bit floats whose bits are the vectors'
+// bits IN PLACE (a nibble with one bit set is 0.5, 1 or 2; the other operand is stored with the
+// bits of every nibble reversed, so that every product is 1 or 0; see search_mfma.hip, which
+// uses the same operands).  U itself comes from the quantised features kept as bit planes over the
+// features: [q >= t] for 32 features at once is one 3-input bit operation per plane.
+//
+// A block takes 32 samples; its eight waves split the tiles of dimensions.  The bits come out with
+// a dimension per lane and a sample per register: a lane strings the 16 bits of its registers
+// together (the sign of a fused multiply-add, shifted in by v_alignbit) and leaves them in LDS as
+// the word "dimension (tile, column) of 16 samples".  When all tiles are done, thread w collects,
+// for each of the 32 bits of word w of a row, that bit's word over the samples (a table names the
+// tile and column of every varying bit; one LDS read per bit serves all 32 samples), transposes
+// the 32 x 32 bits in registers, adds the model's constant bits and writes word w of the 32 rows.
+// (Tried first: an LDS atomic OR per bit into images of the rows, six times the time of the MFMAs;
+// then the wave's ballots as words over the dimensions and a gather per (bit, sample), LDS bank
+// conflicts making it four times the time of the MFMAs.)
+#include "hdc_internal.h"
+#include "bundle.h"
+
+#include <algorithm>
+#include <vector>
+
+namespace hdc {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kCtWaves = 8;
+constexpr int kCtPlanes = 6;      // bit planes of a bin number: L <= 64
+constexpr int kCtMaxSteps = 10;   // MFMAs per tile: 64 features each
+constexpr int kCtCols = 32;       // dimensions per tile
+constexpr int kCtSamples = 32;    // samples per block and job
+constexpr float kCtNever = -1.0e30f;
+
+// bits 0..2 of every nibble reversed, bit 3 in place
+static inline uint32_t reverse3_host(uint32_t m) {
+    return (m & 0xaaaaaaaau) | ((m & 0x11111111u) << 2) | ((m >> 2) & 0x11111111u);
+}
+
+template <typename T>
+static int upload(T **dst, const std::vector<T> &src) {
+    void *ptr = nullptr;
+    hipError_t e = hipMalloc(&ptr, src.size() * sizeof(T) + 256);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return HDC_ENOMEM;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    *dst = reinterpret_cast<T *>(ptr);
+    e = hipMemcpy(ptr, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+    return e == hipSuccess ? HDC_OK : hip_fail(e, "hipMemcpy");
+}
+
+// ---- host: tables of the model -----------------------------------------------------------------
+// Leaves c->ct_ready false when the model is not of the shape described above (or on any doubt);
+// only a failed allocation or copy is an error.
+int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie) {
+    const hdc_params &p = c->p;
+    const int W = c->W, F = p.F, L = p.L;
+    c->ct_ready = false;
+    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || W > kCtWaves * kWave) return HDC_OK;   // a thread per word of a row
+    const int steps = (F + 63) / 64;
+    const int thr = (c->votes + 1) / 2;
+    const bool tie_votes = c->votes != F;
+
+    // threshold of every varying dimension; any dimension that flips twice rules the model out
+    std::vector<std::vector<int>> by_tau((size_t)L);
+    for (int d = 0; d < p.D; ++d) {
+        const int w = d >> 5, b = d & 31;
+        const uint32_t first = (level[w] >> b) & 1u;
+        int tau = 0;
+        for (int l = 1; l < L; ++l) {
+            const uint32_t bit = (level[(size_t)l * W + w] >> b) & 1u;
+            if (!tau && bit != first) tau = l;
+            else if (tau && bit == first) return HDC_OK;
+        }
+        if (tau) by_tau[(size_t)tau].push_back(d);
+    }
+    std::vector<int32_t> tau_of;
+    std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: tile * 32 + column holding that bit
+    std::vector<float> kc;
+    std::vector<uint32_t> bt;   // [tile][step][lane][4]: the four masks of the column's word, ready as an operand
+    std::vector<uint32_t> vec((size_t)2 * steps);
+    for (int tau = 1; tau < L; ++tau) {
+        const std::vector<int> &dims = by_tau[(size_t)tau];
+        for (size_t at = 0; at < dims.size(); at += kCtCols) {
+            const size_t t = tau_of.size();
+            tau_of.push_back(tau);
+            kc.resize((t + 1) * 32, kCtNever);
+            bt.resize((t + 1) * steps * 64 * 4, 0u);
+            for (int j = 0; j < 32; ++j) {
+                std::fill(vec.begin(), vec.end(), 0u);
+                if (j < kCtCols && at + j < dims.size()) {
+                    const int d = dims[at + j], w = d >> 5, b = d & 31;
+                    const uint32_t l0 = (level[w] >> b) & 1u;
+                    int ones = 0;
+                    for (int f = 0; f < F; ++f) {
+                        const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
+                        ones += (int)bit;
+                        vec[(size_t)f >> 5] |= bit << (f & 31);
+                    }
+                    const int tie_vote = tie_votes ? (int)((tie[w] >> b) & 1u) : 0;
+                    src_of[(size_t)b * W + w] = (uint32_t)(t * 32 + j);
+                    kc[t * 32 + j] = (float)(ones + tie_vote - thr);   // the bit is set iff 2 <U,B> - |U| <= this
+                }
+                for (int k = 0; k < steps; ++k)
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t m = reverse3_host(vec[(size_t)2 * k + h]);
+                        uint32_t *q = &bt[((t * steps + k) * 64 + h * 32 + j) * 4];
+                        q[0] = m & 0x44444444u;
+                        q[1] = m & 0x22222222u;
+                        q[2] = m & 0x11111111u;
+                        q[3] = (m >> 3) & 0x11111111u;
+                    }
+            }
+        }
+    }
+    if (tau_of.empty() || tau_of.size() > (size_t)kCtWaves * kWave) return HDC_OK;   // a wave keeps its tiles' thresholds a lane each
+    c->ct_tiles = (int)tau_of.size();
+    c->ct_steps = steps;
+    int rc = upload(&c->ct_tau_d, tau_of);
+    if (rc == HDC_OK) rc = upload(&c->ct_col_d, src_of);
+    if (rc == HDC_OK) rc = upload(&c->ct_k_d, kc);
+    if (rc == HDC_OK) rc = upload(&c->ct_bt_d, bt);
+    if (rc != HDC_OK) return rc;
+    c->ct_ready = true;
+    return HDC_OK;
+}
+
+// Both operands as 4-bit floats (format code 4), no block scales; 16 bytes of each are used.
+__device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
+    const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0}, b8 = {b[0], b[1], b[2], b[3], 0, 0, 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
+}
+
+// Dynamic LDS: the job's bit planes [6][KS][64], then per (tile, column) the bits of the job's 32
+// samples [T * 32] (two 16-bit halves, one per lane half).
+template <int KS, bool kU8>
+__global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
+    const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
+    const float *__restrict__ scale, int W, int T, const uint4 *__restrict__ bt,
+    const uint32_t *__restrict__ src_of, const float *__restrict__ kc, const int32_t *__restrict__ tau,
+    const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
+    extern __shared__ uint32_t pl_lds[];
+    constexpr int kPlaneWords = kCtPlanes * KS * 64;
+    uint32_t *over = pl_lds + kPlaneWords;
+    uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int j = lane & 31, h = lane >> 5;
+    // the wave's tiles (at most 64: the host sees to that) and their thresholds, a tile per lane
+    const int t_lo = (int)((int64_t)wave * T / kCtWaves), t_hi = (int)((int64_t)(wave + 1) * T / kCtWaves);
+    const int tau_mine = t_lo + lane < t_hi ? tau[t_lo + lane] : 0;
+    // this thread's word of a row
+    const int w_mine = min((int)threadIdx.x, W - 1);
+    const uint32_t cbits = const_row[w_mine];
+    // every lane's read address for the value of lane 4 * h of its own half (see u_of below)
+    const int u_addr = (4 * h) * 4;
+
+    const int64_t jobs = (N + kCtSamples - 1) / kCtSamples;
+    for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
+        // The job's quantised features as bit planes over the features.  Wave v takes samples 4v .. 4v + 3;
+        // pass k covers features 64k .. 64k + 63, a feature per lane.  Plane b of a pass is the ballot
+        // of bit b of the bin numbers: its low word belongs to lane half 0 of MFMA step k, its high
+        // word to half 1.  Layout [plane][step][half * 32 + sample].
+        {
+            const int64_t first = job * kCtSamples;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {   // two samples at a time: their loads first, all in flight
+                uint32_t raw[2][KS];
+#pragma unroll
+                for (int sn = 0; sn < 2; ++sn) {   // (rows past N and features past F clamp)
+                    const int64_t at = first + wave * 4 + half * 2 + sn;
+                    const int64_t n = at < N ? at : N - 1;
+#pragma unroll
+                    for (int k = 0; k < KS; ++k) {
+                        const int f = min(k * kWave + lane, F - 1);
+                        if (kU8) raw[sn][k] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
+                        else raw[sn][k] = reinterpret_cast<const uint32_t *>(feats)[n * F + f];
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < KS; ++k) {
+                    const int f = min(k * kWave + lane, F - 1);
+                    const float lo_f = kU8 ? 0.0f : lo[f], sc_f = kU8 ? 0.0f : scale[f];
+#pragma unroll
+                    for (int sn = 0; sn < 2; ++sn) {
+                        uint32_t q = kU8 ? (raw[sn][k] * (uint32_t)L) >> 8
+                                         : bin_f32(__builtin_bit_cast(float, raw[sn][k]), lo_f, sc_f, L);
+                        if (k * kWave + lane >= F) q = 0;
+                        uint32_t mine = 0;
+#pragma unroll
+                        for (int b = 0; b < kCtPlanes; ++b) {
+                            const uint64_t m = __ballot((q >> b) & 1u);
+                            if (lane == 2 * b) mine = (uint32_t)m;
+                            if (lane == 2 * b + 1) mine = (uint32_t)(m >> 32);
+                        }
+                        if (lane < 2 * kCtPlanes)
+                            pl_lds[((lane >> 1) * KS + k) * 64 + (lane & 1) * 32 + wave * 4 + half * 2 + sn] = mine;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+
+        int cur_tau = 0;
+        v4i a[KS];
+        float u_of[16];   // -|U| of the sample that accumulator register r belongs to
+        uint4 btw[KS];
+        float k_mine = 0.0f;
+        if (t_lo < t_hi) {
+#pragma unroll
+            for (int k = 0; k < KS; ++k) btw[k] = bt[((size_t)t_lo * KS + k) * 64 + lane];
+            k_mine = kc[t_lo * 32 + j];
+        }
+        for (int t = t_lo; t < t_hi; ++t) {
+            const int tt = __builtin_amdgcn_readlane(tau_mine, t - t_lo);
+            if (tt != cur_tau) {   // wave-uniform: the samples' [q >= tt] over the features, their masks, their counts
+                cur_tau = tt;
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int k = 0; k < KS; ++k) {
+                    uint32_t ge = 0xffffffffu;
+#pragma unroll
+                    for (int b = 0; b < kCtPlanes; ++b) {
+                        const uint32_t q = pl_lds[(b * KS + k) * 64 + lane];
+                        const uint32_t tb = (tt >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
+                        ge = __builtin_amdgcn_bitop3_b32(q, ge, tb, 0xD4);      // tb ? q & ge : q | ge
+                    }
+                    cnt += __popc(ge);
+                    a[k] = v4i{(int)(ge & 0x11111111u), (int)(ge & 0x22222222u), (int)(ge & 0x44444444u),
+                               (int)((ge >> 1) & 0x44444444u)};
+                }
+                cnt += (uint32_t)__shfl_xor((int)cnt, 32, kWave);   // both halves of a sample's features
+                // register r of a lane belongs to sample 8 * (r / 4) + 4 * h + r % 4 of the job
+                const int neg = __builtin_bit_cast(int, -(float)cnt);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    u_of[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(u_addr + (8 * (r >> 2) + (r & 3)) * 4, neg));
+            }
+            // The bit of (sample, dimension) is [2 <U,B> - |U| <= K], i.e. the sign of 2 * (<U,B> - K / 2 -
+            // 0.25) - |U| (whole numbers but for the half): the accumulators start at -K / 2 - 0.25.
+            v16f acc;
+            {
+                const float start = -0.5f * k_mine - 0.25f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = start;
+            }
+#pragma unroll
+            for (int k = 0; k < KS; ++k) {
+                const v4i b = {(int)btw[k].x, (int)btw[k].y, (int)btw[k].z, (int)btw[k].w};
+                acc = mfma_fp4(a[k], b, acc);
+            }
+            {   // the next tile's operands and constants (past the wave's last tile: the same again)
+                const int tn = t + 1 < t_hi ? t + 1 : t;
+#pragma unroll
+                for (int k = 0; k < KS; ++k) btw[k] = bt[((size_t)tn * KS + k) * 64 + lane];
+            }
+            // register 0's bit ends up highest
+            uint32_t bits = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float d = fmaf(2.0f, acc[r], u_of[r]);
+                bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
+            }
+            over16[(size_t)(t * 32 + j) * 2 + h] = (uint16_t)bits;
+            k_mine = kc[(t + 1 < t_hi ? t + 1 : t) * 32 + j];
+        }
+        __syncthreads();
+
+        // Word w of the job's rows.  Bit p of a word of `over` is the sample of register 15 - p of
+        // lane half 0 (p < 16) or register 31 - p of half 1.
+        if ((int)threadIdx.x < W) {
+            uint32_t x[32];
+#pragma unroll
+            for (int b = 0; b < 32; ++b) x[b] = src_of[(size_t)b * W + threadIdx.x];   // (~0: a constant of the model)
+#pragma unroll
+            for (int b = 0; b < 32; ++b) x[b] = x[b] != 0xffffffffu ? over[x[b]] : 0u;
+            // x[b] bit p  ->  x[p] bit b
+#pragma unroll
+            for (int k = 16; k; k >>= 1) {
+                const uint32_t m = k == 16 ? 0x0000ffffu : k == 8 ? 0x00ff00ffu : k == 4 ? 0x0f0f0f0fu : k == 2 ? 0x33333333u : 0x55555555u;
+#pragma unroll
+                for (int i = 0; i < 32; ++i)
+                    if ((i & k) == 0) {
+                        const uint32_t tsw = ((x[i] >> k) ^ x[i + k]) & m;
+                        x[i + k] ^= tsw;
+                        x[i] ^= tsw << k;
+                    }
+            }
+            const int64_t first = job * kCtSamples;
+#pragma unroll
+            for (int p = 0; p < 32; ++p) {
+                const int r = p < 16 ? 15 - p : 31 - p;
+                const int sn = 8 * (r >> 2) + (p < 16 ? 0 : 4) + (r & 3);
+                if (first + sn < N) hv[(first + sn) * W + threadIdx.x] = x[p] | cbits;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+constexpr int64_t kCtMinSamples = 2048;   // a block takes 32 samples: below this most of the chip would stay idle
+
+template <int KS, bool kU8>
+static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
+    const size_t lds = (size_t)kCtPlanes * KS * 64 * 4 + (size_t)c->ct_tiles * 32 * 4;
+    auto kern = encode_contract_kernel<KS, kU8>;
+    if (lds > 64 * 1024)
+        HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+    const int64_t jobs = (n + kCtSamples - 1) / kCtSamples;
+    const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kCtWaves * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
+                       c->scale_d, c->W, c->ct_tiles, reinterpret_cast<const uint4 *>(c->ct_bt_d), c->ct_col_d, c->ct_k_d,
+                       c->ct_tau_d, c->expand_d + (size_t)7 * c->W, out);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
+template <bool kU8>
+static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
+    switch (c->ct_steps) {
+    case 1: return launch_contract<1, kU8>(c, x, n, out, s);
+    case 2: return launch_contract<2, kU8>(c, x, n, out, s);
+    case 3: return launch_contract<3, kU8>(c, x, n, out, s);
+    case 4: return launch_contract<4, kU8>(c, x, n, out, s);
+    case 5: return launch_contract<5, kU8>(c, x, n, out, s);
+    case 6: return launch_contract<6, kU8>(c, x, n, out, s);
+    case 7: return launch_contract<7, kU8>(c, x, n, out, s);
+    case 8: return launch_contract<8, kU8>(c, x, n, out, s);
+    case 9: return launch_contract<9, kU8>(c, x, n, out, s);
+    default: return launch_contract<10, kU8>(c, x, n, out, s);
+    }
+}
+
+// Encodes with the contraction if the model and the call are of its shape; false otherwise (then
+// nothing was launched).
+bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc) {
+    if (!c->ct_ready || N < kCtMinSamples) return false;
+    ProfScope prof(c, HDC_K_ENCODE_CONTRACT, s);
+    *rc = c->p.feat_dtype == HDC_U8 ? launch_contract_steps<true>(c, feats, N, hv, s)
+                                    : launch_contract_steps<false>(c, feats, N, hv, s);
+    return true;
+}
+
+}  // namespace hdc

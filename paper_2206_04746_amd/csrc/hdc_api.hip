@@ -29,7 +29,8 @@ static void free_ctx(hdc_ctx_impl *c) {
                     c->cls_off_d, c->cls_cur_d, c->cls_blk_d, c->perm_d, c->partial_d, c->ob_part_d, c->ob_wts_d, c->ob_norm_d,
                     c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d, c->ob_ln_d, c->ob_lw_d, c->ob_meta_d,
                     c->citem_d, c->clevel_d, c->hvc_d, c->expand_d,
-                    c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d};
+                    c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d,
+                    c->ct_tau_d, c->ct_col_d, c->ct_k_d, c->ct_bt_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -276,6 +277,7 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     TRY_HIP(hipDeviceSynchronize());
     try {
         TRY(prepare_compact(c, item, level, tie));
+        TRY(prepare_contract(c, item, level, tie));
     } catch (const std::bad_alloc &) {
         rc = HDC_ENOMEM;
     }

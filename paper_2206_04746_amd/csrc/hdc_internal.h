@@ -96,6 +96,15 @@ struct hdc_ctx_impl {
     uint32_t *sp_blocks_d;  // [q_rows]         16-entry blocks per sample
     int sp_bpc;             // blocks of encode_sparse_kernel a CU holds (0 = not asked yet)
 
+    // Encoding as a contraction over the features (encode_contract.hip); tables derived at create
+    // when the level table is of the shape it needs.
+    bool ct_ready;
+    int ct_tiles, ct_steps;     // tiles of 32 dimensions; MFMA steps (64 features each) per tile
+    int32_t *ct_tau_d;          // [tiles] the level at which the tile's dimensions flip
+    uint32_t *ct_col_d;         // [32][W] per bit of every word of a row: tile * 32 + column that holds it, ~0 for a constant bit
+    float *ct_k_d;              // [tiles][32] the column's vote threshold, constants folded in
+    uint32_t *ct_bt_d;          // [tiles][steps][64][4] item ^ level 0 along the features, per column and lane half: its four operand masks
+
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).
     int enc_bpc[24];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
@@ -161,7 +170,11 @@ int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
 int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(hdc_ctx_impl *c);
-// Hamming search on the matrix cores for long query streams with 7..31 classes; false when the
+// Encoding as a contraction (encode_contract.hip): tables at create; the launcher returns false
+// when the model or the call is not of its shape (then nothing was launched).
+int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie);
+bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc);
+// Hamming search on the matrix cores for long query streams with 9..31 classes; false when the
 // shape is not its own (then nothing was launched and *rc is untouched).
 bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
                      uint32_t *dist, int32_t *pred, hipStream_t s, int *rc);
