@@ -291,8 +291,10 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             for (int b = 0; b < 32; ++b) x[b] = x[b] != 0xffffffffu ? over[x[b]] : 0u;
             // x[b] bit p  ->  x[p] bit b
 #pragma unroll
-            for (int k = 16; k; k >>= 1) {
-                const uint32_t m = k == 16 ? 0x0000ffffu : k == 8 ? 0x00ff00ffu : k == 4 ? 0x0f0f0f0fu : k == 2 ? 0x33333333u : 0x55555555u;
+            for (int stage = 0; stage < 5; ++stage) {
+                const int k = 16 >> stage;
+                const uint32_t m = stage == 0 ? 0x0000ffffu : stage == 1 ? 0x00ff00ffu : stage == 2 ? 0x0f0f0f0fu
+                                 : stage == 3 ? 0x33333333u : 0x55555555u;
 #pragma unroll
                 for (int i = 0; i < 32; ++i)
                     if ((i & k) == 0) {
