@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
 
         int cur_tau = 0;
         v4i a[KS];
-        float u_of[16];   // -|U| of the sample that accumulator register r belongs to
+        float u_of[16];   // -|U| / 2 of the sample that accumulator register r belongs to
         uint4 btw[KS];
         float k_mine = 0.0f;
         if (t_lo < t_hi) {
@@ -246,18 +246,18 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                 }
                 cnt += (uint32_t)__shfl_xor((int)cnt, 32, kWave);   // both halves of a sample's features
                 // register r of a lane belongs to sample 8 * (r / 4) + 4 * h + r % 4 of the job
-                const int neg = __builtin_bit_cast(int, -(float)cnt);
+                const int neg = __builtin_bit_cast(int, -0.5f * (float)cnt);
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     u_of[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(u_addr + (8 * (r >> 2) + (r & 3)) * 4, neg));
             }
-            // The bit of (sample, dimension) is [2 <U,B> - |U| <= K], i.e. the sign of 2 * (<U,B> - K / 2 -
-            // 0.25) - |U| (whole numbers but for the half): the accumulators start at -K / 2 - 0.25.
+            // The bit of (sample, dimension) is [2 <U,B> - |U| <= K], i.e. the sign of <U,B> - K / 2 - |U| / 2 -
+            // 0.25 (multiples of a half but for the quarter): the accumulators start at what follows <U,B>.
             v16f acc;
             {
                 const float start = -0.5f * k_mine - 0.25f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = start;
+                for (int r = 0; r < 16; ++r) acc[r] = start + u_of[r];
             }
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             uint32_t bits = 0;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float d = fmaf(2.0f, acc[r], u_of[r]);
+                const float d = acc[r];   // (a copy: __builtin_bit_cast applied to the vector element itself reads element 0)
                 bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
             }
             over16[(size_t)(t * 32 + j) * 2 + h] = (uint16_t)bits;
