@@ -1,7 +1,7 @@
 // ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features, on the
 // matrix cores.  Same bits as encode_kernel; taken for level tables in which every dimension that
 // varies along the levels flips exactly once (the construction of Sec. III: neighbouring level
-// vectors differ in a few more dimensions each), with at most 64 levels and 640 features.
+// vectors differ in a few more dimensions each), with at most 256 levels and 640 features.
 //
 // For such a dimension d let t_d be the first level whose bit differs from level 0's, and
 // B[f][d] = item[f][d] ^ level[0][d].  The vote of feature f is B[f][d] ^ [q_f >= t_d], so the
@@ -39,7 +39,7 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kCtWaves = 8;
-constexpr int kCtPlanes = 6;      // bit planes of a bin number: L <= 64
+constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
 constexpr int kCtMaxSteps = 10;   // MFMAs per tile: 64 features each
 constexpr int kCtCols = 32;       // dimensions per tile
 constexpr int kCtSamples = 32;    // samples per block and job
@@ -72,7 +72,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     const int W = c->W, F = p.F, L = p.L;
     c->ct_ready = false;
     if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || W > kCtWaves * kWave) return HDC_OK;   // a thread per word of a row
-    const int steps = (F + 63) / 64;
+    const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
     const int thr = (c->votes + 1) / 2;
     const bool tie_votes = c->votes != F;
 
@@ -146,16 +146,16 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-// Dynamic LDS: the job's bit planes [6][KS][64], then per (tile, column) the bits of the job's 32
+// Dynamic LDS: the job's bit planes [NB][KS][64], then per (tile, column) the bits of the job's 32
 // samples [T * 32] (two 16-bit halves, one per lane half).
-template <int KS, bool kU8>
+template <int KS, int NB, bool kU8>
 __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
     const float *__restrict__ scale, int W, int T, const uint4 *__restrict__ bt,
     const uint32_t *__restrict__ src_of, const float *__restrict__ kc, const int32_t *__restrict__ tau,
     const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
     extern __shared__ uint32_t pl_lds[];
-    constexpr int kPlaneWords = kCtPlanes * KS * 64;
+    constexpr int kPlaneWords = NB * KS * 64;
     uint32_t *over = pl_lds + kPlaneWords;
     uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -203,12 +203,12 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                         if (k * kWave + lane >= F) q = 0;
                         uint32_t mine = 0;
 #pragma unroll
-                        for (int b = 0; b < kCtPlanes; ++b) {
+                        for (int b = 0; b < NB; ++b) {
                             const uint64_t m = __ballot((q >> b) & 1u);
                             if (lane == 2 * b) mine = (uint32_t)m;
                             if (lane == 2 * b + 1) mine = (uint32_t)(m >> 32);
                         }
-                        if (lane < 2 * kCtPlanes)
+                        if (lane < 2 * NB)
                             pl_lds[((lane >> 1) * KS + k) * 64 + (lane & 1) * 32 + wave * 4 + half * 2 + sn] = mine;
                     }
                 }
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                 for (int k = 0; k < KS; ++k) {
                     uint32_t ge = 0xffffffffu;
 #pragma unroll
-                    for (int b = 0; b < kCtPlanes; ++b) {
+                    for (int b = 0; b < NB; ++b) {
                         const uint32_t q = pl_lds[(b * KS + k) * 64 + lane];
                         const uint32_t tb = (tt >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
                         ge = __builtin_amdgcn_bitop3_b32(q, ge, tb, 0xD4);      // tb ? q & ge : q | ge
@@ -317,10 +317,10 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
 
 constexpr int64_t kCtMinSamples = 2048;   // a block takes 32 samples: below this most of the chip would stay idle
 
-template <int KS, bool kU8>
+template <int KS, int NB, bool kU8>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
-    const size_t lds = (size_t)kCtPlanes * KS * 64 * 4 + (size_t)c->ct_tiles * 32 * 4;
-    auto kern = encode_contract_kernel<KS, kU8>;
+    const size_t lds = (size_t)NB * KS * 64 * 4 + (size_t)c->ct_tiles * 32 * 4;
+    auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
@@ -333,19 +333,15 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     return HDC_OK;
 }
 
-template <bool kU8>
+// The kernel is built for an even number of steps and for 6 or 8 bit planes (L <= 64, L <= 256).
+template <int NB, bool kU8>
 static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
     switch (c->ct_steps) {
-    case 1: return launch_contract<1, kU8>(c, x, n, out, s);
-    case 2: return launch_contract<2, kU8>(c, x, n, out, s);
-    case 3: return launch_contract<3, kU8>(c, x, n, out, s);
-    case 4: return launch_contract<4, kU8>(c, x, n, out, s);
-    case 5: return launch_contract<5, kU8>(c, x, n, out, s);
-    case 6: return launch_contract<6, kU8>(c, x, n, out, s);
-    case 7: return launch_contract<7, kU8>(c, x, n, out, s);
-    case 8: return launch_contract<8, kU8>(c, x, n, out, s);
-    case 9: return launch_contract<9, kU8>(c, x, n, out, s);
-    default: return launch_contract<10, kU8>(c, x, n, out, s);
+    case 2: return launch_contract<2, NB, kU8>(c, x, n, out, s);
+    case 4: return launch_contract<4, NB, kU8>(c, x, n, out, s);
+    case 6: return launch_contract<6, NB, kU8>(c, x, n, out, s);
+    case 8: return launch_contract<8, NB, kU8>(c, x, n, out, s);
+    default: return launch_contract<10, NB, kU8>(c, x, n, out, s);
     }
 }
 
@@ -354,8 +350,9 @@ static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint
 bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc) {
     if (!c->ct_ready || N < kCtMinSamples) return false;
     ProfScope prof(c, HDC_K_ENCODE_CONTRACT, s);
-    *rc = c->p.feat_dtype == HDC_U8 ? launch_contract_steps<true>(c, feats, N, hv, s)
-                                    : launch_contract_steps<false>(c, feats, N, hv, s);
+    const bool u8 = c->p.feat_dtype == HDC_U8;
+    if (c->p.L <= 64) *rc = u8 ? launch_contract_steps<6, true>(c, feats, N, hv, s) : launch_contract_steps<6, false>(c, feats, N, hv, s);
+    else *rc = u8 ? launch_contract_steps<8, true>(c, feats, N, hv, s) : launch_contract_steps<8, false>(c, feats, N, hv, s);
     return true;
 }
 
