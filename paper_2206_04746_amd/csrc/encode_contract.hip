@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     }
 }
 
-constexpr int64_t kCtMinSamples = 2048;   // a block takes 32 samples: below this most of the chip would stay idle
+constexpr int64_t kCtMinSamples = 1024;   // a block takes 32 samples: below this most of the chip would stay idle
 
 template <int KS, int NB, bool kU8>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {

@@ -1,6 +1,6 @@
 """GPU parity of hdc_encode where it runs as a contraction over the features on the matrix cores
 (Sec. III Eq. 1; level tables whose dimensions flip at most once along the levels, L <= 256,
-F <= 640, 2048 samples or more): bit-exact against the CPU oracle, over feature counts on both
+F <= 640, 1024 samples or more): bit-exact against the CPU oracle, over feature counts on both
 sides of a multiple of 64, even and odd (the tie vote), u8 and fp32 features, sample counts that
 leave a ragged last block, and rows whose last word is partial; and the tables that are not of
 that shape, which must take the other kernel and give the same bits."""
@@ -37,7 +37,7 @@ def _oracle(wl, x):
     (2, 777, 33, 7, 2500), (2, 5000, 200, 32, 2111), (2, 10000, 342, 64, 4097), (2, 2048, 65, 2, 2050),
     (2, 16384, 128, 64, 2048), (2, 96, 10, 3, 3000), (2, 10000, 31, 64, 2300),
     (4, 10000, 561, 100, 2200), (2, 8000, 300, 256, 2100), (2, 6000, 90, 65, 2049), (2, 3000, 50, 129, 2048),
-    (3, 2048, 400, 32, 2100), (3, 10000, 625, 64, 2065), (3, 3000, 36, 5, 2048),
+    (3, 2048, 400, 32, 2100), (3, 10000, 625, 64, 2065), (3, 3000, 36, 5, 2048), (2, 10000, 617, 64, 1024), (2, 1024, 100, 16, 1055),
 ])
 def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L, n_train=N)
