@@ -178,39 +178,36 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
         // word to half 1.  Layout [plane][step][half * 32 + sample].
         {
             const int64_t first = job * kCtSamples;
+            uint32_t raw[4][KS];
+            float lo_f[KS], sc_f[KS];
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {   // two samples at a time: their loads first, all in flight
-                uint32_t raw[2][KS];
+            for (int k = 0; k < KS; ++k) {   // all loads first (rows past N and features past F clamp)
+                const int f = min(k * kWave + lane, F - 1);
+                lo_f[k] = kU8 ? 0.0f : lo[f];
+                sc_f[k] = kU8 ? 0.0f : scale[f];
 #pragma unroll
-                for (int sn = 0; sn < 2; ++sn) {   // (rows past N and features past F clamp)
-                    const int64_t at = first + wave * 4 + half * 2 + sn;
+                for (int sn = 0; sn < 4; ++sn) {
+                    const int64_t at = first + wave * 4 + sn;
                     const int64_t n = at < N ? at : N - 1;
-#pragma unroll
-                    for (int k = 0; k < KS; ++k) {
-                        const int f = min(k * kWave + lane, F - 1);
-                        if (kU8) raw[sn][k] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
-                        else raw[sn][k] = reinterpret_cast<const uint32_t *>(feats)[n * F + f];
-                    }
+                    if (kU8) raw[sn][k] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
+                    else raw[sn][k] = reinterpret_cast<const uint32_t *>(feats)[n * F + f];
                 }
+            }
 #pragma unroll
-                for (int k = 0; k < KS; ++k) {
-                    const int f = min(k * kWave + lane, F - 1);
-                    const float lo_f = kU8 ? 0.0f : lo[f], sc_f = kU8 ? 0.0f : scale[f];
+            for (int k = 0; k < KS; ++k) {
 #pragma unroll
-                    for (int sn = 0; sn < 2; ++sn) {
-                        uint32_t q = kU8 ? (raw[sn][k] * (uint32_t)L) >> 8
-                                         : bin_f32(__builtin_bit_cast(float, raw[sn][k]), lo_f, sc_f, L);
-                        if (k * kWave + lane >= F) q = 0;
-                        uint32_t mine = 0;
+                for (int sn = 0; sn < 4; ++sn) {
+                    uint32_t q = kU8 ? (raw[sn][k] * (uint32_t)L) >> 8
+                                     : bin_f32(__builtin_bit_cast(float, raw[sn][k]), lo_f[k], sc_f[k], L);
+                    if (k * kWave + lane >= F) q = 0;
+                    uint32_t mine = 0;
 #pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            const uint64_t m = __ballot((q >> b) & 1u);
-                            if (lane == 2 * b) mine = (uint32_t)m;
-                            if (lane == 2 * b + 1) mine = (uint32_t)(m >> 32);
-                        }
-                        if (lane < 2 * NB)
-                            pl_lds[((lane >> 1) * KS + k) * 64 + (lane & 1) * 32 + wave * 4 + half * 2 + sn] = mine;
+                    for (int b = 0; b < NB; ++b) {
+                        const uint64_t m = __ballot((q >> b) & 1u);
+                        if (lane == 2 * b) mine = (uint32_t)m;
+                        if (lane == 2 * b + 1) mine = (uint32_t)(m >> 32);
                     }
+                    if (lane < 2 * NB) pl_lds[((lane >> 1) * KS + k) * 64 + (lane & 1) * 32 + wave * 4 + sn] = mine;
                 }
             }
         }
@@ -279,14 +276,19 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             over16[(size_t)(t * 32 + j) * 2 + h] = (uint16_t)bits;
             k_mine = kc[(t + 1 < t_hi ? t + 1 : t) * 32 + j];
         }
+        // (this thread's entries of the bit table are asked for before the barrier, not after it)
+        uint32_t x[32];
+        {
+            const int w = min((int)threadIdx.x, W - 1);
+#pragma unroll
+            for (int b = 0; b < 32; ++b) x[b] = src_of[(size_t)b * W + w];   // (~0: a constant of the model)
+        }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
 
         // Word w of the job's rows.  Bit p of a word of `over` is the sample of register 15 - p of
         // lane half 0 (p < 16) or register 31 - p of half 1.
         if ((int)threadIdx.x < W) {
-            uint32_t x[32];
-#pragma unroll
-            for (int b = 0; b < 32; ++b) x[b] = src_of[(size_t)b * W + threadIdx.x];   // (~0: a constant of the model)
 #pragma unroll
             for (int b = 0; b < 32; ++b) x[b] = x[b] != 0xffffffffu ? over[x[b]] : 0u;
             // x[b] bit p  ->  x[p] bit b
