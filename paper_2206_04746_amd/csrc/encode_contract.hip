@@ -197,10 +197,15 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             for (int k = 0; k < KS; ++k) {
 #pragma unroll
                 for (int sn = 0; sn < 4; ++sn) {
-                    uint32_t q = kU8 ? (raw[sn][k] * (uint32_t)L) >> 8
-                                     : bin_f32(__builtin_bit_cast(float, raw[sn][k]), lo_f[k], sc_f[k], L);
+                    uint32_t q;
+                    if (kU8) {
+                        q = (raw[sn][k] * (uint32_t)L) >> 8;
+                    } else {   // bin_f32 without its branches: NaN and negatives go to 0 through the maximum
+                        const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[sn][k]), lo_f[k]), sc_f[k]);
+                        q = (uint32_t)(int)fminf(fmaxf(t, 0.0f), (float)(L - 1));
+                    }
                     if (k * kWave + lane >= F) q = 0;
-                    uint32_t mine = 0;
+                    uint32_t mine = 0;   // lane 2b takes the low word of plane b's ballot, lane 2b + 1 the high word
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
                         const uint64_t m = __ballot((q >> b) & 1u);
