@@ -92,7 +92,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     std::vector<int32_t> tau_of;
     std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: tile * 32 + column holding that bit
     std::vector<float> kc;
-    std::vector<uint32_t> bt;   // [tile][step][lane][4]: the four masks of the column's word, ready as an operand
+    std::vector<uint32_t> bt;   // [tile][step][lane]: the column's word (bits of every nibble reversed)
     std::vector<uint32_t> vec((size_t)2 * steps);
     for (int tau = 1; tau < L; ++tau) {
         const std::vector<int> &dims = by_tau[(size_t)tau];
@@ -100,7 +100,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
             const size_t t = tau_of.size();
             tau_of.push_back(tau);
             kc.resize((t + 1) * 32, kCtNever);
-            bt.resize((t + 1) * steps * 64 * 4, 0u);
+            bt.resize((t + 1) * steps * 64, 0u);
             for (int j = 0; j < 32; ++j) {
                 std::fill(vec.begin(), vec.end(), 0u);
                 if (j < kCtCols && at + j < dims.size()) {
@@ -117,14 +117,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
                     kc[t * 32 + j] = (float)(ones + tie_vote - thr);   // the bit is set iff 2 <U,B> - |U| <= this
                 }
                 for (int k = 0; k < steps; ++k)
-                    for (int h = 0; h < 2; ++h) {
-                        const uint32_t m = reverse3_host(vec[(size_t)2 * k + h]);
-                        uint32_t *q = &bt[((t * steps + k) * 64 + h * 32 + j) * 4];
-                        q[0] = m & 0x44444444u;
-                        q[1] = m & 0x22222222u;
-                        q[2] = m & 0x11111111u;
-                        q[3] = (m >> 3) & 0x11111111u;
-                    }
+                    for (int h = 0; h < 2; ++h) bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
             }
         }
     }
@@ -151,7 +144,7 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
 template <int KS, int NB, bool kU8>
 __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
-    const float *__restrict__ scale, int W, int T, const uint4 *__restrict__ bt,
+    const float *__restrict__ scale, int W, int T, const uint32_t *__restrict__ bt,
     const uint32_t *__restrict__ src_of, const float *__restrict__ kc, const int32_t *__restrict__ tau,
     const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
     extern __shared__ uint32_t pl_lds[];
@@ -221,7 +214,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
         int cur_tau = 0;
         v4i a[KS];
         float u_of[16];   // -|U| / 2 of the sample that accumulator register r belongs to
-        uint4 btw[KS];
+        uint32_t btw[KS];
         float k_mine = 0.0f;
         if (t_lo < t_hi) {
 #pragma unroll
@@ -263,7 +256,9 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             }
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
-                const v4i b = {(int)btw[k].x, (int)btw[k].y, (int)btw[k].z, (int)btw[k].w};
+                const uint32_t m = btw[k];
+                const v4i b = {(int)(m & 0x44444444u), (int)(m & 0x22222222u), (int)(m & 0x11111111u),
+                               (int)((m >> 3) & 0x11111111u)};
                 acc = mfma_fp4(a[k], b, acc);
             }
             {   // the next tile's operands and constants (past the wave's last tile: the same again)
@@ -334,7 +329,7 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     const int64_t jobs = (n + kCtSamples - 1) / kCtSamples;
     const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kCtWaves * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
-                       c->scale_d, c->W, c->ct_tiles, reinterpret_cast<const uint4 *>(c->ct_bt_d), c->ct_col_d, c->ct_k_d,
+                       c->scale_d, c->W, c->ct_tiles, c->ct_bt_d, c->ct_col_d, c->ct_k_d,
                        c->ct_tau_d, c->expand_d + (size_t)7 * c->W, out);
     HDC_HIP(hipGetLastError());
     return HDC_OK;

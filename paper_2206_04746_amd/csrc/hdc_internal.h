@@ -103,7 +103,7 @@ struct hdc_ctx_impl {
     int32_t *ct_tau_d;          // [tiles] the level at which the tile's dimensions flip
     uint32_t *ct_col_d;         // [32][W] per bit of every word of a row: tile * 32 + column that holds it, ~0 for a constant bit
     float *ct_k_d;              // [tiles][32] the column's vote threshold, constants folded in
-    uint32_t *ct_bt_d;          // [tiles][steps][64][4] item ^ level 0 along the features, per column and lane half: its four operand masks
+    uint32_t *ct_bt_d;          // [tiles][steps][64] item ^ level 0 along the features, per column and lane half (nibbles reversed)
 
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).
