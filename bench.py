@@ -322,9 +322,10 @@ def extras(torch, binding, make_workload):
     hv5 = torch.empty((65536, ctx.W), dtype=torch.int32, device=dev)
     ms = _timed(torch, lambda: ctx.hdc_encode(x5d, hv5), 3)
     res["encode_64k_cfg5"] = {"ms": round(ms, 4), "samples_per_s": round(65536 / ms * 1e3, 0),
-                              "frac_valu": round(3.0 * wl5.F * ctx.hdc_encoded_words() * 65536 / (ms * 1e-3) / 1e12
-                                                 / VALU_PEAK_TOPS, 4),
-                              "note": "whole hdc_encode (quantise + bundle + expand) against the words the kernel bundles"}
+                              "frac_mfma_fp4": round(2.0 * wl5.F * ctx.hdc_encoded_words() * 32 * 65536 / (ms * 1e-3)
+                                                     / 1e12 / MFMA_FP4_PEAK_TFLOPS, 4),
+                              "note": "whole hdc_encode (one contraction launch: quantise + bundle + placement), "
+                                      "2 flops per (feature, varying dimension) against the FP4 matrix peak"}
     ctx.close()
     del hv, y, pred, x5d, hv5
     # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): the dense
