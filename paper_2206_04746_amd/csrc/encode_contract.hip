@@ -16,7 +16,12 @@
 // uses the same operands).  U itself comes from the quantised features kept as bit planes over the
 // features: [q >= t] for 32 features at once is one 3-input bit operation per plane.
 //
-// A block takes 32 samples; its eight waves split the tiles of dimensions.  The bits come out with
+// A block takes 32 samples.  It quantises them first, a thread per four neighbouring features of a
+// sample, and leaves the bin numbers in LDS a byte each; every wave then builds the bit planes of
+// all 32 samples in its own registers (32 bytes per lane and MFMA step, three rounds of masked
+// swaps among eight words).  (Before: a ballot per plane over a wave of 64 features of one sample,
+// 55 instructions per 64 bin numbers against 6 + 9 now, and the block waited 16 k clocks instead
+// of 8 k for its operands.)  The eight waves split the tiles of dimensions.  The bits come out with
 // a dimension per lane and a sample per register: a lane strings the 16 bits of its registers
 // together (the sign of a fused multiply-add, shifted in by v_alignbit) and leaves them in LDS as
 // the word "dimension (tile, column) of 16 samples".  When all tiles are done, thread w collects,
@@ -49,6 +54,11 @@ constexpr float kCtNever = -1.0e30f;
 static inline uint32_t reverse3_host(uint32_t m) {
     return (m & 0xaaaaaaaau) | ((m & 0x11111111u) << 2) | ((m >> 2) & 0x11111111u);
 }
+
+// Where feature f sits in its word of 32 features, on both sides of the contraction: the kernel
+// turns 32 bin numbers (bytes, four to a word) into bit planes with three rounds of masked swaps
+// among eight words, which leaves feature 4 m + i at bit 8 i + m.
+static inline int feature_bit(int f) { return 8 * (f & 3) + ((f & 31) >> 2); }
 
 template <typename T>
 static int upload(T **dst, const std::vector<T> &src) {
@@ -110,7 +120,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
                     for (int f = 0; f < F; ++f) {
                         const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
                         ones += (int)bit;
-                        vec[(size_t)f >> 5] |= bit << (f & 31);
+                        vec[(size_t)f >> 5] |= bit << feature_bit(f);
                     }
                     const int tie_vote = tie_votes ? (int)((tie[w] >> b) & 1u) : 0;
                     src_of[(size_t)b * W + w] = (uint32_t)(t * 32 + j);
@@ -139,8 +149,12 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-// Dynamic LDS: the job's bit planes [NB][KS][64], then per (tile, column) the bits of the job's 32
-// samples [T * 32] (two 16-bit halves, one per lane half).
+typedef uint32_t ct_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a global load of 16 bytes at any word
+typedef uint32_t ct_u32x4 __attribute__((ext_vector_type(4)));
+
+// Dynamic LDS: the job's bin numbers, a byte each, [sample][KS * 64 + 16] (the 16 spread the rows
+// over the banks), then per (tile, column) the bits of the job's 32 samples [T * 32] (two 16-bit
+// halves, one per lane half).
 template <int KS, int NB, bool kU8>
 __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
@@ -148,8 +162,11 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const uint32_t *__restrict__ src_of, const float *__restrict__ kc, const int32_t *__restrict__ tau,
     const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
     extern __shared__ uint32_t pl_lds[];
-    constexpr int kPlaneWords = NB * KS * 64;
-    uint32_t *over = pl_lds + kPlaneWords;
+    constexpr int kQuads = KS * 16;                                  // groups of four features per sample
+    constexpr int kPerRound = kCtWaves * kWave / kQuads;             // samples the block quantises at a time
+    constexpr int kRounds = (kCtSamples + kPerRound - 1) / kPerRound;
+    constexpr int kRowBytes = KS * 64 + 16;
+    uint32_t *over = pl_lds + kCtSamples * kRowBytes / 4;
     uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
@@ -162,54 +179,95 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const uint32_t cbits = const_row[w_mine];
     // every lane's read address for the value of lane 4 * h of its own half (see u_of below)
     const int u_addr = (4 * h) * 4;
+    // this thread's four features when the block quantises (the same in every round) and its sample of a round
+    const int f0 = 4 * ((int)threadIdx.x % kQuads), s_in = (int)threadIdx.x / kQuads;
+    uint32_t keep = 0;   // the bytes of its word that are features at all
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (f0 + i < F) keep |= 0xffu << (8 * i);
 
     const int64_t jobs = (N + kCtSamples - 1) / kCtSamples;
     for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
-        // The job's quantised features as bit planes over the features.  Wave v takes samples 4v .. 4v + 3;
-        // pass k covers features 64k .. 64k + 63, a feature per lane.  Plane b of a pass is the ballot
-        // of bit b of the bin numbers: its low word belongs to lane half 0 of MFMA step k, its high
-        // word to half 1.  Layout [plane][step][half * 32 + sample].
+        // The job's bin numbers.  A thread takes four neighbouring features of a sample (one 16-byte
+        // load; the group that straddles F loads what exists), kPerRound samples to a round, and
+        // leaves the four bin numbers as one word in LDS.
         {
             const int64_t first = job * kCtSamples;
-            uint32_t raw[4][KS];
-            float lo_f[KS], sc_f[KS];
+            uint32_t raw[kRounds][4];
+            float lo_f[4], sc_f[4];
 #pragma unroll
-            for (int k = 0; k < KS; ++k) {   // all loads first (rows past N and features past F clamp)
-                const int f = min(k * kWave + lane, F - 1);
-                lo_f[k] = kU8 ? 0.0f : lo[f];
-                sc_f[k] = kU8 ? 0.0f : scale[f];
+            for (int i = 0; i < 4; ++i) {
+                lo_f[i] = kU8 ? 0.0f : lo[min(f0 + i, F - 1)];
+                sc_f[i] = kU8 ? 0.0f : scale[min(f0 + i, F - 1)];
+            }
 #pragma unroll
-                for (int sn = 0; sn < 4; ++sn) {
-                    const int64_t at = first + wave * 4 + sn;
-                    const int64_t n = at < N ? at : N - 1;
-                    if (kU8) raw[sn][k] = reinterpret_cast<const uint8_t *>(feats)[n * F + f];
-                    else raw[sn][k] = reinterpret_cast<const uint32_t *>(feats)[n * F + f];
+            for (int r = 0; r < kRounds; ++r) {   // all loads first (rows past N: the last row again)
+                const int sn = r * kPerRound + s_in;
+                const int64_t at = first + sn;
+                const int64_t n = at < N ? at : N - 1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) raw[r][i] = 0;
+                if (s_in < kPerRound && sn < kCtSamples) {
+                    if (kU8) {
+                        const uint8_t *row = reinterpret_cast<const uint8_t *>(feats) + n * F;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) raw[r][i] = row[min(f0 + i, F - 1)];
+                    } else {
+                        const uint32_t *row = reinterpret_cast<const uint32_t *>(feats) + n * F;
+                        if (f0 + 3 < F) {
+                            const ct_u32x4_a4 v = *reinterpret_cast<const ct_u32x4_a4 *>(row + f0);
+                            raw[r][0] = v[0], raw[r][1] = v[1], raw[r][2] = v[2], raw[r][3] = v[3];
+                        } else if (f0 < F) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) raw[r][i] = row[min(f0 + i, F - 1)];
+                        }
+                    }
                 }
             }
 #pragma unroll
-            for (int k = 0; k < KS; ++k) {
+            for (int r = 0; r < kRounds; ++r) {
+                const int sn = r * kPerRound + s_in;
+                uint32_t word = 0;
 #pragma unroll
-                for (int sn = 0; sn < 4; ++sn) {
+                for (int i = 0; i < 4; ++i) {
                     uint32_t q;
                     if (kU8) {
-                        q = (raw[sn][k] * (uint32_t)L) >> 8;
+                        q = (raw[r][i] * (uint32_t)L) >> 8;
                     } else {   // bin_f32 without its branches: NaN and negatives go to 0 through the maximum
-                        const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[sn][k]), lo_f[k]), sc_f[k]);
+                        const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[r][i]), lo_f[i]), sc_f[i]);
                         q = (uint32_t)(int)fminf(fmaxf(t, 0.0f), (float)(L - 1));
                     }
-                    if (k * kWave + lane >= F) q = 0;
-                    uint32_t mine = 0;   // lane 2b takes the low word of plane b's ballot, lane 2b + 1 the high word
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        const uint64_t m = __ballot((q >> b) & 1u);
-                        if (lane == 2 * b) mine = (uint32_t)m;
-                        if (lane == 2 * b + 1) mine = (uint32_t)(m >> 32);
-                    }
-                    if (lane < 2 * NB) pl_lds[((lane >> 1) * KS + k) * 64 + (lane & 1) * 32 + wave * 4 + sn] = mine;
+                    word |= q << (8 * i);
                 }
+                if (s_in < kPerRound && sn < kCtSamples) pl_lds[(sn * kRowBytes + f0) >> 2] = word & keep;
             }
         }
         __syncthreads();
+        // Every wave turns them into bit planes over the features, kept in registers: lane (sample j,
+        // half h) reads its 32 bytes of MFMA step k and moves bit b of byte i of word m to bit
+        // 8 i + m of plane b (word index and bit index trade three of their bits, one per round).
+        uint32_t pln[KS][NB];
+#pragma unroll
+        for (int k = 0; k < KS; ++k) {
+            const ct_u32x4 *src = reinterpret_cast<const ct_u32x4 *>(
+                reinterpret_cast<const uint8_t *>(pl_lds) + j * kRowBytes + k * 64 + h * 32);
+            const ct_u32x4 v0 = src[0], v1 = src[1];
+            uint32_t x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+#pragma unroll
+            for (int stage = 0; stage < 3; ++stage) {
+                const int sh = 1 << stage;
+                const uint32_t m = stage == 0 ? 0x55555555u : stage == 1 ? 0x33333333u : 0x0f0f0f0fu;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if ((i & sh) == 0) {
+                        const uint32_t a = x[i], b = x[i + sh];
+                        x[i] = (a & m) | ((b << sh) & ~m);
+                        x[i + sh] = ((a >> sh) & m) | (b & ~m);
+                    }
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) pln[k][b] = x[b];
+        }
 
         int cur_tau = 0;
         v4i a[KS];
@@ -231,7 +289,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                     uint32_t ge = 0xffffffffu;
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const uint32_t q = pl_lds[(b * KS + k) * 64 + lane];
+                        const uint32_t q = pln[k][b];
                         const uint32_t tb = (tt >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
                         ge = __builtin_amdgcn_bitop3_b32(q, ge, tb, 0xD4);      // tb ? q & ge : q | ge
                     }
@@ -321,7 +379,7 @@ constexpr int64_t kCtMinSamples = 1024;   // a block takes 32 samples: below thi
 
 template <int KS, int NB, bool kU8>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
-    const size_t lds = (size_t)NB * KS * 64 * 4 + (size_t)c->ct_tiles * 32 * 4;
+    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (size_t)c->ct_tiles * 32 * 4;
     auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
