@@ -337,7 +337,10 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
         // (this thread's entries of the bit table are asked for before the barrier, not after it)
         uint32_t x[32];
         {
-            const int w = min((int)threadIdx.x, W - 1);
+            int w = min((int)threadIdx.x, W - 1);
+            // (opaque to the compiler, or it lifts these 32 loads out of the job loop: a block with one
+            // job would then wait for them before it starts, and hold 32 registers throughout)
+            asm volatile("" : "+v"(w));
 #pragma unroll
             for (int b = 0; b < 32; ++b) x[b] = src_of[(size_t)b * W + w];   // (~0: a constant of the model)
         }
