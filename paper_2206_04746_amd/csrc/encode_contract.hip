@@ -28,6 +28,10 @@
 // for each of the 32 bits of word w of a row, that bit's word over the samples (a table names the
 // tile and column of every varying bit; one LDS read per bit serves all 32 samples), transposes
 // the 32 x 32 bits in registers, adds the model's constant bits and writes word w of the 32 rows.
+// With few samples (fewer blocks of 32 than a quarter or half of the CUs) a row's words are split
+// into 4 or 2 ranges and a block takes 32 samples and one range: its tiles are the range's
+// dimensions (a table set per way of splitting), it places only the range's words, and it still
+// quantises all features of its samples.
 // (Tried first: an LDS atomic OR per bit into images of the rows, six times the time of the MFMAs;
 // then the wave's ballots as words over the dimensions and a gather per (bit, sample), LDS bank
 // conflicts making it four times the time of the MFMAs.)
@@ -81,7 +85,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     const hdc_params &p = c->p;
     const int W = c->W, F = p.F, L = p.L;
     c->ct_ready = false;
-    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || W > kCtWaves * kWave) return HDC_OK;   // a thread per word of a row
+    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > kCtWaves * kWave) return HDC_OK;   // a thread per word of a row, four features per load
     const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
     const int thr = (c->votes + 1) / 2;
     const bool tie_votes = c->votes != F;
@@ -99,46 +103,65 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
         }
         if (tau) by_tau[(size_t)tau].push_back(d);
     }
-    std::vector<int32_t> tau_of;
-    std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: tile * 32 + column holding that bit
-    std::vector<float> kc;
-    std::vector<uint32_t> bt;   // [tile][step][lane]: the column's word (bits of every nibble reversed)
     std::vector<uint32_t> vec((size_t)2 * steps);
-    for (int tau = 1; tau < L; ++tau) {
-        const std::vector<int> &dims = by_tau[(size_t)tau];
-        for (size_t at = 0; at < dims.size(); at += kCtCols) {
-            const size_t t = tau_of.size();
-            tau_of.push_back(tau);
-            kc.resize((t + 1) * 32, kCtNever);
-            bt.resize((t + 1) * steps * 64, 0u);
-            for (int j = 0; j < 32; ++j) {
-                std::fill(vec.begin(), vec.end(), 0u);
-                if (j < kCtCols && at + j < dims.size()) {
-                    const int d = dims[at + j], w = d >> 5, b = d & 31;
-                    const uint32_t l0 = (level[w] >> b) & 1u;
-                    int ones = 0;
-                    for (int f = 0; f < F; ++f) {
-                        const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
-                        ones += (int)bit;
-                        vec[(size_t)f >> 5] |= bit << feature_bit(f);
+    for (int v = 0; v < 3; ++v) {   // the row's words in 1 << v ranges, a block per (32 samples, range)
+        const int S = 1 << v;
+        if (W < S) break;   // every range of words has a word
+        std::vector<int32_t> tau_of, range_tile;
+        std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: (tile in its range) * 32 + column holding that bit
+        std::vector<float> kc;
+        std::vector<uint32_t> bt;   // [tile][step][lane]: the column's word (bits of every nibble reversed)
+        int range_max = 0;
+        for (int r = 0; r < S; ++r) {
+            const int w_lo = (int)((int64_t)r * W >> v), w_hi = (int)((int64_t)(r + 1) * W >> v);
+            const size_t t_first = tau_of.size();
+            range_tile.push_back((int32_t)t_first);
+            for (int tau = 1; tau < L; ++tau) {
+                std::vector<int> dims;
+                for (int d : by_tau[(size_t)tau])
+                    if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
+                for (size_t at = 0; at < dims.size(); at += kCtCols) {
+                    const size_t t = tau_of.size();
+                    tau_of.push_back(tau);
+                    kc.resize((t + 1) * 32, kCtNever);
+                    bt.resize((t + 1) * steps * 64, 0u);
+                    for (int j = 0; j < 32; ++j) {
+                        std::fill(vec.begin(), vec.end(), 0u);
+                        if (j < kCtCols && at + j < dims.size()) {
+                            const int d = dims[at + j], w = d >> 5, b = d & 31;
+                            const uint32_t l0 = (level[w] >> b) & 1u;
+                            int ones = 0;
+                            for (int f = 0; f < F; ++f) {
+                                const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
+                                ones += (int)bit;
+                                vec[(size_t)f >> 5] |= bit << feature_bit(f);
+                            }
+                            const int tie_vote = tie_votes ? (int)((tie[w] >> b) & 1u) : 0;
+                            src_of[(size_t)b * W + w] = (uint32_t)((t - t_first) * 32 + j);
+                            kc[t * 32 + j] = (float)(ones + tie_vote - thr);   // the bit is set iff 2 <U,B> - |U| <= this
+                        }
+                        for (int k = 0; k < steps; ++k)
+                            for (int h = 0; h < 2; ++h)
+                                bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
                     }
-                    const int tie_vote = tie_votes ? (int)((tie[w] >> b) & 1u) : 0;
-                    src_of[(size_t)b * W + w] = (uint32_t)(t * 32 + j);
-                    kc[t * 32 + j] = (float)(ones + tie_vote - thr);   // the bit is set iff 2 <U,B> - |U| <= this
                 }
-                for (int k = 0; k < steps; ++k)
-                    for (int h = 0; h < 2; ++h) bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
             }
+            range_max = std::max(range_max, (int)(tau_of.size() - t_first));
         }
+        range_tile.push_back((int32_t)tau_of.size());
+        // a wave keeps its tiles' thresholds a lane each
+        if (tau_of.empty() || range_max > kCtWaves * kWave) return HDC_OK;
+        c->ct_tiles[v] = (int)tau_of.size();
+        c->ct_range_max[v] = range_max;
+        for (int r = 0; r <= 4; ++r) c->ct_range[v][r] = range_tile[(size_t)std::min(r, S)];
+        int rc = upload(&c->ct_tau_d[v], tau_of);
+        if (rc == HDC_OK) rc = upload(&c->ct_col_d[v], src_of);
+        if (rc == HDC_OK) rc = upload(&c->ct_k_d[v], kc);
+        if (rc == HDC_OK) rc = upload(&c->ct_bt_d[v], bt);
+        if (rc != HDC_OK) return rc;
+        c->ct_max_split = v;
     }
-    if (tau_of.empty() || tau_of.size() > (size_t)kCtWaves * kWave) return HDC_OK;   // a wave keeps its tiles' thresholds a lane each
-    c->ct_tiles = (int)tau_of.size();
     c->ct_steps = steps;
-    int rc = upload(&c->ct_tau_d, tau_of);
-    if (rc == HDC_OK) rc = upload(&c->ct_col_d, src_of);
-    if (rc == HDC_OK) rc = upload(&c->ct_k_d, kc);
-    if (rc == HDC_OK) rc = upload(&c->ct_bt_d, bt);
-    if (rc != HDC_OK) return rc;
     c->ct_ready = true;
     return HDC_OK;
 }
@@ -149,6 +172,10 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
+struct CtRanges {
+    int t[5];   // first tile of each of up to four ranges of words, and the end of the last
+};
+
 typedef uint32_t ct_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a global load of 16 bytes at any word
 typedef uint32_t ct_u32x4 __attribute__((ext_vector_type(4)));
 
@@ -158,9 +185,9 @@ typedef uint32_t ct_u32x4 __attribute__((ext_vector_type(4)));
 template <int KS, int NB, bool kU8>
 __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
-    const float *__restrict__ scale, int W, int T, const uint32_t *__restrict__ bt,
-    const uint32_t *__restrict__ src_of, const float *__restrict__ kc, const int32_t *__restrict__ tau,
-    const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
+    const float *__restrict__ scale, int W, int split, const CtRanges range_tile,
+    const uint32_t *__restrict__ bt, const uint32_t *__restrict__ src_of, const float *__restrict__ kc,
+    const int32_t *__restrict__ tau, const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
     extern __shared__ uint32_t pl_lds[];
     constexpr int kQuads = KS * 16;                                  // groups of four features per sample
     constexpr int kPerRound = kCtWaves * kWave / kQuads;             // samples the block quantises at a time
@@ -171,59 +198,61 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int j = lane & 31, h = lane >> 5;
-    // the wave's tiles (at most 64: the host sees to that) and their thresholds, a tile per lane
-    const int t_lo = (int)((int64_t)wave * T / kCtWaves), t_hi = (int)((int64_t)(wave + 1) * T / kCtWaves);
-    const int tau_mine = t_lo + lane < t_hi ? tau[t_lo + lane] : 0;
-    // this thread's word of a row
-    const int w_mine = min((int)threadIdx.x, W - 1);
-    const uint32_t cbits = const_row[w_mine];
     // every lane's read address for the value of lane 4 * h of its own half (see u_of below)
     const int u_addr = (4 * h) * 4;
     // this thread's four features when the block quantises (the same in every round) and its sample of a round
     const int f0 = 4 * ((int)threadIdx.x % kQuads), s_in = (int)threadIdx.x / kQuads;
+    const int fq = min(f0, F - 4);                 // what it loads: four features that exist (F >= 4: the host sees to that)
+    const int q_shift = 8 * min(f0 - fq, 3);       // and where its own first feature's bin number is in them
     uint32_t keep = 0;   // the bytes of its word that are features at all
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         if (f0 + i < F) keep |= 0xffu << (8 * i);
 
-    const int64_t jobs = (N + kCtSamples - 1) / kCtSamples;
-    for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
-        // The job's bin numbers.  A thread takes four neighbouring features of a sample (one 16-byte
-        // load; the group that straddles F loads what exists), kPerRound samples to a round, and
-        // leaves the four bin numbers as one word in LDS.
+    // A unit of work: 32 samples and one of the 1 << split ranges of a row's words.
+    const int64_t units = ((N + kCtSamples - 1) / kCtSamples) << split;
+    for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {   // block-uniform
+        const int64_t job = unit >> split;
+        const int range = (int)(unit & ((1 << split) - 1));
+        // (the bounds come with the kernel's arguments: a table in memory would put a load in front of every job)
+        const int t_first = range == 0 ? range_tile.t[0] : range == 1 ? range_tile.t[1] : range == 2 ? range_tile.t[2] : range_tile.t[3];
+        const int t_end = range == 0 ? range_tile.t[1] : range == 1 ? range_tile.t[2] : range == 2 ? range_tile.t[3] : range_tile.t[4];
+        const int w_first = (int)((int64_t)range * W >> split), w_end = (int)((int64_t)(range + 1) * W >> split);
+        // the wave's tiles (at most 64: the host sees to that) and their thresholds, a tile per lane
+        const int t_lo = t_first + (int)((int64_t)wave * (t_end - t_first) / kCtWaves);
+        const int t_hi = t_first + (int)((int64_t)(wave + 1) * (t_end - t_first) / kCtWaves);
+        // The job's bin numbers.  A thread takes four neighbouring features of a sample with one 16-byte
+        // load, kPerRound samples to a round, and leaves the four bin numbers as one word in LDS.  No
+        // branches around the loads (all of a thread's rounds are in flight together): the group that
+        // straddles F, and those past it, load the row's last four features and shift the word.
         {
             const int64_t first = job * kCtSamples;
             uint32_t raw[kRounds][4];
             float lo_f[4], sc_f[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo_f[i] = kU8 ? 0.0f : lo[min(f0 + i, F - 1)];
-                sc_f[i] = kU8 ? 0.0f : scale[min(f0 + i, F - 1)];
-            }
-#pragma unroll
-            for (int r = 0; r < kRounds; ++r) {   // all loads first (rows past N: the last row again)
-                const int sn = r * kPerRound + s_in;
-                const int64_t at = first + sn;
+            for (int r = 0; r < kRounds; ++r) {   // (rows past N, and the threads with no sample in this round: some row that exists)
+                const int64_t at = first + min(r * kPerRound + s_in, kCtSamples - 1);
                 const int64_t n = at < N ? at : N - 1;
+                if (kU8) {
+                    const uint8_t *row = reinterpret_cast<const uint8_t *>(feats) + n * F + fq;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) raw[r][i] = 0;
-                if (s_in < kPerRound && sn < kCtSamples) {
-                    if (kU8) {
-                        const uint8_t *row = reinterpret_cast<const uint8_t *>(feats) + n * F;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) raw[r][i] = row[min(f0 + i, F - 1)];
-                    } else {
-                        const uint32_t *row = reinterpret_cast<const uint32_t *>(feats) + n * F;
-                        if (f0 + 3 < F) {
-                            const ct_u32x4_a4 v = *reinterpret_cast<const ct_u32x4_a4 *>(row + f0);
-                            raw[r][0] = v[0], raw[r][1] = v[1], raw[r][2] = v[2], raw[r][3] = v[3];
-                        } else if (f0 < F) {
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) raw[r][i] = row[min(f0 + i, F - 1)];
-                        }
-                    }
+                    for (int i = 0; i < 4; ++i) raw[r][i] = row[i];
+                } else {
+                    const ct_u32x4_a4 v = *reinterpret_cast<const ct_u32x4_a4 *>(reinterpret_cast<const uint32_t *>(feats) + n * F + fq);
+                    raw[r][0] = v[0], raw[r][1] = v[1], raw[r][2] = v[2], raw[r][3] = v[3];
                 }
             }
+            {   // the features' ranges after the features (index opaque: lifted out of the job loop, the block's
+                // first feature loads would wait for these)
+                int fqo = fq;
+                asm volatile("" : "+v"(fqo));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    lo_f[i] = kU8 ? 0.0f : lo[fqo + i];
+                    sc_f[i] = kU8 ? 0.0f : scale[fqo + i];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);   // (or the first round is worked on before the others are asked for)
 #pragma unroll
             for (int r = 0; r < kRounds; ++r) {
                 const int sn = r * kPerRound + s_in;
@@ -239,13 +268,14 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                     }
                     word |= q << (8 * i);
                 }
-                if (s_in < kPerRound && sn < kCtSamples) pl_lds[(sn * kRowBytes + f0) >> 2] = word & keep;
+                if (s_in < kPerRound && sn < kCtSamples) pl_lds[(sn * kRowBytes + f0) >> 2] = (word >> q_shift) & keep;
             }
         }
         __syncthreads();
         // Every wave turns them into bit planes over the features, kept in registers: lane (sample j,
         // half h) reads its 32 bytes of MFMA step k and moves bit b of byte i of word m to bit
         // 8 i + m of plane b (word index and bit index trade three of their bits, one per round).
+        const int tau_mine = t_lo + lane < t_hi ? tau[t_lo + lane] : 0;   // (on its way while the planes are made)
         uint32_t pln[KS][NB];
 #pragma unroll
         for (int k = 0; k < KS; ++k) {
@@ -331,25 +361,27 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                 const float d = acc[r];   // (a copy: __builtin_bit_cast applied to the vector element itself reads element 0)
                 bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
             }
-            over16[(size_t)(t * 32 + j) * 2 + h] = (uint16_t)bits;
+            over16[(size_t)((t - t_first) * 32 + j) * 2 + h] = (uint16_t)bits;
             k_mine = kc[(t + 1 < t_hi ? t + 1 : t) * 32 + j];
         }
         // (this thread's entries of the bit table are asked for before the barrier, not after it)
         uint32_t x[32];
+        uint32_t cbits;
         {
-            int w = min((int)threadIdx.x, W - 1);
+            int w = min(w_first + (int)threadIdx.x, w_end - 1);   // this thread's word of a row
             // (opaque to the compiler, or it lifts these 32 loads out of the job loop: a block with one
             // job would then wait for them before it starts, and hold 32 registers throughout)
             asm volatile("" : "+v"(w));
 #pragma unroll
             for (int b = 0; b < 32; ++b) x[b] = src_of[(size_t)b * W + w];   // (~0: a constant of the model)
+            cbits = const_row[w];
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
 
         // Word w of the job's rows.  Bit p of a word of `over` is the sample of register 15 - p of
         // lane half 0 (p < 16) or register 31 - p of half 1.
-        if ((int)threadIdx.x < W) {
+        if (w_first + (int)threadIdx.x < w_end) {
 #pragma unroll
             for (int b = 0; b < 32; ++b) x[b] = x[b] != 0xffffffffu ? over[x[b]] : 0u;
             // x[b] bit p  ->  x[p] bit b
@@ -371,27 +403,36 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             for (int p = 0; p < 32; ++p) {
                 const int r = p < 16 ? 15 - p : 31 - p;
                 const int sn = 8 * (r >> 2) + (p < 16 ? 0 : 4) + (r & 3);
-                if (first + sn < N) hv[(first + sn) * W + threadIdx.x] = x[p] | cbits;
+                if (first + sn < N) hv[(first + sn) * W + w_first + threadIdx.x] = x[p] | cbits;
             }
         }
         __syncthreads();
     }
 }
 
+constexpr int kCtSplitWork = 1024;         // MFMAs per 32 samples from which a row's words are split over blocks
 constexpr int64_t kCtMinSamples = 1024;   // a block takes 32 samples: below this most of the chip would stay idle
 
 template <int KS, int NB, bool kU8>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
-    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (size_t)c->ct_tiles * 32 * 4;
+    // With few samples, several blocks per 32 of them, each with a range of the row's words -- where
+    // the tiles are most of a block's work (every block quantises its 32 samples in full, and ranges
+    // make more, emptier tiles: with 300 MFMAs per 32 samples the split was 8 % slower, with 1900 25 % faster).
+    const int64_t jobs = (n + kCtSamples - 1) / kCtSamples;
+    int v = jobs * 4 <= c->num_cus ? 2 : jobs * 2 <= c->num_cus ? 1 : 0;
+    if (c->ct_tiles[0] * c->ct_steps < kCtSplitWork) v = 0;
+    v = std::min(v, c->ct_max_split);
+    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (size_t)c->ct_range_max[v] * 32 * 4;
     auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
-    const int64_t jobs = (n + kCtSamples - 1) / kCtSamples;
-    const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus);
+    const int64_t blocks = std::min<int64_t>(jobs << v, (int64_t)c->num_cus);
+    CtRanges rt;
+    for (int r = 0; r <= 4; ++r) rt.t[r] = c->ct_range[v][r];
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kCtWaves * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
-                       c->scale_d, c->W, c->ct_tiles, c->ct_bt_d, c->ct_col_d, c->ct_k_d,
-                       c->ct_tau_d, c->expand_d + (size_t)7 * c->W, out);
+                       c->scale_d, c->W, v, rt, c->ct_bt_d[v], c->ct_col_d[v], c->ct_k_d[v],
+                       c->ct_tau_d[v], c->expand_d + (size_t)7 * c->W, out);
     HDC_HIP(hipGetLastError());
     return HDC_OK;
 }

@@ -30,7 +30,9 @@ static void free_ctx(hdc_ctx_impl *c) {
                     c->ob_col_d, c->ob_carry_d, c->ob_coef_d, c->ob_share_d, c->on_bits_d, c->ob_ln_d, c->ob_lw_d, c->ob_meta_d,
                     c->citem_d, c->clevel_d, c->hvc_d, c->expand_d,
                     c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d,
-                    c->ct_tau_d, c->ct_col_d, c->ct_k_d, c->ct_bt_d};
+                    c->ct_tau_d[0], c->ct_col_d[0], c->ct_k_d[0], c->ct_bt_d[0],
+                    c->ct_tau_d[1], c->ct_col_d[1], c->ct_k_d[1], c->ct_bt_d[1],
+                    c->ct_tau_d[2], c->ct_col_d[2], c->ct_k_d[2], c->ct_bt_d[2]};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {

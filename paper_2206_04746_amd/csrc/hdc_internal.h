@@ -98,12 +98,18 @@ struct hdc_ctx_impl {
 
     // Encoding as a contraction over the features (encode_contract.hip); tables derived at create
     // when the level table is of the shape it needs.
+    // A table set per way of splitting a row's words over blocks (1, 2 or 4 blocks per 32 samples:
+    // few samples would leave most of the chip idle otherwise); set v splits 1 << v ways.
     bool ct_ready;
-    int ct_tiles, ct_steps;     // tiles of 32 dimensions; MFMA steps (64 features each) per tile
-    int32_t *ct_tau_d;          // [tiles] the level at which the tile's dimensions flip
-    uint32_t *ct_col_d;         // [32][W] per bit of every word of a row: tile * 32 + column that holds it, ~0 for a constant bit
-    float *ct_k_d;              // [tiles][32] the column's vote threshold, constants folded in
-    uint32_t *ct_bt_d;          // [tiles][steps][64] item ^ level 0 along the features, per column and lane half (nibbles reversed)
+    int ct_steps;               // MFMA steps (64 features each) per tile
+    int ct_max_split;           // the last table set built (a row of fewer than 4 words is not split 4 ways)
+    int ct_tiles[3];            // tiles of 32 dimensions, all word ranges together
+    int ct_range_max[3];        // most tiles of one word range
+    int ct_range[3][5];         // first tile of every word range, then the end of the last (repeated up to the fifth entry)
+    int32_t *ct_tau_d[3];       // [tiles] the level at which the tile's dimensions flip
+    uint32_t *ct_col_d[3];      // [32][W] per bit of every word of a row: (tile - its range's first) * 32 + column that holds it, ~0 for a constant bit
+    float *ct_k_d[3];           // [tiles][32] the column's vote threshold, constants folded in
+    uint32_t *ct_bt_d[3];       // [tiles][steps][64] item ^ level 0 along the features, per column and lane half (nibbles reversed)
 
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).

@@ -2,7 +2,8 @@
 (Sec. III Eq. 1; level tables whose dimensions flip at most once along the levels, L <= 256,
 F <= 640, 1024 samples or more): bit-exact against the CPU oracle, over feature counts on both
 sides of a multiple of 64, even and odd (the tie vote), u8 and fp32 features, sample counts that
-leave a ragged last block, and rows whose last word is partial; and the tables that are not of
+leave a ragged last block (and few enough that the words of a row are split over blocks), and
+rows whose last word is partial; and the tables that are not of
 that shape, which must take the other kernel and give the same bits."""
 import numpy as np
 import pytest
@@ -38,6 +39,9 @@ def _oracle(wl, x):
     (2, 16384, 128, 64, 2048), (2, 96, 10, 3, 3000), (2, 10000, 31, 64, 2300),
     (4, 10000, 561, 100, 2200), (2, 8000, 300, 256, 2100), (2, 6000, 90, 65, 2049), (2, 3000, 50, 129, 2048),
     (3, 2048, 400, 32, 2100), (3, 10000, 625, 64, 2065), (3, 3000, 36, 5, 2048), (2, 10000, 617, 64, 1024), (2, 1024, 100, 16, 1055),
+    # few samples: a row's words are split over two or four blocks per 32 samples
+    (2, 10000, 617, 64, 1559), (2, 10000, 617, 64, 4000), (2, 200, 50, 8, 1100), (2, 128, 20, 4, 1030), (3, 10000, 625, 64, 3333),
+    (2, 10000, 617, 64, 4096), (2, 9999, 100, 200, 1500),
 ])
 def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L, n_train=N)
