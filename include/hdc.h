@@ -88,7 +88,8 @@ int hdc_destroy(hdc_ctx *ctx);
  * strict majority (2*count > F), an exact tie takes tie[d]; pad bits are written 0.
  *   feats_dev [N][F]  fp32 or uint8 as given by feat_dtype, row-major, 4-byte aligned
  *   hv_dev    [N][W]  out
- * The bits do not depend on how the call is carried out: calls of 1024 samples or more on a
+ * The bits do not depend on how the call is carried out: calls of 1024 samples or more (256 for
+ * models of a thousand matrix instructions per 32 samples, e.g. 600 features at D = 10000) on a
  * model whose level vectors change every dimension at most once from one level to the next
  * (at most 256 levels, 4 to 640 features) run as a contraction over the features on the matrix
  * cores, all others on the vector unit.

@@ -411,7 +411,11 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
 }
 
 constexpr int kCtSplitWork = 1024;         // MFMAs per 32 samples from which a row's words are split over blocks
-constexpr int64_t kCtMinSamples = 1024;   // a block takes 32 samples: below this most of the chip would stay idle
+// A block takes 32 samples and is a chain of some 60 k clocks whatever the call's size: below these
+// counts the vector kernels are as fast (measured as whole calls, three launches against one:
+// 512 samples of the 617-feature shape 36 us against 28, 128 samples 29 against 26).
+constexpr int64_t kCtMinSamples = 1024;        // models whose words are not split over blocks
+constexpr int64_t kCtMinSamplesSplit = 256;    // models whose words are
 
 template <int KS, int NB, bool kU8>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
@@ -452,7 +456,8 @@ static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint
 // Encodes with the contraction if the model and the call are of its shape; false otherwise (then
 // nothing was launched).
 bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc) {
-    if (!c->ct_ready || N < kCtMinSamples) return false;
+    const bool splits = c->ct_max_split > 0 && c->ct_tiles[0] * c->ct_steps >= kCtSplitWork;
+    if (!c->ct_ready || N < (splits ? kCtMinSamplesSplit : kCtMinSamples)) return false;
     ProfScope prof(c, HDC_K_ENCODE_CONTRACT, s);
     const bool u8 = c->p.feat_dtype == HDC_U8;
     if (c->p.L <= 64) *rc = u8 ? launch_contract_steps<6, true>(c, feats, N, hv, s) : launch_contract_steps<6, false>(c, feats, N, hv, s);

@@ -1,6 +1,6 @@
 """GPU parity of hdc_encode where it runs as a contraction over the features on the matrix cores
 (Sec. III Eq. 1; level tables whose dimensions flip at most once along the levels, L <= 256,
-F <= 640, 1024 samples or more): bit-exact against the CPU oracle, over feature counts on both
+F <= 640, 1024 samples or more, 256 for large models): bit-exact against the CPU oracle, over feature counts on both
 sides of a multiple of 64, even and odd (the tie vote), u8 and fp32 features, sample counts that
 leave a ragged last block (and few enough that the words of a row are split over blocks), and
 rows whose last word is partial; and the tables that are not of
@@ -42,6 +42,8 @@ def _oracle(wl, x):
     # few samples: a row's words are split over two or four blocks per 32 samples
     (2, 10000, 617, 64, 1559), (2, 10000, 617, 64, 4000), (2, 200, 50, 8, 1100), (2, 128, 20, 4, 1030), (3, 10000, 625, 64, 3333),
     (2, 10000, 617, 64, 4096), (2, 9999, 100, 200, 1500),
+    # large models take the contraction from 256 samples on
+    (2, 10000, 617, 64, 256), (2, 10000, 617, 64, 300), (4, 10000, 561, 100, 700), (3, 10000, 625, 64, 513),
 ])
 def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L, n_train=N)
@@ -59,7 +61,7 @@ def test_encode_contraction_bit_exact(cfg, D, F, L, N):
         assert np.all(got[:, -1] >> last_bits == 0)
     t, n = ctx.hdc_profile_read("encode_contract")
     ctx.hdc_profile_enable(True)
-    _encode(ctx, x[:2048])
+    _encode(ctx, x[:2048] if N >= 1024 else x)
     t, n = ctx.hdc_profile_read("encode_contract")
     assert n == 1, "the call was expected to take the contraction kernel"
     ctx.close()
