@@ -31,7 +31,8 @@
 // With few samples (fewer blocks of 32 than a quarter or half of the CUs) a row's words are split
 // into 4 or 2 ranges and a block takes 32 samples and one range: its tiles are the range's
 // dimensions (a table set per way of splitting), it places only the range's words, and it still
-// quantises all features of its samples.
+// quantises all features of its samples.  Rows of more than 512 words are always split (a thread
+// places one word of its block's range), which takes the kernel to D = 65536.
 // (Tried first: an LDS atomic OR per bit into images of the rows, six times the time of the MFMAs;
 // then the wave's ballots as words over the dimensions and a gather per (bit, sample), LDS bank
 // conflicts making it four times the time of the MFMAs.)
@@ -85,7 +86,8 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     const hdc_params &p = c->p;
     const int W = c->W, F = p.F, L = p.L;
     c->ct_ready = false;
-    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > kCtWaves * kWave) return HDC_OK;   // a thread per word of a row, four features per load
+    c->ct_min_split = -1;
+    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > 4 * kCtWaves * kWave) return HDC_OK;   // four features per load; a thread per word of a quarter of a row at least
     const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
     const int thr = (c->votes + 1) / 2;
     const bool tie_votes = c->votes != F;
@@ -107,6 +109,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     for (int v = 0; v < 3; ++v) {   // the row's words in 1 << v ranges, a block per (32 samples, range)
         const int S = 1 << v;
         if (W < S) break;   // every range of words has a word
+        if ((W + S - 1) / S > kCtWaves * kWave) continue;   // and a thread for each of its words
         std::vector<int32_t> tau_of, range_tile;
         std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: (tile in its range) * 32 + column holding that bit
         std::vector<float> kc;
@@ -149,8 +152,8 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
             range_max = std::max(range_max, (int)(tau_of.size() - t_first));
         }
         range_tile.push_back((int32_t)tau_of.size());
-        // a wave keeps its tiles' thresholds a lane each
-        if (tau_of.empty() || range_max > kCtWaves * kWave) return HDC_OK;
+        if (tau_of.empty()) return HDC_OK;
+        if (range_max > kCtWaves * kWave) continue;   // a wave keeps its tiles' thresholds a lane each
         c->ct_tiles[v] = (int)tau_of.size();
         c->ct_range_max[v] = range_max;
         for (int r = 0; r <= 4; ++r) c->ct_range[v][r] = range_tile[(size_t)std::min(r, S)];
@@ -159,8 +162,10 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
         if (rc == HDC_OK) rc = upload(&c->ct_k_d[v], kc);
         if (rc == HDC_OK) rc = upload(&c->ct_bt_d[v], bt);
         if (rc != HDC_OK) return rc;
+        if (c->ct_min_split < 0) c->ct_min_split = v;
         c->ct_max_split = v;
     }
+    if (c->ct_min_split < 0) return HDC_OK;
     c->ct_steps = steps;
     c->ct_ready = true;
     return HDC_OK;
@@ -424,8 +429,8 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     // make more, emptier tiles: with 300 MFMAs per 32 samples the split was 8 % slower, with 1900 25 % faster).
     const int64_t jobs = (n + kCtSamples - 1) / kCtSamples;
     int v = jobs * 4 <= c->num_cus ? 2 : jobs * 2 <= c->num_cus ? 1 : 0;
-    if (c->ct_tiles[0] * c->ct_steps < kCtSplitWork) v = 0;
-    v = std::min(v, c->ct_max_split);
+    if (c->ct_tiles[c->ct_min_split] * c->ct_steps < kCtSplitWork) v = 0;
+    v = std::max(c->ct_min_split, std::min(v, c->ct_max_split));   // (wide rows are always split: a thread per word of a range)
     const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (size_t)c->ct_range_max[v] * 32 * 4;
     auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
@@ -456,8 +461,9 @@ static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint
 // Encodes with the contraction if the model and the call are of its shape; false otherwise (then
 // nothing was launched).
 bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc) {
-    const bool splits = c->ct_max_split > 0 && c->ct_tiles[0] * c->ct_steps >= kCtSplitWork;
-    if (!c->ct_ready || N < (splits ? kCtMinSamplesSplit : kCtMinSamples)) return false;
+    if (!c->ct_ready) return false;
+    const bool splits = c->ct_max_split > 0 && c->ct_tiles[c->ct_min_split] * c->ct_steps >= kCtSplitWork;
+    if (N < (splits ? kCtMinSamplesSplit : kCtMinSamples)) return false;
     ProfScope prof(c, HDC_K_ENCODE_CONTRACT, s);
     const bool u8 = c->p.feat_dtype == HDC_U8;
     if (c->p.L <= 64) *rc = u8 ? launch_contract_steps<6, true>(c, feats, N, hv, s) : launch_contract_steps<6, false>(c, feats, N, hv, s);

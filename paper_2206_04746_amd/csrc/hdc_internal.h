@@ -102,7 +102,7 @@ struct hdc_ctx_impl {
     // few samples would leave most of the chip idle otherwise); set v splits 1 << v ways.
     bool ct_ready;
     int ct_steps;               // MFMA steps (64 features each) per tile
-    int ct_max_split;           // the last table set built (a row of fewer than 4 words is not split 4 ways)
+    int ct_min_split, ct_max_split;   // the first and last table set built (rows over 512 words are always split, rows under 4 never 4 ways)
     int ct_tiles[3];            // tiles of 32 dimensions, all word ranges together
     int ct_range_max[3];        // most tiles of one word range
     int ct_range[3][5];         // first tile of every word range, then the end of the last (repeated up to the fifth entry)

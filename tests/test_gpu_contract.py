@@ -44,6 +44,8 @@ def _oracle(wl, x):
     (2, 10000, 617, 64, 4096), (2, 9999, 100, 200, 1500),
     # large models take the contraction from 256 samples on
     (2, 10000, 617, 64, 256), (2, 10000, 617, 64, 300), (4, 10000, 561, 100, 700), (3, 10000, 625, 64, 513),
+    # rows of more than 512 words are always split (a thread per word of a range)
+    (2, 32768, 617, 64, 2100), (2, 20000, 200, 32, 5000), (2, 65536, 64, 16, 1100), (2, 40001, 100, 64, 9000),
 ])
 def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L, n_train=N)
