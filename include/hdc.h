@@ -91,7 +91,7 @@ int hdc_destroy(hdc_ctx *ctx);
  * The bits do not depend on how the call is carried out: calls of 1024 samples or more (256 for
  * models of a thousand matrix instructions per 32 samples, e.g. 600 features at D = 10000) on a
  * model whose level vectors change every dimension at most once from one level to the next
- * (at most 256 levels, 4 to 640 features) run as a contraction over the features on the matrix
+ * (at most 256 levels, 4 to 896 features) run as a contraction over the features on the matrix
  * cores, all others on the vector unit.
  */
 int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);

@@ -1,7 +1,7 @@
 // ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features, on the
 // matrix cores.  Same bits as encode_kernel; taken for level tables in which every dimension that
 // varies along the levels flips exactly once (the construction of Sec. III: neighbouring level
-// vectors differ in a few more dimensions each), with at most 256 levels and 640 features.
+// vectors differ in a few more dimensions each), with at most 256 levels and 896 features.
 //
 // For such a dimension d let t_d be the first level whose bit differs from level 0's, and
 // B[f][d] = item[f][d] ^ level[0][d].  The vote of feature f is B[f][d] ^ [q_f >= t_d], so the
@@ -50,7 +50,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kCtWaves = 8;
 constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
-constexpr int kCtMaxSteps = 10;   // MFMAs per tile: 64 features each
+constexpr int kCtMaxSteps = 14;   // MFMAs per tile: 64 features each
 constexpr int kCtCols = 32;       // dimensions per tile
 constexpr int kCtSamples = 32;    // samples per block and job
 constexpr float kCtNever = -1.0e30f;
@@ -193,12 +193,16 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
     const float *__restrict__ scale, int W, int split, const CtRanges range_tile,
     const uint32_t *__restrict__ bt, const uint32_t *__restrict__ src_of, const float *__restrict__ kc,
     const int32_t *__restrict__ tau, const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
-    extern __shared__ uint32_t pl_lds[];
+    extern __shared__ __attribute__((aligned(16))) uint32_t pl_lds[];
     constexpr int kQuads = KS * 16;                                  // groups of four features per sample
     constexpr int kPerRound = kCtWaves * kWave / kQuads;             // samples the block quantises at a time
     constexpr int kRounds = (kCtSamples + kPerRound - 1) / kPerRound;
     constexpr int kRowBytes = KS * 64 + 16;
-    uint32_t *over = pl_lds + kCtSamples * kRowBytes / 4;
+    // From 12 steps on the planes do not fit the registers next to the operands: the waves share
+    // their construction and leave them in LDS, [step][planes 0..3 | 4..7][lane] of four words.
+    constexpr bool kPlanesInLds = KS > 10;
+    ct_u32x4 *planes = reinterpret_cast<ct_u32x4 *>(pl_lds + kCtSamples * kRowBytes / 4);
+    uint32_t *over = pl_lds + kCtSamples * kRowBytes / 4 + (kPlanesInLds ? KS * 2 * kWave * 4 : 0);
     uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
@@ -277,17 +281,16 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
             }
         }
         __syncthreads();
-        // Every wave turns them into bit planes over the features, kept in registers: lane (sample j,
+        // The bin numbers as bit planes over the features, made by every wave for itself and kept in
+        // registers (up to 10 MFMA steps; beyond, see kPlanesInLds): lane (sample j,
         // half h) reads its 32 bytes of MFMA step k and moves bit b of byte i of word m to bit
         // 8 i + m of plane b (word index and bit index trade three of their bits, one per round).
         const int tau_mine = t_lo + lane < t_hi ? tau[t_lo + lane] : 0;   // (on its way while the planes are made)
-        uint32_t pln[KS][NB];
-#pragma unroll
-        for (int k = 0; k < KS; ++k) {
+        auto planes_of = [&](const int k, uint32_t (&x)[8]) {
             const ct_u32x4 *src = reinterpret_cast<const ct_u32x4 *>(
                 reinterpret_cast<const uint8_t *>(pl_lds) + j * kRowBytes + k * 64 + h * 32);
             const ct_u32x4 v0 = src[0], v1 = src[1];
-            uint32_t x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+            x[0] = v0[0], x[1] = v0[1], x[2] = v0[2], x[3] = v0[3], x[4] = v1[0], x[5] = v1[1], x[6] = v1[2], x[7] = v1[3];
 #pragma unroll
             for (int stage = 0; stage < 3; ++stage) {
                 const int sh = 1 << stage;
@@ -300,8 +303,28 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
                         x[i + sh] = ((a >> sh) & m) | (b & ~m);
                     }
             }
+        };
+        uint32_t pln[kPlanesInLds ? 1 : KS][NB];
+        if constexpr (kPlanesInLds) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) pln[k][b] = x[b];
+            for (int k0 = 0; k0 < KS; k0 += kCtWaves) {
+                const int k = k0 + wave;
+                if (k < KS) {   // wave-uniform
+                    uint32_t x[8];
+                    planes_of(k, x);
+                    planes[(k * 2 + 0) * kWave + lane] = ct_u32x4{x[0], x[1], x[2], x[3]};
+                    if (NB > 4) planes[(k * 2 + 1) * kWave + lane] = ct_u32x4{x[4], x[5], x[6], x[7]};
+                }
+            }
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int k = 0; k < KS; ++k) {
+                uint32_t x[8];
+                planes_of(k, x);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) pln[k][b] = x[b];
+            }
         }
 
         int cur_tau = 0;
@@ -322,9 +345,18 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
 #pragma unroll
                 for (int k = 0; k < KS; ++k) {
                     uint32_t ge = 0xffffffffu;
+                    uint32_t qp[8];
+                    if constexpr (kPlanesInLds) {
+                        const ct_u32x4 p0 = planes[(k * 2 + 0) * kWave + lane];
+                        const ct_u32x4 p1 = NB > 4 ? planes[(k * 2 + 1) * kWave + lane] : ct_u32x4{0u, 0u, 0u, 0u};
+                        qp[0] = p0[0], qp[1] = p0[1], qp[2] = p0[2], qp[3] = p0[3], qp[4] = p1[0], qp[5] = p1[1], qp[6] = p1[2], qp[7] = p1[3];
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) qp[b] = pln[k][b];
+                    }
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const uint32_t q = pln[k][b];
+                        const uint32_t q = qp[b];
                         const uint32_t tb = (tt >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
                         ge = __builtin_amdgcn_bitop3_b32(q, ge, tb, 0xD4);      // tb ? q & ge : q | ge
                     }
@@ -431,7 +463,8 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     int v = jobs * 4 <= c->num_cus ? 2 : jobs * 2 <= c->num_cus ? 1 : 0;
     if (c->ct_tiles[c->ct_min_split] * c->ct_steps < kCtSplitWork) v = 0;
     v = std::max(c->ct_min_split, std::min(v, c->ct_max_split));   // (wide rows are always split: a thread per word of a range)
-    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (size_t)c->ct_range_max[v] * 32 * 4;
+    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (KS > 10 ? (size_t)KS * 2 * kWave * 16 : 0) +
+                       (size_t)c->ct_range_max[v] * 32 * 4;
     auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -454,7 +487,9 @@ static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint
     case 4: return launch_contract<4, NB, kU8>(c, x, n, out, s);
     case 6: return launch_contract<6, NB, kU8>(c, x, n, out, s);
     case 8: return launch_contract<8, NB, kU8>(c, x, n, out, s);
-    default: return launch_contract<10, NB, kU8>(c, x, n, out, s);
+    case 10: return launch_contract<10, NB, kU8>(c, x, n, out, s);
+    case 12: return launch_contract<12, NB, kU8>(c, x, n, out, s);
+    default: return launch_contract<14, NB, kU8>(c, x, n, out, s);
     }
 }
 

@@ -1,6 +1,6 @@
 """GPU parity of hdc_encode where it runs as a contraction over the features on the matrix cores
 (Sec. III Eq. 1; level tables whose dimensions flip at most once along the levels, L <= 256,
-F <= 640, 1024 samples or more, 256 for large models): bit-exact against the CPU oracle, over feature counts on both
+F <= 896, 1024 samples or more, 256 for large models): bit-exact against the CPU oracle, over feature counts on both
 sides of a multiple of 64, even and odd (the tie vote), u8 and fp32 features, sample counts that
 leave a ragged last block (and few enough that the words of a row are split over blocks), and
 rows whose last word is partial; and the tables that are not of
@@ -46,6 +46,9 @@ def _oracle(wl, x):
     (2, 10000, 617, 64, 256), (2, 10000, 617, 64, 300), (4, 10000, 561, 100, 700), (3, 10000, 625, 64, 513),
     # rows of more than 512 words are always split (a thread per word of a range)
     (2, 32768, 617, 64, 2100), (2, 20000, 200, 32, 5000), (2, 65536, 64, 16, 1100), (2, 40001, 100, 64, 9000),
+    # 641 to 896 features: 12 or 14 MFMA steps, the bit planes shared through LDS
+    (3, 10000, 784, 256, 2100), (3, 10000, 784, 256, 9000), (2, 10000, 700, 64, 2222), (2, 5000, 896, 64, 1300),
+    (2, 10000, 769, 100, 600), (3, 3000, 841, 32, 4100), (2, 20000, 650, 16, 2050),
 ])
 def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L, n_train=N)
