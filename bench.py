@@ -351,8 +351,9 @@ def extras(torch, binding, make_workload):
                                       "2 flops per (feature, varying dimension) against the FP4 matrix peak"}
     ctx.close()
     del hv, y, pred, x5d, hv5
-    # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): the dense
-    # encoder against the one that bundles only the features that leave bin 0 (same bits out)
+    # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): hdc_encode
+    # (all features; for this model the contraction on the matrix cores, 14 MFMA steps per tile)
+    # against the call that bundles only the features that leave bin 0 (same bits out)
     wl3 = make_workload(3)
     ctx = binding.Context(wl3.D, wl3.F, wl3.L, wl3.C, wl3.item, wl3.level, wl3.tie, wl3.lo, wl3.scale, wl3.dtype)
     x3, _ = wl3.train()
