@@ -49,7 +49,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kCtWaves = 8;
+constexpr int kCtWaves = 8;        // waves per block at least (the kernel runs with 8 or 12)
 constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
 constexpr int kCtMaxSteps = 14;   // MFMAs per tile: 64 features each
 constexpr int kCtCols = 32;       // dimensions per tile
@@ -188,20 +188,20 @@ typedef uint32_t ct_u32x4 __attribute__((ext_vector_type(4)));
 // Dynamic LDS: the job's bin numbers, a byte each, [sample][KS * 64 + 16] (the 16 spread the rows
 // over the banks), then per (tile, column) the bits of the job's 32 samples [T * 32] (two 16-bit
 // halves, one per lane half).
-template <int KS, int NB, bool kU8>
-__global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
+template <int KS, int NB, bool kU8, int NW>
+__global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
     const float *__restrict__ scale, int W, int split, const CtRanges range_tile,
     const uint32_t *__restrict__ bt, const uint32_t *__restrict__ src_of, const float *__restrict__ kc,
     const int32_t *__restrict__ tau, const uint32_t *__restrict__ const_row, uint32_t *__restrict__ hv) {
     extern __shared__ __attribute__((aligned(16))) uint32_t pl_lds[];
     constexpr int kQuads = KS * 16;                                  // groups of four features per sample
-    constexpr int kPerRound = kCtWaves * kWave / kQuads;             // samples the block quantises at a time
+    constexpr int kPerRound = NW * kWave / kQuads;             // samples the block quantises at a time
     constexpr int kRounds = (kCtSamples + kPerRound - 1) / kPerRound;
     constexpr int kRowBytes = KS * 64 + 16;
     // From 12 steps on the planes do not fit the registers next to the operands: the waves share
     // their construction and leave them in LDS, [step][planes 0..3 | 4..7][lane] of four words.
-    constexpr bool kPlanesInLds = KS > 10;
+    constexpr bool kPlanesInLds = KS > 10 || NW > 8;
     ct_u32x4 *planes = reinterpret_cast<ct_u32x4 *>(pl_lds + kCtSamples * kRowBytes / 4);
     uint32_t *over = pl_lds + kCtSamples * kRowBytes / 4 + (kPlanesInLds ? KS * 2 * kWave * 4 : 0);
     uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
@@ -229,8 +229,8 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
         const int t_end = range == 0 ? range_tile.t[1] : range == 1 ? range_tile.t[2] : range == 2 ? range_tile.t[3] : range_tile.t[4];
         const int w_first = (int)((int64_t)range * W >> split), w_end = (int)((int64_t)(range + 1) * W >> split);
         // the wave's tiles (at most 64: the host sees to that) and their thresholds, a tile per lane
-        const int t_lo = t_first + (int)((int64_t)wave * (t_end - t_first) / kCtWaves);
-        const int t_hi = t_first + (int)((int64_t)(wave + 1) * (t_end - t_first) / kCtWaves);
+        const int t_lo = t_first + (int)((int64_t)wave * (t_end - t_first) / NW);
+        const int t_hi = t_first + (int)((int64_t)(wave + 1) * (t_end - t_first) / NW);
         // The job's bin numbers.  A thread takes four neighbouring features of a sample with one 16-byte
         // load, kPerRound samples to a round, and leaves the four bin numbers as one word in LDS.  No
         // branches around the loads (all of a thread's rounds are in flight together): the group that
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kCtWaves *kWave) void encode_contract_kernel(
         uint32_t pln[kPlanesInLds ? 1 : KS][NB];
         if constexpr (kPlanesInLds) {
 #pragma unroll
-            for (int k0 = 0; k0 < KS; k0 += kCtWaves) {
+            for (int k0 = 0; k0 < KS; k0 += NW) {
                 const int k = k0 + wave;
                 if (k < KS) {   // wave-uniform
                     uint32_t x[8];
@@ -464,16 +464,22 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     int v = jobs * 4 <= c->num_cus ? 2 : jobs * 2 <= c->num_cus ? 1 : 0;
     if (c->ct_tiles[c->ct_min_split] * c->ct_steps < kCtSplitWork) v = 0;
     v = std::max(c->ct_min_split, std::min(v, c->ct_max_split));   // (wide rows are always split: a thread per word of a range)
-    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (KS > 10 ? (size_t)KS * 2 * kWave * 16 : 0) +
+    // Twelve waves where the tiles are most of the work (a third wave per SIMD fills more of the gaps
+    // between matrix and vector instructions: 3 to 6 % on the 342- to 784-feature shapes), eight
+    // for small models (100 features: 3 % slower with twelve).  The limits the host applies to the
+    // tables are those of eight.
+    constexpr int NW = KS >= 6 ? 12 : kCtWaves;
+    constexpr bool kPlanesInLds = KS > 10 || NW > 8;
+    auto kern = encode_contract_kernel<KS, NB, kU8, NW>;
+    const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (kPlanesInLds ? (size_t)KS * 2 * kWave * 16 : 0) +
                        (size_t)c->ct_range_max[v] * 32 * 4;
-    auto kern = encode_contract_kernel<KS, NB, kU8>;
     if (lds > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
     const int64_t blocks = std::min<int64_t>(jobs << v, (int64_t)c->num_cus);
     CtRanges rt;
     for (int r = 0; r <= 4; ++r) rt.t[r] = c->ct_range[v][r];
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kCtWaves * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NW * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
                        c->scale_d, c->W, v, rt, c->ct_bt_d[v], c->ct_col_d[v], c->ct_k_d[v],
                        c->ct_tau_d[v], c->expand_d + (size_t)7 * c->W, out);
     HDC_HIP(hipGetLastError());
