@@ -17,12 +17,14 @@
 // features: [q >= t] for 32 features at once is one 3-input bit operation per plane.
 //
 // A block takes 32 samples.  It quantises them first, a thread per four neighbouring features of a
-// sample, and leaves the bin numbers in LDS a byte each; every wave then builds the bit planes of
-// all 32 samples in its own registers (32 bytes per lane and MFMA step, three rounds of masked
-// swaps among eight words; from 12 MFMA steps on, i.e. above 640 features, the waves share that
-// work and read the planes from LDS: they no longer fit the registers).  (Before: a ballot per plane over a wave of 64 features of one sample,
-// 55 instructions per 64 bin numbers against 6 + 9 now, and the block waited 16 k clocks instead
-// of 8 k for its operands.)  The eight waves split the tiles of dimensions.  The bits come out with
+// sample, and leaves the bin numbers in LDS a byte each; from these come the bit planes of all 32
+// samples (32 bytes per lane and MFMA step, three rounds of masked swaps among eight words).
+// Models of up to 4 MFMA steps run with eight waves, each of which builds all planes in its own
+// registers; from 6 steps on a block has twelve waves (168 registers each), which share the work
+// and read the planes from LDS at every threshold.  (Before: a ballot per plane over a wave of 64
+// features of one sample, 55 instructions per 64 bin numbers against 6 + 9 now, and the block
+// waited 16 k clocks instead of 8 k for its operands.)  The waves split the tiles of dimensions.
+// The bits come out with
 // a dimension per lane and a sample per register: a lane strings the 16 bits of its registers
 // together (the sign of a fused multiply-add, shifted in by v_alignbit) and leaves them in LDS as
 // the word "dimension (tile, column) of 16 samples".  When all tiles are done, thread w collects,
