@@ -3,15 +3,18 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
-A step is one pass of the classical pipeline over the ISOLET-shaped synthetic workload
-(D=10000, F=617, L=64, C=26, 6238 train / 1559 test samples, all resident in HBM):
-    encode(train) -> classical accumulate -> majority binarise -> encode(test) -> Hamming search.
-Prints ONE JSON line.  `value` = encoded+trained samples/s (N_train over the device time of
-encode(train) + train + binarise, from events inside the timed steps); Hamming queries/s,
-the online-training rate (UCIHAR-shaped config) and large-N figures for the HBM-bound
-kernels ride along as extra keys.  `roofline` describes the dominant kernel (encode_kernel,
-VALU-bound); `cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded
-sample of the same workload.
+The workload is the largest configuration that fits one GPU: the long-term-EEG-shaped stream
+(D=10000, F=342 fp32 features, L=64 levels, C=2 classes, 5,000,000 windows with 1 % positives,
+taken in five chunks of 1,000,000 windows; Sec. VI-E / Table II shape), all inputs resident in HBM.
+A step is one pass of the whole path over it:
+    for each chunk: encode -> classical accumulate;  majority binarise;  for each chunk: search.
+Prints ONE JSON line.  `value` = encoded+trained windows/s (all windows over the device time of
+the encode + train + binarise leg, median over the timed steps); `queries_per_s` comes from the
+search leg.  `roofline` describes the dominant kernel (the contraction form of the encoder on a
+1M-window chunk) against the FP4 matrix peak it runs on, with the HBM fraction of the same
+launch next to it; `hbm_roofline` gives the HBM fractions of the two legs the metric names.
+`cpu_baseline` is the CPU oracle timed on this machine's host cores (all cores and one thread) on a
+bounded prefix of the same windows.  The smaller configurations ride along under `secondary`.
 """
 from __future__ import annotations
 
@@ -35,17 +38,42 @@ HBM_PEAK_GBS = 8000.0
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 MFMA_FP4_PEAK_TFLOPS = 10100.0    # MI355X published dense FP4 matrix peak
 FP64_PEAK_TFLOPS = 78.6           # MI355X published fp64 vector peak (FMA = 2 flop)
+CHUNK_WINDOWS = 1_000_000         # the stream is taken in chunks of this many windows
+PROFILE_STEPS = 40                # steps of the per-kernel timing pass (5 launches a step; 512 slots)
+
+
+def _load_stream(torch, wl, n_windows, dev):
+    """The first `n_windows` windows of the stream and their labels, generated block by block
+    (independently seeded blocks of 65536 rows) on the host threads and copied to the GPU."""
+    from concurrent.futures import ThreadPoolExecutor
+    from workloads.synthetic import CHUNK as BLOCK
+    x = torch.empty((n_windows, wl.F), dtype=torch.float32, device=dev)
+    y = torch.empty(n_windows, dtype=torch.int32, device=dev)
+    starts = list(range(0, n_windows, BLOCK))
+
+    def make(s):
+        return s, wl.train(min(BLOCK, n_windows - s), s)
+    t0 = time.perf_counter()
+    h2d = 0.0
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        for s, (xb, yb) in ex.map(make, starts):
+            t = time.perf_counter()
+            x[s:s + xb.shape[0]].copy_(torch.from_numpy(xb))
+            y[s:s + yb.shape[0]].copy_(torch.from_numpy(yb))
+            torch.cuda.synchronize()
+            h2d += time.perf_counter() - t
+    return x, y, time.perf_counter() - t0, h2d
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--windows", type=int, default=5_000_000,
+                    help="windows of the stream (default: all 5,000,000 of the configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="diagnosis: do not bracket the hot kernels with events in the timed region (no roofline)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a 1 GiB device copy 10 times (known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -74,15 +102,180 @@ def main() -> int:
                           "launches": 10}))
         return 0
 
+    dev = "cuda"
+    wl = make_workload(5)
+    N = int(args.windows)
+    if not 0 < N <= wl.n_train:
+        print("bench.py: --windows must be 1..5000000", file=sys.stderr)
+        return 2
+    x, y, gen_s, h2d_s = _load_stream(torch, wl, N, dev)
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    W = ctx.W
+    chunks = [(s, min(N, s + CHUNK_WINDOWS)) for s in range(0, N, CHUNK_WINDOWS)]
+    hv = torch.empty((N, W), dtype=torch.int32, device=dev)
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device=dev)
+    cn = torch.zeros(wl.C, dtype=torch.int64, device=dev)
+    cls = torch.empty((wl.C, W), dtype=torch.int32, device=dev)
+    pred = torch.empty(N, dtype=torch.int32, device=dev)
+
+    def step(e=None):
+        if e:
+            e[0].record()
+        acc.zero_()
+        cn.zero_()
+        for a, b in chunks:
+            ctx.hdc_encode(x[a:b], hv[a:b])
+            ctx.hdc_train_classical(hv[a:b], y[a:b], acc, cn)
+        ctx.hdc_binarize_classical(acc, cn, cls)
+        if e:
+            e[1].record()
+        for a, b in chunks:
+            ctx.hdc_search(hv[a:b], cls, pred[a:b], None)
+        if e:
+            e[2].record()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize()
+    # ---- the timed region: exactly K steps, the two legs separated by events on the stream
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    t_train = np.array([e[0].elapsed_time(e[1]) for e in ev])    # ms: encode + train + binarise, all chunks
+    t_search = np.array([e[1].elapsed_time(e[2]) for e in ev])   # ms: search, all chunks
+    value = N / (float(np.median(t_train)) * 1e-3)
+    queries = N / (float(np.median(t_search)) * 1e-3)
+    # sanity of the trained model on the stream itself (the configuration searches what it trained on)
+    y_h = y.cpu().numpy()
+    p_h = pred.cpu().numpy()
+    accuracy = float((p_h == y_h).mean())
+    recall_pos = float((p_h[y_h == 1] == 1).mean()) if (y_h == 1).any() else None
+
+    # ---- per-kernel durations: the same step again, every hot kernel bracketed by its own pair of
+    # events on the launch stream (hdc_profile_*).  Kept out of the region above because the
+    # extra events hold the stream up between kernels.  The work is counted from the launches
+    # that were actually timed.
+    kinds = ("encode", "encode_contract", "quantize", "accumulate", "search")
+    ctx.hdc_profile_enable(True)
+    for k in kinds:
+        ctx.hdc_profile_read(k)
+    psteps = min(K, PROFILE_STEPS)
+    for _ in range(psteps):
+        step()
+    torch.cuda.synchronize()
+    prof = {k: ctx.hdc_profile_read(k) for k in kinds}
+    ctx.hdc_profile_enable(False)
+    full = [b - a for a, b in chunks]
+    per_launch = float(np.mean(full))                       # windows per launch (1,000,000 unless --windows cuts it)
+
+    # Algorithmic work (Sec. III Eq. 1): per window and varying dimension one dot product of two
+    # F-bit vectors = 2 F flops on the matrix cores (dimensions no level vector changes are
+    # constants of the model); bytes: the features in, the packed row out.
+    Wk = ctx.hdc_encoded_words()
+    Dv = 32 * Wk
+    enc_bytes = 4.0 * wl.F + 4.0 * W
+    ct_ms, ct_n = prof["encode_contract"]
+    en_ms, en_n = prof["encode"]
+    if ct_n:
+        assert ct_n == psteps * len(chunks), "timed launches of the encoder do not match the steps run"
+        us = ct_ms * 1e3 / ct_n
+        flops = 2.0 * wl.F * Dv * per_launch
+        achieved = flops / (us * 1e-6) / 1e12
+        gbs = enc_bytes * per_launch / (us * 1e-6) / 1e9
+        roofline = {
+            "kernel": "encode_contract_kernel (quantise + contraction + bit placement, one launch per chunk)",
+            "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "traffic_note": "HBM bytes per launch are in profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                            "command); counters cannot be read from inside the run",
+            "avg_launch_us": round(us, 1), "launches": ct_n, "windows_per_launch": per_launch,
+            "algorithmic_flops_per_window": 2.0 * wl.F * Dv, "dimensions_contracted_of": [Dv, wl.D],
+            "hbm": {"algorithmic_bytes_per_window": enc_bytes, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)},
+        }
+    else:
+        assert en_n, "no encoder launch was timed"
+        us = en_ms * 1e3 / en_n
+        ops = 3.0 * wl.F * Wk * (N * psteps / en_n)
+        achieved = ops / (us * 1e-6) / 1e12
+        roofline = {"kernel": "encode_kernel", "bound": "alu", "achieved": round(achieved, 3),
+                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
+                    "frac": round(achieved / VALU_PEAK_TOPS, 4), "traffic": None,
+                    "avg_launch_us": round(us, 1), "launches": en_n}
+    ac_ms, ac_n = prof["accumulate"]
+    se_ms, se_n = prof["search"]
+    row_bytes = 4.0 * W + 4.0
+    kernels = {}
+    if ac_n:
+        us = ac_ms * 1e3 / ac_n
+        kernels["accumulate_kernel"] = {"avg_launch_us": round(us, 1), "launches": ac_n,
+                                        "frac_hbm": round(row_bytes * per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    if se_n:
+        us = se_ms * 1e3 / se_n
+        kernels["search_kernel"] = {"avg_launch_us": round(us, 1), "launches": se_n,
+                                    "frac_hbm": round(row_bytes * per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    # HBM fractions of the two legs the metric names, from the step's own stage times: what the
+    # method must move per window (features in, row out, row and label in again for training; row
+    # in and prediction out for the search) over the leg's device time.
+    train_bytes = enc_bytes + row_bytes
+    hbm = {
+        "encode_plus_train": {"algorithmic_bytes_per_window": train_bytes,
+                              "frac": round(train_bytes * value / 1e9 / HBM_PEAK_GBS, 4)},
+        "search": {"algorithmic_bytes_per_query": row_bytes,
+                   "frac": round(row_bytes * queries / 1e9 / HBM_PEAK_GBS, 4)},
+    }
+
+    out = {
+        "metric": "encoded+trained samples/sec and Hamming queries/sec at D=10000; % HBM roofline",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": f"configs[4]: long-term-EEG-shaped classical HDC, D=10000, F=342 fp32, L=64, C=2, "
+                               f"{N} windows (1 % positive, lognormal per channel) in {len(chunks)} chunks of "
+                               f"{CHUNK_WINDOWS}",
+                   "step": "per chunk: encode + train_classical; binarize; per chunk: search"},
+        "queries_per_s": round(queries, 1),
+        "stage_ms_median": {"encode_plus_train": round(float(np.median(t_train)), 4),
+                            "search": round(float(np.median(t_search)), 4)},
+        "stage_ms_mean": {"encode_plus_train": round(float(t_train.mean()), 4),
+                          "search": round(float(t_search.mean()), 4)},
+        "hbm_roofline": hbm,
+        "accuracy_on_stream": round(accuracy, 4), "recall_of_positives": recall_pos,
+        "roofline": roofline,
+        "kernels": kernels,
+        "input": {"generated_s": round(gen_s, 1), "h2d_s": round(h2d_s, 2),
+                  "h2d_GBs": round((x.numel() * 4 + y.numel() * 4) / max(h2d_s, 1e-9) / 1e9, 2),
+                  "note": "host-to-device copies are outside the timed region (the boundary takes device pointers)"},
+    }
+    ctx.close()
+    del x, hv, pred
+    torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        out["secondary"] = secondary(torch, binding, make_workload, K)
+        out["extras"] = extras(torch, binding, make_workload)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+    return 0
+
+
+def secondary(torch, binding, make_workload, K):
+    """The small classical configuration (ISOLET shape: 6238 train / 1559 test samples, 26 classes)
+    as one step of eight launches - bound by launch sizes, not by any roofline."""
+    dev = "cuda"
     wl = make_workload(2)
     xt_h, yt_h = wl.train()
     xs_h, ys_h = wl.test()
     ntr, nte = xt_h.shape[0], xs_h.shape[0]
     ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
     W = ctx.W
-    dev = "cuda"
-    xt, yt = torch.from_numpy(xt_h).to(dev), torch.from_numpy(yt_h).to(dev)
-    xs = torch.from_numpy(xs_h).to(dev)
+    xt, yt, xs = torch.from_numpy(xt_h).to(dev), torch.from_numpy(yt_h).to(dev), torch.from_numpy(xs_h).to(dev)
     hv_t = torch.empty((ntr, W), dtype=torch.int32, device=dev)
     hv_s = torch.empty((nte, W), dtype=torch.int32, device=dev)
     acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device=dev)
@@ -90,7 +283,7 @@ def main() -> int:
     cls = torch.empty((wl.C, W), dtype=torch.int32, device=dev)
     dist = torch.empty((nte, wl.C), dtype=torch.int32, device=dev)
     pred = torch.empty(nte, dtype=torch.int32, device=dev)
-
+    K = max(K, 50)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
 
     def step(e=None):
@@ -109,165 +302,47 @@ def main() -> int:
         ctx.hdc_search(hv_s, cls, pred, dist)
         if e:
             e[3].record()
-
-    for _ in range(Wm):
+    for _ in range(10):
         step()
     torch.cuda.synchronize()
-    # ---- the timed region: exactly K steps, stage boundaries marked by four events per step
     t0 = time.perf_counter()
     for k in range(K):
         step(ev[k])
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    # ---- the same K steps once more with every hot kernel bracketed by its own pair of events on
-    # the launch stream (hdc_profile_*): per-kernel durations for the roofline.  Kept out of the
-    # region above because the extra events hold the stream up between kernels (about 20 % of a
-    # step of this size); a kernel's own duration is the same in both passes and in
-    # profiles/bench_cfg2_kernel_stats.txt.
-    ctx.hdc_profile_enable(not args.no_kernel_events)
-    for k in ("encode", "encode_contract", "quantize", "accumulate", "search"):
-        ctx.hdc_profile_read(k)
-    for k in range(K):
-        step()
-    torch.cuda.synchronize()
-    prof = {k: ctx.hdc_profile_read(k) for k in ("encode", "encode_contract", "quantize", "accumulate", "search")}
-    ctx.hdc_profile_enable(False)
-    t_train = np.array([e[0].elapsed_time(e[1]) for e in ev])    # ms: encode(train)+train+binarise
-    t_enc_s = np.array([e[1].elapsed_time(e[2]) for e in ev])    # ms: encode(test)
-    t_search = np.array([e[2].elapsed_time(e[3]) for e in ev])   # ms: search
-    value = ntr / (t_train.mean() * 1e-3)
-    queries = nte / (t_search.mean() * 1e-3)
-    accuracy = float((pred.cpu().numpy() == ys_h).mean())
-
-    # ---- roofline of the dominant kernel -------------------------------------------------
-    # hdc_encode has two forms.  From 1024 samples on (here: both sets) it runs as a contraction
-    # over the features on the matrix cores, encode_contract_kernel: per sample and varying dimension
-    # one dot product of two F-bit vectors, 2 * F flops, on FP4 operands - the dominant kernel of
-    # the step, priced against the FP4 matrix peak.  Smaller calls take
-    # encode_kernel on the vector unit: one bind XOR + one full adder (two 3-input bit ops) per
-    # (sample, feature, 32-bit word) = 3 * F * Wk lane-ops per sample, Wk the words it bundles
-    # (dimensions that no level vector changes are constants of the model and are not computed).
-    enc_ms, enc_launches = prof["encode"]
-    ct_ms, ct_launches = prof["encode_contract"]
-    Wk = ctx.hdc_encoded_words()
-    ops_per_sample = 3.0 * wl.F * Wk
-    # which calls took which form shows in the launch counts (the library decides by the call's size)
-    ct_samples = 0 if ct_launches == 0 else ntr if ct_launches == K else ntr + nte
-    valu_samples = ntr + nte - ct_samples
-    valu_achieved = ops_per_sample * valu_samples * K / (enc_ms * 1e-3) / 1e12 if enc_ms > 0 else 0.0
-    valu_kernel = {
-        "kernel": "encode_kernel", "bound": "alu", "achieved": round(valu_achieved, 3),
-        "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s", "frac": round(valu_achieved / VALU_PEAK_TOPS, 4),
-        "avg_launch_us": round(enc_ms * 1e3 / max(1, enc_launches), 2), "launches": enc_launches,
-        "samples_per_launch": valu_samples // max(1, enc_launches // K) if enc_launches else 0,
-        "algorithmic_ops_per_sample": ops_per_sample, "words_bundled_of": [Wk, W],
-    }
-    if ct_launches:
-        flops_per_sample = 2.0 * wl.F * Wk * 32
-        achieved = flops_per_sample * ct_samples * K / (ct_ms * 1e-3) / 1e12
-        roofline = {
-            "kernel": "encode_contract_kernel", "bound": "mfma", "achieved": round(achieved, 2),
-            "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
-            "traffic": _profiled_traffic("hdc::encode_contract_kernel"),
-            "avg_launch_us": round(ct_ms * 1e3 / ct_launches, 2), "launches": ct_launches,
-            "samples_per_step": ct_samples, "launches_per_step": ct_launches // K,
-            "algorithmic_flops_per_sample": flops_per_sample,
-            "dimensions_contracted_of": [Wk * 32, wl.D],
-            "note": "quantise + contraction + bit placement in one kernel; the vector kernel it replaces took "
-                    "83 us (6238 samples) and 33 us (1559) at 0.48 of the VALU peak over both",
-        }
-        if enc_launches:
-            roofline["vector_kernel"] = valu_kernel
-    else:
-        roofline = dict(valu_kernel)
-        roofline["traffic"] = _profiled_traffic("hdc::encode_kernel")
-        roofline["frac_if_all_words_were_bundled"] = round(valu_achieved / VALU_PEAK_TOPS * W / max(1, Wk), 4)
-    srch_ms, srch_launches = prof["search"]
-    accu_ms, accu_launches = prof["accumulate"]
-    kernels = {
-        "search_kernel": {"avg_launch_us": round(srch_ms * 1e3 / max(1, srch_launches), 2),
-                          "GBs": round((nte * W * 4 + nte * 4 * (wl.C + 1)) * srch_launches / (srch_ms * 1e-3) / 1e9, 2)
-                          if srch_ms > 0 else 0.0},
-        "accumulate_kernel": {"avg_launch_us": round(accu_ms * 1e3 / max(1, accu_launches), 2),
-                              "GBs": round((ntr * W * 4 + ntr * 4) * accu_launches / (accu_ms * 1e-3) / 1e9, 2)
-                              if accu_ms > 0 else 0.0},
-        "quantize_kernel": {"avg_launch_us": round(prof["quantize"][0] * 1e3 / max(1, prof["quantize"][1]), 2)},
-    }
-
-    out = {
-        "metric": "encoded+trained samples/sec and Hamming queries/sec at D=10000; % HBM roofline",
-        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "configs[1]: classical HDC, D=10000, F=617 fp32, L=64, C=26, "
-                               "6238 train / 1559 test (ISOLET shape, seeded Gaussian clusters)",
-                   "step": "encode(train)+train_classical+binarize | encode(test) | search"},
-        "queries_per_s": round(queries, 1),
-        "encode_test_samples_per_s": round(nte / (t_enc_s.mean() * 1e-3), 1),
-        "stage_ms": {"encode_train_plus_train": round(float(t_train.mean()), 4),
-                     "encode_test": round(float(t_enc_s.mean()), 4),
-                     "search": round(float(t_search.mean()), 4)},
-        "test_accuracy": round(accuracy, 4),
-        "roofline": roofline,
-        "kernels": kernels,
-    }
-
-    if not args.no_extras:
-        out["extras"] = extras(torch, binding, make_workload)
-        # The same step recorded once in a HIP graph and replayed K times (one submission per step
-        # instead of seven launches): what a serving loop would do.  Not `value`: reported beside it.
-        try:
-            pred_eager = pred.clone()
-            side = torch.cuda.Stream()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                step()
-            torch.cuda.synchronize()
-            for _ in range(Wm):
-                graph.replay()
-            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            g0.record()
-            for _ in range(K):
-                graph.replay()
-            g1.record()
-            torch.cuda.synchronize()
-            out["extras"]["step_replayed_from_hip_graph"] = {
-                "ms_per_step": round(g0.elapsed_time(g1) / K, 4), "steps": K,
-                "same_predictions_as_eager": bool(torch.equal(pred, pred_eager))}
-        except RuntimeError as err:   # the headline above does not depend on this
-            out["extras"]["step_replayed_from_hip_graph"] = {"error": str(err)[:200]}
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, xt_h, yt_h)
-    ctx.close()
-    print(json.dumps(out))
-    return 0
-
-
-def _profiled_traffic(kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE in KiB per dispatch, scaled by the copy-kernel factors stated in that file); None
-    if the summary is absent.  Counters cannot be collected from inside this process."""
-    path = os.path.join(ROOT, "profiles", "encode_kernel_cfg2_pmc.txt")
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+    t_train = float(np.median([e[0].elapsed_time(e[1]) for e in ev]))
+    t_enc_s = float(np.median([e[1].elapsed_time(e[2]) for e in ev]))
+    t_search = float(np.median([e[2].elapsed_time(e[3]) for e in ev]))
+    res = {"workload": "configs[1]: D=10000, F=617 fp32, L=64, C=26, 6238 train / 1559 test",
+           "steps": K, "ms_per_step": round(ms_per_step, 4),
+           "encoded_plus_trained_samples_per_s": round(ntr / (t_train * 1e-3), 1),
+           "queries_per_s": round(nte / (t_search * 1e-3), 1),
+           "stage_ms_median": {"encode_train_plus_train": round(t_train, 4), "encode_test": round(t_enc_s, 4),
+                               "search": round(t_search, 4)},
+           "test_accuracy": round(float((pred.cpu().numpy() == ys_h).mean()), 4)}
+    # The same step recorded once in a HIP graph and replayed (one submission per step).
     try:
-        text = open(path).read()
-    except OSError:
-        return None
-    import re
-    scale = {"FETCH_SIZE": 2.0, "WRITE_SIZE": 1.0}
-    m = re.search(r"FETCH_SIZE x ([0-9.]+), WRITE_SIZE x ([0-9.]+)", text)
-    if m:
-        scale = {"FETCH_SIZE": float(m.group(1)), "WRITE_SIZE": float(m.group(2))}
-    total = 0.0
-    for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
-        # one line per kernel instantiation: average over all launches of all of them
-        rows = re.findall(re.escape(kernel) + r"[^\n]*," + ctr + r",launches=(\d+),mean=([0-9.]+)", text)
-        if not rows:
-            return None
-        launches = sum(int(n) for n, _ in rows)
-        total += sum(int(n) * float(m) for n, m in rows) / launches * 1024.0 * scale[ctr]
-    return round(total, 1)
+        pred_eager = pred.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        torch.cuda.synchronize()
+        for _ in range(10):
+            graph.replay()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        g0.record()
+        for _ in range(K):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        res["step_replayed_from_hip_graph"] = {"ms_per_step": round(g0.elapsed_time(g1) / K, 4),
+                                               "same_predictions_as_eager": bool(torch.equal(pred, pred_eager))}
+    except RuntimeError as err:
+        res["step_replayed_from_hip_graph"] = {"error": str(err)[:200]}
+    ctx.close()
+    return {"cfg2_step": res}
 
 
 def _timed(torch, fn, reps):
@@ -314,8 +389,9 @@ def extras(torch, binding, make_workload):
     res["search_1M_C26"] = {"ms": round(ms, 4), "queries_per_s": round(N / ms * 1e3, 0),
                             "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),
                             "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4),
-                            "mfma_Pflops": round(2.0 * N * 32 * ctx.W * 32 / (ms * 1e-3) / 1e15, 3),
-                            "frac_mfma_fp4": round(2.0 * N * 32 * ctx.W * 32 / (ms * 1e-3) / 1e15 / 10.1, 4)}
+                            "mfma_Pflops": round(2.0 * N * 26 * wl5.D / (ms * 1e-3) / 1e15, 3),
+                            "frac_mfma_fp4": round(2.0 * N * 26 * wl5.D / (ms * 1e-3) / 1e15 / 10.1, 4),
+                            "note": "flops are the method's own 2 N C D (26 classes, 10000 dimensions)"}
     ctx26.close()
     del cls26
     ms = _timed(torch, lambda: ctx.hdc_train_classical(hv, y, acc, cn), 5)
@@ -351,6 +427,40 @@ def extras(torch, binding, make_workload):
                                       "2 flops per (feature, varying dimension) against the FP4 matrix peak"}
     ctx.close()
     del hv, y, pred, x5d, hv5
+    # --- config 2 shape at 65536 samples: the contraction encoder on a level table of Sec. III's
+    # construction, and the vector kernel on a level table without any structure (random bits:
+    # every dimension flips many times, nothing is level-invariant), the general case of Eq. (1)
+    wl2 = make_workload(2)
+    x2, _ = wl2.train(6238)
+    x2 = np.ascontiguousarray(np.tile(x2, (11, 1))[:65536])
+    x2d = torch.from_numpy(x2).to(dev)
+    ctx = binding.Context(wl2.D, wl2.F, wl2.L, wl2.C, wl2.item, wl2.level, wl2.tie, wl2.lo, wl2.scale, wl2.dtype)
+    hv2 = torch.empty((65536, ctx.W), dtype=torch.int32, device=dev)
+    ms = _timed(torch, lambda: ctx.hdc_encode(x2d, hv2), 3)
+    b2 = 4.0 * wl2.F + 4.0 * ctx.W
+    res["encode_64k_cfg2"] = {"ms": round(ms, 4), "samples_per_s": round(65536 / ms * 1e3, 0),
+                              "frac_mfma_fp4": round(2.0 * wl2.F * ctx.hdc_encoded_words() * 32 * 65536 / (ms * 1e-3)
+                                                     / 1e12 / MFMA_FP4_PEAK_TFLOPS, 4),
+                              "frac_hbm": round(b2 * 65536 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    ctx.close()
+    rng = np.random.default_rng(7)
+    level_rand = rng.integers(0, 2 ** 32, size=wl2.level.shape, dtype=np.uint64).astype(np.uint32)
+    level_rand[:, -1] &= np.uint32((1 << (wl2.D - 32 * (level_rand.shape[1] - 1))) - 1)
+    ctx = binding.Context(wl2.D, wl2.F, wl2.L, wl2.C, wl2.item, level_rand, wl2.tie, wl2.lo, wl2.scale, wl2.dtype)
+    ctx.hdc_profile_enable(True)
+    ms = _timed(torch, lambda: ctx.hdc_encode(x2d, hv2), 3)
+    k_ms, k_n = ctx.hdc_profile_read("encode")
+    ctx.hdc_profile_enable(False)
+    ops = 3.0 * wl2.F * ctx.hdc_encoded_words() * 65536
+    res["encode_generic_64k"] = {
+        "ms": round(ms, 4), "samples_per_s": round(65536 / ms * 1e3, 0),
+        "encode_kernel_us": round(k_ms * 1e3 / max(1, k_n), 1),
+        "frac_valu": round(ops / (k_ms * 1e-3 / max(1, k_n)) / 1e12 / VALU_PEAK_TOPS, 4) if k_n else None,
+        "words_bundled_of": [ctx.hdc_encoded_words(), ctx.W],
+        "note": "random level table (no structure): quantize_kernel + encode_kernel on the vector unit, "
+                "3 lane-ops per (feature, word) against 39.3 T lane-ops/s"}
+    ctx.close()
+    del x2d, hv2
     # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): hdc_encode
     # (all features; for this model the contraction on the matrix cores, 14 MFMA steps per tile)
     # against the call that bundles only the features that leave bin 0 (same bits out)
@@ -480,28 +590,47 @@ def extras(torch, binding, make_workload):
     return res
 
 
-def cpu_baseline(wl, xt_h, yt_h):
-    """The CPU oracle, as it stands, on a bounded prefix of the same train set (about 15 s)."""
+def _omp_threads(n: int) -> None:
+    """Sets the thread count of the OpenMP runtime the oracle's library uses (the oracle itself is
+    left as it stands)."""
+    import ctypes
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
+def cpu_baseline(wl):
+    """The CPU oracle, as it stands, on a bounded prefix of the same stream: encode + classical
+    training + binarise, then the search of the same windows; on all host cores (about 15 s) and
+    on one thread (about 8 s)."""
     import oracle
     oracle.build()
-    probe = 128
-    t = time.perf_counter()
-    oracle.encode(xt_h[:probe], wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
-    per = (time.perf_counter() - t) / probe
-    n = int(min(xt_h.shape[0], max(probe, 15.0 / max(per, 1e-9))))
-    t = time.perf_counter()
-    hv = oracle.encode(xt_h[:n], wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
-    acc, cn = oracle.train_classical(hv, yt_h[:n], wl.D, wl.C)
-    m = oracle.binarize_classical(acc, cn, wl.tie)
-    dt = time.perf_counter() - t
-    t = time.perf_counter()
-    oracle.search(hv, m, wl.D)
-    ds = time.perf_counter() - t
-    return {"value": round(n / dt, 1), "unit": "samples/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"first {n} of {xt_h.shape[0]} train samples of configs[1]: oracle encode + "
-                      f"train_classical + binarize ({dt:.1f} s); search of the same {n} rows: "
-                      f"{n / ds:.0f} queries/s",
-            "queries_per_s": round(n / ds, 1)}
+    cores = oracle.threads()
+
+    def run(n):
+        x, y = wl.train(n)
+        t = time.perf_counter()
+        hv = oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+        acc, cn = oracle.train_classical(hv, y, wl.D, wl.C)
+        m = oracle.binarize_classical(acc, cn, wl.tie)
+        dt = time.perf_counter() - t
+        t = time.perf_counter()
+        oracle.search(hv, m, wl.D)
+        return dt, time.perf_counter() - t
+    probe = 256
+    per = run(probe)[0] / probe
+    n_all = int(min(65536, max(probe, 15.0 / max(per, 1e-9))))
+    dt, ds = run(n_all)
+    _omp_threads(1)
+    try:
+        n_one = int(min(n_all, max(64, 8.0 / max(per * cores, 1e-9))))
+        dt1, ds1 = run(n_one)
+    finally:
+        _omp_threads(cores)
+    return {"value": round(n_all / dt, 1), "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n_all} of the 5,000,000 windows of configs[4]: oracle encode + train_classical + "
+                      f"binarize ({dt:.1f} s); search of the same windows: {n_all / ds:.0f} queries/s",
+            "queries_per_s": round(n_all / ds, 1),
+            "one_thread": {"value": round(n_one / dt1, 1), "queries_per_s": round(n_one / ds1, 1),
+                           "sample": f"first {n_one} windows, OpenMP limited to 1 thread ({dt1:.1f} s)"}}
 
 
 if __name__ == "__main__":
