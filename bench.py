@@ -159,7 +159,7 @@ def main() -> int:
     # events on the launch stream (hdc_profile_*).  Kept out of the region above because the
     # extra events hold the stream up between kernels.  The work is counted from the launches
     # that were actually timed.
-    kinds = ("encode", "encode_contract", "quantize", "accumulate", "search")
+    kinds = ("encode", "encode_contract", "encode_wide", "quantize", "accumulate", "search")
     ctx.hdc_profile_enable(True)
     for k in kinds:
         ctx.hdc_profile_read(k)
@@ -178,7 +178,11 @@ def main() -> int:
     Wk = ctx.hdc_encoded_words()
     Dv = 32 * Wk
     enc_bytes = 4.0 * wl.F + 4.0 * W
-    ct_ms, ct_n = prof["encode_contract"]
+    ct_ms, ct_n = prof["encode_wide"]
+    ct_name = "encode_wide_kernel (quantise + contraction + bit placement, one launch per chunk, jobs of 128 windows)"
+    if not ct_n:
+        ct_ms, ct_n = prof["encode_contract"]
+        ct_name = "encode_contract_kernel (quantise + contraction + bit placement, one launch per chunk)"
     en_ms, en_n = prof["encode"]
     if ct_n:
         assert ct_n == psteps * len(chunks), "timed launches of the encoder do not match the steps run"
@@ -187,7 +191,7 @@ def main() -> int:
         achieved = flops / (us * 1e-6) / 1e12
         gbs = enc_bytes * per_launch / (us * 1e-6) / 1e9
         roofline = {
-            "kernel": "encode_contract_kernel (quantise + contraction + bit placement, one launch per chunk)",
+            "kernel": ct_name,
             "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
             "traffic": None,

@@ -92,7 +92,8 @@ int hdc_destroy(hdc_ctx *ctx);
  * models of a thousand matrix instructions per 32 samples, e.g. 600 features at D = 10000) on a
  * model whose level vectors change every dimension at most once from one level to the next
  * (at most 256 levels, 4 to 896 features) run as a contraction over the features on the matrix
- * cores, all others on the vector unit.
+ * cores (long streams, 128 samples or more per compute unit, of models of at most about 370
+ * features in a form of their own), all others on the vector unit.
  */
 int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);
 
@@ -245,7 +246,8 @@ typedef enum {
     HDC_K_ONLINE_FWD = 5, /* partial dot products of hdc_train_online_batched */
     HDC_K_ONLINE_BWD = 6, /* batch sum + accumulator update of hdc_train_online_batched */
     HDC_K_ENCODE_CONTRACT = 7, /* the contraction form of hdc_encode (quantises, bundles and spreads in one kernel) */
-    HDC_K_COUNT = 8
+    HDC_K_ENCODE_WIDE = 8,     /* the contraction form of hdc_encode for long streams (jobs of 64 or 128 samples) */
+    HDC_K_COUNT = 9
 } hdc_kernel_id;
 #define HDC_PROFILE_SLOTS 512
 int hdc_profile_enable(hdc_ctx *ctx, int enable);

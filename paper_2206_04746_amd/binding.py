@@ -28,7 +28,7 @@ SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_encode_sparse", "hdc_
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
 KERNEL_IDS = {"encode": 0, "quantize": 1, "accumulate": 2, "online": 3, "search": 4,
-              "online_fwd": 5, "online_bwd": 6, "encode_contract": 7}
+              "online_fwd": 5, "online_bwd": 6, "encode_contract": 7, "encode_wide": 8}
 
 
 class HdcParams(ctypes.Structure):

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhdc.so")
-SOURCES = ["hdc_api.hip", "encode.hip", "encode_contract.hip", "encode_sparse.hip", "classical.hip", "online.hip", "online_batched.hip", "search.hip", "search_mfma.hip", "primitives.hip"]
+SOURCES = ["hdc_api.hip", "encode.hip", "encode_contract.hip", "encode_wide.hip", "encode_sparse.hip", "classical.hip", "online.hip", "online_batched.hip", "search.hip", "search_mfma.hip", "primitives.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -422,6 +422,7 @@ void launch_expand(hdc_ctx_impl *c, int64_t n, uint32_t *out, hipStream_t s) {
 int launch_encode(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
     {
         int rc = HDC_OK;
+        if (try_encode_wide(c, feats, N, hv, s, &rc)) return rc;
         if (try_encode_contract(c, feats, N, hv, s, &rc)) return rc;
     }
     int P;

@@ -1,0 +1,646 @@
+// ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features on the
+// matrix cores, for long streams of samples and models of at most 384 feature slots: the form of
+// encode_contract.hip rearranged so that the vector unit has less to do per matrix instruction.
+//
+// As there, a dimension d that flips once along the levels, at level t_d, gets from feature f the
+// vote B[f][d] ^ [q_f >= t_d] with B = item ^ level[0], and with U_f = [q_f >= t_d]
+//     count[d] = sum_f B[f][d] - sum_f U_f (2 B[f][d] - 1).
+// The second sum is a dot product of a 0/1 vector with a +-1 vector: on 4-bit floats the sample
+// side is a nibble with one bit set (0.5, 1 or 2, the bits of U in place), the model side is
+// the reciprocal of that with the sign of 2 B - 1, every product is +-1 and the fp32 sums are
+// exact.  What the vote threshold and the constant sum_f B need is added by the contraction
+// itself: the feature slots between F and the next multiple of 64 are given U = 1 for every
+// sample (their bin number is all ones) and model-side values that add up to -(K_d + 1/2),
+// K_d = sum_f B[f][d] + tie_d - ceil(votes / 2).  The accumulators start at zero (an inline
+// constant of the instruction) and the encoded bit is their sign: no per-sample count of U, no
+// start values, no compare.
+//
+// A block of eight waves takes a job of G groups of 32 samples (G = 4, or 2 where the LDS does not
+// hold four), a job after the other:
+//   Q  it loads and quantises the job (cache hits: the lines were touched while the previous
+//      job's rows were written), leaves the bin numbers in LDS a byte each, and turns them into
+//      bit planes over the features, [group][step] of 64 lanes x NB words, in LDS;
+//   T  a wave takes a threshold and up to three tiles of 32 of its dimensions at a time.  The
+//      tiles' model-side operands come ready-made from memory, 16 bytes a lane (L2 hits: every
+//      block reads the same table), and stay in registers for the G groups.  Per group and step of
+//      64 features the wave reads the planes, forms [q >= t] with one 3-input bit operation per
+//      plane and the four operand words with five more instructions, and issues three matrix
+//      instructions: 11 vector instructions per 3 matrix instructions, against 19 per matrix
+//      instruction in encode_contract.hip.  The signs of a lane's 16 accumulators, strung
+//      together, are the word "dimension x 16 samples", left in LDS;
+//   P  a wave places 64 words of a group's 32 rows at a time: a lane collects the 32 words of
+//      its row word (a table names the column of every bit; constant bits of the model point at
+//      an all-zero or all-one word), transposes 32 x 32 bits in registers and writes the word
+//      of the 32 rows.
+// What bounds it (measured with clock stamps per phase, 342 features, 128 samples a job): T takes
+// 38 us of a job's 60, the matrix instructions alone 20 (32 clocks each, one at a time per SIMD,
+// whatever the number of accumulators in flight) and the vector instructions 18: a wave issues
+// in order, so its own two kinds never overlap, and its SIMD partner fills only part of the
+// gaps.  Finely interleaved streams overlap up to about six vector instructions per matrix
+// instruction; here there are 7.4 and they come in runs.
+#include "hdc_internal.h"
+
+#include <algorithm>
+#include <cstdlib>
+#include <type_traits>
+#include <vector>
+
+namespace hdc {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t wd_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t wd_u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t wd_u32x6 __attribute__((ext_vector_type(6)));
+typedef uint32_t wd_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a global load of 16 bytes at any word
+
+constexpr int kWdWaves = 8, kWdThreads = kWdWaves * kWave;   // two waves per SIMD, 256 registers each
+constexpr int kWdTiles = 3;          // tiles of one threshold a wave works on at a time: their model-side operands stay in registers
+// Matrix instructions per tile, 64 features each.  Beyond 6 the resident operands of three tiles
+// (12 registers a step) no longer fit beside the accumulators, and with fewer tiles per turn the
+// vector work per matrix instruction is that of encode_contract.hip again, which such models take.
+constexpr int kWdMaxSteps = 6;
+constexpr size_t kWdLdsLimit = 160 * 1024;
+
+// ---- host: tables of the model ----------------------------------------------------------------
+// 4-bit float (1 sign, 2 exponent, 1 mantissa bit) of a value it can hold exactly
+static uint32_t fp4_of(float v) {
+    const uint32_t s = v < 0.0f ? 8u : 0u;
+    const float a = v < 0.0f ? -v : v;
+    const float mags[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    for (uint32_t i = 0; i < 8; ++i)
+        if (mags[i] == a) return s | i;
+    return 0u;   // never asked for
+}
+
+// Where feature f of a step sits on both sides of the contraction: the kernel turns 32 bin numbers
+// (bytes, four to a word) into bit planes with three rounds of masked swaps among eight words,
+// which leaves feature 4 m + i of a lane's 32 at bit 8 i + m: operand word (bit & 3), nibble (bit >> 2).
+static inline int wd_feature_bit(int f) { return 8 * (f & 3) + ((f & 31) >> 2); }
+// the value the sample side has at that place when U = 1
+static inline float wd_sample_value(int f) {
+    const float v[4] = {0.5f, 1.0f, 2.0f, 2.0f};
+    return v[wd_feature_bit(f) & 3];
+}
+
+template <typename T>
+static int wd_upload(T **dst, const std::vector<T> &src) {
+    void *ptr = nullptr;
+    hipError_t e = hipMalloc(&ptr, src.size() * sizeof(T) + 256);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return HDC_ENOMEM;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    *dst = reinterpret_cast<T *>(ptr);
+    e = hipMemcpy(ptr, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+    return e == hipSuccess ? HDC_OK : hip_fail(e, "hipMemcpy");
+}
+
+// Model-side values of the feature slots past F that add up to a target (a multiple of 1/2) when
+// every such slot has U = 1.  Which sums the slots can reach is worked out once per model, slot
+// after slot (in halves; a slot's sample-side value times each 4-bit float that gives a multiple
+// of 1/2); a dimension's values are then read off backwards from its target.
+struct WdBias {
+    int F = 0, slots = 0, bound = 0;
+    std::vector<std::vector<uint8_t>> reach;   // [slot count][sum + bound]: reachable with the first slots
+    static constexpr float kMags[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    void prepare(int F_, int slots_end, int max_halves) {
+        F = F_, slots = slots_end - F_, bound = max_halves;
+        reach.assign((size_t)slots + 1, std::vector<uint8_t>((size_t)2 * bound + 1, 0));
+        reach[0][(size_t)bound] = 1;
+        for (int i = 0; i < slots; ++i) {
+            const float a = wd_sample_value(F + i);
+            for (int sum = -bound; sum <= bound; ++sum) {
+                if (!reach[(size_t)i][(size_t)(sum + bound)]) continue;
+                for (float m : kMags)
+                    for (int sg = -1; sg <= 1; sg += 2) {
+                        const float c2 = 2.0f * a * m * (float)sg;   // the slot's contribution in halves
+                        if (c2 != (float)(int)c2) continue;
+                        const int to = sum + (int)c2;
+                        if (to >= -bound && to <= bound) reach[(size_t)i + 1][(size_t)(to + bound)] = 1;
+                    }
+            }
+        }
+    }
+    // false if the slots cannot make the target
+    bool solve(int target_halves, std::vector<float> &val) const {
+        val.assign((size_t)slots, 0.0f);
+        if (target_halves < -bound || target_halves > bound || !reach[(size_t)slots][(size_t)(target_halves + bound)]) return false;
+        int sum = target_halves;
+        for (int i = slots - 1; i >= 0; --i) {
+            const float a = wd_sample_value(F + i);
+            bool found = false;
+            for (int mi = 0; mi < 8 && !found; ++mi)
+                for (int sg = -1; sg <= 1 && !found; sg += 2) {
+                    const float c2 = 2.0f * a * kMags[mi] * (float)sg;
+                    if (c2 != (float)(int)c2) continue;
+                    const int from = sum - (int)c2;
+                    if (from >= -bound && from <= bound && reach[(size_t)i][(size_t)(from + bound)]) {
+                        val[(size_t)i] = kMags[mi] * (float)sg;
+                        sum = from;
+                        found = true;
+                    }
+                }
+            if (!found) return false;   // (never: reach says otherwise)
+        }
+        return sum == 0;
+    }
+};
+
+size_t wide_lds_bytes(int steps, int nb, int groups, int ovs) {
+    const size_t planes = (size_t)groups * steps * kWave * (16 + (nb > 6 ? 16 : 8));
+    const size_t over = (size_t)groups * ovs * 4;
+    const size_t bins = (size_t)groups * 32 * (steps * 64 + 16);
+    return planes + std::max(over, bins);
+}
+
+// Leaves c->wd_ready false when the model is not of the kernel's shape; only a failed allocation
+// or copy is an error.  Needs c->expand_d (the constant bits of the level-invariant dimensions).
+int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie) {
+    const hdc_params &p = c->p;
+    const int W = c->W, F = p.F, L = p.L;
+    c->wd_ready = false;
+    if (!c->compact || L < 2 || L > 256 || F < 4 || F > 64 * kWdMaxSteps || W > 512) return HDC_OK;
+    const int thr = (c->votes + 1) / 2;
+    const bool tie_votes = c->votes != F;
+
+    // threshold of every varying dimension; a dimension that flips twice rules the model out
+    std::vector<std::vector<int>> by_tau((size_t)L);
+    int64_t varying = 0;
+    for (int d = 0; d < p.D; ++d) {
+        const int w = d >> 5, b = d & 31;
+        const uint32_t first = (level[w] >> b) & 1u;
+        int tau = 0;
+        for (int l = 1; l < L; ++l) {
+            const uint32_t bit = (level[(size_t)l * W + w] >> b) & 1u;
+            if (!tau && bit != first) tau = l;
+            else if (tau && bit == first) return HDC_OK;
+        }
+        if (tau) by_tau[(size_t)tau].push_back(d), ++varying;
+    }
+    if (!varying) return HDC_OK;
+
+    // K_d of every varying dimension and the most slots any of them needs
+    std::vector<int> ones((size_t)p.D, 0);
+    for (int f = 0; f < F; ++f)
+        for (int d = 0; d < p.D; ++d)
+            ones[(size_t)d] += (int)(((item[(size_t)f * W + (d >> 5)] ^ level[d >> 5]) >> (d & 31)) & 1u);
+    auto target_of = [&](int d) {   // in halves: -(2 K_d + 1); the bit is set iff sum_f U (2B - 1) <= K_d
+        const int tie_vote = tie_votes ? (int)((tie[d >> 5] >> (d & 31)) & 1u) : 0;
+        return -(2 * (ones[(size_t)d] + tie_vote - thr) + 1);
+    };
+    int max_halves = 0;
+    for (int tau = 1; tau < L; ++tau)
+        for (int d : by_tau[(size_t)tau]) max_halves = std::max(max_halves, std::abs(target_of(d)));
+    int steps = 0;
+    std::vector<float> val;
+    WdBias bias;
+    for (int ks = ((F + 63) / 64 + 1) / 2 * 2; ks <= kWdMaxSteps && !steps; ks += 2) {   // the kernel is built for even counts
+        if (ks * 64 == F) continue;
+        bias.prepare(F, ks * 64, max_halves);
+        bool ok = true;
+        for (int tau = 1; tau < L && ok; ++tau)
+            for (int d : by_tau[(size_t)tau])
+                if (!bias.solve(target_of(d), val)) {
+                    ok = false;
+                    break;
+                }
+        if (ok) steps = ks;
+    }
+    if (!steps) return HDC_OK;
+    const int nb = L <= 64 ? 6 : 8;
+
+    // work items: a threshold and up to three tiles of its dimensions; columns of `over` in item order
+    std::vector<int32_t> items;          // [n][4]: threshold, first tile, dimensions, first column
+    std::vector<uint32_t> bx;            // [tile][step][lane][4]
+    std::vector<uint32_t> src((size_t)32 * W, 0u);
+    int tiles = 0, cols = 0;
+    for (int tau = 1; tau < L; ++tau) {
+        const std::vector<int> &dims = by_tau[(size_t)tau];
+        for (size_t at = 0; at < dims.size(); at += 32 * kWdTiles) {
+            const int nd = (int)std::min<size_t>(dims.size() - at, 32 * kWdTiles);
+            const int nt = (nd + 31) / 32;
+            items.insert(items.end(), {tau, tiles, nd, cols});
+            bx.resize((size_t)(tiles + nt) * steps * 64 * 4, 0u);
+            for (int i = 0; i < nd; ++i) {
+                const int d = dims[at + i], w = d >> 5, b = d & 31, t = tiles + i / 32, j = i & 31;
+                const uint32_t l0 = (level[w] >> b) & 1u;
+                src[(size_t)b * W + w] = (uint32_t)(cols + i);
+                if (!bias.solve(target_of(d), val)) return HDC_OK;   // (checked above)
+                for (int f = 0; f < steps * 64; ++f) {
+                    uint32_t nib;
+                    if (f < F) {
+                        const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
+                        nib = fp4_of((bit ? 1.0f : -1.0f) / wd_sample_value(f));
+                    } else {
+                        nib = fp4_of(val[(size_t)(f - F)]);
+                    }
+                    const int k = f >> 6, h = (f >> 5) & 1, at_bit = wd_feature_bit(f);
+                    bx[(((size_t)t * steps + k) * 64 + h * 32 + j) * 4 + (at_bit & 3)] |= nib << (4 * (at_bit >> 2));
+                }
+            }
+            tiles += nt;
+            cols += nd;
+        }
+    }
+    // constant bits of the model: the all-zero word at column `cols`, the all-one word after it
+    const uint32_t *const_row = nullptr;
+    std::vector<uint32_t> tab((size_t)W);
+    {
+        hipError_t e = hipMemcpy(tab.data(), c->expand_d + (size_t)7 * W, (size_t)W * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+        const_row = tab.data();
+    }
+    std::vector<uint8_t> is_var((size_t)p.D, 0);
+    for (int tau = 1; tau < L; ++tau)
+        for (int d : by_tau[(size_t)tau]) is_var[(size_t)d] = 1;
+    for (int w = 0; w < W; ++w)
+        for (int b = 0; b < 32; ++b) {
+            const int d = 32 * w + b;
+            if (d < p.D && is_var[(size_t)d]) continue;
+            src[(size_t)b * W + w] = (uint32_t)(cols + (int)((const_row[w] >> b) & 1u));
+        }
+    const int ovs = cols + 2;
+    int groups = 0;
+    for (int g : {4, 2})
+        if (!groups && wide_lds_bytes(steps, nb, g, ovs) + 64 <= kWdLdsLimit) groups = g;
+    if (!groups) return HDC_OK;
+
+    if (ovs > 65535) return HDC_OK;   // (the kernel's table holds column numbers in 16 bits; the LDS limit is far below)
+    std::vector<uint32_t> src2((size_t)16 * W);   // [bit / 2][word]: the columns of bits 2 i and 2 i + 1
+    for (int i = 0; i < 16; ++i)
+        for (int w = 0; w < W; ++w) src2[(size_t)i * W + w] = src[(size_t)(2 * i) * W + w] | (src[(size_t)(2 * i + 1) * W + w] << 16);
+    int rc = wd_upload(&c->wd_items_d, items);
+    if (rc == HDC_OK) rc = wd_upload(&c->wd_bx_d, bx);
+    if (rc == HDC_OK) rc = wd_upload(&c->wd_src_d, src2);
+    if (rc != HDC_OK) return rc;
+    c->wd_steps = steps;
+    c->wd_nb = nb;
+    c->wd_groups = groups;
+    c->wd_items = (int)(items.size() / 4);
+    c->wd_ovs = ovs;
+    c->wd_ready = true;
+    return HDC_OK;
+}
+
+// Both operands as 4-bit floats (format code 4), no block scales; 16 bytes of each are used.
+__device__ __forceinline__ v16f wd_mfma(v4i a, wd_u32x4 b, v16f c) {
+    const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
+    const v8i b8 = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
+}
+
+
+// Dynamic LDS: the planes [G * KS][64 lanes] of 16 bytes (planes 0..3), then of 8 or 16 bytes (planes
+// 4..), then a region that holds first the job's bin numbers, a byte each, [sample][KS * 64 + 16]
+// (the 16 spread the rows over the banks), and later per group and column the bits of the
+// group's 32 samples, [G][ovs] words, the last two of each group all zeros and all ones.
+template <int KS, int NB, bool kU8, int G>
+__global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
+    const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
+    const float *__restrict__ scale, int W, const int4 *__restrict__ items, int n_items,
+    const wd_u32x4 *__restrict__ bx, const uint32_t *__restrict__ src_of, int ovs, uint32_t *__restrict__ hv) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t wd_lds[];
+    constexpr int kSamples = 32 * G;
+    constexpr int kQuads = KS * 16;                              // groups of four features per sample row, pad slots included
+    constexpr int kPerRound = kWdThreads / kQuads;               // samples the block loads at a time
+    constexpr int kRounds = (kSamples + kPerRound - 1) / kPerRound;
+    constexpr int kRowBytes = KS * 64 + 16;
+    constexpr int kRawRegs = kU8 ? 1 : 4;
+    constexpr int kTouches = (kSamples * KS * 64 * (kU8 ? 1 : 4) / 128 + kWdThreads - 1) / kWdThreads;   // 128-byte lines of a job's features per thread
+    constexpr int TB = kWdTiles;
+    wd_u32x4 *planes_a = reinterpret_cast<wd_u32x4 *>(wd_lds);
+    typedef typename std::conditional<(NB > 6), wd_u32x4, wd_u32x2>::type plane_b_t;
+    plane_b_t *planes_b = reinterpret_cast<plane_b_t *>(wd_lds + G * KS * kWave * 4);
+    uint32_t *over = wd_lds + G * KS * kWave * (4 + (NB > 6 ? 4 : 2));
+    uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
+    const uint8_t *bins = reinterpret_cast<const uint8_t *>(over);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int j = lane & 31, h = lane >> 5;
+
+    wd_u32x4 bm[TB][KS];
+    const int64_t jobs = (N + kSamples - 1) / kSamples;
+    for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
+        // ---- Q: bin numbers, a byte each; slots past F get all ones (U = 1 at every threshold).
+        // A thread takes four neighbouring features (the same in every round) of kPerRound samples
+        // a round, all rounds in flight together (cache hits but for a block's first job: the lines
+        // were asked for while the previous job's rows were written).  Every thread loads in every
+        // round (those without a feature or a sample of their own: something that exists).
+        {
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));   // (opaque: what follows is worked out per job, not kept in registers across the phases)
+            const int f0 = 4 * (tid % kQuads), s_in = tid / kQuads;
+            const bool feats_mine = f0 < F;                               // (slots past F are not features)
+            const int fq = min(f0, F - 4);                                // what it loads: four features that exist
+            const int q_shift = 8 * min(max(f0 - fq, 0), 3);              // where its own first feature's bin number is in them
+            uint32_t keep = 0;                                            // the bytes of its word that are features
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (f0 + i < F) keep |= 0xffu << (8 * i);
+            const int64_t first = job * kSamples;
+            const int last = (int)min((int64_t)(kSamples - 1), N - 1 - first);   // (rows past N: the last row)
+            const uint8_t *base = reinterpret_cast<const uint8_t *>(feats) + first * F * (kU8 ? 1 : 4);
+            uint32_t raw[kRounds][kRawRegs];
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                const int sn = min(r * kPerRound + s_in, last);
+                if (kU8) {
+                    const uint8_t *row = base + (sn * F + fq);
+                    raw[r][0] = (uint32_t)row[0] | ((uint32_t)row[1] << 8) | ((uint32_t)row[2] << 16) | ((uint32_t)row[3] << 24);
+                } else {
+                    const wd_u32x4_a4 v = *reinterpret_cast<const wd_u32x4_a4 *>(base + (size_t)(uint32_t)((sn * F + fq) * 4));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) raw[r][i] = v[i];
+                }
+            }
+            float lo_f[4], sc_f[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo_f[i] = kU8 ? 0.0f : lo[fq + i];
+                sc_f[i] = kU8 ? 0.0f : scale[fq + i];
+            }
+            if (s_in < kPerRound) {
+#pragma unroll
+                for (int r = 0; r < kRounds; ++r) {
+                    const int sn = r * kPerRound + s_in;
+                    uint32_t word = 0;
+                    if (feats_mine) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            uint32_t q;
+                            if (kU8) {
+                                q = (((raw[r][0] >> (8 * i)) & 0xffu) * (uint32_t)L) >> 8;
+                            } else {   // the bin rule without its branches: NaN and negatives go to 0 through the maximum
+                                const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[r][i]), lo_f[i]), sc_f[i]);
+                                q = (uint32_t)(int)fminf(fmaxf(t, 0.0f), (float)(L - 1));
+                            }
+                            word |= q << (8 * i);
+                        }
+                        word = (word >> q_shift) & keep;
+                    }
+                    if (sn < kSamples) over[(sn * kRowBytes + f0) >> 2] = word | ~keep;
+                }
+            }
+        }
+        __syncthreads();
+        // The bin numbers as bit planes over the features: lane (sample j, half h) reads its 32 bytes of
+        // step k of group g and moves bit b of byte i of word m to bit 8 i + m of plane b (word index
+        // and bit index trade three of their bits, one per round).
+#pragma unroll 1
+        for (int task = wave; task < G * KS; task += kWdWaves) {
+            const int g = task / KS, k = task - g * KS;
+            const wd_u32x4 *from = reinterpret_cast<const wd_u32x4 *>(bins + (g * 32 + j) * kRowBytes + k * 64 + h * 32);
+            const wd_u32x4 v0 = from[0], v1 = from[1];
+            uint32_t x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+#pragma unroll
+            for (int stage = 0; stage < 3; ++stage) {
+                const int sh = 1 << stage;
+                const uint32_t m = stage == 0 ? 0x55555555u : stage == 1 ? 0x33333333u : 0x0f0f0f0fu;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if ((i & sh) == 0) {
+                        const uint32_t a = x[i], b = x[i + sh];
+                        x[i] = (a & m) | ((b << sh) & ~m);
+                        x[i + sh] = ((a >> sh) & m) | (b & ~m);
+                    }
+            }
+            planes_a[task * kWave + lane] = wd_u32x4{x[0], x[1], x[2], x[3]};
+            if constexpr (NB > 6) planes_b[task * kWave + lane] = wd_u32x4{x[4], x[5], x[6], x[7]};
+            else planes_b[task * kWave + lane] = wd_u32x2{x[4], x[5]};
+        }
+        __syncthreads();
+        if (threadIdx.x < 2 * G) over[(threadIdx.x >> 1) * ovs + ovs - 2 + (threadIdx.x & 1)] = (threadIdx.x & 1) ? 0xffffffffu : 0u;
+
+        // ---- T: a threshold and up to TB tiles of its dimensions per wave and turn.  The tiles'
+        // model-side operands stay in registers for the G groups; while the last group is worked
+        // on, each is replaced by the next item's as soon as its instruction has been issued.
+        {
+            int it = wave;
+            int4 item = items[min(it, n_items - 1)];
+            if (it < n_items) {
+                const int tile0 = __builtin_amdgcn_readfirstlane(item.y), nt = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
+#pragma unroll
+                for (int t = 0; t < TB; ++t)
+#pragma unroll
+                    for (int k = 0; k < KS; ++k) bm[t][k] = bx[((size_t)(tile0 + min(t, nt - 1)) * KS + k) * kWave + lane];
+            }
+#pragma unroll 1
+            for (; it < n_items; it += kWdWaves) {
+                const int tau = __builtin_amdgcn_readfirstlane(item.x);
+                const int nd = __builtin_amdgcn_readfirstlane(item.z), col0 = __builtin_amdgcn_readfirstlane(item.w);
+                const int nt = (nd + 31) >> 5;
+                item = items[it + kWdWaves < n_items ? it + kWdWaves : it];   // (after the wave's last item: the same again, unused)
+                const int tile0_n = __builtin_amdgcn_readfirstlane(item.y), nt_n = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
+                const wd_u32x4 *bn[TB];
+#pragma unroll
+                for (int t = 0; t < TB; ++t) bn[t] = bx + (size_t)(tile0_n + min(t, nt_n - 1)) * KS * kWave + lane;
+                uint32_t tb[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) tb[b] = (tau >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
+                wd_u32x4 pa = planes_a[lane];
+                plane_b_t pb = planes_b[lane];
+                // One group of 32 samples against the item's NT tiles (a constant here: no branch in the
+                // loop); the last group also fetches the next item's operands, each as soon as its
+                // last instruction has been issued.
+                auto group = [&](const int g, auto nt_c, auto last_c) {
+                    constexpr int NT = decltype(nt_c)::value;
+                    constexpr bool kLast = decltype(last_c)::value;
+                    v16f acc[NT];
+                    const wd_u32x4 *pa_at = planes_a + (kLast ? 0 : (g + 1) * KS * kWave) + lane;   // where the planes after this group's are
+                    const plane_b_t *pb_at = planes_b + (kLast ? 0 : (g + 1) * KS * kWave) + lane;
+                    const wd_u32x4 *pa_in = planes_a + g * KS * kWave + lane;
+                    const plane_b_t *pb_in = planes_b + g * KS * kWave + lane;
+#pragma unroll
+                    for (int k = 0; k < KS; ++k) {
+                        // the samples' [q >= tau] over the lane's 32 features, from the least significant plane up
+                        uint32_t qp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], 0u, 0u};
+                        if constexpr (NB > 6) qp[6] = pb[2], qp[7] = pb[3];
+                        if (k + 1 < KS) {   // the next turn's planes
+                            pa = pa_in[(k + 1) * kWave];
+                            pb = pb_in[(k + 1) * kWave];
+                        } else {
+                            pa = pa_at[0];
+                            pb = pb_at[0];
+                        }
+                        uint32_t ge = 0xffffffffu;
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) ge = __builtin_amdgcn_bitop3_b32(qp[b], ge, tb[b], 0xD4);   // tb ? q & ge : q | ge
+                        const v4i a = {(int)(ge & 0x11111111u), (int)(ge & 0x22222222u), (int)(ge & 0x44444444u),
+                                       (int)((ge >> 1) & 0x44444444u)};
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            if (k == 0) acc[t] = wd_mfma(a, bm[t][k], v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0});
+                            else acc[t] = wd_mfma(a, bm[t][k], acc[t]);
+                        }
+                        if constexpr (kLast) {
+#pragma unroll
+                            for (int t = 0; t < TB; ++t) bm[t][k] = bn[t][k * kWave];
+                        }
+                    }
+                    // the signs, register 0's highest: bit p of a half word is the sample of register 15 - p
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        uint32_t bits = 0;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float d = acc[t][r];
+                            bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
+                        }
+                        if (32 * t + j < nd) over16[(size_t)(g * ovs + col0 + 32 * t + j) * 2 + h] = (uint16_t)bits;
+                    }
+                };
+                auto run = [&](auto nt_c) {
+#pragma unroll 1
+                    for (int g = 0; g < G - 1; ++g) group(g, nt_c, std::false_type{});
+                    group(G - 1, nt_c, std::true_type{});
+                };
+                if (nt == 1) run(std::integral_constant<int, 1>{});
+                else if (nt == 2) run(std::integral_constant<int, 2>{});
+                else run(std::integral_constant<int, TB>{});
+            }
+        }
+        __syncthreads();
+
+        // ---- P: a wave places 64 words of a group's 32 rows at a time: lane l, word w = 64 c + l, reads
+        // the 32 entries of `over` that its table names (asked for a chunk ahead), transposes 32 x 32
+        // bits in registers and writes word w of the 32 rows.  Wave v takes group v % G and every
+        // (waves / G)-th chunk of 64 words, which gives each SIMD the same number of chunks.  The next
+        // job's features are asked for here (a word of every 128 bytes), so that they are in the
+        // cache when the job starts.
+        {
+            const int64_t first = job * kSamples;
+            constexpr int kChunkStep = kWdWaves / G;
+            int lane_p = lane;
+            asm volatile("" : "+v"(lane_p));   // (opaque: the offsets below are worked out per job, not kept in registers across the phases)
+            const int g = wave % G;
+            const int chunks = (W + kWave - 1) / kWave;
+            constexpr int kMaxChunks = (8 + kChunkStep - 1) / kChunkStep;   // rows of up to 512 words (the host sees to that)
+            uint32_t from[kMaxChunks][16];   // all of the wave's table entries first: nothing else is in flight yet
+            uint32_t touched = 0;
+#pragma unroll
+            for (int ci = 0; ci < kMaxChunks; ++ci) {
+                // (a uniform base and a 32-bit offset per lane: no 64-bit address per load to keep)
+                const uint32_t off = 4u * (uint32_t)min((wave / G + ci * kChunkStep) * kWave + lane_p, W - 1);
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    from[ci][i] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(src_of + (size_t)i * W) + off);
+            }
+            {
+                const int64_t nj = min(job + (int64_t)gridDim.x, jobs - 1);   // (after the last job: once more)
+                const uint32_t *base = reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(feats) + nj * kSamples * F * (kU8 ? 1 : 4));
+                const int64_t words = (min((int64_t)kSamples, N - nj * kSamples) * F * (kU8 ? 1 : 4)) >> 2;
+                const int64_t lines = (words + 31) >> 5;
+#pragma unroll
+                for (int i = 0; i < kTouches; ++i) {
+                    const int64_t at = min((int64_t)(threadIdx.x + i * kWdThreads), lines - 1) * 32;
+                    touched ^= base[min(at, words - 1)];
+                }
+            }
+            const bool whole = first + kSamples <= N;   // block-uniform: no row of the job is past N
+#pragma unroll
+            for (int ci = 0; ci < kMaxChunks; ++ci) {
+                const int c = wave / G + ci * kChunkStep;
+                if (c >= chunks) break;   // wave-uniform
+                const int w = min(c * kWave + lane_p, W - 1);
+                uint32_t x[32];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    x[2 * i] = over[g * ovs + (from[ci][i] & 0xffffu)];
+                    x[2 * i + 1] = over[g * ovs + (from[ci][i] >> 16)];
+                }
+                // x[b] bit p  ->  x[p] bit b: halves and bytes trade places by byte permutes, the finer
+                // stages by masked merges
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t lo = x[i], hi = x[i + 16];
+                    x[i] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                    x[i + 16] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+                }
+#pragma unroll
+                for (int i = 0; i < 32; ++i)
+                    if ((i & 8) == 0) {
+                        const uint32_t lo = x[i], hi = x[i + 8];
+                        x[i] = __builtin_amdgcn_perm(hi, lo, 0x06020400u);
+                        x[i + 8] = __builtin_amdgcn_perm(hi, lo, 0x07030501u);
+                    }
+#pragma unroll
+                for (int stage = 2; stage < 5; ++stage) {
+                    const int k = 16 >> stage;
+                    const uint32_t m = stage == 2 ? 0x0f0f0f0fu : stage == 3 ? 0x33333333u : 0x55555555u;
+#pragma unroll
+                    for (int i = 0; i < 32; ++i)
+                        if ((i & k) == 0) {
+                            const uint32_t lo = x[i], hi = x[i + k];
+                            x[i] = (lo & m) | ((hi << k) & ~m);
+                            x[i + k] = ((lo >> k) & m) | (hi & ~m);
+                        }
+                }
+                // bit p of a word of `over` is the sample of register 15 - p of lane half 0 (p < 16) or
+                // register 31 - p of half 1; register r of half h is sample 8 (r / 4) + 4 h + r % 4 of the group
+                if (c * kWave + lane_p < W) {
+                    uint8_t *out = reinterpret_cast<uint8_t *>(hv + (first + 32 * g) * W);   // wave-uniform
+#pragma unroll
+                    for (int p = 0; p < 32; ++p) {
+                        const int r = p < 16 ? 15 - p : 31 - p;
+                        const int sn = 8 * (r >> 2) + (p < 16 ? 0 : 4) + (r & 3);
+                        if (whole || first + 32 * g + sn < N) *reinterpret_cast<uint32_t *>(out + 4u * (uint32_t)(sn * W + w)) = x[p];
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);   // (a chunk after the other: their registers are the same)
+            }
+            if (touched == 0x9e3779b9u && N < 0) hv[0] = touched;   // (never: keeps the loads above)
+        }
+        __syncthreads();
+    }
+}
+
+template <int KS, int NB, bool kU8, int G>
+static int launch_wide(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
+    auto kern = encode_wide_kernel<KS, NB, kU8, G>;
+    const size_t lds = wide_lds_bytes(KS, NB, G, c->wd_ovs);
+    if (lds > 64 * 1024)
+        HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+    const int64_t jobs = (n + 32 * G - 1) / (32 * G);
+    const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kWdThreads), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
+                       c->scale_d, c->W, reinterpret_cast<const int4 *>(c->wd_items_d), c->wd_items,
+                       reinterpret_cast<const wd_u32x4 *>(c->wd_bx_d), c->wd_src_d, c->wd_ovs, out);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
+template <int NB, bool kU8, int G>
+static int launch_wide_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
+    switch (c->wd_steps) {
+    case 2: return launch_wide<2, NB, kU8, G>(c, x, n, out, s);
+    case 4: return launch_wide<4, NB, kU8, G>(c, x, n, out, s);
+    default: return launch_wide<6, NB, kU8, G>(c, x, n, out, s);
+    }
+}
+
+// The kernel is taken when the jobs of 32 G samples fill the chip's blocks, which work through
+// their jobs one after the other, to seven tenths at least (so from one job per compute unit on;
+// 1.2 jobs per unit would be two rounds for the price of 1.2).
+bool try_encode_wide(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc) {
+    if (!c->wd_ready) return false;
+    const int64_t jobs = (N + 32 * c->wd_groups - 1) / (32 * c->wd_groups);
+    const int64_t rounds = (jobs + c->num_cus - 1) / c->num_cus;
+    if (jobs < c->num_cus || jobs * 10 < rounds * c->num_cus * 7) return false;
+    ProfScope prof(c, HDC_K_ENCODE_WIDE, s);
+    const bool u8 = c->p.feat_dtype == HDC_U8;
+    if (c->wd_groups == 4) {
+        if (c->wd_nb == 6) *rc = u8 ? launch_wide_steps<6, true, 4>(c, feats, N, hv, s) : launch_wide_steps<6, false, 4>(c, feats, N, hv, s);
+        else *rc = u8 ? launch_wide_steps<8, true, 4>(c, feats, N, hv, s) : launch_wide_steps<8, false, 4>(c, feats, N, hv, s);
+    } else {
+        if (c->wd_nb == 6) *rc = u8 ? launch_wide_steps<6, true, 2>(c, feats, N, hv, s) : launch_wide_steps<6, false, 2>(c, feats, N, hv, s);
+        else *rc = u8 ? launch_wide_steps<8, true, 2>(c, feats, N, hv, s) : launch_wide_steps<8, false, 2>(c, feats, N, hv, s);
+    }
+    return true;
+}
+
+}  // namespace hdc
+

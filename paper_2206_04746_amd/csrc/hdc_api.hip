@@ -32,7 +32,8 @@ static void free_ctx(hdc_ctx_impl *c) {
                     c->sp_b_d, c->sp_e_d, c->sp_base_d, c->sp_fb_d, c->sp_blocks_d,
                     c->ct_tau_d[0], c->ct_col_d[0], c->ct_k_d[0], c->ct_bt_d[0],
                     c->ct_tau_d[1], c->ct_col_d[1], c->ct_k_d[1], c->ct_bt_d[1],
-                    c->ct_tau_d[2], c->ct_col_d[2], c->ct_k_d[2], c->ct_bt_d[2]};
+                    c->ct_tau_d[2], c->ct_col_d[2], c->ct_k_d[2], c->ct_bt_d[2],
+                    c->wd_items_d, c->wd_bx_d, c->wd_src_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -280,6 +281,7 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     try {
         TRY(prepare_compact(c, item, level, tie));
         TRY(prepare_contract(c, item, level, tie));
+        TRY(prepare_wide(c, item, level, tie));
     } catch (const std::bad_alloc &) {
         rc = HDC_ENOMEM;
     }

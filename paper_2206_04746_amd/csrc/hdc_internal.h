@@ -111,6 +111,16 @@ struct hdc_ctx_impl {
     float *ct_k_d[3];           // [tiles][32] the column's vote threshold, constants folded in
     uint32_t *ct_bt_d[3];       // [tiles][steps][64] item ^ level 0 along the features, per column and lane half (nibbles reversed)
 
+    // The same contraction for long streams (encode_wide.hip): jobs of 32 * wd_groups samples, the
+    // model-side operands ready-made, the vote threshold folded into the contraction.
+    bool wd_ready;
+    int wd_steps, wd_nb, wd_groups;   // matrix instructions per tile, bit planes of a bin number (6 or 8), groups of 32 samples per job
+    int wd_items;               // work items: a threshold and up to three tiles of its dimensions
+    int wd_ovs;                 // words per group of the kernel's column array: the varying dimensions, an all-zero and an all-one word
+    int32_t *wd_items_d;        // [wd_items][4] threshold, first tile, dimensions, first column
+    uint32_t *wd_bx_d;          // [tiles][wd_steps][64][4] model-side operands: 4-bit floats +-1 / (sample-side value), bias in the slots past F
+    uint32_t *wd_src_d;         // [32][W] per bit of every word of a row: the column that holds it
+
     // Launch properties looked up once per context (kept here, not in function-local statics,
     // so that two contexts used from two threads share no mutable state).
     int enc_bpc[24];        // encode_kernel variant -> blocks of it a CU holds (0 = not asked yet)
@@ -180,6 +190,10 @@ int64_t classical_max_items(hdc_ctx_impl *c);
 // when the model or the call is not of its shape (then nothing was launched).
 int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie);
 bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc);
+// The contraction for long streams (encode_wide.hip); same conventions.  prepare_wide needs the
+// tables of prepare_compact.
+int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie);
+bool try_encode_wide(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s, int *rc);
 // Hamming search on the matrix cores for long query streams with 9..31 classes; false when the
 // shape is not its own (then nothing was launched and *rc is untouched).
 bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint32_t *class_hv,

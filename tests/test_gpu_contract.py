@@ -99,6 +99,8 @@ def test_encode_contraction_many_samples_and_agreement_with_small_calls():
     got = _encode(ctx, x)
     rows = np.concatenate([np.arange(0, 40000, 613), [31, 32, 39967, 39968, 39999]])
     assert np.array_equal(got[rows], _oracle(wl, x[rows]))
-    small = _encode(ctx, x[:1500])
-    assert np.array_equal(small, got[:1500])
+    ctx.hdc_profile_enable(True)
+    small = _encode(ctx, x[:200])
+    assert ctx.hdc_profile_read("encode_contract")[1] == 0, "200 samples were expected to take the vector kernel"
+    assert np.array_equal(small, got[:200])
     ctx.close()

@@ -1,0 +1,111 @@
+"""GPU parity of hdc_encode where it runs as the contraction for long streams (Sec. III Eq. 1;
+level tables whose dimensions flip at most once along the levels, at most 6 matrix-instruction
+steps of 64 feature slots, enough samples to give every compute unit a job of 64 or 128): bit-exact
+against the CPU oracle on the first and last rows (a ragged last job) and on random rows in
+between, over feature counts that leave few or many spare slots for the vote threshold, even and
+odd (the tie vote), fp32 and u8 features, 6 and 8 bit planes, two and four groups per job, rows
+whose last word is partial, NaN and out-of-range values; and agreement with the same rows encoded in
+small calls, which take the vector kernel."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from workloads import make_workload  # noqa: E402
+
+
+def _ctx(wl):
+    from paper_2206_04746_amd import binding
+    return binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+
+
+def _rows(wl, n):
+    """n rows of the workload (its blocks of rows repeated if it has fewer)."""
+    x, _ = wl.train(min(n, wl.n_train))
+    if x.shape[0] < n:
+        x = np.ascontiguousarray(np.tile(x, ((n + x.shape[0] - 1) // x.shape[0], 1))[:n])
+    return x
+
+
+def _encode(ctx, x):
+    xd = torch.from_numpy(x).cuda()
+    hv = torch.full((x.shape[0], ctx.W), -1, dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(xd, hv)
+    torch.cuda.synchronize()
+    return hv.cpu().numpy().view(np.uint32)
+
+
+def _oracle(wl, x):
+    return oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)
+
+
+@pytest.mark.parametrize("cfg,D,F,L,N", [
+    (5, 10000, 342, 64, 65536 - 51),     # the stream's shape: 6 steps, 42 spare slots, even F, four groups per job
+    (5, 10000, 342, 64, 32768),          # a job per compute unit exactly
+    (1, 1024, 100, 16, 65536 - 3),       # 2 steps
+    (6, 10000, 31, 64, 98304 - 77),      # odd F, one step's worth of features
+    (2, 10000, 320, 64, 65536 - 127),    # no spare slot in 5 steps: the threshold takes the sixth
+    (2, 10000, 375, 64, 65536 - 1),      # 9 spare slots
+    (2, 4099, 200, 32, 65536),           # partial last word
+    (4, 10000, 300, 100, 65536 - 64),    # 8 bit planes
+    (2, 6000, 129, 256, 65536 - 9),      # 255 thresholds of a few dimensions: a tile each
+    (3, 2048, 256, 32, 65536 - 33),      # u8 features, 6 planes
+    (3, 3000, 324, 200, 65536 - 17),     # u8 features, 8 planes
+    (5, 16384, 342, 64, 32768 - 5),      # the LDS holds two groups per job only
+    (2, 96, 10, 3, 70000),               # a handful of dimensions
+])
+def test_encode_wide_bit_exact(cfg, D, F, L, N):
+    wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L)
+    x = _rows(wl, N)
+    if wl.dtype == "f32":
+        x[5, :] = np.nan                       # NaN and values outside the range go to the end bins
+        x[6, ::2] = -1e30
+        x[N - 2, 1::2] = 1e30
+    ctx = _ctx(wl)
+    ctx.hdc_profile_enable(True)
+    got = _encode(ctx, x)
+    _, n = ctx.hdc_profile_read("encode_wide")
+    assert n == 1, "the call was expected to take the kernel for long streams"
+    rng = np.random.default_rng(D + N)
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(N - 300, N), rng.integers(0, N, 1400)]))
+    want = _oracle(wl, x[rows])
+    assert np.array_equal(got[rows], want)
+    last_bits = D - 32 * (ctx.W - 1)
+    if last_bits < 32:
+        assert np.all(got[:, -1] >> last_bits == 0)
+    # the same rows in a call too small for any contraction (the vector kernel) and in one that takes
+    # the other contraction kernel
+    small = _encode(ctx, x[:200])
+    assert np.array_equal(small, got[:200])
+    mid = _encode(ctx, x[N - 3000:])
+    assert np.array_equal(mid, got[N - 3000:])
+    _, n = ctx.hdc_profile_read("encode_wide")
+    assert n == 0
+    ctx.close()
+
+
+def test_encode_wide_is_left_to_the_other_kernels_where_it_does_not_fit():
+    # more than 6 steps of features, a level table that flips a dimension twice, a call that would
+    # leave the second round of jobs nearly empty: bit-exact all the same, by the other kernels
+    from paper_2206_04746_amd import binding  # noqa: F401
+    wl = make_workload(2, n_train=70000)
+    x = _rows(wl, 66000)
+    ctx = _ctx(wl)
+    ctx.hdc_profile_enable(True)
+    got = _encode(ctx, x)
+    assert ctx.hdc_profile_read("encode_wide")[1] == 0 and ctx.hdc_profile_read("encode_contract")[1] == 1
+    rows = np.arange(0, 66000, 97)
+    assert np.array_equal(got[rows], _oracle(wl, x[rows]))
+    ctx.close()
+    wl = make_workload(5)
+    x = _rows(wl, 40000)                       # 313 jobs of 128 on 256 units: two rounds, the second a quarter full
+    ctx = _ctx(wl)
+    ctx.hdc_profile_enable(True)
+    got = _encode(ctx, x)
+    assert ctx.hdc_profile_read("encode_wide")[1] == 0
+    rows = np.arange(0, 40000, 61)
+    assert np.array_equal(got[rows], _oracle(wl, x[rows]))
+    ctx.close()
