@@ -229,6 +229,19 @@ int hdc_hsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, 
 int hdc_vsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
 
 /*
+ * hdc_vsum for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context: D is passed, W = ceil(D / 32).  The call allocates
+ * nothing and frees nothing; the scratch of its kernels (a row permutation, a work list, the
+ * blocks' partial counts) is a static device array of 7.3 MB that every GPU the library runs on
+ * holds until the process ends.  Limits: D <= 16384 (HDC_ELIMIT beyond), N <= INT32_MAX; rows are
+ * taken 262144 at a time.  The first call on a device looks up the array's address and the device's
+ * properties (no allocation; make it outside a capture).  All calls on one GPU share the array:
+ * calls on one stream follow each other and are safe, calls that overlap on one GPU (different
+ * streams) race.  Result and argument rules as hdc_vsum: sum_dev [D] int32 is overwritten.
+ */
+int hdc_vsum_static(int32_t D, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
+
+/*
  * Measurement aid (not an operation of the paper): per-kernel device time.  While enabled,
  * every launch of a hot kernel is bracketed by a pair of HIP events recorded on the stream
  * the kernel runs on.  hdc_profile_read waits for the recorded events of one kernel, returns

@@ -23,7 +23,7 @@ HDC_F32, HDC_U8 = 0, 1
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_encode_sparse", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
-           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_encoded_words",
+           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_vsum_static", "hdc_encoded_words",
            "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
@@ -64,6 +64,8 @@ def _load() -> ctypes.CDLL:
     for name in ("hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum"):
         getattr(lib, name).argtypes = [vp, vp, i64, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    lib.hdc_vsum_static.argtypes = [i32, vp, i64, vp, vp]
+    lib.hdc_vsum_static.restype = ctypes.c_int
     lib.hdc_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.hdc_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_int64)]
@@ -235,6 +237,13 @@ class Context:
         ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
         _check(lib.hdc_profile_read(self._h, KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
+
+
+def hdc_vsum_static(D: int, hv: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """hdc_vsum without a context and without any allocation (D <= 16384)."""
+    N, W = hv.shape[0], (int(D) + 31) // 32
+    _check(lib.hdc_vsum_static(int(D), _dev(hv, torch.int32, (N, W)), N, _dev(out, torch.int32, (int(D),)),
+                               _stream(stream)))
 
 
 def version() -> str:

@@ -607,6 +607,85 @@ int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
     return HDC_OK;
 }
 
+// ---- vertical summation without a context and without any allocation ------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid it):
+// the kernels of launch_vsum with their scratch (the identity permutation, the work list and the
+// blocks' partial count rows) in a static device array instead of a context's buffers.  Rows are
+// taken kStaticRows at a time, which bounds the scratch; the launches of one call, and of calls
+// on one stream, follow each other on the stream and so share the array safely; calls that
+// overlap on one GPU (two streams) race on it.
+constexpr int kStaticMaxD = 16384;                 // 512 words per row
+constexpr int64_t kStaticRows = 262144;            // rows per round of launches
+constexpr int64_t kStaticItems = 192;              // partial rows a round can produce (see vsum_static below)
+constexpr size_t kStaticPermWords = (size_t)kStaticRows;
+constexpr size_t kStaticListWords = 64;            // cnt[2], off[2], blk[2] of the one "class", padded
+constexpr size_t kStaticPartialWords = (size_t)kStaticItems * (kStaticMaxD / 32) * 16;
+constexpr size_t kStaticWords = kStaticPermWords + kStaticListWords + kStaticPartialWords;   // 7.3 MB
+static __device__ __align__(256) uint32_t scratch[kStaticWords];
+
+constexpr int kStaticMaxDevices = 64;
+struct StaticDevice {
+    uint32_t *ptr;   // this device's copy of `scratch` (the array's name is no device address on the host)
+    int num_cus;
+    int bpc[kAccWaves + 1];   // blocks of accumulate_kernel a CU holds, by slices per block (0 = not asked yet)
+};
+static StaticDevice g_static[kStaticMaxDevices];
+static bool g_static_ready[kStaticMaxDevices];
+
+int vsum_static(int32_t D, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s) {
+    int dev = -1;
+    HDC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return HDC_ELIMIT;
+    StaticDevice &sd = g_static[dev];
+    if (!g_static_ready[dev]) {   // once per device, with that device current
+        void *ptr = nullptr;
+        HDC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        HDC_HIP(hipDeviceGetAttribute(&sd.num_cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (!ptr || sd.num_cus < 1) return HDC_EHIP;
+        sd.ptr = static_cast<uint32_t *>(ptr);
+        for (int &b : sd.bpc) b = 0;
+        g_static_ready[dev] = true;
+    }
+    const int W = (D + 31) / 32, Wp = (W + kSliceWords - 1) / kSliceWords * kSliceWords;
+    const int nslices = Wp / kSliceWords;
+    const int spb = nslices < kAccWaves ? nslices : kAccWaves, rg = kAccWaves / spb;
+    const int ychunks = (nslices + spb - 1) / spb;
+    const size_t lds = (size_t)(rg - 1) * spb * kWavePlanes * kWave * sizeof(uint32_t);
+    if (sd.bpc[spb] == 0) {
+        int bpc = 0;
+        HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, reinterpret_cast<const void *>(accumulate_kernel),
+                                                             spb * rg * kWave, lds));
+        sd.bpc[spb] = bpc < 1 ? 1 : bpc;
+    }
+    uint32_t *perm = sd.ptr, *cnt = perm + kStaticPermWords, *off = cnt + 2, *blk = off + 2;
+    uint32_t *partial = cnt + kStaticListWords;
+    // rows per wave so that a round of rows is one round of blocks, within what a block's planes count
+    int64_t cap = (int64_t)sd.num_cus * sd.bpc[spb] / ychunks - 1;
+    cap = cap < 1 ? 1 : (cap > kStaticItems - 2 ? kStaticItems - 2 : cap);
+    int64_t rb_max = (4088 / rg) / 8 * 8;
+    rb_max = rb_max > 2040 ? 2040 : rb_max;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, s, out, (int64_t)D);
+    for (int64_t n0 = 0; n0 < N; n0 += kStaticRows) {
+        const int64_t n = N - n0 < kStaticRows ? N - n0 : kStaticRows;
+        int64_t rb = ((n + rg * cap - 1) / (rg * cap) + 7) / 8 * 8;
+        rb = rb < 16 ? 16 : (rb > rb_max ? rb_max : rb);
+        const uint32_t block_rows = (uint32_t)(rg * rb);
+        const int64_t items = (n + block_rows - 1) / block_rows + 1;
+        if (items > kStaticItems) return HDC_ELIMIT;   // (262144 rows in blocks of at least 2040 rows: 130 items at most)
+        hipLaunchKernelGGL(group_all_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t)n, block_rows,
+                           cnt, off, blk, perm);
+        hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks), dim3(spb * rg * kWave), lds, s,
+                           hv + (size_t)n0 * W, perm, cnt, off, blk, 1, W, Wp, (int)rb, spb, rg, partial);
+        const int pairs = Wp * 16;
+        int K = (int)((262144 + (int64_t)pairs - 1) / pairs);
+        K = K < 1 ? 1 : (K > 16 ? 16 : K);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), 1u, (unsigned)K), dim3(256), 0, s,
+                           partial, blk, Wp, D, K, out);
+    }
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 // ---- majority vote to class vectors ----------------------------------------------------
 // One lane per dimension; a wave's 64 decisions are gathered with a ballot into two words.
 __global__ __launch_bounds__(256) void binarize_classical_kernel(const int32_t *__restrict__ acc,

@@ -423,6 +423,13 @@ int hdc_vsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, 
     return launch_vsum(impl(ctx), hv_dev, N, sum_dev, static_cast<hipStream_t>(stream));
 }
 
+int hdc_vsum_static(int32_t D, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream) {
+    if (D < 1 || N < 0 || N > INT32_MAX) return HDC_EINVAL;
+    if (D > 16384) return HDC_ELIMIT;
+    if (!sum_dev || !aligned4(sum_dev) || (N > 0 && (!hv_dev || !aligned4(hv_dev)))) return HDC_EINVAL;
+    return vsum_static(D, hv_dev, N, sum_dev, static_cast<hipStream_t>(stream));
+}
+
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream) {
     if (!ctx || N < 0) return HDC_EINVAL;

@@ -184,6 +184,8 @@ int launch_pack(hdc_ctx_impl *c, const uint8_t *bits, int64_t N, uint32_t *hv, h
 int launch_unpack(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, uint8_t *bits, hipStream_t s);
 int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
+// hdc_vsum without a context, its scratch in a static device array (no allocation); D <= 16384
+int vsum_static(int32_t D, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(hdc_ctx_impl *c);
 // Encoding as a contraction (encode_contract.hip): tables at create; the launcher returns false
