@@ -55,7 +55,10 @@ typedef uint32_t wd_u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t wd_u32x6 __attribute__((ext_vector_type(6)));
 typedef uint32_t wd_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a global load of 16 bytes at any word
 
-constexpr int kWdWaves = 8, kWdThreads = kWdWaves * kWave;   // two waves per SIMD, 256 registers each
+// Waves per block: two per group of a job.  Four groups: eight waves, a block per compute unit (two
+// waves per SIMD, 256 registers each).  Two groups: four waves, and two blocks per compute unit where
+// the LDS holds both, so that one block's tile phase fills the other's loads and stores.
+constexpr int wd_waves_of(int groups) { return 2 * groups; }
 constexpr int kWdTiles = 3;          // tiles of one threshold a wave works on at a time: their model-side operands stay in registers
 // Matrix instructions per tile, 64 features each.  Beyond 6 the resident operands of three tiles
 // (12 registers a step) no longer fit beside the accumulators, and with fewer tiles per turn the
@@ -153,7 +156,7 @@ size_t wide_lds_bytes(int steps, int nb, int groups, int ovs) {
     const size_t planes = (size_t)groups * steps * kWave * (16 + (nb > 6 ? 16 : 8));
     const size_t over = (size_t)groups * ovs * 4;
     const size_t bins = (size_t)groups * 32 * (steps * 64 + 16);
-    return planes + std::max(over, bins);
+    return 16 + planes + std::max(over, bins);
 }
 
 // Leaves c->wd_ready false when the model is not of the kernel's shape; only a failed allocation
@@ -298,11 +301,12 @@ __device__ __forceinline__ v16f wd_mfma(v4i a, wd_u32x4 b, v16f c) {
 // (the 16 spread the rows over the banks), and later per group and column the bits of the
 // group's 32 samples, [G][ovs] words, the last two of each group all zeros and all ones.
 template <int KS, int NB, bool kU8, int G>
-__global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
+__global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
     const float *__restrict__ scale, int W, const int4 *__restrict__ items, int n_items,
     const wd_u32x4 *__restrict__ bx, const uint32_t *__restrict__ src_of, int ovs, uint32_t *__restrict__ hv) {
     extern __shared__ __attribute__((aligned(16))) uint32_t wd_lds[];
+    constexpr int kWdWaves = wd_waves_of(G), kWdThreads = kWdWaves * kWave;
     constexpr int kSamples = 32 * G;
     constexpr int kQuads = KS * 16;                              // groups of four features per sample row, pad slots included
     constexpr int kPerRound = kWdThreads / kQuads;               // samples the block loads at a time
@@ -311,10 +315,11 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
     constexpr int kRawRegs = kU8 ? 1 : 4;
     constexpr int kTouches = (kSamples * KS * 64 * (kU8 ? 1 : 4) / 128 + kWdThreads - 1) / kWdThreads;   // 128-byte lines of a job's features per thread
     constexpr int TB = kWdTiles;
-    wd_u32x4 *planes_a = reinterpret_cast<wd_u32x4 *>(wd_lds);
+    uint32_t *ticket = wd_lds;   // the next item of the tile phase (16 bytes in front of the planes)
+    wd_u32x4 *planes_a = reinterpret_cast<wd_u32x4 *>(wd_lds + 4);
     typedef typename std::conditional<(NB > 6), wd_u32x4, wd_u32x2>::type plane_b_t;
-    plane_b_t *planes_b = reinterpret_cast<plane_b_t *>(wd_lds + G * KS * kWave * 4);
-    uint32_t *over = wd_lds + G * KS * kWave * (4 + (NB > 6 ? 4 : 2));
+    plane_b_t *planes_b = reinterpret_cast<plane_b_t *>(wd_lds + 4 + G * KS * kWave * 4);
+    uint32_t *over = wd_lds + 4 + G * KS * kWave * (4 + (NB > 6 ? 4 : 2));
     uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
     const uint8_t *bins = reinterpret_cast<const uint8_t *>(over);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -330,6 +335,7 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
         // were asked for while the previous job's rows were written).  Every thread loads in every
         // round (those without a feature or a sample of their own: something that exists).
         {
+            if (threadIdx.x == 0) *ticket = kWdWaves;   // (every wave starts on item `wave`)
             int tid = threadIdx.x;
             asm volatile("" : "+v"(tid));   // (opaque: what follows is worked out per job, not kept in registers across the phases)
             const int f0 = 4 * (tid % kQuads), s_in = tid / kQuads;
@@ -417,10 +423,22 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
         // ---- T: a threshold and up to TB tiles of its dimensions per wave and turn.  The tiles'
         // model-side operands stay in registers for the G groups; while the last group is worked
         // on, each is replaced by the next item's as soon as its instruction has been issued.
+        // The items are dealt out by a counter: the SIMD favours its older wave, which would be
+        // through a fixed share early and leave the younger one to finish alone (1.95 -> 1.75 ms per
+        // million samples).  Units of an item and half of the groups, to shorten the wait for the
+        // last wave, were slower (1.90 ms): every unit fetches its tiles' operands again.
         {
-            int it = wave;
-            int4 item = items[min(it, n_items - 1)];
-            if (it < n_items) {
+            constexpr int kSplit = 1, kUnitGroups = G;   // units per item, groups per unit
+            const int n_units = n_items * kSplit;
+            int unit = wave;
+            auto claim = [&]() {
+                uint32_t got = 0;
+                if (lane == 0) got = atomicAdd(ticket, 1u);
+                return (int)__builtin_amdgcn_readfirstlane(got);
+            };
+            int unit_next = claim();
+            int4 item = items[min(unit / kSplit, n_items - 1)];
+            if (unit < n_units) {
                 const int tile0 = __builtin_amdgcn_readfirstlane(item.y), nt = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
 #pragma unroll
                 for (int t = 0; t < TB; ++t)
@@ -428,11 +446,14 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
                     for (int k = 0; k < KS; ++k) bm[t][k] = bx[((size_t)(tile0 + min(t, nt - 1)) * KS + k) * kWave + lane];
             }
 #pragma unroll 1
-            for (; it < n_items; it += kWdWaves) {
+            for (; unit < n_units; unit = unit_next, unit_next = claim()) {
+                const int g0 = (unit % kSplit) * kUnitGroups;
                 const int tau = __builtin_amdgcn_readfirstlane(item.x);
                 const int nd = __builtin_amdgcn_readfirstlane(item.z), col0 = __builtin_amdgcn_readfirstlane(item.w);
                 const int nt = (nd + 31) >> 5;
-                item = items[it + kWdWaves < n_items ? it + kWdWaves : it];   // (after the wave's last item: the same again, unused)
+                const int un = unit_next < n_units ? unit_next : unit;   // (after the wave's last unit: the same again, unused)
+                const int g0_n = (un % kSplit) * kUnitGroups;
+                item = items[un / kSplit];
                 const int tile0_n = __builtin_amdgcn_readfirstlane(item.y), nt_n = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
                 const wd_u32x4 *bn[TB];
 #pragma unroll
@@ -440,8 +461,8 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
                 uint32_t tb[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) tb[b] = (tau >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
-                wd_u32x4 pa = planes_a[lane];
-                plane_b_t pb = planes_b[lane];
+                wd_u32x4 pa = planes_a[g0 * KS * kWave + lane];
+                plane_b_t pb = planes_b[g0 * KS * kWave + lane];
                 // One group of 32 samples against the item's NT tiles (a constant here: no branch in the
                 // loop); the last group also fetches the next item's operands, each as soon as its
                 // last instruction has been issued.
@@ -449,8 +470,8 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
                     constexpr int NT = decltype(nt_c)::value;
                     constexpr bool kLast = decltype(last_c)::value;
                     v16f acc[NT];
-                    const wd_u32x4 *pa_at = planes_a + (kLast ? 0 : (g + 1) * KS * kWave) + lane;   // where the planes after this group's are
-                    const plane_b_t *pb_at = planes_b + (kLast ? 0 : (g + 1) * KS * kWave) + lane;
+                    const wd_u32x4 *pa_at = planes_a + (kLast ? g0_n : g + 1) * KS * kWave + lane;   // where the planes after this group's are
+                    const plane_b_t *pb_at = planes_b + (kLast ? g0_n : g + 1) * KS * kWave + lane;
                     const wd_u32x4 *pa_in = planes_a + g * KS * kWave + lane;
                     const plane_b_t *pb_in = planes_b + g * KS * kWave + lane;
 #pragma unroll
@@ -494,8 +515,8 @@ __global__ __launch_bounds__(kWdThreads) void encode_wide_kernel(
                 };
                 auto run = [&](auto nt_c) {
 #pragma unroll 1
-                    for (int g = 0; g < G - 1; ++g) group(g, nt_c, std::false_type{});
-                    group(G - 1, nt_c, std::true_type{});
+                    for (int g = g0; g < g0 + kUnitGroups - 1; ++g) group(g, nt_c, std::false_type{});
+                    group(g0 + kUnitGroups - 1, nt_c, std::true_type{});
                 };
                 if (nt == 1) run(std::integral_constant<int, 1>{});
                 else if (nt == 2) run(std::integral_constant<int, 2>{});
@@ -605,8 +626,9 @@ static int launch_wide(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out,
         HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
     const int64_t jobs = (n + 32 * G - 1) / (32 * G);
-    const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus);
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kWdThreads), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
+    const int per_cu = G == 2 && 2 * (lds + 1024) <= kWdLdsLimit ? 2 : 1;
+    const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus * per_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(wd_waves_of(G) * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
                        c->scale_d, c->W, reinterpret_cast<const int4 *>(c->wd_items_d), c->wd_items,
                        reinterpret_cast<const wd_u32x4 *>(c->wd_bx_d), c->wd_src_d, c->wd_ovs, out);
     HDC_HIP(hipGetLastError());
