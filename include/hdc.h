@@ -39,7 +39,8 @@ typedef enum {
     HDC_EINVAL = -1, /* null pointer, size out of range, misaligned pointer */
     HDC_ENOMEM = -2, /* host or device allocation failed */
     HDC_EHIP = -3,   /* a HIP runtime call or kernel launch failed */
-    HDC_ELIMIT = -4  /* argument is valid but beyond what this build supports */
+    HDC_ELIMIT = -4, /* argument is valid but beyond what this build supports */
+    HDC_ELABEL = -5  /* a label is outside [0, C) and label checking is on (hdc_set_label_check) */
 } hdc_status;
 
 typedef enum { HDC_F32 = 0, HDC_U8 = 1 } hdc_dtype;
@@ -227,6 +228,33 @@ int hdc_pack(hdc_ctx *ctx, const uint8_t *bits_dev, int64_t N, uint32_t *hv_dev,
 int hdc_unpack(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, uint8_t *bits_dev, void *stream);
 int hdc_hsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
 int hdc_vsum(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, int32_t *sum_dev, void *stream);
+
+/*
+ * Labels outside [0, C) are a caller's mistake.  By default the training calls skip such samples
+ * (defined behaviour, see hdc_train_classical).  With label checking on (a debugging aid, off by
+ * default) hdc_train_classical, hdc_train_online and hdc_train_online_batched first count the
+ * labels outside the range on `stream`, wait for the count (the call synchronises the stream)
+ * and return HDC_ELABEL without training anything if there is one.
+ */
+int hdc_set_label_check(hdc_ctx *ctx, int enable);
+
+/*
+ * Allocate now what entry points otherwise allocate at their first call (and which makes that
+ * call synchronise the device): after hdc_reserve has covered the sizes that are used, no entry
+ * point allocates, frees or synchronises.  `what` is a mask of
+ *   HDC_RESERVE_ONLINE          the 64 MB of hdc_train_online's fast path
+ *   HDC_RESERVE_ONLINE_BATCHED  hdc_train_online_batched for batches of up to max_batch samples
+ *   HDC_RESERVE_SEARCH_COSINE   hdc_search_cosine for calls of up to max_queries queries
+ *   HDC_RESERVE_ENCODE_SPARSE   hdc_encode_sparse (its derived tables are computed on `stream`)
+ * max_batch / max_queries are read only with their flag (>= 1 then).  Errors: HDC_EINVAL,
+ * HDC_ENOMEM, HDC_EHIP.  Growing a buffer frees the old one, which waits for the device.
+ */
+#define HDC_RESERVE_ONLINE 1u
+#define HDC_RESERVE_ONLINE_BATCHED 2u
+#define HDC_RESERVE_SEARCH_COSINE 4u
+#define HDC_RESERVE_ENCODE_SPARSE 8u
+#define HDC_RESERVE_ALL 15u
+int hdc_reserve(hdc_ctx *ctx, unsigned what, int64_t max_batch, int64_t max_queries, void *stream);
 
 /*
  * hdc_vsum for callers that cannot allocate: code under HIP graph capture, tight serving loops,

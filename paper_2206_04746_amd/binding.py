@@ -17,13 +17,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # HDC_LIBRARY may point at another build of the same ABI (e.g. a tuning variant)
 LIB_PATH = os.environ.get("HDC_LIBRARY") or os.path.join(_HERE, "libhdc.so")
 
-HDC_OK, HDC_EINVAL, HDC_ENOMEM, HDC_EHIP, HDC_ELIMIT = 0, -1, -2, -3, -4
+HDC_OK, HDC_EINVAL, HDC_ENOMEM, HDC_EHIP, HDC_ELIMIT, HDC_ELABEL = 0, -1, -2, -3, -4, -5
+HDC_RESERVE_ONLINE, HDC_RESERVE_ONLINE_BATCHED, HDC_RESERVE_SEARCH_COSINE, HDC_RESERVE_ENCODE_SPARSE = 1, 2, 4, 8
 HDC_F32, HDC_U8 = 0, 1
 
 # every symbol include/hdc.h declares
 SYMBOLS = ["hdc_create", "hdc_destroy", "hdc_encode", "hdc_encode_sparse", "hdc_train_classical",
            "hdc_binarize_classical", "hdc_train_online", "hdc_train_online_batched", "hdc_binarize_online", "hdc_search",
-           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_vsum_static", "hdc_encoded_words",
+           "hdc_search_cosine", "hdc_pack", "hdc_unpack", "hdc_hsum", "hdc_vsum", "hdc_vsum_static", "hdc_encoded_words", "hdc_set_label_check", "hdc_reserve",
            "hdc_profile_enable", "hdc_profile_read",
            "hdc_strerror", "hdc_last_hip_error", "hdc_version"]
 
@@ -65,6 +66,10 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).argtypes = [vp, vp, i64, vp, vp]
     lib.hdc_search.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     lib.hdc_vsum_static.argtypes = [i32, vp, i64, vp, vp]
+    lib.hdc_set_label_check.argtypes = [vp, ctypes.c_int]
+    lib.hdc_set_label_check.restype = ctypes.c_int
+    lib.hdc_reserve.argtypes = [vp, ctypes.c_uint, i64, i64, vp]
+    lib.hdc_reserve.restype = ctypes.c_int
     lib.hdc_vsum_static.restype = ctypes.c_int
     lib.hdc_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.hdc_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -228,6 +233,12 @@ class Context:
                               _dev(dist, torch.int32, (N, self.C)), _dev(pred, torch.int32, (N,)),
                               _stream(stream)))
 
+
+    def hdc_set_label_check(self, enable: bool = True) -> None:
+        _check(lib.hdc_set_label_check(self._h, int(bool(enable))))
+
+    def hdc_reserve(self, what: int, max_batch: int = 0, max_queries: int = 0, stream=None) -> None:
+        _check(lib.hdc_reserve(self._h, int(what), int(max_batch), int(max_queries), _stream(stream)))
 
     def hdc_profile_enable(self, enable: bool = True) -> None:
         _check(lib.hdc_profile_enable(self._h, int(bool(enable))))

@@ -304,6 +304,14 @@ static int prepare_sparse(hdc_ctx_impl *c, int P, uint32_t bias, hipStream_t s) 
     return HDC_OK;
 }
 
+// Scratch and derived tables of hdc_encode_sparse (a no-op when they are there).
+int reserve_sparse(hdc_ctx_impl *c, hipStream_t s) {
+    int P;
+    uint32_t bias;
+    majority_planes(c, &P, &bias);
+    return prepare_sparse(c, P, bias, s);
+}
+
 int launch_encode_sparse(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t *hv, hipStream_t s) {
     int P;
     uint32_t bias;

@@ -33,7 +33,7 @@ static void free_ctx(hdc_ctx_impl *c) {
                     c->ct_tau_d[0], c->ct_col_d[0], c->ct_k_d[0], c->ct_bt_d[0],
                     c->ct_tau_d[1], c->ct_col_d[1], c->ct_k_d[1], c->ct_bt_d[1],
                     c->ct_tau_d[2], c->ct_col_d[2], c->ct_k_d[2], c->ct_bt_d[2],
-                    c->wd_items_d, c->wd_bx_d, c->wd_src_d};
+                    c->wd_items_d, c->wd_bx_d, c->wd_src_d, c->bad_labels_d};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (int k = 0; k < HDC_K_COUNT; ++k) {
@@ -268,6 +268,7 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     }
     c->q_rows = kEncodeChunk;
     TRY(dev_alloc(&c->q_d, (size_t)c->q_rows * c->Fp));
+    TRY(dev_alloc(&c->bad_labels_d, 1));
     TRY(dev_alloc(&c->cls_cnt_d, (size_t)p->C + 1));
     TRY(dev_alloc(&c->cls_off_d, (size_t)p->C + 1));
     TRY(dev_alloc(&c->cls_cur_d, (size_t)p->C + 1));
@@ -294,6 +295,38 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
     }
     *out = reinterpret_cast<hdc_ctx *>(c);
     return HDC_OK;
+}
+
+__global__ __launch_bounds__(256) void count_bad_labels_kernel(const int32_t *__restrict__ labels, int64_t N, int C,
+                                                               unsigned long long *bad) {
+    int64_t mine = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
+        const int y = labels[i];
+        mine += (y < 0 || y >= C) ? 1 : 0;
+    }
+    if (mine) atomicAdd(bad, (unsigned long long)mine);
+}
+__global__ void zero_u64_kernel(unsigned long long *p) { *p = 0; }
+
+int count_bad_labels(hdc_ctx_impl *c, const int32_t *labels, int64_t N, hipStream_t s, int64_t *bad) {
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, s, c->bad_labels_d);
+    const int64_t blocks = std::min<int64_t>((N + 255) / 256, 4096);
+    hipLaunchKernelGGL(count_bad_labels_kernel, dim3((unsigned)blocks), dim3(256), 0, s, labels, N, c->p.C,
+                       c->bad_labels_d);
+    unsigned long long got = 0;
+    HDC_HIP(hipMemcpyAsync(&got, c->bad_labels_d, sizeof(got), hipMemcpyDeviceToHost, s));
+    HDC_HIP(hipStreamSynchronize(s));
+    *bad = (int64_t)got;
+    return HDC_OK;
+}
+
+// HDC_ELABEL if label checking is on and a label is outside [0, C); HDC_OK otherwise.
+static int labels_ok(hdc_ctx_impl *c, const int32_t *labels, int64_t N, hipStream_t s) {
+    if (!c->check_labels) return HDC_OK;
+    int64_t bad = 0;
+    const int rc = count_bad_labels(c, labels, N, s, &bad);
+    if (rc != HDC_OK) return rc;
+    return bad ? HDC_ELABEL : HDC_OK;
 }
 
 static inline hdc_ctx_impl *impl(hdc_ctx *c) { return reinterpret_cast<hdc_ctx_impl *>(c); }
@@ -349,6 +382,7 @@ int hdc_train_classical(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *lab
     if (!hv_dev || !labels_dev || !acc_dev || !class_n_dev) return HDC_EINVAL;
     if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev) || !aligned8(class_n_dev))
         return HDC_EINVAL;
+    if (const int rc = labels_ok(impl(ctx), labels_dev, N, static_cast<hipStream_t>(stream))) return rc;
     return launch_train_classical(impl(ctx), hv_dev, labels_dev, N, acc_dev, class_n_dev,
                                   static_cast<hipStream_t>(stream));
 }
@@ -367,6 +401,7 @@ int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels
     if (N == 0 || epochs == 0) return HDC_OK;
     if (!hv_dev || !labels_dev || !acc_dev) return HDC_EINVAL;
     if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev)) return HDC_EINVAL;
+    if (const int rc = labels_ok(impl(ctx), labels_dev, N, static_cast<hipStream_t>(stream))) return rc;
     return launch_train_online(impl(ctx), hv_dev, labels_dev, N, epochs, lr, acc_dev,
                                static_cast<hipStream_t>(stream));
 }
@@ -377,6 +412,7 @@ int hdc_train_online_batched(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t
     if (N == 0 || epochs == 0) return HDC_OK;
     if (!hv_dev || !labels_dev || !acc_dev) return HDC_EINVAL;
     if (!aligned4(hv_dev) || !aligned4(labels_dev) || !aligned4(acc_dev)) return HDC_EINVAL;
+    if (const int rc = labels_ok(impl(ctx), labels_dev, N, static_cast<hipStream_t>(stream))) return rc;
     return launch_train_online_batched(impl(ctx), hv_dev, labels_dev, N, epochs, lr, batch, acc_dev,
                                        static_cast<hipStream_t>(stream));
 }
@@ -441,6 +477,25 @@ int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *
                          static_cast<hipStream_t>(stream));
 }
 
+int hdc_set_label_check(hdc_ctx *ctx, int enable) {
+    if (!ctx) return HDC_EINVAL;
+    impl(ctx)->check_labels = enable != 0;
+    return HDC_OK;
+}
+
+int hdc_reserve(hdc_ctx *ctx, unsigned what, int64_t max_batch, int64_t max_queries, void *stream) {
+    if (!ctx || (what & ~(unsigned)HDC_RESERVE_ALL)) return HDC_EINVAL;
+    if (((what & HDC_RESERVE_ONLINE_BATCHED) && max_batch < 1) || ((what & HDC_RESERVE_SEARCH_COSINE) && max_queries < 1))
+        return HDC_EINVAL;
+    hdc_ctx_impl *c = impl(ctx);
+    int rc = HDC_OK;
+    if (rc == HDC_OK && (what & HDC_RESERVE_ONLINE)) rc = reserve_online(c);
+    if (rc == HDC_OK && (what & HDC_RESERVE_ONLINE_BATCHED)) rc = reserve_online_batched(c, max_batch);
+    if (rc == HDC_OK && (what & HDC_RESERVE_SEARCH_COSINE)) rc = reserve_search_cosine(c, max_queries);
+    if (rc == HDC_OK && (what & HDC_RESERVE_ENCODE_SPARSE)) rc = reserve_sparse(c, static_cast<hipStream_t>(stream));
+    return rc;
+}
+
 int hdc_profile_enable(hdc_ctx *ctx, int enable) {
     if (!ctx) return HDC_EINVAL;
     hdc_ctx_impl *c = impl(ctx);
@@ -480,6 +535,7 @@ const char *hdc_strerror(int code) {
         case HDC_ENOMEM: return "out of memory";
         case HDC_EHIP: return "HIP runtime error (see hdc_last_hip_error)";
         case HDC_ELIMIT: return "size beyond what this build supports";
+        case HDC_ELABEL: return "a label is outside [0, C) (label checking is on)";
         default: return "unknown status";
     }
 }

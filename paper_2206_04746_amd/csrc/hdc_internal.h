@@ -61,7 +61,9 @@ struct hdc_ctx_impl {
     int64_t perm_rows;
     uint32_t *partial_d;  // [partial_items][Wp * 16] per-block partial counts, two u16 per dword
     int64_t partial_items;
-    uint32_t *on_bits_d;  // [16384][1024] per-thread sample bits of hdc_train_online (first call allocates)
+    uint32_t *on_bits_d;  // [16384][1024] per-thread sample bits of hdc_train_online (first call or hdc_reserve allocates)
+    bool check_labels;    // hdc_set_label_check: training calls refuse labels outside [0, C)
+    unsigned long long *bad_labels_d;   // [1] counter of count_bad_labels
 
     // Scratch of hdc_train_online_batched, allocated on its first call and grown when a call
     // needs more (batch size is a call argument, not a property of the model).
@@ -186,6 +188,13 @@ int launch_hsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
 int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
 // hdc_vsum without a context, its scratch in a static device array (no allocation); D <= 16384
 int vsum_static(int32_t D, const uint32_t *hv, int64_t N, int32_t *out, hipStream_t s);
+// Scratch that entry points otherwise allocate at their first call (hdc_reserve); no-ops when it is there.
+int reserve_online(hdc_ctx_impl *c);
+int reserve_online_batched(hdc_ctx_impl *c, int64_t batch);
+int reserve_search_cosine(hdc_ctx_impl *c, int64_t queries);
+int reserve_sparse(hdc_ctx_impl *c, hipStream_t s);
+// Counts the labels outside [0, C) of a training call (hdc_set_label_check); synchronises the stream.
+int count_bad_labels(hdc_ctx_impl *c, const int32_t *labels, int64_t N, hipStream_t s, int64_t *bad);
 // Most partial rows one hdc_train_classical launch can produce (sizes partial_d at create).
 int64_t classical_max_items(hdc_ctx_impl *c);
 // Encoding as a contraction (encode_contract.hip): tables at create; the launcher returns false

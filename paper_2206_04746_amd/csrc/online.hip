@@ -540,6 +540,20 @@ __global__ __launch_bounds__(kOnlineThreads) void online_bits_kernel(const uint3
 
 constexpr int64_t kOnlineChunk = 16384;   // samples whose per-thread bit words are prepared at a time (64 MB)
 
+// The per-thread sample words of the LDS variant of hdc_train_online (64 MB; a no-op when there).
+int reserve_online(hdc_ctx_impl *c) {
+    if (c->on_bits_d) return HDC_OK;
+    HDC_HIP(hipSetDevice(c->device));
+    const hipError_t e = hipMalloc(reinterpret_cast<void **>(&c->on_bits_d),
+                                   (size_t)kOnlineChunk * kOnlineThreads * sizeof(uint32_t));
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return HDC_ENOMEM;
+    }
+    HDC_HIP(e);
+    return HDC_OK;
+}
+
 template <int CMAX, int KPT>
 static int launch_online_lds(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                              int32_t epochs, float lr, float *acc, hipStream_t s) {
@@ -551,15 +565,9 @@ static int launch_online_lds(hdc_ctx_impl *c, const uint32_t *hv, const int32_t 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         c->on_attr_set[CMAX] = true;
     }
-    if (!c->on_bits_d) {
-        HDC_HIP(hipSetDevice(c->device));
-        const hipError_t e = hipMalloc(reinterpret_cast<void **>(&c->on_bits_d),
-                                       (size_t)kOnlineChunk * kOnlineThreads * sizeof(uint32_t));
-        if (e == hipErrorOutOfMemory) {
-            (void)hipGetLastError();
-            return HDC_ENOMEM;
-        }
-        HDC_HIP(e);
+    {
+        const int rc = reserve_online(c);
+        if (rc != HDC_OK) return rc;
     }
     // A set that fits one chunk is prepared once and walked `epochs` times by one launch; a
     // longer one is walked chunk by chunk, every epoch (the accumulators rest in memory between

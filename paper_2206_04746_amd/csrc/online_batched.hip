@@ -956,15 +956,12 @@ static int launch_norm(hdc_ctx_impl *c, const float *acc, int G, hipStream_t s) 
     return HDC_OK;
 }
 
-int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
-                                int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s) {
-    const int C = c->p.C, D = c->p.D, W = c->W;
+// Scratch of hdc_train_online_batched for batches of up to `batch` samples (grown if smaller; a
+// no-op, without any synchronisation, when it is there already).
+int reserve_online_batched(hdc_ctx_impl *c, int64_t batch) {
+    const int C = c->p.C, D = c->p.D;
     const int G = (D + kWave - 1) / kWave;
     const FwdShape f = fwd_shape(C, G);
-    if (batch > N) batch = N;
-
-    // A batch is worked off in pieces of at most `sb` samples (forward, weights, backward each);
-    // sb bounds the scratch: partial dot products and transposed masks.
     const int64_t sb = fwd_sub_batch(f, C, batch);
     const int64_t ld = (sb + kTileSamples - 1) / kTileSamples * kTileSamples;
     HDC_HIP(hipSetDevice(c->device));
@@ -986,6 +983,32 @@ int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32
         if (rc == HDC_OK) rc = grow(&c->ob_meta_d, &c->ob_meta_bytes, (3 * (size_t)C + 1 + rows) * sizeof(uint32_t));
     }
     if (rc == HDC_OK && share_bytes) rc = grow(&c->ob_share_d, &c->ob_share_bytes, share_bytes);
+    return rc;
+}
+
+// Scratch of hdc_search_cosine for calls of up to `queries` queries.
+int reserve_search_cosine(hdc_ctx_impl *c, int64_t queries) {
+    const int C = c->p.C, G = (c->p.D + kWave - 1) / kWave;
+    const FwdShape f = fwd_shape(C, G);
+    const int64_t sb = fwd_sub_batch(f, C, queries);
+    HDC_HIP(hipSetDevice(c->device));
+    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)f.slices * sb * C * sizeof(double));
+    if (rc == HDC_OK) rc = grow(&c->ob_norm_d, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
+    return rc;
+}
+
+int launch_train_online_batched(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                                int32_t epochs, float lr, int64_t batch, float *acc, hipStream_t s) {
+    const int C = c->p.C, D = c->p.D, W = c->W;
+    const int G = (D + kWave - 1) / kWave;
+    const FwdShape f = fwd_shape(C, G);
+    if (batch > N) batch = N;
+
+    // A batch is worked off in pieces of at most `sb` samples (forward, weights, backward each);
+    // sb bounds the scratch: partial dot products and transposed masks.
+    const int64_t sb = fwd_sub_batch(f, C, batch);
+    const int cb = bwd_dense_width(C);
+    int rc = reserve_online_batched(c, batch);
     if (rc != HDC_OK) return rc;
     if (!c->ob_attr_set) {
         const void *kernels[] = {reinterpret_cast<const void *>(online_bwd_kernel<0>),
@@ -1036,9 +1059,7 @@ int launch_search_cosine(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const f
     const int G = (D + kWave - 1) / kWave;
     const FwdShape f = fwd_shape(C, G);
     const int64_t sb = fwd_sub_batch(f, C, N);
-    HDC_HIP(hipSetDevice(c->device));
-    int rc = grow(&c->ob_part_d, &c->ob_part_bytes, (size_t)f.slices * sb * C * sizeof(double));
-    if (rc == HDC_OK) rc = grow(&c->ob_norm_d, &c->ob_norm_bytes, (size_t)C * G * sizeof(double));
+    int rc = reserve_search_cosine(c, N);
     if (rc != HDC_OK) return rc;
     rc = launch_norm(c, acc, G, s);
     if (rc != HDC_OK) return rc;

@@ -1,0 +1,99 @@
+"""Boundary behaviour that is not arithmetic (the calls the C ABI lists beside the operations of
+the paper): label checking (labels outside [0, C) are skipped by default and refused with
+HDC_ELABEL when checking is on, Sec. III's training calls), and hdc_reserve (after it, the calls
+that otherwise allocate at first use give the same results and allocate nothing more)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from workloads import make_workload  # noqa: E402
+
+
+def _setup(n=600):
+    from paper_2206_04746_amd import binding
+    wl = make_workload(1, n_train=n)
+    x, y = wl.train(n)
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    hv = torch.empty((n, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(torch.from_numpy(x).cuda(), hv)
+    return binding, wl, ctx, hv, y
+
+
+def test_label_check_refuses_out_of_range_labels_and_trains_nothing():
+    binding, wl, ctx, hv, y = _setup()
+    bad = y.copy()
+    bad[17] = wl.C
+    bad[400] = -1
+    yd, bd = torch.from_numpy(y).cuda(), torch.from_numpy(bad).cuda()
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device="cuda")
+    cn = torch.zeros(wl.C, dtype=torch.int64, device="cuda")
+    facc = torch.zeros((wl.C, wl.D), dtype=torch.float32, device="cuda")
+    # default: such samples are skipped
+    ctx.hdc_train_classical(hv, bd, acc, cn)
+    torch.cuda.synchronize()
+    hv_h = hv.cpu().numpy().view(np.uint32)
+    o_acc, o_cn = oracle.train_classical(hv_h, bad, wl.D, wl.C)
+    assert np.array_equal(acc.cpu().numpy(), o_acc) and int(cn.sum()) == len(y) - 2
+    # checking on: refused, nothing touched
+    ctx.hdc_set_label_check(True)
+    acc.zero_(), cn.zero_()
+    for call in (lambda: ctx.hdc_train_classical(hv, bd, acc, cn),
+                 lambda: ctx.hdc_train_online(hv, bd, facc, 1, 1.0),
+                 lambda: ctx.hdc_train_online_batched(hv, bd, facc, 64, 1, 1.0)):
+        with pytest.raises(binding.HdcError) as err:
+            call()
+        assert err.value.code == binding.HDC_ELABEL
+    torch.cuda.synchronize()
+    assert int(acc.abs().sum()) == 0 and int(cn.sum()) == 0 and float(facc.abs().sum()) == 0.0
+    assert "label" in binding.strerror(binding.HDC_ELABEL)
+    # good labels pass with checking on, and give the usual result
+    ctx.hdc_train_classical(hv, yd, acc, cn)
+    torch.cuda.synchronize()
+    o_acc, o_cn = oracle.train_classical(hv_h, y, wl.D, wl.C)
+    assert np.array_equal(acc.cpu().numpy(), o_acc) and np.array_equal(cn.cpu().numpy(), o_cn)
+    ctx.hdc_set_label_check(False)
+    ctx.close()
+
+
+def test_reserve_then_calls_allocate_nothing_and_match():
+    binding, wl, ctx, hv, y = _setup()
+    yd = torch.from_numpy(y).cuda()
+    n = hv.shape[0]
+    ctx.hdc_reserve(binding.HDC_RESERVE_ONLINE | binding.HDC_RESERVE_ONLINE_BATCHED | binding.HDC_RESERVE_SEARCH_COSINE
+                    | binding.HDC_RESERVE_ENCODE_SPARSE, max_batch=256, max_queries=n)
+    torch.cuda.synchronize()
+    facc = torch.zeros((wl.C, wl.D), dtype=torch.float32, device="cuda")
+    facb = torch.zeros((wl.C, wl.D), dtype=torch.float32, device="cuda")
+    pred = torch.empty(n, dtype=torch.int32, device="cuda")
+    cos = torch.empty((n, wl.C), dtype=torch.float32, device="cuda")
+    x, _ = wl.train(n)
+    hv2 = torch.empty_like(hv)
+    xd = torch.from_numpy(x).cuda()
+    free0 = torch.cuda.mem_get_info()[0]
+    ctx.hdc_train_online(hv, yd, facc, 2, 1.0)
+    ctx.hdc_train_online_batched(hv, yd, facb, 256, 2, 1.0)
+    ctx.hdc_search_cosine(hv, facb, pred, cos)
+    ctx.hdc_encode_sparse(xd, hv2)
+    torch.cuda.synchronize()
+    # (the HIP runtime may take a few MB of its own at a kernel's first launch; the scratch these calls
+    # would allocate without hdc_reserve is 64 MB for hdc_train_online alone)
+    assert free0 - torch.cuda.mem_get_info()[0] < (16 << 20), "a call after hdc_reserve allocated device memory"
+    hv_h = hv.cpu().numpy().view(np.uint32)
+    want = oracle.train_online(hv_h, y, wl.D, wl.C, epochs=2, lr=1.0)
+    assert np.max(np.abs(facc.cpu().numpy() - want) / np.maximum(np.abs(want), 1e-3 * np.abs(want).max())) < 1e-4
+    wantb = oracle.train_online_batched(hv_h, y, wl.D, wl.C, 256, 2, 1.0)
+    assert np.max(np.abs(facb.cpu().numpy() - wantb)) <= 1e-5 * np.abs(wantb).max()
+    o_cos, _ = oracle.search_cosine(hv_h, facb.cpu().numpy(), wl.D)
+    assert float(np.max(np.abs(cos.cpu().numpy() - o_cos))) <= 1e-5
+    assert torch.equal(hv2, hv)
+    # bad arguments
+    with pytest.raises(binding.HdcError) as err:
+        ctx.hdc_reserve(binding.HDC_RESERVE_ONLINE_BATCHED, max_batch=0)
+    assert err.value.code == binding.HDC_EINVAL
+    with pytest.raises(binding.HdcError):
+        ctx.hdc_reserve(1 << 9)
+    ctx.close()

@@ -100,10 +100,12 @@ def test_random_shapes_online_paths_match_oracle(seed):
     from paper_2206_04746_amd import binding
     rng = np.random.default_rng(2000 + seed)
     done = 0
-    while done < 6:
-        # (no tiny D here: with a few dozen dimensions class rows are often exactly proportional early
-        # in training, the two best cosines tie exactly, and the summation order decides the step)
-        D = int(rng.choice([1000, 2049, 4097, 10000, 16384, 32768]))
+    undecided = 0     # draws whose per-sample trajectories part at a step the oracle marks as decided by rounding
+    while done < 8:
+        # (with a few dozen dimensions class rows are sometimes exactly proportional early in
+        # training: the two best cosines then tie in exact arithmetic and the summation order
+        # decides the step; such draws are counted and must stay rare)
+        D = int(rng.choice([33, 64, 1000, 2049, 4097, 10000, 16384, 32768]))
         C = int(rng.choice([1, 2, 3, 5, 6, 10, 12, 13, 16, 17, 26]))
         N = int(rng.choice([1, 7, 64, 65, 300, 1000, 2500]))
         epochs = int(rng.choice([1, 2, 3]))
@@ -125,8 +127,14 @@ def test_random_shapes_online_paths_match_oracle(seed):
         acc = torch.zeros((C, D), dtype=torch.float32, device="cuda")
         ctx.hdc_train_online(hv, yd, acc, epochs, lr)
         want, _, margins = oracle.train_online(hv_h, y, D, C, epochs, lr, log=True)
-        if C == 1 or margins.min() > 1e-9:   # no step decided by rounding
-            assert _rel(acc.cpu().numpy(), want) <= 1e-4, what
+        # Every draw is compared.  A mismatch is excused (and counted) only where the oracle itself
+        # logs a step whose two best cosines agree to rounding: there the summation order decides.
+        # (A margin of exactly 0 between all-zero rows, as at every first step, is no such case:
+        # their cosine is 0 by definition on both sides, and both take the lowest class.)
+        if _rel(acc.cpu().numpy(), want) > 1e-4:
+            assert C > 1 and margins.min() <= 1e-9, what
+            undecided += 1
+            print(f"per-sample trajectory parts at a step decided by rounding (oracle margin {margins.min():.3g}): {what}")
         accb = torch.zeros((C, D), dtype=torch.float32, device="cuda")
         ctx.hdc_train_online_batched(hv, yd, accb, batch, epochs, lr)
         assert _rel(accb.cpu().numpy(), oracle.train_online_batched(hv_h, y, D, C, batch, epochs, lr)) <= 1e-4, what
@@ -141,3 +149,4 @@ def test_random_shapes_online_paths_match_oracle(seed):
             assert C > 1 and np.all(top2[:, 1] - top2[:, 0] < 1e-6), what
         ctx.close()
         done += 1
+    assert undecided <= 1, f"{undecided} of {done} draws had a step decided by rounding"

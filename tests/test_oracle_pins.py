@@ -566,3 +566,30 @@ def test_cosine_scores_are_the_ones_online_training_uses():
     if pred[0] != y[0]:
         want[pred[0]] -= np.float32(1.0 - cosv[0, pred[0]]) * s
     np.testing.assert_allclose(nxt, want.astype(np.float32), rtol=1e-6, atol=1e-6)
+
+
+def test_online_exact_tie_between_proportional_rows_goes_to_the_lowest_class():
+    """Two class rows that are exact multiples of one another score every sample identically: in
+    exact arithmetic the two best cosines tie.  With a power-of-two factor the fp64 sums are
+    scaled exactly, the oracle's margin is exactly 0 and the lowest class wins (reading Q12); the
+    step then subtracts from class 0 because the label is 1.  With the factor 3 the tie holds in
+    exact arithmetic only: the logged margin stays within rounding of 0 (far below the 1e-9 below
+    which parity tests do not compare trajectories), whichever way rounding decides it."""
+    D = 16
+    rng = np.random.default_rng(5)
+    s = rng.integers(0, 2, D).astype(np.uint8)
+    t = s.copy()
+    t[:5] ^= 1                                     # a sample that is neither s nor its complement
+    row = (2.0 * s - 1.0).astype(np.float32)
+    hv = pack_bits_lsb(t[None, :])
+    y = np.array([1], dtype=np.int32)
+    acc0 = np.stack([row, 2.0 * row]).astype(np.float32)
+    acc, pred, margin = oracle.train_online(hv, y, D, 2, 1, 1.0, acc=acc0, log=True)
+    assert margin[0] == 0.0 and pred[0] == 0
+    cos = float(np.dot(row, 2.0 * t - 1.0)) / (np.sqrt(float(D)) * np.sqrt(float(D)))
+    w = np.float32(1.0 - cos)
+    assert np.array_equal(acc[1], (2.0 * row + w * (2.0 * t - 1.0)).astype(np.float32))
+    assert np.array_equal(acc[0], (row - w * (2.0 * t - 1.0)).astype(np.float32))
+    acc3 = np.stack([row, 3.0 * row]).astype(np.float32)
+    _, _, margin3 = oracle.train_online(hv, y, D, 2, 1, 1.0, acc=acc3, log=True)
+    assert abs(margin3[0]) < 1e-12
