@@ -154,8 +154,9 @@ int hdc_binarize_classical(hdc_ctx *ctx, const int32_t *acc_dev, const int64_t *
  * dependency between samples is the method's; one call is one dependency chain.
  * epochs >= 0; lr is the paper's learning rate gamma.  Beyond D = 32768 the call runs
  * hdc_train_online_batched with batches of one sample (the same method, three launches per sample).
- * For C <= 12 and D <= 10240 the first call allocates 64 MB of context-owned scratch
- * (HDC_ENOMEM if that fails); later calls only enqueue on `stream`.
+ * Where the fastest kernel applies (C <= 12 with D <= 4096, or C <= 6 with D <= 10240) the first
+ * call allocates 64 MB of context-owned scratch unless hdc_reserve has done so (HDC_ENOMEM if
+ * that fails); later calls only enqueue on `stream`.  Other shapes allocate nothing.
  */
 int hdc_train_online(hdc_ctx *ctx, const uint32_t *hv_dev, const int32_t *labels_dev, int64_t N,
                      int32_t epochs, float lr, float *acc_dev, void *stream);

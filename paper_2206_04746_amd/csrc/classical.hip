@@ -89,17 +89,33 @@ __global__ __launch_bounds__(kGroupThreads) void group_small_kernel(
     }
 }
 
-// Large batches: clear -> count -> scan -> scatter, count and scatter over many blocks.
-__global__ void clear_counts_kernel(uint32_t *cnt, uint32_t *cur, int C) {
-    for (int i = threadIdx.x; i <= C; i += blockDim.x) {
-        cnt[i] = 0;
-        cur[i] = 0;
+// Large batches: count and scatter over many blocks.  The per-class totals and cursors live in
+// cur[0..C), cur[C + 1] counts the blocks that are through; all of them are zero between launches:
+// the block that finds itself last (a ticket from the counter) takes the totals out with exchanges
+// that leave zeros, so no launch is needed to clear them, and does the launch's serial part (the
+// scan over the classes).  These words are only ever touched by device-wide atomics, and a block
+// takes its ticket after its own atomics have returned their values, so the last block's
+// exchanges see every addition; nothing else is passed between blocks, and no fence is used (a
+// device-wide release writes back the whole L2 of the block's die: 20 us here after an encode).
+// One stream at a time per context, as for all of the training scratch.
+__device__ __forceinline__ bool last_block_done(uint32_t *done, uint32_t *flag_s) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t t = atomicAdd(done, 1u);
+        const bool last = t == gridDim.x - 1;
+        if (last) atomicExch(done, 0u);   // (nobody else touches it again in this launch)
+        *flag_s = last;
     }
+    __syncthreads();
+    return *flag_s != 0;
 }
 
+// Count the labels; the last block scans the totals into cnt / off / blk and adds them to class_n.
 __global__ __launch_bounds__(256) void count_labels_kernel(const int32_t *__restrict__ labels,
-                                                            int64_t N, int C, uint32_t *cnt) {
-    extern __shared__ uint32_t h[];
+                                                            int64_t N, int C, uint32_t block_rows,
+                                                            uint32_t *cur, uint32_t *cnt, uint32_t *off,
+                                                            uint32_t *blk, int64_t *class_n) {
+    extern __shared__ uint32_t h[];   // h[C], then the flag
     for (int i = threadIdx.x; i < C; i += 256) h[i] = 0;
     __syncthreads();
     for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)gridDim.x * 256) {
@@ -108,22 +124,25 @@ __global__ __launch_bounds__(256) void count_labels_kernel(const int32_t *__rest
     }
     __syncthreads();
     for (int i = threadIdx.x; i < C; i += 256)
-        if (h[i]) atomicAdd(&cnt[i], h[i]);
-}
-
-__global__ __launch_bounds__(kWave) void scan_counts_kernel(uint32_t *cnt, uint32_t *off, uint32_t *blk,
-                                                            int C, uint32_t block_rows, int64_t *class_n) {
-    scan_counts(cnt, C, block_rows, cnt, off, blk, nullptr, class_n);
+        if (h[i]) {
+            const uint32_t was = atomicAdd(&cur[i], h[i]);
+            asm volatile("" ::"v"(was));   // (waited for: the addition is done before the block's ticket is taken)
+        }
+    if (!last_block_done(cur + C + 1, h + C)) return;
+    for (int i = threadIdx.x; i < C; i += 256) h[i] = atomicExch(&cur[i], 0u);
+    __syncthreads();
+    scan_counts(h, C, block_rows, cnt, off, blk, nullptr, class_n);
 }
 
 // Each block handles contiguous runs of labels: local histogram, ONE global atomic per class to
-// reserve the run's range in perm, then local ranks from LDS cursors.
+// reserve the run's range in perm, then local ranks from LDS cursors.  The last block clears the
+// cursors.
 constexpr int kScatterRun = 4096;
 __global__ __launch_bounds__(256) void scatter_rows_kernel(const int32_t *__restrict__ labels,
                                                             int64_t N, int C,
                                                             const uint32_t *__restrict__ off,
                                                             uint32_t *cur, uint32_t *perm) {
-    extern __shared__ uint32_t h[];   // h[C]: count, then the run's next free slot per class
+    extern __shared__ uint32_t h[];   // h[C]: count, then the run's next free slot per class; then the flag
     for (int64_t run0 = (int64_t)blockIdx.x * kScatterRun; run0 < N;
          run0 += (int64_t)gridDim.x * kScatterRun) {
         const int64_t run1 = min(run0 + (int64_t)kScatterRun, N);
@@ -144,6 +163,77 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const int32_t *__rest
             if (y >= 0 && y < C) perm[atomicAdd(&h[y], 1u)] = (uint32_t)n;
         }
         __syncthreads();
+    }
+    if (!last_block_done(cur + C + 1, h + C)) return;
+    for (int i = threadIdx.x; i < C; i += 256) atomicExch(&cur[i], 0u);
+}
+
+// One or two classes: no totals are needed before the rows are placed.  Class 0 fills perm from
+// the front, class 1 from the back (the order inside a class does not matter to a sum), so one
+// launch counts and scatters; the last block writes cnt / off / blk and adds to class_n.  A
+// block's threads hold the 16384 labels of its run in registers (all loads in flight together);
+// wave ballots count the classes and rank the rows, one atomic per class reserves the run's
+// ranges.
+constexpr int kTwoPer = 64;                 // labels per thread: few blocks, since every block's three atomics
+constexpr int kTwoRun = 256 * kTwoPer;      // on the same words are served one after the other (about 30 ns each)
+__global__ __launch_bounds__(256) void group_two_kernel(const int32_t *__restrict__ labels, int64_t N, int C,
+                                                         uint32_t block_rows, uint32_t *cur, uint32_t *cnt,
+                                                         uint32_t *off, uint32_t *blk, uint32_t *perm,
+                                                         int64_t *class_n) {
+    __shared__ uint32_t wsum[4], base_s[2], flag_s;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+    for (int64_t run0 = (int64_t)blockIdx.x * kTwoRun; run0 < N; run0 += (int64_t)gridDim.x * kTwoRun) {
+        // label i of a thread is number i * 256 + thread of the run: neighbouring lanes, neighbouring labels
+        int32_t y[kTwoPer];
+#pragma unroll
+        for (int i = 0; i < kTwoPer; ++i) {
+            const int64_t n = run0 + i * 256 + threadIdx.x;
+            y[i] = n < N ? labels[n] : -1;
+        }
+        uint32_t mine = 0;   // the wave's rows of class 0 | of class 1 << 16 (wave-uniform)
+#pragma unroll
+        for (int i = 0; i < kTwoPer; ++i)
+            mine += (uint32_t)__popcll(__ballot(y[i] == 0)) + ((uint32_t)__popcll(__ballot(y[i] == 1 && C > 1)) << 16);
+        if (lane == 0) wsum[wave] = mine;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) before += wsum[w];
+            total += wsum[w];
+        }
+        if (threadIdx.x < 2) {
+            const uint32_t k = threadIdx.x == 0 ? (total & 0xffffu) : (total >> 16);
+            base_s[threadIdx.x] = k ? atomicAdd(&cur[threadIdx.x], k) : 0u;
+        }
+        __syncthreads();
+        // the wave's rows in the order (step, lane): the rows of a class in one step go to neighbouring places
+        uint32_t at0 = base_s[0] + (before & 0xffffu), at1 = base_s[1] + (before >> 16);
+#pragma unroll
+        for (int i = 0; i < kTwoPer; ++i) {
+            const uint64_t m0 = __ballot(y[i] == 0), m1 = __ballot(y[i] == 1 && C > 1);
+            const uint32_t row = (uint32_t)(run0 + i * 256 + threadIdx.x);
+            if (y[i] == 0) perm[at0 + (uint32_t)__popcll(m0 & below)] = row;
+            else if (y[i] == 1 && C > 1) perm[(uint32_t)N - 1u - (at1 + (uint32_t)__popcll(m1 & below))] = row;
+            at0 += (uint32_t)__popcll(m0);
+            at1 += (uint32_t)__popcll(m1);
+        }
+        __syncthreads();   // (wsum and base_s are written again in the next run)
+    }
+    if (!last_block_done(cur + C + 1, &flag_s)) return;
+    if (threadIdx.x == 0) {
+        const uint32_t k0 = atomicExch(&cur[0], 0u), k1 = C > 1 ? atomicExch(&cur[1], 0u) : 0u;
+        const uint32_t b0 = (k0 + block_rows - 1) / block_rows, b1 = (k1 + block_rows - 1) / block_rows;
+        cnt[0] = k0, off[0] = 0, blk[0] = 0;
+        class_n[0] += (int64_t)k0;
+        if (C > 1) {
+            cnt[1] = k1, off[1] = (uint32_t)N - k1, blk[1] = b0;
+            class_n[1] += (int64_t)k1;
+            off[2] = (uint32_t)N, blk[2] = b0 + b1;
+        } else {
+            off[1] = k0, blk[1] = b0;
+        }
     }
 }
 
@@ -530,11 +620,9 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
     if (prc != HDC_OK) return prc;
     if (N <= kFusedMaxN) {
         const size_t lds = kFusedSlotWords * sizeof(uint32_t) + (size_t)(N + 1) / 2 * 2 * sizeof(uint16_t);
-        if (lds > 64 * 1024 && lds > c->acc_small_lds) {
+        if (lds > 64 * 1024)   // (per launch: the limit belongs to the function, and another context may have set a smaller one)
             HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(accumulate_small_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            c->acc_small_lds = lds;
-        }
         ProfScope prof(c, HDC_K_ACCUMULATE, s);
         hipLaunchKernelGGL(accumulate_small_kernel, dim3((unsigned)C, (unsigned)(c->Wp / kSliceWords)),
                            dim3(kAccWaves * kWave), lds, s, hv, labels, (int)N, c->W, c->p.D, acc, class_n);
@@ -554,13 +642,16 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
         } else {
             const int64_t runs = (n + kScatterRun - 1) / kScatterRun;
             const unsigned nb = (unsigned)(runs > 4096 ? 4096 : runs);
-            hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(256), 0, s, c->cls_cnt_d, c->cls_cur_d, C);
-            hipLaunchKernelGGL(count_labels_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
-                               c->cls_cnt_d);
-            hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kWave), 0, s, c->cls_cnt_d, c->cls_off_d,
-                               c->cls_blk_d, C, block_rows, class_n);
-            hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), (size_t)C * 4, s, lab0, n, C,
-                               c->cls_off_d, c->cls_cur_d, c->perm_d);
+            if (C <= 2) {
+                const unsigned nb2 = (unsigned)((n + kTwoRun - 1) / kTwoRun);
+                hipLaunchKernelGGL(group_two_kernel, dim3(nb2), dim3(256), 0, s, lab0, n, C, block_rows, c->cls_cur_d,
+                                   c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, c->perm_d, class_n);
+            } else {
+                hipLaunchKernelGGL(count_labels_kernel, dim3(nb), dim3(256), (size_t)(C + 1) * 4, s, lab0, n, C,
+                                   block_rows, c->cls_cur_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, class_n);
+                hipLaunchKernelGGL(scatter_rows_kernel, dim3(nb), dim3(256), (size_t)(C + 1) * 4, s, lab0, n, C,
+                                   c->cls_off_d, c->cls_cur_d, c->perm_d);
+            }
         }
         const int rc = accumulate_grouped(c, plan, hv0, n, C, rb, acc, s);
         if (rc != HDC_OK) return rc;

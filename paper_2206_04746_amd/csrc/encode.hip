@@ -309,13 +309,14 @@ static int launch_encode_kernel(hdc_ctx_impl *c, const uint32_t *item, const uin
         encode_fn fn = which ? HDC_SPLIT(16) : HDC_SPLIT(8);
 #undef HDC_SPLIT
         const size_t lds_split = lds + (size_t)2 * (kSplitWaves - 1) * P * kSliceWords * sizeof(uint32_t);
+        // (the limit belongs to the function, not to a context: another context may have set a smaller one since)
+        if (lds_split > 64 * 1024)
+            HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)lds_split));
         if (c->enc_split_bpc[which] == 0 || c->enc_split_L[which] != c->p.L) {
             hipFuncAttributes attr;
             HDC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(fn)));
             if (attr.sharedSizeBytes != 0) return HDC_ELIMIT;
-            if (lds_split > 64 * 1024)
-                HDC_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_split));
             int n = 0;
             HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(fn),
                                                                  kSplitWaves * kWave, lds_split));

@@ -90,7 +90,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     const int W = c->W, F = p.F, L = p.L;
     c->ct_ready = false;
     c->ct_min_split = -1;
-    if (!c->compact || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > 4 * kCtWaves * kWave) return HDC_OK;   // four features per load; a thread per word of a quarter of a row at least
+    if (!c->expand_d || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > 4 * kCtWaves * kWave) return HDC_OK;   // four features per load; a thread per word of a quarter of a row at least
     const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
     const int thr = (c->votes + 1) / 2;
     const bool tie_votes = c->votes != F;

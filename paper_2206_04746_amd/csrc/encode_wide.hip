@@ -32,12 +32,17 @@
 //      its row word (a table names the column of every bit; constant bits of the model point at
 //      an all-zero or all-one word), transposes 32 x 32 bits in registers and writes the word
 //      of the 32 rows.
-// What bounds it (measured with clock stamps per phase, 342 features, 128 samples a job): T takes
-// 38 us of a job's 60, the matrix instructions alone 20 (32 clocks each, one at a time per SIMD,
-// whatever the number of accumulators in flight) and the vector instructions 18: a wave issues
-// in order, so its own two kinds never overlap, and its SIMD partner fills only part of the
-// gaps.  Finely interleaved streams overlap up to about six vector instructions per matrix
-// instruction; here there are 7.4 and they come in runs.
+// What bounds it (measured with clock stamps per phase, 342 features, 128 samples a job): Q takes 7,
+// T 33 and P 15 us of a job's 56.  In T a SIMD's two waves issue 36 us' worth of work if counted
+// one after the other: 17 us of matrix instructions (32 clocks each, one at a time per SIMD,
+// whatever the number of accumulators in flight) and 14 us of vector instructions (6.5 per matrix
+// instruction: 3.7 for the operands, 2.8 to string the signs together), and that sum is what
+// the phase takes.  A wave issues in order, so its own two kinds never overlap; its SIMD
+// partner's vector instructions overlap a matrix instruction only up to about four per
+// instruction when the accumulators are vector registers (a replica of the loop, with parts
+// taken away, gives the same sum; spreading the sign work over the steps with a second set of
+// accumulators, wave priorities around the matrix instructions, plane reads two steps ahead
+// and barriers that wait for the LDS only changed nothing).
 #include "hdc_internal.h"
 
 #include <algorithm>
@@ -165,7 +170,7 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     const hdc_params &p = c->p;
     const int W = c->W, F = p.F, L = p.L;
     c->wd_ready = false;
-    if (!c->compact || L < 2 || L > 256 || F < 4 || F > 64 * kWdMaxSteps || W > 512) return HDC_OK;
+    if (!c->expand_d || L < 2 || L > 256 || F < 4 || F > 64 * kWdMaxSteps || W > 512) return HDC_OK;
     const int thr = (c->votes + 1) / 2;
     const bool tie_votes = c->votes != F;
 
@@ -600,14 +605,18 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                         }
                 }
                 // bit p of a word of `over` is the sample of register 15 - p of lane half 0 (p < 16) or
-                // register 31 - p of half 1; register r of half h is sample 8 (r / 4) + 4 h + r % 4 of the group
+                // register 31 - p of half 1; register r of half h is sample 8 (r / 4) + 4 h + r % 4 of the group.
+                // The rows go past the caches (streaming stores): a long stream's rows are read again
+                // only after many more have been written, and kept in the L2 they push out the next
+                // job's features and leave the kernel that reads the rows next a cache full of lines
+                // to write back (the accumulating pass over 1M rows: 274 -> 225 us).
                 if (c * kWave + lane_p < W) {
                     uint8_t *out = reinterpret_cast<uint8_t *>(hv + (first + 32 * g) * W);   // wave-uniform
 #pragma unroll
                     for (int p = 0; p < 32; ++p) {
                         const int r = p < 16 ? 15 - p : 31 - p;
                         const int sn = 8 * (r >> 2) + (p < 16 ? 0 : 4) + (r & 3);
-                        if (whole || first + 32 * g + sn < N) *reinterpret_cast<uint32_t *>(out + 4u * (uint32_t)(sn * W + w)) = x[p];
+                        if (whole || first + 32 * g + sn < N) __builtin_nontemporal_store(x[p], reinterpret_cast<uint32_t *>(out + 4u * (uint32_t)(sn * W + w)));
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);   // (a chunk after the other: their registers are the same)

@@ -70,10 +70,11 @@ static inline size_t slice_major(int rows, int r, int w) {
 
 constexpr int64_t kCompactMaxBits = 200000000;   // table bits the host is willing to repack at create
 
-// Decides whether encoding runs on the varying dimensions only and, if so, builds the compact
-// tables, the spreading table and the constant bits (the latter by encoding one sample with the
-// full tables: at an invariant dimension every sample gives the same bit).  Leaves c->compact
-// false on any doubt; only a failed allocation or copy is an error.
+// Builds the spreading table and the constant bits of the level-invariant dimensions (the latter
+// by encoding one sample with the full tables: at an invariant dimension every sample gives the
+// same bit), decides whether the vector kernels encode the varying dimensions only and, if so,
+// builds the compact tables.  Leaves c->compact false (and, before the table is up, c->expand_d
+// null) on any doubt; only a failed allocation or copy is an error.
 static int prepare_compact(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, const uint32_t *tie) {
     const hdc_params &p = c->p;
     const int W = c->W;
@@ -87,7 +88,6 @@ static int prepare_compact(hdc_ctx_impl *c, const uint32_t *item, const uint32_t
         keep[w] = diff;
         varying += __builtin_popcount(diff);
     }
-    if (varying * 4 > (int64_t)p.D * 3) return HDC_OK;   // less than a quarter to gain: not worth a second pass
     const int Wc = (int)((varying + 31) / 32);
     const int Wcp = (Wc + kSliceWords - 1) / kSliceWords * kSliceWords;
 
@@ -132,11 +132,13 @@ static int prepare_compact(hdc_ctx_impl *c, const uint32_t *item, const uint32_t
         for (int w = 0; w < W; ++w) tab[(size_t)7 * W + w] = h[w] & ~keep[w];
     }
 
-    // compact tables in the same padded slice-major layout as the full ones
+    // The table is kept in any case (the contraction encoders take the constant bits from it).
     int rc = dev_alloc(&c->expand_d, tab.size());
     if (rc != HDC_OK) return rc;
     hipError_t e = hipMemcpy(c->expand_d, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    if (varying * 4 > (int64_t)p.D * 3) return HDC_OK;   // less than a quarter to gain: not worth a second pass of the vector kernels
+    // compact tables in the same padded slice-major layout as the full ones
     if (Wc > 0) {
         std::vector<uint32_t> item_h((size_t)c->Fp * Wcp, 0u), level_h((size_t)p.L * Wcp, 0u);
         std::vector<uint32_t> row((size_t)W), crow((size_t)Wc);
@@ -266,12 +268,15 @@ static int create(hdc_ctx **out, const hdc_params *p, const uint32_t *item, cons
         TRY_HIP(hipMemcpy(c->lo_d, lo, (size_t)p->F * 4, hipMemcpyHostToDevice));
         TRY_HIP(hipMemcpy(c->scale_d, scale, (size_t)p->F * 4, hipMemcpyHostToDevice));
     }
-    c->q_rows = kEncodeChunk;
+    // rows of a chunk of the vector encoders: their scratch (2 bytes a feature here, 4 more in the
+    // sparse encoder) stays within 512 MB whatever F is; the chunk loops take any count
+    c->q_rows = std::max<int64_t>(64, std::min<int64_t>(kEncodeChunk, ((int64_t)512 << 20) / ((int64_t)c->Fp * 6) / 64 * 64));
     TRY(dev_alloc(&c->q_d, (size_t)c->q_rows * c->Fp));
     TRY(dev_alloc(&c->bad_labels_d, 1));
     TRY(dev_alloc(&c->cls_cnt_d, (size_t)p->C + 1));
     TRY(dev_alloc(&c->cls_off_d, (size_t)p->C + 1));
-    TRY(dev_alloc(&c->cls_cur_d, (size_t)p->C + 1));
+    TRY(dev_alloc(&c->cls_cur_d, (size_t)p->C + 2));
+    TRY_HIP(hipMemset(c->cls_cur_d, 0, ((size_t)p->C + 2) * 4));   // (the grouping kernels leave it zero again)
     TRY(dev_alloc(&c->cls_blk_d, (size_t)p->C + 1));
     c->perm_rows = kPermRows;
     TRY(dev_alloc(&c->perm_d, (size_t)c->perm_rows));

@@ -55,7 +55,7 @@ struct hdc_ctx_impl {
     int64_t q_rows;       // rows q_d can hold
     uint32_t *cls_cnt_d;  // [C + 1] per-class sample counts of the current training chunk
     uint32_t *cls_off_d;  // [C + 1] exclusive prefix of cls_cnt_d
-    uint32_t *cls_cur_d;  // [C] scatter cursors
+    uint32_t *cls_cur_d;  // [C + 2] per-class totals / scatter cursors and, last, the count of finished blocks; zero between launches
     uint32_t *cls_blk_d;  // [C + 1] exclusive prefix of per-class row-block counts
     uint32_t *perm_d;     // [perm_rows] sample indices grouped by class
     int64_t perm_rows;
@@ -130,7 +130,6 @@ struct hdc_ctx_impl {
     int enc_split_bpc[2];   // blocks of encode_split_kernel (8 / 16 waves) a CU holds (0 = not asked yet) ...
     int enc_split_L[2];     //   ... and the level count that answer was for
     int acc_bpc;            // blocks of accumulate_kernel a CU holds (0 = not asked yet)
-    size_t acc_small_lds;   // dynamic LDS accumulate_small_kernel is cleared for so far
     bool on_attr_set[16];   // online_lds_kernel<CMAX, .>: dynamic-LDS limit raised, by CMAX
 
     // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.

@@ -90,6 +90,28 @@ def test_encode_tables_that_flip_twice_take_the_other_kernel():
     ctx.close()
 
 
+def test_encode_tables_whose_every_dimension_flips_once_take_the_contraction():
+    """Level vectors that run from a vector to its complement (the other usual construction of
+    Sec. III): no dimension is level-invariant, every one flips exactly once."""
+    wl = make_workload(2, D=2048, F=100, L=17, n_train=3000)
+    rng = np.random.default_rng(5)
+    order = rng.permutation(2048)
+    bits = np.zeros((17, 2048), dtype=np.uint8)
+    bits[0] = rng.integers(0, 2, 2048)
+    for l in range(1, 17):
+        bits[l] = bits[l - 1]
+        bits[l, order[(l - 1) * 128:l * 128]] ^= 1
+    assert np.array_equal(bits[16], 1 - bits[0])
+    wl.level = np.packbits(bits, axis=1, bitorder="little").view(np.uint32).reshape(17, 64).copy()
+    x, _ = wl.train(3000)
+    ctx = _ctx(wl)
+    ctx.hdc_profile_enable(True)
+    got = _encode(ctx, x)
+    assert ctx.hdc_profile_read("encode_contract")[1] == 1
+    assert np.array_equal(got, _oracle(wl, x))
+    ctx.close()
+
+
 def test_encode_contraction_many_samples_and_agreement_with_small_calls():
     # more samples than blocks in flight (several jobs per block); the same rows encoded in calls too
     # small for the contraction must give the same bits
