@@ -41,6 +41,7 @@
 // conflicts making it four times the time of the MFMAs.)
 #include "hdc_internal.h"
 #include "bundle.h"
+#include "contract_tables.h"
 
 #include <algorithm>
 #include <vector>
@@ -54,19 +55,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int kCtWaves = 8;        // waves per block at least (the kernel runs with 8 or 12)
 constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
 constexpr int kCtMaxSteps = 14;   // MFMAs per tile: 64 features each
-constexpr int kCtCols = 32;       // dimensions per tile
 constexpr int kCtSamples = 32;    // samples per block and job
-constexpr float kCtNever = -1.0e30f;
-
-// bits 0..2 of every nibble reversed, bit 3 in place
-static inline uint32_t reverse3_host(uint32_t m) {
-    return (m & 0xaaaaaaaau) | ((m & 0x11111111u) << 2) | ((m >> 2) & 0x11111111u);
-}
-
-// Where feature f sits in its word of 32 features, on both sides of the contraction: the kernel
-// turns 32 bin numbers (bytes, four to a word) into bit planes with three rounds of masked swaps
-// among eight words, which leaves feature 4 m + i at bit 8 i + m.
-static inline int feature_bit(int f) { return 8 * (f & 3) + ((f & 31) >> 2); }
 
 template <typename T>
 static int upload(T **dst, const std::vector<T> &src) {
@@ -92,69 +81,19 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     c->ct_min_split = -1;
     if (!c->expand_d || L < 2 || L > (1 << kCtPlanes) || F > 64 * kCtMaxSteps || F < 4 || W > 4 * kCtWaves * kWave) return HDC_OK;   // four features per load; a thread per word of a quarter of a row at least
     const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
-    const int thr = (c->votes + 1) / 2;
-    const bool tie_votes = c->votes != F;
-
-    // threshold of every varying dimension; any dimension that flips twice rules the model out
-    std::vector<std::vector<int>> by_tau((size_t)L);
-    for (int d = 0; d < p.D; ++d) {
-        const int w = d >> 5, b = d & 31;
-        const uint32_t first = (level[w] >> b) & 1u;
-        int tau = 0;
-        for (int l = 1; l < L; ++l) {
-            const uint32_t bit = (level[(size_t)l * W + w] >> b) & 1u;
-            if (!tau && bit != first) tau = l;
-            else if (tau && bit == first) return HDC_OK;
-        }
-        if (tau) by_tau[(size_t)tau].push_back(d);
-    }
-    std::vector<uint32_t> vec((size_t)2 * steps);
+    const ModelView model = {p.D, W, F, L, c->votes, item, level, tie};
+    std::vector<std::vector<int>> by_tau;
+    if (!flip_thresholds(model, &by_tau)) return HDC_OK;   // a dimension that flips twice rules the model out
     for (int v = 0; v < 3; ++v) {   // the row's words in 1 << v ranges, a block per (32 samples, range)
         const int S = 1 << v;
         if (W < S) break;   // every range of words has a word
         if ((W + S - 1) / S > kCtWaves * kWave) continue;   // and a thread for each of its words
-        std::vector<int32_t> tau_of, range_tile;
-        std::vector<uint32_t> src_of((size_t)32 * W, 0xffffffffu);   // [bit][word]: (tile in its range) * 32 + column holding that bit
-        std::vector<float> kc;
-        std::vector<uint32_t> bt;   // [tile][step][lane]: the column's word (bits of every nibble reversed)
-        int range_max = 0;
-        for (int r = 0; r < S; ++r) {
-            const int w_lo = (int)((int64_t)r * W >> v), w_hi = (int)((int64_t)(r + 1) * W >> v);
-            const size_t t_first = tau_of.size();
-            range_tile.push_back((int32_t)t_first);
-            for (int tau = 1; tau < L; ++tau) {
-                std::vector<int> dims;
-                for (int d : by_tau[(size_t)tau])
-                    if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
-                for (size_t at = 0; at < dims.size(); at += kCtCols) {
-                    const size_t t = tau_of.size();
-                    tau_of.push_back(tau);
-                    kc.resize((t + 1) * 32, kCtNever);
-                    bt.resize((t + 1) * steps * 64, 0u);
-                    for (int j = 0; j < 32; ++j) {
-                        std::fill(vec.begin(), vec.end(), 0u);
-                        if (j < kCtCols && at + j < dims.size()) {
-                            const int d = dims[at + j], w = d >> 5, b = d & 31;
-                            const uint32_t l0 = (level[w] >> b) & 1u;
-                            int ones = 0;
-                            for (int f = 0; f < F; ++f) {
-                                const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
-                                ones += (int)bit;
-                                vec[(size_t)f >> 5] |= bit << feature_bit(f);
-                            }
-                            const int tie_vote = tie_votes ? (int)((tie[w] >> b) & 1u) : 0;
-                            src_of[(size_t)b * W + w] = (uint32_t)((t - t_first) * 32 + j);
-                            kc[t * 32 + j] = (float)(ones + tie_vote - thr);   // the bit is set iff 2 <U,B> - |U| <= this
-                        }
-                        for (int k = 0; k < steps; ++k)
-                            for (int h = 0; h < 2; ++h)
-                                bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
-                    }
-                }
-            }
-            range_max = std::max(range_max, (int)(tau_of.size() - t_first));
-        }
-        range_tile.push_back((int32_t)tau_of.size());
+        CtTables tabs;
+        build_contract_tables(model, by_tau, steps, v, &tabs);
+        const std::vector<int32_t> &tau_of = tabs.tau_of, &range_tile = tabs.range_tile;
+        const std::vector<uint32_t> &src_of = tabs.src_of, &bt = tabs.bt;
+        const std::vector<float> &kc = tabs.kc;
+        const int range_max = tabs.range_max;
         if (tau_of.empty()) return HDC_OK;
         if (range_max > kCtWaves * kWave) continue;   // a wave keeps its tiles' thresholds a lane each
         c->ct_tiles[v] = (int)tau_of.size();

@@ -44,6 +44,7 @@
 // accumulators, wave priorities around the matrix instructions, plane reads two steps ahead
 // and barriers that wait for the LDS only changed nothing).
 #include "hdc_internal.h"
+#include "contract_tables.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -71,27 +72,7 @@ constexpr int kWdTiles = 3;          // tiles of one threshold a wave works on a
 constexpr int kWdMaxSteps = 6;
 constexpr size_t kWdLdsLimit = 160 * 1024;
 
-// ---- host: tables of the model ----------------------------------------------------------------
-// 4-bit float (1 sign, 2 exponent, 1 mantissa bit) of a value it can hold exactly
-static uint32_t fp4_of(float v) {
-    const uint32_t s = v < 0.0f ? 8u : 0u;
-    const float a = v < 0.0f ? -v : v;
-    const float mags[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
-    for (uint32_t i = 0; i < 8; ++i)
-        if (mags[i] == a) return s | i;
-    return 0u;   // never asked for
-}
-
-// Where feature f of a step sits on both sides of the contraction: the kernel turns 32 bin numbers
-// (bytes, four to a word) into bit planes with three rounds of masked swaps among eight words,
-// which leaves feature 4 m + i of a lane's 32 at bit 8 i + m: operand word (bit & 3), nibble (bit >> 2).
-static inline int wd_feature_bit(int f) { return 8 * (f & 3) + ((f & 31) >> 2); }
-// the value the sample side has at that place when U = 1
-static inline float wd_sample_value(int f) {
-    const float v[4] = {0.5f, 1.0f, 2.0f, 2.0f};
-    return v[wd_feature_bit(f) & 3];
-}
-
+// ---- host: tables of the model (built in contract_tables.h) ------------------------------------
 template <typename T>
 static int wd_upload(T **dst, const std::vector<T> &src) {
     void *ptr = nullptr;
@@ -105,57 +86,6 @@ static int wd_upload(T **dst, const std::vector<T> &src) {
     e = hipMemcpy(ptr, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
     return e == hipSuccess ? HDC_OK : hip_fail(e, "hipMemcpy");
 }
-
-// Model-side values of the feature slots past F that add up to a target (a multiple of 1/2) when
-// every such slot has U = 1.  Which sums the slots can reach is worked out once per model, slot
-// after slot (in halves; a slot's sample-side value times each 4-bit float that gives a multiple
-// of 1/2); a dimension's values are then read off backwards from its target.
-struct WdBias {
-    int F = 0, slots = 0, bound = 0;
-    std::vector<std::vector<uint8_t>> reach;   // [slot count][sum + bound]: reachable with the first slots
-    static constexpr float kMags[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
-    void prepare(int F_, int slots_end, int max_halves) {
-        F = F_, slots = slots_end - F_, bound = max_halves;
-        reach.assign((size_t)slots + 1, std::vector<uint8_t>((size_t)2 * bound + 1, 0));
-        reach[0][(size_t)bound] = 1;
-        for (int i = 0; i < slots; ++i) {
-            const float a = wd_sample_value(F + i);
-            for (int sum = -bound; sum <= bound; ++sum) {
-                if (!reach[(size_t)i][(size_t)(sum + bound)]) continue;
-                for (float m : kMags)
-                    for (int sg = -1; sg <= 1; sg += 2) {
-                        const float c2 = 2.0f * a * m * (float)sg;   // the slot's contribution in halves
-                        if (c2 != (float)(int)c2) continue;
-                        const int to = sum + (int)c2;
-                        if (to >= -bound && to <= bound) reach[(size_t)i + 1][(size_t)(to + bound)] = 1;
-                    }
-            }
-        }
-    }
-    // false if the slots cannot make the target
-    bool solve(int target_halves, std::vector<float> &val) const {
-        val.assign((size_t)slots, 0.0f);
-        if (target_halves < -bound || target_halves > bound || !reach[(size_t)slots][(size_t)(target_halves + bound)]) return false;
-        int sum = target_halves;
-        for (int i = slots - 1; i >= 0; --i) {
-            const float a = wd_sample_value(F + i);
-            bool found = false;
-            for (int mi = 0; mi < 8 && !found; ++mi)
-                for (int sg = -1; sg <= 1 && !found; sg += 2) {
-                    const float c2 = 2.0f * a * kMags[mi] * (float)sg;
-                    if (c2 != (float)(int)c2) continue;
-                    const int from = sum - (int)c2;
-                    if (from >= -bound && from <= bound && reach[(size_t)i][(size_t)(from + bound)]) {
-                        val[(size_t)i] = kMags[mi] * (float)sg;
-                        sum = from;
-                        found = true;
-                    }
-                }
-            if (!found) return false;   // (never: reach says otherwise)
-        }
-        return sum == 0;
-    }
-};
 
 size_t wide_lds_bytes(int steps, int nb, int groups, int ovs) {
     const size_t planes = (size_t)groups * steps * kWave * (16 + (nb > 6 ? 16 : 8));
@@ -171,115 +101,28 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     const int W = c->W, F = p.F, L = p.L;
     c->wd_ready = false;
     if (!c->expand_d || L < 2 || L > 256 || F < 4 || F > 64 * kWdMaxSteps || W > 512) return HDC_OK;
-    const int thr = (c->votes + 1) / 2;
-    const bool tie_votes = c->votes != F;
-
-    // threshold of every varying dimension; a dimension that flips twice rules the model out
-    std::vector<std::vector<int>> by_tau((size_t)L);
-    int64_t varying = 0;
-    for (int d = 0; d < p.D; ++d) {
-        const int w = d >> 5, b = d & 31;
-        const uint32_t first = (level[w] >> b) & 1u;
-        int tau = 0;
-        for (int l = 1; l < L; ++l) {
-            const uint32_t bit = (level[(size_t)l * W + w] >> b) & 1u;
-            if (!tau && bit != first) tau = l;
-            else if (tau && bit == first) return HDC_OK;
-        }
-        if (tau) by_tau[(size_t)tau].push_back(d), ++varying;
-    }
-    if (!varying) return HDC_OK;
-
-    // K_d of every varying dimension and the most slots any of them needs
-    std::vector<int> ones((size_t)p.D, 0);
-    for (int f = 0; f < F; ++f)
-        for (int d = 0; d < p.D; ++d)
-            ones[(size_t)d] += (int)(((item[(size_t)f * W + (d >> 5)] ^ level[d >> 5]) >> (d & 31)) & 1u);
-    auto target_of = [&](int d) {   // in halves: -(2 K_d + 1); the bit is set iff sum_f U (2B - 1) <= K_d
-        const int tie_vote = tie_votes ? (int)((tie[d >> 5] >> (d & 31)) & 1u) : 0;
-        return -(2 * (ones[(size_t)d] + tie_vote - thr) + 1);
-    };
-    int max_halves = 0;
-    for (int tau = 1; tau < L; ++tau)
-        for (int d : by_tau[(size_t)tau]) max_halves = std::max(max_halves, std::abs(target_of(d)));
-    int steps = 0;
-    std::vector<float> val;
-    WdBias bias;
-    for (int ks = ((F + 63) / 64 + 1) / 2 * 2; ks <= kWdMaxSteps && !steps; ks += 2) {   // the kernel is built for even counts
-        if (ks * 64 == F) continue;
-        bias.prepare(F, ks * 64, max_halves);
-        bool ok = true;
-        for (int tau = 1; tau < L && ok; ++tau)
-            for (int d : by_tau[(size_t)tau])
-                if (!bias.solve(target_of(d), val)) {
-                    ok = false;
-                    break;
-                }
-        if (ok) steps = ks;
-    }
-    if (!steps) return HDC_OK;
+    const ModelView model = {p.D, W, F, L, c->votes, item, level, tie};
+    std::vector<std::vector<int>> by_tau;
+    if (!flip_thresholds(model, &by_tau)) return HDC_OK;   // a dimension that flips twice rules the model out
+    WdTables tabs;
+    build_wide_tables(model, by_tau, kWdMaxSteps, kWdTiles, &tabs);
+    if (!tabs.steps) return HDC_OK;
+    const int steps = tabs.steps, cols = tabs.cols;
     const int nb = L <= 64 ? 6 : 8;
-
-    // work items: a threshold and up to three tiles of its dimensions; columns of `over` in item order
-    std::vector<int32_t> items;          // [n][4]: threshold, first tile, dimensions, first column
-    std::vector<uint32_t> bx;            // [tile][step][lane][4]
-    std::vector<uint32_t> src((size_t)32 * W, 0u);
-    int tiles = 0, cols = 0;
-    for (int tau = 1; tau < L; ++tau) {
-        const std::vector<int> &dims = by_tau[(size_t)tau];
-        for (size_t at = 0; at < dims.size(); at += 32 * kWdTiles) {
-            const int nd = (int)std::min<size_t>(dims.size() - at, 32 * kWdTiles);
-            const int nt = (nd + 31) / 32;
-            items.insert(items.end(), {tau, tiles, nd, cols});
-            bx.resize((size_t)(tiles + nt) * steps * 64 * 4, 0u);
-            for (int i = 0; i < nd; ++i) {
-                const int d = dims[at + i], w = d >> 5, b = d & 31, t = tiles + i / 32, j = i & 31;
-                const uint32_t l0 = (level[w] >> b) & 1u;
-                src[(size_t)b * W + w] = (uint32_t)(cols + i);
-                if (!bias.solve(target_of(d), val)) return HDC_OK;   // (checked above)
-                for (int f = 0; f < steps * 64; ++f) {
-                    uint32_t nib;
-                    if (f < F) {
-                        const uint32_t bit = ((item[(size_t)f * W + w] >> b) & 1u) ^ l0;
-                        nib = fp4_of((bit ? 1.0f : -1.0f) / wd_sample_value(f));
-                    } else {
-                        nib = fp4_of(val[(size_t)(f - F)]);
-                    }
-                    const int k = f >> 6, h = (f >> 5) & 1, at_bit = wd_feature_bit(f);
-                    bx[(((size_t)t * steps + k) * 64 + h * 32 + j) * 4 + (at_bit & 3)] |= nib << (4 * (at_bit >> 2));
-                }
-            }
-            tiles += nt;
-            cols += nd;
-        }
-    }
+    const std::vector<int32_t> &items = tabs.items;
+    const std::vector<uint32_t> &bx = tabs.bx;
     // constant bits of the model: the all-zero word at column `cols`, the all-one word after it
-    const uint32_t *const_row = nullptr;
-    std::vector<uint32_t> tab((size_t)W);
+    std::vector<uint32_t> const_row((size_t)W), src2;
     {
-        hipError_t e = hipMemcpy(tab.data(), c->expand_d + (size_t)7 * W, (size_t)W * 4, hipMemcpyDeviceToHost);
+        hipError_t e = hipMemcpy(const_row.data(), c->expand_d + (size_t)7 * W, (size_t)W * 4, hipMemcpyDeviceToHost);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
-        const_row = tab.data();
     }
-    std::vector<uint8_t> is_var((size_t)p.D, 0);
-    for (int tau = 1; tau < L; ++tau)
-        for (int d : by_tau[(size_t)tau]) is_var[(size_t)d] = 1;
-    for (int w = 0; w < W; ++w)
-        for (int b = 0; b < 32; ++b) {
-            const int d = 32 * w + b;
-            if (d < p.D && is_var[(size_t)d]) continue;
-            src[(size_t)b * W + w] = (uint32_t)(cols + (int)((const_row[w] >> b) & 1u));
-        }
+    if (!wide_place_table(tabs, const_row.data(), p.D, W, &src2)) return HDC_OK;   // (16-bit column numbers; the LDS limit is far below)
     const int ovs = cols + 2;
     int groups = 0;
     for (int g : {4, 2})
         if (!groups && wide_lds_bytes(steps, nb, g, ovs) + 64 <= kWdLdsLimit) groups = g;
     if (!groups) return HDC_OK;
-
-    if (ovs > 65535) return HDC_OK;   // (the kernel's table holds column numbers in 16 bits; the LDS limit is far below)
-    std::vector<uint32_t> src2((size_t)16 * W);   // [bit / 2][word]: the columns of bits 2 i and 2 i + 1
-    for (int i = 0; i < 16; ++i)
-        for (int w = 0; w < W; ++w) src2[(size_t)i * W + w] = src[(size_t)(2 * i) * W + w] | (src[(size_t)(2 * i + 1) * W + w] << 16);
     int rc = wd_upload(&c->wd_items_d, items);
     if (rc == HDC_OK) rc = wd_upload(&c->wd_bx_d, bx);
     if (rc == HDC_OK) rc = wd_upload(&c->wd_src_d, src2);
