@@ -482,6 +482,21 @@ def extras(torch, binding, make_workload):
         "sparse_ms": round(ms_s, 4), "sparse_samples_per_s": round(n3 / ms_s * 1e3, 0),
         "speedup": round(ms_d / ms_s, 2)}
     ctx.close()
+    # the same input on a level table without structure (random level vectors: every dimension flips
+    # many times, so hdc_encode runs the vector kernel on all 313 words): where the sparse call is meant for
+    rng3 = np.random.default_rng(11)
+    level3 = rng3.integers(0, 2 ** 32, size=wl3.level.shape, dtype=np.uint64).astype(np.uint32)
+    level3[:, -1] &= np.uint32((1 << (wl3.D - 32 * (level3.shape[1] - 1))) - 1)
+    ctx = binding.Context(wl3.D, wl3.F, wl3.L, wl3.C, wl3.item, level3, wl3.tie, wl3.lo, wl3.scale, wl3.dtype)
+    ms_d = _timed(torch, lambda: ctx.hdc_encode(x3d, hv3), 3)
+    ms_s = _timed(torch, lambda: ctx.hdc_encode_sparse(x3d, hv3), 3)
+    res["encode_cfg3_random_levels_dense_vs_sparse"] = {
+        "samples": n3, "dense_ms": round(ms_d, 4), "dense_samples_per_s": round(n3 / ms_d * 1e3, 0),
+        "sparse_ms": round(ms_s, 4), "sparse_samples_per_s": round(n3 / ms_s * 1e3, 0),
+        "speedup": round(ms_d / ms_s, 2),
+        "note": "level vectors without structure: no contraction, no level-invariant dimensions; "
+                "hdc_encode = quantize_kernel + encode_kernel over all words"}
+    ctx.close()
     del x3d, hv3
     # --- config 4 shape: online training, one epoch over 7352 samples (a dependency chain)
     wl4 = make_workload(4)
