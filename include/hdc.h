@@ -20,8 +20,17 @@
  *     every table the caller passes and in every vector the library writes.  Matrices
  *     are row-major and contiguous: hv[N][W], acc[C][D], dist[N][C].
  *   - N == 0 is a successful no-op.  A context may be used from one host thread at a
- *     time; work enqueued on different streams with the same context must not overlap
- *     (the context owns small device scratch buffers).
+ *     time.  Work of one context on different streams may overlap only where it shares no
+ *     device scratch of the context:
+ *       hdc_search, hdc_pack, hdc_unpack, hdc_hsum, hdc_binarize_classical and
+ *       hdc_binarize_online use none and may overlap with anything (so the search of one
+ *       chunk of a stream can run beside the encoding of the next);
+ *       hdc_encode and hdc_encode_sparse share the encoders' staging buffers: one at a time;
+ *       hdc_train_classical and hdc_vsum share the training scratch: one at a time;
+ *       hdc_train_online, hdc_train_online_batched and hdc_search_cosine share theirs: one
+ *       at a time.
+ *     With profiling on (hdc_profile_enable) no two calls may overlap.  A second context of
+ *     the same model gives a second set of every buffer.
  */
 #ifndef HDC_H
 #define HDC_H

@@ -97,3 +97,43 @@ def test_reserve_then_calls_allocate_nothing_and_match():
     with pytest.raises(binding.HdcError):
         ctx.hdc_reserve(1 << 9)
     ctx.close()
+
+
+def test_search_of_one_chunk_beside_the_encoding_of_the_next_on_two_streams():
+    """hdc_search uses no scratch of the context, so with one context the search of chunk k may run
+    on one stream while chunk k + 1 is encoded on another (the long stream of configs[4] invites
+    that): the rows and predictions equal those of the same calls made one after the other."""
+    wl = make_workload(5)
+    from paper_2206_04746_amd import binding
+    n = 65000                                    # per chunk: enough for the long-stream encoder
+    x, y = wl.train(3 * n)
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    xd = torch.from_numpy(x).cuda()
+    yd = torch.from_numpy(y.astype(np.int32)).cuda()
+    hv_ref = torch.empty((3 * n, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(xd, hv_ref)
+    acc = torch.zeros((wl.C, wl.D), dtype=torch.int32, device="cuda")
+    cn = torch.zeros(wl.C, dtype=torch.int64, device="cuda")
+    ctx.hdc_train_classical(hv_ref, yd, acc, cn)
+    cls = torch.empty((wl.C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_binarize_classical(acc, cn, cls)
+    pred_ref = torch.empty(3 * n, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hv_ref, cls, pred_ref, None)
+    torch.cuda.synchronize()
+
+    hv = torch.full((3 * n, ctx.W), -1, dtype=torch.int32, device="cuda")
+    pred = torch.full((3 * n,), -1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    s_enc, s_srch = torch.cuda.Stream(), torch.cuda.Stream()
+    done = [torch.cuda.Event() for _ in range(3)]
+    for k in range(3):
+        with torch.cuda.stream(s_enc):
+            ctx.hdc_encode(xd[k * n:(k + 1) * n], hv[k * n:(k + 1) * n])
+            done[k].record(s_enc)
+        with torch.cuda.stream(s_srch):
+            s_srch.wait_event(done[k])           # chunk k is searched once it is encoded, beside the encoding of k + 1
+            ctx.hdc_search(hv[k * n:(k + 1) * n], cls, pred[k * n:(k + 1) * n], None)
+    torch.cuda.synchronize()
+    assert torch.equal(hv, hv_ref)
+    assert torch.equal(pred, pred_ref)
+    ctx.close()
