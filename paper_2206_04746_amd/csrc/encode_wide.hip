@@ -131,6 +131,7 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     c->wd_nb = nb;
     c->wd_groups = groups;
     c->wd_items = (int)(items.size() / 4);
+    c->wd_tiles = tabs.tiles;
     c->wd_ovs = ovs;
     c->wd_ready = true;
     return HDC_OK;
@@ -152,7 +153,7 @@ template <int KS, int NB, bool kU8, int G>
 __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
     const float *__restrict__ scale, int W, const int4 *__restrict__ items, int n_items,
-    const wd_u32x4 *__restrict__ bx, const uint32_t *__restrict__ src_of, int ovs, uint32_t *__restrict__ hv) {
+    const wd_u32x4 *__restrict__ bx, const uint32_t *__restrict__ src_of, int ovs, int stagger, uint32_t *__restrict__ hv) {
     extern __shared__ __attribute__((aligned(16))) uint32_t wd_lds[];
     constexpr int kWdWaves = wd_waves_of(G), kWdThreads = kWdWaves * kWave;
     constexpr int kSamples = 32 * G;
@@ -176,6 +177,16 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
 
     wd_u32x4 bm[TB][KS];
     const int64_t jobs = (N + kSamples - 1) / kSamples;
+    // All blocks start together and a job takes every block the same time, so for their first ten
+    // jobs or so (until they have drifted apart by themselves) the whole chip loads, computes and
+    // stores in step, and the loads and stores of 256 blocks at once queue up behind each other.
+    // Blocks therefore start up to half a job apart (measured on 1M samples: 4 % of the launch).
+    // The wait ends with the clock, and after a bounded number of naps whatever the clock does.
+    if (stagger > 0) {
+        const uint64_t t0 = wall_clock64();
+        const uint64_t ticks = (uint64_t)((blockIdx.x >> 3) & 7) * (uint64_t)stagger;   // 10 ns each; neighbours in a die start apart
+        for (int nap = 0; nap < 20000 && wall_clock64() - t0 < ticks; ++nap) __builtin_amdgcn_s_sleep(8);
+    }
     for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
         // ---- Q: bin numbers, a byte each; slots past F get all ones (U = 1 at every threshold).
         // A thread takes four neighbouring features (the same in every round) of kPerRound samples
@@ -480,9 +491,17 @@ static int launch_wide(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out,
     const int64_t jobs = (n + 32 * G - 1) / (32 * G);
     const int per_cu = G == 2 && 2 * (lds + 1024) <= kWdLdsLimit ? 2 : 1;
     const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus * per_cu);
+    // Start offsets between blocks (see the kernel): a sixteenth of a job's time per step, eight steps, from ten
+    // jobs per block on.  A job takes about 3.2 times what its matrix instructions take alone
+    // (15.2 ns each, four SIMDs).
+    int stagger = 0;
+    if (jobs >= 10 * blocks) {
+        const double job_us = (double)c->wd_tiles * KS * G * 0.0152 / 4.0 * 3.2;
+        stagger = (int)std::min(job_us * 100.0 / 16.0, 1000.0);   // in 10 ns; at most 10 us a step
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(wd_waves_of(G) * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,
                        c->scale_d, c->W, reinterpret_cast<const int4 *>(c->wd_items_d), c->wd_items,
-                       reinterpret_cast<const wd_u32x4 *>(c->wd_bx_d), c->wd_src_d, c->wd_ovs, out);
+                       reinterpret_cast<const wd_u32x4 *>(c->wd_bx_d), c->wd_src_d, c->wd_ovs, stagger, out);
     HDC_HIP(hipGetLastError());
     return HDC_OK;
 }

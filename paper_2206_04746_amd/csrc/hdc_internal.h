@@ -118,6 +118,7 @@ struct hdc_ctx_impl {
     bool wd_ready;
     int wd_steps, wd_nb, wd_groups;   // matrix instructions per tile, bit planes of a bin number (6 or 8), groups of 32 samples per job
     int wd_items;               // work items: a threshold and up to three tiles of its dimensions
+    int wd_tiles;               // tiles of 32 dimensions of all items together
     int wd_ovs;                 // words per group of the kernel's column array: the varying dimensions, an all-zero and an all-one word
     int32_t *wd_items_d;        // [wd_items][4] threshold, first tile, dimensions, first column
     uint32_t *wd_bx_d;          // [tiles][wd_steps][64][4] model-side operands: 4-bit floats +-1 / (sample-side value), bias in the slots past F
