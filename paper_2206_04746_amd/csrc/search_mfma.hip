@@ -302,7 +302,8 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     }
 }
 
-constexpr int64_t kMfmaQueries = 32768;   // from here on there is a job for most blocks of the chip
+constexpr int64_t kMfmaQueries = 20480;        // from here on with 9 to 12 classes (measured against the vector kernels at D = 10000)
+constexpr int64_t kMfmaQueriesMany = 8192;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 14 us   // from here on there is a job for most blocks of the chip
 
 template <int P>
 static int launch_mfma(hdc_ctx_impl *c, const RowGeo &g, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
@@ -332,7 +333,7 @@ bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint3
     const int C = c->p.C, W = c->W;
     // fewer classes: the row-per-16-lanes kernel is as fast or faster (this one takes the same time for
     // any number of classes: at D = 10000, 0.25 ms for a million queries, 0.29 ms with distances)
-    if (N < kMfmaQueries || C < 9 || C > kOnes || W < 4) return false;
+    if (N < (C >= 13 ? kMfmaQueriesMany : kMfmaQueries) || C < 9 || C > kOnes || W < 4) return false;
     const RowGeo g = row_geo(W);
     if (g.lds_bytes > 160 * 1024) return false;   // D above 10240 or so: the job's rows would not fit in LDS
     switch (g.pieces) {

@@ -223,9 +223,10 @@ def test_search_bit_exact(D, C, N):
                                    (8001, 8, 8197), (10000, 10, 8195), (10240, 1, 8193), (12000, 26, 8194),
                                    (16384, 16, 8195), (24000, 5, 8193), (31000, 4, 8194), (32768, 2, 8195),
                                    (10000, 40, 8193),
-                                   # from 32768 queries on, 9 to 31 classes, D up to 10240: the
-                                   # matrix-core kernel (64 rows per block at a time, a row split in two halves, every
-                                   # half in eight slices); around it the shapes that just miss it
+                                   # from 8192 queries on with 13 to 31 classes, from 20480 on with 9 to 12, D up
+                                   # to 10240: the matrix-core kernel (64 rows per block at a time, a row split in
+                                   # two halves, every half in eight slices); around it the shapes that just miss it
+                                   (10000, 26, 8192), (10000, 26, 8191), (10000, 13, 8193), (10000, 12, 20480), (10000, 12, 20479),
                                    (10000, 26, 32771), (10000, 12, 32833), (2049, 31, 32768), (128, 19, 40001),
                                    (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 8, 32768), (10000, 9, 32768), (6400, 31, 32770), (10030, 13, 32785), (10240, 20, 32768), (10241, 20, 32768)])
 def test_search_long_streams_bit_exact(D, C, N):
