@@ -221,7 +221,7 @@ def main() -> int:
                                         "frac_hbm": round(row_bytes * per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
     if se_n:
         us = se_ms * 1e3 / se_n
-        kernels["search_kernel"] = {"avg_launch_us": round(us, 1), "launches": se_n,
+        kernels["search_rows16_kernel" if wl.C <= 8 else "search_mfma_kernel"] = {"avg_launch_us": round(us, 1), "launches": se_n,
                                     "frac_hbm": round(row_bytes * per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
     # HBM fractions of the two legs the metric names, from the step's own stage times: what the
     # method must move per window (features in, row out, row and label in again for training; row
