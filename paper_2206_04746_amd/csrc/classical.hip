@@ -6,10 +6,13 @@
 // keeps the 32 counts bit-sliced (plane i = bit i of each count); adding rows is carry-save
 // arithmetic with v_bitop3_b32 full adders, a few VALU ops per streamed word, so the kernel
 // stays HBM-bound.  Rows are first grouped by class (a counting sort of the labels, only the
-// row indices move).  A block then takes a run of rows of ONE class: its waves cover the
-// slices of 64 word columns side by side (so rows are read as whole contiguous lines) times a
-// few row groups; the row groups' bit-sliced counts are added through LDS and written out as
-// 16-bit partial sums, one row of partials per block.  A second, tiny kernel adds the partial
+// row indices move).  A block then takes a run of rows of ONE class.  Rows of up to 320 words:
+// each of its 16 waves reads whole rows of a share of the run, a lane the words l, l + 64, ...
+// (accumulate_rows_kernel: no wave waits for another while it streams).  Wider rows: its waves
+// cover the slices of 64 word columns side by side (so rows are read as whole contiguous
+// lines) times a few row groups, meeting at a barrier every 16 rows (accumulate_kernel).  The
+// waves' bit-sliced counts are added through LDS and written out as 16-bit partial sums, one
+// row of partials per block.  A second, tiny kernel adds the partial
 // rows of each class into acc.  (Flushing blocks straight into acc with atomics was measured at
 // 10-25 G atomics/s, several times slower than streaming the rows themselves.)  Everything is
 // integer addition, so any order gives the same bits.
@@ -356,6 +359,174 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
     }
 }
 
+// ---- vertical count, a wave per row (rows of up to 512 words) -----------------------------------
+// grid.x = work item as above.  The block's 16 waves take a sixteenth of the item's rows each, a
+// contiguous run; a wave reads whole rows, lane l the words l, l + 64, ... (kpl of them), eight
+// rows at a time, and keeps a set of count planes per word position.  As soon as a position's
+// eight words have been counted, the same eight registers are asked for again from the next
+// eight rows, so a lane always has 8 kpl loads in flight and the waves never wait for one
+// another: no barrier in the stream.  A wave counts at most 248 rows (eight planes); the waves'
+// counts meet in LDS in two rounds (waves 8..15 into 0..7, then 1..7 into 0), and the block
+// total, twelve planes, goes back through LDS so that kpl waves turn a position each into
+// 16-bit sums.  Dynamic LDS: 8 x kpl x 9 planes of 64 words.
+constexpr int kRowsWaves = 16;
+constexpr int kRowsPlanes = 8;                      // a wave counts at most 255 rows ...
+constexpr int kRowsPerWaveMax = 248;                // ... in steps of 8
+template <int KPL>
+__global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_rows_kernel(
+    const uint32_t *__restrict__ hv, const uint32_t *__restrict__ perm, const uint32_t *__restrict__ cnt,
+    const uint32_t *__restrict__ off, const uint32_t *__restrict__ blk, int C, int W, int Wp, int rpw,
+    uint32_t *__restrict__ partial) {
+    extern __shared__ uint32_t merge[];
+    const uint32_t item = blockIdx.x;
+    if (item >= blk[C]) return;
+    int lo = 0, hi = C - 1;   // class of this work item: last c with blk[c] <= item (blk is non-decreasing)
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (blk[mid] <= item) lo = mid; else hi = mid - 1;
+    }
+    const int c = lo;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t first = __builtin_amdgcn_readfirstlane((item - blk[c]) * (uint32_t)(kRowsWaves * rpw) + (uint32_t)(wave * rpw));
+    const uint32_t total = __builtin_amdgcn_readfirstlane(cnt[c]);
+    // (wave-uniform, and said so: the row numbers below then come by scalar loads)
+    const uint32_t rows = __builtin_amdgcn_readfirstlane(first < total ? min((uint32_t)rpw, total - first) : 0u);
+    const_u32_ptr idx = (const_u32_ptr)(uintptr_t)(perm + __builtin_amdgcn_readfirstlane(off[c]) + first);
+
+    uint32_t pl[KPL][12];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int i = 0; i < 12; ++i) pl[k][i] = 0;
+    int at[KPL];         // the lane's words of a row (clamped: a lane past the row's end reads the last word and drops it)
+    uint32_t mine[KPL];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) {
+        at[k] = min(lane + k * kWave, W - 1);
+        mine[k] = lane + k * kWave < W ? 0xffffffffu : 0u;
+    }
+    uint32_t x[KPL][8];
+    // Eight whole rows at a time with nothing conditional about the loads and no use of a loaded
+    // word before its turn to be counted (a select on it would make the wave wait for every
+    // load at once); the up to seven rows left over come afterwards, masked.  Lanes past the end
+    // of a row read its last word again; their counts are dropped at the end.
+    auto load8 = [&](const uint32_t r0, const int k) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[k][j] = __builtin_nontemporal_load(hv + (int64_t)idx[r0 + j] * W + at[k]);
+    };
+    auto add8 = [&](const int k) {
+        uint32_t a, b, p, c2a, c2b, c3;
+        uint32_t *q = pl[k];
+        p = q[0]; a = maj3(p, x[k][0], x[k][1]); p = xor3(p, x[k][0], x[k][1]);
+        b = maj3(p, x[k][2], x[k][3]); p = xor3(p, x[k][2], x[k][3]); q[0] = p;
+        p = q[1]; c2a = maj3(p, a, b); q[1] = xor3(p, a, b);
+        p = q[0]; a = maj3(p, x[k][4], x[k][5]); p = xor3(p, x[k][4], x[k][5]);
+        b = maj3(p, x[k][6], x[k][7]); p = xor3(p, x[k][6], x[k][7]); q[0] = p;
+        p = q[1]; c2b = maj3(p, a, b); q[1] = xor3(p, a, b);
+        p = q[2]; c3 = maj3(p, c2a, c2b); q[2] = xor3(p, c2a, c2b);
+#pragma unroll
+        for (int i = 3; i < kRowsPlanes; ++i) {
+            const uint32_t t = q[i] & c3;
+            q[i] ^= c3;
+            c3 = t;
+        }
+    };
+    const uint32_t full = rows & ~7u;
+    if (full > 0) {   // wave-uniform
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) load8(0, k);
+        for (uint32_t r0 = 0; r0 < full; r0 += 8) {
+            const uint32_t next = min(r0 + 8, full - 8);   // (after the last batch: the same again, unused)
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                add8(k);
+                load8(next, k);
+            }
+        }
+    }
+    if (rows > full) {   // wave-uniform
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[k][j] = hv[(int64_t)idx[min(full + j, rows - 1)] * W + at[k]];
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[k][j] = full + j < rows ? x[k][j] : 0u;
+            add8(k);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int i = 0; i < kRowsPlanes; ++i) pl[k][i] &= mine[k];
+
+    // the waves' counts meet: a (planes)-bit number per lane and position added to another
+    auto park = [&](const int slot, const int planes) {
+        uint32_t *dst = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int i = 0; i < 9; ++i)
+                if (i < planes) dst[(k * 9 + i) * kWave] = pl[k][i];
+    };
+    auto take = [&](const int slot, const int planes) {   // pl += the parked number of `planes` planes
+        const uint32_t *src = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            uint32_t carry = 0;
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                const uint32_t a = pl[k][i], b = i < planes ? src[(k * 9 + i) * kWave] : 0u;
+                pl[k][i] = xor3(a, b, carry);
+                carry = maj3(a, b, carry);
+            }
+        }
+    };
+    if (wave >= 8) park(wave - 8, kRowsPlanes);
+    __syncthreads();
+    if (wave < 8) take(wave, kRowsPlanes);      // at most 496 rows: nine planes
+    __syncthreads();
+    if (wave >= 1 && wave < 8) park(wave, 9);
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll 1
+        for (int w = 1; w < 8; ++w) take(w, 9);   // the block total stays below 2^12
+    }
+    __syncthreads();
+    // the total back through LDS, twelve planes per position: wave k turns position k into 16-bit sums
+    uint32_t *tot = merge;
+    if (wave == 0) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int i = 0; i < 12; ++i) tot[(k * 12 + i) * kWave + lane] = pl[k][i];
+    }
+    __syncthreads();
+    if (wave >= KPL) return;
+    const int col = wave * kWave + lane;
+    if (col >= Wp) return;
+    uint32_t t12[12];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) t12[i] = tot[(wave * 12 + i) * kWave + lane];
+    uint4 *dst = reinterpret_cast<uint4 *>(partial + ((size_t)item * Wp + col) * 16);   // (pad columns store zeros)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        uint32_t w4[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int b0 = (q4 * 4 + k) * 2;
+            uint32_t v = 0;
+#pragma unroll
+            for (int i = 0; i < 12; ++i)
+                v |= (((t12[i] >> b0) & 1u) << i) | (((t12[i] >> (b0 + 1)) & 1u) << (16 + i));
+            w4[k] = v;
+        }
+        dst[q4] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    }
+}
+
 // ---- small batches: grouping, counting and the update of acc in one launch ----------------------
 // Up to kFusedMaxN rows.  grid = (C, slices of 64 word columns), 16 waves per block.  A block takes
 // class c and one slice: it lists the rows of the class in LDS by itself (every block reads the few
@@ -549,13 +720,43 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__
 // that the whole chunk is ONE round of blocks (a second, nearly empty round would double the
 // time), capped so that a block's count fits its planes, and a multiple of the 8-row step.
 struct AccPlan {
+    bool rows;        // rows of at most 320 words: the wave-per-row kernel (rg = its 16 waves, rb = rows per wave)
     int spb, rg, ychunks;
     int64_t cap;      // blocks per launch that run at once, minus the C possible partial blocks
     int64_t rb_max;   // most rows per wave
     int64_t rows_max; // most rows one launch takes in a single round
 };
+constexpr int kRowsMaxKpl = 5;   // word positions per lane the wave-per-row kernel is built for (its registers)
+static size_t rows_lds(int kpl) { return (size_t)8 * kpl * 9 * kWave * sizeof(uint32_t); }
+static const void *rows_kernel(int kpl) {
+    switch (kpl) {
+    case 1: return reinterpret_cast<const void *>(accumulate_rows_kernel<1>);
+    case 2: return reinterpret_cast<const void *>(accumulate_rows_kernel<2>);
+    case 3: return reinterpret_cast<const void *>(accumulate_rows_kernel<3>);
+    case 4: return reinterpret_cast<const void *>(accumulate_rows_kernel<4>);
+    default: return reinterpret_cast<const void *>(accumulate_rows_kernel<5>);
+    }
+}
 static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
     const int nslices = c->Wp / kSliceWords;
+    p->rows = nslices <= kRowsMaxKpl;
+    if (p->rows) {
+        p->spb = 1, p->rg = kRowsWaves, p->ychunks = 1;
+        int bpc = c->acc_bpc;
+        if (bpc == 0) {
+            if (rows_lds(nslices) > 64 * 1024)
+                HDC_HIP(hipFuncSetAttribute(rows_kernel(nslices), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(nslices)));
+            HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, rows_kernel(nslices), kRowsWaves * kWave, rows_lds(nslices)));
+            if (bpc < 1) bpc = 1;
+            c->acc_bpc = bpc;
+        }
+        p->cap = (int64_t)c->num_cus * bpc - c->p.C;
+        if (p->cap < 1) p->cap = 1;
+        p->rb_max = kRowsPerWaveMax;
+        p->rows_max = p->cap * p->rg * p->rb_max;
+        if (p->rows_max > c->perm_rows) p->rows_max = c->perm_rows;
+        return HDC_OK;
+    }
     p->spb = nslices < kAccWaves ? nslices : kAccWaves;
     p->rg = kAccWaves / p->spb;
     p->ychunks = (nslices + p->spb - 1) / p->spb;
@@ -592,11 +793,20 @@ int64_t classical_max_items(hdc_ctx_impl *c) {
 static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32_t *hv0, int64_t n,
                               int classes, int64_t rb, int32_t *acc, hipStream_t s) {
     const int spb = plan.spb, rg = plan.rg, ychunks = plan.ychunks;
+    const int rb32 = (int)rb;
     const uint32_t block_rows = (uint32_t)(rg * rb);
     const int64_t items = (n + block_rows - 1) / block_rows + classes;
     if (items > c->partial_items) return HDC_ELIMIT;   // cannot happen: sized for the worst case
     const size_t lds = (size_t)(rg - 1) * spb * kWavePlanes * kWave * sizeof(uint32_t);
-    {
+    if (plan.rows) {
+        const int kpl = c->Wp / kSliceWords;
+        if (rows_lds(kpl) > 64 * 1024)   // (per launch: the limit belongs to the function, not to a context)
+            HDC_HIP(hipFuncSetAttribute(rows_kernel(kpl), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(kpl)));
+        ProfScope prof(c, HDC_K_ACCUMULATE, s);
+        void *args[] = {(void *)&hv0, (void *)&c->perm_d, (void *)&c->cls_cnt_d, (void *)&c->cls_off_d, (void *)&c->cls_blk_d,
+                        (void *)&classes, (void *)&c->W, (void *)&c->Wp, (void *)&rb32, (void *)&c->partial_d};
+        HDC_HIP(hipLaunchKernel(rows_kernel(kpl), dim3((unsigned)items), dim3(kRowsWaves * kWave), args, rows_lds(kpl), s));
+    } else {
         ProfScope prof(c, HDC_K_ACCUMULATE, s);
         hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks), dim3(spb * rg * kWave),
                            lds, s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, classes, c->W,
