@@ -103,7 +103,8 @@ int hdc_destroy(hdc_ctx *ctx);
  * model whose level vectors change every dimension at most once from one level to the next
  * (at most 256 levels, 4 to 896 features) run as a contraction over the features on the matrix
  * cores (long streams, 128 samples or more per compute unit, of models of at most about 370
- * features in a form of their own), all others on the vector unit.
+ * features, or about 630 with at most 64 levels, in a form of their own), all others on the
+ * vector unit.
  */
 int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);
 

@@ -1,5 +1,5 @@
 // ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features on the
-// matrix cores, for long streams of samples and models of at most 384 feature slots: the form of
+// matrix cores, for long streams of samples and models of at most 640 feature slots: the form of
 // encode_contract.hip rearranged so that the vector unit has less to do per matrix instruction.
 //
 // As there, a dimension d that flips once along the levels, at level t_d, gets from feature f the
@@ -66,10 +66,12 @@ typedef uint32_t wd_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   
 // the LDS holds both, so that one block's tile phase fills the other's loads and stores.
 constexpr int wd_waves_of(int groups) { return 2 * groups; }
 constexpr int kWdTiles = 3;          // tiles of one threshold a wave works on at a time: their model-side operands stay in registers
-// Matrix instructions per tile, 64 features each.  Beyond 6 the resident operands of three tiles
-// (12 registers a step) no longer fit beside the accumulators, and with fewer tiles per turn the
-// vector work per matrix instruction is that of encode_contract.hip again, which such models take.
-constexpr int kWdMaxSteps = 6;
+constexpr int kWdTilesLong = 2;      // ... of models of more than 6 steps (12 registers a step and tile)
+constexpr int wd_tiles_of(int steps) { return steps > 6 ? kWdTilesLong : kWdTiles; }
+// Matrix instructions per tile, 64 features each, at most.  Up to 6 steps a wave keeps the operands
+// of three tiles (all the dimensions of a threshold at 79 per threshold); beyond, of two: the
+// operands of three tiles of ten steps do not fit beside the accumulators.
+constexpr int kWdMaxSteps = 10;
 constexpr size_t kWdLdsLimit = 160 * 1024;
 
 // ---- host: tables of the model (built in contract_tables.h) ------------------------------------
@@ -106,6 +108,7 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     if (!flip_thresholds(model, &by_tau)) return HDC_OK;   // a dimension that flips twice rules the model out
     WdTables tabs;
     build_wide_tables(model, by_tau, kWdMaxSteps, kWdTiles, &tabs);
+    if (tabs.steps > 6) build_wide_tables(model, by_tau, kWdMaxSteps, kWdTilesLong, &tabs);   // (the steps come out the same)
     if (!tabs.steps) return HDC_OK;
     const int steps = tabs.steps, cols = tabs.cols;
     const int nb = L <= 64 ? 6 : 8;
@@ -123,6 +126,7 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     for (int g : {4, 2})
         if (!groups && wide_lds_bytes(steps, nb, g, ovs) + 64 <= kWdLdsLimit) groups = g;
     if (!groups) return HDC_OK;
+    if (steps > 6 && groups != 4) return HDC_OK;   // (measured: with two groups a job the other kernel is faster for such models)
     int rc = wd_upload(&c->wd_items_d, items);
     if (rc == HDC_OK) rc = wd_upload(&c->wd_bx_d, bx);
     if (rc == HDC_OK) rc = wd_upload(&c->wd_src_d, src2);
@@ -160,10 +164,11 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
     constexpr int kQuads = KS * 16;                              // groups of four features per sample row, pad slots included
     constexpr int kPerRound = kWdThreads / kQuads;               // samples the block loads at a time
     constexpr int kRounds = (kSamples + kPerRound - 1) / kPerRound;
+    constexpr int kBatch = kRounds <= 26 ? kRounds : (kRounds + 1) / 2;   // rounds in flight together (their registers)
     constexpr int kRowBytes = KS * 64 + 16;
     constexpr int kRawRegs = kU8 ? 1 : 4;
     constexpr int kTouches = (kSamples * KS * 64 * (kU8 ? 1 : 4) / 128 + kWdThreads - 1) / kWdThreads;   // 128-byte lines of a job's features per thread
-    constexpr int TB = kWdTiles;
+    constexpr int TB = wd_tiles_of(KS);
     uint32_t *ticket = wd_lds;   // the next item of the tile phase (16 bytes in front of the planes)
     wd_u32x4 *planes_a = reinterpret_cast<wd_u32x4 *>(wd_lds + 4);
     typedef typename std::conditional<(NB > 6), wd_u32x4, wd_u32x2>::type plane_b_t;
@@ -208,46 +213,50 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
             const int64_t first = job * kSamples;
             const int last = (int)min((int64_t)(kSamples - 1), N - 1 - first);   // (rows past N: the last row)
             const uint8_t *base = reinterpret_cast<const uint8_t *>(feats) + first * F * (kU8 ? 1 : 4);
-            uint32_t raw[kRounds][kRawRegs];
-#pragma unroll
-            for (int r = 0; r < kRounds; ++r) {
-                const int sn = min(r * kPerRound + s_in, last);
-                if (kU8) {
-                    const uint8_t *row = base + (sn * F + fq);
-                    raw[r][0] = (uint32_t)row[0] | ((uint32_t)row[1] << 8) | ((uint32_t)row[2] << 16) | ((uint32_t)row[3] << 24);
-                } else {
-                    const wd_u32x4_a4 v = *reinterpret_cast<const wd_u32x4_a4 *>(base + (size_t)(uint32_t)((sn * F + fq) * 4));
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) raw[r][i] = v[i];
-                }
-            }
             float lo_f[4], sc_f[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 lo_f[i] = kU8 ? 0.0f : lo[fq + i];
                 sc_f[i] = kU8 ? 0.0f : scale[fq + i];
             }
-            if (s_in < kPerRound) {
 #pragma unroll
-                for (int r = 0; r < kRounds; ++r) {
-                    const int sn = r * kPerRound + s_in;
-                    uint32_t word = 0;
-                    if (feats_mine) {
+            for (int r0 = 0; r0 < kRounds; r0 += kBatch) {   // (one turn up to 384 feature slots; the turns one after the other)
+                uint32_t raw[kBatch][kRawRegs];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            uint32_t q;
-                            if (kU8) {
-                                q = (((raw[r][0] >> (8 * i)) & 0xffu) * (uint32_t)L) >> 8;
-                            } else {   // the bin rule without its branches: NaN and negatives go to 0 through the maximum
-                                const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[r][i]), lo_f[i]), sc_f[i]);
-                                q = (uint32_t)(int)fminf(fmaxf(t, 0.0f), (float)(L - 1));
-                            }
-                            word |= q << (8 * i);
-                        }
-                        word = (word >> q_shift) & keep;
+                for (int rr = 0; rr < kBatch; ++rr) {
+                    const int sn = min((r0 + rr) * kPerRound + s_in, last);
+                    if (kU8) {
+                        const uint8_t *row = base + (sn * F + fq);
+                        raw[rr][0] = (uint32_t)row[0] | ((uint32_t)row[1] << 8) | ((uint32_t)row[2] << 16) | ((uint32_t)row[3] << 24);
+                    } else {
+                        const wd_u32x4_a4 v = *reinterpret_cast<const wd_u32x4_a4 *>(base + (size_t)(uint32_t)((sn * F + fq) * 4));
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) raw[rr][i] = v[i];
                     }
-                    if (sn < kSamples) over[(sn * kRowBytes + f0) >> 2] = word | ~keep;
                 }
+                if (s_in < kPerRound) {
+#pragma unroll
+                    for (int rr = 0; rr < kBatch; ++rr) {
+                        const int sn = (r0 + rr) * kPerRound + s_in;
+                        uint32_t word = 0;
+                        if (feats_mine) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                uint32_t q;
+                                if (kU8) {
+                                    q = (((raw[rr][0] >> (8 * i)) & 0xffu) * (uint32_t)L) >> 8;
+                                } else {   // the bin rule without its branches: NaN and negatives go to 0 through the maximum
+                                    const float t = __fmul_rn(__fsub_rn(__builtin_bit_cast(float, raw[rr][i]), lo_f[i]), sc_f[i]);
+                                    q = (uint32_t)(int)fminf(fmaxf(t, 0.0f), (float)(L - 1));
+                                }
+                                word |= q << (8 * i);
+                            }
+                            word = (word >> q_shift) & keep;
+                        }
+                        if (sn < kSamples) over[(sn * kRowBytes + f0) >> 2] = word | ~keep;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         __syncthreads();
@@ -378,7 +387,7 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                     group(g0 + kUnitGroups - 1, nt_c, std::true_type{});
                 };
                 if (nt == 1) run(std::integral_constant<int, 1>{});
-                else if (nt == 2) run(std::integral_constant<int, 2>{});
+                else if (nt == 2 || TB == 2) run(std::integral_constant<int, 2>{});
                 else run(std::integral_constant<int, TB>{});
             }
         }
@@ -511,7 +520,9 @@ static int launch_wide_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t
     switch (c->wd_steps) {
     case 2: return launch_wide<2, NB, kU8, G>(c, x, n, out, s);
     case 4: return launch_wide<4, NB, kU8, G>(c, x, n, out, s);
-    default: return launch_wide<6, NB, kU8, G>(c, x, n, out, s);
+    case 6: return launch_wide<6, NB, kU8, G>(c, x, n, out, s);
+    case 8: return launch_wide<8, NB, kU8, G>(c, x, n, out, s);
+    default: return launch_wide<10, NB, kU8, G>(c, x, n, out, s);
     }
 }
 

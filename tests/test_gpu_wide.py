@@ -1,5 +1,5 @@
 """GPU parity of hdc_encode where it runs as the contraction for long streams (Sec. III Eq. 1;
-level tables whose dimensions flip at most once along the levels, at most 6 matrix-instruction
+level tables whose dimensions flip at most once along the levels, at most 10 matrix-instruction
 steps of 64 feature slots, enough samples to give every compute unit a job of 64 or 128): bit-exact
 against the CPU oracle on the first and last rows (a ragged last job) and on random rows in
 between, over feature counts that leave few or many spare slots for the vote threshold, even and
@@ -56,6 +56,10 @@ def _oracle(wl, x):
     (3, 3000, 324, 200, 65536 - 17),     # u8 features, 8 planes
     (5, 16384, 342, 64, 32768 - 5),      # the LDS holds two groups per job only
     (2, 96, 10, 3, 70000),               # a handful of dimensions
+    (2, 10000, 617, 64, 65536 - 7),      # 10 steps: two tiles of a threshold at a time
+    (4, 10000, 561, 64, 65536 - 100),    # 10 steps, 561 features
+    (2, 5000, 500, 64, 65536 - 11),      # 8 steps
+    (3, 2048, 576, 32, 65536 - 29),      # u8 features, 10 steps (9 of them features)
 ])
 def test_encode_wide_bit_exact(cfg, D, F, L, N):
     wl = make_workload(cfg, seed=D + F + L, D=D, F=F, L=L)
@@ -88,16 +92,17 @@ def test_encode_wide_bit_exact(cfg, D, F, L, N):
 
 
 def test_encode_wide_is_left_to_the_other_kernels_where_it_does_not_fit():
-    # more than 6 steps of features, a level table that flips a dimension twice, a call that would
-    # leave the second round of jobs nearly empty: bit-exact all the same, by the other kernels
+    # more than 6 steps of features together with more than 64 levels (the LDS does not hold four
+    # groups of such a model), a call that would leave the second round of jobs nearly empty:
+    # bit-exact all the same, by the other kernels
     from paper_2206_04746_amd import binding  # noqa: F401
-    wl = make_workload(2, n_train=70000)
-    x = _rows(wl, 66000)
+    wl = make_workload(4)
+    x = _rows(wl, 65536)
     ctx = _ctx(wl)
     ctx.hdc_profile_enable(True)
     got = _encode(ctx, x)
     assert ctx.hdc_profile_read("encode_wide")[1] == 0 and ctx.hdc_profile_read("encode_contract")[1] == 1
-    rows = np.arange(0, 66000, 97)
+    rows = np.arange(0, 65536, 97)
     assert np.array_equal(got[rows], _oracle(wl, x[rows]))
     ctx.close()
     wl = make_workload(5)
