@@ -206,10 +206,10 @@ int main() {
         {2049, 31, 64, 16, true},      // odd F, a partial last word
         {513, 64, 4, 171, true},       // every dimension flips once; F fills a step exactly: the threshold takes two more
         {700, 342, 64, 5, true},       // the long stream's feature count, 42 spare slots
-        {300, 383, 8, 20, false},      // one spare slot in six steps cannot carry the thresholds
+        {300, 383, 8, 20, true},       // one spare slot in six steps cannot carry the thresholds: eight steps
         {96, 4, 2, 40, true},          // the smallest model
         {640, 129, 256, 2, true},      // many thresholds of two dimensions
-        {1500, 617, 64, 11, false},    // ten steps: the other encoder's
+        {1500, 617, 64, 11, true},     // ten steps: two tiles of a threshold per work item
     };
     long checked = 0;
     for (const Shape &sh : shapes) {
@@ -223,7 +223,9 @@ int main() {
         constant_row(m, by_tau, &crow);
         for (int v = 0; v < 3 && (1 << v) <= m.W; ++v)
             if (!check_contract(m, by_tau, crow, v, 6)) return 1;
-        if (!check_wide(m, by_tau, crow, 6, 3, 6, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 10, 3, 6, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 10, 2, 4, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 6, 3, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
         ++checked;
     }
     {   // a dimension that flips and flips back is refused
