@@ -350,15 +350,18 @@ def secondary(torch, binding, make_workload, K):
 
 
 def _timed(torch, fn, reps):
-    fn()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
+    """Median device time of a call in ms: two untimed calls, then at least ten calls each between its own pair of events."""
+    for _ in range(2):
         fn()
-    e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
+    reps = max(reps, 10)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.median([a.elapsed_time(b) for a, b in ev]))
 
 
 def extras(torch, binding, make_workload):
@@ -369,7 +372,7 @@ def extras(torch, binding, make_workload):
     # --- config 5 shape: search and classical accumulation over 1M packed rows
     wl5 = make_workload(5)
     ctx = binding.Context(wl5.D, wl5.F, wl5.L, wl5.C, wl5.item, wl5.level, wl5.tie, wl5.lo, wl5.scale, wl5.dtype)
-    N = 1 << 20
+    N = 1_000_000                       # the stream's chunk of windows
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     hv = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, ctx.W), dtype=torch.int32, device=dev, generator=g)

@@ -753,8 +753,7 @@ static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
         p->cap = (int64_t)c->num_cus * bpc - c->p.C;
         if (p->cap < 1) p->cap = 1;
         p->rb_max = kRowsPerWaveMax;
-        p->rows_max = p->cap * p->rg * p->rb_max;
-        if (p->rows_max > c->perm_rows) p->rows_max = c->perm_rows;
+        p->rows_max = c->perm_rows;   // (any number of whole rounds of blocks in one launch, see plan_rb)
         return HDC_OK;
     }
     p->spb = nslices < kAccWaves ? nslices : kAccWaves;
@@ -777,7 +776,11 @@ static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
     return HDC_OK;
 }
 static int64_t plan_rb(const AccPlan &p, int64_t n) {
-    int64_t rb = ((n + p.rg * p.cap - 1) / (p.rg * p.cap) + 7) / 8 * 8;
+    // The wave-per-row kernel takes more rows than one round of full blocks holds as several
+    // rounds of equal, smaller blocks in the same launch (a last round of a few full blocks
+    // would take as long as a whole one).
+    const int64_t rounds = p.rows ? (n + p.rg * p.cap * p.rb_max - 1) / (p.rg * p.cap * p.rb_max) : 1;
+    int64_t rb = ((n + p.rg * p.cap * rounds - 1) / (p.rg * p.cap * rounds) + 7) / 8 * 8;
     return rb < 16 ? 16 : (rb > p.rb_max ? p.rb_max : rb);
 }
 
