@@ -372,7 +372,167 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
 constexpr int kRowsWaves = 16;
 constexpr int kRowsPlanes = 8;                      // a wave counts at most 255 rows ...
 constexpr int kRowsPerWaveMax = 248;                // ... in steps of 8
-template <int KPL>
+
+// eight words into a position's count planes (carry-save: seven full adders, then a ripple from plane 3)
+__device__ __forceinline__ void count8(uint32_t *q, const uint32_t *x) {
+    uint32_t a, b, p, c2a, c2b, c3;
+    p = q[0]; a = maj3(p, x[0], x[1]); p = xor3(p, x[0], x[1]);
+    b = maj3(p, x[2], x[3]); p = xor3(p, x[2], x[3]); q[0] = p;
+    p = q[1]; c2a = maj3(p, a, b); q[1] = xor3(p, a, b);
+    p = q[0]; a = maj3(p, x[4], x[5]); p = xor3(p, x[4], x[5]);
+    b = maj3(p, x[6], x[7]); p = xor3(p, x[6], x[7]); q[0] = p;
+    p = q[1]; c2b = maj3(p, a, b); q[1] = xor3(p, a, b);
+    p = q[2]; c3 = maj3(p, c2a, c2b); q[2] = xor3(p, c2a, c2b);
+#pragma unroll
+    for (int i = 3; i < kRowsPlanes; ++i) {
+        const uint32_t t = q[i] & c3;
+        q[i] ^= c3;
+        c3 = t;
+    }
+}
+
+// Which words of a row a lane holds, position k = 0 .. KPL - 1.  Plain: word k * 64 + lane.
+// Quad (rows of 257 to 320 words): words 4 * lane + k for k < 4, which one 16-byte load
+// brings, and word 256 + lane for k = 4.
+template <bool QUAD>
+__device__ __forceinline__ int word_of(const int k, const int lane) {
+    return QUAD ? (k < 4 ? 4 * lane + k : 4 * kWave + lane) : k * kWave + lane;
+}
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // (rows start at any word)
+
+// A wave counts `nrows` rows into its planes, eight rows at a time.  rows8(r0, last, row) gives
+// the addresses of rows r0 .. r0 + 7 of the wave's run, none past `last` (wave-uniform
+// values).  A batch is asked for in one burst, row after row, so that the memory sees a row's
+// pieces together, and counted as it comes in; while the burst is under way the next batch's
+// addresses are worked out.  The wave's own loads and counting overlap little; those of the
+// block's other 15 waves do.  (Measured on 1M rows of 313 words: asking for the next batch
+// slice by slice while this one is counted, 32 to 38 loads always in flight, was 10 % slower
+// than the burst; a burst that goes through the batch position by position, eight rows'
+// first 256 bytes, then their second, 8 % slower than row by row; 16-byte loads 2.5 % faster
+// than 4-byte ones.)  Nothing is conditional about the loads and no loaded word is used before
+// its turn to be counted (either would make the wave wait for every load at once): the up to
+// seven rows left over come as one more batch of eight, the surplus a repeat of the last row,
+// masked.  Lanes past the end of a row read its last word; the caller drops their counts.
+template <int KPL, bool QUAD, typename Rows8>
+__device__ __forceinline__ void count_rows(uint32_t (&pl)[KPL][kRowsPlanes], const uint32_t nrows, const int lane,
+                                           const int W, Rows8 rows8) {
+    static_assert(!QUAD || KPL == 5, "the quad layout is for rows of 257 to 320 words");
+    int at[KPL];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) at[k] = min(word_of<QUAD>(k, lane), W - 1);
+    uint32_t x[KPL][8];
+    const uint32_t *row[8];
+    auto ask = [&]() {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if constexpr (QUAD) {
+                const u32x4_a4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4 *>(row[j] + 4 * lane));
+                x[0][j] = q.x, x[1][j] = q.y, x[2][j] = q.z, x[3][j] = q.w;
+                x[4][j] = __builtin_nontemporal_load(row[j] + at[4]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < KPL; ++k) x[k][j] = __builtin_nontemporal_load(row[j] + at[k]);
+            }
+        }
+    };
+    const uint32_t full = nrows & ~7u;
+    if (full > 0) rows8(0u, full - 1, row);
+    for (uint32_t r0 = 0; r0 < full; r0 += 8) {
+        ask();
+        __builtin_amdgcn_sched_barrier(0);
+        rows8(min(r0 + 8, full - 8), full - 1, row);   // (after the last batch: the same again, unused)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) count8(pl[k], x[k]);
+    }
+    if (nrows > full) {   // wave-uniform
+        rows8(full, nrows - 1, row);
+        ask();
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[k][j] = full + j < nrows ? x[k][j] : 0u;
+            count8(pl[k], x[k]);
+        }
+    }
+}
+
+// The 16 waves' counts (eight planes per lane and word position) meet in LDS in two rounds
+// (waves 8..15 into 0..7, then 1..7 into 0); the block total, twelve planes, goes back through
+// LDS so that wave k turns position k into 16-bit sums, 32 dimensions per lane as 16 dwords
+// (pad columns store zeros), at dst + word_of(k, lane) * 16.  All threads of the block call it; four
+// barriers inside.  merge: 8 x KPL x 9 planes of 64 words.  extra (block-uniform, may be
+// null): one more count of at most 248 parked elsewhere in LDS, KPL x 9 planes of 64 words.
+template <int KPL, bool QUAD>
+__device__ __forceinline__ void merge_and_store(uint32_t (&pl)[KPL][12], uint32_t *merge, const int wave,
+                                                const int lane, const int Wp, uint32_t *dst_row,
+                                                const uint32_t *extra = nullptr) {
+    auto park = [&](const int slot, const int planes) {
+        uint32_t *dst = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int i = 0; i < 9; ++i)
+                if (i < planes) dst[(k * 9 + i) * kWave] = pl[k][i];
+    };
+    auto take_at = [&](const uint32_t *slot, const int planes) {   // pl += the parked number of `planes` planes
+        const uint32_t *src = slot + lane;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            uint32_t carry = 0;
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                const uint32_t a = pl[k][i], b = i < planes ? src[(k * 9 + i) * kWave] : 0u;
+                pl[k][i] = xor3(a, b, carry);
+                carry = maj3(a, b, carry);
+            }
+        }
+    };
+    auto take = [&](const int slot, const int planes) { take_at(merge + (size_t)slot * (KPL * 9 * kWave), planes); };
+    if (wave >= 8) park(wave - 8, kRowsPlanes);
+    __syncthreads();
+    if (wave < 8) take(wave, kRowsPlanes);      // at most 496 rows: nine planes
+    if (wave == 0 && extra) take_at(extra, kRowsPlanes);   // (a seventeenth count of at most 248, parked in the same layout)
+    __syncthreads();
+    if (wave >= 1 && wave < 8) park(wave, 9);
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll 1
+        for (int w = 1; w < 8; ++w) take(w, 9);   // the block total stays below 2^12
+    }
+    __syncthreads();
+    uint32_t *tot = merge;
+    if (wave == 0) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int i = 0; i < 12; ++i) tot[(k * 12 + i) * kWave + lane] = pl[k][i];
+    }
+    __syncthreads();
+    if (wave >= KPL) return;
+    const int col = word_of<QUAD>(wave, lane);
+    if (col >= Wp) return;
+    uint32_t t12[12];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) t12[i] = tot[(wave * 12 + i) * kWave + lane];
+    uint4 *dst = reinterpret_cast<uint4 *>(dst_row + (size_t)col * 16);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        uint32_t w4[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int b0 = (q4 * 4 + k) * 2;
+            uint32_t v = 0;
+#pragma unroll
+            for (int i = 0; i < 12; ++i)
+                v |= (((t12[i] >> b0) & 1u) << i) | (((t12[i] >> (b0 + 1)) & 1u) << (16 + i));
+            w4[k] = v;
+        }
+        dst[q4] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    }
+}
+
+template <int KPL, bool QUAD>
 __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_rows_kernel(
     const uint32_t *__restrict__ hv, const uint32_t *__restrict__ perm, const uint32_t *__restrict__ cnt,
     const uint32_t *__restrict__ off, const uint32_t *__restrict__ blk, int C, int W, int Wp, int rpw,
@@ -394,136 +554,141 @@ __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_rows_kernel(
     const uint32_t rows = __builtin_amdgcn_readfirstlane(first < total ? min((uint32_t)rpw, total - first) : 0u);
     const_u32_ptr idx = (const_u32_ptr)(uintptr_t)(perm + __builtin_amdgcn_readfirstlane(off[c]) + first);
 
-    uint32_t pl[KPL][12];
+    uint32_t pl[KPL][kRowsPlanes];
 #pragma unroll
     for (int k = 0; k < KPL; ++k)
 #pragma unroll
-        for (int i = 0; i < 12; ++i) pl[k][i] = 0;
-    int at[KPL];         // the lane's words of a row (clamped: a lane past the row's end reads the last word and drops it)
-    uint32_t mine[KPL];
+        for (int i = 0; i < kRowsPlanes; ++i) pl[k][i] = 0;
+    count_rows<KPL, QUAD>(pl, rows, lane, W, [&](const uint32_t r0, const uint32_t last, const uint32_t *(&row)[8]) {
 #pragma unroll
-    for (int k = 0; k < KPL; ++k) {
-        at[k] = min(lane + k * kWave, W - 1);
-        mine[k] = lane + k * kWave < W ? 0xffffffffu : 0u;
-    }
-    uint32_t x[KPL][8];
-    // Eight whole rows at a time with nothing conditional about the loads and no use of a loaded
-    // word before its turn to be counted (a select on it would make the wave wait for every
-    // load at once); the up to seven rows left over come afterwards, masked.  Lanes past the end
-    // of a row read its last word again; their counts are dropped at the end.
-    auto load8 = [&](const uint32_t r0, const int k) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[k][j] = __builtin_nontemporal_load(hv + (int64_t)idx[r0 + j] * W + at[k]);
-    };
-    auto add8 = [&](const int k) {
-        uint32_t a, b, p, c2a, c2b, c3;
-        uint32_t *q = pl[k];
-        p = q[0]; a = maj3(p, x[k][0], x[k][1]); p = xor3(p, x[k][0], x[k][1]);
-        b = maj3(p, x[k][2], x[k][3]); p = xor3(p, x[k][2], x[k][3]); q[0] = p;
-        p = q[1]; c2a = maj3(p, a, b); q[1] = xor3(p, a, b);
-        p = q[0]; a = maj3(p, x[k][4], x[k][5]); p = xor3(p, x[k][4], x[k][5]);
-        b = maj3(p, x[k][6], x[k][7]); p = xor3(p, x[k][6], x[k][7]); q[0] = p;
-        p = q[1]; c2b = maj3(p, a, b); q[1] = xor3(p, a, b);
-        p = q[2]; c3 = maj3(p, c2a, c2b); q[2] = xor3(p, c2a, c2b);
-#pragma unroll
-        for (int i = 3; i < kRowsPlanes; ++i) {
-            const uint32_t t = q[i] & c3;
-            q[i] ^= c3;
-            c3 = t;
-        }
-    };
-    const uint32_t full = rows & ~7u;
-    if (full > 0) {   // wave-uniform
-#pragma unroll
-        for (int k = 0; k < KPL; ++k) load8(0, k);
-        for (uint32_t r0 = 0; r0 < full; r0 += 8) {
-            const uint32_t next = min(r0 + 8, full - 8);   // (after the last batch: the same again, unused)
-#pragma unroll
-            for (int k = 0; k < KPL; ++k) {
-                add8(k);
-                load8(next, k);
-            }
-        }
-    }
-    if (rows > full) {   // wave-uniform
-#pragma unroll
-        for (int k = 0; k < KPL; ++k)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[k][j] = hv[(int64_t)idx[min(full + j, rows - 1)] * W + at[k]];
-#pragma unroll
-        for (int k = 0; k < KPL; ++k) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[k][j] = full + j < rows ? x[k][j] : 0u;
-            add8(k);
-        }
-    }
+        for (int j = 0; j < 8; ++j) row[j] = hv + (int64_t)idx[min(r0 + (uint32_t)j, last)] * W;
+    });
+    uint32_t t[KPL][12];
 #pragma unroll
     for (int k = 0; k < KPL; ++k)
 #pragma unroll
-        for (int i = 0; i < kRowsPlanes; ++i) pl[k][i] &= mine[k];
+        for (int i = 0; i < 12; ++i) t[k][i] = (i < kRowsPlanes && word_of<QUAD>(k, lane) < W) ? pl[k][i] : 0u;
+    merge_and_store<KPL, QUAD>(t, merge, wave, lane, Wp, partial + (size_t)item * Wp * 16);
+}
 
-    // the waves' counts meet: a (planes)-bit number per lane and position added to another
-    auto park = [&](const int slot, const int planes) {
-        uint32_t *dst = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+// ---- vertical count of a few classes without grouping the rows first ----------------------------
+// Up to kLocalMaxC classes.  grid.x = blocks of 16 * rpw consecutive rows (rpw at most 248).  The
+// block orders its rows by class by itself: a wave reads the labels of its rpw rows, a lane four
+// of them, and counts the classes with ballots; after a barrier every wave knows where its rows
+// of each class go in the block's list (LDS, 16-bit row offsets, class after class) and writes
+// them there.  Then the list is dealt out again, rpw entries per wave, so that a wave's run
+// holds one class except where a class ends inside it: the wave counts a class's stretch as
+// accumulate_rows_kernel does (the batch's eight row numbers come from the list with one LDS
+// read and eight readlanes) and, where more of its run follows, parks that count in the class's
+// own LDS slot (a class ends in one wave only) and starts again.  No wave waits for another
+// until all have streamed.  The classes are then merged one after the other, a wave giving
+// the count it still holds to its class and zeros to the others, the parked count going in
+// as a seventeenth; the class's partial row is item c * gridDim.x + block.  Rows whose label
+// is outside [0, C) are on no list.  Saved against grouped rows: the grouping launch and the
+// trip of the row numbers through memory.
+// labels == nullptr: every row is of class 0 (the vertical sum on its own).  Block 0 writes the
+// work list of the reduction (blk[c] = c * gridDim.x); class_n[c] grows by the block's rows of c.
+// Dynamic LDS: (8 + C - 1) x KPL x 9 planes of 64 words.
+constexpr int kLocalMaxC = 4;
+template <int KPL, bool QUAD>
+__global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_local_kernel(
+    const uint32_t *__restrict__ hv, const int32_t *__restrict__ labels, uint32_t n, int C, int W, int Wp, int rpw,
+    uint32_t *__restrict__ partial, uint32_t *__restrict__ blk, unsigned long long *class_n) {
+    extern __shared__ uint32_t merge[];
+    __shared__ uint16_t list_s[kRowsWaves * 256];
+    __shared__ uint32_t wc_s[kRowsWaves][kLocalMaxC], used_s[kLocalMaxC];
+    constexpr int kSlotWords = KPL * 9 * kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t block_first = blockIdx.x * (uint32_t)(kRowsWaves * rpw);
+    const uint32_t first = __builtin_amdgcn_readfirstlane(block_first + (uint32_t)(wave * rpw));
+    const uint32_t rows = __builtin_amdgcn_readfirstlane(first < n ? min((uint32_t)rpw, n - first) : 0u);
+    if (blockIdx.x == 0 && threadIdx.x <= (unsigned)C) blk[threadIdx.x] = threadIdx.x * gridDim.x;
+    if (threadIdx.x < kLocalMaxC) used_s[threadIdx.x] = 0;
+    int32_t y[4];
 #pragma unroll
-        for (int k = 0; k < KPL; ++k)
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t r = (uint32_t)(j * kWave + lane);
+        y[j] = r < rows ? (labels ? labels[(size_t)first + r] : 0) : -1;
+    }
+    for (int c = 0; c < C; ++c) {
+        uint32_t k = 0;
 #pragma unroll
-            for (int i = 0; i < 9; ++i)
-                if (i < planes) dst[(k * 9 + i) * kWave] = pl[k][i];
-    };
-    auto take = [&](const int slot, const int planes) {   // pl += the parked number of `planes` planes
-        const uint32_t *src = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+        for (int j = 0; j < 4; ++j) k += (uint32_t)__popcll(__ballot(y[j] == c));
+        if (lane == 0) wc_s[wave][c] = k;
+    }
+    __syncthreads();
+    uint32_t bnd[kLocalMaxC + 1];   // where the classes start in the block's list (block-uniform)
+    bnd[0] = 0;
+    {
+        const uint64_t below = ((uint64_t)1 << lane) - 1;
 #pragma unroll
-        for (int k = 0; k < KPL; ++k) {
-            uint32_t carry = 0;
+        for (int c = 0; c < kLocalMaxC; ++c) {
+            uint32_t before = 0, total = 0;
+            if (c < C) {
+                for (int w = 0; w < kRowsWaves; ++w) {
+                    const uint32_t k = wc_s[w][c];
+                    before += w < wave ? k : 0u;
+                    total += k;
+                }
+                uint32_t at = bnd[c] + before;
 #pragma unroll
-            for (int i = 0; i < 12; ++i) {
-                const uint32_t a = pl[k][i], b = i < planes ? src[(k * 9 + i) * kWave] : 0u;
-                pl[k][i] = xor3(a, b, carry);
-                carry = maj3(a, b, carry);
+                for (int j = 0; j < 4; ++j) {
+                    const uint64_t m = __ballot(y[j] == c);
+                    if (y[j] == c) list_s[at + (uint32_t)__popcll(m & below)] = (uint16_t)(wave * rpw + j * kWave + lane);
+                    at += (uint32_t)__popcll(m);
+                }
+                if (class_n && threadIdx.x == 0 && total) atomicAdd(class_n + c, (unsigned long long)total);
             }
+            bnd[c + 1] = __builtin_amdgcn_readfirstlane(bnd[c] + total);
         }
-    };
-    if (wave >= 8) park(wave - 8, kRowsPlanes);
-    __syncthreads();
-    if (wave < 8) take(wave, kRowsPlanes);      // at most 496 rows: nine planes
-    __syncthreads();
-    if (wave >= 1 && wave < 8) park(wave, 9);
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll 1
-        for (int w = 1; w < 8; ++w) take(w, 9);   // the block total stays below 2^12
     }
     __syncthreads();
-    // the total back through LDS, twelve planes per position: wave k turns position k into 16-bit sums
-    uint32_t *tot = merge;
-    if (wave == 0) {
+    uint32_t mine[KPL];   // (a lane past the row's end read the last word again: its counts are dropped)
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) mine[k] = word_of<QUAD>(k, lane) < W ? 0xffffffffu : 0u;
+    uint32_t pl[KPL][kRowsPlanes];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int i = 0; i < kRowsPlanes; ++i) pl[k][i] = 0;
+    int mine_c = -1;     // the class of the count the wave holds at the end
+    const uint32_t run0 = (uint32_t)(wave * rpw), run1 = min(run0 + (uint32_t)rpw, bnd[kLocalMaxC]);
+#pragma unroll
+    for (int c = 0; c < kLocalMaxC; ++c) {
+        const uint32_t s0 = max(run0, bnd[c]), s1 = min(run1, bnd[c + 1]);
+        if (c >= C || s0 >= s1) continue;   // wave-uniform
+        const uint16_t *lst = list_s + s0;
+        count_rows<KPL, QUAD>(pl, s1 - s0, lane, W, [&](const uint32_t r0, const uint32_t last, const uint32_t *(&row)[8]) {
+            const uint32_t v = lst[min(r0 + (uint32_t)(lane & 7), last)];   // one LDS read, eight readlanes
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                row[j] = hv + (int64_t)(block_first + (uint32_t)__builtin_amdgcn_readlane((int)v, j)) * W;
+        });
+        if (run1 > bnd[c + 1]) {   // more of the run follows: this class's count waits in its slot
+            uint32_t *dst = merge + (size_t)(8 + c) * kSlotWords + lane;
+#pragma unroll
+            for (int k = 0; k < KPL; ++k)
+#pragma unroll
+                for (int i = 0; i < kRowsPlanes; ++i) {
+                    dst[(k * 9 + i) * kWave] = pl[k][i] & mine[k];
+                    pl[k][i] = 0;
+                }
+            if (lane == 0) used_s[c] = 1;
+        } else {
+            mine_c = c;
+        }
+    }
+    __syncthreads();
+    for (int c = 0; c < C; ++c) {
+        uint32_t t[KPL][12];
 #pragma unroll
         for (int k = 0; k < KPL; ++k)
 #pragma unroll
-            for (int i = 0; i < 12; ++i) tot[(k * 12 + i) * kWave + lane] = pl[k][i];
-    }
-    __syncthreads();
-    if (wave >= KPL) return;
-    const int col = wave * kWave + lane;
-    if (col >= Wp) return;
-    uint32_t t12[12];
-#pragma unroll
-    for (int i = 0; i < 12; ++i) t12[i] = tot[(wave * 12 + i) * kWave + lane];
-    uint4 *dst = reinterpret_cast<uint4 *>(partial + ((size_t)item * Wp + col) * 16);   // (pad columns store zeros)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-        uint32_t w4[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int b0 = (q4 * 4 + k) * 2;
-            uint32_t v = 0;
-#pragma unroll
-            for (int i = 0; i < 12; ++i)
-                v |= (((t12[i] >> b0) & 1u) << i) | (((t12[i] >> (b0 + 1)) & 1u) << (16 + i));
-            w4[k] = v;
-        }
-        dst[q4] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            for (int i = 0; i < 12; ++i) t[k][i] = (i < kRowsPlanes && mine_c == c) ? (pl[k][i] & mine[k]) : 0u;
+        const uint32_t *extra = used_s[c] ? merge + (size_t)(8 + c) * kSlotWords : nullptr;
+        merge_and_store<KPL, QUAD>(t, merge, wave, lane, Wp, partial + ((size_t)c * gridDim.x + blockIdx.x) * Wp * 16, extra);
+        __syncthreads();   // (the totals in LDS have been read before the next class parks there)
     }
 }
 
@@ -728,13 +893,25 @@ struct AccPlan {
 };
 constexpr int kRowsMaxKpl = 5;   // word positions per lane the wave-per-row kernel is built for (its registers)
 static size_t rows_lds(int kpl) { return (size_t)8 * kpl * 9 * kWave * sizeof(uint32_t); }
-static const void *rows_kernel(int kpl) {
+// (the 16-byte layout where the rows have 257 to 320 words)
+static const void *rows_kernel(int kpl, int W) {
     switch (kpl) {
-    case 1: return reinterpret_cast<const void *>(accumulate_rows_kernel<1>);
-    case 2: return reinterpret_cast<const void *>(accumulate_rows_kernel<2>);
-    case 3: return reinterpret_cast<const void *>(accumulate_rows_kernel<3>);
-    case 4: return reinterpret_cast<const void *>(accumulate_rows_kernel<4>);
-    default: return reinterpret_cast<const void *>(accumulate_rows_kernel<5>);
+    case 1: return reinterpret_cast<const void *>(accumulate_rows_kernel<1, false>);
+    case 2: return reinterpret_cast<const void *>(accumulate_rows_kernel<2, false>);
+    case 3: return reinterpret_cast<const void *>(accumulate_rows_kernel<3, false>);
+    case 4: return reinterpret_cast<const void *>(accumulate_rows_kernel<4, false>);
+    default: return W > 4 * kWave ? reinterpret_cast<const void *>(accumulate_rows_kernel<5, true>)
+                                  : reinterpret_cast<const void *>(accumulate_rows_kernel<5, false>);
+    }
+}
+static const void *local_kernel(int kpl, int W) {
+    switch (kpl) {
+    case 1: return reinterpret_cast<const void *>(accumulate_local_kernel<1, false>);
+    case 2: return reinterpret_cast<const void *>(accumulate_local_kernel<2, false>);
+    case 3: return reinterpret_cast<const void *>(accumulate_local_kernel<3, false>);
+    case 4: return reinterpret_cast<const void *>(accumulate_local_kernel<4, false>);
+    default: return W > 4 * kWave ? reinterpret_cast<const void *>(accumulate_local_kernel<5, true>)
+                                  : reinterpret_cast<const void *>(accumulate_local_kernel<5, false>);
     }
 }
 static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
@@ -745,8 +922,8 @@ static int plan_static(hdc_ctx_impl *c, AccPlan *p) {
         int bpc = c->acc_bpc;
         if (bpc == 0) {
             if (rows_lds(nslices) > 64 * 1024)
-                HDC_HIP(hipFuncSetAttribute(rows_kernel(nslices), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(nslices)));
-            HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, rows_kernel(nslices), kRowsWaves * kWave, rows_lds(nslices)));
+                HDC_HIP(hipFuncSetAttribute(rows_kernel(nslices, c->W), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(nslices)));
+            HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, rows_kernel(nslices, c->W), kRowsWaves * kWave, rows_lds(nslices)));
             if (bpc < 1) bpc = 1;
             c->acc_bpc = bpc;
         }
@@ -791,6 +968,18 @@ int64_t classical_max_items(hdc_ctx_impl *c) {
     return p.cap + 2 * (int64_t)c->p.C + 16 + c->perm_rows / (p.rg * p.rb_max);
 }
 
+// acc += the partial rows of each class (blk in the context's scratch lists them).
+static int reduce_partials(hdc_ctx_impl *c, int classes, int32_t *acc, hipStream_t s) {
+    // enough threads for the reduction: split a class's partial rows K ways when C is small
+    const int pairs = c->Wp * 16;
+    int K = (int)((262144 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
+    K = K < 1 ? 1 : (K > 16 ? 16 : K);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)classes, (unsigned)K),
+                       dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
+    HDC_HIP(hipGetLastError());
+    return HDC_OK;
+}
+
 // The accumulate + reduce launches for n rows already grouped into `classes` classes (perm,
 // cnt, off, blk in the context's scratch); acc [classes][D] is added to.
 static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32_t *hv0, int64_t n,
@@ -804,24 +993,64 @@ static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32
     if (plan.rows) {
         const int kpl = c->Wp / kSliceWords;
         if (rows_lds(kpl) > 64 * 1024)   // (per launch: the limit belongs to the function, not to a context)
-            HDC_HIP(hipFuncSetAttribute(rows_kernel(kpl), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(kpl)));
+            HDC_HIP(hipFuncSetAttribute(rows_kernel(kpl, c->W), hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_lds(kpl)));
         ProfScope prof(c, HDC_K_ACCUMULATE, s);
         void *args[] = {(void *)&hv0, (void *)&c->perm_d, (void *)&c->cls_cnt_d, (void *)&c->cls_off_d, (void *)&c->cls_blk_d,
                         (void *)&classes, (void *)&c->W, (void *)&c->Wp, (void *)&rb32, (void *)&c->partial_d};
-        HDC_HIP(hipLaunchKernel(rows_kernel(kpl), dim3((unsigned)items), dim3(kRowsWaves * kWave), args, rows_lds(kpl), s));
+        HDC_HIP(hipLaunchKernel(rows_kernel(kpl, c->W), dim3((unsigned)items), dim3(kRowsWaves * kWave), args, rows_lds(kpl), s));
     } else {
         ProfScope prof(c, HDC_K_ACCUMULATE, s);
         hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)items, (unsigned)ychunks), dim3(spb * rg * kWave),
                            lds, s, hv0, c->perm_d, c->cls_cnt_d, c->cls_off_d, c->cls_blk_d, classes, c->W,
                            c->Wp, (int)rb, spb, rg, c->partial_d);
     }
-    // enough threads for the reduction: split a class's partial rows K ways when C is small
-    const int pairs = c->Wp * 16;
-    int K = (int)((262144 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
-    K = K < 1 ? 1 : (K > 16 ? 16 : K);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)classes, (unsigned)K),
-                       dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
-    HDC_HIP(hipGetLastError());
+    return reduce_partials(c, classes, acc, s);
+}
+
+// Rows of at most 320 words and at most kLocalMaxC classes: no grouping, accumulate_local_kernel
+// on the rows as they lie (labels == nullptr: one class) and the reduction.  A launch takes as
+// many rows as its blocks' partial rows (classes per block) fit the scratch; as in plan_rb, more
+// rows than one round of full blocks holds run as equal rounds of smaller blocks.
+static int accumulate_local(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
+                            int classes, int32_t *acc, int64_t *class_n, hipStream_t s) {
+    const int kpl = c->Wp / kSliceWords;
+    const void *fn = local_kernel(kpl, c->W);
+    const size_t lds = rows_lds(kpl) / 8 * (8 + classes - 1);   // (a slot more per class that can end inside a wave's run)
+    const bool raise = lds + 16 * 1024 > 64 * 1024;     // (the kernel has some static LDS of its own)
+    if (raise) HDC_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    int &held = c->acc_local_bpc[classes > 1];   // (the LDS of a block grows with the classes: one answer for the sum on its own, one for training)
+    if (held == 0) {
+        int bpc = 0;
+        HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, fn, kRowsWaves * kWave, lds));
+        held = bpc < 1 ? 1 : bpc;
+    }
+    const int64_t most = c->partial_items / classes;   // blocks a launch may have
+    if (most < 1) return HDC_ELIMIT;                   // cannot happen: the scratch holds a row per class and more
+    int64_t cap = (int64_t)c->num_cus * held;
+    if (cap > most) cap = most;
+    const int64_t round_rows = cap * kRowsWaves * kRowsPerWaveMax;
+    const int64_t rows_max = most / cap * round_rows;
+    for (int64_t n0 = 0; n0 < N; n0 += rows_max) {
+        const int64_t n = (N - n0 < rows_max) ? N - n0 : rows_max;
+        const int64_t rounds = (n + round_rows - 1) / round_rows;
+        int64_t rpw = ((n + kRowsWaves * cap * rounds - 1) / (kRowsWaves * cap * rounds) + 7) / 8 * 8;
+        rpw = rpw < 16 ? 16 : (rpw > kRowsPerWaveMax ? kRowsPerWaveMax : rpw);
+        const int64_t blocks = (n + kRowsWaves * rpw - 1) / (kRowsWaves * rpw);
+        if (blocks > most) return HDC_ELIMIT;          // cannot happen: blocks <= cap * rounds <= most
+        const uint32_t *hv0 = hv + (size_t)n0 * c->W;
+        const int32_t *lab0 = labels ? labels + n0 : nullptr;
+        const uint32_t n32 = (uint32_t)n;
+        const int rpw32 = (int)rpw;
+        unsigned long long *cn = reinterpret_cast<unsigned long long *>(class_n);
+        {
+            ProfScope prof(c, HDC_K_ACCUMULATE, s);
+            void *args[] = {(void *)&hv0, (void *)&lab0, (void *)&n32, (void *)&classes, (void *)&c->W, (void *)&c->Wp,
+                            (void *)&rpw32, (void *)&c->partial_d, (void *)&c->cls_blk_d, (void *)&cn};
+            HDC_HIP(hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(kRowsWaves * kWave), args, lds, s));
+        }
+        const int rc = reduce_partials(c, classes, acc, s);
+        if (rc != HDC_OK) return rc;
+    }
     return HDC_OK;
 }
 
@@ -842,6 +1071,7 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
         HDC_HIP(hipGetLastError());
         return HDC_OK;
     }
+    if (plan.rows && C <= kLocalMaxC) return accumulate_local(c, hv, labels, N, C, acc, class_n, s);
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
@@ -899,6 +1129,7 @@ int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
     if (prc != HDC_OK) return prc;
     hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((c->p.D + 255) / 256)), dim3(256), 0, s, out,
                        (int64_t)c->p.D);
+    if (plan.rows) return accumulate_local(c, hv, nullptr, N, 1, out, nullptr, s);
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const int64_t rb = plan_rb(plan, n);

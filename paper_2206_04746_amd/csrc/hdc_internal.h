@@ -131,6 +131,7 @@ struct hdc_ctx_impl {
     int enc_split_bpc[2];   // blocks of encode_split_kernel (8 / 16 waves) a CU holds (0 = not asked yet) ...
     int enc_split_L[2];     //   ... and the level count that answer was for
     int acc_bpc;            // blocks of accumulate_kernel a CU holds (0 = not asked yet)
+    int acc_local_bpc[2];   // the same of accumulate_local_kernel with one class / with the context's classes
     bool on_attr_set[16];   // online_lds_kernel<CMAX, .>: dynamic-LDS limit raised, by CMAX
 
     // Optional per-kernel timing (hdc_profile_*): event pairs per hot kernel.
