@@ -108,7 +108,8 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
     if (!flip_thresholds(model, &by_tau)) return HDC_OK;   // a dimension that flips twice rules the model out
     WdTables tabs;
     build_wide_tables(model, by_tau, kWdMaxSteps, kWdTiles, &tabs);
-    if (tabs.steps > 6) build_wide_tables(model, by_tau, kWdMaxSteps, kWdTilesLong, &tabs);   // (the steps come out the same)
+    if (tabs.steps && wd_tiles_of(tabs.steps) != kWdTiles)   // (the steps come out the same)
+        build_wide_tables(model, by_tau, kWdMaxSteps, wd_tiles_of(tabs.steps), &tabs);
     if (!tabs.steps) return HDC_OK;
     const int steps = tabs.steps, cols = tabs.cols;
     const int nb = L <= 64 ? 6 : 8;
@@ -167,7 +168,12 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
     constexpr int kBatch = kRounds <= 26 ? kRounds : (kRounds + 1) / 2;   // rounds in flight together (their registers)
     constexpr int kRowBytes = KS * 64 + 16;
     constexpr int kRawRegs = kU8 ? 1 : 4;
-    constexpr int kTouches = (kSamples * KS * 64 * (kU8 ? 1 : 4) / 128 + kWdThreads - 1) / kWdThreads;   // 128-byte lines of a job's features per thread
+    // 128-byte lines of the next job's features a thread asks for ahead of time: all of them up to
+    // three per thread (192 KB a block); of longer feature rows only that much, since what a
+    // compute unit can count on in its die's L2 (4 MB for 32 units, the model's tables in it as
+    // well) is less than a job (617 features: 316 KB; asking for all of it was 2 to 4 % slower than
+    // for none, the counters showing the lines fetched twice)
+    constexpr int kTouches = std::min(3, (kSamples * KS * 64 * (kU8 ? 1 : 4) / 128 + kWdThreads - 1) / kWdThreads);
     constexpr int TB = wd_tiles_of(KS);
     uint32_t *ticket = wd_lds;   // the next item of the tile phase (16 bytes in front of the planes)
     wd_u32x4 *planes_a = reinterpret_cast<wd_u32x4 *>(wd_lds + 4);
