@@ -5,14 +5,16 @@
 // (Sec. IV-B2).  Here it needs no transposition: a lane owns one 32-bit word column and
 // keeps the 32 counts bit-sliced (plane i = bit i of each count); adding rows is carry-save
 // arithmetic with v_bitop3_b32 full adders, a few VALU ops per streamed word, so the kernel
-// stays HBM-bound.  Rows are first grouped by class (a counting sort of the labels, only the
-// row indices move).  A block then takes a run of rows of ONE class.  Rows of up to 320 words:
-// each of its 16 waves reads whole rows of a share of the run, a lane the words l, l + 64, ...
-// (accumulate_rows_kernel: no wave waits for another while it streams).  Wider rows: its waves
+// stays HBM-bound.  Rows of up to 320 words and up to four classes: a block takes a run of
+// consecutive rows, orders them by class by itself in LDS and gives each of its 16 waves a
+// share to read as whole rows (accumulate_local_kernel: no grouping pass, no wave waits for
+// another while it streams).  More classes: the rows are first grouped by class (a counting
+// sort of the labels, only the row indices move) and a block takes a run of rows of ONE class
+// (accumulate_rows_kernel, the same streaming).  Wider rows: grouped as well; a block's waves
 // cover the slices of 64 word columns side by side (so rows are read as whole contiguous
 // lines) times a few row groups, meeting at a barrier every 16 rows (accumulate_kernel).  The
 // waves' bit-sliced counts are added through LDS and written out as 16-bit partial sums, one
-// row of partials per block.  A second, tiny kernel adds the partial
+// row of partials per block and class.  A second, tiny kernel adds the partial
 // rows of each class into acc.  (Flushing blocks straight into acc with atomics was measured at
 // 10-25 G atomics/s, several times slower than streaming the rows themselves.)  Everything is
 // integer addition, so any order gives the same bits.
@@ -359,16 +361,14 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
     }
 }
 
-// ---- vertical count, a wave per row (rows of up to 512 words) -----------------------------------
+// ---- vertical count, a wave per row (rows of up to 320 words) -----------------------------------
 // grid.x = work item as above.  The block's 16 waves take a sixteenth of the item's rows each, a
-// contiguous run; a wave reads whole rows, lane l the words l, l + 64, ... (kpl of them), eight
-// rows at a time, and keeps a set of count planes per word position.  As soon as a position's
-// eight words have been counted, the same eight registers are asked for again from the next
-// eight rows, so a lane always has 8 kpl loads in flight and the waves never wait for one
-// another: no barrier in the stream.  A wave counts at most 248 rows (eight planes); the waves'
-// counts meet in LDS in two rounds (waves 8..15 into 0..7, then 1..7 into 0), and the block
-// total, twelve planes, goes back through LDS so that kpl waves turn a position each into
-// 16-bit sums.  Dynamic LDS: 8 x kpl x 9 planes of 64 words.
+// contiguous run; a wave reads whole rows, a lane KPL words of each (word_of below), eight
+// rows at a time (count_rows), and keeps a set of count planes per word position; the waves
+// never wait for one another: no barrier in the stream.  A wave counts at most 248 rows (eight
+// planes); the waves' counts meet in LDS in two rounds (waves 8..15 into 0..7, then 1..7
+// into 0), and the block total, twelve planes, goes back through LDS so that KPL waves turn a
+// position each into 16-bit sums.  Dynamic LDS: 8 x KPL x 9 planes of 64 words.
 constexpr int kRowsWaves = 16;
 constexpr int kRowsPlanes = 8;                      // a wave counts at most 255 rows ...
 constexpr int kRowsPerWaveMax = 248;                // ... in steps of 8
