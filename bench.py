@@ -217,7 +217,10 @@ def main() -> int:
     kernels = {}
     if ac_n:
         us = ac_ms * 1e3 / ac_n
-        kernels["accumulate_kernel"] = {"avg_launch_us": round(us, 1), "launches": ac_n,
+        # (the kernel hdc_train_classical takes for long calls: rows of up to 320 words are streamed a
+        # wave per row, without a grouping pass for up to four classes)
+        acc_name = "accumulate_kernel" if W > 320 else ("accumulate_local_kernel" if wl.C <= 4 else "accumulate_rows_kernel")
+        kernels[acc_name] = {"avg_launch_us": round(us, 1), "launches": ac_n,
                                         "frac_hbm": round(row_bytes * per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
     if se_n:
         us = se_ms * 1e3 / se_n

@@ -183,16 +183,21 @@ struct WdBias {
     }
 };
 
+constexpr int kWdTileCols = 16;   // dimensions of a tile: the N of the 16 x 16 x 128 matrix instruction
+
 struct WdTables {
-    int steps = 0;                  // matrix instructions per tile (64 feature slots each); 0: the model does not fit
-    int tiles = 0, cols = 0;        // tiles of 32 dimensions, columns = varying dimensions
+    int steps = 0;                  // 64-feature steps per tile (two to a matrix instruction); 0: the model does not fit
+    int tiles = 0, cols = 0;        // tiles of 16 dimensions, columns = varying dimensions
     std::vector<int32_t> items;     // [n][4]: threshold, first tile, dimensions, first column
-    std::vector<uint32_t> bx;       // [tile][step][lane][4]: 4-bit floats +-1 / (sample-side value), bias in the slots past F
+    std::vector<uint32_t> bx;       // [tile][step / 2][lane][4]: 4-bit floats +-1 / (sample-side value), bias in the slots past F
     std::vector<uint32_t> src;      // [32][W]: the column of every varying bit of a row (constant bits: left at 0 here)
     std::vector<uint8_t> is_var;    // [D]
 };
 
 // tiles_per_item tiles of one threshold at most per work item; steps even, at most max_steps.
+// Operand layout: lane 16 b + j of (tile, matrix instruction s) holds column j of the tile
+// against the 32 feature slots 128 s + 32 b ..., a slot's nibble where feature_bit puts the
+// feature's bit in the sample side's plane word.
 inline void build_wide_tables(const ModelView &m, const std::vector<std::vector<int>> &by_tau, int max_steps,
                               int tiles_per_item, WdTables *t_out) {
     WdTables &T = *t_out;
@@ -217,7 +222,7 @@ inline void build_wide_tables(const ModelView &m, const std::vector<std::vector<
     int steps = 0;
     std::vector<float> val;
     WdBias bias;
-    for (int ks = ((F + 63) / 64 + 1) / 2 * 2; ks <= max_steps && !steps; ks += 2) {   // the kernel is built for even counts
+    for (int ks = ((F + 63) / 64 + 1) / 2 * 2; ks <= max_steps && !steps; ks += 2) {   // two steps to a matrix instruction
         if (ks * 64 == F) continue;
         bias.prepare(F, ks * 64, max_halves);
         bool ok = true;
@@ -234,16 +239,17 @@ inline void build_wide_tables(const ModelView &m, const std::vector<std::vector<
     // work items: a threshold and up to tiles_per_item tiles of its dimensions; columns in item order
     T.src.assign((size_t)32 * W, 0u);
     T.is_var.assign((size_t)D, 0);
+    const int per_item = kWdTileCols * tiles_per_item, mis = steps / 2;
     int tiles = 0, cols = 0;
     for (int tau = 1; tau < L; ++tau) {
         const std::vector<int> &dims = by_tau[(size_t)tau];
-        for (size_t at = 0; at < dims.size(); at += (size_t)32 * tiles_per_item) {
-            const int nd = (int)std::min<size_t>(dims.size() - at, (size_t)32 * tiles_per_item);
-            const int nt = (nd + 31) / 32;
+        for (size_t at = 0; at < dims.size(); at += (size_t)per_item) {
+            const int nd = (int)std::min<size_t>(dims.size() - at, (size_t)per_item);
+            const int nt = (nd + kWdTileCols - 1) / kWdTileCols;
             T.items.insert(T.items.end(), {tau, tiles, nd, cols});
-            T.bx.resize((size_t)(tiles + nt) * steps * 64 * 4, 0u);
+            T.bx.resize((size_t)(tiles + nt) * mis * 64 * 4, 0u);
             for (int i = 0; i < nd; ++i) {
-                const int d = dims[at + i], w = d >> 5, b = d & 31, t = tiles + i / 32, j = i & 31;
+                const int d = dims[at + i], w = d >> 5, b = d & 31, t = tiles + i / kWdTileCols, j = i % kWdTileCols;
                 const uint32_t l0 = (m.level[w] >> b) & 1u;
                 T.src[(size_t)b * W + w] = (uint32_t)(cols + i);
                 T.is_var[(size_t)d] = 1;
@@ -256,8 +262,8 @@ inline void build_wide_tables(const ModelView &m, const std::vector<std::vector<
                     } else {
                         nib = fp4_of(val[(size_t)(f - F)]);
                     }
-                    const int k = f >> 6, h = (f >> 5) & 1, at_bit = feature_bit(f);
-                    T.bx[(((size_t)t * steps + k) * 64 + h * 32 + j) * 4 + (at_bit & 3)] |= nib << (4 * (at_bit >> 2));
+                    const int s = f >> 7, blk = (f >> 5) & 3, at_bit = feature_bit(f);
+                    T.bx[(((size_t)t * mis + s) * 64 + blk * kWdTileCols + j) * 4 + (at_bit & 3)] |= nib << (4 * (at_bit >> 2));
                 }
             }
             tiles += nt;

@@ -55,7 +55,7 @@ namespace hdc {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t wd_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t wd_u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t wd_u32x6 __attribute__((ext_vector_type(6)));
@@ -65,12 +65,13 @@ typedef uint32_t wd_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   
 // waves per SIMD, 256 registers each).  Two groups: four waves, and two blocks per compute unit where
 // the LDS holds both, so that one block's tile phase fills the other's loads and stores.
 constexpr int wd_waves_of(int groups) { return 2 * groups; }
-constexpr int kWdTiles = 3;          // tiles of one threshold a wave works on at a time: their model-side operands stay in registers
-constexpr int kWdTilesLong = 2;      // ... of models of more than 6 steps (12 registers a step and tile)
+// Tiles of 16 dimensions of one threshold a wave works on at a time: their model-side operands
+// stay in registers (4 a tile and matrix instruction of 128 feature slots).  Six tiles hold the
+// dimensions of a threshold of the usual models (79 or 80 at D = 10000, L = 64) with room to spare.
+constexpr int kWdTiles = 6;
+constexpr int kWdTilesLong = 5;      // ... of models of more than 6 steps (the operands of six tiles of ten steps do not fit beside the rest)
 constexpr int wd_tiles_of(int steps) { return steps > 6 ? kWdTilesLong : kWdTiles; }
-// Matrix instructions per tile, 64 features each, at most.  Up to 6 steps a wave keeps the operands
-// of three tiles (all the dimensions of a threshold at 79 per threshold); beyond, of two: the
-// operands of three tiles of ten steps do not fit beside the accumulators.
+// Steps of 64 feature slots per tile at most, two to a matrix instruction.
 constexpr int kWdMaxSteps = 10;
 constexpr size_t kWdLdsLimit = 160 * 1024;
 
@@ -143,10 +144,13 @@ int prepare_wide(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *level, c
 }
 
 // Both operands as 4-bit floats (format code 4), no block scales; 16 bytes of each are used.
-__device__ __forceinline__ v16f wd_mfma(v4i a, wd_u32x4 b, v16f c) {
+// 16 samples x 16 dimensions x 128 feature slots: lane 16 b + i brings sample i (first operand) or
+// dimension i (second) against the 32 slots of block b; it gets back dimension i of samples
+// 4 b .. 4 b + 3.
+__device__ __forceinline__ v4f wd_mfma(v4i a, wd_u32x4 b, v4f c) {
     const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
     const v8i b8 = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
 
@@ -180,13 +184,19 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
     typedef typename std::conditional<(NB > 6), wd_u32x4, wd_u32x2>::type plane_b_t;
     plane_b_t *planes_b = reinterpret_cast<plane_b_t *>(wd_lds + 4 + G * KS * kWave * 4);
     uint32_t *over = wd_lds + 4 + G * KS * kWave * (4 + (NB > 6 ? 4 : 2));
-    uint16_t *over16 = reinterpret_cast<uint16_t *>(over);
+    uint8_t *over8 = reinterpret_cast<uint8_t *>(over);
     const uint8_t *bins = reinterpret_cast<const uint8_t *>(over);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int j = lane & 31, h = lane >> 5;
+    static_assert(KS % 2 == 0, "two steps of 64 feature slots to a matrix instruction");
+    constexpr int KH = KS / 2;          // matrix instructions per tile and half group
+    // In the tile phase lane 16 b + i stands for sample i of a half group and the 32 feature slots
+    // of block b of a matrix instruction: step b / 2, half b % 2 of the planes
+    const int jc = lane & 15, kq = lane >> 4;
+    const int plane_lane = (kq >> 1) * kWave + (kq & 1) * 32 + jc;
 
-    wd_u32x4 bm[TB][KS];
+    wd_u32x4 bm[TB][KH];
     const int64_t jobs = (N + kSamples - 1) / kSamples;
     // All blocks start together and a job takes every block the same time, so for their first ten
     // jobs or so (until they have drifted apart by themselves) the whole chip loads, computes and
@@ -294,9 +304,9 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
         __syncthreads();
         if (threadIdx.x < 2 * G) over[(threadIdx.x >> 1) * ovs + ovs - 2 + (threadIdx.x & 1)] = (threadIdx.x & 1) ? 0xffffffffu : 0u;
 
-        // ---- T: a threshold and up to TB tiles of its dimensions per wave and turn.  The tiles'
+        // ---- T: a threshold and up to TB tiles of 16 of its dimensions per wave and turn.  The tiles'
         // model-side operands stay in registers for the G groups; while the last group is worked
-        // on, each is replaced by the next item's as soon as its instruction has been issued.
+        // on, each is replaced by the next item's as soon as its last instruction has been issued.
         // The items are dealt out by a counter: the SIMD favours its older wave, which would be
         // through a fixed share early and leave the younger one to finish alone (1.95 -> 1.75 ms per
         // million samples).  Units of an item and half of the groups, to shorten the wait for the
@@ -313,78 +323,87 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
             int unit_next = claim();
             int4 item = items[min(unit / kSplit, n_items - 1)];
             if (unit < n_units) {
-                const int tile0 = __builtin_amdgcn_readfirstlane(item.y), nt = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
+                const int tile0 = __builtin_amdgcn_readfirstlane(item.y), nt = (__builtin_amdgcn_readfirstlane(item.z) + 15) >> 4;
 #pragma unroll
                 for (int t = 0; t < TB; ++t)
 #pragma unroll
-                    for (int k = 0; k < KS; ++k) bm[t][k] = bx[((size_t)(tile0 + min(t, nt - 1)) * KS + k) * kWave + lane];
+                    for (int k = 0; k < KH; ++k) bm[t][k] = bx[((size_t)(tile0 + min(t, nt - 1)) * KH + k) * kWave + lane];
             }
 #pragma unroll 1
             for (; unit < n_units; unit = unit_next, unit_next = claim()) {
                 const int g0 = (unit % kSplit) * kUnitGroups;
                 const int tau = __builtin_amdgcn_readfirstlane(item.x);
                 const int nd = __builtin_amdgcn_readfirstlane(item.z), col0 = __builtin_amdgcn_readfirstlane(item.w);
-                const int nt = (nd + 31) >> 5;
+                const int nt = (nd + 15) >> 4;
                 const int un = unit_next < n_units ? unit_next : unit;   // (after the wave's last unit: the same again, unused)
                 const int g0_n = (un % kSplit) * kUnitGroups;
                 item = items[un / kSplit];
-                const int tile0_n = __builtin_amdgcn_readfirstlane(item.y), nt_n = (__builtin_amdgcn_readfirstlane(item.z) + 31) >> 5;
+                const int tile0_n = __builtin_amdgcn_readfirstlane(item.y), nt_n = (__builtin_amdgcn_readfirstlane(item.z) + 15) >> 4;
                 const wd_u32x4 *bn[TB];
 #pragma unroll
-                for (int t = 0; t < TB; ++t) bn[t] = bx + (size_t)(tile0_n + min(t, nt_n - 1)) * KS * kWave + lane;
+                for (int t = 0; t < TB; ++t) bn[t] = bx + (size_t)(tile0_n + min(t, nt_n - 1)) * KH * kWave + lane;
                 uint32_t tb[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) tb[b] = (tau >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
-                wd_u32x4 pa = planes_a[g0 * KS * kWave + lane];
-                plane_b_t pb = planes_b[g0 * KS * kWave + lane];
-                // One group of 32 samples against the item's NT tiles (a constant here: no branch in the
-                // loop); the last group also fetches the next item's operands, each as soon as its
-                // last instruction has been issued.
+                wd_u32x4 pa = planes_a[g0 * KS * kWave + plane_lane];
+                plane_b_t pb = planes_b[g0 * KS * kWave + plane_lane];
+                // One group of 32 samples, as two halves of 16, against the item's NT tiles (a
+                // constant here: no branch in the loop); the last group also fetches the next
+                // item's operands, each as soon as its last instruction has been issued.
                 auto group = [&](const int g, auto nt_c, auto last_c) {
                     constexpr int NT = decltype(nt_c)::value;
                     constexpr bool kLast = decltype(last_c)::value;
-                    v16f acc[NT];
-                    const wd_u32x4 *pa_at = planes_a + (kLast ? g0_n : g + 1) * KS * kWave + lane;   // where the planes after this group's are
-                    const plane_b_t *pb_at = planes_b + (kLast ? g0_n : g + 1) * KS * kWave + lane;
-                    const wd_u32x4 *pa_in = planes_a + g * KS * kWave + lane;
-                    const plane_b_t *pb_in = planes_b + g * KS * kWave + lane;
+                    v4f acc[NT][2];
+                    const wd_u32x4 *pa_at = planes_a + (kLast ? g0_n : g + 1) * KS * kWave + plane_lane;   // where the planes after this group's are
+                    const plane_b_t *pb_at = planes_b + (kLast ? g0_n : g + 1) * KS * kWave + plane_lane;
+                    const wd_u32x4 *pa_in = planes_a + g * KS * kWave + plane_lane;
+                    const plane_b_t *pb_in = planes_b + g * KS * kWave + plane_lane;
 #pragma unroll
-                    for (int k = 0; k < KS; ++k) {
-                        // the samples' [q >= tau] over the lane's 32 features, from the least significant plane up
-                        uint32_t qp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], 0u, 0u};
-                        if constexpr (NB > 6) qp[6] = pb[2], qp[7] = pb[3];
-                        if (k + 1 < KS) {   // the next turn's planes
-                            pa = pa_in[(k + 1) * kWave];
-                            pb = pb_in[(k + 1) * kWave];
-                        } else {
-                            pa = pa_at[0];
-                            pb = pb_at[0];
-                        }
-                        uint32_t ge = 0xffffffffu;
+                    for (int k = 0; k < KH; ++k) {
 #pragma unroll
-                        for (int b = 0; b < NB; ++b) ge = __builtin_amdgcn_bitop3_b32(qp[b], ge, tb[b], 0xD4);   // tb ? q & ge : q | ge
-                        const v4i a = {(int)(ge & 0x11111111u), (int)(ge & 0x22222222u), (int)(ge & 0x44444444u),
-                                       (int)((ge >> 1) & 0x44444444u)};
+                        for (int rh = 0; rh < 2; ++rh) {
+                            // the samples' [q >= tau] over the lane's 32 feature slots, from the least significant plane up
+                            uint32_t qp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], 0u, 0u};
+                            if constexpr (NB > 6) qp[6] = pb[2], qp[7] = pb[3];
+                            if (rh == 0) {   // the next turn's planes: the other half group, then the next two steps
+                                pa = pa_in[2 * k * kWave + 16];
+                                pb = pb_in[2 * k * kWave + 16];
+                            } else if (k + 1 < KH) {
+                                pa = pa_in[2 * (k + 1) * kWave];
+                                pb = pb_in[2 * (k + 1) * kWave];
+                            } else {
+                                pa = pa_at[0];
+                                pb = pb_at[0];
+                            }
+                            uint32_t ge = 0xffffffffu;
 #pragma unroll
-                        for (int t = 0; t < NT; ++t) {
-                            if (k == 0) acc[t] = wd_mfma(a, bm[t][k], v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0});
-                            else acc[t] = wd_mfma(a, bm[t][k], acc[t]);
+                            for (int b = 0; b < NB; ++b) ge = __builtin_amdgcn_bitop3_b32(qp[b], ge, tb[b], 0xD4);   // tb ? q & ge : q | ge
+                            const v4i a = {(int)(ge & 0x11111111u), (int)(ge & 0x22222222u), (int)(ge & 0x44444444u),
+                                           (int)((ge >> 1) & 0x44444444u)};
+#pragma unroll
+                            for (int t = 0; t < NT; ++t) {
+                                if (k == 0) acc[t][rh] = wd_mfma(a, bm[t][k], v4f{0, 0, 0, 0});
+                                else acc[t][rh] = wd_mfma(a, bm[t][k], acc[t][rh]);
+                            }
                         }
                         if constexpr (kLast) {
 #pragma unroll
                             for (int t = 0; t < TB; ++t) bm[t][k] = bn[t][k * kWave];
                         }
                     }
-                    // the signs, register 0's highest: bit p of a half word is the sample of register 15 - p
+                    // the signs strung together, the first half group's first register highest: bit
+                    // 7 - (4 rh + r) of the lane's byte is sample 16 rh + 4 kq + r of the group
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         uint32_t bits = 0;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const float d = acc[t][r];
-                            bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
-                        }
-                        if (32 * t + j < nd) over16[(size_t)(g * ovs + col0 + 32 * t + j) * 2 + h] = (uint16_t)bits;
+                        for (int rh = 0; rh < 2; ++rh)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float d = acc[t][rh][r];
+                                bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
+                            }
+                        if (16 * t + jc < nd) over8[((size_t)(g * ovs + col0 + 16 * t + jc) << 2) + kq] = (uint8_t)bits;
                     }
                 };
                 auto run = [&](auto nt_c) {
@@ -392,8 +411,10 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                     for (int g = g0; g < g0 + kUnitGroups - 1; ++g) group(g, nt_c, std::false_type{});
                     group(g0 + kUnitGroups - 1, nt_c, std::true_type{});
                 };
-                if (nt == 1) run(std::integral_constant<int, 1>{});
-                else if (nt == 2 || TB == 2) run(std::integral_constant<int, 2>{});
+                if (nt <= 1) run(std::integral_constant<int, 1>{});
+                else if (nt == 2) run(std::integral_constant<int, 2>{});
+                else if (nt == 3 && TB > 3) run(std::integral_constant<int, 3>{});
+                else if (nt <= 5 && TB > 5) run(std::integral_constant<int, 5>{});
                 else run(std::integral_constant<int, TB>{});
             }
         }
@@ -473,8 +494,9 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                             x[i + k] = ((lo >> k) & m) | (hi & ~m);
                         }
                 }
-                // bit p of a word of `over` is the sample of register 15 - p of lane half 0 (p < 16) or
-                // register 31 - p of half 1; register r of half h is sample 8 (r / 4) + 4 h + r % 4 of the group.
+                // bit p of a word of `over`: byte p / 8 came from the lanes of feature block p / 8, whose
+                // registers hold samples 4 (p / 8) .. + 3 of either half group; bit 7 - (4 rh + r) of the byte is
+                // register r of half group rh.
                 // The rows go past the caches (streaming stores): a long stream's rows are read again
                 // only after many more have been written, and kept in the L2 they push out the next
                 // job's features and leave the kernel that reads the rows next a cache full of lines
@@ -483,8 +505,7 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                     uint8_t *out = reinterpret_cast<uint8_t *>(hv + (first + 32 * g) * W);   // wave-uniform
 #pragma unroll
                     for (int p = 0; p < 32; ++p) {
-                        const int r = p < 16 ? 15 - p : 31 - p;
-                        const int sn = 8 * (r >> 2) + (p < 16 ? 0 : 4) + (r & 3);
+                        const int sn = 16 * ((7 - (p & 7)) >> 2) + 4 * (p >> 3) + ((7 - (p & 7)) & 3);
                         if (whole || first + 32 * g + sn < N) __builtin_nontemporal_store(x[p], reinterpret_cast<uint32_t *>(out + 4u * (uint32_t)(sn * W + w)));
                     }
                 }
@@ -508,10 +529,10 @@ static int launch_wide(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out,
     const int64_t blocks = std::min<int64_t>(jobs, (int64_t)c->num_cus * per_cu);
     // Start offsets between blocks (see the kernel): a sixteenth of a job's time per step, eight steps, from ten
     // jobs per block on.  A job takes about 3.2 times what its matrix instructions take alone
-    // (15.2 ns each, four SIMDs).
+    // (7.6 ns each, four SIMDs).
     int stagger = 0;
     if (jobs >= 10 * blocks) {
-        const double job_us = (double)c->wd_tiles * KS * G * 0.0152 / 4.0 * 3.2;
+        const double job_us = (double)c->wd_tiles * KS * G * 0.0076 / 4.0 * 3.2;
         stagger = (int)std::min(job_us * 100.0 / 16.0, 1000.0);   // in 10 ns; at most 10 us a step
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(wd_waves_of(G) * kWave), lds, s, x, n, c->p.F, c->p.L, c->lo_d,

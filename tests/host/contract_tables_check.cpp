@@ -153,7 +153,7 @@ static bool check_wide(const Model &m, const std::vector<std::vector<int>> &by_t
     std::vector<uint32_t> src2;
     if (!hdc::wide_place_table(T, crow.data(), m.D, m.W, &src2)) FAIL("wide: placement table");
     const int n_items = (int)(T.items.size() / 4);
-    if (T.bx.size() != (size_t)T.tiles * T.steps * 64 * 4) FAIL("wide: operand table size");
+    if (T.bx.size() != (size_t)T.tiles * (T.steps / 2) * 64 * 4) FAIL("wide: operand table size");
     for (int s = 0; s < samples; ++s) {
         std::vector<int> q((size_t)m.F);
         for (int f = 0; f < m.F; ++f) q[(size_t)f] = s == 0 ? 0 : s == 1 ? m.L - 1 : (int)(rnd() % (uint32_t)m.L);
@@ -165,16 +165,17 @@ static bool check_wide(const Model &m, const std::vector<std::vector<int>> &by_t
         for (int it = 0; it < n_items; ++it) {
             const int tau = T.items[(size_t)4 * it], tile0 = T.items[(size_t)4 * it + 1], nd = T.items[(size_t)4 * it + 2],
                       col0 = T.items[(size_t)4 * it + 3];
-            if (tau < 1 || tau >= m.L || nd < 1 || nd > 32 * tiles_per_item || tile0 != next_tile || col0 != next_col) FAIL("wide: item %d", it);
-            next_tile += (nd + 31) / 32, next_col += nd;
+            if (tau < 1 || tau >= m.L || nd < 1 || nd > 16 * tiles_per_item || tile0 != next_tile || col0 != next_col) FAIL("wide: item %d", it);
+            next_tile += (nd + 15) / 16, next_col += nd;
             for (int i = 0; i < nd; ++i) {
-                const int t = tile0 + i / 32, j = i & 31;
+                const int t = tile0 + i / 16, j = i & 15;
                 float acc = 0.0f;
                 for (int f = 0; f < T.steps * 64; ++f) {
                     const bool u = f < m.F ? q[(size_t)f] >= tau : true;   // (slots past F: bin number all ones)
                     if (!u) continue;
-                    const int k = f >> 6, h = (f >> 5) & 1, p = hdc::feature_bit(f);
-                    const uint32_t word = T.bx[(((size_t)t * T.steps + k) * 64 + h * 32 + j) * 4 + (p & 3)];
+                    // (the kernel's lane 16 b + j of matrix instruction mi: column j, the 32 slots of block b of its 128)
+                    const int mi = f / 128, blk = (f % 128) / 32, p = hdc::feature_bit(f);
+                    const uint32_t word = T.bx[(((size_t)t * (T.steps / 2) + mi) * 64 + 16 * blk + j) * 4 + (p & 3)];
                     acc += hdc::wd_sample_value(f) * hdc::fp4_value((word >> (4 * (p >> 2))) & 15u);
                 }
                 if (acc == 0.0f) FAIL("wide: a sum of exactly zero (the threshold slots must leave a half)");
@@ -209,7 +210,7 @@ int main() {
         {300, 383, 8, 20, true},       // one spare slot in six steps cannot carry the thresholds: eight steps
         {96, 4, 2, 40, true},          // the smallest model
         {640, 129, 256, 2, true},      // many thresholds of two dimensions
-        {1500, 617, 64, 11, true},     // ten steps: two tiles of a threshold per work item
+        {1500, 617, 64, 11, true},     // ten steps: five tiles of a threshold per work item
     };
     long checked = 0;
     for (const Shape &sh : shapes) {
@@ -223,9 +224,9 @@ int main() {
         constant_row(m, by_tau, &crow);
         for (int v = 0; v < 3 && (1 << v) <= m.W; ++v)
             if (!check_contract(m, by_tau, crow, v, 6)) return 1;
-        if (!check_wide(m, by_tau, crow, 10, 3, 6, sh.wide_fits)) return 1;
-        if (!check_wide(m, by_tau, crow, 10, 2, 4, sh.wide_fits)) return 1;
-        if (!check_wide(m, by_tau, crow, 6, 3, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
+        if (!check_wide(m, by_tau, crow, 10, 6, 6, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 10, 5, 4, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 6, 6, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
         ++checked;
     }
     {   // a dimension that flips and flips back is refused
