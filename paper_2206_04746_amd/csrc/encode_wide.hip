@@ -20,29 +20,30 @@
 //   Q  it loads and quantises the job (cache hits: the lines were touched while the previous
 //      job's rows were written), leaves the bin numbers in LDS a byte each, and turns them into
 //      bit planes over the features, [group][step] of 64 lanes x NB words, in LDS;
-//   T  a wave takes a threshold and up to three tiles of 32 of its dimensions at a time.  The
+//   T  a wave takes a threshold and up to six tiles of 16 of its dimensions at a time.  The
 //      tiles' model-side operands come ready-made from memory, 16 bytes a lane (L2 hits: every
-//      block reads the same table), and stay in registers for the G groups.  Per group and step of
-//      64 features the wave reads the planes, forms [q >= t] with one 3-input bit operation per
-//      plane and the four operand words with five more instructions, and issues three matrix
-//      instructions: 11 vector instructions per 3 matrix instructions, against 19 per matrix
-//      instruction in encode_contract.hip.  The signs of a lane's 16 accumulators, strung
-//      together, are the word "dimension x 16 samples", left in LDS;
+//      block reads the same table), and stay in registers for the G groups.  The matrix
+//      instruction is the 16 samples x 16 dimensions x 128 feature slots one: per group, half
+//      group and 128 slots the wave reads the planes, forms [q >= t] with one 3-input bit
+//      operation per plane and the four operand words with five more instructions, and issues
+//      an instruction per tile: 11 vector instructions per five or six matrix instructions of 16
+//      clocks (the 32 x 32 x 64 instruction, 32 clocks, got three per operand: a threshold's 79
+//      or 80 dimensions at D = 10000, L = 64 left its third tile of 32 half empty; 19 per
+//      matrix instruction in encode_contract.hip).  The signs of a lane's 8 accumulators of a
+//      tile, strung together, are a byte of the word "dimension x 32 samples", left in LDS;
 //   P  a wave places 64 words of a group's 32 rows at a time: a lane collects the 32 words of
 //      its row word (a table names the column of every bit; constant bits of the model point at
 //      an all-zero or all-one word), transposes 32 x 32 bits in registers and writes the word
 //      of the 32 rows.
-// What bounds it (measured with clock stamps per phase, 342 features, 128 samples a job): Q takes 7,
-// T 33 and P 15 us of a job's 56.  In T a SIMD's two waves issue 36 us' worth of work if counted
-// one after the other: 17 us of matrix instructions (32 clocks each, one at a time per SIMD,
-// whatever the number of accumulators in flight) and 14 us of vector instructions (6.5 per matrix
-// instruction: 3.7 for the operands, 2.8 to string the signs together), and that sum is what
-// the phase takes.  A wave issues in order, so its own two kinds never overlap; its SIMD
-// partner's vector instructions overlap a matrix instruction only up to about four per
-// instruction when the accumulators are vector registers (a replica of the loop, with parts
-// taken away, gives the same sum; spreading the sign work over the steps with a second set of
-// accumulators, wave priorities around the matrix instructions, plane reads two steps ahead
-// and barriers that wait for the LDS only changed nothing).
+// What bounds it (342 features, 128 samples a job): T takes 25, P 9 and Q 3 us of a job's 45.
+// In T a SIMD's two waves issue, per threshold and group, 30 matrix instructions (16 clocks each,
+// one at a time per SIMD) and 106 vector instructions (66 for the operands, 40 to string the
+// signs together), 904 clocks if counted one after the other, and that sum is what they take.
+// A wave issues in order, so its own two kinds never overlap, and its SIMD partner's overlap
+// little (a replica of the loop, with parts taken away, gives the same sum; spreading the sign
+// work over the steps with a second set of accumulators, wave priorities around the matrix
+// instructions, plane reads two steps ahead and barriers that wait for the LDS only changed
+// nothing).
 #include "hdc_internal.h"
 #include "contract_tables.h"
 

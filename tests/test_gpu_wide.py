@@ -56,7 +56,7 @@ def _oracle(wl, x):
     (3, 3000, 324, 200, 65536 - 17),     # u8 features, 8 planes
     (5, 16384, 342, 64, 32768 - 5),      # the LDS holds two groups per job only
     (2, 96, 10, 3, 70000),               # a handful of dimensions
-    (2, 10000, 617, 64, 65536 - 7),      # 10 steps: two tiles of a threshold at a time
+    (2, 10000, 617, 64, 65536 - 7),      # 10 steps: five tiles of a threshold at a time
     (4, 10000, 561, 64, 65536 - 100),    # 10 steps, 561 features
     (2, 5000, 500, 64, 65536 - 11),      # 8 steps
     (3, 2048, 576, 32, 65536 - 29),      # u8 features, 10 steps (9 of them features)
