@@ -67,10 +67,11 @@ typedef uint32_t wd_u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   
 // the LDS holds both, so that one block's tile phase fills the other's loads and stores.
 constexpr int wd_waves_of(int groups) { return 2 * groups; }
 // Tiles of 16 dimensions of one threshold a wave works on at a time: their model-side operands
-// stay in registers (4 a tile and matrix instruction of 128 feature slots).  Six tiles hold the
-// dimensions of a threshold of the usual models (79 or 80 at D = 10000, L = 64) with room to spare.
-constexpr int kWdTiles = 6;
-constexpr int kWdTilesLong = 5;      // ... of models of more than 6 steps (the operands of six tiles of ten steps do not fit beside the rest)
+// stay in registers (4 a tile and matrix instruction of 128 feature slots).  Five tiles hold the
+// dimensions of a threshold of the usual models (79 or 80 at D = 10000, L = 64); a threshold
+// with more is several items.
+constexpr int kWdTiles = 5;
+constexpr int kWdTilesLong = 5;      // ... of models of more than 6 steps
 constexpr int wd_tiles_of(int steps) { return steps > 6 ? kWdTilesLong : kWdTiles; }
 // Steps of 64 feature slots per tile at most, two to a matrix instruction.
 constexpr int kWdMaxSteps = 10;
@@ -307,7 +308,9 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
 
         // ---- T: a threshold and up to TB tiles of 16 of its dimensions per wave and turn.  The tiles'
         // model-side operands stay in registers for the G groups; while the last group is worked
-        // on, each is replaced by the next item's as soon as its last instruction has been issued.
+        // on, each is replaced by the next item's as soon as its last instruction has been issued
+        // (those of the first matrix instruction, wanted first, wait in registers of their own
+        // from the item's start: 1 % of the kernel).
         // The items are dealt out by a counter: the SIMD favours its older wave, which would be
         // through a fixed share early and leave the younger one to finish alone (1.95 -> 1.75 ms per
         // million samples).  Units of an item and half of the groups, to shorten the wait for the
@@ -343,6 +346,11 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                 const wd_u32x4 *bn[TB];
 #pragma unroll
                 for (int t = 0; t < TB; ++t) bn[t] = bx + (size_t)(tile0_n + min(t, nt_n - 1)) * KH * kWave + lane;
+                // the next item's operands of the first matrix instruction are asked for now, a whole
+                // item ahead (those of the others replace this item's in its last group, a group ahead)
+                wd_u32x4 b0n[TB];
+#pragma unroll
+                for (int t = 0; t < TB; ++t) b0n[t] = bn[t][0];
                 uint32_t tb[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) tb[b] = (tau >> b) & 1 ? 0xffffffffu : 0u;   // wave-uniform
@@ -388,8 +396,10 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                             }
                         }
                         if constexpr (kLast) {
+                            if (k > 0) {
 #pragma unroll
-                            for (int t = 0; t < TB; ++t) bm[t][k] = bn[t][k * kWave];
+                                for (int t = 0; t < TB; ++t) bm[t][k] = bn[t][k * kWave];
+                            }
                         }
                     }
                     // the signs strung together, the first half group's first register highest: bit
@@ -415,8 +425,9 @@ __global__ __launch_bounds__(wd_waves_of(G) * kWave, 2) void encode_wide_kernel(
                 if (nt <= 1) run(std::integral_constant<int, 1>{});
                 else if (nt == 2) run(std::integral_constant<int, 2>{});
                 else if (nt == 3 && TB > 3) run(std::integral_constant<int, 3>{});
-                else if (nt <= 5 && TB > 5) run(std::integral_constant<int, 5>{});
                 else run(std::integral_constant<int, TB>{});
+#pragma unroll
+                for (int t = 0; t < TB; ++t) bm[t][0] = b0n[t];
             }
         }
         __syncthreads();

@@ -224,9 +224,9 @@ int main() {
         constant_row(m, by_tau, &crow);
         for (int v = 0; v < 3 && (1 << v) <= m.W; ++v)
             if (!check_contract(m, by_tau, crow, v, 6)) return 1;
-        if (!check_wide(m, by_tau, crow, 10, 6, 6, sh.wide_fits)) return 1;
-        if (!check_wide(m, by_tau, crow, 10, 5, 4, sh.wide_fits)) return 1;
-        if (!check_wide(m, by_tau, crow, 6, 6, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
+        if (!check_wide(m, by_tau, crow, 10, 5, 6, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 10, 3, 4, sh.wide_fits)) return 1;
+        if (!check_wide(m, by_tau, crow, 6, 5, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
         ++checked;
     }
     {   // a dimension that flips and flips back is refused
