@@ -20,13 +20,13 @@
 //   Q  it loads and quantises the job (cache hits: the lines were touched while the previous
 //      job's rows were written), leaves the bin numbers in LDS a byte each, and turns them into
 //      bit planes over the features, [group][step] of 64 lanes x NB words, in LDS;
-//   T  a wave takes a threshold and up to six tiles of 16 of its dimensions at a time.  The
+//   T  a wave takes a threshold and up to five tiles of 16 of its dimensions at a time.  The
 //      tiles' model-side operands come ready-made from memory, 16 bytes a lane (L2 hits: every
 //      block reads the same table), and stay in registers for the G groups.  The matrix
 //      instruction is the 16 samples x 16 dimensions x 128 feature slots one: per group, half
 //      group and 128 slots the wave reads the planes, forms [q >= t] with one 3-input bit
 //      operation per plane and the four operand words with five more instructions, and issues
-//      an instruction per tile: 11 vector instructions per five or six matrix instructions of 16
+//      an instruction per tile: 11 vector instructions per five matrix instructions of 16
 //      clocks (the 32 x 32 x 64 instruction, 32 clocks, got three per operand: a threshold's 79
 //      or 80 dimensions at D = 10000, L = 64 left its third tile of 32 half empty; 19 per
 //      matrix instruction in encode_contract.hip).  The signs of a lane's 8 accumulators of a
