@@ -457,79 +457,100 @@ __device__ __forceinline__ void count_rows(uint32_t (&pl)[KPL][kRowsPlanes], con
     }
 }
 
-// The 16 waves' counts (eight planes per lane and word position) meet in LDS in two rounds
-// (waves 8..15 into 0..7, then 1..7 into 0); the block total, twelve planes, goes back through
-// LDS so that wave k turns position k into 16-bit sums, 32 dimensions per lane as 16 dwords
-// (pad columns store zeros), at dst + word_of(k, lane) * 16.  All threads of the block call it; four
-// barriers inside.  merge: 8 x KPL x 9 planes of 64 words.  extra (block-uniform, may be
-// null): one more count of at most 248 parked elsewhere in LDS, KPL x 9 planes of 64 words.
+// x[b] bit p  ->  x[p] bit b (32 x 32 bits per lane): halves and bytes trade places by byte
+// permutes, the finer stages by masked merges.  Registers known to be zero cost nothing.
+__device__ __forceinline__ void transpose32(uint32_t (&x)[32]) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t lo = x[i], hi = x[i + 16];
+        x[i] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        x[i + 16] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+        if ((i & 8) == 0) {
+            const uint32_t lo = x[i], hi = x[i + 8];
+            x[i] = __builtin_amdgcn_perm(hi, lo, 0x06020400u);
+            x[i + 8] = __builtin_amdgcn_perm(hi, lo, 0x07030501u);
+        }
+#pragma unroll
+    for (int stage = 2; stage < 5; ++stage) {
+        const int k = 16 >> stage;
+        const uint32_t m = stage == 2 ? 0x0f0f0f0fu : stage == 3 ? 0x33333333u : 0x55555555u;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            if ((i & k) == 0) {
+                const uint32_t lo = x[i], hi = x[i + k];
+                x[i] = (lo & m) | ((hi << k) & ~m);
+                x[i + k] = ((lo >> k) & m) | (hi & ~m);
+            }
+    }
+}
+
+// The 16 waves' counts (eight planes per lane and word position; pl's ninth plane comes in zero)
+// meet in LDS: waves 8..15 park theirs and waves 0..7 add them to their own (nine planes), park
+// the sums in the same slots, and then wave k adds up position k of the eight slots - and of
+// `extra`, one more count of at most 248 parked elsewhere in LDS in the same layout (block-
+// uniform, may be null) - into the block total, twelve planes, turns the planes into 32 counts
+// by a bit transposition and writes them as 16-bit sums, 32 dimensions per lane as 16 dwords
+// (pad columns store zeros), at dst + word_of(k, lane) * 16.  All threads of the block call it;
+// two barriers inside, and the caller keeps the slots untouched until every wave is through
+// (a barrier, or the kernel's end).  merge: 8 slots of KPL x 9 planes of 64 words.  (Adding the
+// eight sums up in wave 0 alone, every position, and turning planes into sums bit by bit took
+// 14 us per call and block; this form about 4.)
 template <int KPL, bool QUAD>
-__device__ __forceinline__ void merge_and_store(uint32_t (&pl)[KPL][12], uint32_t *merge, const int wave,
+__device__ __forceinline__ void merge_and_store(uint32_t (&pl)[KPL][9], uint32_t *merge, const int wave,
                                                 const int lane, const int Wp, uint32_t *dst_row,
                                                 const uint32_t *extra = nullptr) {
-    auto park = [&](const int slot, const int planes) {
-        uint32_t *dst = merge + (size_t)slot * (KPL * 9 * kWave) + lane;
+    constexpr int kSlot = KPL * 9 * kWave;
+    if (wave >= 8) {
+        uint32_t *dst = merge + (size_t)(wave - 8) * kSlot + lane;
 #pragma unroll
         for (int k = 0; k < KPL; ++k)
 #pragma unroll
-            for (int i = 0; i < 9; ++i)
-                if (i < planes) dst[(k * 9 + i) * kWave] = pl[k][i];
-    };
-    auto take_at = [&](const uint32_t *slot, const int planes) {   // pl += the parked number of `planes` planes
-        const uint32_t *src = slot + lane;
+            for (int i = 0; i < kRowsPlanes; ++i) dst[(k * 9 + i) * kWave] = pl[k][i];
+    }
+    __syncthreads();
+    if (wave < 8) {   // at most 496 rows: nine planes, back into the slot they came from
+        uint32_t *slot = merge + (size_t)wave * kSlot + lane;
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             uint32_t carry = 0;
 #pragma unroll
-            for (int i = 0; i < 12; ++i) {
-                const uint32_t a = pl[k][i], b = i < planes ? src[(k * 9 + i) * kWave] : 0u;
-                pl[k][i] = xor3(a, b, carry);
+            for (int i = 0; i < kRowsPlanes; ++i) {
+                const uint32_t a = pl[k][i], b = slot[(k * 9 + i) * kWave];
+                slot[(k * 9 + i) * kWave] = xor3(a, b, carry);
                 carry = maj3(a, b, carry);
             }
+            slot[(k * 9 + kRowsPlanes) * kWave] = carry;
         }
-    };
-    auto take = [&](const int slot, const int planes) { take_at(merge + (size_t)slot * (KPL * 9 * kWave), planes); };
-    if (wave >= 8) park(wave - 8, kRowsPlanes);
-    __syncthreads();
-    if (wave < 8) take(wave, kRowsPlanes);      // at most 496 rows: nine planes
-    if (wave == 0 && extra) take_at(extra, kRowsPlanes);   // (a seventeenth count of at most 248, parked in the same layout)
-    __syncthreads();
-    if (wave >= 1 && wave < 8) park(wave, 9);
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll 1
-        for (int w = 1; w < 8; ++w) take(w, 9);   // the block total stays below 2^12
-    }
-    __syncthreads();
-    uint32_t *tot = merge;
-    if (wave == 0) {
-#pragma unroll
-        for (int k = 0; k < KPL; ++k)
-#pragma unroll
-            for (int i = 0; i < 12; ++i) tot[(k * 12 + i) * kWave + lane] = pl[k][i];
     }
     __syncthreads();
     if (wave >= KPL) return;
     const int col = word_of<QUAD>(wave, lane);
-    if (col >= Wp) return;
-    uint32_t t12[12];
+    uint32_t x[32];
 #pragma unroll
-    for (int i = 0; i < 12; ++i) t12[i] = tot[(wave * 12 + i) * kWave + lane];
+    for (int i = 0; i < 32; ++i) x[i] = 0;
+    auto add = [&](const uint32_t *from, const int planes) {   // x += position `wave` of a parked count
+        const uint32_t *src = from + (size_t)(wave * 9) * kWave + lane;
+        uint32_t carry = 0;
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            const uint32_t a = x[i], b = i < planes ? src[i * kWave] : 0u;
+            x[i] = xor3(a, b, carry);
+            carry = maj3(a, b, carry);
+        }
+    };
+#pragma unroll
+    for (int w = 0; w < 8; ++w) add(merge + (size_t)w * kSlot, 9);
+    if (extra) add(extra, kRowsPlanes);   // (the block total stays below 2^12)
+    if (col >= Wp) return;
+    transpose32(x);   // x[p] = the count of the word's dimension p
     uint4 *dst = reinterpret_cast<uint4 *>(dst_row + (size_t)col * 16);
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-        uint32_t w4[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int b0 = (q4 * 4 + k) * 2;
-            uint32_t v = 0;
-#pragma unroll
-            for (int i = 0; i < 12; ++i)
-                v |= (((t12[i] >> b0) & 1u) << i) | (((t12[i] >> (b0 + 1)) & 1u) << (16 + i));
-            w4[k] = v;
-        }
-        dst[q4] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-    }
+    for (int q4 = 0; q4 < 4; ++q4)
+        dst[q4] = make_uint4(x[8 * q4] | (x[8 * q4 + 1] << 16), x[8 * q4 + 2] | (x[8 * q4 + 3] << 16),
+                             x[8 * q4 + 4] | (x[8 * q4 + 5] << 16), x[8 * q4 + 6] | (x[8 * q4 + 7] << 16));
 }
 
 template <int KPL, bool QUAD>
@@ -563,11 +584,11 @@ __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_rows_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) row[j] = hv + (int64_t)idx[min(r0 + (uint32_t)j, last)] * W;
     });
-    uint32_t t[KPL][12];
+    uint32_t t[KPL][9];
 #pragma unroll
     for (int k = 0; k < KPL; ++k)
 #pragma unroll
-        for (int i = 0; i < 12; ++i) t[k][i] = (i < kRowsPlanes && word_of<QUAD>(k, lane) < W) ? pl[k][i] : 0u;
+        for (int i = 0; i < 9; ++i) t[k][i] = (i < kRowsPlanes && word_of<QUAD>(k, lane) < W) ? pl[k][i] : 0u;
     merge_and_store<KPL, QUAD>(t, merge, wave, lane, Wp, partial + (size_t)item * Wp * 16);
 }
 
@@ -681,11 +702,11 @@ __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_local_kernel(
     }
     __syncthreads();
     for (int c = 0; c < C; ++c) {
-        uint32_t t[KPL][12];
+        uint32_t t[KPL][9];
 #pragma unroll
         for (int k = 0; k < KPL; ++k)
 #pragma unroll
-            for (int i = 0; i < 12; ++i) t[k][i] = (i < kRowsPlanes && mine_c == c) ? (pl[k][i] & mine[k]) : 0u;
+            for (int i = 0; i < 9; ++i) t[k][i] = (i < kRowsPlanes && mine_c == c) ? (pl[k][i] & mine[k]) : 0u;
         const uint32_t *extra = used_s[c] ? merge + (size_t)(8 + c) * kSlotWords : nullptr;
         merge_and_store<KPL, QUAD>(t, merge, wave, lane, Wp, partial + ((size_t)c * gridDim.x + blockIdx.x) * Wp * 16, extra);
         __syncthreads();   // (the totals in LDS have been read before the next class parks there)
