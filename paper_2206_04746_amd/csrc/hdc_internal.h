@@ -116,12 +116,12 @@ struct hdc_ctx_impl {
     // The same contraction for long streams (encode_wide.hip): jobs of 32 * wd_groups samples, the
     // model-side operands ready-made, the vote threshold folded into the contraction.
     bool wd_ready;
-    int wd_steps, wd_nb, wd_groups;   // matrix instructions per tile, bit planes of a bin number (6 or 8), groups of 32 samples per job
-    int wd_items;               // work items: a threshold and up to three tiles of its dimensions
-    int wd_tiles;               // tiles of 32 dimensions of all items together
+    int wd_steps, wd_nb, wd_groups;   // steps of 64 feature slots per tile (two to a matrix instruction), bit planes of a bin number (6 or 8), groups of 32 samples per job
+    int wd_items;               // work items: a threshold and up to five tiles of its dimensions
+    int wd_tiles;               // tiles of 16 dimensions of all items together
     int wd_ovs;                 // words per group of the kernel's column array: the varying dimensions, an all-zero and an all-one word
     int32_t *wd_items_d;        // [wd_items][4] threshold, first tile, dimensions, first column
-    uint32_t *wd_bx_d;          // [tiles][wd_steps][64][4] model-side operands: 4-bit floats +-1 / (sample-side value), bias in the slots past F
+    uint32_t *wd_bx_d;          // [tiles][wd_steps / 2][64][4] model-side operands: 4-bit floats +-1 / (sample-side value), bias in the slots past F
     uint32_t *wd_src_d;         // [32][W] per bit of every word of a row: the column that holds it
 
     // Launch properties looked up once per context (kept here, not in function-local statics,
