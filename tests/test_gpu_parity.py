@@ -148,6 +148,8 @@ def gpu_classical(ctx, hv_d, y, acc=None, cn=None):
                                    (10000, 2, 70001), (4000, 26, 40000), (64, 1000, 50000),
                                    (2000, 1, 40001), (512, 3, 150000), (320, 2, 300007),
                                    (3000, 4, 260000), (10000, 5, 33000), (9000, 2, 8193),
+                                   # rows of more than 320 words: grouped rows, a slice of 64 words per wave
+                                   (12000, 2, 40000), (20000, 3, 20001), (10400, 1, 9000),
                                    # the fused launch at its row limit: everything in one or two classes,
                                    # many classes, a dimension count that is no multiple of 4, very wide rows
                                    (10000, 1, 8192), (10000, 2, 8192), (1024, 1000, 8000), (10001, 3, 5000),
