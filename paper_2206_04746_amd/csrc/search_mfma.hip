@@ -40,8 +40,15 @@
 // the wave half).  Each wave writes its partial dot products (at most 64 * 4P each: two to a
 // 32-bit word) to its LDS area; after a barrier wave w adds up, over the eight waves, four
 // registers of one tile, turns them into keys (distance, class) and takes their minimum; after
-// a second barrier 64 threads take the minimum over the four register groups.  Slot 31 holds an all-ones class: its dot product is
-// popcount(x), needed only when distances are written out.  Hence C <= 31.
+// a second barrier 64 threads take the minimum over the four register groups.  Slot 31 holds an
+// all-ones class: its dot product is popcount(x), needed only when distances are written out.
+// Hence 31 classes to a pass.  More classes (up to 124) take up to four passes over the same row
+// images, each with class words of its own in registers; the running minimum of a query's keys
+// stays in the reducing wave's registers between the passes, and the partial sums of consecutive
+// passes go to two LDS areas used in turn, so that a pass costs one barrier.  Rows too long for
+// 64 images in LDS (D above 10240 or so) are taken 32 at a time, one tile of queries per job,
+// with one pass.  Beyond what one launch holds the classes are dealt out over several launches:
+// all but the last leave a query's best key so far in pred[], all but the first start from it.
 #include "hdc_internal.h"
 
 #include <algorithm>
@@ -58,32 +65,33 @@ typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 constexpr int kMfmaWaves = 8;    // per block: two per SIMD, one block per CU
 constexpr int kSlots = 32;       // class slots of an MFMA (its M)
 constexpr int kTile = 32;        // queries of an MFMA (its N)
-constexpr int kTiles = 2;        // tiles a block carries at a time
-constexpr int kJob = kTile * kTiles;
-constexpr int kWaveRows = kJob / kMfmaWaves;   // rows of a job a wave fetches
+constexpr int kMaxTiles = 2;     // tiles of queries a block carries at a time: two, or one where the rows are long
 constexpr int kOnes = kSlots - 1;              // the slot of the all-ones class
-constexpr int kPartialBytes = kTiles * 8 * kWave * 4;    // a wave's partial dot products, two to a word
-constexpr int kRegs = kTiles * 16 / kMfmaWaves;          // accumulator registers a wave reduces (of one tile)
-constexpr int kGroups = 16 / kRegs;                     // such groups per tile
-static_assert(kRegs == 4, "two packed words per lane and group");
+constexpr int kPassClasses = kOnes;            // classes of a pass
+constexpr int kMaxPasses = 4;
+constexpr int kRegs = 4;                       // accumulator registers a wave reduces (of one tile): two packed words per lane
+constexpr int kGroups = 16 / kRegs;            // such groups per tile; wave w reduces group w % 4 of tile w / 4
+constexpr int partial_bytes(int tiles) { return tiles * 8 * kWave * 4; }   // a wave's partial dot products, two to a word
 
 // Host and device agree on the geometry of a row: the first half is s0 words (a multiple of 4, so
 // that both halves start on a 16-byte boundary of the row), each wave takes 4P words of each half,
 // and a row's image in LDS is row_bytes long (an odd number of 16-byte units: the 16-byte reads of
 // 8 neighbouring lanes, a row each, then fall into different banks).
 struct RowGeo {
-    int s0, pieces, row_bytes;
+    int s0, pieces, row_bytes, tiles, passes;
     size_t lds_bytes;
 };
-static inline RowGeo row_geo(int W) {
+static inline RowGeo row_geo(int W, int tiles, int passes) {
     RowGeo g;
+    g.tiles = tiles;
+    g.passes = passes;
     g.s0 = ((W + 1) / 2 + 3) / 4 * 4;
     g.pieces = (g.s0 / 4 + kMfmaWaves - 1) / kMfmaWaves;
     const int units = (W + 3) / 4;
     g.row_bytes = 16 * (units | 1);
     // the last wave's slice of the second half may reach past the last row's image: one more image of slack
-    g.lds_bytes = (size_t)(kSlots + 2 * kTiles * kGroups * kTile) * 4 + (size_t)(kJob + 1) * g.row_bytes +
-                  (size_t)kMfmaWaves * kPartialBytes;
+    g.lds_bytes = (size_t)(kSlots * passes + 2 * tiles * kGroups * kTile) * 4 + (size_t)(tiles * kTile + 1) * g.row_bytes +
+                  (size_t)(passes > 1 ? 2 : 1) * kMfmaWaves * partial_bytes(tiles);
     return g;
 }
 
@@ -98,16 +106,24 @@ __device__ __forceinline__ v16f mfma(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-// Dynamic LDS: popcount(m_c) [32], keys [2 tiles][4 groups][32 queries], popcount(x) parts of the
-// same shape, the images of the job's 64 rows (and one of slack), then the waves' partial sums.
-template <int P, bool kDist>
+// Dynamic LDS: popcount(m_c) [32 a pass], keys [tiles][4 groups][32 queries], popcount(x) parts of
+// the same shape, the images of the job's rows (and one of slack), then the waves' partial sums
+// (two areas where there are several passes).
+template <int P, int kTiles, int kPasses, bool kDist>
 __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     const uint32_t *__restrict__ hv, int64_t N, const uint32_t *__restrict__ class_hv, int C, int W, int D,
-    int s0, int row_bytes, uint32_t *__restrict__ dist, int32_t *__restrict__ pred) {
-    constexpr int kSteps = 4 * P;      // words of a row half per wave = MFMA steps per job
-    constexpr int kLoads = 2 * P;      // 16-byte loads per lane per job: 8 rows of at most 16P pieces over 64 lanes
+    int s0, int row_bytes, uint32_t *__restrict__ dist, int32_t *__restrict__ pred, int c0, int Cn, int keys_in,
+    int keys_out) {
+    // this launch: classes c0 .. c0 + Cn - 1 of the C; keys_in: pred[] holds the best key of the
+    // classes before c0; keys_out: leave the key there, not the class
+    constexpr int kJob = kTile * kTiles;
+    constexpr int kWaveRows = kJob / kMfmaWaves;   // rows of a job a wave fetches
+    constexpr int kPartialBytes = partial_bytes(kTiles);
+    constexpr int kAreaBytes = kMfmaWaves * kPartialBytes;
+    constexpr int kSteps = 4 * P;      // words of a row half per wave = MFMA steps per job and pass
+    constexpr int kLoads = kTiles * P; // 16-byte loads per lane per job: a wave's rows of at most 16P pieces over 64 lanes
     extern __shared__ uint32_t popc_m[];
-    int *keyq = reinterpret_cast<int *>(popc_m + kSlots);
+    int *keyq = reinterpret_cast<int *>(popc_m + kSlots * kPasses);
     int *popx = keyq + kTiles * kGroups * kTile;
     char *rows = reinterpret_cast<char *>(popx + kTiles * kGroups * kTile);
     char *partials = rows + (size_t)(kJob + 1) * row_bytes;
@@ -116,22 +132,27 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     const int q = lane & (kTile - 1), h = lane >> 5;
     const uint32_t tail = (D & 31) ? (1u << (D & 31)) - 1u : 0xffffffffu;
 
-    // The lane's class words: slot q's words h * s0 + wave * 4P + s of the class vector, zero where
-    // that is outside the half (the row words they meet there are other words or no words at all).
-    uint32_t cw[kSteps];
+    // The lane's class words: words h * s0 + wave * 4P + s of the class its slot q stands for in
+    // each pass, zero where that is outside the half (the row words they meet there are other
+    // words or no words at all).
+    uint32_t cw[kPasses][kSteps];
 #pragma unroll
-    for (int s = 0; s < kSteps; ++s) {
-        const int w = h * s0 + wave * kSteps + s;
-        uint32_t m = 0;
-        if (w < (h ? W : s0)) {
-            if (q < C) m = class_hv[(int64_t)q * W + w];
-            else if (q == kOnes) m = w == W - 1 ? tail : 0xffffffffu;
+    for (int p = 0; p < kPasses; ++p) {
+        const int cls = p * kPassClasses + q;    // counted from c0
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const int w = h * s0 + wave * kSteps + s;
+            uint32_t m = 0;
+            if (w < (h ? W : s0)) {
+                if (q < kOnes && cls < Cn) m = class_hv[(int64_t)(c0 + cls) * W + w];
+                else if (q == kOnes && p == 0) m = w == W - 1 ? tail : 0xffffffffu;
+            }
+            cw[p][s] = reverse3(m);
         }
-        cw[s] = reverse3(m);
     }
-    for (int j = wave; j < C; j += kMfmaWaves) {
+    for (int j = wave; j < Cn; j += kMfmaWaves) {
         uint32_t n = 0;
-        for (int w = lane; w < W; w += kWave) n += __popc(class_hv[(int64_t)j * W + w]);
+        for (int w = lane; w < W; w += kWave) n += __popc(class_hv[(int64_t)(c0 + j) * W + w]);
 #pragma unroll
         for (int sft = 1; sft < kWave; sft <<= 1) n += (uint32_t)__shfl_xor((int)n, sft, kWave);
         if (lane == 0) popc_m[j] = n;
@@ -145,7 +166,8 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // slots and key bases ((popcount(m) << 10) | class; slots without a class start so high that
     // no dot product brings them below a real one).
     const int rg = wave % kGroups, rt = wave / kGroups;
-    int slot_of[kRegs], base_of[kRegs];
+    const bool reduces = rt < kTiles;     // wave-uniform: with one tile waves 4 to 7 have nothing to reduce
+    int slot_of[kRegs], base_of[kPasses][kRegs];
     {
         const int bits = (q & 1 ? 0x2 : 0) | (q & 2 ? 0x20 : 0) | (q & 4 ? 0x600 : 0) | (q & 8 ? 0x6000 : 0) |
                          (q & 16 ? 0x60000 : 0);
@@ -160,13 +182,19 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) v = rg == g ? z[g * kRegs + j] : v;
             slot_of[j] = (int)v;
-            base_of[j] = slot_of[j] < C ? (int)((popc_m[slot_of[j]] << 10) | (uint32_t)slot_of[j]) : INT_MAX;
+#pragma unroll
+            for (int p = 0; p < kPasses; ++p) {
+                const int cls = p * kPassClasses + slot_of[j];
+                base_of[p][j] =
+                    slot_of[j] < kOnes && cls < Cn ? (int)((popc_m[cls] << 10) | (uint32_t)(c0 + cls)) : INT_MAX;
+            }
         }
     }
 
-    // The lane's share of a job's fetch.  Wave v brings rows 8v .. 8v + 7 of the job: their whole
-    // 16-byte pieces, piece after piece over the lanes (load i: piece number i * 64 + lane of the
-    // 8 * (W / 4); numbers past the end repeat the last piece), and, where W is no multiple of 4,
+    // The lane's share of a job's fetch.  Wave v brings a job's rows 8v .. 8v + 7 (4v .. 4v + 3
+    // where it has one tile): their whole 16-byte pieces, piece after piece over the lanes (load i:
+    // piece number i * 64 + lane of the rows' W / 4 each; numbers past the end repeat the last
+    // piece), and, where W is no multiple of 4,
     // the one to three words left over, a word per lane.  One register per load: the word's offset
     // from the job's first word in bits 0..15, the 16-byte unit of the images from bit 16.
     const int whole = W / 4;
@@ -184,7 +212,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 
     const char *take_at = rows + q * row_bytes + (h * s0 + wave * kSteps) * 4;
     const int tile_bytes = kTile * row_bytes;
-    uint32_t *mine = reinterpret_cast<uint32_t *>(partials + wave * kPartialBytes);
+    char *mine = partials + wave * kPartialBytes;
 
     const int64_t jobs = (N + kJob - 1) / kJob;
     const int64_t last_word = N * W - 1;
@@ -217,65 +245,85 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 #pragma unroll
             for (int t = 0; t < kTiles; ++t) x[t] = *reinterpret_cast<const u32x4 *>(take_at + t * tile_bytes + k * 16);
         };
-        v16f acc[kTiles];
+        int key = INT_MAX;
+        int dot[kPasses][kRegs];
 #pragma unroll
-        for (int t = 0; t < kTiles; ++t)
+        for (int p = 0; p < kPasses; ++p) {
+            const int area = (p & 1) * kAreaBytes;    // the passes take the two areas in turn
+            v16f acc[kTiles];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-        u32x4 x[2][kTiles];
-        take(x[0], 0);
+            for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-        for (int k = 0; k < P; ++k) {
-            if (k + 1 < P) take(x[(k + 1) & 1], k + 1);
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+            u32x4 x[2][kTiles];
+            take(x[0], 0);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t c = cw[4 * k + e];
-                const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
-                               (int)((c >> 3) & 0x11111111u)};
+            for (int k = 0; k < P; ++k) {
+                if (k + 1 < P) take(x[(k + 1) & 1], k + 1);
 #pragma unroll
-                for (int t = 0; t < kTiles; ++t) {
-                    const uint32_t xw = x[k & 1][t][e];
-                    const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
-                                   (int)((xw >> 1) & 0x44444444u)};
-                    acc[t] = mfma(a, b, acc[t]);
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t c = cw[p][4 * k + e];
+                    // With one pass over two tiles the compiler keeps all the masks of the class words
+                    // in registers over the whole launch; the other forms have no room for that
+                    // (it would spill them in this loop), so there the word is made opaque here.
+                    if constexpr (kPasses > 1 || kTiles == 1) asm volatile("" : "+v"(c));
+                    const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
+                                   (int)((c >> 3) & 0x11111111u)};
+#pragma unroll
+                    for (int t = 0; t < kTiles; ++t) {
+                        const uint32_t xw = x[k & 1][t][e];
+                        const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
+                                       (int)((xw >> 1) & 0x44444444u)};
+                        acc[t] = mfma(a, b, acc[t]);
+                    }
                 }
             }
-        }
 
-        // partial dot products, registers 2i and 2i + 1 in one word: [tile][group of four registers][lane][2 words]
+            // partial dot products, registers 2i and 2i + 1 in one word: [tile][group of four registers][lane][2 words]
+            uint32_t *out = reinterpret_cast<uint32_t *>(mine + area);
 #pragma unroll
-        for (int t = 0; t < kTiles; ++t)
+            for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
-                uint32_t pk[2];
+                for (int g = 0; g < kGroups; ++g) {
+                    uint32_t pk[2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    pk[i] = (uint32_t)acc[t][kRegs * g + 2 * i] | ((uint32_t)acc[t][kRegs * g + 2 * i + 1] << 16);
-                *reinterpret_cast<uint2 *>(mine + ((t * kGroups + g) * kWave + lane) * 2) = make_uint2(pk[0], pk[1]);
+                    for (int i = 0; i < 2; ++i)
+                        pk[i] = (uint32_t)acc[t][kRegs * g + 2 * i] | ((uint32_t)acc[t][kRegs * g + 2 * i + 1] << 16);
+                    *reinterpret_cast<uint2 *>(out + ((t * kGroups + g) * kWave + lane) * 2) = make_uint2(pk[0], pk[1]);
+                }
+            __syncthreads();
+            // (the pass after the next writes this area again: every wave has then passed the next
+            // pass's barrier, or the job's last one, and so has read what it needs here)
+
+            if (reduces) {
+                // the halves of a word add up separately: eight partials stay far below 2^16
+                uint2 sum = make_uint2(0u, 0u);
+#pragma unroll
+                for (int v = 0; v < kMfmaWaves; ++v) {
+                    const uint2 part = *reinterpret_cast<const uint2 *>(
+                        reinterpret_cast<const uint32_t *>(partials + area + v * kPartialBytes) +
+                        ((rt * kGroups + rg) * kWave + lane) * 2);
+                    sum.x += part.x;
+                    sum.y += part.y;
+                }
+                dot[p][0] = (int)(sum.x & 0xffffu);
+                dot[p][1] = (int)(sum.x >> 16);
+                dot[p][2] = (int)(sum.y & 0xffffu);
+                dot[p][3] = (int)(sum.y >> 16);
+#pragma unroll
+                for (int j = 0; j < kRegs; ++j) key = min(key, base_of[p][j] - (dot[p][j] << 11));   // the key takes 2048 * dot off
             }
-        __syncthreads();
-
-        // the halves of a word add up separately: eight partials stay far below 2^16
-        uint2 sum = make_uint2(0u, 0u);
-#pragma unroll
-        for (int v = 0; v < kMfmaWaves; ++v) {
-            const uint2 part = *reinterpret_cast<const uint2 *>(
-                reinterpret_cast<const uint32_t *>(partials + v * kPartialBytes) + ((rt * kGroups + rg) * kWave + lane) * 2);
-            sum.x += part.x;
-            sum.y += part.y;
         }
-        const int dot[kRegs] = {(int)(sum.x & 0xffffu), (int)(sum.x >> 16), (int)(sum.y & 0xffffu), (int)(sum.y >> 16)};
-        int key = INT_MAX;
+        if (reduces) {
+            key = min(key, __shfl_xor(key, 32, kWave));
+            if (h == 0) keyq[(rt * kGroups + rg) * kTile + q] = key;
+            if (kDist) {
+                int part = 0;
 #pragma unroll
-        for (int j = 0; j < kRegs; ++j) key = min(key, base_of[j] - (dot[j] << 11));   // the key takes 2048 * dot off
-        key = min(key, __shfl_xor(key, 32, kWave));
-        if (h == 0) keyq[(rt * kGroups + rg) * kTile + q] = key;
-        if (kDist) {
-            int part = 0;
-#pragma unroll
-            for (int j = 0; j < kRegs; ++j) part += slot_of[j] == kOnes ? dot[j] : 0;
-            part += __shfl_xor(part, 32, kWave);
-            if (h == 0) popx[(rt * kGroups + rg) * kTile + q] = part;
+                for (int j = 0; j < kRegs; ++j) part += slot_of[j] == kOnes ? dot[0][j] : 0;
+                part += __shfl_xor(part, 32, kWave);
+                if (h == 0) popx[(rt * kGroups + rg) * kTile + q] = part;
+            }
         }
         __syncthreads();
 
@@ -285,18 +333,24 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 #pragma unroll
             for (int g = 1; g < kGroups; ++g) k = min(k, keyq[(t * kGroups + g) * kTile + qq]);
             const int64_t n = job * kJob + threadIdx.x;
-            if (n < N) pred[n] = k & 1023;
+            if (n < N) {
+                if (keys_in) k = min(k, pred[n]);
+                pred[n] = keys_out ? k : k & 1023;
+            }
         }
-        if (kDist) {
+        if (kDist && reduces) {
             int popc_x = 0;
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) popc_x += popx[(rt * kGroups + g) * kTile + q];
             const int64_t n = job * kJob + rt * kTile + q;
             if (n < N) {
 #pragma unroll
-                for (int j = 0; j < kRegs; ++j)
-                    if (slot_of[j] < C)
-                        dist[n * C + slot_of[j]] = (uint32_t)(popc_x + (base_of[j] >> 10) - 2 * dot[j]);
+                for (int p = 0; p < kPasses; ++p)
+#pragma unroll
+                    for (int j = 0; j < kRegs; ++j)
+                        if (base_of[p][j] != INT_MAX)
+                            dist[n * C + (base_of[p][j] & 1023)] =
+                                (uint32_t)(popc_x + (base_of[p][j] >> 10) - 2 * dot[p][j]);
             }
         }
     }
@@ -305,26 +359,66 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 constexpr int64_t kMfmaQueries = 20480;        // from here on with 9 to 12 classes (measured against the vector kernels at D = 10000)
 constexpr int64_t kMfmaQueriesMany = 8192;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 14 us   // from here on there is a job for most blocks of the chip
 
-template <int P>
-static int launch_mfma(hdc_ctx_impl *c, const RowGeo &g, const uint32_t *hv, int64_t N, const uint32_t *class_hv,
-                       uint32_t *dist, int32_t *pred, hipStream_t s) {
-    const void *kern = dist ? reinterpret_cast<const void *>(search_mfma_kernel<P, true>)
-                            : reinterpret_cast<const void *>(search_mfma_kernel<P, false>);
+// What one launch is given: its classes and what pred[] holds before and after it.
+struct ClassSpan {
+    int c0, n, keys_in, keys_out;
+};
+
+template <int P, int kTiles, int kPasses>
+static int launch_mfma(hdc_ctx_impl *c, const RowGeo &g, const ClassSpan &cs, const uint32_t *hv, int64_t N,
+                       const uint32_t *class_hv, uint32_t *dist, int32_t *pred, hipStream_t s) {
+    const void *kern = dist ? reinterpret_cast<const void *>(search_mfma_kernel<P, kTiles, kPasses, true>)
+                            : reinterpret_cast<const void *>(search_mfma_kernel<P, kTiles, kPasses, false>);
     if (g.lds_bytes > 64 * 1024)
         HDC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes));
+    constexpr int kJob = kTile * kTiles;
     const int64_t jobs = (N + kJob - 1) / kJob;
     const int64_t blocks = std::min<int64_t>(256, jobs);
     {
         ProfScope prof(c, HDC_K_SEARCH, s);
         if (dist)
-            hipLaunchKernelGGL((search_mfma_kernel<P, true>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave),
-                               g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0, g.row_bytes, dist, pred);
+            hipLaunchKernelGGL((search_mfma_kernel<P, kTiles, kPasses, true>), dim3((unsigned)blocks),
+                               dim3(kMfmaWaves * kWave), g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0,
+                               g.row_bytes, dist, pred, cs.c0, cs.n, cs.keys_in, cs.keys_out);
         else
-            hipLaunchKernelGGL((search_mfma_kernel<P, false>), dim3((unsigned)blocks), dim3(kMfmaWaves * kWave),
-                               g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0, g.row_bytes, dist, pred);
+            hipLaunchKernelGGL((search_mfma_kernel<P, kTiles, kPasses, false>), dim3((unsigned)blocks),
+                               dim3(kMfmaWaves * kWave), g.lds_bytes, s, hv, N, class_hv, c->p.C, c->W, c->p.D, g.s0,
+                               g.row_bytes, dist, pred, cs.c0, cs.n, cs.keys_in, cs.keys_out);
     }
     HDC_HIP(hipGetLastError());
     return HDC_OK;
+}
+
+template <int P>
+static int launch_passes(hdc_ctx_impl *c, const RowGeo &g, const ClassSpan &cs, const uint32_t *hv, int64_t N,
+                         const uint32_t *class_hv, uint32_t *dist, int32_t *pred, hipStream_t s) {
+    switch (g.passes) {
+    case 1: return launch_mfma<P, 2, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 2: return launch_mfma<P, 2, 2>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 3: return launch_mfma<P, 2, 3>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    default: return launch_mfma<P, 2, 4>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    }
+}
+
+static int launch_span(hdc_ctx_impl *c, const RowGeo &g, const ClassSpan &cs, const uint32_t *hv, int64_t N,
+                       const uint32_t *class_hv, uint32_t *dist, int32_t *pred, hipStream_t s) {
+    if (g.tiles == 2) {
+        switch (g.pieces) {
+        case 1: return launch_passes<1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        case 2: return launch_passes<2>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        case 3: return launch_passes<3>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        case 4: return launch_passes<4>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        default: return launch_passes<5>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        }
+    }
+    switch ((g.pieces + 1) / 2) {    // an odd count takes the next even one: its last slices meet zero class words
+    case 3: return launch_mfma<6, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 4: return launch_mfma<8, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 5: return launch_mfma<10, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 6: return launch_mfma<12, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    case 7: return launch_mfma<14, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    default: return launch_mfma<16, 1, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
+    }
 }
 
 // Takes the search if it is of the shape this kernel is for; returns false otherwise.
@@ -332,18 +426,27 @@ bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint3
                      uint32_t *dist, int32_t *pred, hipStream_t s, int *rc) {
     const int C = c->p.C, W = c->W;
     // fewer classes: the row-per-16-lanes kernel is as fast or faster (this one takes the same time for
-    // any number of classes: at D = 10000, 0.25 ms for a million queries, 0.29 ms with distances)
-    if (N < (C >= 13 ? kMfmaQueriesMany : kMfmaQueries) || C < 9 || C > kOnes || W < 4) return false;
-    const RowGeo g = row_geo(W);
-    if (g.lds_bytes > 160 * 1024) return false;   // D above 10240 or so: the job's rows would not fit in LDS
-    switch (g.pieces) {
-    case 1: *rc = launch_mfma<1>(c, g, hv, N, class_hv, dist, pred, s); return true;
-    case 2: *rc = launch_mfma<2>(c, g, hv, N, class_hv, dist, pred, s); return true;
-    case 3: *rc = launch_mfma<3>(c, g, hv, N, class_hv, dist, pred, s); return true;
-    case 4: *rc = launch_mfma<4>(c, g, hv, N, class_hv, dist, pred, s); return true;
-    case 5: *rc = launch_mfma<5>(c, g, hv, N, class_hv, dist, pred, s); return true;
-    default: return false;
+    // any number of classes of a pass: at D = 10000, 0.25 ms for a million queries, 0.29 ms with distances)
+    if (N < (C >= 13 ? kMfmaQueriesMany : kMfmaQueries) || C < 9 || W < 4) return false;
+    static_assert(HDC_MAX_C <= 1024, "a key keeps the class in ten bits");
+    // D up to 10240: two tiles of queries per job and up to four passes a launch; up to 32768: a
+    // tile per job (the class words of such a row fill the registers) and one pass a launch
+    const int pieces = row_geo(W, 1, 1).pieces;
+    if (pieces > 16) return false;
+    const int tiles = pieces <= 5 ? 2 : 1;
+    const int launch_passes_max = tiles == 2 ? kMaxPasses : 1;
+    const int passes = (C + kPassClasses - 1) / kPassClasses;
+    const int launches = (passes + launch_passes_max - 1) / launch_passes_max;
+    if (row_geo(W, tiles, std::min(passes, launch_passes_max)).lds_bytes > 160 * 1024) return false;
+    for (int i = 0, p0 = 0; i < launches; ++i) {
+        const int np = passes / launches + (i < passes % launches ? 1 : 0);   // as equal as they come
+        const ClassSpan cs = {p0 * kPassClasses, std::min(C - p0 * kPassClasses, np * kPassClasses), i > 0,
+                              i + 1 < launches};
+        *rc = launch_span(c, row_geo(W, tiles, np), cs, hv, N, class_hv, dist, pred, s);
+        if (*rc != HDC_OK) return true;
+        p0 += np;
     }
+    return true;
 }
 
 }  // namespace hdc
