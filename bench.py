@@ -409,6 +409,28 @@ def extras(torch, binding, make_workload):
                             "note": "flops are the method's own 2 N C D (26 classes, 10000 dimensions)"}
     ctx26.close()
     del cls26
+    # 124 classes: four passes over the class slots in one launch, the rows read once
+    ctxm = binding.Context(wl5.D, wl5.F, wl5.L, 124, wl5.item, wl5.level, wl5.tie, wl5.lo, wl5.scale, wl5.dtype)
+    clsm = hv[:124].clone()
+    ms = _timed(torch, lambda: ctxm.hdc_search(hv, clsm, pred, None), 5)
+    res["search_1M_C124"] = {"ms": round(ms, 4), "queries_per_s": round(N / ms * 1e3, 0),
+                             "frac_hbm": round((bytes_rows + 4 * N) / ms / 1e6 / HBM_PEAK_GBS, 4),
+                             "mfma_Pflops": round(2.0 * N * 124 * wl5.D / (ms * 1e-3) / 1e15, 3),
+                             "frac_mfma_fp4": round(2.0 * N * 124 * wl5.D / (ms * 1e-3) / 1e15 / 10.1, 4)}
+    ctxm.close()
+    del clsm
+    # D = 32768, 26 classes: a tile of 32 queries per block at a time (the rows are 4 KB each)
+    wlL = make_workload(1, D=32768, C=26, F=3, L=2)
+    ctxL = binding.Context(wlL.D, wlL.F, wlL.L, 26, wlL.item, wlL.level, wlL.tie, wlL.lo, wlL.scale, wlL.dtype)
+    NL = 250_000
+    hvL = hv.view(-1)[:NL * ctxL.W].view(NL, ctxL.W)
+    clsL = hvL[:26].clone()
+    ms = _timed(torch, lambda: ctxL.hdc_search(hvL, clsL, pred[:NL], None), 5)
+    res["search_250k_D32768_C26"] = {"ms": round(ms, 4), "queries_per_s": round(NL / ms * 1e3, 0),
+                                     "frac_hbm": round((NL * ctxL.W * 4 + 4 * NL) / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                     "frac_mfma_fp4": round(2.0 * NL * 26 * 32768 / (ms * 1e-3) / 1e15 / 10.1, 4)}
+    ctxL.close()
+    del clsL, hvL
     ms = _timed(torch, lambda: ctx.hdc_train_classical(hv, y, acc, cn), 5)
     res["train_classical_1M_C2"] = {"ms": round(ms, 4), "samples_per_s": round(N / ms * 1e3, 0),
                                     "GBs": round((bytes_rows + 4 * N) / ms / 1e6, 1),

@@ -201,10 +201,13 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
  *   hv_dev [N][W], class_hv_dev [C][W] (pad bits zero), dist_dev [N][C] uint32 out or
  *   NULL when only predictions are wanted, pred_dev [N] int32 out (required).
  * Any D up to HDC_MAX_D; the fast paths hold a query row in the registers of one wave
- * (D <= 32768), longer rows are read again for every class.  Streams of 32768 or more
- * queries against 9 to 31 classes at D <= 10240 run as a matrix-core contraction
- * (dist = |hv| + |class_hv| - 2 <hv, class_hv>, exact); the results are the same bits
- * whichever kernel runs.  The pad bits of both inputs must be zero as stated: the kernels
+ * (D <= 32768), longer rows are read again for every class.  Streams of 8192 or more
+ * queries against 13 or more classes (20480 or more against 9 to 12) at D <= 32768 run as
+ * a matrix-core contraction (dist = |hv| + |class_hv| - 2 <hv, class_hv>, exact), 31
+ * classes to a pass; beyond 124 classes (31 where D > 10240) the classes are dealt out
+ * over several launches, and between them pred_dev holds intermediate keys, not classes:
+ * read it after the call's work on the stream is complete, as ever.  The results are the
+ * same bits whichever kernel runs.  The pad bits of both inputs must be zero as stated: the kernels
  * differ in what they would make of set pad bits.
  */
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,

@@ -90,7 +90,7 @@ static inline RowGeo row_geo(int W, int tiles, int passes) {
     const int units = (W + 3) / 4;
     g.row_bytes = 16 * (units | 1);
     // the last wave's slice of the second half may reach past the last row's image: one more image of slack
-    g.lds_bytes = (size_t)(kSlots * passes + 2 * tiles * kGroups * kTile) * 4 + (size_t)(tiles * kTile + 1) * g.row_bytes +
+    g.lds_bytes = (size_t)(2 * kSlots * passes + 2 * tiles * kGroups * kTile) * 4 + (size_t)(tiles * kTile + 1) * g.row_bytes +
                   (size_t)(passes > 1 ? 2 : 1) * kMfmaWaves * partial_bytes(tiles);
     return g;
 }
@@ -106,7 +106,7 @@ __device__ __forceinline__ v16f mfma(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-// Dynamic LDS: popcount(m_c) [32 a pass], keys [tiles][4 groups][32 queries], popcount(x) parts of
+// Dynamic LDS: popcount(m_c) [32 a pass], key bases of as many, keys [tiles][4 groups][32 queries], popcount(x) parts of
 // the same shape, the images of the job's rows (and one of slack), then the waves' partial sums
 // (two areas where there are several passes).
 template <int P, int kTiles, int kPasses, bool kDist>
@@ -123,7 +123,8 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     constexpr int kSteps = 4 * P;      // words of a row half per wave = MFMA steps per job and pass
     constexpr int kLoads = kTiles * P; // 16-byte loads per lane per job: a wave's rows of at most 16P pieces over 64 lanes
     extern __shared__ uint32_t popc_m[];
-    int *keyq = reinterpret_cast<int *>(popc_m + kSlots * kPasses);
+    int *base_tab = reinterpret_cast<int *>(popc_m + kSlots * kPasses);   // [pass][group][wave half][register]
+    int *keyq = base_tab + kSlots * kPasses;
     int *popx = keyq + kTiles * kGroups * kTile;
     char *rows = reinterpret_cast<char *>(popx + kTiles * kGroups * kTile);
     char *partials = rows + (size_t)(kJob + 1) * row_bytes;
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // no dot product brings them below a real one).
     const int rg = wave % kGroups, rt = wave / kGroups;
     const bool reduces = rt < kTiles;     // wave-uniform: with one tile waves 4 to 7 have nothing to reduce
-    int slot_of[kRegs], base_of[kPasses][kRegs];
+    int slot_of[kRegs], base_of[kRegs];      // the bases of the first pass; with several passes all of them are in LDS
     {
         const int bits = (q & 1 ? 0x2 : 0) | (q & 2 ? 0x20 : 0) | (q & 4 ? 0x600 : 0) | (q & 8 ? 0x6000 : 0) |
                          (q & 16 ? 0x60000 : 0);
@@ -185,10 +186,13 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 #pragma unroll
             for (int p = 0; p < kPasses; ++p) {
                 const int cls = p * kPassClasses + slot_of[j];
-                base_of[p][j] =
+                const int base =
                     slot_of[j] < kOnes && cls < Cn ? (int)((popc_m[cls] << 10) | (uint32_t)(c0 + cls)) : INT_MAX;
+                if (p == 0) base_of[j] = base;
+                if (kPasses > 1 && rt == 0 && q == 0) base_tab[((p * kGroups + rg) * 2 + h) * kRegs + j] = base;
             }
         }
+        if (kPasses > 1) __syncthreads();
     }
 
     // The lane's share of a job's fetch.  Wave v brings a job's rows 8v .. 8v + 7 (4v .. 4v + 3
@@ -212,6 +216,15 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 
     const char *take_at = rows + q * row_bytes + (h * s0 + wave * kSteps) * 4;
     const int tile_bytes = kTile * row_bytes;
+    auto bases = [&](int(&base)[kRegs], int p) {   // of the lane's registers in pass p
+        if constexpr (kPasses > 1) {
+            const int4 b = *reinterpret_cast<const int4 *>(base_tab + ((p * kGroups + rg) * 2 + h) * kRegs);
+            base[0] = b.x, base[1] = b.y, base[2] = b.z, base[3] = b.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kRegs; ++j) base[j] = base_of[j];
+        }
+    };
     char *mine = partials + wave * kPartialBytes;
 
     const int64_t jobs = (N + kJob - 1) / kJob;
@@ -230,6 +243,38 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
             f_left = hv[at <= last_word ? at : last_word];
         }
     };
+    // Several passes: a row's distances are many, and lanes that each write single words of 32
+    // rows reach a fraction of the memory's rate.  They meet in the second area of the partial
+    // sums (row pitch odd) after the job's last barrier and leave as whole rows after the next
+    // job's first one, under its matrix instructions; that area is next written in that job's
+    // second pass, a barrier later.
+    constexpr bool kStaged = kDist && kPasses > 1;
+    int *stage = reinterpret_cast<int *>(partials + kAreaBytes);
+    const int stage_pitch = Cn | 1;
+    static_assert(!kStaged || kJob * (kMaxPasses * kPassClasses + 1) * 4 <= kAreaBytes, "a job's distances fit an area");
+    auto rows_out = [&](int64_t of_job) {   // wave v: rows v, v + 8, ...; four rows read before the first of them is written
+        constexpr int kCols = (kPasses * kPassClasses + kWave - 1) / kWave;
+        constexpr int kAtOnce = 4;
+        uint32_t *out = dist + (of_job * kJob + wave) * C + c0;
+        const int64_t rows_left = N - of_job * kJob - wave;    // this wave's rows: those with i * 8 below this
+#pragma unroll 1
+        for (int i0 = 0; i0 < kWaveRows; i0 += kAtOnce) {
+            int v[kAtOnce][kCols];
+#pragma unroll
+            for (int i = 0; i < kAtOnce; ++i)
+#pragma unroll
+                for (int cc = 0; cc < kCols; ++cc)
+                    v[i][cc] = stage[(wave + (i0 + i) * kMfmaWaves) * stage_pitch + min(lane + cc * kWave, Cn - 1)];
+#pragma unroll
+            for (int i = 0; i < kAtOnce; ++i)
+#pragma unroll
+                for (int cc = 0; cc < kCols; ++cc)
+                    if ((i0 + i) * kMfmaWaves < rows_left && lane + cc * kWave < Cn)
+                        out[(int64_t)(i0 + i) * kMfmaWaves * C + lane + cc * kWave] = (uint32_t)v[i][cc];
+        }
+    };
+    int64_t staged = -1;    // the job whose distances wait there (block-uniform)
+
     fetch(blockIdx.x);
     for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {   // block-uniform
         // (every wave has taken the previous job's words: it has passed that job's second barrier)
@@ -239,6 +284,9 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         __syncthreads();
         fetch(job + gridDim.x);                 // past the last job it reads the buffer's last words
         __builtin_amdgcn_sched_barrier(0);      // the loads go out before the MFMAs, not after
+        if constexpr (kStaged) {
+            if (staged >= 0) rows_out(staged);
+        }
 
         // the lane's words come out of the images a piece (four steps) ahead of their use
         auto take = [&](u32x4(&x)[kTiles], int k) {
@@ -310,8 +358,10 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
                 dot[p][1] = (int)(sum.x >> 16);
                 dot[p][2] = (int)(sum.y & 0xffffu);
                 dot[p][3] = (int)(sum.y >> 16);
+                int base[kRegs];
+                bases(base, p);
 #pragma unroll
-                for (int j = 0; j < kRegs; ++j) key = min(key, base_of[p][j] - (dot[p][j] << 11));   // the key takes 2048 * dot off
+                for (int j = 0; j < kRegs; ++j) key = min(key, base[j] - (dot[p][j] << 11));   // the key takes 2048 * dot off
             }
         }
         if (reduces) {
@@ -338,20 +388,40 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
                 pred[n] = keys_out ? k : k & 1023;
             }
         }
-        if (kDist && reduces) {
+        if constexpr (kStaged) {
+            if (reduces) {
+                int popc_x = 0;
+#pragma unroll
+                for (int g = 0; g < kGroups; ++g) popc_x += popx[(rt * kGroups + g) * kTile + q];
+#pragma unroll
+                for (int p = 0; p < kPasses; ++p) {
+                    int base[kRegs];
+                    bases(base, p);
+#pragma unroll
+                    for (int j = 0; j < kRegs; ++j)
+                        if (base[j] != INT_MAX)
+                            stage[(rt * kTile + q) * stage_pitch + p * kPassClasses + slot_of[j]] =
+                                popc_x + (base[j] >> 10) - 2 * dot[p][j];
+                }
+            }
+            staged = job;
+        } else if (kDist && reduces) {
             int popc_x = 0;
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) popc_x += popx[(rt * kGroups + g) * kTile + q];
             const int64_t n = job * kJob + rt * kTile + q;
             if (n < N) {
 #pragma unroll
-                for (int p = 0; p < kPasses; ++p)
-#pragma unroll
-                    for (int j = 0; j < kRegs; ++j)
-                        if (base_of[p][j] != INT_MAX)
-                            dist[n * C + (base_of[p][j] & 1023)] =
-                                (uint32_t)(popc_x + (base_of[p][j] >> 10) - 2 * dot[p][j]);
+                for (int j = 0; j < kRegs; ++j)
+                    if (base_of[j] != INT_MAX)
+                        dist[n * C + (base_of[j] & 1023)] = (uint32_t)(popc_x + (base_of[j] >> 10) - 2 * dot[0][j]);
             }
+        }
+    }
+    if constexpr (kStaged) {
+        if (staged >= 0) {
+            __syncthreads();
+            rows_out(staged);
         }
     }
 }
