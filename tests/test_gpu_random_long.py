@@ -75,3 +75,47 @@ def test_random_long_calls_match_oracle(seed):
     assert np.array_equal(pred.cpu().numpy()[rows], o_p), what
     assert torch.equal(pred, pred2), what
     ctx.close()
+
+
+# The search alone over a wider range of class counts and dimensions than the workloads have: one
+# pass or several over the class slots of the matrix-core kernel, several launches, rows of one
+# tile per job, and the vector kernels around it.  Sampled rows against the oracle, both outputs;
+# the predictions of every row against the distances the GPU wrote (lowest class of the minimum).
+@pytest.mark.parametrize("seed", range(12))
+def test_random_search_draws_match_oracle(seed):
+    from paper_2206_04746_amd import binding
+    rng = np.random.default_rng(7000 + seed)
+    D = int(rng.choice([130, 1000, 4097, 10000, 10240, 10241, 13000, 16384, 20001, 27000, 32768, 33000]))
+    C = int(rng.choice([8, 9, 13, 26, 31, 32, 45, 62, 63, 100, 124, 125, 200, 260]))
+    N = int(rng.choice([8192, 9001, 20480, 32768 + 7, 50000]))
+    if D * C * N > 3e10:
+        N = 8192 + seed
+    what = f"D={D} C={C} N={N}"
+    wl = make_workload(1, D=D, C=C, F=3, L=2)
+    W = (D + 31) // 32
+    tail = np.uint32((1 << (D - 32 * (W - 1))) - 1) if D % 32 else np.uint32(0xffffffff)
+    cls = rng.integers(0, 2 ** 32, size=(C, W), dtype=np.uint64).astype(np.uint32)
+    cls[:, -1] &= tail
+    cls[C // 2] = cls[1]                                             # a duplicate: the lower class wins
+    q = rng.integers(0, 2 ** 32, size=(N, W), dtype=np.uint64).astype(np.uint32)
+    near = np.arange(0, N, 2)                                        # every other query: near some class
+    q[near] = cls[rng.integers(0, C, near.size)]
+    q[near, rng.integers(0, W, near.size)] ^= np.uint32(0x0ff00ff0)
+    q[:, -1] &= tail
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    qd = torch.from_numpy(q.view(np.int32)).cuda()
+    cd = torch.from_numpy(cls.view(np.int32)).cuda()
+    dist = torch.full((N, C), -1, dtype=torch.int32, device="cuda")
+    pred = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    pred2 = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(qd, cd, pred, dist)
+    ctx.hdc_search(qd, cd, pred2, None)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, 100), np.arange(N - 100, N), rng.integers(0, N, 600)]))
+    o_d, o_p = oracle.search(q[rows], cls, D)
+    assert np.array_equal(_u32(dist)[rows], o_d), what
+    assert np.array_equal(pred.cpu().numpy()[rows], o_p), what
+    assert torch.equal(pred, pred2), what
+    first_min = (dist == dist.min(dim=1, keepdim=True).values).int().argmax(dim=1)
+    assert torch.equal(pred.long(), first_min), what
+    ctx.close()
