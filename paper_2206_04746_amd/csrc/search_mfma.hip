@@ -136,27 +136,28 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // The lane's class words: words h * s0 + wave * 4P + s of the class its slot q stands for in
     // each pass, zero where that is outside the half (the row words they meet there are other
     // words or no words at all).
+    // The slices of the waves and halves cover every word of a class once, so popcount(m_c) is
+    // the sum of the lanes' counts over their own words: no second reading of the class vectors.
     uint32_t cw[kPasses][kSteps];
+    for (int j = threadIdx.x; j < kSlots * kPasses; j += kMfmaWaves * kWave) popc_m[j] = 0;
+    __syncthreads();
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         const int cls = p * kPassClasses + q;    // counted from c0
+        const bool real = q < kOnes && cls < Cn;
+        uint32_t ones = 0;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
             const int w = h * s0 + wave * kSteps + s;
             uint32_t m = 0;
             if (w < (h ? W : s0)) {
-                if (q < kOnes && cls < Cn) m = class_hv[(int64_t)(c0 + cls) * W + w];
+                if (real) m = class_hv[(int64_t)(c0 + cls) * W + w];
                 else if (q == kOnes && p == 0) m = w == W - 1 ? tail : 0xffffffffu;
             }
+            ones += __popc(m);
             cw[p][s] = reverse3(m);
         }
-    }
-    for (int j = wave; j < Cn; j += kMfmaWaves) {
-        uint32_t n = 0;
-        for (int w = lane; w < W; w += kWave) n += __popc(class_hv[(int64_t)(c0 + j) * W + w]);
-#pragma unroll
-        for (int sft = 1; sft < kWave; sft <<= 1) n += (uint32_t)__shfl_xor((int)n, sft, kWave);
-        if (lane == 0) popc_m[j] = n;
+        if (real) atomicAdd(&popc_m[cls], ones);
     }
     __syncthreads();
 
@@ -427,7 +428,10 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 }
 
 constexpr int64_t kMfmaQueries = 20480;        // from here on with 9 to 12 classes (measured against the vector kernels at D = 10000)
-constexpr int64_t kMfmaQueriesMany = 8192;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 14 us   // from here on there is a job for most blocks of the chip
+#ifndef HDC_X_MANY
+#define HDC_X_MANY 8192
+#endif
+constexpr int64_t kMfmaQueriesMany = HDC_X_MANY;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 14 us   // from here on there is a job for most blocks of the chip
 
 // What one launch is given: its classes and what pred[] holds before and after it.
 struct ClassSpan {
