@@ -497,6 +497,32 @@ def extras(torch, binding, make_workload):
         "note": "random level table (no structure): quantize_kernel + encode_kernel on the vector unit, "
                 "3 lane-ops per (feature, word) against 39.3 T lane-ops/s"}
     ctx.close()
+    # level vectors on a circle (what flips at level l flips back at level l + L/2: half of the
+    # dimensions flip twice): the contraction follows such dimensions through two tiles of opposite sign
+    half = wl2.L // 2
+    first = rng.integers(1, half + 1, wl2.D)
+    vary = rng.random(wl2.D) < 0.5
+    change = np.zeros((wl2.L, wl2.D), dtype=np.uint8)
+    dims = np.nonzero(vary)[0]
+    change[first[dims], dims] = 1
+    back = dims[first[dims] + half < wl2.L]
+    change[first[back] + half, back] = 1
+    bits = (rng.integers(0, 2, wl2.D, dtype=np.uint8)[None, :] ^ (np.cumsum(change, axis=0) & 1)).astype(np.uint8)
+    padded = np.zeros((wl2.L, level_rand.shape[1] * 32), dtype=np.uint8)
+    padded[:, :wl2.D] = bits
+    level_circle = np.packbits(padded.reshape(wl2.L, -1, 32), axis=2, bitorder="little").view(np.uint32).reshape(wl2.L, -1)
+    ctx = binding.Context(wl2.D, wl2.F, wl2.L, wl2.C, wl2.item, level_circle, wl2.tie, wl2.lo, wl2.scale, wl2.dtype)
+    ctx.hdc_profile_enable(True)
+    ms = _timed(torch, lambda: ctx.hdc_encode(x2d, hv2), 3)
+    k_ms, k_n = ctx.hdc_profile_read("encode_contract")
+    ctx.hdc_profile_enable(False)
+    res["encode_circular_levels_64k"] = {
+        "ms": round(ms, 4), "samples_per_s": round(65536 / ms * 1e3, 0),
+        "contraction_kernel_us": round(k_ms * 1e3 / max(1, k_n), 1) if k_n else None,
+        "dimensions_that_flip_twice": int(back.size),
+        "note": "config-2 shape with circular level vectors: encode_contract_kernel, two tiles of opposite "
+                "sign per 32 such dimensions; the vector kernel takes 0.98 ms on this table"}
+    ctx.close()
     del x2d, hv2
     # --- config 3 shape (digit images, u8, L = 256, about 80 % of the pixels in bin 0): hdc_encode
     # (all features; for this model the contraction on the matrix cores, 14 MFMA steps per tile)

@@ -9,6 +9,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <map>
 #include <vector>
 
 namespace hdc {
@@ -38,6 +39,41 @@ inline bool flip_thresholds(const ModelView &m, std::vector<std::vector<int>> *b
     return true;
 }
 
+// Dimensions that flip more than once along the levels, kept together where they flip at the
+// same levels: with t_1 < t_2 < ... the levels at which the bit changes, the level bit is
+// level0 ^ [q >= t_1] ^ [q >= t_2] ^ ..., and as [q >= t_2] implies [q >= t_1] the vote of a
+// feature is B ^ ([q >= t_1] - [q >= t_2] + ...): the sums of the single-flip form, one per t_i,
+// with alternating sign.
+constexpr int kCtMaxChain = 8;   // most flips of a dimension that the contraction follows
+struct FlipChain {
+    std::vector<int> taus;   // ascending, two at least
+    std::vector<int> dims;   // ascending
+};
+
+// by_tau as flip_thresholds leaves it for the dimensions that flip once; the others in chains,
+// ordered by their levels.  False if some dimension flips more than kCtMaxChain times.
+inline bool flip_chains(const ModelView &m, std::vector<std::vector<int>> *by_tau, std::vector<FlipChain> *chains) {
+    by_tau->assign((size_t)m.L, std::vector<int>());
+    chains->clear();
+    std::map<std::vector<int>, std::vector<int>> sets;
+    std::vector<int> taus;
+    for (int d = 0; d < m.D; ++d) {
+        const int w = d >> 5, b = d & 31;
+        taus.clear();
+        uint32_t before = (m.level[w] >> b) & 1u;
+        for (int l = 1; l < m.L; ++l) {
+            const uint32_t bit = (m.level[(size_t)l * m.W + w] >> b) & 1u;
+            if (bit != before) taus.push_back(l);
+            before = bit;
+        }
+        if ((int)taus.size() > kCtMaxChain) return false;
+        if (taus.size() == 1) (*by_tau)[(size_t)taus[0]].push_back(d);
+        else if (taus.size() > 1) sets[taus].push_back(d);
+    }
+    for (auto &kv : sets) chains->push_back(FlipChain{kv.first, kv.second});
+    return true;
+}
+
 // Where feature f sits in its word of 32 features, on both sides of the contraction: the kernels
 // turn 32 bin numbers (bytes, four to a word) into bit planes with three rounds of masked swaps
 // among eight words, which leaves feature 4 m + i of a lane's 32 at bit 8 i + m.
@@ -51,58 +87,82 @@ inline uint32_t reverse3_host(uint32_t x) {
 
 constexpr int kCtCols = 32;       // dimensions per tile
 constexpr float kCtNever = -1.0e30f;
+// Flags beside the threshold in tau_of, set only in the tables of a model with chains: a chain's
+// 32 dimensions take one tile per threshold, one after the other, whose sums the kernel carries
+// from tile to tile with a change of sign each time; the bit comes out of the last one, inverted
+// where the chain has an even number of tiles.  A tile of dimensions that flip once is first and last.
+constexpr int32_t kCtTauMask = 0xffff, kCtFirst = 1 << 16, kCtLast = 1 << 17, kCtInvert = 1 << 18;
 
 // One table set: the row's words in 1 << v ranges, the tiles of a range together.
 struct CtTables {
-    std::vector<int32_t> tau_of;       // [tiles] the level at which the tile's dimensions flip
+    std::vector<int32_t> tau_of;       // [tiles] the level at which the tile's dimensions flip (and the flags above)
     std::vector<int32_t> range_tile;   // [(1 << v) + 1] first tile of every range, then the end
     std::vector<uint32_t> src_of;      // [32][W]: (tile in its range) * 32 + column holding that bit, ~0 for a constant bit
     std::vector<float> kc;             // [tiles][32]: the bit is set iff 2 <U,B> - |U| <= this
     std::vector<uint32_t> bt;          // [tile][step][lane]: the column's bits of item ^ level 0 (every nibble reversed)
     int range_max = 0;                 // most tiles of one range
+    bool chained = false;              // tau_of carries flags
 };
 
-inline void build_contract_tables(const ModelView &m, const std::vector<std::vector<int>> &by_tau, int steps, int v,
-                                  CtTables *t_out) {
+inline void build_contract_tables(const ModelView &m, const std::vector<std::vector<int>> &by_tau,
+                                  const std::vector<FlipChain> &chains, int steps, int v, CtTables *t_out) {
     CtTables &T = *t_out;
     const int W = m.W, F = m.F, L = m.L, S = 1 << v;
     const int thr = (m.votes + 1) / 2;
     const bool tie_votes = m.votes != F;
     T = CtTables();
+    T.chained = !chains.empty();
     T.src_of.assign((size_t)32 * W, 0xffffffffu);
     std::vector<uint32_t> vec((size_t)2 * steps);
     for (int r = 0; r < S; ++r) {
         const int w_lo = (int)((int64_t)r * W >> v), w_hi = (int)((int64_t)(r + 1) * W >> v);
         const size_t t_first = T.tau_of.size();
         T.range_tile.push_back((int32_t)t_first);
+        // one tile: columns dims[at ...] (32 at most) against threshold tau; the row's bits point at tile `owner`
+        auto add_tile = [&](const std::vector<int> &dims, size_t at, int32_t tau_entry, size_t owner) {
+            const size_t t = T.tau_of.size();
+            T.tau_of.push_back(tau_entry);
+            T.kc.resize((t + 1) * 32, kCtNever);
+            T.bt.resize((t + 1) * steps * 64, 0u);
+            for (int j = 0; j < 32; ++j) {
+                std::fill(vec.begin(), vec.end(), 0u);
+                if (j < kCtCols && at + j < dims.size()) {
+                    const int d = dims[at + j], w = d >> 5, b = d & 31;
+                    const uint32_t l0 = (m.level[w] >> b) & 1u;
+                    int ones = 0;
+                    for (int f = 0; f < F; ++f) {
+                        const uint32_t bit = ((m.item[(size_t)f * W + w] >> b) & 1u) ^ l0;
+                        ones += (int)bit;
+                        vec[(size_t)f >> 5] |= bit << feature_bit(f);
+                    }
+                    const int tie_vote = tie_votes ? (int)((m.tie[w] >> b) & 1u) : 0;
+                    T.src_of[(size_t)b * W + w] = (uint32_t)((owner - t_first) * 32 + j);
+                    T.kc[t * 32 + j] = (float)(ones + tie_vote - thr);
+                }
+                for (int k = 0; k < steps; ++k)
+                    for (int h = 0; h < 2; ++h)
+                        T.bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
+            }
+        };
+        std::vector<int> dims;
         for (int tau = 1; tau < L; ++tau) {
-            std::vector<int> dims;
+            dims.clear();
             for (int d : by_tau[(size_t)tau])
                 if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
+            for (size_t at = 0; at < dims.size(); at += kCtCols)
+                add_tile(dims, at, T.chained ? tau | kCtFirst | kCtLast : tau, T.tau_of.size());
+        }
+        for (const FlipChain &ch : chains) {
+            dims.clear();
+            for (int d : ch.dims)
+                if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
+            const size_t n = ch.taus.size();
             for (size_t at = 0; at < dims.size(); at += kCtCols) {
-                const size_t t = T.tau_of.size();
-                T.tau_of.push_back(tau);
-                T.kc.resize((t + 1) * 32, kCtNever);
-                T.bt.resize((t + 1) * steps * 64, 0u);
-                for (int j = 0; j < 32; ++j) {
-                    std::fill(vec.begin(), vec.end(), 0u);
-                    if (j < kCtCols && at + j < dims.size()) {
-                        const int d = dims[at + j], w = d >> 5, b = d & 31;
-                        const uint32_t l0 = (m.level[w] >> b) & 1u;
-                        int ones = 0;
-                        for (int f = 0; f < F; ++f) {
-                            const uint32_t bit = ((m.item[(size_t)f * W + w] >> b) & 1u) ^ l0;
-                            ones += (int)bit;
-                            vec[(size_t)f >> 5] |= bit << feature_bit(f);
-                        }
-                        const int tie_vote = tie_votes ? (int)((m.tie[w] >> b) & 1u) : 0;
-                        T.src_of[(size_t)b * W + w] = (uint32_t)((t - t_first) * 32 + j);
-                        T.kc[t * 32 + j] = (float)(ones + tie_vote - thr);
-                    }
-                    for (int k = 0; k < steps; ++k)
-                        for (int h = 0; h < 2; ++h)
-                            T.bt[(t * steps + k) * 64 + h * 32 + j] = reverse3_host(vec[(size_t)2 * k + h]);
-                }
+                const size_t owner = T.tau_of.size() + n - 1;   // the chain's last tile holds the bits
+                for (size_t i = 0; i < n; ++i)
+                    add_tile(dims, at,
+                             ch.taus[i] | (i == 0 ? kCtFirst : 0) | (i + 1 == n ? kCtLast | (n % 2 == 0 ? kCtInvert : 0) : 0),
+                             owner);
             }
         }
         T.range_max = std::max(T.range_max, (int)(T.tau_of.size() - t_first));

@@ -1,9 +1,10 @@
 // ID-Level encoding (arXiv 2206.04746, Sec. III Eq. 1) as a contraction over the features, on the
 // matrix cores.  Same bits as encode_kernel; taken for level tables in which every dimension that
 // varies along the levels flips exactly once (the construction of Sec. III: neighbouring level
-// vectors differ in a few more dimensions each), with at most 256 levels and 896 features.
+// vectors differ in a few more dimensions each), with at most 256 levels and 896 features, and
+// for tables with dimensions that flip several times where these share their levels (below).
 //
-// For such a dimension d let t_d be the first level whose bit differs from level 0's, and
+// For a dimension d that flips once let t_d be the first level whose bit differs from level 0's, and
 // B[f][d] = item[f][d] ^ level[0][d].  The vote of feature f is B[f][d] ^ [q_f >= t_d], so the
 // number of votes is
 //     count[d] = sum_f B[f][d] + |U| - 2 * <U, B[.][d]>,     U_f = [q_f >= t_d],
@@ -36,6 +37,14 @@
 // dimensions (a table set per way of splitting), it places only the range's words, and it still
 // quantises all features of its samples.  Rows of more than 512 words are always split (a thread
 // places one word of its block's range), which takes the kernel to D = 65536.
+// Dimensions that flip more than once (up to 8 times) are followed too, where enough of them flip
+// at the same levels to fill tiles: with t_1 < t_2 < ... the levels at which such a dimension
+// changes, its level bit is level0 ^ [q >= t_1] ^ [q >= t_2] ^ ..., the vote of a feature
+// B ^ ([q >= t_1] - [q >= t_2] + ...), and the count the single-flip sums of its thresholds with
+// alternating sign.  Its 32-dimension group takes one tile per threshold, one after the other in
+// the same wave; the accumulators carry the running value from tile to tile, negated each time
+// (-R + <U_i, B> - |U_i| / 2), and the bits come out of the last tile, inverted where the tiles
+// are even in number.  (kChain; a model without such dimensions runs the kernel without it.)
 // (Tried first: an LDS atomic OR per bit into images of the rows, six times the time of the MFMAs;
 // then the wave's ballots as words over the dimensions and a gather per (bit, sample), LDS bank
 // conflicts making it four times the time of the MFMAs.)
@@ -56,6 +65,12 @@ constexpr int kCtWaves = 8;        // waves per block at least (the kernel runs 
 constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
 constexpr int kCtMaxSteps = 14;   // MFMAs per tile: 64 features each
 constexpr int kCtSamples = 32;    // samples per block and job
+// A model with chains is taken while its tiles, a chain's counted one and a half times (each
+// brings a new threshold), are at most (24 + F / 34) / 10 times the tiles its varying dimensions
+// would fill: measured at D = 10000 on 65536 samples against the vector kernel, whose time grows
+// with F -- 617 features, 30 % of the dimensions in chains of 2 to 8: 1.09 against 1.20 ms at 3.8
+// times; 100 features, chains of 2 to 4: 0.31 against 0.28 ms at 3.1 times.
+constexpr int chain_work_tenths(int F) { return 24 + F / 34; }
 
 template <typename T>
 static int upload(T **dst, const std::vector<T> &src) {
@@ -83,19 +98,31 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     const int steps = ((F + 63) / 64 + 1) / 2 * 2;   // the kernel is built for even counts; a step past F meets zeros
     const ModelView model = {p.D, W, F, L, c->votes, item, level, tie};
     std::vector<std::vector<int>> by_tau;
-    if (!flip_thresholds(model, &by_tau)) return HDC_OK;   // a dimension that flips twice rules the model out
+    std::vector<FlipChain> chains;
+    if (!flip_chains(model, &by_tau, &chains)) return HDC_OK;   // a dimension that flips more often than the kernel follows
+    if (!chains.empty()) {
+        // A chain's tiles are as many as its thresholds per 32 dimensions, full or not: where the
+        // dimensions that flip more than once do not share their levels (a random table), the tiles
+        // are many and nearly empty, and the vector kernel is the faster one.
+        int64_t varying = 0, tiles2 = 0;   // tiles in halves
+        for (const std::vector<int> &dims : by_tau) varying += (int64_t)dims.size(), tiles2 += 2 * (((int64_t)dims.size() + 31) / 32);
+        for (const FlipChain &ch : chains)
+            varying += (int64_t)ch.dims.size(), tiles2 += 3 * (int64_t)ch.taus.size() * (((int64_t)ch.dims.size() + 31) / 32);
+        if (tiles2 * 10 > 2 * chain_work_tenths(F) * ((varying + 31) / 32)) return HDC_OK;
+    }
     for (int v = 0; v < 3; ++v) {   // the row's words in 1 << v ranges, a block per (32 samples, range)
         const int S = 1 << v;
         if (W < S) break;   // every range of words has a word
         if ((W + S - 1) / S > kCtWaves * kWave) continue;   // and a thread for each of its words
         CtTables tabs;
-        build_contract_tables(model, by_tau, steps, v, &tabs);
+        build_contract_tables(model, by_tau, chains, steps, v, &tabs);
         const std::vector<int32_t> &tau_of = tabs.tau_of, &range_tile = tabs.range_tile;
         const std::vector<uint32_t> &src_of = tabs.src_of, &bt = tabs.bt;
         const std::vector<float> &kc = tabs.kc;
         const int range_max = tabs.range_max;
         if (tau_of.empty()) return HDC_OK;
-        if (range_max > kCtWaves * kWave) continue;   // a wave keeps its tiles' thresholds a lane each
+        // a wave keeps its tiles' thresholds a lane each (with chains its share of the tiles ends a chain's length later at most)
+        if (range_max > kCtWaves * (kWave - (chains.empty() ? 0 : kCtMaxChain))) continue;
         c->ct_tiles[v] = (int)tau_of.size();
         c->ct_range_max[v] = range_max;
         for (int r = 0; r <= 4; ++r) c->ct_range[v][r] = range_tile[(size_t)std::min(r, S)];
@@ -109,6 +136,7 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
     }
     if (c->ct_min_split < 0) return HDC_OK;
     c->ct_steps = steps;
+    c->ct_chained = !chains.empty();
     c->ct_ready = true;
     return HDC_OK;
 }
@@ -129,7 +157,7 @@ typedef uint32_t ct_u32x4 __attribute__((ext_vector_type(4)));
 // Dynamic LDS: the job's bin numbers, a byte each, [sample][KS * 64 + 16] (the 16 spread the rows
 // over the banks), then per (tile, column) the bits of the job's 32 samples [T * 32] (two 16-bit
 // halves, one per lane half).
-template <int KS, int NB, bool kU8, int NW>
+template <int KS, int NB, bool kU8, int NW, bool kChain>
 __global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
     const void *__restrict__ feats, int64_t N, int F, int L, const float *__restrict__ lo,
     const float *__restrict__ scale, int W, int split, const CtRanges range_tile,
@@ -170,8 +198,12 @@ __global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
         const int t_end = range == 0 ? range_tile.t[1] : range == 1 ? range_tile.t[2] : range == 2 ? range_tile.t[3] : range_tile.t[4];
         const int w_first = (int)((int64_t)range * W >> split), w_end = (int)((int64_t)(range + 1) * W >> split);
         // the wave's tiles (at most 64: the host sees to that) and their thresholds, a tile per lane
-        const int t_lo = t_first + (int)((int64_t)wave * (t_end - t_first) / NW);
-        const int t_hi = t_first + (int)((int64_t)(wave + 1) * (t_end - t_first) / NW);
+        int t_lo = t_first + (int)((int64_t)wave * (t_end - t_first) / NW);
+        int t_hi = t_first + (int)((int64_t)(wave + 1) * (t_end - t_first) / NW);
+        if constexpr (kChain) {   // a chain's tiles stay in one wave: both ends move on to the next tile that starts one
+            while (t_lo < t_end && !(tau[t_lo] & kCtFirst)) ++t_lo;
+            while (t_hi < t_end && !(tau[t_hi] & kCtFirst)) ++t_hi;
+        }
         // The job's bin numbers.  A thread takes four neighbouring features of a sample with one 16-byte
         // load, kPerRound samples to a round, and leaves the four bin numbers as one word in LDS.  No
         // branches around the loads (all of a thread's rounds are in flight together): the group that
@@ -279,8 +311,14 @@ __global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
             for (int k = 0; k < KS; ++k) btw[k] = bt[((size_t)t_lo * KS + k) * 64 + lane];
             k_mine = kc[t_lo * 32 + j];
         }
+        v16f acc;
+        if constexpr (kChain) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        }
         for (int t = t_lo; t < t_hi; ++t) {
-            const int tt = __builtin_amdgcn_readlane(tau_mine, t - t_lo);
+            const int entry = __builtin_amdgcn_readlane(tau_mine, t - t_lo);
+            const int tt = kChain ? entry & kCtTauMask : entry;
             if (tt != cur_tau) {   // wave-uniform: the samples' [q >= tt] over the features, their masks, their counts
                 cur_tau = tt;
                 uint32_t cnt = 0;
@@ -315,11 +353,14 @@ __global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
             }
             // The bit of (sample, dimension) is [2 <U,B> - |U| <= K], i.e. the sign of <U,B> - K / 2 - |U| / 2 -
             // 0.25 (multiples of a half but for the quarter): the accumulators start at what follows <U,B>.
-            v16f acc;
-            {
+            // (a chain's further tiles: what follows <U,B> there, less the running value)
+            if (!kChain || (entry & kCtFirst)) {
                 const float start = -0.5f * k_mine - 0.25f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = start + u_of[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = u_of[r] - acc[r];
             }
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
@@ -333,14 +374,17 @@ __global__ __launch_bounds__(NW *kWave) void encode_contract_kernel(
 #pragma unroll
                 for (int k = 0; k < KS; ++k) btw[k] = bt[((size_t)tn * KS + k) * 64 + lane];
             }
-            // register 0's bit ends up highest
-            uint32_t bits = 0;
+            if (!kChain || (entry & kCtLast)) {   // wave-uniform
+                // register 0's bit ends up highest
+                uint32_t bits = 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float d = acc[r];   // (a copy: __builtin_bit_cast applied to the vector element itself reads element 0)
-                bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
+                for (int r = 0; r < 16; ++r) {
+                    const float d = acc[r];   // (a copy: __builtin_bit_cast applied to the vector element itself reads element 0)
+                    bits = __builtin_amdgcn_alignbit(bits, __builtin_bit_cast(uint32_t, d), 31);
+                }
+                if (kChain && (entry & kCtInvert)) bits = ~bits;
+                over16[(size_t)((t - t_first) * 32 + j) * 2 + h] = (uint16_t)bits;
             }
-            over16[(size_t)((t - t_first) * 32 + j) * 2 + h] = (uint16_t)bits;
             k_mine = kc[(t + 1 < t_hi ? t + 1 : t) * 32 + j];
         }
         // (this thread's entries of the bit table are asked for before the barrier, not after it)
@@ -396,7 +440,7 @@ constexpr int kCtSplitWork = 1024;         // MFMAs per 32 samples from which a 
 constexpr int64_t kCtMinSamples = 1024;        // models whose words are not split over blocks
 constexpr int64_t kCtMinSamplesSplit = 256;    // models whose words are
 
-template <int KS, int NB, bool kU8>
+template <int KS, int NB, bool kU8, bool kChain>
 static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
     // With few samples, several blocks per 32 of them, each with a range of the row's words -- where
     // the tiles are most of a block's work (every block quantises its 32 samples in full, and ranges
@@ -411,7 +455,7 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
     // tables are those of eight.
     constexpr int NW = KS >= 6 ? 12 : kCtWaves;
     constexpr bool kPlanesInLds = KS > 10 || NW > 8;
-    auto kern = encode_contract_kernel<KS, NB, kU8, NW>;
+    auto kern = encode_contract_kernel<KS, NB, kU8, NW, kChain>;
     const size_t lds = (size_t)kCtSamples * (KS * 64 + 16) + (kPlanesInLds ? (size_t)KS * 2 * kWave * 16 : 0) +
                        (size_t)c->ct_range_max[v] * 32 * 4;
     if (lds > 64 * 1024)
@@ -428,17 +472,25 @@ static int launch_contract(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *
 }
 
 // The kernel is built for an even number of steps and for 6 or 8 bit planes (L <= 64, L <= 256).
-template <int NB, bool kU8>
+template <int NB, bool kU8, bool kChain>
 static int launch_contract_steps(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
     switch (c->ct_steps) {
-    case 2: return launch_contract<2, NB, kU8>(c, x, n, out, s);
-    case 4: return launch_contract<4, NB, kU8>(c, x, n, out, s);
-    case 6: return launch_contract<6, NB, kU8>(c, x, n, out, s);
-    case 8: return launch_contract<8, NB, kU8>(c, x, n, out, s);
-    case 10: return launch_contract<10, NB, kU8>(c, x, n, out, s);
-    case 12: return launch_contract<12, NB, kU8>(c, x, n, out, s);
-    default: return launch_contract<14, NB, kU8>(c, x, n, out, s);
+    case 2: return launch_contract<2, NB, kU8, kChain>(c, x, n, out, s);
+    case 4: return launch_contract<4, NB, kU8, kChain>(c, x, n, out, s);
+    case 6: return launch_contract<6, NB, kU8, kChain>(c, x, n, out, s);
+    case 8: return launch_contract<8, NB, kU8, kChain>(c, x, n, out, s);
+    case 10: return launch_contract<10, NB, kU8, kChain>(c, x, n, out, s);
+    case 12: return launch_contract<12, NB, kU8, kChain>(c, x, n, out, s);
+    default: return launch_contract<14, NB, kU8, kChain>(c, x, n, out, s);
     }
+}
+
+template <bool kChain>
+static int launch_contract_planes(hdc_ctx_impl *c, const void *x, int64_t n, uint32_t *out, hipStream_t s) {
+    const bool u8 = c->p.feat_dtype == HDC_U8;
+    if (c->p.L <= 64)
+        return u8 ? launch_contract_steps<6, true, kChain>(c, x, n, out, s) : launch_contract_steps<6, false, kChain>(c, x, n, out, s);
+    return u8 ? launch_contract_steps<8, true, kChain>(c, x, n, out, s) : launch_contract_steps<8, false, kChain>(c, x, n, out, s);
 }
 
 // Encodes with the contraction if the model and the call are of its shape; false otherwise (then
@@ -448,9 +500,7 @@ bool try_encode_contract(hdc_ctx_impl *c, const void *feats, int64_t N, uint32_t
     const bool splits = c->ct_max_split > 0 && c->ct_tiles[c->ct_min_split] * c->ct_steps >= kCtSplitWork;
     if (N < (splits ? kCtMinSamplesSplit : kCtMinSamples)) return false;
     ProfScope prof(c, HDC_K_ENCODE_CONTRACT, s);
-    const bool u8 = c->p.feat_dtype == HDC_U8;
-    if (c->p.L <= 64) *rc = u8 ? launch_contract_steps<6, true>(c, feats, N, hv, s) : launch_contract_steps<6, false>(c, feats, N, hv, s);
-    else *rc = u8 ? launch_contract_steps<8, true>(c, feats, N, hv, s) : launch_contract_steps<8, false>(c, feats, N, hv, s);
+    *rc = c->ct_chained ? launch_contract_planes<true>(c, feats, N, hv, s) : launch_contract_planes<false>(c, feats, N, hv, s);
     return true;
 }
 

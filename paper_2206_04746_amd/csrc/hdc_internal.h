@@ -103,6 +103,7 @@ struct hdc_ctx_impl {
     // A table set per way of splitting a row's words over blocks (1, 2 or 4 blocks per 32 samples:
     // few samples would leave most of the chip idle otherwise); set v splits 1 << v ways.
     bool ct_ready;
+    bool ct_chained = false;   // some dimensions flip more than once: the tables carry chains, the kernel follows them
     int ct_steps;               // MFMA steps (64 features each) per tile
     int ct_min_split, ct_max_split;   // the first and last table set built (rows over 512 words are always split, rows under 4 never 4 ways)
     int ct_tiles[3];            // tiles of 32 dimensions, all word ranges together

@@ -61,6 +61,30 @@ static Model make_model(int D, int F, int L, int flips_per_level, bool twice) {
     return m;
 }
 
+// On top of make_model: `sets` sets of 2 to `most` levels each, and some 40 dimensions per set
+// (more than a tile's 32) that flip at exactly those levels, whatever the flips above did there.
+static Model make_chain_model(int D, int F, int L, int flips_per_level, int sets, int most) {
+    Model m = make_model(D, F, L, flips_per_level, false);
+    int d = 0;
+    for (int s = 0; s < sets; ++s) {
+        std::vector<int> at((size_t)L, 0);
+        const int n = 2 + (int)(rnd() % (uint32_t)(most - 1));
+        for (int i = 0; i < n;) {
+            const int l = 1 + (int)(rnd() % (uint32_t)(L - 1));
+            if (!at[(size_t)l]) at[(size_t)l] = 1, ++i;
+        }
+        for (int i = 0; i < 40 && d < D; ++i, d += 1 + (int)(rnd() % 3u)) {
+            uint32_t bit = (m.level[(size_t)(d >> 5)] >> (d & 31)) & 1u;
+            for (int l = 1; l < L; ++l) {
+                bit ^= (uint32_t)at[(size_t)l];
+                uint32_t &word = m.level[(size_t)l * m.W + (d >> 5)];
+                word = (word & ~(1u << (d & 31))) | (bit << (d & 31));
+            }
+        }
+    }
+    return m;
+}
+
 static int bit_of(const std::vector<uint32_t> &t, size_t row, int W, int d) { return (int)((t[row * W + (d >> 5)] >> (d & 31)) & 1u); }
 
 // Eq. (1) bit by bit
@@ -75,11 +99,14 @@ static void encode_definition(const Model &m, const std::vector<int> &q, std::ve
 }
 
 // the row every sample gets at the level-invariant dimensions (hdc_create takes it from one encoded sample)
-static void constant_row(const Model &m, const std::vector<std::vector<int>> &by_tau, std::vector<uint32_t> *row) {
+static void constant_row(const Model &m, const std::vector<std::vector<int>> &by_tau,
+                         const std::vector<hdc::FlipChain> &chains, std::vector<uint32_t> *row) {
     std::vector<int> q((size_t)m.F, 0);
     encode_definition(m, q, row);
     for (size_t t = 1; t < by_tau.size(); ++t)
         for (int d : by_tau[t]) (*row)[(size_t)d >> 5] &= ~(1u << (d & 31));
+    for (const hdc::FlipChain &ch : chains)
+        for (int d : ch.dims) (*row)[(size_t)d >> 5] &= ~(1u << (d & 31));
 }
 
 #define FAIL(...)            \
@@ -89,12 +116,15 @@ static void constant_row(const Model &m, const std::vector<std::vector<int>> &by
         return false;        \
     } while (0)
 
-// encode_contract.hip's use of its tables: bit = [2 <U, B> - |U| <= kc], placed through src_of
-static bool check_contract(const Model &m, const std::vector<std::vector<int>> &by_tau, const std::vector<uint32_t> &crow,
-                           int v, int samples) {
+// encode_contract.hip's use of its tables: bit = [2 <U, B> - |U| <= kc], placed through src_of;
+// with chains, the running value R = <U, B> - |U| / 2 - kc / 2 - 1 / 4 of a chain's first tile,
+// then <U, B> - |U| / 2 - R at every further one, the bit its sign at the last (inverted where flagged)
+static bool check_contract(const Model &m, const std::vector<std::vector<int>> &by_tau,
+                           const std::vector<hdc::FlipChain> &chains, const std::vector<uint32_t> &crow, int v, int samples) {
     const int steps = ((m.F + 63) / 64 + 1) / 2 * 2;
     hdc::CtTables T;
-    hdc::build_contract_tables(m.view(), by_tau, steps, v, &T);
+    hdc::build_contract_tables(m.view(), by_tau, chains, steps, v, &T);
+    if (T.chained != !chains.empty()) FAIL("chained flag");
     const int S = 1 << v, tiles = (int)T.tau_of.size();
     if ((int)T.range_tile.size() != S + 1 || T.range_tile[0] != 0 || T.range_tile[(size_t)S] != tiles) FAIL("range table");
     if (T.kc.size() != (size_t)tiles * 32 || T.bt.size() != (size_t)tiles * steps * 64) FAIL("table sizes");
@@ -105,8 +135,17 @@ static bool check_contract(const Model &m, const std::vector<std::vector<int>> &
         encode_definition(m, q, &want);
         // every tile's 32 columns
         std::vector<uint8_t> colbit((size_t)tiles * 32, 0);
+        std::vector<float> run(32, 0.0f);
+        bool open = false;   // inside a chain
         for (int t = 0; t < tiles; ++t) {
-            const int tau = T.tau_of[(size_t)t];
+            const int entry = T.tau_of[(size_t)t];
+            const int tau = T.chained ? entry & hdc::kCtTauMask : entry;
+            const bool first = !T.chained || (entry & hdc::kCtFirst), last = !T.chained || (entry & hdc::kCtLast);
+            const bool invert = T.chained && (entry & hdc::kCtInvert);
+            if (first == open) FAIL("tile %d: chain flags out of order", t);
+            for (int r = 0; r <= S; ++r)
+                if (T.range_tile[(size_t)r] == t && open) FAIL("tile %d: a chain runs across two ranges", t);
+            open = !last;
             if (tau < 1 || tau >= m.L) FAIL("threshold %d of tile %d", tau, t);
             int nu = 0;
             for (int f = 0; f < m.F; ++f) nu += q[(size_t)f] >= tau;
@@ -118,9 +157,12 @@ static bool check_contract(const Model &m, const std::vector<std::vector<int>> &
                     const uint32_t word = hdc::reverse3_host(T.bt[((size_t)t * steps + k) * 64 + h * 32 + j]);   // (its own inverse)
                     dot += (int)((word >> p) & 1u);
                 }
-                colbit[(size_t)t * 32 + j] = (float)(2 * dot - nu) <= T.kc[(size_t)t * 32 + j];
+                const float a = (float)dot - 0.5f * (float)nu;
+                run[(size_t)j] = first ? a - 0.5f * T.kc[(size_t)t * 32 + j] - 0.25f : a - run[(size_t)j];
+                if (last) colbit[(size_t)t * 32 + j] = (run[(size_t)j] < 0.0f) != invert;
             }
         }
+        if (open) FAIL("the last chain is not closed");
         for (int r = 0; r < S; ++r) {
             const int w_lo = (int)((int64_t)r * m.W >> v), w_hi = (int)((int64_t)(r + 1) * m.W >> v);
             const int t0 = T.range_tile[(size_t)r], t1 = T.range_tile[(size_t)r + 1];
@@ -215,25 +257,75 @@ int main() {
     long checked = 0;
     for (const Shape &sh : shapes) {
         const Model m = make_model(sh.D, sh.F, sh.L, sh.flips, false);
-        std::vector<std::vector<int>> by_tau;
-        if (!hdc::flip_thresholds(m.view(), &by_tau)) {
+        std::vector<std::vector<int>> by_tau, by_tau2;
+        std::vector<hdc::FlipChain> chains;
+        if (!hdc::flip_thresholds(m.view(), &by_tau) || !hdc::flip_chains(m.view(), &by_tau2, &chains)) {
             printf("D=%d F=%d L=%d: thresholds refused\n", sh.D, sh.F, sh.L);
             return 1;
         }
+        if (!chains.empty() || by_tau != by_tau2) {
+            printf("D=%d F=%d L=%d: the two readings of the thresholds differ\n", sh.D, sh.F, sh.L);
+            return 1;
+        }
         std::vector<uint32_t> crow;
-        constant_row(m, by_tau, &crow);
+        constant_row(m, by_tau, chains, &crow);
         for (int v = 0; v < 3 && (1 << v) <= m.W; ++v)
-            if (!check_contract(m, by_tau, crow, v, 6)) return 1;
+            if (!check_contract(m, by_tau, chains, crow, v, 6)) return 1;
         if (!check_wide(m, by_tau, crow, 10, 5, 6, sh.wide_fits)) return 1;
         if (!check_wide(m, by_tau, crow, 10, 3, 4, sh.wide_fits)) return 1;
         if (!check_wide(m, by_tau, crow, 6, 5, 2, false)) return 1;   // (the six-step limit: fits or is refused, never wrong)
         ++checked;
     }
-    {   // a dimension that flips and flips back is refused
+    {   // a dimension that flips and flips back: refused by the reading that wants single flips, a chain for the other
         const Model m = make_model(400, 20, 8, 10, true);
         std::vector<std::vector<int>> by_tau;
+        std::vector<hdc::FlipChain> chains;
         if (hdc::flip_thresholds(m.view(), &by_tau)) {
             printf("a dimension that flips twice was accepted\n");
+            return 1;
+        }
+        if (!hdc::flip_chains(m.view(), &by_tau, &chains) || chains.size() != 1 || chains[0].dims != std::vector<int>{3} ||
+            chains[0].taus != std::vector<int>{2, 3}) {
+            printf("the dimension that flips twice is not the one chain\n");
+            return 1;
+        }
+        std::vector<uint32_t> crow;
+        constant_row(m, by_tau, chains, &crow);
+        for (int v = 0; v < 3; ++v)
+            if (!check_contract(m, by_tau, chains, crow, v, 8)) return 1;
+        ++checked;
+    }
+    // dimensions that flip 2 to 8 times, in sets that share their levels, beside the single flips
+    const struct {
+        int D, F, L, flips, sets, most;
+    } chained[] = {{1000, 100, 16, 20, 6, 4}, {2049, 31, 64, 10, 12, 8}, {700, 342, 64, 5, 5, 3}, {300, 64, 4, 50, 3, 3},
+                   {96, 4, 3, 10, 1, 2}, {1500, 617, 9, 40, 20, 8}};
+    for (const auto &sh : chained) {
+        const Model m = make_chain_model(sh.D, sh.F, sh.L, sh.flips, sh.sets, sh.most);
+        std::vector<std::vector<int>> by_tau;
+        std::vector<hdc::FlipChain> chains;
+        if (!hdc::flip_chains(m.view(), &by_tau, &chains) || chains.empty()) {
+            printf("chained D=%d F=%d L=%d: no chains\n", sh.D, sh.F, sh.L);
+            return 1;
+        }
+        for (const hdc::FlipChain &ch : chains)
+            if (ch.taus.size() < 2 || (int)ch.taus.size() > hdc::kCtMaxChain || ch.dims.empty()) {
+                printf("chained D=%d: a chain of %zu levels and %zu dimensions\n", sh.D, ch.taus.size(), ch.dims.size());
+                return 1;
+            }
+        std::vector<uint32_t> crow;
+        constant_row(m, by_tau, chains, &crow);
+        for (int v = 0; v < 3 && (1 << v) <= m.W; ++v)
+            if (!check_contract(m, by_tau, chains, crow, v, 8)) return 1;
+        ++checked;
+    }
+    {   // more flips than the contraction follows: refused
+        Model m = make_model(400, 20, 12, 10, false);
+        for (int l = 0; l < m.L; ++l) m.level[(size_t)l * m.W] = (m.level[(size_t)l * m.W] & ~1u) | (uint32_t)(l & 1);
+        std::vector<std::vector<int>> by_tau;
+        std::vector<hdc::FlipChain> chains;
+        if (hdc::flip_chains(m.view(), &by_tau, &chains)) {
+            printf("a dimension that flips eleven times was accepted\n");
             return 1;
         }
     }

@@ -1,5 +1,6 @@
 """GPU parity of hdc_encode where it runs as a contraction over the features on the matrix cores
-(Sec. III Eq. 1; level tables whose dimensions flip at most once along the levels, L <= 256,
+(Sec. III Eq. 1; level tables whose dimensions flip once along the levels, or up to 8 times where
+they share the levels at which they do, L <= 256,
 F <= 896, 1024 samples or more, 256 for large models): bit-exact against the CPU oracle, over feature counts on both
 sides of a multiple of 64, even and odd (the tie vote), u8 and fp32 features, sample counts that
 leave a ragged last block (and few enough that the words of a row are split over blocks), and
@@ -72,7 +73,7 @@ def test_encode_contraction_bit_exact(cfg, D, F, L, N):
     ctx.close()
 
 
-def test_encode_tables_that_flip_twice_take_the_other_kernel():
+def test_encode_tables_that_flip_twice_take_the_contraction_and_match():
     wl = make_workload(2, D=2000, F=100, L=16, n_train=2100)
     lv = wl.level.copy()
     # dimension 3 differs from level 0 at level 5 only: it flips and flips back
@@ -85,9 +86,92 @@ def test_encode_tables_that_flip_twice_take_the_other_kernel():
     ctx.hdc_profile_enable(True)
     got = _encode(ctx, x)
     _, n = ctx.hdc_profile_read("encode_contract")
-    assert n == 0
+    assert n == 1, "a dimension that flips twice enters two tiles with opposite signs"
     assert np.array_equal(got, _oracle(wl, x))
     ctx.close()
+
+
+def _levels_from_flips(rng, D, L, flips_at):
+    """Packed level table [L][W]: level 0 random, dimension d changes at the levels flips_at[d]."""
+    bits = np.zeros((L, D), dtype=np.uint8)
+    bits[0] = rng.integers(0, 2, D)
+    change = np.zeros((L, D), dtype=np.uint8)
+    for d, at in enumerate(flips_at):
+        change[list(at), d] = 1
+    bits = (bits[0][None, :] ^ (np.cumsum(change, axis=0) & 1)).astype(np.uint8)
+    W = (D + 31) // 32
+    padded = np.zeros((L, W * 32), dtype=np.uint8)
+    padded[:, :D] = bits
+    return np.packbits(padded.reshape(L, W, 32), axis=2, bitorder="little").view(np.uint32).reshape(L, W)
+
+
+@pytest.mark.parametrize("D,F,L,N,kind,frac,most,nsets", [
+    # level vectors on a circle (level l and level l + L/2 are complements in the dimensions that
+    # vary, the last level is one step from the first): what flips at level l flips back at l + L/2
+    (10000, 617, 64, 2100, "circle", 0, 0, 0), (10000, 342, 64, 5000, "circle", 0, 0, 0), (2049, 400, 16, 1559, "circle", 0, 0, 0),
+    (10000, 617, 64, 300, "circle", 0, 0, 0), (4000, 256, 8, 1100, "circle", 0, 0, 0), (10000, 640, 128, 2048, "circle", 0, 0, 0),
+    # a share `frac` of the dimensions in `nsets` sets that flip at the same 2 to `most` levels, single flips elsewhere
+    (10000, 617, 64, 2111, "sets", 0.2, 8, 12), (3000, 100, 8, 4097, "sets", 0.2, 3, 3), (5000, 400, 100, 1500, "sets", 0.2, 4, 4),
+    (1000, 342, 9, 2048, "sets", 0.2, 4, 2), (10000, 617, 64, 1559, "sets", 0.1, 8, 6), (2048, 896, 16, 1024, "sets", 0.3, 4, 3),
+])
+def test_encode_dimensions_that_flip_several_times_take_the_contraction_and_match(D, F, L, N, kind, frac, most, nsets):
+    """Sec. III Eq. 1 on level tables whose dimensions change more than once along the levels:
+    the sums of the single-flip form, one per level at which the dimension changes, with
+    alternating sign.  Same bits as the oracle; u8 and fp32 features."""
+    rng = np.random.default_rng(D + F + L)
+    wl = make_workload(2, D=D, F=F, L=L, n_train=N)
+    if kind == "circle":
+        half = L // 2
+        step = rng.integers(1, half + 1, D)                    # the level at which a dimension first flips
+        vary = rng.random(D) < 0.5
+        flips_at = [((int(s), int(s) + half) if v and s + half < L else ((int(s),) if v else ())) for s, v in zip(step, vary)]
+    else:
+        sets = [tuple(sorted(rng.choice(np.arange(1, L), size=int(rng.integers(2, min(most, L - 1) + 1)), replace=False).tolist()))
+                for _ in range(nsets)]
+        flips_at = []
+        for d in range(D):
+            r = rng.random()
+            flips_at.append(sets[int(rng.integers(0, nsets))] if r < frac else ((int(rng.integers(1, L)),) if r < 0.6 else ()))
+    wl.level = _levels_from_flips(rng, D, L, flips_at)
+    x, _ = wl.train(N)
+    x[rng.integers(0, N, 20), rng.integers(0, F, 20)] = np.nan
+    ctx = _ctx(wl)
+    ctx.hdc_profile_enable(True)
+    got = _encode(ctx, x)
+    _, n = ctx.hdc_profile_read("encode_contract")
+    assert n == 1, "the call was expected to take the contraction kernel"
+    assert np.array_equal(got, _oracle(wl, x))
+    ctx.close()
+    if int(np.sqrt(F)) ** 2 == F:                              # the same table with byte features (a square grid of them)
+        wl8 = make_workload(3, D=D, F=F, L=L, n_train=N)
+        wl8.item, wl8.level, wl8.tie = wl.item, wl.level, wl.tie
+        x8, _ = wl8.train(N)
+        ctx = _ctx(wl8)
+        assert np.array_equal(_encode(ctx, x8), _oracle(wl8, x8))
+        ctx.close()
+
+
+def test_encode_tables_with_too_many_or_too_scattered_flips_take_the_other_kernel():
+    """A dimension that changes nine times, and a table whose repeated flips share no levels (every
+    level vector drawn afresh): not worth or not fit for the contraction; same bits from the vector kernel."""
+    rng = np.random.default_rng(77)
+    for case in ("nine", "random"):
+        wl = make_workload(2, D=2000, F=100, L=16, n_train=2100)
+        if case == "nine":
+            flips_at = [(int(rng.integers(1, 16)),) if rng.random() < 0.5 else () for _ in range(2000)]
+            flips_at[7] = tuple(range(1, 10))
+            wl.level = _levels_from_flips(rng, 2000, 16, flips_at)
+        else:
+            wl.level = rng.integers(0, 2 ** 32, size=wl.level.shape, dtype=np.uint64).astype(np.uint32)
+            wl.level[:, -1] &= np.uint32((1 << (2000 - 32 * (wl.level.shape[1] - 1))) - 1)
+        x, _ = wl.train(2100)
+        ctx = _ctx(wl)
+        ctx.hdc_profile_enable(True)
+        got = _encode(ctx, x)
+        _, n = ctx.hdc_profile_read("encode_contract")
+        assert n == 0, case
+        assert np.array_equal(got, _oracle(wl, x)), case
+        ctx.close()
 
 
 def test_encode_tables_whose_every_dimension_flips_once_take_the_contraction():
