@@ -210,3 +210,36 @@ def test_encode_contraction_many_samples_and_agreement_with_small_calls():
     assert ctx.hdc_profile_read("encode_contract")[1] == 0, "200 samples were expected to take the vector kernel"
     assert np.array_equal(small, got[:200])
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_multi_flip_tables_match_oracle(seed):
+    """Randomly drawn level tables with dimensions that flip several times, in shared sets of levels
+    of random size and number (so that some models take the chained contraction and some the vector
+    kernel): the bits are the oracle's either way."""
+    rng = np.random.default_rng(9000 + seed)
+    D = int(rng.choice([500, 2049, 4096, 10000, 20000]))
+    F = int(rng.choice([16, 100, 342, 617, 896]))
+    L = int(rng.choice([3, 8, 16, 64, 100, 256]))
+    N = int(rng.choice([256, 700, 1024, 1559, 2048, 3001, 4500]))
+    while D * F * N > 1.5e10:
+        N //= 2
+    N = max(N, 256)
+    frac = float(rng.choice([0.02, 0.2, 0.5, 1.0]))
+    nsets = int(rng.choice([1, 3, 10, 40]))
+    most = int(rng.choice([2, 3, 5, 8]))
+    sets = [tuple(sorted(rng.choice(np.arange(1, L), size=int(rng.integers(2, max(2, min(most, L - 1)) + 1)), replace=False).tolist()))
+            for _ in range(nsets)] if L > 2 else [(1,)]
+    flips_at = []
+    for d in range(D):
+        r = rng.random()
+        flips_at.append(sets[int(rng.integers(0, len(sets)))] if r < frac else ((int(rng.integers(1, L)),) if r < 0.7 else ()))
+    u8 = int(round(F ** 0.5)) ** 2 == F and bool(rng.integers(0, 2))
+    wl = make_workload(3 if u8 else 2, seed=seed, D=D, F=F, L=L, n_train=N)
+    wl.level = _levels_from_flips(rng, D, L, flips_at)
+    x, _ = wl.train(N)
+    what = f"D={D} F={F} L={L} N={N} frac={frac} sets={nsets} most={most} u8={u8}"
+    ctx = _ctx(wl)
+    got = _encode(ctx, x)
+    assert np.array_equal(got, _oracle(wl, x)), what
+    ctx.close()
