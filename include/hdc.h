@@ -204,7 +204,8 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
  * (D <= 32768), longer rows are read again for every class.  Streams of 8192 or more
  * queries against 13 or more classes (20480 or more against 9 to 12) at D <= 32768 run as
  * a matrix-core contraction (dist = |hv| + |class_hv| - 2 <hv, class_hv>, exact), 31
- * classes to a pass; beyond 124 classes (31 where D > 10240) the classes are dealt out
+ * classes to a pass (32 without distances); beyond four passes (one where D > 10240) the
+ * classes are dealt out
  * over several launches, and between them pred_dev holds intermediate keys, not classes:
  * read it after the call's work on the stream is complete, as ever.  The results are the
  * same bits whichever kernel runs.  The pad bits of both inputs must be zero as stated: the kernels

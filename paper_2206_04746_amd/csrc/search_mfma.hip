@@ -42,7 +42,7 @@
 // registers of one tile, turns them into keys (distance, class) and takes their minimum; after
 // a second barrier 64 threads take the minimum over the four register groups.  Slot 31 holds an
 // all-ones class: its dot product is popcount(x), needed only when distances are written out.
-// Hence 31 classes to a pass.  More classes (up to 124) take up to four passes over the same row
+// Hence 31 classes to a pass where distances are asked for, 32 where not.  More classes (up to 124) take up to four passes over the same row
 // images, each with class words of its own in registers; the running minimum of a query's keys
 // stays in the reducing wave's registers between the passes, and the partial sums of consecutive
 // passes go to two LDS areas used in turn, so that a pass costs one barrier.  Rows too long for
@@ -67,7 +67,7 @@ constexpr int kSlots = 32;       // class slots of an MFMA (its M)
 constexpr int kTile = 32;        // queries of an MFMA (its N)
 constexpr int kMaxTiles = 2;     // tiles of queries a block carries at a time: two, or one where the rows are long
 constexpr int kOnes = kSlots - 1;              // the slot of the all-ones class
-constexpr int kPassClasses = kOnes;            // classes of a pass
+constexpr int pass_classes(bool with_dist) { return with_dist ? kOnes : kSlots; }   // classes of a pass: the all-ones class takes a slot only where distances are written
 constexpr int kMaxPasses = 4;
 constexpr int kRegs = 4;                       // accumulator registers a wave reduces (of one tile): two packed words per lane
 constexpr int kGroups = 16 / kRegs;            // such groups per tile; wave w reduces group w % 4 of tile w / 4
@@ -117,6 +117,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     // this launch: classes c0 .. c0 + Cn - 1 of the C; keys_in: pred[] holds the best key of the
     // classes before c0; keys_out: leave the key there, not the class
     constexpr int kJob = kTile * kTiles;
+    constexpr int kPassClasses = pass_classes(kDist);
     constexpr int kWaveRows = kJob / kMfmaWaves;   // rows of a job a wave fetches
     constexpr int kPartialBytes = partial_bytes(kTiles);
     constexpr int kAreaBytes = kMfmaWaves * kPartialBytes;
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         const int cls = p * kPassClasses + q;    // counted from c0
-        const bool real = q < kOnes && cls < Cn;
+        const bool real = q < kPassClasses && cls < Cn;
         uint32_t ones = 0;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
             uint32_t m = 0;
             if (w < (h ? W : s0)) {
                 if (real) m = class_hv[(int64_t)(c0 + cls) * W + w];
-                else if (q == kOnes && p == 0) m = w == W - 1 ? tail : 0xffffffffu;
+                else if (kDist && q == kOnes && p == 0) m = w == W - 1 ? tail : 0xffffffffu;
             }
             ones += __popc(m);
             cw[p][s] = reverse3(m);
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
             for (int p = 0; p < kPasses; ++p) {
                 const int cls = p * kPassClasses + slot_of[j];
                 const int base =
-                    slot_of[j] < kOnes && cls < Cn ? (int)((popc_m[cls] << 10) | (uint32_t)(c0 + cls)) : INT_MAX;
+                    slot_of[j] < kPassClasses && cls < Cn ? (int)((popc_m[cls] << 10) | (uint32_t)(c0 + cls)) : INT_MAX;
                 if (p == 0) base_of[j] = base;
                 if (kPasses > 1 && rt == 0 && q == 0) base_tab[((p * kGroups + rg) * 2 + h) * kRegs + j] = base;
             }
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
     constexpr bool kStaged = kDist && kPasses > 1;
     int *stage = reinterpret_cast<int *>(partials + kAreaBytes);
     const int stage_pitch = Cn | 1;
-    static_assert(!kStaged || kJob * (kMaxPasses * kPassClasses + 1) * 4 <= kAreaBytes, "a job's distances fit an area");
+    static_assert(!kStaged || kJob * (kMaxPasses * kOnes + 1) * 4 <= kAreaBytes, "a job's distances fit an area");
     auto rows_out = [&](int64_t of_job) {   // wave v: rows v, v + 8, ...; four rows read before the first of them is written
         constexpr int kCols = (kPasses * kPassClasses + kWave - 1) / kWave;
         constexpr int kAtOnce = 4;
@@ -509,6 +510,7 @@ bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint3
     if (pieces > 16) return false;
     const int tiles = pieces <= 5 ? 2 : 1;
     const int launch_passes_max = tiles == 2 ? kMaxPasses : 1;
+    const int kPassClasses = pass_classes(dist != nullptr);
     const int passes = (C + kPassClasses - 1) / kPassClasses;
     const int launches = (passes + launch_passes_max - 1) / launch_passes_max;
     if (row_geo(W, tiles, std::min(passes, launch_passes_max)).lds_bytes > 160 * 1024) return false;

@@ -234,7 +234,7 @@ def test_search_bit_exact(D, C, N):
                                    (20000, 12, 32770), (4127, 16, 32801), (7000, 11, 32769), (10000, 32, 32768), (10000, 8, 32768), (10000, 9, 32768), (6400, 31, 32770), (10030, 13, 32785), (10240, 20, 32768), (10241, 20, 32768),
                                    # more than 31 classes: up to four passes over the class slots; 125 miss it
                                    (10000, 62, 8195), (10000, 63, 8193), (9000, 93, 8194), (10000, 94, 8200), (10000, 124, 8199),
-                                   (10000, 125, 8192), (2049, 50, 16390), (400, 100, 16411), (6000, 77, 8193),
+                                   (10000, 125, 8192), (10000, 64, 8195), (10000, 128, 8193), (10000, 129, 8192), (5000, 96, 8194), (10000, 33, 8193), (2049, 50, 16390), (400, 100, 16411), (6000, 77, 8193),
                                    # D above 10240: a tile of 32 rows per block at a time, every count of slices
                                    (10272, 9, 20481), (14000, 31, 8193), (18000, 13, 8195), (23000, 16, 8197), (26000, 14, 8194),
                                    (30000, 13, 8193), (32768, 20, 8193), (32737, 31, 8225), (32800, 14, 8192), (16384, 40, 8200)])
