@@ -205,11 +205,11 @@ int hdc_binarize_online(hdc_ctx *ctx, const float *acc_dev, uint32_t *class_hv_d
  * queries against 13 or more classes (20480 or more against 9 to 12) at D <= 32768 run as
  * a matrix-core contraction (dist = |hv| + |class_hv| - 2 <hv, class_hv>, exact), 31
  * classes to a pass (32 without distances); beyond four passes (one where D > 10240) the
- * classes are dealt out
- * over several launches, and between them pred_dev holds intermediate keys, not classes:
- * read it after the call's work on the stream is complete, as ever.  The results are the
- * same bits whichever kernel runs.  The pad bits of both inputs must be zero as stated: the kernels
- * differ in what they would make of set pad bits.
+ * classes are dealt out over several launches, and between them pred_dev holds
+ * intermediate keys, not classes: read it after the call's work on the stream is
+ * complete, as ever.  The results are the same bits whichever kernel runs.  The pad bits
+ * of both inputs must be zero as stated: the kernels differ in what they would make of
+ * set pad bits.
  */
 int hdc_search(hdc_ctx *ctx, const uint32_t *hv_dev, int64_t N, const uint32_t *class_hv_dev,
                uint32_t *dist_dev, int32_t *pred_dev, void *stream);
