@@ -316,7 +316,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
                     // With one pass over two tiles the compiler keeps all the masks of the class words
                     // in registers over the whole launch; the other forms have no room for that
                     // (it would spill them in this loop), so there the word is made opaque here.
-                    if constexpr (kPasses > 1 || kTiles == 1) asm volatile("" : "+v"(c));
+                    if constexpr (kPasses > 1 || kTiles == 1 || P > 5) asm volatile("" : "+v"(c));
                     const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
                                    (int)((c >> 3) & 0x11111111u)};
 #pragma unroll
@@ -483,7 +483,9 @@ static int launch_span(hdc_ctx_impl *c, const RowGeo &g, const ClassSpan &cs, co
         case 2: return launch_passes<2>(c, g, cs, hv, N, class_hv, dist, pred, s);
         case 3: return launch_passes<3>(c, g, cs, hv, N, class_hv, dist, pred, s);
         case 4: return launch_passes<4>(c, g, cs, hv, N, class_hv, dist, pred, s);
-        default: return launch_passes<5>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        case 5: return launch_passes<5>(c, g, cs, hv, N, class_hv, dist, pred, s);
+        case 6: return launch_mfma<6, 2, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);   // (one pass: see try_search_mfma)
+        default: return launch_mfma<7, 2, 1>(c, g, cs, hv, N, class_hv, dist, pred, s);
         }
     }
     switch ((g.pieces + 1) / 2) {    // an odd count takes the next even one: its last slices meet zero class words
@@ -508,10 +510,11 @@ bool try_search_mfma(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, const uint3
     // tile per job (the class words of such a row fill the registers) and one pass a launch
     const int pieces = row_geo(W, 1, 1).pieces;
     if (pieces > 16) return false;
-    const int tiles = pieces <= 5 ? 2 : 1;
-    const int launch_passes_max = tiles == 2 ? kMaxPasses : 1;
     const int kPassClasses = pass_classes(dist != nullptr);
     const int passes = (C + kPassClasses - 1) / kPassClasses;
+    // (D up to 14336 and one pass: two tiles still fit, the registers and the LDS)
+    const int tiles = pieces <= 5 || (pieces <= 7 && passes == 1 && row_geo(W, 2, 1).lds_bytes <= 160 * 1024) ? 2 : 1;
+    const int launch_passes_max = tiles == 2 && pieces <= 5 ? kMaxPasses : 1;
     const int launches = (passes + launch_passes_max - 1) / launch_passes_max;
     if (row_geo(W, tiles, std::min(passes, launch_passes_max)).lds_bytes > 160 * 1024) return false;
     for (int i = 0, p0 = 0; i < launches; ++i) {

@@ -236,7 +236,7 @@ def test_search_bit_exact(D, C, N):
                                    (10000, 62, 8195), (10000, 63, 8193), (9000, 93, 8194), (10000, 94, 8200), (10000, 124, 8199),
                                    (10000, 125, 8192), (10000, 64, 8195), (10000, 128, 8193), (10000, 129, 8192), (5000, 96, 8194), (10000, 33, 8193), (2049, 50, 16390), (400, 100, 16411), (6000, 77, 8193),
                                    # D above 10240: a tile of 32 rows per block at a time, every count of slices
-                                   (10272, 9, 20481), (14000, 31, 8193), (18000, 13, 8195), (23000, 16, 8197), (26000, 14, 8194),
+                                   (10272, 9, 20481), (14000, 31, 8193), (12288, 26, 8195), (14336, 13, 8193), (14337, 13, 8193), (13000, 40, 8194), (11000, 32, 8200), (18000, 13, 8195), (23000, 16, 8197), (26000, 14, 8194),
                                    (30000, 13, 8193), (32768, 20, 8193), (32737, 31, 8225), (32800, 14, 8192), (16384, 40, 8200)])
 def test_search_long_streams_bit_exact(D, C, N):
     rng = np.random.default_rng(D + 13 * C)
