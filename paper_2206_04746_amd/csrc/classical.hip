@@ -8,7 +8,8 @@
 // stays HBM-bound.  Rows of up to 320 words and up to four classes: a block takes a run of
 // consecutive rows, orders them by class by itself in LDS and gives each of its 16 waves a
 // share to read as whole rows (accumulate_local_kernel: no grouping pass, no wave waits for
-// another while it streams).  More classes: the rows are first grouped by class (a counting
+// another while it streams; rows of up to 640 words go through it twice, a half of every
+// row each time).  More classes: the rows are first grouped by class (a counting
 // sort of the labels, only the row indices move) and a block takes a run of rows of ONE class
 // (accumulate_rows_kernel, the same streaming).  Wider rows: grouped as well; a block's waves
 // cover the slices of 64 word columns side by side (so rows are read as whole contiguous
@@ -332,6 +333,7 @@ __global__ __launch_bounds__(1024) void accumulate_kernel(
     }
     __syncthreads();
     if (group != 0) return;
+    if (col >= Wp) return;   // (wave-uniform: the last chunk of slices may reach past the row, and a partial row has Wp columns)
     for (int g = 0; g < rg - 1; ++g) {
         const uint32_t *src = merge + (size_t)(g * spb + sl) * (kWavePlanes * kWave) + lane;
         uint32_t carry = 0;
@@ -614,7 +616,8 @@ constexpr int kLocalMaxC = 4;
 template <int KPL, bool QUAD>
 __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_local_kernel(
     const uint32_t *__restrict__ hv, const int32_t *__restrict__ labels, uint32_t n, int C, int W, int Wp, int rpw,
-    uint32_t *__restrict__ partial, uint32_t *__restrict__ blk, unsigned long long *class_n) {
+    uint32_t *__restrict__ partial, uint32_t *__restrict__ blk, unsigned long long *class_n, int stride) {
+    // (W, Wp: the words this launch counts, which start at hv; stride: the words from a row to the next)
     extern __shared__ uint32_t merge[];
     __shared__ uint16_t list_s[kRowsWaves * 256];
     __shared__ uint32_t wc_s[kRowsWaves][kLocalMaxC], used_s[kLocalMaxC];
@@ -684,7 +687,7 @@ __global__ __launch_bounds__(kRowsWaves *kWave) void accumulate_local_kernel(
             const uint32_t v = lst[min(r0 + (uint32_t)(lane & 7), last)];   // one LDS read, eight readlanes
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                row[j] = hv + (int64_t)(block_first + (uint32_t)__builtin_amdgcn_readlane((int)v, j)) * W;
+                row[j] = hv + (int64_t)(block_first + (uint32_t)__builtin_amdgcn_readlane((int)v, j)) * stride;
         });
         if (run1 > bnd[c + 1]) {   // more of the run follows: this class's count waits in its slot
             uint32_t *dst = merge + (size_t)(8 + c) * kSlotWords + lane;
@@ -869,7 +872,7 @@ __global__ __launch_bounds__(kAccWaves *kWave) void accumulate_small_kernel(
 // K parts of a class's item range are combined with atomics only when K > 1.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__restrict__ partial,
                                                                const uint32_t *__restrict__ blk, int Wp,
-                                                               int D, int K, int32_t *acc) {
+                                                               int D, int K, int32_t *acc, int d0) {
     const int c = blockIdx.y;
     const int pair = blockIdx.x * 256 + threadIdx.x;   // dims 2*pair, 2*pair + 1
     if (pair >= Wp * 16) return;
@@ -890,7 +893,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const uint32_t *__
         s0 += v & 0xffffu;
         s1 += v >> 16;
     }
-    const int d = pair * 2;
+    const int d = d0 + pair * 2;   // (d0: the first dimension of the partial rows, even)
     int32_t *dst = acc + (int64_t)c * D + d;
     if (K == 1) {
         if (d < D && s0) dst[0] += (int32_t)s0;
@@ -913,6 +916,11 @@ struct AccPlan {
     int64_t rows_max; // most rows one launch takes in a single round
 };
 constexpr int kRowsMaxKpl = 5;   // word positions per lane the wave-per-row kernel is built for (its registers)
+// Rows up to here go through accumulate_local, the wider ones of them in two column slices.  More
+// slices lose to the slice-per-wave kernel: every pass opens the same memory pages again for a
+// shorter piece of each row (1 M-row-equivalents at C = 2: D = 20000 333 -> 247 us, 16384 233 -> 220,
+// 14000 274 -> 253; three slices at D = 28000 263 -> 274, four at 32768 251 -> 266).
+constexpr int kLocalMaxWords = 2 * kRowsMaxKpl * kSliceWords;
 static size_t rows_lds(int kpl) { return (size_t)8 * kpl * 9 * kWave * sizeof(uint32_t); }
 // (the 16-byte layout where the rows have 257 to 320 words)
 static const void *rows_kernel(int kpl, int W) {
@@ -989,14 +997,16 @@ int64_t classical_max_items(hdc_ctx_impl *c) {
     return p.cap + 2 * (int64_t)c->p.C + 16 + c->perm_rows / (p.rg * p.rb_max);
 }
 
-// acc += the partial rows of each class (blk in the context's scratch lists them).
-static int reduce_partials(hdc_ctx_impl *c, int classes, int32_t *acc, hipStream_t s) {
+// acc += the partial rows of each class (blk in the context's scratch lists them); the rows are
+// Wp words wide (0: the model's) and start at word w0 of the model's rows.
+static int reduce_partials(hdc_ctx_impl *c, int classes, int32_t *acc, hipStream_t s, int Wp = 0, int w0 = 0) {
+    if (Wp == 0) Wp = c->Wp;
     // enough threads for the reduction: split a class's partial rows K ways when C is small
-    const int pairs = c->Wp * 16;
+    const int pairs = Wp * 16;
     int K = (int)((262144 + (int64_t)classes * pairs - 1) / ((int64_t)classes * pairs));
     K = K < 1 ? 1 : (K > 16 ? 16 : K);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)classes, (unsigned)K),
-                       dim3(256), 0, s, c->partial_d, c->cls_blk_d, c->Wp, c->p.D, K, acc);
+                       dim3(256), 0, s, c->partial_d, c->cls_blk_d, Wp, c->p.D, K, acc, 32 * w0);
     HDC_HIP(hipGetLastError());
     return HDC_OK;
 }
@@ -1034,8 +1044,13 @@ static int accumulate_grouped(hdc_ctx_impl *c, const AccPlan &plan, const uint32
 // rows than one round of full blocks holds run as equal rounds of smaller blocks.
 static int accumulate_local(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *labels, int64_t N,
                             int classes, int32_t *acc, int64_t *class_n, hipStream_t s) {
-    const int kpl = c->Wp / kSliceWords;
-    const void *fn = local_kernel(kpl, c->W);
+    // Rows of more than 320 words (up to 640: the callers see to that) are taken in two column
+    // slices of equal width (a multiple of four words), a pass of the same kernel per slice: a
+    // wave then reads a kilobyte or more of a row in one piece, and the labels once per slice.
+    const int nsl = (c->W + kRowsMaxKpl * kSliceWords - 1) / (kRowsMaxKpl * kSliceWords);
+    const int ws = nsl == 1 ? c->W : ((c->W + nsl - 1) / nsl + 3) / 4 * 4;
+    const int kpl = (ws + kSliceWords - 1) / kSliceWords;
+    const void *fn = local_kernel(kpl, ws);
     const size_t lds = rows_lds(kpl) / 8 * (8 + classes - 1);   // (a slot more per class that can end inside a wave's run)
     const bool raise = lds + 16 * 1024 > 64 * 1024;     // (the kernel has some static LDS of its own)
     if (raise) HDC_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -1045,7 +1060,7 @@ static int accumulate_local(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *
         HDC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&bpc, fn, kRowsWaves * kWave, lds));
         held = bpc < 1 ? 1 : bpc;
     }
-    const int64_t most = c->partial_items / classes;   // blocks a launch may have
+    const int64_t most = c->partial_items / classes;   // blocks a launch may have (the scratch is sized for partial rows of the model's width)
     if (most < 1) return HDC_ELIMIT;                   // cannot happen: the scratch holds a row per class and more
     int64_t cap = (int64_t)c->num_cus * held;
     if (cap > most) cap = most;
@@ -1058,19 +1073,24 @@ static int accumulate_local(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *
         rpw = rpw < 16 ? 16 : (rpw > kRowsPerWaveMax ? kRowsPerWaveMax : rpw);
         const int64_t blocks = (n + kRowsWaves * rpw - 1) / (kRowsWaves * rpw);
         if (blocks > most) return HDC_ELIMIT;          // cannot happen: blocks <= cap * rounds <= most
-        const uint32_t *hv0 = hv + (size_t)n0 * c->W;
         const int32_t *lab0 = labels ? labels + n0 : nullptr;
         const uint32_t n32 = (uint32_t)n;
         const int rpw32 = (int)rpw;
-        unsigned long long *cn = reinterpret_cast<unsigned long long *>(class_n);
-        {
-            ProfScope prof(c, HDC_K_ACCUMULATE, s);
-            void *args[] = {(void *)&hv0, (void *)&lab0, (void *)&n32, (void *)&classes, (void *)&c->W, (void *)&c->Wp,
-                            (void *)&rpw32, (void *)&c->partial_d, (void *)&c->cls_blk_d, (void *)&cn};
-            HDC_HIP(hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(kRowsWaves * kWave), args, lds, s));
+        for (int sl = 0; sl < nsl; ++sl) {
+            const int w0 = sl * ws;
+            int w_sl = c->W - w0 < ws ? c->W - w0 : ws;
+            int wp_sl = (w_sl + kSliceWords - 1) / kSliceWords * kSliceWords;
+            const uint32_t *hv0 = hv + (size_t)n0 * c->W + w0;
+            unsigned long long *cn = sl == 0 ? reinterpret_cast<unsigned long long *>(class_n) : nullptr;   // (the rows are counted once)
+            {
+                ProfScope prof(c, HDC_K_ACCUMULATE, s);
+                void *args[] = {(void *)&hv0, (void *)&lab0, (void *)&n32, (void *)&classes, (void *)&w_sl, (void *)&wp_sl,
+                                (void *)&rpw32, (void *)&c->partial_d, (void *)&c->cls_blk_d, (void *)&cn, (void *)&c->W};
+                HDC_HIP(hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(kRowsWaves * kWave), args, lds, s));
+            }
+            const int rc = reduce_partials(c, classes, acc, s, wp_sl, w0);
+            if (rc != HDC_OK) return rc;
         }
-        const int rc = reduce_partials(c, classes, acc, s);
-        if (rc != HDC_OK) return rc;
     }
     return HDC_OK;
 }
@@ -1092,7 +1112,7 @@ int launch_train_classical(hdc_ctx_impl *c, const uint32_t *hv, const int32_t *l
         HDC_HIP(hipGetLastError());
         return HDC_OK;
     }
-    if (plan.rows && C <= kLocalMaxC) return accumulate_local(c, hv, labels, N, C, acc, class_n, s);
+    if (C <= kLocalMaxC && c->W <= kLocalMaxWords) return accumulate_local(c, hv, labels, N, C, acc, class_n, s);
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const uint32_t *hv0 = hv + (size_t)n0 * c->W;
@@ -1150,7 +1170,7 @@ int launch_vsum(hdc_ctx_impl *c, const uint32_t *hv, int64_t N, int32_t *out, hi
     if (prc != HDC_OK) return prc;
     hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((c->p.D + 255) / 256)), dim3(256), 0, s, out,
                        (int64_t)c->p.D);
-    if (plan.rows) return accumulate_local(c, hv, nullptr, N, 1, out, nullptr, s);
+    if (c->W <= kLocalMaxWords) return accumulate_local(c, hv, nullptr, N, 1, out, nullptr, s);
     for (int64_t n0 = 0; n0 < N; n0 += plan.rows_max) {
         const int64_t n = (N - n0 < plan.rows_max) ? N - n0 : plan.rows_max;
         const int64_t rb = plan_rb(plan, n);
@@ -1236,7 +1256,7 @@ int vsum_static(int32_t D, const uint32_t *hv, int64_t N, int32_t *out, hipStrea
         int K = (int)((262144 + (int64_t)pairs - 1) / pairs);
         K = K < 1 ? 1 : (K > 16 ? 16 : K);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((pairs + 255) / 256), 1u, (unsigned)K), dim3(256), 0, s,
-                           partial, blk, Wp, D, K, out);
+                           partial, blk, Wp, D, K, out, 0);
     }
     HDC_HIP(hipGetLastError());
     return HDC_OK;

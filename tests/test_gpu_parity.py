@@ -148,8 +148,15 @@ def gpu_classical(ctx, hv_d, y, acc=None, cn=None):
                                    (10000, 2, 70001), (4000, 26, 40000), (64, 1000, 50000),
                                    (2000, 1, 40001), (512, 3, 150000), (320, 2, 300007),
                                    (3000, 4, 260000), (10000, 5, 33000), (9000, 2, 8193),
-                                   # rows of more than 320 words: grouped rows, a slice of 64 words per wave
-                                   (12000, 2, 40000), (20000, 3, 20001), (10400, 1, 9000),
+                                   # rows of more than 320 words and up to four classes: column slices of up to 320
+                                   # words, a pass each (two slices; three; four of 256; a last slice of few words;
+                                   # the widest rows of this path); more classes or wider rows: grouped rows, a slice
+                                   # of 64 words per wave
+                                   (12000, 2, 40000), (20000, 3, 20001), (10400, 1, 9000), (10272, 4, 9001), (16384, 2, 30000),
+                                   (32768, 4, 12000), (30001, 2, 9000), (20512, 3, 8200), (65536, 2, 8300), (65600, 2, 8300),
+                                   (20000, 5, 9000), (16384, 26, 9000),
+                                   # slices that do not fill the last block of sixteen
+                                   (40000, 5, 9000), (34000, 26, 8200), (100000, 3, 8193),
                                    # the fused launch at its row limit: everything in one or two classes,
                                    # many classes, a dimension count that is no multiple of 4, very wide rows
                                    (10000, 1, 8192), (10000, 2, 8192), (1024, 1000, 8000), (10001, 3, 5000),

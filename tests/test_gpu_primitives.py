@@ -61,7 +61,8 @@ def test_pack_and_unpack_unaligned_matrix():
     ctx.close()
 
 
-@pytest.mark.parametrize("D,N", [(10000, 5000), (33, 7), (1, 3), (2049, 130), (32768, 65), (10000, 70001)])
+@pytest.mark.parametrize("D,N", [(10000, 5000), (33, 7), (1, 3), (2049, 130), (32768, 65), (10000, 70001),
+                                 (16384, 9000), (20000, 20001), (10272, 8193), (65536, 300), (70000, 100)])
 def test_hsum_and_vsum_bit_exact(D, N):
     rng = np.random.default_rng(D * 3 + N)
     dens = rng.random(N)[:, None]                              # rows of very different weight
