@@ -119,3 +119,54 @@ def test_random_search_draws_match_oracle(seed):
     first_min = (dist == dist.min(dim=1, keepdim=True).values).int().argmax(dim=1)
     assert torch.equal(pred.long(), first_min), what
     ctx.close()
+
+
+# Very long hypervectors (D above 32768, where the rows no longer fit a wave's registers and the
+# wide-row forms of every kernel run) on calls long enough for the streaming kernels: encoding,
+# classical training, the sums and the search against the oracle, everything compared in full.
+@pytest.mark.parametrize("seed", range(8))
+def test_random_very_wide_rows_match_oracle(seed):
+    from paper_2206_04746_amd import binding
+    rng = np.random.default_rng(8000 + seed)
+    D = int(rng.choice([32800, 40000, 50001, 65536, 65600, 100000, 131072 + 5, 200000]))
+    F = int(rng.choice([4, 9, 20, 33]))
+    L = int(rng.choice([2, 8, 64]))
+    C = int(rng.choice([1, 2, 3, 5, 12, 26]))
+    N = int(rng.choice([300, 5000, 8193, 9000, 20000]))
+    while D * F * N > 1.2e10:
+        N = N * 2 // 3
+    what = f"D={D} F={F} L={L} C={C} N={N}"
+    wl = make_workload(2, seed=seed, D=D, F=F, L=L, C=C, n_train=min(N, 4096))
+    x0, _ = wl.train(min(N, 4096))
+    x = np.ascontiguousarray(np.tile(x0, ((N + x0.shape[0] - 1) // x0.shape[0], 1))[:N])
+    y = rng.integers(0, C, N).astype(np.int32)
+    y[rng.integers(0, N, 20)] = C + 2
+    ctx = binding.Context(wl.D, wl.F, wl.L, wl.C, wl.item, wl.level, wl.tie, wl.lo, wl.scale, wl.dtype)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    hv = torch.full((N, ctx.W), -1, dtype=torch.int32, device="cuda")
+    ctx.hdc_encode(xd, hv)
+    got = _u32(hv)
+    assert np.array_equal(got, oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)), what
+    acc = torch.zeros((C, D), dtype=torch.int32, device="cuda")
+    cn = torch.zeros(C, dtype=torch.int64, device="cuda")
+    cls = torch.empty((C, ctx.W), dtype=torch.int32, device="cuda")
+    ctx.hdc_train_classical(hv, yd, acc, cn)
+    ctx.hdc_binarize_classical(acc, cn, cls)
+    o_acc, o_cn = oracle.train_classical(got, y, D, C)
+    o_cls = oracle.binarize_classical(o_acc, o_cn, wl.tie)
+    assert np.array_equal(acc.cpu().numpy(), o_acc), what
+    assert np.array_equal(cn.cpu().numpy(), o_cn), what
+    assert np.array_equal(_u32(cls), o_cls), what
+    vs = torch.empty(D, dtype=torch.int32, device="cuda")
+    hs = torch.empty(N, dtype=torch.int32, device="cuda")
+    ctx.hdc_vsum(hv, vs)
+    ctx.hdc_hsum(hv, hs)
+    assert np.array_equal(vs.cpu().numpy(), oracle.vsum(got, D)), what
+    assert np.array_equal(hs.cpu().numpy(), oracle.hsum(got, D)), what
+    dist = torch.empty((N, C), dtype=torch.int32, device="cuda")
+    pred = torch.empty(N, dtype=torch.int32, device="cuda")
+    ctx.hdc_search(hv, cls, pred, dist)
+    o_d, o_p = oracle.search(got, o_cls, D)
+    assert np.array_equal(_u32(dist), o_d), what
+    assert np.array_equal(pred.cpu().numpy(), o_p), what
+    ctx.close()
