@@ -147,6 +147,17 @@ def test_random_very_wide_rows_match_oracle(seed):
     ctx.hdc_encode(xd, hv)
     got = _u32(hv)
     assert np.array_equal(got, oracle.encode(x, wl.D, wl.L, wl.item, wl.level, wl.tie, wl.lo, wl.scale)), what
+    hv_s = torch.full_like(hv, -1)
+    ctx.hdc_encode_sparse(xd, hv_s)
+    assert torch.equal(hv_s, hv), what
+    n_bits = min(N, 257)                                             # the byte form of a few hundred rows
+    bits = torch.empty((n_bits, D), dtype=torch.uint8, device="cuda")
+    back = torch.full((n_bits, ctx.W), -1, dtype=torch.int32, device="cuda")
+    ctx.hdc_unpack(hv[:n_bits], bits)
+    ctx.hdc_pack(bits, back)
+    assert np.array_equal(bits.cpu().numpy(), oracle.unpack(got[:n_bits], D)), what
+    assert torch.equal(back, hv[:n_bits]), what
+    del bits, back, hv_s
     acc = torch.zeros((C, D), dtype=torch.int32, device="cuda")
     cn = torch.zeros(C, dtype=torch.int64, device="cuda")
     cls = torch.empty((C, ctx.W), dtype=torch.int32, device="cuda")
