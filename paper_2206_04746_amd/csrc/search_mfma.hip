@@ -429,10 +429,7 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
 }
 
 constexpr int64_t kMfmaQueries = 20480;        // from here on with 9 to 12 classes (measured against the vector kernels at D = 10000)
-#ifndef HDC_X_MANY
-#define HDC_X_MANY 8192
-#endif
-constexpr int64_t kMfmaQueriesMany = HDC_X_MANY;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 14 us   // from here on there is a job for most blocks of the chip
+constexpr int64_t kMfmaQueriesMany = 8192;     // and from here on with 13 or more: 10000 queries x 26 classes 19 -> 12 us (below, a block's set-up -- its class words -- outweighs its one or two jobs: 4096 x 100 classes 20 us on the vector kernel, 35 here)
 
 // What one launch is given: its classes and what pred[] holds before and after it.
 struct ClassSpan {
