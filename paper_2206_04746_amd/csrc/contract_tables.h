@@ -119,7 +119,7 @@ inline void build_contract_tables(const ModelView &m, const std::vector<std::vec
         const size_t t_first = T.tau_of.size();
         T.range_tile.push_back((int32_t)t_first);
         // one tile: columns dims[at ...] (32 at most) against threshold tau; the row's bits point at tile `owner`
-        auto add_tile = [&](const std::vector<int> &dims, size_t at, int32_t tau_entry, size_t owner) {
+        auto add_tile = [&](const std::vector<int> &dims, size_t at, int32_t tau_entry, size_t owner, bool negated_start) {
             const size_t t = T.tau_of.size();
             T.tau_of.push_back(tau_entry);
             T.kc.resize((t + 1) * 32, kCtNever);
@@ -137,7 +137,9 @@ inline void build_contract_tables(const ModelView &m, const std::vector<std::vec
                     }
                     const int tie_vote = tie_votes ? (int)((m.tie[w] >> b) & 1u) : 0;
                     T.src_of[(size_t)b * W + w] = (uint32_t)((owner - t_first) * 32 + j);
-                    T.kc[t * 32 + j] = (float)(ones + tie_vote - thr);
+                    // (the kernel starts a column at -kc / 2 - 1 / 4; a chain that wants the opposite start says -kc - 1)
+                    const int kc = ones + tie_vote - thr;
+                    T.kc[t * 32 + j] = (float)(negated_start ? -kc - 1 : kc);
                 }
                 for (int k = 0; k < steps; ++k)
                     for (int h = 0; h < 2; ++h)
@@ -150,19 +152,28 @@ inline void build_contract_tables(const ModelView &m, const std::vector<std::vec
             for (int d : by_tau[(size_t)tau])
                 if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
             for (size_t at = 0; at < dims.size(); at += kCtCols)
-                add_tile(dims, at, T.chained ? tau | kCtFirst | kCtLast : tau, T.tau_of.size());
+                add_tile(dims, at, T.chained ? tau | kCtFirst | kCtLast : tau, T.tau_of.size(), false);
         }
         for (const FlipChain &ch : chains) {
             dims.clear();
             for (int d : ch.dims)
                 if ((d >> 5) >= w_lo && (d >> 5) < w_hi) dims.push_back(d);
+            // The kernel negates the running value at every further tile, so the i-th of n tiles
+            // enters with the sign (-1)^(n - i).  Thresholds in ascending order: the wanted sums
+            // times (-1)^(n - 1), hence the inverted bits for even n.  In descending order the signs
+            // are the wanted ones and only the start value needs the factor (-1)^(n - 1).  The
+            // groups of 32 dimensions of a chain take the two orders in turn, so that a group's
+            // first threshold is its predecessor's last and the kernel forms its masks once for both.
             const size_t n = ch.taus.size();
-            for (size_t at = 0; at < dims.size(); at += kCtCols) {
+            bool descending = false;
+            for (size_t at = 0; at < dims.size(); at += kCtCols, descending = !descending) {
                 const size_t owner = T.tau_of.size() + n - 1;   // the chain's last tile holds the bits
-                for (size_t i = 0; i < n; ++i)
-                    add_tile(dims, at,
-                             ch.taus[i] | (i == 0 ? kCtFirst : 0) | (i + 1 == n ? kCtLast | (n % 2 == 0 ? kCtInvert : 0) : 0),
-                             owner);
+                for (size_t i = 0; i < n; ++i) {
+                    const int tau = ch.taus[descending ? n - 1 - i : i];
+                    const int32_t last = kCtLast | (!descending && n % 2 == 0 ? kCtInvert : 0);
+                    add_tile(dims, at, tau | (i == 0 ? kCtFirst : 0) | (i + 1 == n ? last : 0), owner,
+                             descending && n % 2 == 0);
+                }
             }
         }
         T.range_max = std::max(T.range_max, (int)(T.tau_of.size() - t_first));
