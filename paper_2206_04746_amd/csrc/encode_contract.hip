@@ -44,7 +44,9 @@
 // alternating sign.  Its 32-dimension group takes one tile per threshold, one after the other in
 // the same wave; the accumulators carry the running value from tile to tile, negated each time
 // (-R + <U_i, B> - |U_i| / 2), and the bits come out of the last tile, inverted where the tiles
-// are even in number.  (kChain; a model without such dimensions runs the kernel without it.)
+// are even in number and their thresholds ascend (the host lets every other group of a chain
+// descend, with the start value to match, so that neighbouring tiles share a threshold and its
+// masks).  (kChain; a model without such dimensions runs the kernel without it.)
 // (Tried first: an LDS atomic OR per bit into images of the rows, six times the time of the MFMAs;
 // then the wave's ballots as words over the dimensions and a gather per (bit, sample), LDS bank
 // conflicts making it four times the time of the MFMAs.)
