@@ -67,11 +67,11 @@ constexpr int kCtWaves = 8;        // waves per block at least (the kernel runs 
 constexpr int kCtPlanes = 8;      // most bit planes of a bin number: L <= 256 (a model has ceil(log2 L) of them)
 constexpr int kCtMaxSteps = 14;   // MFMAs per tile: 64 features each
 constexpr int kCtSamples = 32;    // samples per block and job
-// A model with chains is taken while its tiles, a chain's counted one and a half times (each
-// brings a new threshold), are at most (24 + F / 34) / 10 times the tiles its varying dimensions
+// A model with chains is taken while its tiles, a chain's counted one and a quarter times (most
+// bring a new threshold), are at most (24 + F / 34) / 10 times the tiles its varying dimensions
 // would fill: measured at D = 10000 on 65536 samples against the vector kernel, whose time grows
-// with F -- 617 features, 30 % of the dimensions in chains of 2 to 8: 1.09 against 1.20 ms at 3.8
-// times; 100 features, chains of 2 to 4: 0.31 against 0.28 ms at 3.1 times.
+// with F (617 features, 30 % of the dimensions in chains of 2 to 8, 3.3 times; 100 features,
+// chains of 2 to 4, 2.7 times: see the measurements where prepare_contract is described).
 constexpr int chain_work_tenths(int F) { return 24 + F / 34; }
 
 template <typename T>
@@ -106,11 +106,11 @@ int prepare_contract(hdc_ctx_impl *c, const uint32_t *item, const uint32_t *leve
         // A chain's tiles are as many as its thresholds per 32 dimensions, full or not: where the
         // dimensions that flip more than once do not share their levels (a random table), the tiles
         // are many and nearly empty, and the vector kernel is the faster one.
-        int64_t varying = 0, tiles2 = 0;   // tiles in halves
-        for (const std::vector<int> &dims : by_tau) varying += (int64_t)dims.size(), tiles2 += 2 * (((int64_t)dims.size() + 31) / 32);
+        int64_t varying = 0, tiles4 = 0;   // tiles in quarters
+        for (const std::vector<int> &dims : by_tau) varying += (int64_t)dims.size(), tiles4 += 4 * (((int64_t)dims.size() + 31) / 32);
         for (const FlipChain &ch : chains)
-            varying += (int64_t)ch.dims.size(), tiles2 += 3 * (int64_t)ch.taus.size() * (((int64_t)ch.dims.size() + 31) / 32);
-        if (tiles2 * 10 > 2 * chain_work_tenths(F) * ((varying + 31) / 32)) return HDC_OK;
+            varying += (int64_t)ch.dims.size(), tiles4 += 5 * (int64_t)ch.taus.size() * (((int64_t)ch.dims.size() + 31) / 32);
+        if (tiles4 * 10 > 4 * chain_work_tenths(F) * ((varying + 31) / 32)) return HDC_OK;
     }
     for (int v = 0; v < 3; ++v) {   // the row's words in 1 << v ranges, a block per (32 samples, range)
         const int S = 1 << v;
