@@ -100,11 +100,11 @@ int hdc_destroy(hdc_ctx *ctx);
  *   hv_dev    [N][W]  out
  * The bits do not depend on how the call is carried out: calls of 1024 samples or more (256 for
  * models of a thousand matrix instructions per 32 samples, e.g. 600 features at D = 10000) on a
- * model whose level vectors change every dimension at most once from one level to the next
- * (at most 256 levels, 4 to 896 features) run as a contraction over the features on the matrix
- * cores (long streams, 128 samples or more per compute unit, of models of at most about 370
- * features, or about 630 with at most 64 levels, in a form of their own), all others on the
- * vector unit.
+ * model in which every dimension changes at most once along the levels, or up to 8 times
+ * where enough dimensions change at the same levels (at most 256 levels, 4 to 896 features),
+ * run as a contraction over the features on the matrix cores (long streams, 128 samples or
+ * more per compute unit, of single-change models of at most about 370 features, or about 630
+ * with at most 64 levels, in a form of their own), all others on the vector unit.
  */
 int hdc_encode(hdc_ctx *ctx, const void *feats_dev, int64_t N, uint32_t *hv_dev, void *stream);
 
