@@ -297,14 +297,20 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
         };
         int key = INT_MAX;
         int dot[kPasses][kRegs];
+        // Two passes go through the row images together: the query-side masks of a word are formed
+        // once for both, their partial sums go to the two areas at once, and one barrier serves
+        // both.  (Three and four passes go one at a time: two more sets of accumulators would not
+        // fit beside their class words.)
+        constexpr int kTogether = kPasses == 2 ? 2 : 1;
 #pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            const int area = (p & 1) * kAreaBytes;    // the passes take the two areas in turn
-            v16f acc[kTiles];
+        for (int p0 = 0; p0 < kPasses; p0 += kTogether) {
+            v16f acc[kTogether][kTiles];
 #pragma unroll
-            for (int t = 0; t < kTiles; ++t)
+            for (int i = 0; i < kTogether; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+                for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.0f;
             u32x4 x[2][kTiles];
             take(x[0], 0);
 #pragma unroll
@@ -312,58 +318,71 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void search_mfma_kernel(
                 if (k + 1 < P) take(x[(k + 1) & 1], k + 1);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    uint32_t c = cw[p][4 * k + e];
-                    // With one pass over two tiles the compiler keeps all the masks of the class words
-                    // in registers over the whole launch; the other forms have no room for that
-                    // (it would spill them in this loop), so there the word is made opaque here.
-                    if constexpr (kPasses > 1 || kTiles == 1 || P > 5) asm volatile("" : "+v"(c));
-                    const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
-                                   (int)((c >> 3) & 0x11111111u)};
+                    v4i b[kTiles];
 #pragma unroll
                     for (int t = 0; t < kTiles; ++t) {
                         const uint32_t xw = x[k & 1][t][e];
-                        const v4i b = {(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
-                                       (int)((xw >> 1) & 0x44444444u)};
-                        acc[t] = mfma(a, b, acc[t]);
+                        b[t] = v4i{(int)(xw & 0x11111111u), (int)(xw & 0x22222222u), (int)(xw & 0x44444444u),
+                                   (int)((xw >> 1) & 0x44444444u)};
+                    }
+#pragma unroll
+                    for (int i = 0; i < kTogether; ++i) {
+                        uint32_t c = cw[p0 + i][4 * k + e];
+                        // With one pass over two tiles the compiler keeps all the masks of the class words
+                        // in registers over the whole launch; the other forms have no room for that
+                        // (it would spill them in this loop), so there the word is made opaque here.
+                        if constexpr (kPasses > 1 || kTiles == 1 || P > 5) asm volatile("" : "+v"(c));
+                        const v4i a = {(int)(c & 0x44444444u), (int)(c & 0x22222222u), (int)(c & 0x11111111u),
+                                       (int)((c >> 3) & 0x11111111u)};
+#pragma unroll
+                        for (int t = 0; t < kTiles; ++t) acc[i][t] = mfma(a, b[t], acc[i][t]);
                     }
                 }
             }
 
-            // partial dot products, registers 2i and 2i + 1 in one word: [tile][group of four registers][lane][2 words]
-            uint32_t *out = reinterpret_cast<uint32_t *>(mine + area);
+            // partial dot products, registers 2i and 2i + 1 in one word: [tile][group of four registers][lane][2 words];
+            // pass p takes area p % 2
 #pragma unroll
-            for (int t = 0; t < kTiles; ++t)
+            for (int i = 0; i < kTogether; ++i) {
+                uint32_t *out = reinterpret_cast<uint32_t *>(mine + ((p0 + i) & 1) * kAreaBytes);
 #pragma unroll
-                for (int g = 0; g < kGroups; ++g) {
-                    uint32_t pk[2];
+                for (int t = 0; t < kTiles; ++t)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        pk[i] = (uint32_t)acc[t][kRegs * g + 2 * i] | ((uint32_t)acc[t][kRegs * g + 2 * i + 1] << 16);
-                    *reinterpret_cast<uint2 *>(out + ((t * kGroups + g) * kWave + lane) * 2) = make_uint2(pk[0], pk[1]);
-                }
+                    for (int g = 0; g < kGroups; ++g) {
+                        uint32_t pk[2];
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            pk[j] = (uint32_t)acc[i][t][kRegs * g + 2 * j] | ((uint32_t)acc[i][t][kRegs * g + 2 * j + 1] << 16);
+                        *reinterpret_cast<uint2 *>(out + ((t * kGroups + g) * kWave + lane) * 2) = make_uint2(pk[0], pk[1]);
+                    }
+            }
             __syncthreads();
             // (the pass after the next writes this area again: every wave has then passed the next
             // pass's barrier, or the job's last one, and so has read what it needs here)
 
             if (reduces) {
-                // the halves of a word add up separately: eight partials stay far below 2^16
-                uint2 sum = make_uint2(0u, 0u);
 #pragma unroll
-                for (int v = 0; v < kMfmaWaves; ++v) {
-                    const uint2 part = *reinterpret_cast<const uint2 *>(
-                        reinterpret_cast<const uint32_t *>(partials + area + v * kPartialBytes) +
-                        ((rt * kGroups + rg) * kWave + lane) * 2);
-                    sum.x += part.x;
-                    sum.y += part.y;
+                for (int i = 0; i < kTogether; ++i) {
+                    const int p = p0 + i, area = (p & 1) * kAreaBytes;
+                    // the halves of a word add up separately: eight partials stay far below 2^16
+                    uint2 sum = make_uint2(0u, 0u);
+#pragma unroll
+                    for (int v = 0; v < kMfmaWaves; ++v) {
+                        const uint2 part = *reinterpret_cast<const uint2 *>(
+                            reinterpret_cast<const uint32_t *>(partials + area + v * kPartialBytes) +
+                            ((rt * kGroups + rg) * kWave + lane) * 2);
+                        sum.x += part.x;
+                        sum.y += part.y;
+                    }
+                    dot[p][0] = (int)(sum.x & 0xffffu);
+                    dot[p][1] = (int)(sum.x >> 16);
+                    dot[p][2] = (int)(sum.y & 0xffffu);
+                    dot[p][3] = (int)(sum.y >> 16);
+                    int base[kRegs];
+                    bases(base, p);
+#pragma unroll
+                    for (int j = 0; j < kRegs; ++j) key = min(key, base[j] - (dot[p][j] << 11));   // the key takes 2048 * dot off
                 }
-                dot[p][0] = (int)(sum.x & 0xffffu);
-                dot[p][1] = (int)(sum.x >> 16);
-                dot[p][2] = (int)(sum.y & 0xffffu);
-                dot[p][3] = (int)(sum.y >> 16);
-                int base[kRegs];
-                bases(base, p);
-#pragma unroll
-                for (int j = 0; j < kRegs; ++j) key = min(key, base[j] - (dot[p][j] << 11));   // the key takes 2048 * dot off
             }
         }
         if (reduces) {
